@@ -1,0 +1,149 @@
+"""CPU replica of the load-balanced work partition (Algorithm 1, Sec. 3.3.1).
+
+TEST INFRASTRUCTURE ONLY.  Pure Python integers, `sorted` and `heapq`; takes
+the algorithm's steps in the paper's order.  Shares no code with the C++
+planner of the GPU library; the planner's arrays must equal this replica's
+bit for bit.
+
+Steps (paper's notation):
+  input   {l_qo(i), l_kv(i)}, query tile size T_q
+  cost    cost(l_q, l_kv) = alpha * l_q + beta * l_kv
+  L_kv    = sum_i ceil(l_qo(i)/T_q) * l_kv(i) / #CTA
+  split   every query tile's KV range into chunks of at most L_kv; chunk w has length l_kv(w)
+  sort    W = {(w, l_kv(w))} by descending length
+  assign  pop the CTA with the least accumulated cost, give it the next chunk,
+          add cost(T_q, l_kv(w)) to it, push it back
+plus the output index map of Sec. 3.3.1 / App. D.2: a tile with one chunk
+writes the final output directly (write-through), a split tile writes one
+partial state per chunk into the workspace and is merged afterwards.
+
+Readings where the paper is silent (each is a deliberate choice, listed in the
+design notes):
+  * heads are left out of the plan (as in Algorithm 1): every kv head runs the
+    same work list; #CTA here is the number of CTAs per kv head;
+  * a query tile holds T_pos consecutive positions of one request fused with
+    the g = H_qo/H_kv heads of a group (App. A), so T_q = T_pos * g rows;
+  * under causal masking a tile's KV range is what its last row can see,
+    kv_eff = clamp(l_kv - l_qo + tile_end, 0, l_kv); that is the l_kv(i) of
+    the tile in the L_kv formula and in the split (`literal_lkv=True` uses
+    l_kv(i) for every tile in the L_kv formula as printed);
+  * L_kv = max(min_chunk, round_up(ceil(S / #CTA), page_size)); S = 0 gives
+    min_chunk.  Rounding up to whole pages keeps chunk starts page aligned and
+    keeps the number of partial tiles <= 2 * #CTA (App. D.3);
+  * greedy split: chunk c = [c*L_kv, min((c+1)*L_kv, kv_eff)); a tile with
+    kv_eff = 0 still gets one (empty) chunk so its rows are written;
+  * work indices w are given in (request, tile, chunk) order; sort key
+    (-length, w); heap key (cost, cta); alpha, beta integers;
+  * a CTA's queue keeps assignment order;
+  * split tiles are numbered in (request, tile) order, slot_base is the running
+    sum of their chunk counts, chunk c of a split tile owns slot slot_base + c,
+    the merge folds slots in ascending c.
+"""
+from __future__ import annotations
+
+import heapq
+from typing import Dict, List, Sequence
+
+NO_DIAG = 0x3FFFFFFF   # "row sees everything" marker for non-causal work items
+
+
+def plan_replica(qo_indptr: Sequence[int], kv_indptr: Sequence[int], last_page_len: Sequence[int],
+                 *, page_size: int, t_pos: int, group: int, num_ctas: int, causal: bool,
+                 alpha: int = 1, beta: int = 1, min_chunk: int | None = None,
+                 literal_lkv: bool = False) -> Dict[str, object]:
+    B = len(last_page_len)
+    if min_chunk is None:
+        min_chunk = page_size
+    min_chunk = ((min_chunk + page_size - 1) // page_size) * page_size
+    T_q = t_pos * group
+
+    # -- lengths -----------------------------------------------------------
+    l_qo = [int(qo_indptr[i + 1]) - int(qo_indptr[i]) for i in range(B)]
+    l_kv = []
+    for i in range(B):
+        n_pg = int(kv_indptr[i + 1]) - int(kv_indptr[i])
+        l_kv.append(0 if n_pg == 0 else (n_pg - 1) * page_size + int(last_page_len[i]))
+
+    # -- query tiles and the KV range each one needs -------------------------
+    tiles = []        # (request, tile_start, n_pos, kv_eff, diag0)
+    S = 0
+    for i in range(B):
+        n_tiles = -(-l_qo[i] // t_pos)
+        for t in range(n_tiles):
+            start = t * t_pos
+            end = min(start + t_pos, l_qo[i])
+            if causal:
+                kv_eff = max(0, min(l_kv[i], l_kv[i] - l_qo[i] + end))
+                diag0 = l_kv[i] - l_qo[i] + start
+            else:
+                kv_eff = l_kv[i]
+                diag0 = NO_DIAG
+            tiles.append((i, start, end - start, kv_eff, diag0))
+            S += l_kv[i] if literal_lkv else kv_eff
+
+    # -- maximum chunk size --------------------------------------------------
+    L_kv = -(-S // num_ctas)
+    L_kv = ((L_kv + page_size - 1) // page_size) * page_size
+    L_kv = max(min_chunk, L_kv)
+
+    # -- split ---------------------------------------------------------------
+    work = []         # per w: dict
+    tile_chunks = []  # per tile: number of chunks
+    for (i, start, n_pos, kv_eff, diag0) in tiles:
+        n_chunks = max(1, -(-kv_eff // L_kv))
+        tile_chunks.append(n_chunks)
+        for c in range(n_chunks):
+            lo = c * L_kv
+            hi = min(lo + L_kv, kv_eff)
+            work.append(dict(request=i, q_row0=int(qo_indptr[i]) + start, n_pos=n_pos,
+                             kv_start=lo, kv_len=hi - lo,
+                             kv_page0=int(kv_indptr[i]) + lo // page_size,
+                             diag0=diag0, tile=len(tile_chunks) - 1, chunk=c))
+
+    # -- output index map ------------------------------------------------------
+    slot_base_of_tile = []
+    merge = []        # per split tile: (q_row0, n_pos, slot_base, n_chunks)
+    next_slot = 0
+    for ti, (i, start, n_pos, kv_eff, diag0) in enumerate(tiles):
+        if tile_chunks[ti] > 1:
+            slot_base_of_tile.append(next_slot)
+            merge.append((int(qo_indptr[i]) + start, n_pos, next_slot, tile_chunks[ti]))
+            next_slot += tile_chunks[ti]
+        else:
+            slot_base_of_tile.append(-1)
+    for w in work:
+        base = slot_base_of_tile[w["tile"]]
+        w["out_slot"] = -1 if base < 0 else base + w["chunk"]
+
+    # -- sort by descending length, assign to the least-loaded CTA ------------
+    order = sorted(range(len(work)), key=lambda w: (-work[w]["kv_len"], w))
+    heap = [(0, c) for c in range(num_ctas)]
+    heapq.heapify(heap)
+    queues: List[List[int]] = [[] for _ in range(num_ctas)]
+    for w in order:
+        cost, c = heapq.heappop(heap)
+        queues[c].append(w)
+        heapq.heappush(heap, (cost + alpha * T_q + beta * work[w]["kv_len"], c))
+    cta_cost = [0] * num_ctas
+    for cost, c in heap:
+        cta_cost[c] = cost
+
+    cta_indptr = [0]
+    flat = []
+    for c in range(num_ctas):
+        flat.extend(queues[c])
+        cta_indptr.append(len(flat))
+
+    def col(name):
+        return [work[w][name] for w in flat]
+
+    return dict(
+        L_kv=L_kv, S=S, n_work=len(work), n_merge=len(merge), n_slots=next_slot,
+        cta_indptr=cta_indptr,
+        w_request=col("request"), w_q_row0=col("q_row0"), w_n_pos=col("n_pos"),
+        w_kv_page0=col("kv_page0"), w_kv_start=col("kv_start"), w_kv_len=col("kv_len"),
+        w_diag0=col("diag0"), w_out_slot=col("out_slot"),
+        m_q_row0=[m[0] for m in merge], m_n_pos=[m[1] for m in merge],
+        m_slot_base=[m[2] for m in merge], m_n_chunks=[m[3] for m in merge],
+        cta_cost=cta_cost, work_order=flat,
+    )

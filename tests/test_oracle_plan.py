@@ -1,0 +1,168 @@
+"""Pins for the replica of the paper's scheduling algorithm (Algorithm 1, Sec. 3.3.1):
+two pencil-worked examples stored as text fixtures, and the invariants the paper
+states (App. D.2 write-through, App. D.3 partial-output bound, determinism)."""
+import os
+
+import numpy as np
+import pytest
+
+from oracle.plan_replica import NO_DIAG, plan_replica
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def load_fixture(name):
+    out = {}
+    with open(os.path.join(GOLDEN, name)) as f:
+        for line in f:
+            line = line.strip()
+            if not line or line.startswith("#"):
+                continue
+            key, *vals = line.split()
+            out[key] = [int(v) for v in vals]
+    return out
+
+
+def indptrs_from_lengths(qo_len, kv_len, page_size):
+    qo_indptr = np.concatenate([[0], np.cumsum(qo_len)]).astype(np.int64)
+    n_pg = [(l + page_size - 1) // page_size for l in kv_len]
+    kv_indptr = np.concatenate([[0], np.cumsum(n_pg)]).astype(np.int64)
+    last = [0 if l == 0 else l - (n - 1) * page_size for l, n in zip(kv_len, n_pg)]
+    return qo_indptr, kv_indptr, last
+
+
+@pytest.mark.parametrize("name", ["plan_decode_example.txt", "plan_causal_example.txt"])
+def test_hand_worked_examples(name):
+    fx = load_fixture(name)
+    ps = fx["page_size"][0]
+    qo_indptr, kv_indptr, last = indptrs_from_lengths(fx["qo_len"], fx["kv_len"], ps)
+    p = plan_replica(qo_indptr, kv_indptr, last, page_size=ps, t_pos=fx["t_pos"][0], group=fx["group"][0],
+                     num_ctas=fx["num_ctas"][0], causal=bool(fx["causal"][0]),
+                     alpha=fx.get("alpha", [1])[0], beta=fx.get("beta", [1])[0], min_chunk=ps)
+    assert p["L_kv"] == fx["L_kv"][0]
+    for key in ("cta_indptr", "w_request", "w_q_row0", "w_n_pos", "w_kv_start", "w_kv_len", "w_diag0",
+                "w_out_slot", "cta_cost", "m_q_row0", "m_n_pos", "m_slot_base", "m_n_chunks"):
+        if key in fx:
+            assert list(p[key]) == fx[key], key
+
+
+def random_lengths(rng, kind):
+    B = int(rng.integers(1, 40))
+    if kind == "decode":
+        qo = np.ones(B, dtype=np.int64)
+        kv = rng.integers(0, 3000, size=B)
+        if rng.random() < 0.3:
+            kv[rng.integers(0, B)] = int(rng.integers(20000, 200000))      # one giant request
+        if rng.random() < 0.2:
+            kv[:] = int(rng.integers(1, 500))                              # all equal
+    else:
+        qo = rng.integers(0, 300, size=B)
+        pre = rng.integers(0, 2000, size=B)
+        kv = qo + pre
+        if rng.random() < 0.3:
+            kv = np.maximum(kv - rng.integers(0, 50, size=B), 0)           # fewer keys than queries allowed
+    return qo, kv
+
+
+@pytest.mark.parametrize("kind", ["decode", "append"])
+def test_invariants_random(kind):
+    rng = np.random.default_rng(2024 if kind == "decode" else 2025)
+    for trial in range(150):
+        qo, kv = random_lengths(rng, kind)
+        ps = int(rng.choice([1, 4, 16]))
+        C = int(rng.choice([1, 3, 8, 32, 128]))
+        t_pos = 1 if kind == "decode" else int(rng.choice([16, 32, 128]))
+        g = int(rng.choice([1, 4]))
+        causal = kind == "append"
+        alpha, beta = int(rng.integers(0, 4)), int(rng.integers(1, 4))
+        min_chunk = ps * int(rng.choice([1, 4, 16]))
+        qo_indptr, kv_indptr, last = indptrs_from_lengths(qo, kv, ps)
+        kw = dict(page_size=ps, t_pos=t_pos, group=g, num_ctas=C, causal=causal, alpha=alpha, beta=beta,
+                  min_chunk=min_chunk)
+        p = plan_replica(qo_indptr, kv_indptr, last, **kw)
+        assert p == plan_replica(qo_indptr, kv_indptr, last, **kw)          # deterministic (Sec. 3.3.1)
+        L = p["L_kv"]
+        assert L % ps == 0 and L >= min_chunk and L * C >= p["S"]
+        n_work = p["n_work"]
+        assert p["cta_indptr"][0] == 0 and p["cta_indptr"][-1] == n_work and len(p["cta_indptr"]) == C + 1
+        assert sorted(p["work_order"]) == list(range(n_work))               # each item assigned once
+        # chunks of a tile partition [0, kv_eff) and every chunk is <= L_kv
+        tiles = {}
+        for k in range(n_work):
+            key = (p["w_request"][k], p["w_q_row0"][k])
+            tiles.setdefault(key, []).append(k)
+            assert 0 <= p["w_kv_len"][k] <= L
+            assert p["w_kv_start"][k] % ps == 0
+            i = p["w_request"][k]
+            assert p["w_kv_page0"][k] == kv_indptr[i] + p["w_kv_start"][k] // ps
+        n_tiles_expected = int(sum(-(-int(q) // t_pos) for q in qo))
+        assert len(tiles) == n_tiles_expected
+        n_slots = 0
+        n_split = 0
+        for (i, row0), items in tiles.items():
+            items.sort(key=lambda k: p["w_kv_start"][k])
+            start = row0 - int(qo_indptr[i])
+            end = min(start + t_pos, int(qo[i]))
+            kv_eff = max(0, min(int(kv[i]), int(kv[i]) - int(qo[i]) + end)) if causal else int(kv[i])
+            pos = 0
+            for k in items:
+                assert p["w_kv_start"][k] == pos
+                assert p["w_n_pos"][k] == end - start
+                assert p["w_diag0"][k] == (int(kv[i]) - int(qo[i]) + start if causal else NO_DIAG)
+                pos += p["w_kv_len"][k]
+            assert pos == kv_eff
+            assert (len(items) > 1) == (kv_eff > L)                           # split iff longer than L_kv
+            if len(items) == 1:
+                assert p["w_out_slot"][items[0]] == -1                        # write-through (App. D.2)
+            else:
+                slots = [p["w_out_slot"][k] for k in items]
+                assert slots == list(range(slots[0], slots[0] + len(items)))
+                assert all(p["w_kv_len"][k] == L for k in items[:-1])          # greedy: only the last is short
+                n_slots += len(items)
+                n_split += 1
+        assert n_slots == p["n_slots"] <= 2 * C                                # App. D.3
+        assert p["n_merge"] == n_split <= C
+        assert sum(p["m_n_chunks"]) == n_slots
+        # LPT property: no CTA exceeds the least-loaded one by more than one item's cost
+        T_q = t_pos * g
+        costs = p["cta_cost"]
+        loads = [0] * C
+        for c in range(C):
+            for k in range(p["cta_indptr"][c], p["cta_indptr"][c + 1]):
+                loads[c] += alpha * T_q + beta * p["w_kv_len"][k]
+        assert loads == costs
+        if n_work:
+            max_item = max(alpha * T_q + beta * l for l in p["w_kv_len"])
+            assert max(loads) - min(loads) <= max_item
+        # queues hold items longest first
+        for c in range(C):
+            lens = p["w_kv_len"][p["cta_indptr"][c]:p["cta_indptr"][c + 1]]
+            assert lens == sorted(lens, reverse=True)
+
+
+def test_long_context_split_is_balanced():
+    # two long requests over 32 CTAs: greedy chunks give 31 full + two short pieces that share a CTA
+    qo_indptr, kv_indptr, last = indptrs_from_lengths([1, 1], [131072, 65536], 16)
+    p = plan_replica(qo_indptr, kv_indptr, last, page_size=16, t_pos=1, group=4, num_ctas=32, causal=False)
+    assert p["L_kv"] == 6144
+    assert p["n_work"] == 33 and p["n_slots"] == 33
+    # 31 CTAs hold one full chunk (cost 4 + 6144); the last holds 4096 + 2048 (cost 2 * 4 + 6144)
+    assert sorted(p["cta_cost"]) == [6148] * 31 + [6152]
+
+
+def test_literal_lkv_flag_only_changes_chunk_size():
+    qo_indptr, kv_indptr, last = indptrs_from_lengths([256], [256], 16)
+    a = plan_replica(qo_indptr, kv_indptr, last, page_size=16, t_pos=32, group=4, num_ctas=4, causal=True)
+    b = plan_replica(qo_indptr, kv_indptr, last, page_size=16, t_pos=32, group=4, num_ctas=4, causal=True,
+                     literal_lkv=True)
+    assert a["S"] == sum(32 * (t + 1) for t in range(8)) and b["S"] == 8 * 256
+    assert b["L_kv"] > a["L_kv"]
+
+
+def test_empty_and_degenerate_inputs():
+    # no requests with queries -> no work, L_kv = min_chunk
+    p = plan_replica([0, 0], [0, 3], [5], page_size=16, t_pos=1, group=1, num_ctas=4, causal=False)
+    assert p["n_work"] == 0 and p["L_kv"] == 16 and p["cta_indptr"] == [0, 0, 0, 0, 0]
+    # a request with no pages still gets one empty work item (its rows must be written)
+    p = plan_replica([0, 1], [0, 0], [0], page_size=16, t_pos=1, group=1, num_ctas=2, causal=False)
+    assert p["n_work"] == 1 and p["w_kv_len"] == [0] and p["w_out_slot"] == [-1]
