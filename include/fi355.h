@@ -1,0 +1,173 @@
+/*
+ * fi355 -- batched attention over a paged (block-sparse-row) KV cache for AMD MI355X (gfx950).
+ *
+ * C ABI of the library: plain pointers and sizes only.  Every pointer is marked
+ * HOST or DEVICE.  All functions return an int32 status (FI_OK = 0, negative = error,
+ * message through fi_last_error()); nothing throws, nothing aborts.
+ *
+ * Method (FlashInfer, arXiv 2501.01005):
+ *   - storage: ragged query/output + block-sparse-row KV cache, Sec. 3.1.1;
+ *     several formats over one pool (shared prefix), Sec. 3.1.2;
+ *   - attention state (O, LSE) and its merge operator, Sec. 2.2;
+ *   - plan / run split, workspace with fixed sections, Sec. 3.3.1, Sec. 3.4, App. D;
+ *   - load-balanced partition of KV ranges over a fixed number of CTAs, Algorithm 1;
+ *   - head-group fusion for grouped-query attention, App. A.
+ *
+ * Ownership: the caller owns every device buffer and the pinned staging buffer.
+ * The library allocates no device memory, frees nothing it was handed, and never
+ * synchronises the device.  A handle owns only host-side plan arrays.
+ *
+ * Layouts (all row-major, innermost dimension contiguous):
+ *   q        DEVICE  [nnz_qo, num_qo_heads, head_dim]   fp16 or bf16
+ *   o        DEVICE  [nnz_qo, num_qo_heads, head_dim]   fp32   (attention output)
+ *   lse      DEVICE  [nnz_qo, num_qo_heads]             fp32   (natural log-sum-exp of the
+ *                                                               scaled logits; -inf for an
+ *                                                               empty key set, then o = 0)
+ *   k_pool, v_pool DEVICE, addressed as
+ *            base + page*kv_strides[0] + kv_head*kv_strides[1] + slot*kv_strides[2] + d
+ *            (strides in elements; head_dim contiguous).  The tuned layout is
+ *            [num_pages, num_kv_heads, page_size, head_dim].
+ *   qo_indptr, kv_indptr [batch+1], last_page_len [batch]  HOST int32 (plan input)
+ *   kv_indices DEVICE int32 [kv_indptr[batch]] page ids (run input; not range checked
+ *            on the device -- see fi_check_indices)
+ */
+#ifndef FI355_H_
+#define FI355_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define FI_OK 0
+#define FI_ERR_INVALID_ARG (-1)          /* null pointer, malformed indptr, length out of range ... */
+#define FI_ERR_UNSUPPORTED (-2)          /* head_dim / page_size / group size not instantiated      */
+#define FI_ERR_WORKSPACE_TOO_SMALL (-3)
+#define FI_ERR_NOT_PLANNED (-4)          /* fi_run before a successful fi_plan with a workspace     */
+#define FI_ERR_HIP (-5)                  /* a HIP runtime call failed; message has its string       */
+
+#define FI_DTYPE_F16 0
+#define FI_DTYPE_BF16 1
+
+#define FI_MODE_DECODE 0 /* query tile = 1 position x g fused heads; one wavefront per CTA   */
+#define FI_MODE_APPEND 1 /* query tile = 128/g positions x g fused heads; MFMA tile kernel     */
+
+typedef struct fi_handle fi_handle;
+typedef void* fi_stream; /* a hipStream_t (0 = the null stream) */
+
+/* Fixed at creation; launch grids and workspace section offsets depend on this struct
+ * only, never on sequence lengths (Sec. 3.3.1 last paragraph, App. D.1). */
+typedef struct fi_config {
+  int32_t dtype;        /* FI_DTYPE_*: storage type of q, k_pool, v_pool                       */
+  int32_t num_qo_heads; /* H_qo                                                                */
+  int32_t num_kv_heads; /* H_kv; g = H_qo / H_kv must be an integer                            */
+  int32_t head_dim;     /* D (128)                                                             */
+  int32_t page_size;    /* B_c of the BSR cache (16)                                           */
+  int32_t mode;         /* FI_MODE_*                                                           */
+  int32_t num_ctas;     /* total persistent CTAs over all kv heads; 0 = library default for
+                           the current device (needs a GPU); CTAs per kv head = num_ctas/H_kv   */
+  int32_t max_batch;    /* upper bound on `batch` of any later fi_plan                         */
+  int32_t max_qo_tiles; /* upper bound on the number of query tiles of any later fi_plan
+                           (decode: = max_batch; append: sum_i ceil(l_qo(i) / T_pos))           */
+  int32_t alpha;        /* cost(l_q, l_kv) = alpha*l_q + beta*l_kv of Algorithm 1; 0,0 = 1,1   */
+  int32_t beta;
+  int32_t min_chunk;    /* smallest KV chunk the planner may create, tokens; 0 = default       */
+  int32_t literal_lkv;  /* 1: use l_kv(i) for every query tile in the chunk-size formula as
+                           printed in Algorithm 1 even under causal masking; 0: use what the
+                           tile can see                                                         */
+  int32_t reserved[3];  /* must be 0                                                           */
+} fi_config;
+
+/* Borrowed HOST views of the last plan, for bit-exact checks against a replica of
+ * Algorithm 1.  Work items are listed queue by queue: CTA c owns items
+ * cta_indptr[c] .. cta_indptr[c+1]-1, in the order it executes them. */
+typedef struct fi_plan_arrays {
+  int32_t t_pos;          /* query positions per tile                                          */
+  int32_t group;          /* g                                                                 */
+  int32_t ctas_per_head;  /* #CTA of Algorithm 1                                               */
+  int32_t l_kv_chunk;     /* L_kv: maximum chunk size, tokens                                  */
+  int32_t n_work;         /* number of work items (chunks)                                     */
+  int32_t n_merge;        /* number of query tiles that were split                             */
+  int32_t n_slots;        /* partial-output slots in use (<= 2 * ctas_per_head, App. D.3)      */
+  int32_t pad_;
+  const int32_t* cta_indptr;  /* [ctas_per_head + 1]                                           */
+  const int32_t* w_request;   /* [n_work] request index                                        */
+  const int32_t* w_q_row0;    /* [n_work] first query row (index into q's leading dimension)   */
+  const int32_t* w_n_pos;     /* [n_work] valid query positions in the tile                    */
+  const int32_t* w_kv_page0;  /* [n_work] index into kv_indices of the chunk's first page      */
+  const int32_t* w_kv_start;  /* [n_work] first token of the chunk within the request          */
+  const int32_t* w_kv_len;    /* [n_work] tokens in the chunk (0 for an empty request)         */
+  const int32_t* w_diag0;     /* [n_work] causal: tile row r sees request tokens <= diag0 + r;
+                                 non-causal: 0x3FFFFFFF                                        */
+  const int32_t* w_out_slot;  /* [n_work] -1 = write the final output directly (App. D.2),
+                                 else partial-output slot                                      */
+  const int32_t* m_q_row0;    /* [n_merge] first query row of the split tile                   */
+  const int32_t* m_n_pos;     /* [n_merge]                                                     */
+  const int32_t* m_slot_base; /* [n_merge] first slot; chunk c of the tile is slot base + c    */
+  const int32_t* m_n_chunks;  /* [n_merge]                                                     */
+} fi_plan_arrays;
+
+/* Create / destroy a handle.  cfg HOST.  FI_ERR_UNSUPPORTED unless head_dim = 128,
+ * page_size = 16, g in {1,2,4} (decode) / g in {1,2,4,8} (append).  With num_ctas = 0 the
+ * current HIP device is queried (FI_ERR_HIP without one). */
+int32_t fi_create(const fi_config* cfg, fi_handle** out);
+int32_t fi_destroy(fi_handle* h);
+
+/* Bytes the caller must provide: device workspace (plan sections + partial outputs,
+ * App. D.3 bound 2 * #CTA * T_q * (D + 1) floats per kv head) and pinned staging buffer. */
+int32_t fi_workspace_bytes(const fi_handle* h, size_t* device_bytes, size_t* pinned_host_bytes);
+
+/* The scheduler of Algorithm 1 (Sec. 3.3.1), run on the host once per generation step and
+ * reused by every layer.  Reads the three HOST arrays, writes the plan into `pinned_host`
+ * (HOST, page-locked, >= pinned_host_bytes; NULL = use pageable memory of the handle) and
+ * enqueues ONE async copy into the fixed plan sections of `workspace_dev` on `stream`.
+ * The staging buffer must not be re-planned before that copy has executed.
+ * workspace_dev = NULL plans on the host only (no HIP call; fi_run stays unavailable).
+ * causal != 0: query j of a request sees tokens t <= l_kv - l_qo + j (the appended tokens
+ * are already in the cache).  Errors: FI_ERR_INVALID_ARG for indptr[0] != 0, decreasing
+ * indptr, last_page_len outside [1, page_size] on a non-empty request, batch > max_batch,
+ * more tiles than max_qo_tiles; FI_ERR_WORKSPACE_TOO_SMALL. */
+int32_t fi_plan(fi_handle* h, const int32_t* qo_indptr, const int32_t* kv_indptr,
+                const int32_t* last_page_len, int32_t batch, int32_t causal,
+                void* workspace_dev, size_t workspace_bytes,
+                void* pinned_host, size_t pinned_bytes, fi_stream stream);
+
+/* Borrowed views of the handle's last plan; valid until the next fi_plan / fi_destroy. */
+int32_t fi_plan_view(const fi_handle* h, fi_plan_arrays* out);
+
+/* Attention over the planned batch (Sec. 2.2 states; Sec. 3.2 kernels): one persistent
+ * launch of ctas_per_head x H_kv CTAs that walk their work queues, writing final rows
+ * directly or partial states into the workspace, then one fixed-grid merge launch for the
+ * split tiles.  All pointers DEVICE.  kv_strides HOST [3] = element strides of
+ * (page, kv head, slot-in-page).  sm_scale multiplies q.k before the softmax.
+ * o_cast (may be NULL): the output also rounded to the input dtype, [nnz_qo, H_qo, D].
+ * Asynchronous on `stream`; uses the workspace given to the last fi_plan. */
+int32_t fi_run(fi_handle* h, const void* q, const void* k_pool, const void* v_pool,
+               const int64_t* kv_strides, const int32_t* kv_indices, float sm_scale,
+               float* o, float* lse, void* o_cast, fi_stream stream);
+
+/* Merge operator of Sec. 2.2 over n_states states per row, folded in index order:
+ * o_parts DEVICE [n_rows, n_states, D], lse_parts DEVICE [n_rows, n_states] ->
+ * o DEVICE [n_rows, D], lse DEVICE [n_rows].  A state with lse = -inf is the identity. */
+int32_t fi_merge_states(const float* o_parts, const float* lse_parts, int64_t n_rows,
+                        int32_t n_states, int32_t head_dim, float* o, float* lse,
+                        fi_stream stream);
+
+/* Two-state merge used to compose a shared-prefix pass with a per-request pass
+ * (Sec. 3.1.2, Sec. 4.4).  o may alias o_a and lse may alias lse_a (in place). */
+int32_t fi_merge_state_pair(const float* o_a, const float* lse_a, const float* o_b,
+                            const float* lse_b, int64_t n_rows, int32_t head_dim,
+                            float* o, float* lse, fi_stream stream);
+
+/* HOST helper for tests: FI_OK iff every indices[i] is in [0, num_pages). */
+int32_t fi_check_indices(const int32_t* indices_host, int64_t n, int32_t num_pages);
+
+/* Message for the last non-zero status returned on this thread (never NULL). */
+const char* fi_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FI355_H_ */

@@ -1,0 +1,271 @@
+// C ABI of the library (declared in include/fi355.h): argument checks, the plan/run
+// split of Sec. 3.4, workspace sections at fixed offsets (App. D.1), kernel launches.
+#include <hip/hip_runtime.h>
+
+#include <cstring>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "../../include/fi355.h"
+#include "kernels.h"
+#include "plan.h"
+
+using namespace fi355;
+
+namespace {
+thread_local std::string g_last_error;
+
+int32_t set_error(int32_t code, const std::string& msg) {
+  g_last_error = msg;
+  return code;
+}
+int32_t hip_error(const char* what, hipError_t e) {
+  return set_error(FI_ERR_HIP, std::string(what) + ": " + hipGetErrorString(e));
+}
+}  // namespace
+
+struct fi_handle {
+  fi_config cfg;
+  PlanParams pp;
+  WorkspaceLayout layout;
+  std::vector<int32_t> host_plan;  // last plan section (also the pageable staging buffer)
+  bool planned_host = false;
+  bool planned_dev = false;
+  void* workspace_dev = nullptr;
+  size_t workspace_bytes = 0;
+};
+
+extern "C" {
+
+const char* fi_last_error(void) { return g_last_error.c_str(); }
+
+int32_t fi_create(const fi_config* cfg, fi_handle** out) {
+  if (!cfg || !out) return set_error(FI_ERR_INVALID_ARG, "fi_create: null argument");
+  *out = nullptr;
+  if (cfg->dtype != FI_DTYPE_F16 && cfg->dtype != FI_DTYPE_BF16)
+    return set_error(FI_ERR_INVALID_ARG, "fi_create: dtype must be FI_DTYPE_F16 or FI_DTYPE_BF16");
+  if (cfg->mode != FI_MODE_DECODE && cfg->mode != FI_MODE_APPEND)
+    return set_error(FI_ERR_INVALID_ARG, "fi_create: unknown mode");
+  if (cfg->num_qo_heads <= 0 || cfg->num_kv_heads <= 0 || cfg->num_qo_heads % cfg->num_kv_heads != 0)
+    return set_error(FI_ERR_INVALID_ARG, "fi_create: num_qo_heads must be a positive multiple of num_kv_heads");
+  if (cfg->max_batch <= 0 || cfg->max_qo_tiles <= 0 || cfg->num_ctas < 0 || cfg->alpha < 0 || cfg->beta < 0 ||
+      cfg->min_chunk < 0)
+    return set_error(FI_ERR_INVALID_ARG, "fi_create: max_batch/max_qo_tiles must be > 0, the rest >= 0");
+  for (int r : cfg->reserved)
+    if (r != 0) return set_error(FI_ERR_INVALID_ARG, "fi_create: reserved fields must be 0");
+  if (cfg->head_dim != kHeadDim) return set_error(FI_ERR_UNSUPPORTED, "fi_create: only head_dim = 128 is built");
+  if (cfg->page_size != kPageSize) return set_error(FI_ERR_UNSUPPORTED, "fi_create: only page_size = 16 is built");
+  const int g = cfg->num_qo_heads / cfg->num_kv_heads;
+  if (cfg->mode == FI_MODE_DECODE && !(g == 1 || g == 2 || g == 4))
+    return set_error(FI_ERR_UNSUPPORTED, "fi_create: decode mode is built for group size 1, 2, 4");
+  if (cfg->mode == FI_MODE_APPEND && !(g == 1 || g == 2 || g == 4 || g == 8))
+    return set_error(FI_ERR_UNSUPPORTED, "fi_create: append mode is built for group size 1, 2, 4, 8");
+
+  int num_ctas = cfg->num_ctas;
+  if (num_ctas == 0) {
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return hip_error("fi_create: hipGetDevice (num_ctas = 0 needs a GPU)", e);
+    int cus = 0;
+    e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+    if (e != hipSuccess) return hip_error("fi_create: hipDeviceGetAttribute", e);
+    // decode: one wavefront per CTA, 8 resident per CU; append: 4-wavefront CTAs, 2 per CU
+    num_ctas = cfg->mode == FI_MODE_DECODE ? 8 * cus : 2 * cus;
+  }
+  fi_handle* h = new (std::nothrow) fi_handle();
+  if (!h) return set_error(FI_ERR_INVALID_ARG, "fi_create: out of host memory");
+  h->cfg = *cfg;
+  h->cfg.num_ctas = num_ctas;
+  PlanParams& pp = h->pp;
+  pp.page_size = cfg->page_size;
+  pp.group = g;
+  pp.t_pos = cfg->mode == FI_MODE_DECODE ? 1 : 128 / g;
+  pp.ctas_per_head = num_ctas / cfg->num_kv_heads > 0 ? num_ctas / cfg->num_kv_heads : 1;
+  pp.alpha = (cfg->alpha == 0 && cfg->beta == 0) ? 1 : cfg->alpha;
+  pp.beta = (cfg->alpha == 0 && cfg->beta == 0) ? 1 : cfg->beta;
+  pp.min_chunk = cfg->min_chunk > 0 ? cfg->min_chunk : 256;
+  pp.literal_lkv = cfg->literal_lkv != 0;
+  pp.max_batch = cfg->max_batch;
+  pp.max_qo_tiles = cfg->max_qo_tiles;
+  h->layout.init(pp.ctas_per_head, cfg->max_qo_tiles, pp.t_pos, cfg->num_qo_heads, cfg->head_dim);
+  h->host_plan.assign(h->layout.plan_ints, 0);
+  *out = h;
+  return FI_OK;
+}
+
+int32_t fi_destroy(fi_handle* h) {
+  delete h;
+  return FI_OK;
+}
+
+int32_t fi_workspace_bytes(const fi_handle* h, size_t* device_bytes, size_t* pinned_host_bytes) {
+  if (!h) return set_error(FI_ERR_INVALID_ARG, "fi_workspace_bytes: null handle");
+  if (device_bytes) *device_bytes = h->layout.total_bytes;
+  if (pinned_host_bytes) *pinned_host_bytes = h->layout.plan_bytes;
+  return FI_OK;
+}
+
+int32_t fi_plan(fi_handle* h, const int32_t* qo_indptr, const int32_t* kv_indptr, const int32_t* last_page_len,
+                int32_t batch, int32_t causal, void* workspace_dev, size_t workspace_bytes, void* pinned_host,
+                size_t pinned_bytes, fi_stream stream) {
+  if (!h) return set_error(FI_ERR_INVALID_ARG, "fi_plan: null handle");
+  if (workspace_dev && workspace_bytes < h->layout.total_bytes)
+    return set_error(FI_ERR_WORKSPACE_TOO_SMALL, "fi_plan: device workspace has " + std::to_string(workspace_bytes) +
+                                                     " bytes, needs " + std::to_string(h->layout.total_bytes));
+  if (pinned_host && pinned_bytes < h->layout.plan_bytes)
+    return set_error(FI_ERR_WORKSPACE_TOO_SMALL, "fi_plan: pinned staging buffer has " + std::to_string(pinned_bytes) +
+                                                     " bytes, needs " + std::to_string(h->layout.plan_bytes));
+  h->planned_host = false;
+  h->planned_dev = false;
+  PlanParams pp = h->pp;
+  pp.causal = causal != 0;
+  std::string err;
+  const int32_t rc = make_plan(pp, h->layout, qo_indptr, kv_indptr, last_page_len, batch, h->host_plan.data(), &err);
+  if (rc != FI_OK) return set_error(rc, err);
+  h->planned_host = true;
+  if (!workspace_dev) return FI_OK;
+  const size_t bytes = h->layout.plan_ints * sizeof(int32_t);
+  const void* src = h->host_plan.data();
+  if (pinned_host) {
+    std::memcpy(pinned_host, h->host_plan.data(), bytes);
+    src = pinned_host;
+  }
+  const hipError_t e = hipMemcpyAsync(workspace_dev, src, bytes, hipMemcpyHostToDevice, static_cast<hipStream_t>(stream));
+  if (e != hipSuccess) return hip_error("fi_plan: hipMemcpyAsync", e);
+  h->workspace_dev = workspace_dev;
+  h->workspace_bytes = workspace_bytes;
+  h->planned_dev = true;
+  return FI_OK;
+}
+
+int32_t fi_plan_view(const fi_handle* h, fi_plan_arrays* out) {
+  if (!h || !out) return set_error(FI_ERR_INVALID_ARG, "fi_plan_view: null argument");
+  if (!h->planned_host) return set_error(FI_ERR_NOT_PLANNED, "fi_plan_view: no successful fi_plan yet");
+  const WorkspaceLayout& L = h->layout;
+  const int32_t* base = h->host_plan.data();
+  const int32_t* hdr = base + L.off_header;
+  out->t_pos = h->pp.t_pos;
+  out->group = h->pp.group;
+  out->ctas_per_head = h->pp.ctas_per_head;
+  out->l_kv_chunk = hdr[H_L_KV];
+  out->n_work = hdr[H_N_WORK];
+  out->n_merge = hdr[H_N_MERGE];
+  out->n_slots = hdr[H_N_SLOTS];
+  out->pad_ = 0;
+  out->cta_indptr = base + L.off_cta_indptr;
+  out->w_request = base + L.off_work[W_REQUEST];
+  out->w_q_row0 = base + L.off_work[W_Q_ROW0];
+  out->w_n_pos = base + L.off_work[W_N_POS];
+  out->w_kv_page0 = base + L.off_work[W_KV_PAGE0];
+  out->w_kv_start = base + L.off_work[W_KV_START];
+  out->w_kv_len = base + L.off_work[W_KV_LEN];
+  out->w_diag0 = base + L.off_work[W_DIAG0];
+  out->w_out_slot = base + L.off_work[W_OUT_SLOT];
+  out->m_q_row0 = base + L.off_merge[M_Q_ROW0];
+  out->m_n_pos = base + L.off_merge[M_N_POS];
+  out->m_slot_base = base + L.off_merge[M_SLOT_BASE];
+  out->m_n_chunks = base + L.off_merge[M_N_CHUNKS];
+  return FI_OK;
+}
+
+int32_t fi_run(fi_handle* h, const void* q, const void* k_pool, const void* v_pool, const int64_t* kv_strides,
+               const int32_t* kv_indices, float sm_scale, float* o, float* lse, void* o_cast, fi_stream stream) {
+  if (!h) return set_error(FI_ERR_INVALID_ARG, "fi_run: null handle");
+  if (!h->planned_dev) return set_error(FI_ERR_NOT_PLANNED, "fi_run: call fi_plan with a device workspace first");
+  if (!q || !k_pool || !v_pool || !kv_strides || !kv_indices || !o || !lse)
+    return set_error(FI_ERR_INVALID_ARG, "fi_run: null pointer");
+  if (kv_strides[0] <= 0 || kv_strides[1] <= 0 || kv_strides[2] < kHeadDim || kv_strides[0] % 8 != 0 ||
+      kv_strides[1] % 8 != 0 || kv_strides[2] % 8 != 0)
+    return set_error(FI_ERR_INVALID_ARG,
+                     "fi_run: kv strides must be positive multiples of 8 elements, slot stride >= head_dim");
+  if ((reinterpret_cast<uintptr_t>(q) | reinterpret_cast<uintptr_t>(k_pool) | reinterpret_cast<uintptr_t>(v_pool) |
+       reinterpret_cast<uintptr_t>(o) | reinterpret_cast<uintptr_t>(o_cast)) & 15)
+    return set_error(FI_ERR_INVALID_ARG, "fi_run: q, k_pool, v_pool, o, o_cast must be 16-byte aligned");
+
+  const WorkspaceLayout& L = h->layout;
+  const int32_t* plan = static_cast<const int32_t*>(h->workspace_dev);
+  char* ws = static_cast<char*>(h->workspace_dev);
+  RunParams p{};
+  p.cta_indptr = plan + L.off_cta_indptr;
+  p.w_q_row0 = plan + L.off_work[W_Q_ROW0];
+  p.w_n_pos = plan + L.off_work[W_N_POS];
+  p.w_kv_page0 = plan + L.off_work[W_KV_PAGE0];
+  p.w_kv_len = plan + L.off_work[W_KV_LEN];
+  p.w_diag0 = plan + L.off_work[W_DIAG0];
+  p.w_out_slot = plan + L.off_work[W_OUT_SLOT];
+  p.kv_indices = kv_indices;
+  p.q = q;
+  p.k_pool = k_pool;
+  p.v_pool = v_pool;
+  p.stride_page = kv_strides[0];
+  p.stride_head = kv_strides[1];
+  p.stride_tok = kv_strides[2];
+  p.o = o;
+  p.lse = lse;
+  p.o_cast = o_cast;
+  p.part_lse = reinterpret_cast<float*>(ws + L.off_part_lse);
+  p.part_o = reinterpret_cast<float*>(ws + L.off_part_o);
+  p.scale_log2 = sm_scale * 1.4426950408889634f;
+  p.num_qo_heads = h->cfg.num_qo_heads;
+  p.num_kv_heads = h->cfg.num_kv_heads;
+  p.group = h->pp.group;
+  p.t_pos = h->pp.t_pos;
+  p.ctas_per_head = h->pp.ctas_per_head;
+  const bool bf = h->cfg.dtype == FI_DTYPE_BF16;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  hipError_t e = h->cfg.mode == FI_MODE_DECODE ? launch_decode(p, bf, s) : launch_append(p, bf, s);
+  if (e != hipSuccess) return hip_error("fi_run: attention launch", e);
+
+  MergeParams mp{};
+  mp.header = plan + L.off_header;
+  mp.m_q_row0 = plan + L.off_merge[M_Q_ROW0];
+  mp.m_n_pos = plan + L.off_merge[M_N_POS];
+  mp.m_slot_base = plan + L.off_merge[M_SLOT_BASE];
+  mp.m_n_chunks = plan + L.off_merge[M_N_CHUNKS];
+  mp.part_o = p.part_o;
+  mp.part_lse = p.part_lse;
+  mp.o = o;
+  mp.lse = lse;
+  mp.o_cast = o_cast;
+  mp.num_qo_heads = h->cfg.num_qo_heads;
+  mp.t_pos = h->pp.t_pos;
+  mp.is_bf16 = bf ? 1 : 0;
+  e = launch_merge_planned(mp, kMergeGrid, s);
+  if (e != hipSuccess) return hip_error("fi_run: merge launch", e);
+  return FI_OK;
+}
+
+int32_t fi_merge_states(const float* o_parts, const float* lse_parts, int64_t n_rows, int32_t n_states,
+                        int32_t head_dim, float* o, float* lse, fi_stream stream) {
+  if (head_dim != kHeadDim) return set_error(FI_ERR_UNSUPPORTED, "fi_merge_states: only head_dim = 128 is built");
+  if (n_rows < 0 || n_states < 0) return set_error(FI_ERR_INVALID_ARG, "fi_merge_states: negative size");
+  if (n_rows > 0 && (!o || !lse || (n_states > 0 && (!o_parts || !lse_parts))))
+    return set_error(FI_ERR_INVALID_ARG, "fi_merge_states: null pointer");
+  const hipError_t e = launch_merge_states(o_parts, lse_parts, n_rows, n_states, o, lse, static_cast<hipStream_t>(stream));
+  if (e != hipSuccess) return hip_error("fi_merge_states: launch", e);
+  return FI_OK;
+}
+
+int32_t fi_merge_state_pair(const float* o_a, const float* lse_a, const float* o_b, const float* lse_b, int64_t n_rows,
+                            int32_t head_dim, float* o, float* lse, fi_stream stream) {
+  if (head_dim != kHeadDim) return set_error(FI_ERR_UNSUPPORTED, "fi_merge_state_pair: only head_dim = 128 is built");
+  if (n_rows < 0) return set_error(FI_ERR_INVALID_ARG, "fi_merge_state_pair: negative size");
+  if (n_rows > 0 && (!o_a || !lse_a || !o_b || !lse_b || !o || !lse))
+    return set_error(FI_ERR_INVALID_ARG, "fi_merge_state_pair: null pointer");
+  const hipError_t e = launch_merge_pair(o_a, lse_a, o_b, lse_b, n_rows, o, lse, static_cast<hipStream_t>(stream));
+  if (e != hipSuccess) return hip_error("fi_merge_state_pair: launch", e);
+  return FI_OK;
+}
+
+int32_t fi_check_indices(const int32_t* indices_host, int64_t n, int32_t num_pages) {
+  if (n < 0 || (n > 0 && !indices_host)) return set_error(FI_ERR_INVALID_ARG, "fi_check_indices: bad arguments");
+  for (int64_t i = 0; i < n; ++i)
+    if (indices_host[i] < 0 || indices_host[i] >= num_pages)
+      return set_error(FI_ERR_INVALID_ARG, "fi_check_indices: indices[" + std::to_string(i) + "] = " +
+                                               std::to_string(indices_host[i]) + " outside [0, " +
+                                               std::to_string(num_pages) + ")");
+  return FI_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,264 @@
+// Paged decode attention for gfx950: query tile = one position x g fused query heads
+// (head-group fusion, App. A), one wavefront per CTA, K/V streamed from HBM straight into
+// MFMA operand registers.  HBM-bandwidth bound: every K/V byte of a chunk is read once.
+//
+// Per 32-token step (two 16-token pages) of a work item:
+//   S^T[token][head] = K . Q^T         v_mfma_f32_16x16x32 (A = K page, B = Q^T padded to 16 heads)
+//   online softmax (Sec. 2.1) on the 4 x 2 logits a lane owns, row max across the
+//   four 16-lane groups by two cross-lane exchanges
+//   O^T[d][head]    += V^T . P^T       v_mfma_f32_16x16x32 (A = V^T built by in-lane 16-bit
+//                                      permutes of row-major V rows, B = P^T straight from
+//                                      the S^T accumulator layout -- no cross-lane traffic)
+// The contraction index of the second product is (page, lane group, register), which both
+// operands enumerate identically, so its order inside the instruction never matters.
+//
+// bf16 inputs: P is split into a bf16 head and a bf16 remainder and the second product is
+// issued twice; the matrix pipe has an order of magnitude of slack on this path and it keeps
+// P to ~16 significant bits without restricting the range of V.
+#include "kernels.h"
+
+namespace fi355 {
+namespace {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
+typedef __attribute__((ext_vector_type(8))) _Float16 f16x8_t;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
+typedef __attribute__((ext_vector_type(2))) _Float16 f16x2_t;
+typedef __attribute__((ext_vector_type(4))) float f32x4_t;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4_t;
+
+template <bool BF>
+__device__ __forceinline__ f32x4_t mfma_16x16x32(u32x4_t a, u32x4_t b, f32x4_t c) {
+  if constexpr (BF) {
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a), __builtin_bit_cast(bf16x8_t, b),
+                                                   c, 0, 0, 0);
+  } else {
+    return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8_t, a), __builtin_bit_cast(f16x8_t, b), c,
+                                                  0, 0, 0);
+  }
+}
+
+template <bool BF>
+__device__ __forceinline__ uint32_t pack2(float lo, float hi) {
+  if constexpr (BF) {
+    bf16x2_t v = {static_cast<__bf16>(lo), static_cast<__bf16>(hi)};
+    return __builtin_bit_cast(uint32_t, v);
+  } else {
+    f16x2_t v = {static_cast<_Float16>(lo), static_cast<_Float16>(hi)};
+    return __builtin_bit_cast(uint32_t, v);
+  }
+}
+
+__device__ __forceinline__ float bf16_round(float x) { return static_cast<float>(static_cast<__bf16>(x)); }
+
+// (a.lo16, b.lo16) and (a.hi16, b.hi16) packed as (first, second) halves of one dword
+__device__ __forceinline__ uint32_t lo_halves(uint32_t a, uint32_t b) { return __builtin_amdgcn_perm(b, a, 0x05040100u); }
+__device__ __forceinline__ uint32_t hi_halves(uint32_t a, uint32_t b) { return __builtin_amdgcn_perm(b, a, 0x07060302u); }
+
+__device__ __forceinline__ u32x4_t ld16(const uint16_t* p) { return *reinterpret_cast<const u32x4_t*>(p); }
+
+struct KvTile {
+  u32x4_t k[2][4];  // [page][k-step s]: K[token m][d = 32 s + 8 c .. +8]
+  u32x4_t v[2][4];  // [page][i]:        V[token 4 c + i][d = 8 m .. +8]
+};
+
+template <bool BF>
+__global__ void __launch_bounds__(64) decode_kernel(const RunParams p) {
+  const int lane = threadIdx.x;
+  const int m = lane & 15;  // K: token in page; V: 16-byte column block; S/O: query head
+  const int c = lane >> 4;  // lane group
+  const int cta = blockIdx.x;
+  const int kvh = blockIdx.y;
+  const int g = p.group;
+  const int H = p.num_qo_heads;
+  const float NEG_INF = -__builtin_inff();
+
+  const uint16_t* kbase = static_cast<const uint16_t*>(p.k_pool) + kvh * p.stride_head + m * p.stride_tok + c * 8;
+  const uint16_t* vbase = static_cast<const uint16_t*>(p.v_pool) + kvh * p.stride_head + (4 * c) * p.stride_tok + m * 8;
+  const int64_t stride_tok = p.stride_tok;
+  const int64_t stride_page = p.stride_page;
+
+  const int w_begin = __builtin_amdgcn_readfirstlane(p.cta_indptr[cta]);
+  const int w_end = __builtin_amdgcn_readfirstlane(p.cta_indptr[cta + 1]);
+
+  for (int w = w_begin; w < w_end; ++w) {
+    const int q_row0 = __builtin_amdgcn_readfirstlane(p.w_q_row0[w]);
+    const int kv_page0 = __builtin_amdgcn_readfirstlane(p.w_kv_page0[w]);
+    const int kv_len = __builtin_amdgcn_readfirstlane(p.w_kv_len[w]);
+    const int out_slot = __builtin_amdgcn_readfirstlane(p.w_out_slot[w]);
+    const int n_pages = (kv_len + kPageSize - 1) / kPageSize;
+    const int n_tiles = (kv_len + 31) / 32;
+
+    // Q^T as the B operand of the first product: lane (m, c) holds head m, d = 32 s + 8 c .. +8
+    u32x4_t qreg[4];
+    if (m < g) {
+      const uint16_t* qp =
+          static_cast<const uint16_t*>(p.q) + (static_cast<int64_t>(q_row0) * H + kvh * g + m) * kHeadDim + c * 8;
+#pragma unroll
+      for (int s = 0; s < 4; ++s) qreg[s] = ld16(qp + 32 * s);
+    } else {
+#pragma unroll
+      for (int s = 0; s < 4; ++s) qreg[s] = u32x4_t{0u, 0u, 0u, 0u};
+    }
+
+    f32x4_t acc[8];  // acc[e][i] = O^T[d = 32 c + 8 i + e][head m]
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc[e] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+    float m_run = NEG_INF;  // running max of the scaled logits in log2 units (same in all 4 lane groups)
+    float l_run = 0.f;      // this lane's share of the running sum
+
+    auto load_tile = [&](KvTile& T, int t) {
+      const int pi = kv_page0 + 2 * t;
+      const int pg0 = __builtin_amdgcn_readfirstlane(p.kv_indices[pi]);
+      const int pg1 = (2 * t + 1 < n_pages) ? __builtin_amdgcn_readfirstlane(p.kv_indices[pi + 1]) : pg0;
+      const uint16_t* k0 = kbase + pg0 * stride_page;
+      const uint16_t* k1 = kbase + pg1 * stride_page;
+      const uint16_t* v0 = vbase + pg0 * stride_page;
+      const uint16_t* v1 = vbase + pg1 * stride_page;
+#pragma unroll
+      for (int s = 0; s < 4; ++s) {
+        T.k[0][s] = ld16(k0 + 32 * s);
+        T.k[1][s] = ld16(k1 + 32 * s);
+      }
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        T.v[0][i] = ld16(v0 + i * stride_tok);
+        T.v[1][i] = ld16(v1 + i * stride_tok);
+      }
+    };
+
+    auto compute_tile = [&](KvTile& T, int t) {
+      // ---- S^T = K . Q^T ----
+      f32x4_t s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int s = 0; s < 4; ++s) {
+        s0 = mfma_16x16x32<BF>(T.k[0][s], qreg[s], s0);
+        s1 = mfma_16x16x32<BF>(T.k[1][s], qreg[s], s1);
+      }
+      // lane (m, c) now holds S^T[token 16 pg + 4 c + i][head m]
+      const int tok0 = 32 * t + 4 * c;
+      float sv[8];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        sv[i] = s0[i] * p.scale_log2;
+        sv[4 + i] = s1[i] * p.scale_log2;
+      }
+      if (32 * t + 32 > kv_len) {  // ragged tail: hide tokens past the chunk, and zero their V rows
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const bool ok0 = tok0 + i < kv_len;
+          const bool ok1 = tok0 + 16 + i < kv_len;
+          sv[i] = ok0 ? sv[i] : NEG_INF;
+          sv[4 + i] = ok1 ? sv[4 + i] : NEG_INF;
+          if (!ok0) T.v[0][i] = u32x4_t{0u, 0u, 0u, 0u};
+          if (!ok1) T.v[1][i] = u32x4_t{0u, 0u, 0u, 0u};
+        }
+      }
+      // ---- online softmax ----
+      float tmax = fmaxf(fmaxf(fmaxf(sv[0], sv[1]), fmaxf(sv[2], sv[3])), fmaxf(fmaxf(sv[4], sv[5]), fmaxf(sv[6], sv[7])));
+      tmax = fmaxf(tmax, __shfl_xor(tmax, 16));
+      tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
+      const float m_new = fmaxf(m_run, tmax);  // finite: a tile always holds at least one valid token
+      const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+      m_run = m_new;
+      float pv[8];
+      float psum = 0.f;
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        pv[j] = __builtin_amdgcn_exp2f(sv[j] - m_new);
+        psum += pv[j];
+      }
+      l_run = l_run * alpha + psum;
+      if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[e] *= alpha;
+      }
+      // ---- P^T as B operand: register j <-> (page j / 4, token 4 c + j % 4) ----
+      u32x4_t pb, pb_lo;
+      pb = u32x4_t{pack2<BF>(pv[0], pv[1]), pack2<BF>(pv[2], pv[3]), pack2<BF>(pv[4], pv[5]), pack2<BF>(pv[6], pv[7])};
+      if constexpr (BF) {
+        float r[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) r[j] = pv[j] - bf16_round(pv[j]);
+        pb_lo = u32x4_t{pack2<BF>(r[0], r[1]), pack2<BF>(r[2], r[3]), pack2<BF>(r[4], r[5]), pack2<BF>(r[6], r[7])};
+      }
+      // ---- O^T += V^T . P^T, one product per column e of the lane's 8-wide block ----
+#pragma unroll
+      for (int wd = 0; wd < 4; ++wd) {
+        const uint32_t a0 = T.v[0][0][wd], a1 = T.v[0][1][wd], a2 = T.v[0][2][wd], a3 = T.v[0][3][wd];
+        const uint32_t b0 = T.v[1][0][wd], b1 = T.v[1][1][wd], b2 = T.v[1][2][wd], b3 = T.v[1][3][wd];
+        const u32x4_t vt_even = {lo_halves(a0, a1), lo_halves(a2, a3), lo_halves(b0, b1), lo_halves(b2, b3)};
+        const u32x4_t vt_odd = {hi_halves(a0, a1), hi_halves(a2, a3), hi_halves(b0, b1), hi_halves(b2, b3)};
+        acc[2 * wd] = mfma_16x16x32<BF>(vt_even, pb, acc[2 * wd]);
+        acc[2 * wd + 1] = mfma_16x16x32<BF>(vt_odd, pb, acc[2 * wd + 1]);
+        if constexpr (BF) {
+          acc[2 * wd] = mfma_16x16x32<BF>(vt_even, pb_lo, acc[2 * wd]);
+          acc[2 * wd + 1] = mfma_16x16x32<BF>(vt_odd, pb_lo, acc[2 * wd + 1]);
+        }
+      }
+    };
+
+    KvTile TA, TB;
+    if (n_tiles > 0) load_tile(TA, 0);
+    if (n_tiles > 1) load_tile(TB, 1);
+    for (int t = 0; t < n_tiles; t += 2) {
+      compute_tile(TA, t);
+      if (t + 2 < n_tiles) load_tile(TA, t + 2);
+      if (t + 1 < n_tiles) {
+        compute_tile(TB, t + 1);
+        if (t + 3 < n_tiles) load_tile(TB, t + 3);
+      }
+    }
+
+    // ---- epilogue: o = O / l, lse = ln(sum exp) (Sec. 2.2) ----
+    l_run += __shfl_xor(l_run, 16);
+    l_run += __shfl_xor(l_run, 32);
+    const bool live = l_run > 0.f;
+    const float inv = live ? 1.0f / l_run : 0.f;
+    const float lse_val = live ? (m_run + __builtin_amdgcn_logf(l_run)) * 0.6931471805599453f : NEG_INF;
+    if (m < g) {
+      const int head = kvh * g + m;
+      float* dst_o;
+      float* dst_lse;
+      if (out_slot < 0) {  // write-through (App. D.2)
+        const int64_t row = static_cast<int64_t>(q_row0) * H + head;
+        dst_o = p.o + row * kHeadDim;
+        dst_lse = p.lse + row;
+      } else {
+        const int64_t row = static_cast<int64_t>(out_slot) * H + head;
+        dst_o = p.part_o + row * kHeadDim;
+        dst_lse = p.part_lse + row;
+      }
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        float* d = dst_o + 32 * c + 8 * i;
+        const f32x4_t lo = {acc[0][i] * inv, acc[1][i] * inv, acc[2][i] * inv, acc[3][i] * inv};
+        const f32x4_t hi = {acc[4][i] * inv, acc[5][i] * inv, acc[6][i] * inv, acc[7][i] * inv};
+        *reinterpret_cast<f32x4_t*>(d) = lo;
+        *reinterpret_cast<f32x4_t*>(d + 4) = hi;
+        if (out_slot < 0 && p.o_cast != nullptr) {
+          uint16_t* dc = static_cast<uint16_t*>(p.o_cast) +
+                         (static_cast<int64_t>(q_row0) * H + head) * kHeadDim + 32 * c + 8 * i;
+          const u32x4_t pk = {pack2<BF>(lo[0], lo[1]), pack2<BF>(lo[2], lo[3]), pack2<BF>(hi[0], hi[1]),
+                              pack2<BF>(hi[2], hi[3])};
+          *reinterpret_cast<u32x4_t*>(dc) = pk;
+        }
+      }
+      if (c == 0) *dst_lse = lse_val;
+    }
+  }
+}
+
+}  // namespace
+
+hipError_t launch_decode(const RunParams& p, bool is_bf16, hipStream_t stream) {
+  const dim3 grid(static_cast<unsigned>(p.ctas_per_head), static_cast<unsigned>(p.num_kv_heads), 1);
+  const dim3 block(64, 1, 1);
+  if (is_bf16)
+    hipLaunchKernelGGL(decode_kernel<true>, grid, block, 0, stream, p);
+  else
+    hipLaunchKernelGGL(decode_kernel<false>, grid, block, 0, stream, p);
+  return hipGetLastError();
+}
+
+}  // namespace fi355

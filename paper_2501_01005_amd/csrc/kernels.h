@@ -1,0 +1,63 @@
+// Launch interface between the C-ABI layer and the gfx950 kernels.
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+
+namespace fi355 {
+
+// Everything a persistent attention launch reads.  The plan arrays live in the
+// fixed plan section of the device workspace (App. D.1).
+struct RunParams {
+  const int32_t* cta_indptr;
+  const int32_t* w_q_row0;
+  const int32_t* w_n_pos;
+  const int32_t* w_kv_page0;
+  const int32_t* w_kv_len;
+  const int32_t* w_diag0;
+  const int32_t* w_out_slot;
+  const int32_t* kv_indices;
+  const void* q;
+  const void* k_pool;
+  const void* v_pool;
+  int64_t stride_page, stride_head, stride_tok;  // elements
+  float* o;
+  float* lse;
+  void* o_cast;     // may be null
+  float* part_o;    // [max_slots * t_pos * H_qo, D]
+  float* part_lse;  // [max_slots * t_pos * H_qo]
+  float scale_log2; // sm_scale * log2(e)
+  int32_t num_qo_heads, num_kv_heads, group, t_pos;
+  int32_t ctas_per_head;
+};
+
+struct MergeParams {
+  const int32_t* header;  // plan header: [H_N_MERGE] read on the device
+  const int32_t* m_q_row0;
+  const int32_t* m_n_pos;
+  const int32_t* m_slot_base;
+  const int32_t* m_n_chunks;
+  const float* part_o;
+  const float* part_lse;
+  float* o;
+  float* lse;
+  void* o_cast;
+  int32_t num_qo_heads, t_pos, is_bf16;
+};
+
+// decode.hip: query tile = 1 position x g fused heads, one wavefront per CTA.
+hipError_t launch_decode(const RunParams& p, bool is_bf16, hipStream_t stream);
+// append.hip: query tile = 128/g positions x g fused heads, 4 wavefronts per CTA.
+hipError_t launch_append(const RunParams& p, bool is_bf16, hipStream_t stream);
+// merge.hip
+hipError_t launch_merge_planned(const MergeParams& p, int32_t grid, hipStream_t stream);
+hipError_t launch_merge_states(const float* o_parts, const float* lse_parts, int64_t n_rows, int32_t n_states,
+                               float* o, float* lse, hipStream_t stream);
+hipError_t launch_merge_pair(const float* o_a, const float* lse_a, const float* o_b, const float* lse_b,
+                             int64_t n_rows, float* o, float* lse, hipStream_t stream);
+
+constexpr int kHeadDim = 128;
+constexpr int kPageSize = 16;
+constexpr int kMergeGrid = 1024;  // fixed grid of the planned merge launch
+
+}  // namespace fi355

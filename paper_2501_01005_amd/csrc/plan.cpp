@@ -1,0 +1,201 @@
+// Load-balanced partition of KV ranges over a fixed number of CTAs: Algorithm 1 of
+// Sec. 3.3.1, with the output index map of App. D.2 (write-through for unsplit tiles)
+// and the slot bound of App. D.3.  Heads are left out, as in the paper: every kv head
+// executes the same queues.
+#include "plan.h"
+
+#include <algorithm>
+#include <functional>
+#include <queue>
+#include <utility>
+
+#include "../../include/fi355.h"
+
+namespace fi355 {
+
+static size_t round_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+void WorkspaceLayout::init(int32_t ctas, int32_t max_qo_tiles, int32_t t_pos, int32_t num_qo_heads,
+                           int32_t head_dim) {
+  ctas_per_head = ctas;
+  // sum_t ceil(kv_eff(t) / L_kv) <= n_tiles + S / L_kv <= n_tiles + #CTA
+  max_work = max_qo_tiles + ctas;
+  max_merge = ctas;
+  max_slots = 2 * ctas;
+  size_t o = 0;
+  off_header = o;
+  o += kHeaderInts;
+  off_cta_indptr = o;
+  o += static_cast<size_t>(ctas) + 1;
+  for (int a = 0; a < kWorkArrays; ++a) {
+    off_work[a] = o;
+    o += static_cast<size_t>(max_work);
+  }
+  for (int a = 0; a < kMergeArrays; ++a) {
+    off_merge[a] = o;
+    o += static_cast<size_t>(max_merge);
+  }
+  plan_ints = o;
+  plan_bytes = round_up(o * sizeof(int32_t), 256);
+  const size_t rows = static_cast<size_t>(max_slots) * t_pos * num_qo_heads;
+  off_part_lse = plan_bytes;
+  off_part_o = round_up(off_part_lse + rows * sizeof(float), 256);
+  total_bytes = round_up(off_part_o + rows * head_dim * sizeof(float), 256);
+}
+
+namespace {
+struct Tile {
+  int32_t request, start, n_pos, kv_eff, diag0, q_row0, kv_page_base;
+  int32_t n_chunks, slot_base;
+};
+struct Chunk {
+  int32_t tile, kv_start, kv_len, in_tile;
+};
+}  // namespace
+
+int32_t make_plan(const PlanParams& pp, const WorkspaceLayout& L, const int32_t* qo_indptr,
+                  const int32_t* kv_indptr, const int32_t* last_page_len, int32_t batch,
+                  int32_t* plan, std::string* err) {
+  auto fail = [&](int32_t code, const std::string& msg) {
+    if (err) *err = msg;
+    return code;
+  };
+  if (!qo_indptr || !kv_indptr || (batch > 0 && !last_page_len) || !plan)
+    return fail(FI_ERR_INVALID_ARG, "fi_plan: null array");
+  if (batch < 0 || batch > pp.max_batch)
+    return fail(FI_ERR_INVALID_ARG, "fi_plan: batch " + std::to_string(batch) + " outside [0, max_batch=" +
+                                        std::to_string(pp.max_batch) + "]");
+  if (qo_indptr[0] != 0 || kv_indptr[0] != 0) return fail(FI_ERR_INVALID_ARG, "fi_plan: indptr[0] must be 0");
+
+  const int32_t ps = pp.page_size;
+  const int64_t C = pp.ctas_per_head;
+
+  // ---- lengths, query tiles, and the KV range each tile needs ----
+  std::vector<Tile> tiles;
+  int64_t S = 0;
+  for (int32_t i = 0; i < batch; ++i) {
+    const int64_t l_qo = static_cast<int64_t>(qo_indptr[i + 1]) - qo_indptr[i];
+    const int64_t n_pg = static_cast<int64_t>(kv_indptr[i + 1]) - kv_indptr[i];
+    if (l_qo < 0 || n_pg < 0)
+      return fail(FI_ERR_INVALID_ARG, "fi_plan: indptr decreases at request " + std::to_string(i));
+    if (n_pg > 0 && (last_page_len[i] < 1 || last_page_len[i] > ps))
+      return fail(FI_ERR_INVALID_ARG, "fi_plan: last_page_len[" + std::to_string(i) + "] = " +
+                                          std::to_string(last_page_len[i]) + " outside [1, page_size]");
+    const int64_t l_kv = n_pg == 0 ? 0 : (n_pg - 1) * ps + last_page_len[i];
+    if (l_kv >= kNoDiag) return fail(FI_ERR_INVALID_ARG, "fi_plan: request too long");
+    const int64_t n_tiles = (l_qo + pp.t_pos - 1) / pp.t_pos;
+    if (static_cast<int64_t>(tiles.size()) + n_tiles > pp.max_qo_tiles)
+      return fail(FI_ERR_INVALID_ARG, "fi_plan: more query tiles than max_qo_tiles=" + std::to_string(pp.max_qo_tiles));
+    for (int64_t t = 0; t < n_tiles; ++t) {
+      Tile tl;
+      tl.request = i;
+      tl.start = static_cast<int32_t>(t * pp.t_pos);
+      const int64_t end = std::min<int64_t>(tl.start + pp.t_pos, l_qo);
+      tl.n_pos = static_cast<int32_t>(end - tl.start);
+      if (pp.causal) {
+        tl.kv_eff = static_cast<int32_t>(std::max<int64_t>(0, std::min<int64_t>(l_kv, l_kv - l_qo + end)));
+        tl.diag0 = static_cast<int32_t>(l_kv - l_qo + tl.start);
+      } else {
+        tl.kv_eff = static_cast<int32_t>(l_kv);
+        tl.diag0 = kNoDiag;
+      }
+      tl.q_row0 = qo_indptr[i] + tl.start;
+      tl.kv_page_base = kv_indptr[i];
+      tl.n_chunks = 1;
+      tl.slot_base = -1;
+      tiles.push_back(tl);
+      S += pp.literal_lkv ? l_kv : tl.kv_eff;
+    }
+  }
+
+  // ---- maximum chunk size L_kv: S / #CTA, whole pages, at least min_chunk ----
+  const int64_t min_chunk = (static_cast<int64_t>(pp.min_chunk) + ps - 1) / ps * ps;
+  int64_t Lkv = (S + C - 1) / C;
+  Lkv = (Lkv + ps - 1) / ps * ps;
+  Lkv = std::max(min_chunk, Lkv);
+
+  // ---- split every tile's KV range into chunks of at most L_kv; number the chunks ----
+  std::vector<Chunk> chunks;
+  int32_t next_slot = 0, n_merge = 0;
+  for (size_t ti = 0; ti < tiles.size(); ++ti) {
+    Tile& tl = tiles[ti];
+    tl.n_chunks = static_cast<int32_t>(std::max<int64_t>(1, (tl.kv_eff + Lkv - 1) / Lkv));
+    if (tl.n_chunks > 1) {
+      tl.slot_base = next_slot;
+      next_slot += tl.n_chunks;
+      ++n_merge;
+    }
+    for (int32_t c = 0; c < tl.n_chunks; ++c) {
+      Chunk ch;
+      ch.tile = static_cast<int32_t>(ti);
+      ch.kv_start = static_cast<int32_t>(c * Lkv);
+      ch.kv_len = static_cast<int32_t>(std::min<int64_t>(ch.kv_start + Lkv, tl.kv_eff) - ch.kv_start);
+      ch.in_tile = c;
+      chunks.push_back(ch);
+    }
+  }
+  const int32_t n_work = static_cast<int32_t>(chunks.size());
+  if (n_work > L.max_work || next_slot > L.max_slots || n_merge > L.max_merge)
+    return fail(FI_ERR_WORKSPACE_TOO_SMALL, "fi_plan: plan exceeds the workspace sections (internal bound)");
+
+  // ---- descending length (ties: lower work index first) ----
+  std::vector<int32_t> order(n_work);
+  for (int32_t w = 0; w < n_work; ++w) order[w] = w;
+  std::stable_sort(order.begin(), order.end(),
+                   [&](int32_t a, int32_t b) { return chunks[a].kv_len > chunks[b].kv_len; });
+
+  // ---- least-loaded CTA first (ties: lower CTA index) ----
+  using Entry = std::pair<int64_t, int32_t>;  // (accumulated cost, cta)
+  std::priority_queue<Entry, std::vector<Entry>, std::greater<Entry>> heap;
+  for (int32_t c = 0; c < C; ++c) heap.push({0, c});
+  std::vector<std::vector<int32_t>> queues(static_cast<size_t>(C));
+  const int64_t t_q = static_cast<int64_t>(pp.t_pos) * pp.group;
+  for (int32_t w : order) {
+    Entry e = heap.top();
+    heap.pop();
+    queues[e.second].push_back(w);
+    e.first += pp.alpha * t_q + static_cast<int64_t>(pp.beta) * chunks[w].kv_len;
+    heap.push(e);
+  }
+
+  // ---- emit the plan section ----
+  std::fill(plan, plan + L.plan_ints, 0);
+  int32_t* hdr = plan + L.off_header;
+  hdr[H_N_WORK] = n_work;
+  hdr[H_N_MERGE] = n_merge;
+  hdr[H_N_SLOTS] = next_slot;
+  hdr[H_L_KV] = static_cast<int32_t>(Lkv);
+  hdr[H_T_POS] = pp.t_pos;
+  hdr[H_CTAS] = static_cast<int32_t>(C);
+  int32_t* cta_indptr = plan + L.off_cta_indptr;
+  int32_t k = 0;
+  for (int32_t c = 0; c < C; ++c) {
+    cta_indptr[c] = k;
+    for (int32_t w : queues[c]) {
+      const Chunk& ch = chunks[w];
+      const Tile& tl = tiles[ch.tile];
+      plan[L.off_work[W_REQUEST] + k] = tl.request;
+      plan[L.off_work[W_Q_ROW0] + k] = tl.q_row0;
+      plan[L.off_work[W_N_POS] + k] = tl.n_pos;
+      plan[L.off_work[W_KV_PAGE0] + k] = tl.kv_page_base + ch.kv_start / ps;
+      plan[L.off_work[W_KV_START] + k] = ch.kv_start;
+      plan[L.off_work[W_KV_LEN] + k] = ch.kv_len;
+      plan[L.off_work[W_DIAG0] + k] = tl.diag0;
+      plan[L.off_work[W_OUT_SLOT] + k] = tl.slot_base < 0 ? -1 : tl.slot_base + ch.in_tile;
+      ++k;
+    }
+  }
+  cta_indptr[C] = k;
+  int32_t mi = 0;
+  for (const Tile& tl : tiles) {
+    if (tl.slot_base < 0) continue;
+    plan[L.off_merge[M_Q_ROW0] + mi] = tl.q_row0;
+    plan[L.off_merge[M_N_POS] + mi] = tl.n_pos;
+    plan[L.off_merge[M_SLOT_BASE] + mi] = tl.slot_base;
+    plan[L.off_merge[M_N_CHUNKS] + mi] = tl.n_chunks;
+    ++mi;
+  }
+  return FI_OK;
+}
+
+}  // namespace fi355

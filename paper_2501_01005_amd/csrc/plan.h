@@ -1,0 +1,60 @@
+// Host-side scheduler (Algorithm 1, Sec. 3.3.1) and workspace layout (App. D).
+// Integer-only C++; no HIP types here.
+#pragma once
+#include <cstddef>
+#include <cstdint>
+#include <string>
+#include <vector>
+
+namespace fi355 {
+
+constexpr int32_t kNoDiag = 0x3FFFFFFF;
+constexpr int kHeaderInts = 16;
+constexpr int kWorkArrays = 8;   // request, q_row0, n_pos, kv_page0, kv_start, kv_len, diag0, out_slot
+constexpr int kMergeArrays = 4;  // q_row0, n_pos, slot_base, n_chunks
+
+// Indices of the per-work-item arrays inside the plan section.
+enum WorkField { W_REQUEST = 0, W_Q_ROW0, W_N_POS, W_KV_PAGE0, W_KV_START, W_KV_LEN, W_DIAG0, W_OUT_SLOT };
+enum MergeField { M_Q_ROW0 = 0, M_N_POS, M_SLOT_BASE, M_N_CHUNKS };
+enum HeaderField { H_N_WORK = 0, H_N_MERGE, H_N_SLOTS, H_L_KV, H_T_POS, H_CTAS };
+
+// Section offsets depend only on the creation-time configuration, so the pointers a
+// captured launch holds stay valid across plans (App. D.1).
+struct WorkspaceLayout {
+  int32_t ctas_per_head = 0;  // #CTA of Algorithm 1
+  int32_t max_work = 0;       // max_qo_tiles + ctas_per_head
+  int32_t max_merge = 0;      // ctas_per_head
+  int32_t max_slots = 0;      // 2 * ctas_per_head (App. D.3)
+  size_t off_header = 0;      // int32 offsets (in ints) inside the plan section
+  size_t off_cta_indptr = 0;
+  size_t off_work[kWorkArrays] = {};
+  size_t off_merge[kMergeArrays] = {};
+  size_t plan_ints = 0;       // ints in the plan section
+  size_t plan_bytes = 0;      // rounded up to 256
+  size_t off_part_lse = 0;    // byte offsets in the device workspace
+  size_t off_part_o = 0;
+  size_t total_bytes = 0;
+
+  void init(int32_t ctas, int32_t max_qo_tiles, int32_t t_pos, int32_t num_qo_heads, int32_t head_dim);
+};
+
+struct PlanParams {
+  int32_t page_size = 16;
+  int32_t t_pos = 1;
+  int32_t group = 1;
+  int32_t ctas_per_head = 1;
+  int32_t alpha = 1, beta = 1;
+  int32_t min_chunk = 16;
+  bool causal = false;
+  bool literal_lkv = false;
+  int32_t max_batch = 0;
+  int32_t max_qo_tiles = 0;
+};
+
+// Runs the partition and writes the plan section (header, queues, work items, merge list)
+// into `plan` (layout.plan_ints ints).  Returns 0 or a negative FI_ERR_* with `err` set.
+int32_t make_plan(const PlanParams& pp, const WorkspaceLayout& layout, const int32_t* qo_indptr,
+                  const int32_t* kv_indptr, const int32_t* last_page_len, int32_t batch,
+                  int32_t* plan, std::string* err);
+
+}  // namespace fi355

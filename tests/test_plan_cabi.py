@@ -1,0 +1,160 @@
+"""Host logic of the C-ABI library, runnable without a GPU: the exported symbols, the
+planner (bit-exact against the replica of Algorithm 1), argument errors."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_2501_01005_amd as fi
+from oracle.plan_replica import plan_replica
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+PLAN_KEYS = ("cta_indptr", "w_request", "w_q_row0", "w_n_pos", "w_kv_page0", "w_kv_start", "w_kv_len", "w_diag0",
+             "w_out_slot", "m_q_row0", "m_n_pos", "m_slot_base", "m_n_chunks")
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "fi355.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    names = set(re.findall(r"\b(fi_[a-z_]+)\s*\(", header))
+    assert {"fi_create", "fi_destroy", "fi_workspace_bytes", "fi_plan", "fi_plan_view", "fi_run",
+            "fi_merge_states", "fi_merge_state_pair", "fi_check_indices", "fi_last_error"} <= names
+    L = ctypes.CDLL(fi.library_path())
+    for n in names:
+        assert hasattr(L, n), n
+
+
+def make(mode, g, C, Hkv=2, max_batch=64, max_tiles=4096, **kw):
+    return fi.fi_create(dtype=fi.FI_DTYPE_BF16, num_qo_heads=g * Hkv, num_kv_heads=Hkv, head_dim=128, page_size=16,
+                        mode=mode, num_ctas=C * Hkv, max_batch=max_batch, max_qo_tiles=max_tiles, **kw)
+
+
+def indptrs(qo, kv, ps=16):
+    qo_indptr = np.concatenate([[0], np.cumsum(qo)]).astype(np.int32)
+    n_pg = (np.asarray(kv) + ps - 1) // ps
+    kv_indptr = np.concatenate([[0], np.cumsum(n_pg)]).astype(np.int32)
+    last = np.where(n_pg > 0, np.asarray(kv) - (n_pg - 1) * ps, 0).astype(np.int32)
+    return qo_indptr, kv_indptr, last
+
+
+def compare(h, qo, kv, causal, t_pos, g, C, alpha, beta, min_chunk, literal=False):
+    qo_indptr, kv_indptr, last = indptrs(qo, kv)
+    fi.fi_plan(h, qo_indptr, kv_indptr, last, causal)
+    got = fi.fi_plan_view(h)
+    want = plan_replica(qo_indptr, kv_indptr, last, page_size=16, t_pos=t_pos, group=g, num_ctas=C, causal=causal,
+                        alpha=alpha, beta=beta, min_chunk=min_chunk, literal_lkv=literal)
+    assert got["l_kv_chunk"] == want["L_kv"] and got["n_work"] == want["n_work"]
+    assert got["n_merge"] == want["n_merge"] and got["n_slots"] == want["n_slots"]
+    assert got["t_pos"] == t_pos and got["group"] == g and got["ctas_per_head"] == C
+    for k in PLAN_KEYS:
+        assert got[k].dtype == np.int32
+        assert got[k].tobytes() == np.asarray(want[k], dtype=np.int32).tobytes(), k
+
+
+@pytest.mark.parametrize("mode", ["decode", "append"])
+def test_planner_equals_replica_on_random_length_sets(mode):
+    rng = np.random.default_rng(7 if mode == "decode" else 8)
+    n_cases = 0
+    for g in (1, 4):
+        for C in (1, 5, 32, 256):
+            for (alpha, beta, min_chunk) in ((1, 1, 16), (0, 1, 256), (3, 2, 64)):
+                t_pos = 1 if mode == "decode" else 128 // g
+                h = make(fi.FI_MODE_DECODE if mode == "decode" else fi.FI_MODE_APPEND, g, C, alpha=alpha, beta=beta,
+                         min_chunk=min_chunk)
+                for trial in range(25):
+                    B = int(rng.integers(1, 48))
+                    if mode == "decode":
+                        qo = np.ones(B, dtype=np.int64)
+                        kv = rng.integers(0, 4000, size=B)
+                        r = rng.random()
+                        if r < 0.25:
+                            kv[rng.integers(0, B)] = int(rng.integers(30000, 300000))
+                        elif r < 0.4:
+                            kv[:] = int(rng.integers(1, 700))
+                        elif r < 0.5:
+                            B = 1; qo = qo[:1]; kv = kv[:1]
+                    else:
+                        qo = rng.integers(0, 600, size=B)
+                        kv = qo + rng.integers(0, 3000, size=B)
+                        if rng.random() < 0.2:
+                            kv = np.maximum(kv - rng.integers(0, 100, size=B), 0)
+                    compare(h, qo, kv, mode == "append", t_pos, g, C, alpha, beta, min_chunk)
+                    n_cases += 1
+                fi.fi_destroy(h)
+    assert n_cases >= 600
+
+
+def test_planner_equals_replica_on_the_benchmark_length_sets():
+    import workloads
+    g2 = np.random.Generator(np.random.PCG64(1002))
+    kv2 = workloads.zipf_lengths(g2, 128, 256, 32768, 1.2); kv2[0] = 32768
+    h = make(fi.FI_MODE_DECODE, 4, 256, Hkv=8, max_batch=128, min_chunk=256)
+    compare(h, np.ones(128, dtype=np.int64), kv2, False, 1, 4, 256, 1, 1, 256)
+    compare(h, [1, 1], [131072, 65536], False, 1, 4, 256, 1, 1, 256)
+    fi.fi_destroy(h)
+    g3 = np.random.Generator(np.random.PCG64(1003))
+    qo = g3.integers(128, 1025, size=16); pre = g3.integers(0, 4097, size=16)
+    h = make(fi.FI_MODE_APPEND, 4, 64, Hkv=8, max_batch=16, max_tiles=1024, min_chunk=256)
+    compare(h, qo, qo + pre, True, 32, 4, 64, 1, 1, 256)
+    fi.fi_destroy(h)
+    h = make(fi.FI_MODE_APPEND, 4, 64, Hkv=8, max_batch=16, max_tiles=1024, min_chunk=256, literal_lkv=1)
+    compare(h, qo, qo + pre, True, 32, 4, 64, 1, 1, 256, literal=True)
+    fi.fi_destroy(h)
+
+
+def test_plan_is_deterministic_and_sections_do_not_move():
+    h = make(fi.FI_MODE_DECODE, 4, 16)
+    sizes = fi.fi_workspace_bytes(h)
+    rng = np.random.default_rng(3)
+    kv = rng.integers(1, 9000, size=20)
+    qo_indptr, kv_indptr, last = indptrs(np.ones(20, dtype=np.int64), kv)
+    fi.fi_plan(h, qo_indptr, kv_indptr, last, False)
+    a = fi.fi_plan_view(h)
+    fi.fi_plan(h, *indptrs(np.ones(3, dtype=np.int64), [5, 6, 7]), False)
+    assert fi.fi_workspace_bytes(h) == sizes                 # layout depends on the config only (App. D.1)
+    fi.fi_plan(h, qo_indptr, kv_indptr, last, False)
+    b = fi.fi_plan_view(h)
+    for k in PLAN_KEYS:
+        assert a[k].tobytes() == b[k].tobytes()
+    fi.fi_destroy(h)
+
+
+def expect(code, fn, *a, **kw):
+    with pytest.raises(fi.Fi355Error) as e:
+        fn(*a, **kw)
+    assert e.value.code == code and e.value.message
+
+
+def test_argument_errors():
+    ok = dict(dtype=fi.FI_DTYPE_BF16, num_qo_heads=32, num_kv_heads=8, head_dim=128, page_size=16,
+              mode=fi.FI_MODE_DECODE, num_ctas=64, max_batch=4, max_qo_tiles=4)
+    expect(fi.FI_ERR_UNSUPPORTED, fi.fi_create, **{**ok, "head_dim": 64})
+    expect(fi.FI_ERR_UNSUPPORTED, fi.fi_create, **{**ok, "page_size": 8})
+    expect(fi.FI_ERR_UNSUPPORTED, fi.fi_create, **{**ok, "num_qo_heads": 64})       # g = 8 in decode mode
+    expect(fi.FI_ERR_INVALID_ARG, fi.fi_create, **{**ok, "num_qo_heads": 30})
+    expect(fi.FI_ERR_INVALID_ARG, fi.fi_create, **{**ok, "dtype": 7})
+    expect(fi.FI_ERR_INVALID_ARG, fi.fi_create, **{**ok, "max_batch": 0})
+    h = fi.fi_create(**ok)
+    expect(fi.FI_ERR_NOT_PLANNED, fi.fi_plan_view, h)
+    expect(fi.FI_ERR_INVALID_ARG, fi.fi_plan, h, [1, 2], [0, 1], [3], False)            # indptr[0] != 0
+    expect(fi.FI_ERR_INVALID_ARG, fi.fi_plan, h, [0, 1, 0], [0, 1, 2], [3, 3], False)   # decreasing
+    expect(fi.FI_ERR_INVALID_ARG, fi.fi_plan, h, [0, 1], [0, 1], [0], False)            # last_page_len = 0
+    expect(fi.FI_ERR_INVALID_ARG, fi.fi_plan, h, [0, 1], [0, 1], [17], False)
+    expect(fi.FI_ERR_INVALID_ARG, fi.fi_plan, h, np.arange(6), np.arange(6), [1] * 5, False)   # batch > max_batch
+    expect(fi.FI_ERR_INVALID_ARG, fi.fi_plan, h, [0, 9], [0, 1], [3], False)            # 9 tiles > max_qo_tiles
+    expect(fi.FI_ERR_NOT_PLANNED, fi.fi_plan_view, h)                                   # a failed plan leaves none
+    fi.fi_plan(h, [0, 1], [0, 0], [0], False)                                           # empty request is fine
+    assert fi.fi_plan_view(h)["n_work"] == 1
+    # fi_run needs a plan that went to a device workspace
+    dummy = np.zeros(64, dtype=np.uint8)
+    expect(fi.FI_ERR_NOT_PLANNED, fi.fi_run, h, dummy, dummy, dummy, (1, 1, 1), dummy, 1.0, dummy, dummy)
+    # workspace too small is detected before anything is touched
+    expect(fi.FI_ERR_WORKSPACE_TOO_SMALL, fi.fi_plan, h, [0, 1], [0, 1], [3], False, workspace=dummy,
+           workspace_bytes=64)
+    fi.fi_destroy(h)
+    expect(fi.FI_ERR_INVALID_ARG, fi.fi_check_indices, [0, 5, 2], 5)
+    expect(fi.FI_ERR_INVALID_ARG, fi.fi_check_indices, [0, -1], 5)
+    fi.fi_check_indices([0, 4, 2], 5)
+    expect(fi.FI_ERR_UNSUPPORTED, fi.fi_merge_states, dummy, dummy, 1, 1, 64, dummy, dummy)
