@@ -1,0 +1,224 @@
+#!/usr/bin/env python3
+"""Benchmark of the paged-attention hot path on one MI355X.
+
+Default workload ("c2"): batched GQA decode, Llama-3-8B layer shape, batch 128, 32/8 heads,
+D 128, bf16, page 16, KV lengths Zipf(1.2) over [256, 32768] (seeded synthetic; see
+workloads.config2).  One step = one pass of the whole hot path over the batch:
+fi_plan (host scheduler + async copy of the plan) -> fi_run (persistent attention launch +
+merge launch).  Inputs are resident in HBM before the timed region starts.
+
+Prints ONE JSON line: metric = achieved HBM bandwidth of the step (algorithmic bytes / step
+time), plus `roofline` for the dominant kernel (timed with HIP events recorded by the library
+around that kernel on the launch stream) and `cpu_baseline` (the fp64 oracle on host cores).
+"""
+from __future__ import annotations
+
+import argparse
+import ctypes
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+MFMA_PEAK_TFLOPS = 2516.6
+
+
+class HipEvents:
+    """Raw HIP events (the library records them around its attention kernel)."""
+
+    def __init__(self, n: int):
+        import torch  # noqa: F401  (torch's HIP runtime is the one in this process)
+        self.hip = ctypes.CDLL("libamdhip64.so")
+        self.hip.hipEventCreate.argtypes = [ctypes.POINTER(ctypes.c_void_p)]
+        self.hip.hipEventElapsedTime.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_void_p, ctypes.c_void_p]
+        self.hip.hipEventSynchronize.argtypes = [ctypes.c_void_p]
+        self.hip.hipEventDestroy.argtypes = [ctypes.c_void_p]
+        self.start, self.stop = [], []
+        for _ in range(n):
+            for lst in (self.start, self.stop):
+                e = ctypes.c_void_p()
+                rc = self.hip.hipEventCreate(ctypes.byref(e))
+                if rc != 0:
+                    raise RuntimeError(f"hipEventCreate failed: {rc}")
+                lst.append(e)
+
+    def elapsed_ms(self, i: int) -> float:
+        self.hip.hipEventSynchronize(self.stop[i])
+        ms = ctypes.c_float()
+        rc = self.hip.hipEventElapsedTime(ctypes.byref(ms), self.start[i], self.stop[i])
+        if rc != 0:
+            raise RuntimeError(f"hipEventElapsedTime failed: {rc}")
+        return float(ms.value)
+
+    def close(self):
+        for e in self.start + self.stop:
+            self.hip.hipEventDestroy(e)
+
+
+def decode_algorithmic_bytes(batch, plan_view) -> dict:
+    """Algorithmic HBM bytes of one decode step: K and V of every attended token once per
+    kv head (head-group fusion: not once per query head), q, the (o, lse) rows, one int32 per
+    page, and for every split chunk the partial state written by the attention kernel and read
+    again by the merge."""
+    H, Hk, D = batch.num_qo_heads, batch.num_kv_heads, batch.head_dim
+    tokens = int(batch.kv_lens().sum())
+    kv = tokens * Hk * D * 2 * 2
+    n_rows = int(batch.qo_indptr[-1]) * H
+    q = n_rows * D * 2
+    out = n_rows * (D + 1) * 4
+    idx = int(batch.kv_indptr[-1]) * 4
+    n_split = int((plan_view["w_out_slot"] >= 0).sum())
+    part = n_split * plan_view["t_pos"] * H * (D + 1) * 4
+    final_rows_by_attn = n_rows - int(plan_view["m_n_pos"].sum()) * H
+    attn = kv + q + idx + part + final_rows_by_attn * (D + 1) * 4
+    return dict(kv=kv, q=q, out=out, idx=idx, partial_write=part, attention_kernel=attn,
+                step=kv + q + out + idx + 2 * part, tokens=tokens)
+
+
+def append_algorithmic_flops(batch) -> int:
+    """4*D flop per unmasked (query row, key) pair per query head."""
+    qo, kv = batch.qo_lens().astype(np.int64), batch.kv_lens().astype(np.int64)
+    pairs = 0
+    for lq, lk in zip(qo, kv):
+        j = np.arange(lq)
+        pairs += int(np.clip(lk - lq + j + 1, 0, lk).sum()) if batch.causal else int(lq * lk)
+    return pairs * batch.num_qo_heads * 4 * batch.head_dim
+
+
+def cpu_baseline(batch, unit_work: float, unit: str, budget_s: float = 10.0) -> dict:
+    import oracle
+    cores = len(os.sched_getaffinity(0))
+    passes, t_total = 0, 0.0
+    best = float("inf")
+    while passes < 3 and t_total < budget_s:
+        t0 = time.perf_counter()
+        oracle.run_batch(batch)
+        dt = time.perf_counter() - t0
+        best = min(best, dt)
+        t_total += dt
+        passes += 1
+    return {"value": unit_work / best, "unit": unit, "cores": cores, "kind": "oracle",
+            "sample": f"whole batch ({batch.batch} requests), best of {passes} pass(es), {best:.2f} s per pass",
+            "seconds_per_batch": best}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4"])
+    ap.add_argument("--small", action="store_true", help="small variant of the workload (debug)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-plan", action="store_true", help="time fi_run only (plan once, as for layers 2..L)")
+    ap.add_argument("--num-ctas", type=int, default=0)
+    ap.add_argument("--min-chunk", type=int, default=0)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on exactly one GPU (no multi-GPU path exists); use --gpus 1", file=sys.stderr)
+        return 2
+
+    import torch
+    import workloads
+    import paper_2501_01005_amd as fi
+    sys.path.insert(0, os.path.join(ROOT, "tests"))
+    from gpu_util import DeviceBatch, make_wrapper
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    batch = getattr(workloads, "config" + args.workload[1])(small=args.small)
+    mode = "append" if args.workload == "c3" else "decode"
+    dev = DeviceBatch(batch)
+    w = make_wrapper(batch, mode, num_ctas=args.num_ctas, min_chunk=args.min_chunk)
+    nnz = dev.q.shape[0]
+    o = torch.empty((nnz, batch.num_qo_heads, batch.head_dim), dtype=torch.float32, device=dev.device)
+    lse = torch.empty((nnz, batch.num_qo_heads), dtype=torch.float32, device=dev.device)
+
+    ev = HipEvents(args.steps)
+
+    def step(i_timed: int = -1):
+        if not args.no_plan or i_timed == -2:
+            w.plan(batch.qo_indptr, batch.kv_indptr, batch.last_page_len, causal=batch.causal)
+        if i_timed >= 0:
+            fi.lib.fi_set_timing_events(w.handle, ev.start[i_timed], ev.stop[i_timed])
+        w.run(dev.q, dev.k_pool, dev.v_pool, dev.kv_indices, batch.sm_scale, o=o, lse=lse)
+        if i_timed >= 0:
+            fi.lib.fi_set_timing_events(w.handle, None, None)
+
+    step(-2)
+    view = fi.fi_plan_view(w.handle)
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_per_step = wall * 1e3 / args.steps
+    kern_ms = [ev.elapsed_ms(i) for i in range(args.steps)]
+    kern_avg_ms = float(np.mean(kern_ms))
+
+    # host planner alone
+    tp = time.perf_counter()
+    for _ in range(20):
+        fi.fi_plan(w.handle, batch.qo_indptr, batch.kv_indptr, batch.last_page_len, batch.causal)
+    plan_us = (time.perf_counter() - tp) / 20 * 1e6
+
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "traffic.json")
+    if os.path.exists(tpath):
+        traffic = json.load(open(tpath)).get(args.workload + ("_small" if args.small else ""))
+
+    if mode == "decode":
+        ab = decode_algorithmic_bytes(batch, view)
+        value = ab["step"] / (ms_per_step * 1e-3) / 1e9
+        achieved = ab["attention_kernel"] / (kern_avg_ms * 1e-3) / 1e9
+        metric, unit = "achieved HBM bandwidth, paged GQA decode step (algorithmic bytes / step time)", "GB/s"
+        roof = {"bound": "hbm", "kernel": "decode_kernel", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
+                "algorithmic_bytes_per_launch": ab["attention_kernel"], "avg_kernel_us": kern_avg_ms * 1e3,
+                "min_kernel_us": float(np.min(kern_ms)) * 1e3}
+        base_work, base_unit = ab["step"] / 1e9, "GB/s"
+        extra = {"kv_tokens": ab["tokens"], "algorithmic_bytes_per_step": ab["step"]}
+    else:
+        fl = append_algorithmic_flops(batch)
+        value = fl / (ms_per_step * 1e-3) / 1e12
+        achieved = fl / (kern_avg_ms * 1e-3) / 1e12
+        metric, unit = "achieved MFMA throughput, causal paged append step (algorithmic flop / step time)", "TFLOP/s"
+        roof = {"bound": "mfma", "kernel": "append_kernel", "achieved": achieved, "peak": MFMA_PEAK_TFLOPS,
+                "unit": "TFLOP/s", "frac": achieved / MFMA_PEAK_TFLOPS, "traffic": traffic,
+                "algorithmic_flop_per_launch": fl, "avg_kernel_us": kern_avg_ms * 1e3,
+                "min_kernel_us": float(np.min(kern_ms)) * 1e3}
+        base_work, base_unit = fl / 1e12, "TFLOP/s"
+        extra = {"algorithmic_flop_per_step": fl}
+
+    line = {
+        "metric": metric, "value": value, "unit": unit, "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "us_per_batch": ms_per_step * 1e3, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": batch.dtype, "data": "synthetic",
+        "config": {"workload": batch.name, "batch": batch.batch, "num_qo_heads": batch.num_qo_heads,
+                   "num_kv_heads": batch.num_kv_heads, "head_dim": batch.head_dim, "page_size": batch.page_size,
+                   "step": "fi_run only (plan reused)" if args.no_plan else "fi_plan + fi_run",
+                   "ctas_per_head": int(view["ctas_per_head"]), "l_kv_chunk": int(view["l_kv_chunk"]),
+                   "n_work": int(view["n_work"]), "n_split_tiles": int(view["n_merge"])},
+        "frac_of_peak": (value / HBM_PEAK_GBS) if mode == "decode" else (value / MFMA_PEAK_TFLOPS),
+        "host_plan_us": plan_us, "roofline": roof, **extra,
+    }
+    if not args.no_cpu_baseline:
+        line["cpu_baseline"] = cpu_baseline(batch, base_work, base_unit)
+    print(json.dumps(line))
+    ev.close()
+    w.close()
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -148,6 +148,12 @@ int32_t fi_run(fi_handle* h, const void* q, const void* k_pool, const void* v_po
                const int64_t* kv_strides, const int32_t* kv_indices, float sm_scale,
                float* o, float* lse, void* o_cast, fi_stream stream);
 
+/* Measurement hook: with two hipEvent_t handles set, every later fi_run records `before`
+ * right before and `after` right after the launch of its attention kernel (the merge launch
+ * comes after `after`) on the run's stream, so a caller can time that kernel alone.
+ * NULL, NULL switches the hook off.  The events stay owned by the caller. */
+int32_t fi_set_timing_events(fi_handle* h, void* before, void* after);
+
 /* Merge operator of Sec. 2.2 over n_states states per row, folded in index order:
  * o_parts DEVICE [n_rows, n_states, D], lse_parts DEVICE [n_rows, n_states] ->
  * o DEVICE [n_rows, D], lse DEVICE [n_rows].  A state with lse = -inf is the identity. */

@@ -14,7 +14,8 @@ __all__ = [
     "FI_ERR_HIP", "FI_DTYPE_F16", "FI_DTYPE_BF16", "FI_MODE_DECODE", "FI_MODE_APPEND",
     "Fi355Error", "fi_config", "fi_plan_arrays", "lib", "library_path",
     "fi_create", "fi_destroy", "fi_workspace_bytes", "fi_plan", "fi_plan_view", "fi_run",
-    "fi_merge_states", "fi_merge_state_pair", "fi_check_indices", "fi_last_error", "PagedAttention",
+    "fi_merge_states", "fi_merge_state_pair", "fi_check_indices", "fi_set_timing_events", "fi_last_error",
+    "PagedAttention",
 ]
 
 FI_OK = 0
@@ -80,10 +81,11 @@ def _load() -> ctypes.CDLL:
     L.fi_merge_states.argtypes = [vp, vp, i64, i32, i32, vp, vp, vp]
     L.fi_merge_state_pair.argtypes = [vp, vp, vp, vp, i64, i32, vp, vp, vp]
     L.fi_check_indices.argtypes = [vp, i64, i32]
+    L.fi_set_timing_events.argtypes = [vp, vp, vp]
     L.fi_last_error.argtypes = []
     L.fi_last_error.restype = ctypes.c_char_p
     for name in ("fi_create", "fi_destroy", "fi_workspace_bytes", "fi_plan", "fi_plan_view", "fi_run",
-                 "fi_merge_states", "fi_merge_state_pair", "fi_check_indices"):
+                 "fi_merge_states", "fi_merge_state_pair", "fi_check_indices", "fi_set_timing_events"):
         getattr(L, name).restype = i32
     return L
 
@@ -180,6 +182,10 @@ def fi_merge_state_pair(o_a, lse_a, o_b, lse_b, n_rows: int, head_dim: int, o, l
                                    _ptr(lse), stream or None))
 
 
+def fi_set_timing_events(handle: int, before, after) -> None:
+    _check(lib.fi_set_timing_events(handle, before, after))
+
+
 def fi_check_indices(indices, num_pages: int) -> None:
     a = _host_i32(indices)
     _check(lib.fi_check_indices(a.ctypes.data if len(a) else None, len(a), num_pages))
@@ -212,7 +218,10 @@ class PagedAttention:
         self.num_qo_heads, self.num_kv_heads, self.head_dim = num_qo_heads, num_kv_heads, head_dim
         dev_bytes, pin_bytes = fi_workspace_bytes(self.handle)
         self.workspace = torch.empty(dev_bytes, dtype=torch.uint8, device=self.device)
-        self.pinned = torch.empty(pin_bytes, dtype=torch.uint8, pin_memory=True)
+        # ring of staging buffers: a buffer is rewritten only after the copy that read it has executed
+        self._ring = [torch.empty(pin_bytes, dtype=torch.uint8, pin_memory=True) for _ in range(4)]
+        self._ring_events = [None] * len(self._ring)
+        self._ring_pos = 0
         self.ws_bytes, self.pin_bytes = dev_bytes, pin_bytes
 
     def close(self) -> None:
@@ -230,10 +239,15 @@ class PagedAttention:
         return self.torch.cuda.current_stream(self.device).cuda_stream
 
     def plan(self, qo_indptr, kv_indptr, last_page_len, causal: bool = False) -> None:
-        # the previous plan copy may still be in flight from the same staging buffer
-        self.torch.cuda.current_stream(self.device).synchronize()
+        i = self._ring_pos
+        self._ring_pos = (i + 1) % len(self._ring)
+        if self._ring_events[i] is not None:
+            self._ring_events[i].synchronize()
         fi_plan(self.handle, qo_indptr, kv_indptr, last_page_len, causal, self.workspace, self.ws_bytes,
-                self.pinned, self.pin_bytes, self._stream())
+                self._ring[i], self.pin_bytes, self._stream())
+        ev = self.torch.cuda.Event()
+        ev.record(self.torch.cuda.current_stream(self.device))
+        self._ring_events[i] = ev
 
     def run(self, q, k_pool, v_pool, kv_indices, sm_scale: float, o=None, lse=None, o_cast=None):
         torch = self.torch

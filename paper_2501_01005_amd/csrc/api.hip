@@ -34,6 +34,8 @@ struct fi_handle {
   bool planned_dev = false;
   void* workspace_dev = nullptr;
   size_t workspace_bytes = 0;
+  hipEvent_t ev_before = nullptr;
+  hipEvent_t ev_after = nullptr;
 };
 
 extern "C" {
@@ -214,8 +216,11 @@ int32_t fi_run(fi_handle* h, const void* q, const void* k_pool, const void* v_po
   p.ctas_per_head = h->pp.ctas_per_head;
   const bool bf = h->cfg.dtype == FI_DTYPE_BF16;
   hipStream_t s = static_cast<hipStream_t>(stream);
-  hipError_t e = h->cfg.mode == FI_MODE_DECODE ? launch_decode(p, bf, s) : launch_append(p, bf, s);
+  hipError_t e;
+  if (h->ev_before && (e = hipEventRecord(h->ev_before, s)) != hipSuccess) return hip_error("fi_run: hipEventRecord", e);
+  e = h->cfg.mode == FI_MODE_DECODE ? launch_decode(p, bf, s) : launch_append(p, bf, s);
   if (e != hipSuccess) return hip_error("fi_run: attention launch", e);
+  if (h->ev_after && (e = hipEventRecord(h->ev_after, s)) != hipSuccess) return hip_error("fi_run: hipEventRecord", e);
 
   MergeParams mp{};
   mp.header = plan + L.off_header;
@@ -233,6 +238,15 @@ int32_t fi_run(fi_handle* h, const void* q, const void* k_pool, const void* v_po
   mp.is_bf16 = bf ? 1 : 0;
   e = launch_merge_planned(mp, kMergeGrid, s);
   if (e != hipSuccess) return hip_error("fi_run: merge launch", e);
+  return FI_OK;
+}
+
+int32_t fi_set_timing_events(fi_handle* h, void* before, void* after) {
+  if (!h) return set_error(FI_ERR_INVALID_ARG, "fi_set_timing_events: null handle");
+  if ((before == nullptr) != (after == nullptr))
+    return set_error(FI_ERR_INVALID_ARG, "fi_set_timing_events: set both events or neither");
+  h->ev_before = static_cast<hipEvent_t>(before);
+  h->ev_after = static_cast<hipEvent_t>(after);
   return FI_OK;
 }
 

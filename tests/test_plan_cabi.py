@@ -20,7 +20,8 @@ def test_library_exports_every_declared_symbol():
     header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
     names = set(re.findall(r"\b(fi_[a-z_]+)\s*\(", header))
     assert {"fi_create", "fi_destroy", "fi_workspace_bytes", "fi_plan", "fi_plan_view", "fi_run",
-            "fi_merge_states", "fi_merge_state_pair", "fi_check_indices", "fi_last_error"} <= names
+            "fi_merge_states", "fi_merge_state_pair", "fi_check_indices", "fi_set_timing_events",
+            "fi_last_error"} <= names
     L = ctypes.CDLL(fi.library_path())
     for n in names:
         assert hasattr(L, n), n
