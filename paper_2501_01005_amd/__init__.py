@@ -9,5 +9,6 @@ when the library is not built: there is no fallback path.
 def __getattr__(name):
     if name.startswith("__"):
         raise AttributeError(name)
-    from . import binding
+    import importlib
+    binding = importlib.import_module(__name__ + ".binding")
     return getattr(binding, name)
