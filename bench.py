@@ -117,6 +117,9 @@ def main() -> int:
     ap.add_argument("--small", action="store_true", help="small variant of the workload (debug)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-plan", action="store_true", help="time fi_run only (plan once, as for layers 2..L)")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="instead of the workload, launch a plain elementwise kernel that reads 1 GiB and writes "
+                         "1 GiB per launch (scale reference for the rocprofv3 FETCH_SIZE / WRITE_SIZE counters)")
     ap.add_argument("--num-ctas", type=int, default=0)
     ap.add_argument("--min-chunk", type=int, default=0)
     args = ap.parse_args()
@@ -133,6 +136,16 @@ def main() -> int:
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         return 2
+    if args.calibrate_copy:
+        n = (1 << 30) // 4
+        src = torch.ones(n, dtype=torch.float32, device="cuda:0")
+        dst = torch.empty_like(src)
+        for _ in range(args.warmup + args.steps):
+            torch.add(src, 1.0, out=dst)
+        torch.cuda.synchronize()
+        print(json.dumps({"calibration": "torch.add(src, 1.0, out=dst)", "read_bytes_per_launch": n * 4,
+                          "write_bytes_per_launch": n * 4, "launches": args.warmup + args.steps}))
+        return 0
     batch = getattr(workloads, "config" + args.workload[1])(small=args.small)
     mode = "append" if args.workload == "c3" else "decode"
     dev = DeviceBatch(batch)

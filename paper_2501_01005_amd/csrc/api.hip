@@ -193,6 +193,7 @@ int32_t fi_run(fi_handle* h, const void* q, const void* k_pool, const void* v_po
   p.w_q_row0 = plan + L.off_work[W_Q_ROW0];
   p.w_n_pos = plan + L.off_work[W_N_POS];
   p.w_kv_page0 = plan + L.off_work[W_KV_PAGE0];
+  p.w_kv_start = plan + L.off_work[W_KV_START];
   p.w_kv_len = plan + L.off_work[W_KV_LEN];
   p.w_diag0 = plan + L.off_work[W_DIAG0];
   p.w_out_slot = plan + L.off_work[W_OUT_SLOT];

@@ -13,6 +13,7 @@ struct RunParams {
   const int32_t* w_q_row0;
   const int32_t* w_n_pos;
   const int32_t* w_kv_page0;
+  const int32_t* w_kv_start;
   const int32_t* w_kv_len;
   const int32_t* w_diag0;
   const int32_t* w_out_slot;
@@ -56,6 +57,7 @@ hipError_t launch_merge_states(const float* o_parts, const float* lse_parts, int
 hipError_t launch_merge_pair(const float* o_a, const float* lse_a, const float* o_b, const float* lse_b,
                              int64_t n_rows, float* o, float* lse, hipStream_t stream);
 
+constexpr int kNoDiagMarker = 0x3FFFFFFF;  // w_diag0 of a non-causal work item
 constexpr int kHeadDim = 128;
 constexpr int kPageSize = 16;
 constexpr int kMergeGrid = 1024;  // fixed grid of the planned merge launch
