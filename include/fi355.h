@@ -122,7 +122,9 @@ int32_t fi_workspace_bytes(const fi_handle* h, size_t* device_bytes, size_t* pin
 /* The scheduler of Algorithm 1 (Sec. 3.3.1), run on the host once per generation step and
  * reused by every layer.  Reads the three HOST arrays, writes the plan into `pinned_host`
  * (HOST, page-locked, >= pinned_host_bytes; NULL = use pageable memory of the handle) and
- * enqueues ONE async copy into the fixed plan sections of `workspace_dev` on `stream`.
+ * enqueues ONE async transfer into the fixed plan sections of `workspace_dev` on `stream`
+ * (a copy kernel reading the staging buffer when it is mapped into the device address
+ * space, as hipHostMalloc memory is; hipMemcpyAsync otherwise).
  * The staging buffer must not be re-planned before that copy has executed.
  * workspace_dev = NULL plans on the host only (no HIP call; fi_run stays unavailable).
  * causal != 0: query j of a request sees tokens t <= l_kv - l_qo + j (the appended tokens

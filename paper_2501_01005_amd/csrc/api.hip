@@ -128,13 +128,26 @@ int32_t fi_plan(fi_handle* h, const int32_t* qo_indptr, const int32_t* kv_indptr
   h->planned_host = true;
   if (!workspace_dev) return FI_OK;
   const size_t bytes = h->layout.plan_ints * sizeof(int32_t);
-  const void* src = h->host_plan.data();
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  bool uploaded = false;
   if (pinned_host) {
     std::memcpy(pinned_host, h->host_plan.data(), bytes);
-    src = pinned_host;
+    // page-locked memory that is mapped into the device address space is pulled by a copy kernel
+    void* dev_view = nullptr;
+    if (hipHostGetDevicePointer(&dev_view, pinned_host, 0) == hipSuccess && dev_view) {
+      const hipError_t e = launch_plan_upload(static_cast<const int32_t*>(dev_view), static_cast<int32_t*>(workspace_dev),
+                                              static_cast<int32_t>(h->layout.plan_ints), s);
+      if (e != hipSuccess) return hip_error("fi_plan: plan upload launch", e);
+      uploaded = true;
+    } else {
+      (void)hipGetLastError();  // not device-mapped: fall back to a copy-engine transfer
+    }
   }
-  const hipError_t e = hipMemcpyAsync(workspace_dev, src, bytes, hipMemcpyHostToDevice, static_cast<hipStream_t>(stream));
-  if (e != hipSuccess) return hip_error("fi_plan: hipMemcpyAsync", e);
+  if (!uploaded) {
+    const void* src = pinned_host ? pinned_host : static_cast<const void*>(h->host_plan.data());
+    const hipError_t e = hipMemcpyAsync(workspace_dev, src, bytes, hipMemcpyHostToDevice, s);
+    if (e != hipSuccess) return hip_error("fi_plan: hipMemcpyAsync", e);
+  }
   h->workspace_dev = workspace_dev;
   h->workspace_bytes = workspace_bytes;
   h->planned_dev = true;

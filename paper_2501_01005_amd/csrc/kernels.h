@@ -50,6 +50,9 @@ struct MergeParams {
 hipError_t launch_decode(const RunParams& p, bool is_bf16, hipStream_t stream);
 // append.hip: query tile = 128/g positions x g fused heads, 4 wavefronts per CTA.
 hipError_t launch_append(const RunParams& p, bool is_bf16, hipStream_t stream);
+// upload.hip: staging (device view of page-locked host memory) -> plan section
+hipError_t launch_plan_upload(const int32_t* staging_dev_view, int32_t* plan_section, int32_t n_ints,
+                              hipStream_t stream);
 // merge.hip
 hipError_t launch_merge_planned(const MergeParams& p, int32_t grid, hipStream_t stream);
 hipError_t launch_merge_states(const float* o_parts, const float* lse_parts, int64_t n_rows, int32_t n_states,

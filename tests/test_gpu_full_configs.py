@@ -1,0 +1,64 @@
+"""GPU parity at the full benchmark sizes, in the launch configuration bench.py times
+(library-default grid and chunk size).  Where the fp64 oracle would take minutes, it is
+run on a sample of requests; every sampled output element is compared."""
+import numpy as np
+import pytest
+
+import oracle
+import workloads
+from gpu_util import DeviceBatch, assert_close, make_wrapper, run_gpu
+
+pytestmark = pytest.mark.gpu
+
+
+def sampled_check(batch, mode, requests, what):
+    print(f"[case] {what}: {batch.name} batch={batch.batch} tokens={int(batch.kv_lens().sum())} sample={list(requests)}",
+          flush=True)
+    o, lse = run_gpu(batch, mode)
+    assert not np.isnan(o).any() and not np.isnan(lse).any(), "NaN in GPU output"
+    o_ref, lse_ref = oracle.run_batch(batch, requests=requests)
+    e = assert_close(o, lse, o_ref, lse_ref, what)
+    print(f"[ok] {what}: err_o={e[0]:.2e} err_lse={e[1]:.2e}", flush=True)
+
+
+def test_config2_full_gqa_decode_zipf():
+    b = workloads.config2()
+    kv = b.kv_lens()
+    # the forced 32768-token request (split over many CTAs), the shortest, the longest unsplit ones, a few more
+    order = np.argsort(kv)
+    sample = sorted({0, int(order[0]), int(order[-2]), int(order[len(order) // 2]), 17, 64, 127})
+    sampled_check(b, "decode", sample, "c2 full")
+
+
+def test_config4_full_long_context_decode():
+    b = workloads.config4()
+    sampled_check(b, "decode", [0, 1], "c4 full")
+
+
+def test_config3_full_causal_append():
+    b = workloads.config3()
+    # request 1 has no cached prefix, request 2 a ragged last tile; plus the longest one
+    longest = int(np.argmax(b.kv_lens()))
+    sampled_check(b, "append", sorted({1, 2, longest}), "c3 full")
+
+
+def test_config5_full_shared_prefix():
+    import torch
+    import paper_2501_01005_amd as fi
+    c = workloads.config5()
+    print("[case] c5 full: composed (prefix append pass + suffix decode pass + pair merge) and single format", flush=True)
+    o_ref, lse_ref = oracle.run_batch(c.single)
+    dev_p, dev_s = DeviceBatch(c.prefix), DeviceBatch(c.suffix)
+    wp, ws = make_wrapper(c.prefix, "append"), make_wrapper(c.suffix, "decode")
+    wp.plan(c.prefix.qo_indptr, c.prefix.kv_indptr, c.prefix.last_page_len, causal=False)
+    ws.plan(c.suffix.qo_indptr, c.suffix.kv_indptr, c.suffix.last_page_len, causal=False)
+    o_p, l_p = wp.run(dev_p.q, dev_p.k_pool, dev_p.v_pool, dev_p.kv_indices, c.prefix.sm_scale)
+    o_s, l_s = ws.run(dev_s.q, dev_s.k_pool, dev_s.v_pool, dev_s.kv_indices, c.suffix.sm_scale)
+    fi.fi_merge_state_pair(o_p, l_p, o_s, l_s, o_p.shape[0] * o_p.shape[1], 128, o_p, l_p,
+                           torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    e = assert_close(o_p.double().cpu().numpy(), l_p.double().cpu().numpy(), o_ref, lse_ref, "c5 composed")
+    o1, l1 = run_gpu(c.single, "decode")
+    e1 = assert_close(o1, l1, o_ref, lse_ref, "c5 single")
+    print(f"[ok] c5 full: composed err_o={e[0]:.2e} err_lse={e[1]:.2e}; single err_o={e1[0]:.2e}", flush=True)
+    wp.close(); ws.close()
