@@ -1,6 +1,10 @@
 // Paged decode attention for gfx950: query tile = one position x g fused query heads
-// (head-group fusion, App. A), one wavefront per CTA, K/V streamed from HBM straight into
-// MFMA operand registers.  HBM-bandwidth bound: every K/V byte of a chunk is read once.
+// (head-group fusion, App. A), one wavefront per CTA, K/V streamed from HBM with whole-row
+// coalesced non-temporal loads.  HBM-bandwidth bound: every K/V byte of a chunk is read once.
+// V rows are consumed from registers as loaded; K rows pass through a wavefront-private 8 KB
+// LDS buffer (XOR-swizzled 16-byte blocks, conflict-free both ways) to reach the A-operand
+// layout of the first product, because loading that layout directly (16 rows x 64 B per
+// instruction) halves the request size and loses the benefit of streaming loads.
 //
 // Per 32-token step (two 16-token pages) of a work item:
 //   S^T[token][head] = K . Q^T         v_mfma_f32_16x16x32 (A = K page, B = Q^T padded to 16 heads)
@@ -56,14 +60,19 @@ __device__ __forceinline__ uint32_t lo_halves(uint32_t a, uint32_t b) { return _
 __device__ __forceinline__ uint32_t hi_halves(uint32_t a, uint32_t b) { return __builtin_amdgcn_perm(b, a, 0x07060302u); }
 
 __device__ __forceinline__ u32x4_t ld16(const uint16_t* p) { return *reinterpret_cast<const u32x4_t*>(p); }
+// K/V bytes are used exactly once: streaming (non-temporal) loads keep them from displacing
+// each other in the caches and measure ~13 % faster than plain loads on a pure read stream.
+__device__ __forceinline__ u32x4_t ld16_stream(const uint16_t* p) {
+  return __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(p));
+}
 
 struct KvTile {
-  u32x4_t k[2][4];  // [page][k-step s]: K[token m][d = 32 s + 8 c .. +8]
+  u32x4_t k[2][4];  // [page][j]:        K[token 4 j + c][d = 8 m .. +8]   (as loaded, row-coalesced)
   u32x4_t v[2][4];  // [page][i]:        V[token 4 c + i][d = 8 m .. +8]
 };
 
 template <bool BF>
-__global__ void __launch_bounds__(64) decode_kernel(const RunParams p) {
+__global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2))) decode_kernel(const RunParams p) {
   const int lane = threadIdx.x;
   const int m = lane & 15;  // K: token in page; V: 16-byte column block; S/O: query head
   const int c = lane >> 4;  // lane group
@@ -73,7 +82,9 @@ __global__ void __launch_bounds__(64) decode_kernel(const RunParams p) {
   const int H = p.num_qo_heads;
   const float NEG_INF = -__builtin_inff();
 
-  const uint16_t* kbase = static_cast<const uint16_t*>(p.k_pool) + kvh * p.stride_head + m * p.stride_tok + c * 8;
+  const uint16_t* kbase = static_cast<const uint16_t*>(p.k_pool) + kvh * p.stride_head + c * p.stride_tok + m * 8;
+  // K relayout buffer: block (page pg, token t, 16-byte block x) lives at pg*4096 + t*256 + ((x ^ t) & 15)*16
+  __shared__ __attribute__((aligned(16))) u32x4_t k_lds[2 * 16 * 16];
   const uint16_t* vbase = static_cast<const uint16_t*>(p.v_pool) + kvh * p.stride_head + (4 * c) * p.stride_tok + m * 8;
   const int64_t stride_tok = p.stride_tok;
   const int64_t stride_page = p.stride_page;
@@ -117,23 +128,33 @@ __global__ void __launch_bounds__(64) decode_kernel(const RunParams p) {
       const uint16_t* v1 = vbase + pg1 * stride_page;
 #pragma unroll
       for (int s = 0; s < 4; ++s) {
-        T.k[0][s] = ld16(k0 + 32 * s);
-        T.k[1][s] = ld16(k1 + 32 * s);
+        T.k[0][s] = ld16_stream(k0 + 4 * s * stride_tok);
+        T.k[1][s] = ld16_stream(k1 + 4 * s * stride_tok);
       }
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
-        T.v[0][i] = ld16(v0 + i * stride_tok);
-        T.v[1][i] = ld16(v1 + i * stride_tok);
+        T.v[0][i] = ld16_stream(v0 + i * stride_tok);
+        T.v[1][i] = ld16_stream(v1 + i * stride_tok);
       }
     };
 
     auto compute_tile = [&](KvTile& T, int t) {
       // ---- S^T = K . Q^T ----
+      // K rows -> LDS (token 4 j + c, block m), then back as A operands (token m, block 4 s + c)
+#pragma unroll
+      for (int pg = 0; pg < 2; ++pg)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const int tk = 4 * j + c;
+          k_lds[pg * 256 + tk * 16 + ((m ^ tk) & 15)] = T.k[pg][j];
+        }
       f32x4_t s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
       for (int s = 0; s < 4; ++s) {
-        s0 = mfma_16x16x32<BF>(T.k[0][s], qreg[s], s0);
-        s1 = mfma_16x16x32<BF>(T.k[1][s], qreg[s], s1);
+        const u32x4_t ka0 = k_lds[m * 16 + (((4 * s + c) ^ m) & 15)];
+        const u32x4_t ka1 = k_lds[256 + m * 16 + (((4 * s + c) ^ m) & 15)];
+        s0 = mfma_16x16x32<BF>(ka0, qreg[s], s0);
+        s1 = mfma_16x16x32<BF>(ka1, qreg[s], s1);
       }
       // lane (m, c) now holds S^T[token 16 pg + 4 c + i][head m]
       const int tok0 = 32 * t + 4 * c;
