@@ -143,7 +143,7 @@ int32_t fi_plan_view(const fi_handle* h, fi_plan_arrays* out);
  * launch of ctas_per_head x H_kv CTAs that walk their work queues, writing final rows
  * directly or partial states into the workspace, then one fixed-grid merge launch for the
  * split tiles.  All pointers DEVICE.  kv_strides HOST [3] = element strides of
- * (page, kv head, slot-in-page).  sm_scale multiplies q.k before the softmax.
+ * (page, kv head, slot-in-page).  sm_scale (> 0) multiplies q.k before the softmax.
  * o_cast (may be NULL): the output also rounded to the input dtype, [nnz_qo, H_qo, D].
  * Asynchronous on `stream`; uses the workspace given to the last fi_plan. */
 int32_t fi_run(fi_handle* h, const void* q, const void* k_pool, const void* v_pool,

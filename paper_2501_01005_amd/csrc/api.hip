@@ -190,6 +190,7 @@ int32_t fi_run(fi_handle* h, const void* q, const void* k_pool, const void* v_po
   if (!h->planned_dev) return set_error(FI_ERR_NOT_PLANNED, "fi_run: call fi_plan with a device workspace first");
   if (!q || !k_pool || !v_pool || !kv_strides || !kv_indices || !o || !lse)
     return set_error(FI_ERR_INVALID_ARG, "fi_run: null pointer");
+  if (!(sm_scale > 0.f)) return set_error(FI_ERR_INVALID_ARG, "fi_run: sm_scale must be > 0");
   if (kv_strides[0] <= 0 || kv_strides[1] <= 0 || kv_strides[2] < kHeadDim || kv_strides[0] % 8 != 0 ||
       kv_strides[1] % 8 != 0 || kv_strides[2] % 8 != 0)
     return set_error(FI_ERR_INVALID_ARG,

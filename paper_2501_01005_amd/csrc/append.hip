@@ -4,8 +4,8 @@
 // kv_indices, Sec. 3.2.1) are staged in LDS and shared by the four wavefronts; both products
 // run on the matrix cores:
 //   S^T[token][row] = K . Q^T      v_mfma_f32_16x16x32   A = K rows from LDS, B = Q^T in registers
-//   O^T[d][row]    += V^T . P^T    v_mfma_f32_16x16x32   A = V^T built by in-lane 16-bit permutes
-//                                                        of row-major V rows read from LDS,
+//   O^T[d][row]    += V^T . P^T    v_mfma_f32_16x16x32   A = V^T read from the row-major V tile with
+//                                                        the LDS transpose read ds_read_b64_tr_b16,
 //                                                        B = P^T straight from the S^T accumulators
 // Computing the transposed products puts one query row per lane column, so the online-softmax
 // row maximum is an in-lane reduction plus two cross-lane exchanges, and P never moves
@@ -29,8 +29,10 @@ typedef __attribute__((ext_vector_type(4))) float f32x4_t;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4_t;
 
 constexpr int kTileKv = 64;        // tokens per LDS tile
-constexpr int kRowElems = 136;     // LDS row pitch in 16-bit elements: 128 + 8 pad (272 B) -> conflict-free b128 reads
+constexpr int kRowElems = 136;     // K tile row pitch in 16-bit elements (272 B): rows 4 banks apart, conflict-free b128 reads
+constexpr int kRowElemsV = 144;    // V tile row pitch (288 B): rows 8 banks apart, conflict-free transpose reads
 constexpr int kCtaThreads = 256;
+constexpr float kLazyLog2 = 8.0f;  // P may exceed 1 by at most 2^8 before the running reference is raised
 
 template <bool BF>
 __device__ __forceinline__ f32x4_t mfma_qk(u32x4_t a, u32x4_t b, f32x4_t c) {
@@ -67,13 +69,55 @@ __device__ __forceinline__ uint32_t bf16x2_to_f16x2(uint32_t w) {
   return __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(lo, hi));
 }
 
-__device__ __forceinline__ uint32_t lo_halves(uint32_t a, uint32_t b) { return __builtin_amdgcn_perm(b, a, 0x05040100u); }
-__device__ __forceinline__ uint32_t hi_halves(uint32_t a, uint32_t b) { return __builtin_amdgcn_perm(b, a, 0x07060302u); }
+typedef __attribute__((ext_vector_type(4))) short s16x4_t;
+typedef __attribute__((ext_vector_type(2))) uint32_t u32x2_t;
+// ds_read_b64_tr_b16: within each group of 16 lanes, lane 4 k + q supplies the address of 4
+// consecutive 16-bit elements; lane l of the group receives, in slot k = 0..3, element l % 4 of
+// the row supplied by lane 4 k + l / 4.  With lane 4 k + q pointing at row k, columns
+// c0 + 4 q .. + 3, lane l ends up with column c0 + l of rows 0..3: a 4 x 16 block transposed.
+__device__ __forceinline__ u32x2_t lds_read_tr16(const uint16_t* p) {
+  const s16x4_t v = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+      (__attribute__((address_space(3))) s16x4_t*)(const_cast<uint16_t*>(p)));
+  return __builtin_bit_cast(u32x2_t, v);
+}
+
+// Exchanges between the four 16-lane rows of a wavefront without going through LDS:
+// v_permlane32_swap swaps the upper half of its first operand with the lower half of its
+// second, v_permlane16_swap swaps the odd rows of the first with the even rows of the second.
+// With both operands holding x, the pair afterwards holds (x of lane l, x of lane l ^ 32)
+// resp. (x of lane l, x of lane l ^ 16) in some order, which is all a max or a sum needs.
+__device__ __forceinline__ void swap32(float x, float* a, float* b) {
+  uint32_t u = __builtin_bit_cast(uint32_t, x), v = u;
+  asm volatile("s_nop 1\n\tv_permlane32_swap_b32_e32 %0, %1" : "+v"(u), "+v"(v));
+  *a = __builtin_bit_cast(float, u);
+  *b = __builtin_bit_cast(float, v);
+}
+__device__ __forceinline__ void swap16(float x, float* a, float* b) {
+  uint32_t u = __builtin_bit_cast(uint32_t, x), v = u;
+  asm volatile("s_nop 1\n\tv_permlane16_swap_b32_e32 %0, %1" : "+v"(u), "+v"(v));
+  *a = __builtin_bit_cast(float, u);
+  *b = __builtin_bit_cast(float, v);
+}
+__device__ __forceinline__ float rows_max(float x) {
+  float a, b;
+  swap32(x, &a, &b);
+  x = fmaxf(a, b);
+  swap16(x, &a, &b);
+  return fmaxf(a, b);
+}
+__device__ __forceinline__ float rows_sum(float x) {
+  float a, b;
+  swap32(x, &a, &b);
+  x = a + b;
+  swap16(x, &a, &b);
+  return a + b;
+}
 
 template <bool BF>
-__global__ void __launch_bounds__(kCtaThreads) append_kernel(const RunParams p) {
+__global__ void __launch_bounds__(kCtaThreads) __attribute__((amdgpu_waves_per_eu(2, 2)))
+append_kernel(const RunParams p) {
   __shared__ __attribute__((aligned(16))) uint16_t lds_k[kTileKv * kRowElems];
-  __shared__ __attribute__((aligned(16))) uint16_t lds_v[kTileKv * kRowElems];
+  __shared__ __attribute__((aligned(16))) uint16_t lds_v[kTileKv * kRowElemsV];
 
   const int tid = threadIdx.x;
   const int wave = tid >> 6;
@@ -86,6 +130,7 @@ __global__ void __launch_bounds__(kCtaThreads) append_kernel(const RunParams p) 
   const int g_log2 = 31 - __builtin_clz(g);
   const int H = p.num_qo_heads;
   const float NEG_INF = -__builtin_inff();
+  const float lazy_raw = kLazyLog2 / p.scale_log2;  // kLazyLog2 binary orders of magnitude in raw-logit units
 
   // staging role: this thread moves the 16-byte block `st_chunk` of token slot `st_slot` of each of the 4 pages
   const int st_slot = tid >> 4;
@@ -136,21 +181,26 @@ __global__ void __launch_bounds__(kCtaThreads) append_kernel(const RunParams p) 
     const int wave_lim_lo = (diag0 == kNoDiagMarker) ? 0x3FFFFFFF : diag0 + wave_pos_lo - kv_start;
     const int wave_lim_hi = (diag0 == kNoDiagMarker) ? 0x3FFFFFFF : diag0 + wave_pos_hi - kv_start;
 
-    f32x4_t acc[2][8];  // acc[nb][e][i] = O^T[d = 32 c + 8 i + e][row m of block nb]
+    f32x4_t acc[2][8];  // acc[nb][e][i] = O^T[d = 16 e + 4 c + i][row m of block nb]
 #pragma unroll
     for (int nb = 0; nb < 2; ++nb)
 #pragma unroll
       for (int e = 0; e < 8; ++e) acc[nb][e] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-    float m_run[2] = {NEG_INF, NEG_INF};
+    float m_run[2] = {NEG_INF, NEG_INF};  // reference for the exponentials: raw-logit units, >= row max - lazy_raw
     float l_run[2] = {0.f, 0.f};
 
     u32x4_t stage_k[4], stage_v[4];
-    auto fetch_tile = [&](int t) {
+    // Page ids are fetched one tile ahead of the data they address (lane r holds page r of the
+    // tile), so that the data loads never wait behind an index load.
+    auto fetch_page_ids = [&](int t) -> int {
+      int pi = 4 * t + (lane & 3);
+      pi = pi < n_pages ? pi : n_pages - 1;  // never index past the chunk's pages
+      return p.kv_indices[kv_page0 + pi];
+    };
+    auto fetch_tile = [&](int ids) {
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
-        int pi = 4 * t + r;
-        pi = pi < n_pages ? pi : n_pages - 1;  // never index past the chunk's pages
-        const int pg = __builtin_amdgcn_readfirstlane(p.kv_indices[kv_page0 + pi]);
+        const int pg = __builtin_amdgcn_readlane(ids, r);
         const int64_t off = pg * p.stride_page + st_off;
         stage_k[r] = *reinterpret_cast<const u32x4_t*>(kpool + off);
         stage_v[r] = *reinterpret_cast<const u32x4_t*>(vpool + off);
@@ -166,35 +216,59 @@ __global__ void __launch_bounds__(kCtaThreads) append_kernel(const RunParams p) 
         }
         if (kTileKv * t + tok >= kv_len) v = u32x4_t{0u, 0u, 0u, 0u};  // rows past the chunk must not reach P.V
         *reinterpret_cast<u32x4_t*>(&lds_k[tok * kRowElems + st_chunk * 8]) = stage_k[r];
-        *reinterpret_cast<u32x4_t*>(&lds_v[tok * kRowElems + st_chunk * 8]) = v;
+        *reinterpret_cast<u32x4_t*>(&lds_v[tok * kRowElemsV + st_chunk * 8]) = v;
       }
     };
 
-    if (n_tiles > 0) fetch_tile(0);
+    int ids_next = 0;
+    if (n_tiles > 0) {
+      fetch_tile(fetch_page_ids(0));
+      if (n_tiles > 1) ids_next = fetch_page_ids(1);
+    }
     for (int t = 0; t < n_tiles; ++t) {
       __syncthreads();  // everyone is done reading the previous tile
       store_tile(t);
       __syncthreads();
-      if (t + 1 < n_tiles) fetch_tile(t + 1);  // in flight while this tile is consumed
+      if (t + 1 < n_tiles) {
+        fetch_tile(ids_next);  // in flight while this tile is consumed
+        if (t + 2 < n_tiles) ids_next = fetch_page_ids(t + 2);
+      }
 
 #pragma unroll
       for (int u = 0; u < 2; ++u) {
         const int tok_base = kTileKv * t + 32 * u;  // chunk-local index of this 32-token step
         if (tok_base >= kv_len || tok_base > wave_lim_hi) continue;  // nothing visible to this wavefront
-        // ---- S^T = K . Q^T ----
+        // ---- S^T = K . Q^T: all eight A operands are requested before the first product ----
+        u32x4_t ka[2][4];
+#pragma unroll
+        for (int pg = 0; pg < 2; ++pg) {
+          const uint16_t* krow = &lds_k[(32 * u + 16 * pg + m) * kRowElems + c * 8];
+#pragma unroll
+          for (int s = 0; s < 4; ++s) ka[pg][s] = *reinterpret_cast<const u32x4_t*>(krow + 32 * s);
+        }
         f32x4_t sacc[2][2];
 #pragma unroll
         for (int nb = 0; nb < 2; ++nb)
 #pragma unroll
           for (int pg = 0; pg < 2; ++pg) sacc[nb][pg] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int pg = 0; pg < 2; ++pg) {
-          const uint16_t* krow = &lds_k[(32 * u + 16 * pg + m) * kRowElems + c * 8];
+        for (int s = 0; s < 4; ++s)
 #pragma unroll
-          for (int s = 0; s < 4; ++s) {
-            const u32x4_t ka = *reinterpret_cast<const u32x4_t*>(krow + 32 * s);
-            sacc[0][pg] = mfma_qk<BF>(ka, qreg[0][s], sacc[0][pg]);
-            sacc[1][pg] = mfma_qk<BF>(ka, qreg[1][s], sacc[1][pg]);
+          for (int pg = 0; pg < 2; ++pg) {
+            sacc[0][pg] = mfma_qk<BF>(ka[pg][s], qreg[0][s], sacc[0][pg]);
+            sacc[1][pg] = mfma_qk<BF>(ka[pg][s], qreg[1][s], sacc[1][pg]);
+          }
+        // ---- V^T operands (16 columns d = 16 e + m of tokens (page, 4 c + k)): requested now,
+        //      they arrive while the softmax below runs on the vector ALU ----
+        u32x4_t vt[8];
+        {
+          const int k4 = m >> 2, q4 = m & 3;  // this lane's role as address supplier in its 16-lane group
+          const uint16_t* vsrc = &lds_v[(32 * u + 4 * c + k4) * kRowElemsV + 4 * q4];
+#pragma unroll
+          for (int e = 0; e < 8; ++e) {
+            const u32x2_t lo = lds_read_tr16(vsrc + 16 * e);                    // page 0 of the step
+            const u32x2_t hi = lds_read_tr16(vsrc + 16 * kRowElemsV + 16 * e);  // page 1
+            vt[e] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3);
           }
         }
         // ---- online softmax, one row per (lane column, block) ----
@@ -202,11 +276,11 @@ __global__ void __launch_bounds__(kCtaThreads) append_kernel(const RunParams p) 
         u32x4_t pb[2];
 #pragma unroll
         for (int nb = 0; nb < 2; ++nb) {
-          float sv[8];
+          float sv[8];  // raw logits q.k; the softmax scale is folded into the exponent below
 #pragma unroll
           for (int i = 0; i < 4; ++i) {
-            sv[i] = sacc[nb][0][i] * p.scale_log2;
-            sv[4 + i] = sacc[nb][1][i] * p.scale_log2;
+            sv[i] = sacc[nb][0][i];
+            sv[4 + i] = sacc[nb][1][i];
           }
           if (need_mask) {
             const int cap = min(lim[nb], kv_len - 1);
@@ -217,48 +291,48 @@ __global__ void __launch_bounds__(kCtaThreads) append_kernel(const RunParams p) 
               sv[4 + i] = (t0 + 16 <= cap) ? sv[4 + i] : NEG_INF;
             }
           }
-          float tmax =
-              fmaxf(fmaxf(fmaxf(sv[0], sv[1]), fmaxf(sv[2], sv[3])), fmaxf(fmaxf(sv[4], sv[5]), fmaxf(sv[6], sv[7])));
-          tmax = fmaxf(tmax, __shfl_xor(tmax, 16));
-          tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
-          const float m_new = fmaxf(m_run[nb], tmax);
-          const float m_use = (m_new == NEG_INF) ? 0.f : m_new;  // row has seen nothing yet
-          const float alpha = __builtin_amdgcn_exp2f(m_run[nb] - m_use);
-          m_run[nb] = m_new;
-          float pv[8];
-          float psum = 0.f;
-#pragma unroll
-          for (int j = 0; j < 8; ++j) {
-            pv[j] = __builtin_amdgcn_exp2f(sv[j] - m_use);
-            psum += pv[j];
-          }
-          l_run[nb] = l_run[nb] * alpha + psum;
-          if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {
+          float tmax = fmaxf(fmaxf(fmaxf(sv[0], sv[1]), fmaxf(sv[2], sv[3])), fmaxf(fmaxf(sv[4], sv[5]), fmaxf(sv[6], sv[7])));
+          tmax = rows_max(tmax);
+          // Lazy reference update: the reference m_run only has to bound the logits from above
+          // up to 2^kLazyLog2 (P then stays <= 2^kLazyLog2, well inside fp16 and fp32 range); the
+          // result o = O / l does not depend on it.  Rescaling the 32 accumulator registers is
+          // thus needed only when the row maximum jumps, not on every small increase.
+          if (__builtin_amdgcn_ballot_w64(tmax > m_run[nb] + lazy_raw) != 0) {
+            const float m_new = fmaxf(m_run[nb], tmax);
+            const float m_use = (m_new == NEG_INF) ? 0.f : m_new;  // row has seen nothing yet
+            const float alpha = __builtin_amdgcn_exp2f((m_run[nb] - m_use) * p.scale_log2);
+            m_run[nb] = m_new;
+            l_run[nb] *= alpha;
 #pragma unroll
             for (int e = 0; e < 8; ++e) acc[nb][e] *= alpha;
           }
-          pb[nb] = u32x4_t{pack_f16(pv[0], pv[1]), pack_f16(pv[2], pv[3]), pack_f16(pv[4], pv[5]),
-                           pack_f16(pv[6], pv[7])};
+          const float neg_ms = (m_run[nb] == NEG_INF) ? 0.f : -m_run[nb] * p.scale_log2;
+          float pv[8];
+#pragma unroll
+          for (int j = 0; j < 8; ++j) pv[j] = __builtin_amdgcn_exp2f(__builtin_fmaf(sv[j], p.scale_log2, neg_ms));
+          const f16x2_t h0 = {static_cast<_Float16>(pv[0]), static_cast<_Float16>(pv[1])};
+          const f16x2_t h1 = {static_cast<_Float16>(pv[2]), static_cast<_Float16>(pv[3])};
+          const f16x2_t h2 = {static_cast<_Float16>(pv[4]), static_cast<_Float16>(pv[5])};
+          const f16x2_t h3 = {static_cast<_Float16>(pv[6]), static_cast<_Float16>(pv[7])};
+          pb[nb] = u32x4_t{__builtin_bit_cast(uint32_t, h0), __builtin_bit_cast(uint32_t, h1),
+                           __builtin_bit_cast(uint32_t, h2), __builtin_bit_cast(uint32_t, h3)};
+          // The row sum is taken over the fp16-rounded P that the second product consumes
+          // (v_dot2_f32_f16 with a vector of ones, fp32 accumulation): o = O / l is then an exact
+          // convex combination of V rows whatever the reference, and a single dominant key
+          // returns its V row exactly.
+          const f16x2_t ones = {static_cast<_Float16>(1.0f), static_cast<_Float16>(1.0f)};
+          float l = l_run[nb];
+          l = __builtin_amdgcn_fdot2(h0, ones, l, false);
+          l = __builtin_amdgcn_fdot2(h1, ones, l, false);
+          l = __builtin_amdgcn_fdot2(h2, ones, l, false);
+          l = __builtin_amdgcn_fdot2(h3, ones, l, false);
+          l_run[nb] = l;
         }
         // ---- O^T += V^T . P^T ----
-        u32x4_t vr[2][4];
 #pragma unroll
-        for (int pg = 0; pg < 2; ++pg)
-#pragma unroll
-          for (int i = 0; i < 4; ++i)
-            vr[pg][i] =
-                *reinterpret_cast<const u32x4_t*>(&lds_v[(32 * u + 16 * pg + 4 * c + i) * kRowElems + m * 8]);
-#pragma unroll
-        for (int wd = 0; wd < 4; ++wd) {
-          const uint32_t a0 = vr[0][0][wd], a1 = vr[0][1][wd], a2 = vr[0][2][wd], a3 = vr[0][3][wd];
-          const uint32_t b0 = vr[1][0][wd], b1 = vr[1][1][wd], b2 = vr[1][2][wd], b3 = vr[1][3][wd];
-          const u32x4_t vt_even = {lo_halves(a0, a1), lo_halves(a2, a3), lo_halves(b0, b1), lo_halves(b2, b3)};
-          const u32x4_t vt_odd = {hi_halves(a0, a1), hi_halves(a2, a3), hi_halves(b0, b1), hi_halves(b2, b3)};
-#pragma unroll
-          for (int nb = 0; nb < 2; ++nb) {
-            acc[nb][2 * wd] = mfma_pv(vt_even, pb[nb], acc[nb][2 * wd]);
-            acc[nb][2 * wd + 1] = mfma_pv(vt_odd, pb[nb], acc[nb][2 * wd + 1]);
-          }
+        for (int e = 0; e < 8; ++e) {
+          acc[0][e] = mfma_pv(vt[e], pb[0], acc[0][e]);
+          acc[1][e] = mfma_pv(vt[e], pb[1], acc[1][e]);
         }
       }
     }
@@ -266,12 +340,11 @@ __global__ void __launch_bounds__(kCtaThreads) append_kernel(const RunParams p) 
     // ---- epilogue: o = O / l, lse = ln(sum exp) (Sec. 2.2) ----
 #pragma unroll
     for (int nb = 0; nb < 2; ++nb) {
-      float l = l_run[nb];
-      l += __shfl_xor(l, 16);
-      l += __shfl_xor(l, 32);
+      const float l = rows_sum(l_run[nb]);
       const bool live = l > 0.f;
       const float inv = live ? 1.0f / l : 0.f;
-      const float lse_val = live ? (m_run[nb] + __builtin_amdgcn_logf(l)) * 0.6931471805599453f : NEG_INF;
+      const float lse_val =
+          live ? (m_run[nb] * p.scale_log2 + __builtin_amdgcn_logf(l)) * 0.6931471805599453f : NEG_INF;
       if (row_ok[nb]) {
         const int head = kvh * g + hh[nb];
         const int64_t final_row = static_cast<int64_t>(q_row0 + pos[nb]) * H + head;
@@ -286,17 +359,12 @@ __global__ void __launch_bounds__(kCtaThreads) append_kernel(const RunParams p) 
           dst_lse = p.part_lse + row;
         }
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          float* d = dst_o + 32 * c + 8 * i;
-          const f32x4_t lo = {acc[nb][0][i] * inv, acc[nb][1][i] * inv, acc[nb][2][i] * inv, acc[nb][3][i] * inv};
-          const f32x4_t hi = {acc[nb][4][i] * inv, acc[nb][5][i] * inv, acc[nb][6][i] * inv, acc[nb][7][i] * inv};
-          *reinterpret_cast<f32x4_t*>(d) = lo;
-          *reinterpret_cast<f32x4_t*>(d + 4) = hi;
+        for (int e = 0; e < 8; ++e) {
+          const f32x4_t v = acc[nb][e] * inv;
+          *reinterpret_cast<f32x4_t*>(dst_o + 16 * e + 4 * c) = v;
           if (out_slot < 0 && p.o_cast != nullptr) {
-            uint16_t* dc = static_cast<uint16_t*>(p.o_cast) + final_row * kHeadDim + 32 * c + 8 * i;
-            const u32x4_t pk = {pack_out<BF>(lo[0], lo[1]), pack_out<BF>(lo[2], lo[3]), pack_out<BF>(hi[0], hi[1]),
-                                pack_out<BF>(hi[2], hi[3])};
-            *reinterpret_cast<u32x4_t*>(dc) = pk;
+            uint16_t* dc = static_cast<uint16_t*>(p.o_cast) + final_row * kHeadDim + 16 * e + 4 * c;
+            *reinterpret_cast<u32x2_t*>(dc) = u32x2_t{pack_out<BF>(v[0], v[1]), pack_out<BF>(v[2], v[3])};
           }
         }
         if (c == 0) *dst_lse = lse_val;
