@@ -33,7 +33,8 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 
 
 def library_path() -> str:
-    return os.path.join(_HERE, "lib", "libfi355.so")
+    """The built library; FI355_LIBRARY overrides the in-tree path (e.g. an instrumented build)."""
+    return os.environ.get("FI355_LIBRARY") or os.path.join(_HERE, "lib", "libfi355.so")
 
 
 class Fi355Error(RuntimeError):

@@ -82,7 +82,7 @@ int32_t fi_create(const fi_config* cfg, fi_handle** out) {
   PlanParams& pp = h->pp;
   pp.page_size = cfg->page_size;
   pp.group = g;
-  pp.t_pos = cfg->mode == FI_MODE_DECODE ? 1 : 128 / g;
+  pp.t_pos = cfg->mode == FI_MODE_DECODE ? 1 : append_tile_rows() / g;
   pp.ctas_per_head = num_ctas / cfg->num_kv_heads > 0 ? num_ctas / cfg->num_kv_heads : 1;
   pp.alpha = (cfg->alpha == 0 && cfg->beta == 0) ? 1 : cfg->alpha;
   pp.beta = (cfg->alpha == 0 && cfg->beta == 0) ? 1 : cfg->beta;

@@ -1,16 +1,22 @@
-// Paged append / prefill attention for gfx950 (causal or not): query tile = 128 fused rows
-// (128/g consecutive positions x g query heads of one kv head, App. A), four wavefronts per
-// CTA, each owning 32 rows.  K/V tiles of 64 tokens (four 16-token pages, gathered through
-// kv_indices, Sec. 3.2.1) are staged in LDS and shared by the four wavefronts; both products
-// run on the matrix cores:
-//   S^T[token][row] = K . Q^T      v_mfma_f32_16x16x32   A = K rows from LDS, B = Q^T in registers
-//   O^T[d][row]    += V^T . P^T    v_mfma_f32_16x16x32   A = V^T read from the row-major V tile with
+// Paged append / prefill attention for gfx950 (causal or not): query tile = 256 fused rows
+// (256/g consecutive positions x g query heads of one kv head, App. A), four wavefronts per
+// CTA, each owning two blocks of 32 rows.  K/V tiles of 64 tokens (four 16-token pages,
+// gathered through kv_indices, Sec. 3.2.1) are staged in a double-buffered LDS tile and shared
+// by the four wavefronts (one CTA barrier per tile); both products run on the matrix cores:
+//   S^T[token][row] = K . Q^T      v_mfma_f32_32x32x16   A = K rows from LDS, B = Q^T in registers
+//   O^T[d][row]    += V^T . P^T    v_mfma_f32_32x32x16   A = V^T read from the row-major V tile with
 //                                                        the LDS transpose read ds_read_b64_tr_b16,
 //                                                        B = P^T straight from the S^T accumulators
-// Computing the transposed products puts one query row per lane column, so the online-softmax
-// row maximum is an in-lane reduction plus two cross-lane exchanges, and P never moves
-// between lanes.  The contraction index of the second product is (page, lane group,
-// register) on both operands, so its order inside the instruction does not matter.
+// Computing the transposed products puts one query row per lane column (lane % 32), with 16
+// of the step's 32 tokens in each half of the wavefront: the row maximum (needed only when the
+// reference is raised) is an in-lane reduction plus one cross-lane exchange, and P never
+// moves between lanes.  The contraction index of the second product is (lane half, register)
+// on both operands, so its order inside the instruction does not matter.  The 32x32x16 shape
+// is used because a single wavefront issues it at ~90 % of the matrix pipe's peak, against
+// ~55 % for 16x16x32 (measured), which leaves issue slots for the softmax.  Two row blocks per
+// wavefront halve the LDS and L2 traffic per flop and give the instruction scheduler two
+// independent softmax / product streams to interleave (one block's exponentials run while the
+// other block's products occupy the matrix pipe).
 //
 // P is rounded to fp16 (11 significant bits).  For bf16 inputs V is converted to fp16 while it
 // is staged into LDS (exact for 2^-14 <= |v| <= 65504, saturating above, absolute error
@@ -32,20 +38,27 @@ constexpr int kTileKv = 64;        // tokens per LDS tile
 constexpr int kRowElems = 136;     // K tile row pitch in 16-bit elements (272 B): rows 4 banks apart, conflict-free b128 reads
 constexpr int kRowElemsV = 144;    // V tile row pitch (288 B): rows 8 banks apart, conflict-free transpose reads
 constexpr int kCtaThreads = 256;
-constexpr float kLazyLog2 = 8.0f;  // P may exceed 1 by at most 2^8 before the running reference is raised
+#ifndef FI355_APPEND_ROW_BLOCKS
+#define FI355_APPEND_ROW_BLOCKS 1
+#endif
+constexpr int kRowBlocks = FI355_APPEND_ROW_BLOCKS;  // 32-row blocks per wavefront; CTA tile = 4 * 32 * kRowBlocks fused rows
+constexpr int kLazyLog2 = 8;                                    // P may reach 2^8 before the reference is raised
+constexpr uint16_t kLazyF16Bits = (15 + kLazyLog2) << 10;       // fp16 bit pattern of 2^kLazyLog2
+
+typedef __attribute__((ext_vector_type(16))) float f32x16_t;
 
 template <bool BF>
-__device__ __forceinline__ f32x4_t mfma_qk(u32x4_t a, u32x4_t b, f32x4_t c) {
+__device__ __forceinline__ f32x16_t mfma_qk(u32x4_t a, u32x4_t b, f32x16_t c) {
   if constexpr (BF) {
-    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a), __builtin_bit_cast(bf16x8_t, b),
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, a), __builtin_bit_cast(bf16x8_t, b),
                                                    c, 0, 0, 0);
   } else {
-    return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8_t, a), __builtin_bit_cast(f16x8_t, b), c,
+    return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8_t, a), __builtin_bit_cast(f16x8_t, b), c,
                                                   0, 0, 0);
   }
 }
-__device__ __forceinline__ f32x4_t mfma_pv(u32x4_t a, u32x4_t b, f32x4_t c) {
-  return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8_t, a), __builtin_bit_cast(f16x8_t, b), c, 0,
+__device__ __forceinline__ f32x16_t mfma_pv(u32x4_t a, u32x4_t b, f32x16_t c) {
+  return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8_t, a), __builtin_bit_cast(f16x8_t, b), c, 0,
                                                 0, 0);
 }
 
@@ -70,6 +83,8 @@ __device__ __forceinline__ uint32_t bf16x2_to_f16x2(uint32_t w) {
 }
 
 typedef __attribute__((ext_vector_type(4))) short s16x4_t;
+typedef __attribute__((ext_vector_type(2))) uint16_t u16x2_t;
+typedef __attribute__((ext_vector_type(2))) float f32x2_t;
 typedef __attribute__((ext_vector_type(2))) uint32_t u32x2_t;
 // ds_read_b64_tr_b16: within each group of 16 lanes, lane 4 k + q supplies the address of 4
 // consecutive 16-bit elements; lane l of the group receives, in slot k = 0..3, element l % 4 of
@@ -81,66 +96,71 @@ __device__ __forceinline__ u32x2_t lds_read_tr16(const uint16_t* p) {
   return __builtin_bit_cast(u32x2_t, v);
 }
 
-// Exchanges between the four 16-lane rows of a wavefront without going through LDS:
+// Exchange between the two halves of a wavefront without going through LDS:
 // v_permlane32_swap swaps the upper half of its first operand with the lower half of its
-// second, v_permlane16_swap swaps the odd rows of the first with the even rows of the second.
-// With both operands holding x, the pair afterwards holds (x of lane l, x of lane l ^ 32)
-// resp. (x of lane l, x of lane l ^ 16) in some order, which is all a max or a sum needs.
+// second.  With both operands holding x, the pair afterwards holds (x of lane l, x of lane
+// l ^ 32) in some order, which is all a max or a sum needs.
 __device__ __forceinline__ void swap32(float x, float* a, float* b) {
   uint32_t u = __builtin_bit_cast(uint32_t, x), v = u;
   asm volatile("s_nop 1\n\tv_permlane32_swap_b32_e32 %0, %1" : "+v"(u), "+v"(v));
   *a = __builtin_bit_cast(float, u);
   *b = __builtin_bit_cast(float, v);
 }
-__device__ __forceinline__ void swap16(float x, float* a, float* b) {
-  uint32_t u = __builtin_bit_cast(uint32_t, x), v = u;
-  asm volatile("s_nop 1\n\tv_permlane16_swap_b32_e32 %0, %1" : "+v"(u), "+v"(v));
-  *a = __builtin_bit_cast(float, u);
-  *b = __builtin_bit_cast(float, v);
-}
-__device__ __forceinline__ float rows_max(float x) {
+__device__ __forceinline__ float halves_max(float x) {
   float a, b;
   swap32(x, &a, &b);
-  x = fmaxf(a, b);
-  swap16(x, &a, &b);
   return fmaxf(a, b);
 }
-__device__ __forceinline__ float rows_sum(float x) {
+__device__ __forceinline__ float halves_sum(float x) {
   float a, b;
   swap32(x, &a, &b);
-  x = a + b;
-  swap16(x, &a, &b);
   return a + b;
 }
 
 template <bool BF>
-__global__ void __launch_bounds__(kCtaThreads) __attribute__((amdgpu_waves_per_eu(2, 2)))
-append_kernel(const RunParams p) {
-  __shared__ __attribute__((aligned(16))) uint16_t lds_k[kTileKv * kRowElems];
-  __shared__ __attribute__((aligned(16))) uint16_t lds_v[kTileKv * kRowElemsV];
+__global__ void __launch_bounds__(kCtaThreads)
+    __attribute__((amdgpu_waves_per_eu(kRowBlocks == 1 ? 2 : 1, kRowBlocks == 1 ? 2 : 1))) append_kernel(const RunParams p) {
+  __shared__ __attribute__((aligned(16))) uint16_t lds_k[2][kTileKv * kRowElems];
+  __shared__ __attribute__((aligned(16))) uint16_t lds_v[2][kTileKv * kRowElemsV];
 
   const int tid = threadIdx.x;
   const int wave = tid >> 6;
   const int lane = tid & 63;
-  const int m = lane & 15;  // K: token in page; V: 16-byte column block; S/O: query row in block
-  const int c = lane >> 4;  // lane group
+  const int n = lane & 31;   // K: token of the 32-token step; V: column within a 32-wide block; S/O: query row
+  const int c = lane >> 5;   // wavefront half
   const int cta = blockIdx.x;
   const int kvh = blockIdx.y;
   const int g = p.group;
   const int g_log2 = 31 - __builtin_clz(g);
   const int H = p.num_qo_heads;
   const float NEG_INF = -__builtin_inff();
-  const float lazy_raw = kLazyLog2 / p.scale_log2;  // kLazyLog2 binary orders of magnitude in raw-logit units
+  constexpr int kWaveRows = 32 * kRowBlocks;
 
   // staging role: this thread moves the 16-byte block `st_chunk` of token slot `st_slot` of each of the 4 pages
   const int st_slot = tid >> 4;
   const int st_chunk = tid & 15;
-  const int64_t st_off = kvh * p.stride_head + st_slot * p.stride_tok + st_chunk * 8;
+  const uint32_t st_off = static_cast<uint32_t>(st_slot * p.stride_tok + st_chunk * 8);  // within one (page, head) block
+  const int st_lds_k = st_slot * kRowElems + st_chunk * 8;   // element offsets of this thread's block in a tile
+  const int st_lds_v = st_slot * kRowElemsV + st_chunk * 8;
   const uint16_t* kpool = static_cast<const uint16_t*>(p.k_pool);
   const uint16_t* vpool = static_cast<const uint16_t*>(p.v_pool);
 
+  // transpose-read role (see lds_read_tr16): in its 16-lane group this lane supplies the address of
+  // token row (lane % 16) / 4, columns 4 * (lane % 4) .. + 3 of the group's 16 columns
+  const int tr_row = (lane & 15) >> 2;
+  const int tr_col = 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
+
   const int w_begin = __builtin_amdgcn_readfirstlane(p.cta_indptr[cta]);
   const int w_end = __builtin_amdgcn_readfirstlane(p.cta_indptr[cta + 1]);
+
+  // Two CTAs share a CU (two wavefronts per SIMD) and run the same instruction stream; with
+  // equal priority they fall into lock-step and queue for the matrix pipe, the vector ALU and
+  // LDS at the same moments.  Giving the wavefront in the odd hardware slot a lower issue
+  // priority lets it fill the gaps of the other one instead.
+  if (__builtin_amdgcn_s_getreg((3 << 11) | 4) & 1)  // HW_ID.wave_id, bit 0
+    __builtin_amdgcn_s_setprio(0);
+  else
+    __builtin_amdgcn_s_setprio(3);
 
   for (int w = w_begin; w < w_end; ++w) {
     const int q_row0 = __builtin_amdgcn_readfirstlane(p.w_q_row0[w]);
@@ -152,42 +172,53 @@ append_kernel(const RunParams p) {
     const int out_slot = __builtin_amdgcn_readfirstlane(p.w_out_slot[w]);
     const int n_pages = (kv_len + kPageSize - 1) / kPageSize;
     const int n_tiles = (kv_len + kTileKv - 1) / kTileKv;
+    const bool causal = diag0 != kNoDiagMarker;
 
-    // ---- this lane's two query rows (one per 16-row block) ----
-    int pos[2], hh[2], lim[2];
-    bool row_ok[2];
-    u32x4_t qreg[2][4];
+    // ---- this lane's query rows, one per 32-row block ----
+    int pos[kRowBlocks], hh[kRowBlocks], lim[kRowBlocks];
+    bool row_ok[kRowBlocks];
+    u32x4_t qreg[kRowBlocks][8];  // Q^T as B operand: row n of the block, d = 16 s + 8 c .. + 8
 #pragma unroll
-    for (int nb = 0; nb < 2; ++nb) {
-      const int R = 32 * wave + 16 * nb + m;
-      pos[nb] = R >> g_log2;
-      hh[nb] = R & (g - 1);
-      row_ok[nb] = pos[nb] < n_pos;
-      // row sees request tokens <= diag0 + pos; in chunk-local terms: local index <= lim
-      lim[nb] = (diag0 == kNoDiagMarker) ? 0x3FFFFFFF : diag0 + pos[nb] - kv_start;
-      if (row_ok[nb]) {
+    for (int b = 0; b < kRowBlocks; ++b) {
+      const int R = kWaveRows * wave + 32 * b + n;
+      pos[b] = R >> g_log2;
+      hh[b] = R & (g - 1);
+      row_ok[b] = pos[b] < n_pos;
+      // the row sees request tokens <= diag0 + pos; in chunk-local terms: local index <= lim
+      lim[b] = causal ? diag0 + pos[b] - kv_start : 0x3FFFFFFF;
+      if (row_ok[b]) {
         const uint16_t* qp = static_cast<const uint16_t*>(p.q) +
-                             (static_cast<int64_t>(q_row0 + pos[nb]) * H + kvh * g + hh[nb]) * kHeadDim + c * 8;
+                             (static_cast<int64_t>(q_row0 + pos[b]) * H + kvh * g + hh[b]) * kHeadDim + c * 8;
 #pragma unroll
-        for (int s = 0; s < 4; ++s) qreg[nb][s] = *reinterpret_cast<const u32x4_t*>(qp + 32 * s);
+        for (int s = 0; s < 8; ++s) qreg[b][s] = *reinterpret_cast<const u32x4_t*>(qp + 16 * s);
       } else {
 #pragma unroll
-        for (int s = 0; s < 4; ++s) qreg[nb][s] = u32x4_t{0u, 0u, 0u, 0u};
+        for (int s = 0; s < 8; ++s) qreg[b][s] = u32x4_t{0u, 0u, 0u, 0u};
       }
     }
-    // wave-uniform bounds of lim over the wave's 32 rows (rows are position-major)
-    const int wave_pos_lo = (32 * wave) >> g_log2;
-    const int wave_pos_hi = (32 * wave + 31) >> g_log2;
-    const int wave_lim_lo = (diag0 == kNoDiagMarker) ? 0x3FFFFFFF : diag0 + wave_pos_lo - kv_start;
-    const int wave_lim_hi = (diag0 == kNoDiagMarker) ? 0x3FFFFFFF : diag0 + wave_pos_hi - kv_start;
+    // wave-uniform bounds of lim per block (rows are position-major)
+    int blk_lim_lo[kRowBlocks], blk_lim_hi[kRowBlocks];
+#pragma unroll
+    for (int b = 0; b < kRowBlocks; ++b) {
+      const int r0 = kWaveRows * wave + 32 * b;
+      blk_lim_lo[b] = causal ? diag0 + (r0 >> g_log2) - kv_start : 0x3FFFFFFF;
+      blk_lim_hi[b] = causal ? diag0 + ((r0 + 31) >> g_log2) - kv_start : 0x3FFFFFFF;
+    }
 
-    f32x4_t acc[2][8];  // acc[nb][e][i] = O^T[d = 16 e + 4 c + i][row m of block nb]
+    f32x16_t acc[kRowBlocks][4];  // acc[b][db][r] = O^T[d = 32 db + 8 (r / 4) + 4 c + r % 4][row n of block b]
 #pragma unroll
-    for (int nb = 0; nb < 2; ++nb)
+    for (int b = 0; b < kRowBlocks; ++b)
 #pragma unroll
-      for (int e = 0; e < 8; ++e) acc[nb][e] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-    float m_run[2] = {NEG_INF, NEG_INF};  // reference for the exponentials: raw-logit units, >= row max - lazy_raw
-    float l_run[2] = {0.f, 0.f};
+      for (int db = 0; db < 4; ++db)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[b][db][r] = 0.f;
+    float m_run[kRowBlocks], neg_ms[kRowBlocks], l_run[kRowBlocks];
+#pragma unroll
+    for (int b = 0; b < kRowBlocks; ++b) {
+      m_run[b] = NEG_INF;  // reference of the exponentials, raw-logit units (-inf: none yet)
+      neg_ms[b] = 0.f;     // -reference * scale_log2 (0 while there is none)
+      l_run[b] = 0.f;      // this lane's share of the row sum
+    }
 
     u32x4_t stage_k[4], stage_v[4];
     // Page ids are fetched one tile ahead of the data they address (lane r holds page r of the
@@ -201,172 +232,204 @@ append_kernel(const RunParams p) {
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
         const int pg = __builtin_amdgcn_readlane(ids, r);
-        const int64_t off = pg * p.stride_page + st_off;
-        stage_k[r] = *reinterpret_cast<const u32x4_t*>(kpool + off);
-        stage_v[r] = *reinterpret_cast<const u32x4_t*>(vpool + off);
+        const int64_t page_off = pg * p.stride_page + kvh * p.stride_head;  // wave-uniform
+        stage_k[r] = *reinterpret_cast<const u32x4_t*>(kpool + page_off + st_off);
+        stage_v[r] = *reinterpret_cast<const u32x4_t*>(vpool + page_off + st_off);
       }
     };
     auto store_tile = [&](int t) {
+      uint16_t* dk = lds_k[t & 1];
+      uint16_t* dv = lds_v[t & 1];
+      if constexpr (BF) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+          stage_v[r] = u32x4_t{bf16x2_to_f16x2(stage_v[r][0]), bf16x2_to_f16x2(stage_v[r][1]),
+                               bf16x2_to_f16x2(stage_v[r][2]), bf16x2_to_f16x2(stage_v[r][3])};
+      }
+      if (kTileKv * (t + 1) > kv_len) {  // CTA-uniform: only the chunk's last tile has rows past its end
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+          if (kTileKv * t + 16 * r + st_slot >= kv_len) stage_v[r] = u32x4_t{0u, 0u, 0u, 0u};  // must not reach P.V
+      }
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
-        const int tok = 16 * r + st_slot;
-        u32x4_t v = stage_v[r];
-        if constexpr (BF) {
-          v = u32x4_t{bf16x2_to_f16x2(v[0]), bf16x2_to_f16x2(v[1]), bf16x2_to_f16x2(v[2]), bf16x2_to_f16x2(v[3])};
-        }
-        if (kTileKv * t + tok >= kv_len) v = u32x4_t{0u, 0u, 0u, 0u};  // rows past the chunk must not reach P.V
-        *reinterpret_cast<u32x4_t*>(&lds_k[tok * kRowElems + st_chunk * 8]) = stage_k[r];
-        *reinterpret_cast<u32x4_t*>(&lds_v[tok * kRowElemsV + st_chunk * 8]) = v;
+        *reinterpret_cast<u32x4_t*>(&dk[st_lds_k + 16 * r * kRowElems]) = stage_k[r];
+        *reinterpret_cast<u32x4_t*>(&dv[st_lds_v + 16 * r * kRowElemsV]) = stage_v[r];
       }
     };
 
+    // Pipeline: while tile t is consumed from LDS buffer t % 2, tile t + 1 sits in the staging
+    // registers (its loads were issued a whole tile earlier) and is written to buffer
+    // (t + 1) % 2 after the products of tile t have been issued; one barrier per tile.
     int ids_next = 0;
+    __syncthreads();  // the previous work item's last tile is no longer being read
     if (n_tiles > 0) {
       fetch_tile(fetch_page_ids(0));
       if (n_tiles > 1) ids_next = fetch_page_ids(1);
-    }
-    for (int t = 0; t < n_tiles; ++t) {
-      __syncthreads();  // everyone is done reading the previous tile
-      store_tile(t);
-      __syncthreads();
-      if (t + 1 < n_tiles) {
-        fetch_tile(ids_next);  // in flight while this tile is consumed
-        if (t + 2 < n_tiles) ids_next = fetch_page_ids(t + 2);
+      store_tile(0);
+      if (n_tiles > 1) {
+        fetch_tile(ids_next);
+        if (n_tiles > 2) ids_next = fetch_page_ids(2);
       }
-
+    }
+    __syncthreads();
+    for (int t = 0; t < n_tiles; ++t) {
+      const uint16_t* tk = lds_k[t & 1];
+      const uint16_t* tv = lds_v[t & 1];
 #pragma unroll
       for (int u = 0; u < 2; ++u) {
         const int tok_base = kTileKv * t + 32 * u;  // chunk-local index of this 32-token step
-        if (tok_base >= kv_len || tok_base > wave_lim_hi) continue;  // nothing visible to this wavefront
+        if (tok_base >= kv_len || tok_base > blk_lim_hi[kRowBlocks - 1]) continue;  // nothing visible to this wavefront
         // ---- S^T = K . Q^T: all eight A operands are requested before the first product ----
-        u32x4_t ka[2][4];
-#pragma unroll
-        for (int pg = 0; pg < 2; ++pg) {
-          const uint16_t* krow = &lds_k[(32 * u + 16 * pg + m) * kRowElems + c * 8];
-#pragma unroll
-          for (int s = 0; s < 4; ++s) ka[pg][s] = *reinterpret_cast<const u32x4_t*>(krow + 32 * s);
-        }
-        f32x4_t sacc[2][2];
-#pragma unroll
-        for (int nb = 0; nb < 2; ++nb)
-#pragma unroll
-          for (int pg = 0; pg < 2; ++pg) sacc[nb][pg] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int s = 0; s < 4; ++s)
-#pragma unroll
-          for (int pg = 0; pg < 2; ++pg) {
-            sacc[0][pg] = mfma_qk<BF>(ka[pg][s], qreg[0][s], sacc[0][pg]);
-            sacc[1][pg] = mfma_qk<BF>(ka[pg][s], qreg[1][s], sacc[1][pg]);
-          }
-        // ---- V^T operands (16 columns d = 16 e + m of tokens (page, 4 c + k)): requested now,
-        //      they arrive while the softmax below runs on the vector ALU ----
-        u32x4_t vt[8];
+        u32x4_t ka[8];
         {
-          const int k4 = m >> 2, q4 = m & 3;  // this lane's role as address supplier in its 16-lane group
-          const uint16_t* vsrc = &lds_v[(32 * u + 4 * c + k4) * kRowElemsV + 4 * q4];
+          const uint16_t* krow = &tk[(32 * u + n) * kRowElems + c * 8];
 #pragma unroll
-          for (int e = 0; e < 8; ++e) {
-            const u32x2_t lo = lds_read_tr16(vsrc + 16 * e);                    // page 0 of the step
-            const u32x2_t hi = lds_read_tr16(vsrc + 16 * kRowElemsV + 16 * e);  // page 1
-            vt[e] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3);
-          }
+          for (int s = 0; s < 8; ++s) ka[s] = *reinterpret_cast<const u32x4_t*>(krow + 16 * s);
         }
-        // ---- online softmax, one row per (lane column, block) ----
-        const bool need_mask = (tok_base + 32 > kv_len) || (tok_base + 31 > wave_lim_lo);
-        u32x4_t pb[2];
+        f32x16_t sacc[kRowBlocks];
 #pragma unroll
-        for (int nb = 0; nb < 2; ++nb) {
-          float sv[8];  // raw logits q.k; the softmax scale is folded into the exponent below
+        for (int b = 0; b < kRowBlocks; ++b) {
 #pragma unroll
-          for (int i = 0; i < 4; ++i) {
-            sv[i] = sacc[nb][0][i];
-            sv[4 + i] = sacc[nb][1][i];
-          }
+          for (int r = 0; r < 16; ++r) sacc[b][r] = 0.f;
+#pragma unroll
+          for (int s = 0; s < 8; ++s) sacc[b] = mfma_qk<BF>(ka[s], qreg[b][s], sacc[b]);
+        }
+        // lane (n, c) now holds S^T[token 8 (r / 4) + 4 c + r % 4][row n of block b], r = 0..15
+
+        // ---- V^T operands: requested now, they arrive while the softmax runs on the vector ALU.
+        //      Operand (db, j) = columns d = 32 db + (lane % 32), token slots e = 0..7 <->
+        //      tokens 16 j + 8 (e / 4) + 4 c + e % 4 (the order P^T has in the S^T registers) ----
+        u32x4_t vt[4][2];
+        {
+          const uint16_t* vsrc = &tv[(32 * u + 4 * c + tr_row) * kRowElemsV + tr_col];
+#pragma unroll
+          for (int db = 0; db < 4; ++db)
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+              const u32x2_t lo = lds_read_tr16(vsrc + (16 * j) * kRowElemsV + 32 * db);
+              const u32x2_t hi = lds_read_tr16(vsrc + (16 * j + 8) * kRowElemsV + 32 * db);
+              vt[db][j] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3);
+            }
+        }
+
+#pragma unroll
+        for (int b = 0; b < kRowBlocks; ++b) {
+          if (tok_base > blk_lim_hi[b]) continue;  // block wholly above the diagonal (wave-uniform)
+          // ---- online softmax on the 16 logits of its row this lane owns ----
+          float sv[16];  // raw logits q.k; the softmax scale is folded into the exponent below
+#pragma unroll
+          for (int r = 0; r < 16; ++r) sv[r] = sacc[b][r];
+          const bool need_mask = (tok_base + 32 > kv_len) || (tok_base + 31 > blk_lim_lo[b]);
           if (need_mask) {
-            const int cap = min(lim[nb], kv_len - 1);
+            const int cap = min(lim[b], kv_len - 1);
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-              const int t0 = tok_base + 4 * c + i;
-              sv[i] = (t0 <= cap) ? sv[i] : NEG_INF;
-              sv[4 + i] = (t0 + 16 <= cap) ? sv[4 + i] : NEG_INF;
+            for (int r = 0; r < 16; ++r) {
+              const int tkn = tok_base + 8 * (r >> 2) + 4 * c + (r & 3);
+              sv[r] = (tkn <= cap) ? sv[r] : NEG_INF;
             }
           }
-          float tmax = fmaxf(fmaxf(fmaxf(sv[0], sv[1]), fmaxf(sv[2], sv[3])), fmaxf(fmaxf(sv[4], sv[5]), fmaxf(sv[6], sv[7])));
-          tmax = rows_max(tmax);
-          // Lazy reference update: the reference m_run only has to bound the logits from above
-          // up to 2^kLazyLog2 (P then stays <= 2^kLazyLog2, well inside fp16 and fp32 range); the
-          // result o = O / l does not depend on it.  Rescaling the 32 accumulator registers is
-          // thus needed only when the row maximum jumps, not on every small increase.
-          if (__builtin_amdgcn_ballot_w64(tmax > m_run[nb] + lazy_raw) != 0) {
-            const float m_new = fmaxf(m_run[nb], tmax);
+          // Optimistic softmax: exponentiate against the current reference first, and only if
+          // some P came out above 2^kLazyLog2 (or the row has no reference yet) find the row
+          // maximum, raise the reference, rescale, and redo the exponentials.  The reference
+          // only has to keep P inside fp16 range; o = O / l does not depend on it.  The common
+          // step therefore has no max reduction, no cross-lane exchange and no rescale.
+          f16x2_t h[8];
+          auto exponentiate = [&]() {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+              const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(sv[2 * j], p.scale_log2, neg_ms[b]));
+              const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(sv[2 * j + 1], p.scale_log2, neg_ms[b]));
+              h[j] = __builtin_convertvector(f32x2_t{p0, p1}, f16x2_t);  // one v_cvt_pk_f16_f32
+            }
+          };
+          exponentiate();
+          // P >= 0, so fp16 order is unsigned-integer order on the bit patterns (inf included)
+          u16x2_t hmax = __builtin_bit_cast(u16x2_t, h[0]);
+#pragma unroll
+          for (int j = 1; j < 8; ++j) hmax = __builtin_elementwise_max(hmax, __builtin_bit_cast(u16x2_t, h[j]));
+          const bool redo = hmax[0] > kLazyF16Bits || hmax[1] > kLazyF16Bits || m_run[b] == NEG_INF;
+          if (__builtin_amdgcn_ballot_w64(redo) != 0) {
+            float tmax = sv[0];
+#pragma unroll
+            for (int r = 1; r < 16; ++r) tmax = fmaxf(tmax, sv[r]);
+            tmax = halves_max(tmax);
+            const float m_new = fmaxf(m_run[b], tmax);
             const float m_use = (m_new == NEG_INF) ? 0.f : m_new;  // row has seen nothing yet
-            const float alpha = __builtin_amdgcn_exp2f((m_run[nb] - m_use) * p.scale_log2);
-            m_run[nb] = m_new;
-            l_run[nb] *= alpha;
+            const float alpha = __builtin_amdgcn_exp2f((m_run[b] - m_use) * p.scale_log2);
+            m_run[b] = m_new;
+            neg_ms[b] = -m_use * p.scale_log2;
+            l_run[b] *= alpha;
 #pragma unroll
-            for (int e = 0; e < 8; ++e) acc[nb][e] *= alpha;
+            for (int db = 0; db < 4; ++db) acc[b][db] *= alpha;
+            exponentiate();
           }
-          const float neg_ms = (m_run[nb] == NEG_INF) ? 0.f : -m_run[nb] * p.scale_log2;
-          float pv[8];
-#pragma unroll
-          for (int j = 0; j < 8; ++j) pv[j] = __builtin_amdgcn_exp2f(__builtin_fmaf(sv[j], p.scale_log2, neg_ms));
-          const f16x2_t h0 = {static_cast<_Float16>(pv[0]), static_cast<_Float16>(pv[1])};
-          const f16x2_t h1 = {static_cast<_Float16>(pv[2]), static_cast<_Float16>(pv[3])};
-          const f16x2_t h2 = {static_cast<_Float16>(pv[4]), static_cast<_Float16>(pv[5])};
-          const f16x2_t h3 = {static_cast<_Float16>(pv[6]), static_cast<_Float16>(pv[7])};
-          pb[nb] = u32x4_t{__builtin_bit_cast(uint32_t, h0), __builtin_bit_cast(uint32_t, h1),
-                           __builtin_bit_cast(uint32_t, h2), __builtin_bit_cast(uint32_t, h3)};
           // The row sum is taken over the fp16-rounded P that the second product consumes
           // (v_dot2_f32_f16 with a vector of ones, fp32 accumulation): o = O / l is then an exact
           // convex combination of V rows whatever the reference, and a single dominant key
           // returns its V row exactly.
           const f16x2_t ones = {static_cast<_Float16>(1.0f), static_cast<_Float16>(1.0f)};
-          float l = l_run[nb];
-          l = __builtin_amdgcn_fdot2(h0, ones, l, false);
-          l = __builtin_amdgcn_fdot2(h1, ones, l, false);
-          l = __builtin_amdgcn_fdot2(h2, ones, l, false);
-          l = __builtin_amdgcn_fdot2(h3, ones, l, false);
-          l_run[nb] = l;
-        }
-        // ---- O^T += V^T . P^T ----
+          float l = l_run[b];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-          acc[0][e] = mfma_pv(vt[e], pb[0], acc[0][e]);
-          acc[1][e] = mfma_pv(vt[e], pb[1], acc[1][e]);
+          for (int j = 0; j < 8; ++j) l = __builtin_amdgcn_fdot2(h[j], ones, l, false);
+          l_run[b] = l;
+          const u32x4_t pb0 = {__builtin_bit_cast(uint32_t, h[0]), __builtin_bit_cast(uint32_t, h[1]),
+                               __builtin_bit_cast(uint32_t, h[2]), __builtin_bit_cast(uint32_t, h[3])};
+          const u32x4_t pb1 = {__builtin_bit_cast(uint32_t, h[4]), __builtin_bit_cast(uint32_t, h[5]),
+                               __builtin_bit_cast(uint32_t, h[6]), __builtin_bit_cast(uint32_t, h[7])};
+          // ---- O^T += V^T . P^T ----
+#pragma unroll
+          for (int db = 0; db < 4; ++db) {
+            acc[b][db] = mfma_pv(vt[db][0], pb0, acc[b][db]);
+            acc[b][db] = mfma_pv(vt[db][1], pb1, acc[b][db]);
+          }
         }
       }
+      // hand the next tile over and request the one after it
+      if (t + 1 < n_tiles) {
+        store_tile(t + 1);
+        if (t + 2 < n_tiles) {
+          fetch_tile(ids_next);
+          if (t + 3 < n_tiles) ids_next = fetch_page_ids(t + 3);
+        }
+      }
+      __syncthreads();  // tile t + 1 is visible; nobody reads tile t any more
     }
 
     // ---- epilogue: o = O / l, lse = ln(sum exp) (Sec. 2.2) ----
 #pragma unroll
-    for (int nb = 0; nb < 2; ++nb) {
-      const float l = rows_sum(l_run[nb]);
+    for (int b = 0; b < kRowBlocks; ++b) {
+      const float l = halves_sum(l_run[b]);
       const bool live = l > 0.f;
       const float inv = live ? 1.0f / l : 0.f;
       const float lse_val =
-          live ? (m_run[nb] * p.scale_log2 + __builtin_amdgcn_logf(l)) * 0.6931471805599453f : NEG_INF;
-      if (row_ok[nb]) {
-        const int head = kvh * g + hh[nb];
-        const int64_t final_row = static_cast<int64_t>(q_row0 + pos[nb]) * H + head;
+          live ? (m_run[b] * p.scale_log2 + __builtin_amdgcn_logf(l)) * 0.6931471805599453f : NEG_INF;
+      if (row_ok[b]) {
+        const int head = kvh * g + hh[b];
+        const int64_t final_row = static_cast<int64_t>(q_row0 + pos[b]) * H + head;
         float* dst_o;
         float* dst_lse;
         if (out_slot < 0) {  // write-through (App. D.2)
           dst_o = p.o + final_row * kHeadDim;
           dst_lse = p.lse + final_row;
         } else {
-          const int64_t row = (static_cast<int64_t>(out_slot) * p.t_pos + pos[nb]) * H + head;
+          const int64_t row = (static_cast<int64_t>(out_slot) * p.t_pos + pos[b]) * H + head;
           dst_o = p.part_o + row * kHeadDim;
           dst_lse = p.part_lse + row;
         }
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-          const f32x4_t v = acc[nb][e] * inv;
-          *reinterpret_cast<f32x4_t*>(dst_o + 16 * e + 4 * c) = v;
-          if (out_slot < 0 && p.o_cast != nullptr) {
-            uint16_t* dc = static_cast<uint16_t*>(p.o_cast) + final_row * kHeadDim + 16 * e + 4 * c;
-            *reinterpret_cast<u32x2_t*>(dc) = u32x2_t{pack_out<BF>(v[0], v[1]), pack_out<BF>(v[2], v[3])};
+        for (int db = 0; db < 4; ++db)
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            const int d0 = 32 * db + 8 * q + 4 * c;
+            const f32x4_t v = {acc[b][db][4 * q] * inv, acc[b][db][4 * q + 1] * inv, acc[b][db][4 * q + 2] * inv,
+                               acc[b][db][4 * q + 3] * inv};
+            *reinterpret_cast<f32x4_t*>(dst_o + d0) = v;
+            if (out_slot < 0 && p.o_cast != nullptr) {
+              uint16_t* dc = static_cast<uint16_t*>(p.o_cast) + final_row * kHeadDim + d0;
+              *reinterpret_cast<u32x2_t*>(dc) = u32x2_t{pack_out<BF>(v[0], v[1]), pack_out<BF>(v[2], v[3])};
+            }
           }
-        }
         if (c == 0) *dst_lse = lse_val;
       }
     }
@@ -374,6 +437,8 @@ append_kernel(const RunParams p) {
 }
 
 }  // namespace
+
+int append_tile_rows() { return 4 * 32 * kRowBlocks; }
 
 hipError_t launch_append(const RunParams& p, bool is_bf16, hipStream_t stream) {
   const dim3 grid(static_cast<unsigned>(p.ctas_per_head), static_cast<unsigned>(p.num_kv_heads), 1);

@@ -48,8 +48,9 @@ struct MergeParams {
 
 // decode.hip: query tile = 1 position x g fused heads, one wavefront per CTA.
 hipError_t launch_decode(const RunParams& p, bool is_bf16, hipStream_t stream);
-// append.hip: query tile = 128/g positions x g fused heads, 4 wavefronts per CTA.
+// append.hip: query tile = append_tile_rows()/g positions x g fused heads, 4 wavefronts per CTA.
 hipError_t launch_append(const RunParams& p, bool is_bf16, hipStream_t stream);
+int append_tile_rows();  // fused rows (positions x group) of one append query tile
 // upload.hip: staging (device view of page-locked host memory) -> plan section
 hipError_t launch_plan_upload(const int32_t* staging_dev_view, int32_t* plan_section, int32_t n_ints,
                               hipStream_t stream);
