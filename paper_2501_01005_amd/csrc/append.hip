@@ -153,15 +153,6 @@ __global__ void __launch_bounds__(kCtaThreads)
   const int w_begin = __builtin_amdgcn_readfirstlane(p.cta_indptr[cta]);
   const int w_end = __builtin_amdgcn_readfirstlane(p.cta_indptr[cta + 1]);
 
-  // Two CTAs share a CU (two wavefronts per SIMD) and run the same instruction stream; with
-  // equal priority they fall into lock-step and queue for the matrix pipe, the vector ALU and
-  // LDS at the same moments.  Giving the wavefront in the odd hardware slot a lower issue
-  // priority lets it fill the gaps of the other one instead.
-  if (__builtin_amdgcn_s_getreg((3 << 11) | 4) & 1)  // HW_ID.wave_id, bit 0
-    __builtin_amdgcn_s_setprio(0);
-  else
-    __builtin_amdgcn_s_setprio(3);
-
   for (int w = w_begin; w < w_end; ++w) {
     const int q_row0 = __builtin_amdgcn_readfirstlane(p.w_q_row0[w]);
     const int n_pos = __builtin_amdgcn_readfirstlane(p.w_n_pos[w]);
