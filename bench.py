@@ -108,12 +108,81 @@ def cpu_baseline(batch, unit_work: float, unit: str, budget_s: float = 10.0) -> 
             "seconds_per_batch": best}
 
 
+def bench_shared_prefix(args) -> int:
+    """Workload c5: one decode step of 64 requests sharing a 4096-token prefix.  Composable
+    formats (Sec. 3.1.2): prefix pass = one 64-query row block through the append tile kernel,
+    suffix pass = paged decode, then fi_merge_state_pair; timed against the single-format decode
+    of the same problem on the same box (the comparison of the paper's shared-prefix table)."""
+    import torch
+    import workloads
+    import paper_2501_01005_amd as fi
+    sys.path.insert(0, os.path.join(ROOT, "tests"))
+    from gpu_util import DeviceBatch, make_wrapper
+
+    c = workloads.config5(small=args.small)
+    dev_p, dev_s, dev_1 = DeviceBatch(c.prefix), DeviceBatch(c.suffix), DeviceBatch(c.single)
+    wp = make_wrapper(c.prefix, "append", num_ctas=args.num_ctas, min_chunk=args.min_chunk)
+    ws = make_wrapper(c.suffix, "decode")
+    w1 = make_wrapper(c.single, "decode")
+    n, H, D = dev_p.q.shape[0], c.prefix.num_qo_heads, c.prefix.head_dim
+    o_p = torch.empty((n, H, D), dtype=torch.float32, device="cuda:0"); l_p = torch.empty((n, H), dtype=torch.float32, device="cuda:0")
+    o_s = torch.empty_like(o_p); l_s = torch.empty_like(l_p)
+    o_1 = torch.empty_like(o_p); l_1 = torch.empty_like(l_p)
+    stream = torch.cuda.current_stream().cuda_stream
+
+    def composed(plan=True):
+        if plan:
+            wp.plan(c.prefix.qo_indptr, c.prefix.kv_indptr, c.prefix.last_page_len, causal=False)
+            ws.plan(c.suffix.qo_indptr, c.suffix.kv_indptr, c.suffix.last_page_len, causal=False)
+        wp.run(dev_p.q, dev_p.k_pool, dev_p.v_pool, dev_p.kv_indices, c.prefix.sm_scale, o=o_p, lse=l_p)
+        ws.run(dev_s.q, dev_s.k_pool, dev_s.v_pool, dev_s.kv_indices, c.suffix.sm_scale, o=o_s, lse=l_s)
+        fi.fi_merge_state_pair(o_p, l_p, o_s, l_s, n * H, D, o_p, l_p, stream)
+
+    def single(plan=True):
+        if plan:
+            w1.plan(c.single.qo_indptr, c.single.kv_indptr, c.single.last_page_len, causal=False)
+        w1.run(dev_1.q, dev_1.k_pool, dev_1.v_pool, dev_1.kv_indices, c.single.sm_scale, o=o_1, lse=l_1)
+
+    def timeit(fn, plan):
+        fn(True)
+        for _ in range(args.warmup):
+            fn(plan)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            fn(plan)
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / args.steps * 1e6
+
+    us_comp = timeit(composed, not args.no_plan)
+    us_single = timeit(single, not args.no_plan)
+    bytes_comp = c.prefix.kv_bytes() + c.suffix.kv_bytes() + n * H * D * 2 + 3 * n * H * (D + 1) * 4
+    bytes_single = c.single.kv_bytes() + n * H * D * 2 + n * H * (D + 1) * 4
+    line = {
+        "metric": "achieved HBM bandwidth, shared-prefix decode step in composable formats (algorithmic bytes, prefix once / step time)",
+        "value": bytes_comp / (us_comp * 1e-6) / 1e9, "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": us_comp * 1e-3, "us_per_batch": us_comp, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": c.prefix.dtype, "data": "synthetic",
+        "config": {"workload": "c5_shared_prefix" + ("_small" if args.small else ""), "requests": n,
+                   "prefix_tokens": int(c.prefix.kv_lens()[0]), "step": "3 launches + merge" if args.no_plan else "2 plans + 3 launches + merge"},
+        "frac_of_peak": bytes_comp / (us_comp * 1e-6) / 1e9 / HBM_PEAK_GBS,
+        "composable_us": us_comp, "single_format_us": us_single, "speedup_vs_single_format": us_single / us_comp,
+        "algorithmic_bytes_composable": bytes_comp, "algorithmic_bytes_single_format": bytes_single,
+        "single_format_GBps": bytes_single / (us_single * 1e-6) / 1e9,
+        "roofline": {"bound": "hbm", "kernel": "latency-bound (3 dependent launches); see single_format_GBps for the streaming rate",
+                     "achieved": bytes_comp / (us_comp * 1e-6) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": bytes_comp / (us_comp * 1e-6) / 1e9 / HBM_PEAK_GBS, "traffic": None},
+    }
+    print(json.dumps(line))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4"])
+    ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4", "c5"])
     ap.add_argument("--small", action="store_true", help="small variant of the workload (debug)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-plan", action="store_true", help="time fi_run only (plan once, as for layers 2..L)")
@@ -146,6 +215,8 @@ def main() -> int:
         print(json.dumps({"calibration": "torch.add(src, 1.0, out=dst)", "read_bytes_per_launch": n * 4,
                           "write_bytes_per_launch": n * 4, "launches": args.warmup + args.steps}))
         return 0
+    if args.workload == "c5":
+        return bench_shared_prefix(args)
     batch = getattr(workloads, "config" + args.workload[1])(small=args.small)
     mode = "append" if args.workload == "c3" else "decode"
     dev = DeviceBatch(batch)

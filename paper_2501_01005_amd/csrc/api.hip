@@ -86,7 +86,8 @@ int32_t fi_create(const fi_config* cfg, fi_handle** out) {
   pp.ctas_per_head = num_ctas / cfg->num_kv_heads > 0 ? num_ctas / cfg->num_kv_heads : 1;
   pp.alpha = (cfg->alpha == 0 && cfg->beta == 0) ? 1 : cfg->alpha;
   pp.beta = (cfg->alpha == 0 && cfg->beta == 0) ? 1 : cfg->beta;
-  pp.min_chunk = cfg->min_chunk > 0 ? cfg->min_chunk : 256;
+  // default: decode chunks of at least 128 tokens (4 steps of a wavefront), append chunks of 256
+  pp.min_chunk = cfg->min_chunk > 0 ? cfg->min_chunk : (cfg->mode == FI_MODE_DECODE ? 128 : 256);
   pp.literal_lkv = cfg->literal_lkv != 0;
   pp.max_batch = cfg->max_batch;
   pp.max_qo_tiles = cfg->max_qo_tiles;
