@@ -52,7 +52,7 @@ extern "C" {
 #define FI_DTYPE_BF16 1
 
 #define FI_MODE_DECODE 0 /* query tile = 1 position x g fused heads; one wavefront per CTA   */
-#define FI_MODE_APPEND 1 /* query tile = 128/g positions x g fused heads; MFMA tile kernel     */
+#define FI_MODE_APPEND 1 /* query tile = 256/g positions x g fused heads; MFMA tile kernel     */
 
 typedef struct fi_handle fi_handle;
 typedef void* fi_stream; /* a hipStream_t (0 = the null stream) */

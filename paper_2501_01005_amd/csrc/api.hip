@@ -72,8 +72,8 @@ int32_t fi_create(const fi_config* cfg, fi_handle** out) {
     int cus = 0;
     e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
     if (e != hipSuccess) return hip_error("fi_create: hipDeviceGetAttribute", e);
-    // decode: one wavefront per CTA, 8 resident per CU; append: 4-wavefront CTAs, 2 per CU
-    num_ctas = cfg->mode == FI_MODE_DECODE ? 8 * cus : 2 * cus;
+    // decode: one wavefront per CTA, 8 resident per CU; append: one 8-wavefront CTA per CU
+    num_ctas = cfg->mode == FI_MODE_DECODE ? 8 * cus : cus;
   }
   fi_handle* h = new (std::nothrow) fi_handle();
   if (!h) return set_error(FI_ERR_INVALID_ARG, "fi_create: out of host memory");

@@ -1,8 +1,9 @@
 // Paged append / prefill attention for gfx950 (causal or not): query tile = 256 fused rows
-// (256/g consecutive positions x g query heads of one kv head, App. A), four wavefronts per
-// CTA, each owning two blocks of 32 rows.  K/V tiles of 64 tokens (four 16-token pages,
-// gathered through kv_indices, Sec. 3.2.1) are staged in a double-buffered LDS tile and shared
-// by the four wavefronts (one CTA barrier per tile); both products run on the matrix cores:
+// (256/g consecutive positions x g query heads of one kv head, App. A), one CTA of eight
+// wavefronts per CU, each wavefront owning 32 rows.  K/V tiles of 64 tokens (four 16-token
+// pages, gathered through kv_indices, Sec. 3.2.1) are staged in a double-buffered LDS tile and
+// shared by the eight wavefronts (one CTA barrier per tile, loads issued two tiles ahead); both
+// products run on the matrix cores:
 //   S^T[token][row] = K . Q^T      v_mfma_f32_32x32x16   A = K rows from LDS, B = Q^T in registers
 //   O^T[d][row]    += V^T . P^T    v_mfma_f32_32x32x16   A = V^T read from the row-major V tile with
 //                                                        the LDS transpose read ds_read_b64_tr_b16,
@@ -13,15 +14,14 @@
 // moves between lanes.  The contraction index of the second product is (lane half, register)
 // on both operands, so its order inside the instruction does not matter.  The 32x32x16 shape
 // is used because a single wavefront issues it at ~90 % of the matrix pipe's peak, against
-// ~55 % for 16x16x32 (measured), which leaves issue slots for the softmax.  Two row blocks per
-// wavefront halve the LDS and L2 traffic per flop and give the instruction scheduler two
-// independent softmax / product streams to interleave (one block's exponentials run while the
-// other block's products occupy the matrix pipe).
+// ~55 % for 16x16x32 (measured), which leaves issue slots for the softmax.
 //
 // P is rounded to fp16 (11 significant bits).  For bf16 inputs V is converted to fp16 while it
 // is staged into LDS (exact for 2^-14 <= |v| <= 65504, saturating above, absolute error
 // < 2^-24 below), because a bf16 P (8 bits) would miss the 2e-3 output tolerance on rows that
 // see few keys; Q.K^T stays in the input type.
+#include <type_traits>
+
 #include "kernels.h"
 
 namespace fi355 {
@@ -37,11 +37,8 @@ typedef __attribute__((ext_vector_type(4))) uint32_t u32x4_t;
 constexpr int kTileKv = 64;        // tokens per LDS tile
 constexpr int kRowElems = 136;     // K tile row pitch in 16-bit elements (272 B): rows 4 banks apart, conflict-free b128 reads
 constexpr int kRowElemsV = 144;    // V tile row pitch (288 B): rows 8 banks apart, conflict-free transpose reads
-constexpr int kCtaThreads = 256;
-#ifndef FI355_APPEND_ROW_BLOCKS
-#define FI355_APPEND_ROW_BLOCKS 1
-#endif
-constexpr int kRowBlocks = FI355_APPEND_ROW_BLOCKS;  // 32-row blocks per wavefront; CTA tile = 4 * 32 * kRowBlocks fused rows
+constexpr int kCtaThreads = 512;   // 8 wavefronts, 32 query rows each
+constexpr int kRowBlocks = 1;       // 32-row blocks per wavefront; CTA tile = 8 * 32 * kRowBlocks fused rows
 constexpr int kLazyLog2 = 8;                                    // P may reach 2^8 before the reference is raised
 constexpr uint16_t kLazyF16Bits = (15 + kLazyLog2) << 10;       // fp16 bit pattern of 2^kLazyLog2
 
@@ -118,8 +115,8 @@ __device__ __forceinline__ float halves_sum(float x) {
 }
 
 template <bool BF>
-__global__ void __launch_bounds__(kCtaThreads)
-    __attribute__((amdgpu_waves_per_eu(kRowBlocks == 1 ? 2 : 1, kRowBlocks == 1 ? 2 : 1))) append_kernel(const RunParams p) {
+__global__ void __launch_bounds__(kCtaThreads) __attribute__((amdgpu_waves_per_eu(2, 2)))
+append_kernel(const RunParams p) {
   __shared__ __attribute__((aligned(16))) uint16_t lds_k[2][kTileKv * kRowElems];
   __shared__ __attribute__((aligned(16))) uint16_t lds_v[2][kTileKv * kRowElemsV];
 
@@ -136,12 +133,14 @@ __global__ void __launch_bounds__(kCtaThreads)
   const float NEG_INF = -__builtin_inff();
   constexpr int kWaveRows = 32 * kRowBlocks;
 
-  // staging role: this thread moves the 16-byte block `st_chunk` of token slot `st_slot` of each of the 4 pages
-  const int st_slot = tid >> 4;
+  // staging role: in each of the two passes r over a 64-token tile this thread moves the 16-byte block
+  // `st_chunk` of tile token 32 r + st_tok, i.e. slot st_tok % 16 of page 2 r + st_tok / 16 (wave-uniform)
+  const int st_tok = tid >> 4;  // 0..31
   const int st_chunk = tid & 15;
-  const uint32_t st_off = static_cast<uint32_t>(st_slot * p.stride_tok + st_chunk * 8);  // within one (page, head) block
-  const int st_lds_k = st_slot * kRowElems + st_chunk * 8;   // element offsets of this thread's block in a tile
-  const int st_lds_v = st_slot * kRowElemsV + st_chunk * 8;
+  const int st_page = __builtin_amdgcn_readfirstlane(wave >> 2);  // = st_tok / 16
+  const uint32_t st_off = static_cast<uint32_t>((st_tok & 15) * p.stride_tok + st_chunk * 8);  // within one (page, head) block
+  const int st_lds_k = st_tok * kRowElems + st_chunk * 8;   // element offsets of this thread's block in a tile
+  const int st_lds_v = st_tok * kRowElemsV + st_chunk * 8;
   const uint16_t* kpool = static_cast<const uint16_t*>(p.k_pool);
   const uint16_t* vpool = static_cast<const uint16_t*>(p.v_pool);
 
@@ -211,7 +210,9 @@ __global__ void __launch_bounds__(kCtaThreads)
       l_run[b] = 0.f;      // this lane's share of the row sum
     }
 
-    u32x4_t stage_k[4], stage_v[4];
+    // Two staging register sets: set t % 2 carries tile t from its loads to its LDS store, so two
+    // tiles are in flight while a third is being consumed.
+    u32x4_t stage_k[2][2], stage_v[2][2];
     // Page ids are fetched one tile ahead of the data they address (lane r holds page r of the
     // tile), so that the data loads never wait behind an index load.
     auto fetch_page_ids = [&](int t) -> int {
@@ -219,52 +220,48 @@ __global__ void __launch_bounds__(kCtaThreads)
       pi = pi < n_pages ? pi : n_pages - 1;  // never index past the chunk's pages
       return p.kv_indices[kv_page0 + pi];
     };
-    auto fetch_tile = [&](int ids) {
+    auto fetch_tile = [&](auto set_c, int ids) {
+      constexpr int SET = decltype(set_c)::value;
 #pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        const int pg = __builtin_amdgcn_readlane(ids, r);
+      for (int r = 0; r < 2; ++r) {
+        const int pg = __builtin_amdgcn_readlane(ids, 2 * r + st_page);
         const int64_t page_off = pg * p.stride_page + kvh * p.stride_head;  // wave-uniform
-        stage_k[r] = *reinterpret_cast<const u32x4_t*>(kpool + page_off + st_off);
-        stage_v[r] = *reinterpret_cast<const u32x4_t*>(vpool + page_off + st_off);
+        stage_k[SET][r] = *reinterpret_cast<const u32x4_t*>(kpool + page_off + st_off);
+        stage_v[SET][r] = *reinterpret_cast<const u32x4_t*>(vpool + page_off + st_off);
       }
     };
-    auto store_tile = [&](int t) {
+    auto store_tile = [&](auto set_c, int t) {
+      constexpr int SET = decltype(set_c)::value;
       uint16_t* dk = lds_k[t & 1];
       uint16_t* dv = lds_v[t & 1];
       if constexpr (BF) {
 #pragma unroll
-        for (int r = 0; r < 4; ++r)
-          stage_v[r] = u32x4_t{bf16x2_to_f16x2(stage_v[r][0]), bf16x2_to_f16x2(stage_v[r][1]),
-                               bf16x2_to_f16x2(stage_v[r][2]), bf16x2_to_f16x2(stage_v[r][3])};
+        for (int r = 0; r < 2; ++r)
+          stage_v[SET][r] = u32x4_t{bf16x2_to_f16x2(stage_v[SET][r][0]), bf16x2_to_f16x2(stage_v[SET][r][1]),
+                                    bf16x2_to_f16x2(stage_v[SET][r][2]), bf16x2_to_f16x2(stage_v[SET][r][3])};
       }
       if (kTileKv * (t + 1) > kv_len) {  // CTA-uniform: only the chunk's last tile has rows past its end
 #pragma unroll
-        for (int r = 0; r < 4; ++r)
-          if (kTileKv * t + 16 * r + st_slot >= kv_len) stage_v[r] = u32x4_t{0u, 0u, 0u, 0u};  // must not reach P.V
+        for (int r = 0; r < 2; ++r)
+          if (kTileKv * t + 32 * r + st_tok >= kv_len) stage_v[SET][r] = u32x4_t{0u, 0u, 0u, 0u};  // must not reach P.V
       }
 #pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        *reinterpret_cast<u32x4_t*>(&dk[st_lds_k + 16 * r * kRowElems]) = stage_k[r];
-        *reinterpret_cast<u32x4_t*>(&dv[st_lds_v + 16 * r * kRowElemsV]) = stage_v[r];
+      for (int r = 0; r < 2; ++r) {
+        *reinterpret_cast<u32x4_t*>(&dk[st_lds_k + 32 * r * kRowElems]) = stage_k[SET][r];
+        *reinterpret_cast<u32x4_t*>(&dv[st_lds_v + 32 * r * kRowElemsV]) = stage_v[SET][r];
       }
     };
+    using set0_t = std::integral_constant<int, 0>;
+    using set1_t = std::integral_constant<int, 1>;
 
-    // Pipeline: while tile t is consumed from LDS buffer t % 2, tile t + 1 sits in the staging
-    // registers (its loads were issued a whole tile earlier) and is written to buffer
-    // (t + 1) % 2 after the products of tile t have been issued; one barrier per tile.
-    int ids_next = 0;
-    __syncthreads();  // the previous work item's last tile is no longer being read
-    if (n_tiles > 0) {
-      fetch_tile(fetch_page_ids(0));
-      if (n_tiles > 1) ids_next = fetch_page_ids(1);
-      store_tile(0);
-      if (n_tiles > 1) {
-        fetch_tile(ids_next);
-        if (n_tiles > 2) ids_next = fetch_page_ids(2);
-      }
-    }
-    __syncthreads();
-    for (int t = 0; t < n_tiles; ++t) {
+    // Pipeline: while tile t is consumed from LDS buffer t % 2, tiles t + 1 and t + 2 are in the
+    // staging registers (loads issued two tiles ahead); after the products of tile t have been
+    // issued tile t + 1 is written to buffer (t + 1) % 2, its register set is reloaded with tile
+    // t + 3, and one CTA barrier closes the tile.
+    __syncthreads();   // the previous work item's last tile is no longer being read
+    // One tile: consume tile t, then hand tile t + 1 over from staging set SET = (t + 1) % 2.  The
+    // tile loop below is unrolled by two so that SET is a compile-time constant.
+    auto do_tile = [&](auto set_c, int t, int& ids_load, const int& ids_use) {
       const uint16_t* tk = lds_k[t & 1];
       const uint16_t* tv = lds_v[t & 1];
 #pragma unroll
@@ -376,15 +373,31 @@ __global__ void __launch_bounds__(kCtaThreads)
           }
         }
       }
-      // hand the next tile over and request the one after it
-      if (t + 1 < n_tiles) {
-        store_tile(t + 1);
-        if (t + 2 < n_tiles) {
-          fetch_tile(ids_next);
-          if (t + 3 < n_tiles) ids_next = fetch_page_ids(t + 3);
-        }
-      }
+      // Hand the next tile over and reload its register set with the tile three ahead.  Every
+      // iteration issues the same loads in the same order (tiles past the end re-read the last
+      // page and are never stored), so the counted waits for the oldest loads leave the younger
+      // ones in flight; the index load goes first so that its consumer, one iteration later,
+      // does not wait for the data loads issued after it.
+      ids_load = fetch_page_ids(t + 4);
+      if (t + 1 < n_tiles) store_tile(set_c, t + 1);
+      fetch_tile(set_c, ids_use);
       __syncthreads();  // tile t + 1 is visible; nobody reads tile t any more
+    };
+    if (n_tiles > 0) {  // one region, so that the loop is entered with this work item's Q loads known complete
+      const int ids0 = fetch_page_ids(0), ids1 = fetch_page_ids(1);
+      int ids_even = fetch_page_ids(2), ids_odd = fetch_page_ids(3);  // ids of the next even / odd tile to request
+      fetch_tile(set0_t{}, ids0);
+      fetch_tile(set1_t{}, ids1);
+      store_tile(set0_t{}, 0);
+      fetch_tile(set0_t{}, ids_even);
+      __syncthreads();
+      // A single-exit loop: with an odd tile count the last call finds no visible step and stores
+      // nothing, which is cheaper than a second exit that would make every counted wait assume
+      // the emptiest pipeline.
+      for (int t = 0; t < n_tiles; t += 2) {
+        do_tile(set1_t{}, t, ids_even, ids_odd);
+        do_tile(set0_t{}, t + 1, ids_odd, ids_even);
+      }
     }
 
     // ---- epilogue: o = O / l, lse = ln(sum exp) (Sec. 2.2) ----
@@ -429,7 +442,7 @@ __global__ void __launch_bounds__(kCtaThreads)
 
 }  // namespace
 
-int append_tile_rows() { return 4 * 32 * kRowBlocks; }
+int append_tile_rows() { return (kCtaThreads / 64) * 32 * kRowBlocks; }
 
 hipError_t launch_append(const RunParams& p, bool is_bf16, hipStream_t stream) {
   const dim3 grid(static_cast<unsigned>(p.ctas_per_head), static_cast<unsigned>(p.num_kv_heads), 1);

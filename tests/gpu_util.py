@@ -34,7 +34,7 @@ class DeviceBatch:
 
 def make_wrapper(batch, mode, **kw):
     import paper_2501_01005_amd as fi
-    t_pos = 1 if mode == "decode" else 128 // (batch.num_qo_heads // batch.num_kv_heads)
+    t_pos = 1 if mode == "decode" else 256 // (batch.num_qo_heads // batch.num_kv_heads)
     tiles = int(sum(-(-int(l) // t_pos) for l in batch.qo_lens()))
     return fi.PagedAttention(dtype=batch.dtype, num_qo_heads=batch.num_qo_heads, num_kv_heads=batch.num_kv_heads,
                              head_dim=batch.head_dim, page_size=batch.page_size, mode=mode,

@@ -79,7 +79,7 @@ def test_plan_for_append_equals_replica_with_default_grid():
     w = make_wrapper(b, "append")
     w.plan(b.qo_indptr, b.kv_indptr, b.last_page_len, causal=True)
     got = fi.fi_plan_view(w.handle)
-    want = plan_replica(b.qo_indptr, b.kv_indptr, b.last_page_len, page_size=16, t_pos=32, group=4,
+    want = plan_replica(b.qo_indptr, b.kv_indptr, b.last_page_len, page_size=16, t_pos=64, group=4,
                         num_ctas=got["ctas_per_head"], causal=True, min_chunk=256)
     for k in ("cta_indptr", "w_q_row0", "w_n_pos", "w_kv_page0", "w_kv_start", "w_kv_len", "w_diag0", "w_out_slot"):
         assert got[k].tobytes() == np.asarray(want[k], dtype=np.int32).tobytes(), k

@@ -61,7 +61,7 @@ def test_planner_equals_replica_on_random_length_sets(mode):
     for g in (1, 4):
         for C in (1, 5, 32, 256):
             for (alpha, beta, min_chunk) in ((1, 1, 16), (0, 1, 256), (3, 2, 64)):
-                t_pos = 1 if mode == "decode" else 128 // g
+                t_pos = 1 if mode == "decode" else 256 // g
                 h = make(fi.FI_MODE_DECODE if mode == "decode" else fi.FI_MODE_APPEND, g, C, alpha=alpha, beta=beta,
                          min_chunk=min_chunk)
                 for trial in range(25):
@@ -98,10 +98,10 @@ def test_planner_equals_replica_on_the_benchmark_length_sets():
     g3 = np.random.Generator(np.random.PCG64(1003))
     qo = g3.integers(128, 1025, size=16); pre = g3.integers(0, 4097, size=16)
     h = make(fi.FI_MODE_APPEND, 4, 64, Hkv=8, max_batch=16, max_tiles=1024, min_chunk=256)
-    compare(h, qo, qo + pre, True, 32, 4, 64, 1, 1, 256)
+    compare(h, qo, qo + pre, True, 64, 4, 64, 1, 1, 256)
     fi.fi_destroy(h)
     h = make(fi.FI_MODE_APPEND, 4, 64, Hkv=8, max_batch=16, max_tiles=1024, min_chunk=256, literal_lkv=1)
-    compare(h, qo, qo + pre, True, 32, 4, 64, 1, 1, 256, literal=True)
+    compare(h, qo, qo + pre, True, 64, 4, 64, 1, 1, 256, literal=True)
     fi.fi_destroy(h)
 
 
