@@ -39,6 +39,10 @@ constexpr int kRowElems = 136;     // K tile row pitch in 16-bit elements (272 B
 constexpr int kRowElemsV = 144;    // V tile row pitch (288 B): rows 8 banks apart, conflict-free transpose reads
 constexpr int kCtaThreads = 512;   // 8 wavefronts, 32 query rows each
 constexpr int kRowBlocks = 1;       // 32-row blocks per wavefront; CTA tile = 8 * 32 * kRowBlocks fused rows
+constexpr int kLoopBuffers = 3;                                 // LDS tile buffers of the scheduled loop
+constexpr int kLdsVOffset = kLoopBuffers * kTileKv * kRowElems * 2;
+constexpr int kLdsBytes = kLdsVOffset + kLoopBuffers * kTileKv * kRowElemsV * 2;
+constexpr int kLoopMinTokens = 2 * kTileKv;                     // shorter chunks: generic path only (its start-up is cheaper)
 constexpr int kLazyLog2 = 8;                                    // P may reach 2^8 before the reference is raised
 constexpr uint16_t kLazyF16Bits = (15 + kLazyLog2) << 10;       // fp16 bit pattern of 2^kLazyLog2
 
@@ -114,11 +118,67 @@ __device__ __forceinline__ float halves_sum(float x) {
   return a + b;
 }
 
+#ifndef FI355_APPEND_SCHEDULED_LOOP
+#define FI355_APPEND_SCHEDULED_LOOP 1
+#endif
+constexpr bool kUseScheduledLoop = FI355_APPEND_SCHEDULED_LOOP != 0 && kRowBlocks == 1 && kCtaThreads == 512;
+
+__device__ __forceinline__ uint32_t lds_offset(const void* p) {
+  return static_cast<uint32_t>(reinterpret_cast<uintptr_t>(
+      (__attribute__((address_space(3))) const uint8_t*)(static_cast<const uint8_t*>(p))));
+}
+
+// The hand-scheduled loop over the `n_tiles` KV tiles of a chunk of `kv_len` tokens, of which the
+// first `n_full` >= 1 need no masking (gen/gen_append_loop.py writes it and documents its
+// register map and schedule).  `cap` = chunk-local index of the last token this lane's row sees,
+// minus 4 * (lane / 32).  Starts from the empty attention state, reads Q through `q_addr`,
+// gathers pages through `page_ids` (the chunk's ids; `ids_clamp` = byte offset of the chunk's
+// last one) and finishes the work item: this lane's 64 values of o go to o_base + o_off bytes
+// (o_off = 512 * output row + 16 * (lane / 32)) if row_flags & 1, lse to lse_base[output row] if
+// row_flags & 2, and, if has_cast, o in the input type to cast_base + o_off / 2.  Every
+// wavefront of the CTA must call it with the same tile counts (it contains CTA barriers).
+template <bool BF>
+__device__ __forceinline__ void run_scheduled_loop(int n_full, int n_tiles, int kv_len, int cap, int st_tok, int ids_clamp, const int32_t* page_ids, uint32_t k_lo,
+                                                   uint32_t k_hi, uint32_t v_lo, uint32_t v_hi, uint32_t page_bytes,
+                                                   float scale_log2, int st_page, uint64_t q_addr, uint32_t st_off_bytes,
+                                                   uint32_t k_read, uint32_t v_read, uint32_t k_write, uint32_t v_write,
+                                                   uint32_t o_off, int row_flags, float* o_base, float* lse_base,
+                                                   void* cast_base, int has_cast) {
+  if constexpr (BF) {
+    asm volatile(
+#include "append_loop_bf16.inc"
+        :
+        : [nf] "s"(n_full), [nt] "s"(n_tiles), [kvl] "s"(kv_len), [cap] "v"(cap), [stk] "v"(st_tok), [npg1] "s"(ids_clamp), [idp] "s"(page_ids), [kblo] "s"(k_lo), [kbhi] "s"(k_hi),
+          [vblo] "s"(v_lo), [vbhi] "s"(v_hi), [sp] "s"(page_bytes), [sc] "s"(scale_log2), [stp] "s"(st_page),
+          [qp] "v"(q_addr), [so] "v"(st_off_bytes), [ka] "v"(k_read), [va] "v"(v_read), [wk] "v"(k_write),
+          [wv] "v"(v_write), [ooff] "v"(o_off), [rok] "v"(row_flags), [ob] "s"(o_base), [lb] "s"(lse_base),
+          [cb] "s"(cast_base), [oc] "s"(has_cast)
+        :
+#include "append_loop_clobbers.inc"
+    );
+  } else {
+    asm volatile(
+#include "append_loop_f16.inc"
+        :
+        : [nf] "s"(n_full), [nt] "s"(n_tiles), [kvl] "s"(kv_len), [cap] "v"(cap), [stk] "v"(st_tok), [npg1] "s"(ids_clamp), [idp] "s"(page_ids), [kblo] "s"(k_lo), [kbhi] "s"(k_hi),
+          [vblo] "s"(v_lo), [vbhi] "s"(v_hi), [sp] "s"(page_bytes), [sc] "s"(scale_log2), [stp] "s"(st_page),
+          [qp] "v"(q_addr), [so] "v"(st_off_bytes), [ka] "v"(k_read), [va] "v"(v_read), [wk] "v"(k_write),
+          [wv] "v"(v_write), [ooff] "v"(o_off), [rok] "v"(row_flags), [ob] "s"(o_base), [lb] "s"(lse_base),
+          [cb] "s"(cast_base), [oc] "s"(has_cast)
+        :
+#include "append_loop_clobbers.inc"
+    );
+  }
+}
+
 template <bool BF>
 __global__ void __launch_bounds__(kCtaThreads) __attribute__((amdgpu_waves_per_eu(2, 2)))
 append_kernel(const RunParams p) {
-  __shared__ __attribute__((aligned(16))) uint16_t lds_k[2][kTileKv * kRowElems];
-  __shared__ __attribute__((aligned(16))) uint16_t lds_v[2][kTileKv * kRowElemsV];
+  // K tiles, then V tiles (three buffers each: the scheduled loop rotates over three, the generic
+  // path over the first two).
+  __shared__ __attribute__((aligned(16))) uint8_t lds_raw[kLdsBytes];
+  uint16_t* const lds_k = reinterpret_cast<uint16_t*>(lds_raw);
+  uint16_t* const lds_v = reinterpret_cast<uint16_t*>(lds_raw + kLdsVOffset);
 
   const int tid = threadIdx.x;
   const int wave = tid >> 6;
@@ -160,9 +220,52 @@ append_kernel(const RunParams p) {
     const int kv_len = __builtin_amdgcn_readfirstlane(p.w_kv_len[w]);
     const int diag0 = __builtin_amdgcn_readfirstlane(p.w_diag0[w]);
     const int out_slot = __builtin_amdgcn_readfirstlane(p.w_out_slot[w]);
+    const bool causal = diag0 != kNoDiagMarker;
+
+    // ---- work items whose first tile every row of the CTA sees in full: the scheduled loop ----
+    if constexpr (kUseScheduledLoop) {
+      int vis = kv_len;  // tokens visible to the CTA's first position, which sees the fewest
+      if (causal) vis = min(vis, max(0, diag0 - kv_start + 1));
+      const int n_full = __builtin_amdgcn_readfirstlane(vis / kTileKv);
+      const int64_t page_bytes = p.stride_page * 2;
+      // (the loop addresses its outputs with 32-bit byte offsets)
+      const int64_t out_rows_bound = (out_slot < 0 ? static_cast<int64_t>(q_row0) + p.t_pos : (static_cast<int64_t>(out_slot) + 1) * p.t_pos) * H;
+      if (n_full >= 1 && kv_len >= kLoopMinTokens && page_bytes > 0 && page_bytes < (int64_t(1) << 32) &&
+          out_rows_bound * (kHeadDim * 4) < (int64_t(1) << 32)) {
+        const int R = 32 * wave + n;
+        const int pos_r = R >> g_log2;
+        const int pos_c = min(pos_r, n_pos - 1);  // rows past the tile's end compute on a valid row; never stored
+        const uint64_t q_addr = reinterpret_cast<uint64_t>(static_cast<const uint16_t*>(p.q) +
+                                (static_cast<int64_t>(q_row0 + pos_c) * H + kvh * g + (R & (g - 1))) * kHeadDim + c * 8);
+        const uint64_t k_base = reinterpret_cast<uint64_t>(kpool + kvh * p.stride_head);
+        const uint64_t v_base = reinterpret_cast<uint64_t>(vpool + kvh * p.stride_head);
+        const uint32_t lds0 = lds_offset(lds_raw);
+        const int chunk_pages = (kv_len + kPageSize - 1) / kPageSize;
+        const int last_seen = causal ? min(diag0 + pos_r - kv_start, kv_len - 1) : kv_len - 1;
+        // where the rows go: the final output (write-through, App. D.2) or this item's partial slot
+        const bool final_out = out_slot < 0;
+        const int64_t out_row = final_out ? static_cast<int64_t>(q_row0 + pos_r) * H + kvh * g + (R & (g - 1))
+                                          : (static_cast<int64_t>(out_slot) * p.t_pos + pos_r) * H + kvh * g + (R & (g - 1));
+        const bool row_live = pos_r < n_pos;
+        __syncthreads();  // the previous work item is done with the tile buffers
+        run_scheduled_loop<BF>(n_full, (kv_len + kTileKv - 1) / kTileKv, kv_len, last_seen - 4 * c, st_tok,
+                               (chunk_pages - 1) * 4, p.kv_indices + kv_page0, static_cast<uint32_t>(k_base),
+                               static_cast<uint32_t>(k_base >> 32), static_cast<uint32_t>(v_base),
+                               static_cast<uint32_t>(v_base >> 32), static_cast<uint32_t>(page_bytes), p.scale_log2,
+                               __builtin_amdgcn_readfirstlane(wave >> 2), q_addr, st_off * 2,
+                               lds0 + n * (kRowElems * 2) + c * 16,
+                               lds0 + kLdsVOffset + (4 * c + tr_row) * (kRowElemsV * 2) + tr_col * 2,
+                               lds0 + st_tok * (kRowElems * 2) + st_chunk * 16,
+                               lds0 + kLdsVOffset + st_tok * (kRowElemsV * 2) + st_chunk * 16,
+                               static_cast<uint32_t>(out_row * (kHeadDim * 4) + c * 16),
+                               row_live ? (c == 0 ? 3 : 1) : 0, final_out ? p.o : p.part_o,
+                               final_out ? p.lse : p.part_lse, p.o_cast,
+                               __builtin_amdgcn_readfirstlane(final_out && p.o_cast != nullptr ? 1 : 0));
+        continue;  // the work item is finished
+      }
+    }
     const int n_pages = (kv_len + kPageSize - 1) / kPageSize;
     const int n_tiles = (kv_len + kTileKv - 1) / kTileKv;
-    const bool causal = diag0 != kNoDiagMarker;
 
     // ---- this lane's query rows, one per 32-row block ----
     int pos[kRowBlocks], hh[kRowBlocks], lim[kRowBlocks];
@@ -232,8 +335,8 @@ append_kernel(const RunParams p) {
     };
     auto store_tile = [&](auto set_c, int t) {
       constexpr int SET = decltype(set_c)::value;
-      uint16_t* dk = lds_k[t & 1];
-      uint16_t* dv = lds_v[t & 1];
+      uint16_t* dk = lds_k + (t & 1) * (kTileKv * kRowElems);
+      uint16_t* dv = lds_v + (t & 1) * (kTileKv * kRowElemsV);
       if constexpr (BF) {
 #pragma unroll
         for (int r = 0; r < 2; ++r)
@@ -262,8 +365,8 @@ append_kernel(const RunParams p) {
     // One tile: consume tile t, then hand tile t + 1 over from staging set SET = (t + 1) % 2.  The
     // tile loop below is unrolled by two so that SET is a compile-time constant.
     auto do_tile = [&](auto set_c, int t, int& ids_load, const int& ids_use) {
-      const uint16_t* tk = lds_k[t & 1];
-      const uint16_t* tv = lds_v[t & 1];
+      const uint16_t* tk = lds_k + (t & 1) * (kTileKv * kRowElems);
+      const uint16_t* tv = lds_v + (t & 1) * (kTileKv * kRowElemsV);
 #pragma unroll
       for (int u = 0; u < 2; ++u) {
         const int tok_base = kTileKv * t + 32 * u;  // chunk-local index of this 32-token step

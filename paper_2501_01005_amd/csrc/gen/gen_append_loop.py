@@ -1,0 +1,394 @@
+#!/usr/bin/env python3
+"""Writes append_loop_{bf16,f16}.inc: the hand-scheduled steady-state loop of the append kernel.
+
+The loop covers all KV tiles of a work item whose first tile every row of the CTA sees in full:
+first the tiles that need no masking, then, with a compare-and-select on the logits in front of
+the softmax, the tiles that the causal diagonal or the end of the chunk cuts.  The C++ kernel
+around it does the epilogue (and whole work items that do not qualify).  One wavefront owns 32
+query rows; per 32-token step it issues
+
+    block 1:  S^T(next step) = K . Q^T   (8 MFMA)   ||  softmax of the current step, V^T reads
+    block 2:  O^T += V^T . P^T           (8 MFMA)   ||  row sum, K reads two steps ahead, staging
+
+so that inside a wavefront every matrix instruction is followed by a share of the vector and
+LDS work of a neighbouring step (a wavefront issues in order: a run of dependent matrix
+instructions would otherwise keep its own vector work waiting, and the other way round).  The
+KV tiles are triple-buffered in LDS so that the next tile's K can be read before the CTA
+barrier that publishes the tile after it.
+
+All working registers are fixed (see the map below) and listed as clobbers; the C++ side
+passes only addresses and scalars in, and the loop ends with the epilogue: it writes o, lse
+and the optional cast of o itself.
+
+Run this script after changing it; the .inc files it writes are committed with it.
+"""
+import os
+import sys
+
+sys.path.insert(0, os.path.dirname(os.path.abspath(__file__)))
+from emit import Emitter  # noqa: E402
+
+# ---- fixed vector registers (the compiler keeps v0..v15) ----
+NINF = 16
+NEGMS, MRUN, LSUM, ONES, MAXT, X0, X1 = 17, 18, 19, 20, 21, 22, 23
+ACC, Q, KA, VT, S0, S1, H, T, ST = 24, 88, 120, 152, 184, 200, 216, 224, 240
+FIRST_FIXED_VGPR = 16
+# ---- fixed scalar registers ----
+S_T, S_TMP = 64, 65
+S_OFFS = (66, 67, 86, 87)
+S_IDS, S_IDN = 68, 72          # page ids of the tile to fetch next / of the one after it
+S_PG0, S_PG1, S_LO, S_HI, S_KA, S_VA, S_THR, S_REM = 76, 77, 78, 79, 80, 82, 84, 85
+S_IDA, S_IDB = 88, 92          # two more page id groups, start-up only
+S_EXEC = 96
+FIXED_SGPRS = list(range(64, 98))
+
+KROW, VROW = 272, 288          # LDS row pitch in bytes (K, V)
+KTILE, VTILE = 64 * KROW, 64 * VROW
+NBUF = 3
+LAZY_THR = 0x5C005C00          # fp16 2^8 in both halves: P above it raises the reference
+
+
+def vr(base, n=1):
+    return 'v%d' % base if n == 1 else 'v[%d:%d]' % (base, base + n - 1)
+
+
+def spread(e, mfmas, others):
+    """each matrix instruction is followed by an even share of the other instructions"""
+    n = len(mfmas)
+    k = 0
+    for i, m in enumerate(mfmas):
+        e.emit(m)
+        hi = (len(others) * (i + 1)) // n
+        for o in others[k:hi]:
+            e.emit(o)
+        k = hi
+
+
+def merge_even(*lists):
+    total = sum(len(l) for l in lists)
+    out = []
+    idx = [0] * len(lists)
+    for _ in range(total):
+        best = max(range(len(lists)),
+                   key=lambda i: (len(lists[i]) - idx[i]) / max(len(lists[i]), 1) if idx[i] < len(lists[i]) else -1)
+        out.append(lists[best][idx[best]])
+        idx[best] += 1
+    return out
+
+
+class Gen:
+    def __init__(self, bf16):
+        self.bf = bf16
+        self.e = Emitter()
+
+    # ---- building blocks ----
+    def qk(self, Sn, s):
+        op = 'v_mfma_f32_32x32x16_bf16' if self.bf else 'v_mfma_f32_32x32x16_f16'
+        c = '0' if s == 0 else vr(Sn, 16)
+        return '%s %s, %s, %s, %s' % (op, vr(Sn, 16), vr(KA + 4 * s, 4), vr(Q + 4 * s, 4), c)
+
+    def pv(self, db, j):
+        a = ACC + 16 * db
+        return 'v_mfma_f32_32x32x16_f16 %s, %s, %s, %s' % (vr(a, 16), vr(VT + 8 * db + 4 * j, 4), vr(H + 4 * j, 4), vr(a, 16))
+
+    def exps(self, Sc):
+        ops = []
+        for j in range(8):
+            a, b = T + 2 * j, T + 2 * j + 1
+            ops += ['v_fma_f32 v%d, v%d, %%[sc], v%d' % (a, Sc + 2 * j, NEGMS),
+                    'v_fma_f32 v%d, v%d, %%[sc], v%d' % (b, Sc + 2 * j + 1, NEGMS),
+                    'v_exp_f32 v%d, v%d' % (a, a), 'v_exp_f32 v%d, v%d' % (b, b)]
+        for j in range(8):
+            ops.append('v_cvt_pk_f16_f32 v%d, v%d, v%d' % (H + j, T + 2 * j, T + 2 * j + 1))
+        return ops
+
+    def mask(self, Sc, u):
+        """logits of tokens past this lane's last visible one become -inf: register r holds token
+        32 s + 4 c + 8 (r / 4) + r % 4 of the step, and cap = last visible token - 4 c"""
+        ops = ['s_lshl_b32 s%d, s%d, 6' % (S_TMP, S_T)]
+        if u:
+            ops.append('s_add_u32 s%d, s%d, 32' % (S_TMP, S_TMP))
+        ops.append('v_subrev_u32 v%d, s%d, %%[cap]' % (X1, S_TMP))
+        for r in range(16):
+            ops.append('v_cmp_le_i32 vcc, %d, v%d' % (8 * (r // 4) + r % 4, X1))
+            ops.append('v_cndmask_b32 v%d, v%d, v%d, vcc' % (Sc + r, NINF, Sc + r))
+        return ops
+
+    def lazy_check(self):
+        # P >= 0, so fp16 order is unsigned order on the bit patterns; any half above 2^8 -> vcc != 0
+        ops = ['v_pk_max_u16 v%d, v%d, v%d' % (MAXT, H, H + 1)]
+        for j in range(2, 8):
+            ops.append('v_pk_max_u16 v%d, v%d, v%d' % (MAXT, MAXT, H + j))
+        ops.append('v_pk_min_u16 v%d, v%d, s%d' % (X0, MAXT, S_THR))
+        ops.append('v_cmp_ne_u32 vcc, v%d, v%d' % (X0, MAXT))
+        return ops
+
+    def rowsum(self):
+        return ['v_dot2_f32_f16 v%d, v%d, v%d, v%d' % (LSUM, H + j, ONES, LSUM) for j in range(8)]
+
+    def k_reads(self, buf, u):
+        return ['ds_read_b128 %s, %%[ka] offset:%d' % (vr(KA + 4 * s, 4), buf * KTILE + u * 32 * KROW + 32 * s)
+                for s in range(8)]
+
+    def v_reads(self, buf, u):
+        ops = []
+        for db in range(4):
+            for j in range(2):
+                r = VT + 8 * db + 4 * j
+                base = buf * VTILE + u * 32 * VROW + 64 * db
+                ops.append('ds_read_b64_tr_b16 %s, %%[va] offset:%d' % (vr(r, 2), base + (16 * j) * VROW))
+                ops.append('ds_read_b64_tr_b16 %s, %%[va] offset:%d' % (vr(r + 2, 2), base + (16 * j + 8) * VROW))
+        return ops
+
+    def v_convert(self, base=ST):
+        if not self.bf:
+            return []
+        ops = []
+        for x in range(base + 8, base + 16):  # bf16 pairs -> fp16 pairs, toward zero
+            ops += ['v_lshlrev_b32 v%d, 16, v%d' % (X0, x), 'v_and_b32 v%d, 0xffff0000, v%d' % (X1, x),
+                    'v_cvt_pkrtz_f16_f32 v%d, v%d, v%d' % (x, X0, X1)]
+        return ops
+
+    def stores(self, buf, base=ST):
+        ops = []
+        for r in range(2):
+            ops.append('ds_write_b128 %%[wk], %s offset:%d' % (vr(base + 4 * r, 4), buf * KTILE + r * 32 * KROW))
+            ops.append('ds_write_b128 %%[wv], %s offset:%d' % (vr(base + 8 + 4 * r, 4), buf * VTILE + r * 32 * VROW))
+        return ops
+
+    def v_zero_tail(self, ahead, base=ST):
+        """V rows of tile t + ahead at or past the end of the chunk must not reach P.V (their
+        logits are masked, but 0 x garbage need not be 0): this thread's rows are 32 r + st_tok"""
+        ops = ['s_add_u32 s%d, s%d, %d' % (S_TMP, S_T, ahead), 's_lshl_b32 s%d, s%d, 6' % (S_TMP, S_TMP),
+               's_sub_i32 s%d, %%[kvl], s%d' % (S_REM, S_TMP)]  # rows of that tile inside the chunk (may be <= 0 or > 64)
+        for r in range(2):
+            if r:
+                ops.append('s_sub_i32 s%d, s%d, 32' % (S_REM, S_REM))
+            ops.append('v_cmp_gt_i32 vcc, s%d, %%[stk]' % S_REM)
+            for x in range(base + 8 + 4 * r, base + 12 + 4 * r):
+                ops.append('v_cndmask_b32 v%d, 0, v%d, vcc' % (x, x))
+        return ops
+
+    def fetch(self, ids=S_IDS, base=ST):
+        """global loads of the tile whose four page ids are in s[ids..+3]; this thread's two
+        pages are 2 r + st_page, r = 0, 1"""
+        ops = ['s_cmp_eq_u32 %[stp], 0',
+               's_cselect_b32 s%d, s%d, s%d' % (S_PG0, ids, ids + 1),
+               's_cselect_b32 s%d, s%d, s%d' % (S_PG1, ids + 2, ids + 3)]
+        for r, pg in enumerate((S_PG0, S_PG1)):
+            ops += ['s_mul_hi_u32 s%d, s%d, %%[sp]' % (S_HI, pg), 's_mul_i32 s%d, s%d, %%[sp]' % (S_LO, pg),
+                    's_add_u32 s%d, %%[kblo], s%d' % (S_KA, S_LO), 's_addc_u32 s%d, %%[kbhi], s%d' % (S_KA + 1, S_HI),
+                    's_add_u32 s%d, %%[vblo], s%d' % (S_VA, S_LO), 's_addc_u32 s%d, %%[vbhi], s%d' % (S_VA + 1, S_HI),
+                    'global_load_dwordx4 %s, %%[so], s[%d:%d]' % (vr(base + 4 * r, 4), S_KA, S_KA + 1),
+                    'global_load_dwordx4 %s, %%[so], s[%d:%d]' % (vr(base + 8 + 4 * r, 4), S_VA, S_VA + 1)]
+        return ops
+
+    def ids_load(self, ahead, dst=S_IDN):
+        """request the page ids of tile t + ahead; each of the four is clamped to the chunk's last
+        page, so a partial last tile still gets its own pages and nothing past the chunk is read"""
+        ops = []
+        if ahead:
+            ops.append('s_add_u32 s%d, s%d, %d' % (S_TMP, S_T, ahead))
+            ops.append('s_lshl_b32 s%d, s%d, 4' % (S_TMP, S_TMP))
+        else:
+            ops.append('s_lshl_b32 s%d, s%d, 4' % (S_TMP, S_T))
+        for r, off in enumerate(S_OFFS):
+            if r:
+                ops.append('s_add_u32 s%d, s%d, %d' % (off, S_TMP, 4 * r))
+                ops.append('s_min_u32 s%d, s%d, %%[npg1]' % (off, off))
+            else:
+                ops.append('s_min_u32 s%d, s%d, %%[npg1]' % (off, S_TMP))
+            ops.append('s_load_dword s%d, %%[idp], s%d' % (dst + r, off))
+        return ops
+
+    def ids_take(self):
+        return ['s_mov_b64 s[%d:%d], s[%d:%d]' % (S_IDS, S_IDS + 1, S_IDN, S_IDN + 1),
+                's_mov_b64 s[%d:%d], s[%d:%d]' % (S_IDS + 2, S_IDS + 3, S_IDN + 2, S_IDN + 3)]
+
+    def row_max(self, Sc):
+        """X0 <- max(MRUN, maximum of the 32 logits of this lane's row)"""
+        ops = ['v_max3_f32 v%d, v%d, v%d, v%d' % (X0, Sc, Sc + 1, Sc + 2)]
+        for i in range(3, 15, 2):
+            ops.append('v_max3_f32 v%d, v%d, v%d, v%d' % (X0, X0, Sc + i, Sc + i + 1))
+        ops.append('v_max_f32 v%d, v%d, v%d' % (X0, X0, Sc + 15))
+        # the other half of the wavefront holds the row's other 16 tokens
+        ops += ["v_mov_b32 v%d, v%d" % (X1, X0), "s_nop 1", "v_permlane32_swap_b32 v%d, v%d" % (X0, X1), "s_nop 1",
+                'v_max3_f32 v%d, v%d, v%d, v%d' % (X0, X0, X1, MRUN)]
+        return ops
+
+    def set_reference(self):
+        return ['v_mov_b32 v%d, v%d' % (MRUN, X0), 'v_mul_f32 v%d, v%d, %%[sc]' % (NEGMS, X0),
+                'v_xor_b32 v%d, 0x80000000, v%d' % (NEGMS, NEGMS)]
+
+    def raise_reference(self, Sc):
+        """out-of-line: raise the reference to the row maximum, rescale the state, redo P"""
+        ops = self.row_max(Sc)
+        ops += ['v_sub_f32 v%d, v%d, v%d' % (X1, MRUN, X0), 'v_mul_f32 v%d, v%d, %%[sc]' % (X1, X1),
+                'v_exp_f32 v%d, v%d' % (X1, X1)]
+        ops += self.set_reference()
+        ops.append('v_mul_f32 v%d, v%d, v%d' % (LSUM, LSUM, X1))
+        for i in range(64):
+            ops.append('v_mul_f32 v%d, v%d, v%d' % (ACC + i, ACC + i, X1))
+        ops += self.exps(Sc)
+        ops.append('s_nop 4')  # vector writes of the accumulators settle before the next matrix instruction reads them
+        return ops
+
+    # ---- program ----
+    def tile(self, k, lbl, masked):
+        e = self.e
+        cur, nxt, wr = k % NBUF, (k + 1) % NBUF, (k + 2) % NBUF
+        kind = 'm' if masked else 'p'
+        e.label('tile_%s%d_%s' % (kind, k, lbl))
+        # canonical state after the barrier: no LDS operation in flight, the four loads of the
+        # staged tile (K0, V0, K1, V1) possibly still in flight
+        e.lgkm = []
+        e.vm = [set(('v', ST + 4 * r + i) for i in range(4)) for r in (0, 2, 1, 3)]
+        for u in range(2):
+            Sc, Sn = (S0, S1) if u == 0 else (S1, S0)
+            # block 1
+            head = self.ids_load(4) if u == 0 else []  # consumed after the barrier: long there by then
+            soft = (self.mask(Sc, u) if masked else []) + self.exps(Sc) + self.lazy_check()
+            spread(e, [self.qk(Sn, s) for s in range(8)], head + merge_even(self.v_reads(cur, u), soft))
+            e.raw('s_cbranch_vccnz raise_%s%d%d_%s' % (kind, k, u, lbl))
+            e.label('back_%s%d%d_%s' % (kind, k, u, lbl))
+            # block 2
+            kn = self.k_reads(nxt, u)
+            if u == 0:
+                rest = merge_even(kn, self.rowsum() + self.v_convert())
+            else:
+                rest = merge_even(kn, self.rowsum() + self.v_zero_tail(2)) + self.stores(wr) + self.fetch()
+            spread(e, [self.pv(db, j) for j in range(2) for db in range(4)], rest)
+        e.emit('s_barrier')
+        for o in self.ids_take():
+            e.raw(o)
+        e.raw('s_add_u32 s%d, s%d, 1' % (S_T, S_T))
+        e.raw('s_cmp_ge_u32 s%d, %%[nt]' % S_T)
+        e.raw('s_cbranch_scc1 exit_%s' % lbl)
+        kn = (k + 1) % NBUF
+        if masked:
+            e.raw('s_branch tile_m%d_%s' % (kn, lbl)) if kn == 0 else None  # masked tiles follow each other in memory
+        else:
+            e.raw('s_cmp_lt_u32 s%d, %%[nf]' % S_T)
+            e.raw('s_cbranch_scc0 tile_m%d_%s' % (kn, lbl))
+            if kn == 0:
+                e.raw('s_branch tile_p0_%s' % lbl)
+
+    def program(self):
+        e = self.e
+        lbl = '%='
+        # constants and zero state
+        e.raw('s_mov_b32 s%d, 0' % S_T)
+        e.raw('s_mov_b32 s%d, 0x%x' % (S_THR, LAZY_THR))
+        e.raw('v_mov_b32 v%d, 0x3c003c00' % ONES)
+        e.raw('v_mov_b32 v%d, 0' % LSUM)
+        e.raw('v_mov_b32 v%d, 0xff800000' % MRUN)
+        e.raw('v_mov_b32 v%d, 0xff800000' % NINF)
+        for i in range(64):
+            e.raw('v_mov_b32 v%d, 0' % (ACC + i))
+        for s in range(8):
+            e.emit('global_load_dwordx4 %s, %%[qp], off offset:%d' % (vr(Q + 4 * s, 4), 32 * s))
+        # start-up: the page ids of tiles 0..3 in one go, then tiles 0, 1, 2 in flight together (tiles
+        # 0 and 1 borrow the operand registers as staging), tiles 0 and 1 into LDS
+        for t, dst in enumerate((S_IDA, S_IDB, S_IDS, S_IDN)):
+            for o in self.ids_load(t, dst):
+                e.raw(o)
+        e.raw('s_waitcnt lgkmcnt(0)')
+        for ids, base in ((S_IDA, VT), (S_IDB, KA), (S_IDS, ST)):
+            for o in self.fetch(ids, base):
+                e.emit(o)
+        for t, base in ((0, VT), (1, KA)):
+            for o in self.v_convert(base) + self.v_zero_tail(t, base) + self.stores(t, base):
+                e.emit(o)
+        e.emit('s_barrier')
+        for o in self.ids_take():
+            e.raw(o)
+        # first step: S^T(0, 0), the K operands of step (0, 1), the first reference
+        for o in self.k_reads(0, 0):
+            e.emit(o)
+        for s in range(8):
+            e.emit(self.qk(S0, s))
+        for o in self.k_reads(0, 1):
+            e.emit(o)
+        e.raw('s_nop 15')
+        e.raw('s_nop 15')
+        for o in self.row_max(S0) + self.set_reference():
+            e.emit(o)
+        e.drain(lgkm=True, vm=False)
+        e.raw('s_cmp_lt_u32 s%d, %%[nf]' % S_T)  # t = 0: a first tile that needs masking is possible when nf = 0
+        e.raw('s_cbranch_scc0 tile_m0_%s' % lbl)
+        # steady state, one copy per LDS buffer rotation: unmasked tiles, then masked ones
+        for masked in (False, True):
+            for k in range(NBUF):
+                self.tile(k, lbl, masked)
+        e.raw('s_branch exit_%s' % lbl)
+        # out-of-line reference raises
+        for kind in 'pm':
+            for k in range(NBUF):
+                for u in range(2):
+                    e.label('raise_%s%d%d_%s' % (kind, k, u, lbl))
+                    for o in self.raise_reference(S0 if u == 0 else S1):
+                        e.raw(o)
+                    e.raw('s_branch back_%s%d%d_%s' % (kind, k, u, lbl))
+        # epilogue (every wavefront is past its last tile read: the exit follows a barrier):
+        # o = O / l, lse = ln(sum exp) = (reference * scale_log2 + log2 l) * ln 2
+        e.label('exit_%s' % lbl)
+        e.raw('s_waitcnt vmcnt(0)')
+        e.raw('s_nop 15')
+        e.raw('s_nop 15')
+        for o in ['v_mov_b32 v%d, v%d' % (X0, LSUM), 'v_mov_b32 v%d, v%d' % (X1, LSUM), 's_nop 1',
+                  'v_permlane32_swap_b32 v%d, v%d' % (X0, X1), 's_nop 1', 'v_add_f32 v%d, v%d, v%d' % (LSUM, X0, X1),
+                  # (a transcendental result needs a wait state before an ordinary vector instruction reads it)
+                  'v_log_f32 v%d, v%d' % (X1, LSUM), 'v_rcp_f32 v%d, v%d' % (X0, LSUM), 's_nop 1',
+                  'v_fma_f32 v%d, v%d, %%[sc], v%d' % (X1, MRUN, X1), 'v_mul_f32 v%d, 0x3f317218, v%d' % (X1, X1),
+                  # rows past the end of the query tile are not stored
+                  'v_and_b32 v%d, 1, %%[rok]' % MAXT, 'v_cmp_ne_u32 vcc, 0, v%d' % MAXT,
+                  's_and_saveexec_b64 s[%d:%d], vcc' % (S_EXEC, S_EXEC + 1)]:
+            e.raw(o)
+        for i in range(64):
+            e.raw('v_mul_f32 v%d, v%d, v%d' % (ACC + i, ACC + i, X0))
+        for db in range(4):
+            for q in range(4):
+                e.raw('global_store_dwordx4 %%[ooff], %s, %%[ob] offset:%d' % (vr(ACC + 16 * db + 4 * q, 4), 128 * db + 32 * q))
+        e.raw('s_cmp_eq_u32 %[oc], 0')
+        e.raw('s_cbranch_scc1 nocast_%s' % lbl)
+        e.raw('v_lshrrev_b32 v%d, 1, %%[ooff]' % T)
+        cvt = 'v_cvt_pk_bf16_f32' if self.bf else 'v_cvt_pk_f16_f32'
+        for db in range(4):
+            for q in range(4):
+                a = ACC + 16 * db + 4 * q
+                t = T + 2 + 2 * ((4 * db + q) % 7)
+                e.raw('%s v%d, v%d, v%d' % (cvt, t, a, a + 1))
+                e.raw('%s v%d, v%d, v%d' % (cvt, t + 1, a + 2, a + 3))
+                e.raw('global_store_dwordx2 v%d, %s, %%[cb] offset:%d' % (T, vr(t, 2), 64 * db + 16 * q))
+        e.label('nocast_%s' % lbl)
+        # one lane per row writes lse
+        for o in ['s_mov_b64 exec, s[%d:%d]' % (S_EXEC, S_EXEC + 1), 'v_and_b32 v%d, 2, %%[rok]' % MAXT,
+                  'v_cmp_ne_u32 vcc, 0, v%d' % MAXT, 's_and_saveexec_b64 s[%d:%d], vcc' % (S_EXEC, S_EXEC + 1),
+                  'v_lshrrev_b32 v%d, 9, %%[ooff]' % T, 'v_lshlrev_b32 v%d, 2, v%d' % (T, T),
+                  'global_store_dword v%d, v%d, %%[lb]' % (T, X1), 's_mov_b64 exec, s[%d:%d]' % (S_EXEC, S_EXEC + 1)]:
+            e.raw(o)
+        return e.out
+
+
+def clobbers():
+    c = ['"v%d"' % i for i in range(FIRST_FIXED_VGPR, 256)] + ['"s%d"' % i for i in FIXED_SGPRS]
+    return c + ['"vcc"', '"scc"', '"memory"']
+
+
+def write(path, lines, name):
+    with open(path, 'w') as f:
+        f.write('// Generated by gen/gen_append_loop.py (%s); do not edit by hand.\n' % name)
+        for l in lines:
+            f.write('"%s\\n\\t"\n' % l)
+
+
+if __name__ == '__main__':
+    here = os.path.dirname(os.path.abspath(__file__))
+    for bf, name in ((True, 'bf16'), (False, 'f16')):
+        lines = Gen(bf).program()
+        write(os.path.join(here, '..', 'append_loop_%s.inc' % name), lines, name)
+        n_mfma = sum(1 for l in lines if l.startswith('v_mfma'))
+        print('%s: %d lines, %d matrix instructions, %d waits' % (name, len(lines), n_mfma, sum(1 for l in lines if l.startswith('s_waitcnt'))))
+    with open(os.path.join(here, '..', 'append_loop_clobbers.inc'), 'w') as f:
+        f.write('// Generated by gen/gen_append_loop.py; do not edit by hand.\n')
+        f.write(', '.join(clobbers()) + '\n')
