@@ -171,21 +171,55 @@ __device__ __forceinline__ void run_scheduled_loop(int n_full, int n_tiles, int 
   }
 }
 
+// One entry of the plan's work list (Sec. 3.3.1), in scalar registers.  The fields are read with
+// scalar loads (the plan arrays were written by an earlier kernel): the scalar path does not
+// queue behind the previous item's output stores the way a vector load would.  Loads and wait
+// are one statement, so the compiler never sees a register whose load is still in flight.
+struct WorkItem {
+  int q_row0, n_pos, kv_page0, kv_start, kv_len, diag0, out_slot;
+  __device__ __forceinline__ void load(const RunParams& p, int w) {
+    const int off = w * 4;
+    asm volatile(
+        "s_load_dword %0, %7, %14\n\t"
+        "s_load_dword %1, %8, %14\n\t"
+        "s_load_dword %2, %9, %14\n\t"
+        "s_load_dword %3, %10, %14\n\t"
+        "s_load_dword %4, %11, %14\n\t"
+        "s_load_dword %5, %12, %14\n\t"
+        "s_load_dword %6, %13, %14\n\t"
+        "s_waitcnt lgkmcnt(0)"
+        : "=&s"(q_row0), "=&s"(n_pos), "=&s"(kv_page0), "=&s"(kv_start), "=&s"(kv_len), "=&s"(diag0), "=&s"(out_slot)
+        : "s"(p.w_q_row0), "s"(p.w_n_pos), "s"(p.w_kv_page0), "s"(p.w_kv_start), "s"(p.w_kv_len), "s"(p.w_diag0),
+          "s"(p.w_out_slot), "s"(off)
+        : "memory");
+  }
+};
+
+// K tiles, then V tiles (three buffers each: the scheduled loop rotates over three, the generic
+// path over the first two).
+__shared__ __attribute__((aligned(16))) uint8_t lds_raw[kLdsBytes];
+
+// One work item on the generic path: any chunk length, any masking.  Kept out of line so that
+// its loop-invariant registers do not have to live across the scheduled loop in the caller.
+// Contains CTA barriers: every wavefront of the CTA calls it with the same item.
+// (Arguments of a device function travel in vector registers: the item's fields and the address
+// of the launch parameters, which the kernel takes from its argument segment, are made scalar
+// again here.)
 template <bool BF>
-__global__ void __launch_bounds__(kCtaThreads) __attribute__((amdgpu_waves_per_eu(2, 2)))
-append_kernel(const RunParams p) {
-  // K tiles, then V tiles (three buffers each: the scheduled loop rotates over three, the generic
-  // path over the first two).
-  __shared__ __attribute__((aligned(16))) uint8_t lds_raw[kLdsBytes];
+__device__ __attribute__((noinline)) void generic_work_item(uint64_t params_addr, int a_q_row0, int a_n_pos,
+                                                            int a_kv_page0, int a_kv_start, int a_kv_len, int a_diag0,
+                                                            int a_out_slot) {
+  typedef const __attribute__((address_space(4))) RunParams KernargParams;
+  const uint64_t params_lo = static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(static_cast<int>(params_addr)));
+  const uint64_t params_hi = static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(static_cast<int>(params_addr >> 32)));
+  KernargParams& p = *reinterpret_cast<KernargParams*>(params_lo | (params_hi << 32));
   uint16_t* const lds_k = reinterpret_cast<uint16_t*>(lds_raw);
   uint16_t* const lds_v = reinterpret_cast<uint16_t*>(lds_raw + kLdsVOffset);
-
   const int tid = threadIdx.x;
   const int wave = tid >> 6;
   const int lane = tid & 63;
   const int n = lane & 31;   // K: token of the 32-token step; V: column within a 32-wide block; S/O: query row
   const int c = lane >> 5;   // wavefront half
-  const int cta = blockIdx.x;
   const int kvh = blockIdx.y;
   const int g = p.group;
   const int g_log2 = 31 - __builtin_clz(g);
@@ -209,17 +243,307 @@ append_kernel(const RunParams p) {
   const int tr_row = (lane & 15) >> 2;
   const int tr_col = 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
 
+  const int q_row0 = __builtin_amdgcn_readfirstlane(a_q_row0), n_pos = __builtin_amdgcn_readfirstlane(a_n_pos);
+  const int kv_page0 = __builtin_amdgcn_readfirstlane(a_kv_page0), kv_start = __builtin_amdgcn_readfirstlane(a_kv_start);
+  const int kv_len = __builtin_amdgcn_readfirstlane(a_kv_len), diag0 = __builtin_amdgcn_readfirstlane(a_diag0);
+  const int out_slot = __builtin_amdgcn_readfirstlane(a_out_slot);
+  const bool causal = diag0 != kNoDiagMarker;
+  const int n_pages = (kv_len + kPageSize - 1) / kPageSize;
+  const int n_tiles = (kv_len + kTileKv - 1) / kTileKv;
+
+  // ---- this lane's query rows, one per 32-row block ----
+  int pos[kRowBlocks], hh[kRowBlocks], lim[kRowBlocks];
+  bool row_ok[kRowBlocks];
+  u32x4_t qreg[kRowBlocks][8];  // Q^T as B operand: row n of the block, d = 16 s + 8 c .. + 8
+#pragma unroll
+  for (int b = 0; b < kRowBlocks; ++b) {
+    const int R = kWaveRows * wave + 32 * b + n;
+    pos[b] = R >> g_log2;
+    hh[b] = R & (g - 1);
+    row_ok[b] = pos[b] < n_pos;
+    // the row sees request tokens <= diag0 + pos; in chunk-local terms: local index <= lim
+    lim[b] = causal ? diag0 + pos[b] - kv_start : 0x3FFFFFFF;
+    if (row_ok[b]) {
+      const uint16_t* qp = static_cast<const uint16_t*>(p.q) +
+                           (static_cast<int64_t>(q_row0 + pos[b]) * H + kvh * g + hh[b]) * kHeadDim + c * 8;
+#pragma unroll
+      for (int s = 0; s < 8; ++s) qreg[b][s] = *reinterpret_cast<const u32x4_t*>(qp + 16 * s);
+    } else {
+#pragma unroll
+      for (int s = 0; s < 8; ++s) qreg[b][s] = u32x4_t{0u, 0u, 0u, 0u};
+    }
+  }
+  // wave-uniform bounds of lim per block (rows are position-major)
+  int blk_lim_lo[kRowBlocks], blk_lim_hi[kRowBlocks];
+#pragma unroll
+  for (int b = 0; b < kRowBlocks; ++b) {
+    const int r0 = kWaveRows * wave + 32 * b;
+    blk_lim_lo[b] = causal ? diag0 + (r0 >> g_log2) - kv_start : 0x3FFFFFFF;
+    blk_lim_hi[b] = causal ? diag0 + ((r0 + 31) >> g_log2) - kv_start : 0x3FFFFFFF;
+  }
+
+  f32x16_t acc[kRowBlocks][4];  // acc[b][db][r] = O^T[d = 32 db + 8 (r / 4) + 4 c + r % 4][row n of block b]
+#pragma unroll
+  for (int b = 0; b < kRowBlocks; ++b)
+#pragma unroll
+    for (int db = 0; db < 4; ++db)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[b][db][r] = 0.f;
+  float m_run[kRowBlocks], neg_ms[kRowBlocks], l_run[kRowBlocks];
+#pragma unroll
+  for (int b = 0; b < kRowBlocks; ++b) {
+    m_run[b] = NEG_INF;  // reference of the exponentials, raw-logit units (-inf: none yet)
+    neg_ms[b] = 0.f;     // -reference * scale_log2 (0 while there is none)
+    l_run[b] = 0.f;      // this lane's share of the row sum
+  }
+
+  // Two staging register sets: set t % 2 carries tile t from its loads to its LDS store, so two
+  // tiles are in flight while a third is being consumed.
+  u32x4_t stage_k[2][2], stage_v[2][2];
+  // Page ids are fetched one tile ahead of the data they address (lane r holds page r of the
+  // tile), so that the data loads never wait behind an index load.
+  auto fetch_page_ids = [&](int t) -> int {
+    int pi = 4 * t + (lane & 3);
+    pi = pi < n_pages ? pi : n_pages - 1;  // never index past the chunk's pages
+    return p.kv_indices[kv_page0 + pi];
+  };
+  auto fetch_tile = [&](auto set_c, int ids) {
+    constexpr int SET = decltype(set_c)::value;
+#pragma unroll
+    for (int r = 0; r < 2; ++r) {
+      const int pg = __builtin_amdgcn_readlane(ids, 2 * r + st_page);
+      const int64_t page_off = pg * p.stride_page + kvh * p.stride_head;  // wave-uniform
+      stage_k[SET][r] = *reinterpret_cast<const u32x4_t*>(kpool + page_off + st_off);
+      stage_v[SET][r] = *reinterpret_cast<const u32x4_t*>(vpool + page_off + st_off);
+    }
+  };
+  auto store_tile = [&](auto set_c, int t) {
+    constexpr int SET = decltype(set_c)::value;
+    uint16_t* dk = lds_k + (t & 1) * (kTileKv * kRowElems);
+    uint16_t* dv = lds_v + (t & 1) * (kTileKv * kRowElemsV);
+    if constexpr (BF) {
+#pragma unroll
+      for (int r = 0; r < 2; ++r)
+        stage_v[SET][r] = u32x4_t{bf16x2_to_f16x2(stage_v[SET][r][0]), bf16x2_to_f16x2(stage_v[SET][r][1]),
+                                  bf16x2_to_f16x2(stage_v[SET][r][2]), bf16x2_to_f16x2(stage_v[SET][r][3])};
+    }
+    if (kTileKv * (t + 1) > kv_len) {  // CTA-uniform: only the chunk's last tile has rows past its end
+#pragma unroll
+      for (int r = 0; r < 2; ++r)
+        if (kTileKv * t + 32 * r + st_tok >= kv_len) stage_v[SET][r] = u32x4_t{0u, 0u, 0u, 0u};  // must not reach P.V
+    }
+#pragma unroll
+    for (int r = 0; r < 2; ++r) {
+      *reinterpret_cast<u32x4_t*>(&dk[st_lds_k + 32 * r * kRowElems]) = stage_k[SET][r];
+      *reinterpret_cast<u32x4_t*>(&dv[st_lds_v + 32 * r * kRowElemsV]) = stage_v[SET][r];
+    }
+  };
+  using set0_t = std::integral_constant<int, 0>;
+  using set1_t = std::integral_constant<int, 1>;
+
+  // Pipeline: while tile t is consumed from LDS buffer t % 2, tiles t + 1 and t + 2 are in the
+  // staging registers (loads issued two tiles ahead); after the products of tile t have been
+  // issued tile t + 1 is written to buffer (t + 1) % 2, its register set is reloaded with tile
+  // t + 3, and one CTA barrier closes the tile.
+  __syncthreads();   // the previous work item's last tile is no longer being read
+  // One tile: consume tile t, then hand tile t + 1 over from staging set SET = (t + 1) % 2.  The
+  // tile loop below is unrolled by two so that SET is a compile-time constant.
+  auto do_tile = [&](auto set_c, int t, int& ids_load, const int& ids_use) {
+    const uint16_t* tk = lds_k + (t & 1) * (kTileKv * kRowElems);
+    const uint16_t* tv = lds_v + (t & 1) * (kTileKv * kRowElemsV);
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+      const int tok_base = kTileKv * t + 32 * u;  // chunk-local index of this 32-token step
+      if (tok_base >= kv_len || tok_base > blk_lim_hi[kRowBlocks - 1]) continue;  // nothing visible to this wavefront
+      // ---- S^T = K . Q^T: all eight A operands are requested before the first product ----
+      u32x4_t ka[8];
+      {
+        const uint16_t* krow = &tk[(32 * u + n) * kRowElems + c * 8];
+#pragma unroll
+        for (int s = 0; s < 8; ++s) ka[s] = *reinterpret_cast<const u32x4_t*>(krow + 16 * s);
+      }
+      f32x16_t sacc[kRowBlocks];
+#pragma unroll
+      for (int b = 0; b < kRowBlocks; ++b) {
+#pragma unroll
+        for (int r = 0; r < 16; ++r) sacc[b][r] = 0.f;
+#pragma unroll
+        for (int s = 0; s < 8; ++s) sacc[b] = mfma_qk<BF>(ka[s], qreg[b][s], sacc[b]);
+      }
+      // lane (n, c) now holds S^T[token 8 (r / 4) + 4 c + r % 4][row n of block b], r = 0..15
+
+      // ---- V^T operands: requested now, they arrive while the softmax runs on the vector ALU.
+      //      Operand (db, j) = columns d = 32 db + (lane % 32), token slots e = 0..7 <->
+      //      tokens 16 j + 8 (e / 4) + 4 c + e % 4 (the order P^T has in the S^T registers) ----
+      u32x4_t vt[4][2];
+      {
+        const uint16_t* vsrc = &tv[(32 * u + 4 * c + tr_row) * kRowElemsV + tr_col];
+#pragma unroll
+        for (int db = 0; db < 4; ++db)
+#pragma unroll
+          for (int j = 0; j < 2; ++j) {
+            const u32x2_t lo = lds_read_tr16(vsrc + (16 * j) * kRowElemsV + 32 * db);
+            const u32x2_t hi = lds_read_tr16(vsrc + (16 * j + 8) * kRowElemsV + 32 * db);
+            vt[db][j] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3);
+          }
+      }
+
+#pragma unroll
+      for (int b = 0; b < kRowBlocks; ++b) {
+        if (tok_base > blk_lim_hi[b]) continue;  // block wholly above the diagonal (wave-uniform)
+        // ---- online softmax on the 16 logits of its row this lane owns ----
+        float sv[16];  // raw logits q.k; the softmax scale is folded into the exponent below
+#pragma unroll
+        for (int r = 0; r < 16; ++r) sv[r] = sacc[b][r];
+        const bool need_mask = (tok_base + 32 > kv_len) || (tok_base + 31 > blk_lim_lo[b]);
+        if (need_mask) {
+          const int cap = min(lim[b], kv_len - 1);
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            const int tkn = tok_base + 8 * (r >> 2) + 4 * c + (r & 3);
+            sv[r] = (tkn <= cap) ? sv[r] : NEG_INF;
+          }
+        }
+        // Optimistic softmax: exponentiate against the current reference first, and only if
+        // some P came out above 2^kLazyLog2 (or the row has no reference yet) find the row
+        // maximum, raise the reference, rescale, and redo the exponentials.  The reference
+        // only has to keep P inside fp16 range; o = O / l does not depend on it.  The common
+        // step therefore has no max reduction, no cross-lane exchange and no rescale.
+        f16x2_t h[8];
+        auto exponentiate = [&]() {
+#pragma unroll
+          for (int j = 0; j < 8; ++j) {
+            const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(sv[2 * j], p.scale_log2, neg_ms[b]));
+            const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(sv[2 * j + 1], p.scale_log2, neg_ms[b]));
+            h[j] = __builtin_convertvector(f32x2_t{p0, p1}, f16x2_t);  // one v_cvt_pk_f16_f32
+          }
+        };
+        exponentiate();
+        // P >= 0, so fp16 order is unsigned-integer order on the bit patterns (inf included)
+        u16x2_t hmax = __builtin_bit_cast(u16x2_t, h[0]);
+#pragma unroll
+        for (int j = 1; j < 8; ++j) hmax = __builtin_elementwise_max(hmax, __builtin_bit_cast(u16x2_t, h[j]));
+        const bool redo = hmax[0] > kLazyF16Bits || hmax[1] > kLazyF16Bits || m_run[b] == NEG_INF;
+        if (__builtin_amdgcn_ballot_w64(redo) != 0) {
+          float tmax = sv[0];
+#pragma unroll
+          for (int r = 1; r < 16; ++r) tmax = fmaxf(tmax, sv[r]);
+          tmax = halves_max(tmax);
+          const float m_new = fmaxf(m_run[b], tmax);
+          const float m_use = (m_new == NEG_INF) ? 0.f : m_new;  // row has seen nothing yet
+          const float alpha = __builtin_amdgcn_exp2f((m_run[b] - m_use) * p.scale_log2);
+          m_run[b] = m_new;
+          neg_ms[b] = -m_use * p.scale_log2;
+          l_run[b] *= alpha;
+#pragma unroll
+          for (int db = 0; db < 4; ++db) acc[b][db] *= alpha;
+          exponentiate();
+        }
+        // The row sum is taken over the fp16-rounded P that the second product consumes
+        // (v_dot2_f32_f16 with a vector of ones, fp32 accumulation): o = O / l is then an exact
+        // convex combination of V rows whatever the reference, and a single dominant key
+        // returns its V row exactly.
+        const f16x2_t ones = {static_cast<_Float16>(1.0f), static_cast<_Float16>(1.0f)};
+        float l = l_run[b];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) l = __builtin_amdgcn_fdot2(h[j], ones, l, false);
+        l_run[b] = l;
+        const u32x4_t pb0 = {__builtin_bit_cast(uint32_t, h[0]), __builtin_bit_cast(uint32_t, h[1]),
+                             __builtin_bit_cast(uint32_t, h[2]), __builtin_bit_cast(uint32_t, h[3])};
+        const u32x4_t pb1 = {__builtin_bit_cast(uint32_t, h[4]), __builtin_bit_cast(uint32_t, h[5]),
+                             __builtin_bit_cast(uint32_t, h[6]), __builtin_bit_cast(uint32_t, h[7])};
+        // ---- O^T += V^T . P^T ----
+#pragma unroll
+        for (int db = 0; db < 4; ++db) {
+          acc[b][db] = mfma_pv(vt[db][0], pb0, acc[b][db]);
+          acc[b][db] = mfma_pv(vt[db][1], pb1, acc[b][db]);
+        }
+      }
+    }
+    // Hand the next tile over and reload its register set with the tile three ahead.  Every
+    // iteration issues the same loads in the same order (tiles past the end re-read the last
+    // page and are never stored), so the counted waits for the oldest loads leave the younger
+    // ones in flight; the index load goes first so that its consumer, one iteration later,
+    // does not wait for the data loads issued after it.
+    ids_load = fetch_page_ids(t + 4);
+    if (t + 1 < n_tiles) store_tile(set_c, t + 1);
+    fetch_tile(set_c, ids_use);
+    __syncthreads();  // tile t + 1 is visible; nobody reads tile t any more
+  };
+  if (n_tiles > 0) {  // one region, so that the loop is entered with this work item's Q loads known complete
+    const int ids0 = fetch_page_ids(0), ids1 = fetch_page_ids(1);
+    int ids_even = fetch_page_ids(2), ids_odd = fetch_page_ids(3);  // ids of the next even / odd tile to request
+    fetch_tile(set0_t{}, ids0);
+    fetch_tile(set1_t{}, ids1);
+    store_tile(set0_t{}, 0);
+    fetch_tile(set0_t{}, ids_even);
+    __syncthreads();
+    // A single-exit loop: with an odd tile count the last call finds no visible step and stores
+    // nothing, which is cheaper than a second exit that would make every counted wait assume
+    // the emptiest pipeline.
+    for (int t = 0; t < n_tiles; t += 2) {
+      do_tile(set1_t{}, t, ids_even, ids_odd);
+      do_tile(set0_t{}, t + 1, ids_odd, ids_even);
+    }
+  }
+
+  // ---- epilogue: o = O / l, lse = ln(sum exp) (Sec. 2.2) ----
+#pragma unroll
+  for (int b = 0; b < kRowBlocks; ++b) {
+    const float l = halves_sum(l_run[b]);
+    const bool live = l > 0.f;
+    const float inv = live ? 1.0f / l : 0.f;
+    const float lse_val =
+        live ? (m_run[b] * p.scale_log2 + __builtin_amdgcn_logf(l)) * 0.6931471805599453f : NEG_INF;
+    if (row_ok[b]) {
+      const int head = kvh * g + hh[b];
+      const int64_t final_row = static_cast<int64_t>(q_row0 + pos[b]) * H + head;
+      float* dst_o;
+      float* dst_lse;
+      if (out_slot < 0) {  // write-through (App. D.2)
+        dst_o = p.o + final_row * kHeadDim;
+        dst_lse = p.lse + final_row;
+      } else {
+        const int64_t row = (static_cast<int64_t>(out_slot) * p.t_pos + pos[b]) * H + head;
+        dst_o = p.part_o + row * kHeadDim;
+        dst_lse = p.part_lse + row;
+      }
+#pragma unroll
+      for (int db = 0; db < 4; ++db)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const int d0 = 32 * db + 8 * q + 4 * c;
+          const f32x4_t v = {acc[b][db][4 * q] * inv, acc[b][db][4 * q + 1] * inv, acc[b][db][4 * q + 2] * inv,
+                             acc[b][db][4 * q + 3] * inv};
+          *reinterpret_cast<f32x4_t*>(dst_o + d0) = v;
+          if (out_slot < 0 && p.o_cast != nullptr) {
+            uint16_t* dc = static_cast<uint16_t*>(p.o_cast) + final_row * kHeadDim + d0;
+            *reinterpret_cast<u32x2_t*>(dc) = u32x2_t{pack_out<BF>(v[0], v[1]), pack_out<BF>(v[2], v[3])};
+          }
+        }
+      if (c == 0) *dst_lse = lse_val;
+    }
+  }
+}
+
+template <bool BF>
+__global__ void __launch_bounds__(kCtaThreads) __attribute__((amdgpu_waves_per_eu(2, 2)))
+append_kernel(const RunParams p) {
+  const int tid = threadIdx.x;
+  const int cta = blockIdx.x;
+  const int kvh = blockIdx.y;
+  const int g = p.group;
+  const int g_log2 = 31 - __builtin_clz(g);
+  const int H = p.num_qo_heads;
+
   const int w_begin = __builtin_amdgcn_readfirstlane(p.cta_indptr[cta]);
   const int w_end = __builtin_amdgcn_readfirstlane(p.cta_indptr[cta + 1]);
 
   for (int w = w_begin; w < w_end; ++w) {
-    const int q_row0 = __builtin_amdgcn_readfirstlane(p.w_q_row0[w]);
-    const int n_pos = __builtin_amdgcn_readfirstlane(p.w_n_pos[w]);
-    const int kv_page0 = __builtin_amdgcn_readfirstlane(p.w_kv_page0[w]);
-    const int kv_start = __builtin_amdgcn_readfirstlane(p.w_kv_start[w]);
-    const int kv_len = __builtin_amdgcn_readfirstlane(p.w_kv_len[w]);
-    const int diag0 = __builtin_amdgcn_readfirstlane(p.w_diag0[w]);
-    const int out_slot = __builtin_amdgcn_readfirstlane(p.w_out_slot[w]);
+    WorkItem item;
+    item.load(p, w);
+    const int q_row0 = item.q_row0, n_pos = item.n_pos, kv_page0 = item.kv_page0, kv_start = item.kv_start;
+    const int kv_len = item.kv_len, diag0 = item.diag0, out_slot = item.out_slot;
     const bool causal = diag0 != kNoDiagMarker;
 
     // ---- work items whose first tile every row of the CTA sees in full: the scheduled loop ----
@@ -232,314 +556,51 @@ append_kernel(const RunParams p) {
       const int64_t out_rows_bound = (out_slot < 0 ? static_cast<int64_t>(q_row0) + p.t_pos : (static_cast<int64_t>(out_slot) + 1) * p.t_pos) * H;
       if (n_full >= 1 && kv_len >= kLoopMinTokens && page_bytes > 0 && page_bytes < (int64_t(1) << 32) &&
           out_rows_bound * (kHeadDim * 4) < (int64_t(1) << 32)) {
-        const int R = 32 * wave + n;
+        // The loop clobbers nearly every vector register, so its lane-dependent operands are
+        // derived here from an opaque copy of the thread index: the compiler cannot hoist them out
+        // of the work loop and keep them in scratch memory across the loop.
+        int tid_o = tid;
+        asm volatile("" : "+v"(tid_o));
+        const int wave_o = tid_o >> 6, n_o = tid_o & 31, c_o = (tid_o >> 5) & 1;
+        const int st_tok_o = tid_o >> 4, st_chunk_o = tid_o & 15;
+        const int tr_row_o = (tid_o & 15) >> 2, tr_col_o = 16 * ((tid_o >> 4) & 1) + 4 * (tid_o & 3);
+        const int R = 32 * wave_o + n_o;
         const int pos_r = R >> g_log2;
+        const int head = kvh * g + (R & (g - 1));
         const int pos_c = min(pos_r, n_pos - 1);  // rows past the tile's end compute on a valid row; never stored
         const uint64_t q_addr = reinterpret_cast<uint64_t>(static_cast<const uint16_t*>(p.q) +
-                                (static_cast<int64_t>(q_row0 + pos_c) * H + kvh * g + (R & (g - 1))) * kHeadDim + c * 8);
-        const uint64_t k_base = reinterpret_cast<uint64_t>(kpool + kvh * p.stride_head);
-        const uint64_t v_base = reinterpret_cast<uint64_t>(vpool + kvh * p.stride_head);
+                                (static_cast<int64_t>(q_row0 + pos_c) * H + head) * kHeadDim + c_o * 8);
+        const uint64_t k_base = reinterpret_cast<uint64_t>(static_cast<const uint16_t*>(p.k_pool) + kvh * p.stride_head);
+        const uint64_t v_base = reinterpret_cast<uint64_t>(static_cast<const uint16_t*>(p.v_pool) + kvh * p.stride_head);
         const uint32_t lds0 = lds_offset(lds_raw);
         const int chunk_pages = (kv_len + kPageSize - 1) / kPageSize;
         const int last_seen = causal ? min(diag0 + pos_r - kv_start, kv_len - 1) : kv_len - 1;
         // where the rows go: the final output (write-through, App. D.2) or this item's partial slot
         const bool final_out = out_slot < 0;
-        const int64_t out_row = final_out ? static_cast<int64_t>(q_row0 + pos_r) * H + kvh * g + (R & (g - 1))
-                                          : (static_cast<int64_t>(out_slot) * p.t_pos + pos_r) * H + kvh * g + (R & (g - 1));
-        const bool row_live = pos_r < n_pos;
+        const int64_t out_row = (final_out ? static_cast<int64_t>(q_row0 + pos_r)
+                                           : static_cast<int64_t>(out_slot) * p.t_pos + pos_r) * H + head;
+        const uint32_t st_off_bytes = static_cast<uint32_t>((st_tok_o & 15) * p.stride_tok + st_chunk_o * 8) * 2;
         __syncthreads();  // the previous work item is done with the tile buffers
-        run_scheduled_loop<BF>(n_full, (kv_len + kTileKv - 1) / kTileKv, kv_len, last_seen - 4 * c, st_tok,
+        run_scheduled_loop<BF>(n_full, (kv_len + kTileKv - 1) / kTileKv, kv_len, last_seen - 4 * c_o, st_tok_o,
                                (chunk_pages - 1) * 4, p.kv_indices + kv_page0, static_cast<uint32_t>(k_base),
                                static_cast<uint32_t>(k_base >> 32), static_cast<uint32_t>(v_base),
                                static_cast<uint32_t>(v_base >> 32), static_cast<uint32_t>(page_bytes), p.scale_log2,
-                               __builtin_amdgcn_readfirstlane(wave >> 2), q_addr, st_off * 2,
-                               lds0 + n * (kRowElems * 2) + c * 16,
-                               lds0 + kLdsVOffset + (4 * c + tr_row) * (kRowElemsV * 2) + tr_col * 2,
-                               lds0 + st_tok * (kRowElems * 2) + st_chunk * 16,
-                               lds0 + kLdsVOffset + st_tok * (kRowElemsV * 2) + st_chunk * 16,
-                               static_cast<uint32_t>(out_row * (kHeadDim * 4) + c * 16),
-                               row_live ? (c == 0 ? 3 : 1) : 0, final_out ? p.o : p.part_o,
+                               __builtin_amdgcn_readfirstlane(wave_o >> 2), q_addr, st_off_bytes,
+                               lds0 + n_o * (kRowElems * 2) + c_o * 16,
+                               lds0 + kLdsVOffset + (4 * c_o + tr_row_o) * (kRowElemsV * 2) + tr_col_o * 2,
+                               lds0 + st_tok_o * (kRowElems * 2) + st_chunk_o * 16,
+                               lds0 + kLdsVOffset + st_tok_o * (kRowElemsV * 2) + st_chunk_o * 16,
+                               static_cast<uint32_t>(out_row * (kHeadDim * 4) + c_o * 16),
+                               pos_r < n_pos ? (c_o == 0 ? 3 : 1) : 0, final_out ? p.o : p.part_o,
                                final_out ? p.lse : p.part_lse, p.o_cast,
                                __builtin_amdgcn_readfirstlane(final_out && p.o_cast != nullptr ? 1 : 0));
         continue;  // the work item is finished
       }
     }
-    const int n_pages = (kv_len + kPageSize - 1) / kPageSize;
-    const int n_tiles = (kv_len + kTileKv - 1) / kTileKv;
-
-    // ---- this lane's query rows, one per 32-row block ----
-    int pos[kRowBlocks], hh[kRowBlocks], lim[kRowBlocks];
-    bool row_ok[kRowBlocks];
-    u32x4_t qreg[kRowBlocks][8];  // Q^T as B operand: row n of the block, d = 16 s + 8 c .. + 8
-#pragma unroll
-    for (int b = 0; b < kRowBlocks; ++b) {
-      const int R = kWaveRows * wave + 32 * b + n;
-      pos[b] = R >> g_log2;
-      hh[b] = R & (g - 1);
-      row_ok[b] = pos[b] < n_pos;
-      // the row sees request tokens <= diag0 + pos; in chunk-local terms: local index <= lim
-      lim[b] = causal ? diag0 + pos[b] - kv_start : 0x3FFFFFFF;
-      if (row_ok[b]) {
-        const uint16_t* qp = static_cast<const uint16_t*>(p.q) +
-                             (static_cast<int64_t>(q_row0 + pos[b]) * H + kvh * g + hh[b]) * kHeadDim + c * 8;
-#pragma unroll
-        for (int s = 0; s < 8; ++s) qreg[b][s] = *reinterpret_cast<const u32x4_t*>(qp + 16 * s);
-      } else {
-#pragma unroll
-        for (int s = 0; s < 8; ++s) qreg[b][s] = u32x4_t{0u, 0u, 0u, 0u};
-      }
-    }
-    // wave-uniform bounds of lim per block (rows are position-major)
-    int blk_lim_lo[kRowBlocks], blk_lim_hi[kRowBlocks];
-#pragma unroll
-    for (int b = 0; b < kRowBlocks; ++b) {
-      const int r0 = kWaveRows * wave + 32 * b;
-      blk_lim_lo[b] = causal ? diag0 + (r0 >> g_log2) - kv_start : 0x3FFFFFFF;
-      blk_lim_hi[b] = causal ? diag0 + ((r0 + 31) >> g_log2) - kv_start : 0x3FFFFFFF;
-    }
-
-    f32x16_t acc[kRowBlocks][4];  // acc[b][db][r] = O^T[d = 32 db + 8 (r / 4) + 4 c + r % 4][row n of block b]
-#pragma unroll
-    for (int b = 0; b < kRowBlocks; ++b)
-#pragma unroll
-      for (int db = 0; db < 4; ++db)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) acc[b][db][r] = 0.f;
-    float m_run[kRowBlocks], neg_ms[kRowBlocks], l_run[kRowBlocks];
-#pragma unroll
-    for (int b = 0; b < kRowBlocks; ++b) {
-      m_run[b] = NEG_INF;  // reference of the exponentials, raw-logit units (-inf: none yet)
-      neg_ms[b] = 0.f;     // -reference * scale_log2 (0 while there is none)
-      l_run[b] = 0.f;      // this lane's share of the row sum
-    }
-
-    // Two staging register sets: set t % 2 carries tile t from its loads to its LDS store, so two
-    // tiles are in flight while a third is being consumed.
-    u32x4_t stage_k[2][2], stage_v[2][2];
-    // Page ids are fetched one tile ahead of the data they address (lane r holds page r of the
-    // tile), so that the data loads never wait behind an index load.
-    auto fetch_page_ids = [&](int t) -> int {
-      int pi = 4 * t + (lane & 3);
-      pi = pi < n_pages ? pi : n_pages - 1;  // never index past the chunk's pages
-      return p.kv_indices[kv_page0 + pi];
-    };
-    auto fetch_tile = [&](auto set_c, int ids) {
-      constexpr int SET = decltype(set_c)::value;
-#pragma unroll
-      for (int r = 0; r < 2; ++r) {
-        const int pg = __builtin_amdgcn_readlane(ids, 2 * r + st_page);
-        const int64_t page_off = pg * p.stride_page + kvh * p.stride_head;  // wave-uniform
-        stage_k[SET][r] = *reinterpret_cast<const u32x4_t*>(kpool + page_off + st_off);
-        stage_v[SET][r] = *reinterpret_cast<const u32x4_t*>(vpool + page_off + st_off);
-      }
-    };
-    auto store_tile = [&](auto set_c, int t) {
-      constexpr int SET = decltype(set_c)::value;
-      uint16_t* dk = lds_k + (t & 1) * (kTileKv * kRowElems);
-      uint16_t* dv = lds_v + (t & 1) * (kTileKv * kRowElemsV);
-      if constexpr (BF) {
-#pragma unroll
-        for (int r = 0; r < 2; ++r)
-          stage_v[SET][r] = u32x4_t{bf16x2_to_f16x2(stage_v[SET][r][0]), bf16x2_to_f16x2(stage_v[SET][r][1]),
-                                    bf16x2_to_f16x2(stage_v[SET][r][2]), bf16x2_to_f16x2(stage_v[SET][r][3])};
-      }
-      if (kTileKv * (t + 1) > kv_len) {  // CTA-uniform: only the chunk's last tile has rows past its end
-#pragma unroll
-        for (int r = 0; r < 2; ++r)
-          if (kTileKv * t + 32 * r + st_tok >= kv_len) stage_v[SET][r] = u32x4_t{0u, 0u, 0u, 0u};  // must not reach P.V
-      }
-#pragma unroll
-      for (int r = 0; r < 2; ++r) {
-        *reinterpret_cast<u32x4_t*>(&dk[st_lds_k + 32 * r * kRowElems]) = stage_k[SET][r];
-        *reinterpret_cast<u32x4_t*>(&dv[st_lds_v + 32 * r * kRowElemsV]) = stage_v[SET][r];
-      }
-    };
-    using set0_t = std::integral_constant<int, 0>;
-    using set1_t = std::integral_constant<int, 1>;
-
-    // Pipeline: while tile t is consumed from LDS buffer t % 2, tiles t + 1 and t + 2 are in the
-    // staging registers (loads issued two tiles ahead); after the products of tile t have been
-    // issued tile t + 1 is written to buffer (t + 1) % 2, its register set is reloaded with tile
-    // t + 3, and one CTA barrier closes the tile.
-    __syncthreads();   // the previous work item's last tile is no longer being read
-    // One tile: consume tile t, then hand tile t + 1 over from staging set SET = (t + 1) % 2.  The
-    // tile loop below is unrolled by two so that SET is a compile-time constant.
-    auto do_tile = [&](auto set_c, int t, int& ids_load, const int& ids_use) {
-      const uint16_t* tk = lds_k + (t & 1) * (kTileKv * kRowElems);
-      const uint16_t* tv = lds_v + (t & 1) * (kTileKv * kRowElemsV);
-#pragma unroll
-      for (int u = 0; u < 2; ++u) {
-        const int tok_base = kTileKv * t + 32 * u;  // chunk-local index of this 32-token step
-        if (tok_base >= kv_len || tok_base > blk_lim_hi[kRowBlocks - 1]) continue;  // nothing visible to this wavefront
-        // ---- S^T = K . Q^T: all eight A operands are requested before the first product ----
-        u32x4_t ka[8];
-        {
-          const uint16_t* krow = &tk[(32 * u + n) * kRowElems + c * 8];
-#pragma unroll
-          for (int s = 0; s < 8; ++s) ka[s] = *reinterpret_cast<const u32x4_t*>(krow + 16 * s);
-        }
-        f32x16_t sacc[kRowBlocks];
-#pragma unroll
-        for (int b = 0; b < kRowBlocks; ++b) {
-#pragma unroll
-          for (int r = 0; r < 16; ++r) sacc[b][r] = 0.f;
-#pragma unroll
-          for (int s = 0; s < 8; ++s) sacc[b] = mfma_qk<BF>(ka[s], qreg[b][s], sacc[b]);
-        }
-        // lane (n, c) now holds S^T[token 8 (r / 4) + 4 c + r % 4][row n of block b], r = 0..15
-
-        // ---- V^T operands: requested now, they arrive while the softmax runs on the vector ALU.
-        //      Operand (db, j) = columns d = 32 db + (lane % 32), token slots e = 0..7 <->
-        //      tokens 16 j + 8 (e / 4) + 4 c + e % 4 (the order P^T has in the S^T registers) ----
-        u32x4_t vt[4][2];
-        {
-          const uint16_t* vsrc = &tv[(32 * u + 4 * c + tr_row) * kRowElemsV + tr_col];
-#pragma unroll
-          for (int db = 0; db < 4; ++db)
-#pragma unroll
-            for (int j = 0; j < 2; ++j) {
-              const u32x2_t lo = lds_read_tr16(vsrc + (16 * j) * kRowElemsV + 32 * db);
-              const u32x2_t hi = lds_read_tr16(vsrc + (16 * j + 8) * kRowElemsV + 32 * db);
-              vt[db][j] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3);
-            }
-        }
-
-#pragma unroll
-        for (int b = 0; b < kRowBlocks; ++b) {
-          if (tok_base > blk_lim_hi[b]) continue;  // block wholly above the diagonal (wave-uniform)
-          // ---- online softmax on the 16 logits of its row this lane owns ----
-          float sv[16];  // raw logits q.k; the softmax scale is folded into the exponent below
-#pragma unroll
-          for (int r = 0; r < 16; ++r) sv[r] = sacc[b][r];
-          const bool need_mask = (tok_base + 32 > kv_len) || (tok_base + 31 > blk_lim_lo[b]);
-          if (need_mask) {
-            const int cap = min(lim[b], kv_len - 1);
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-              const int tkn = tok_base + 8 * (r >> 2) + 4 * c + (r & 3);
-              sv[r] = (tkn <= cap) ? sv[r] : NEG_INF;
-            }
-          }
-          // Optimistic softmax: exponentiate against the current reference first, and only if
-          // some P came out above 2^kLazyLog2 (or the row has no reference yet) find the row
-          // maximum, raise the reference, rescale, and redo the exponentials.  The reference
-          // only has to keep P inside fp16 range; o = O / l does not depend on it.  The common
-          // step therefore has no max reduction, no cross-lane exchange and no rescale.
-          f16x2_t h[8];
-          auto exponentiate = [&]() {
-#pragma unroll
-            for (int j = 0; j < 8; ++j) {
-              const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(sv[2 * j], p.scale_log2, neg_ms[b]));
-              const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(sv[2 * j + 1], p.scale_log2, neg_ms[b]));
-              h[j] = __builtin_convertvector(f32x2_t{p0, p1}, f16x2_t);  // one v_cvt_pk_f16_f32
-            }
-          };
-          exponentiate();
-          // P >= 0, so fp16 order is unsigned-integer order on the bit patterns (inf included)
-          u16x2_t hmax = __builtin_bit_cast(u16x2_t, h[0]);
-#pragma unroll
-          for (int j = 1; j < 8; ++j) hmax = __builtin_elementwise_max(hmax, __builtin_bit_cast(u16x2_t, h[j]));
-          const bool redo = hmax[0] > kLazyF16Bits || hmax[1] > kLazyF16Bits || m_run[b] == NEG_INF;
-          if (__builtin_amdgcn_ballot_w64(redo) != 0) {
-            float tmax = sv[0];
-#pragma unroll
-            for (int r = 1; r < 16; ++r) tmax = fmaxf(tmax, sv[r]);
-            tmax = halves_max(tmax);
-            const float m_new = fmaxf(m_run[b], tmax);
-            const float m_use = (m_new == NEG_INF) ? 0.f : m_new;  // row has seen nothing yet
-            const float alpha = __builtin_amdgcn_exp2f((m_run[b] - m_use) * p.scale_log2);
-            m_run[b] = m_new;
-            neg_ms[b] = -m_use * p.scale_log2;
-            l_run[b] *= alpha;
-#pragma unroll
-            for (int db = 0; db < 4; ++db) acc[b][db] *= alpha;
-            exponentiate();
-          }
-          // The row sum is taken over the fp16-rounded P that the second product consumes
-          // (v_dot2_f32_f16 with a vector of ones, fp32 accumulation): o = O / l is then an exact
-          // convex combination of V rows whatever the reference, and a single dominant key
-          // returns its V row exactly.
-          const f16x2_t ones = {static_cast<_Float16>(1.0f), static_cast<_Float16>(1.0f)};
-          float l = l_run[b];
-#pragma unroll
-          for (int j = 0; j < 8; ++j) l = __builtin_amdgcn_fdot2(h[j], ones, l, false);
-          l_run[b] = l;
-          const u32x4_t pb0 = {__builtin_bit_cast(uint32_t, h[0]), __builtin_bit_cast(uint32_t, h[1]),
-                               __builtin_bit_cast(uint32_t, h[2]), __builtin_bit_cast(uint32_t, h[3])};
-          const u32x4_t pb1 = {__builtin_bit_cast(uint32_t, h[4]), __builtin_bit_cast(uint32_t, h[5]),
-                               __builtin_bit_cast(uint32_t, h[6]), __builtin_bit_cast(uint32_t, h[7])};
-          // ---- O^T += V^T . P^T ----
-#pragma unroll
-          for (int db = 0; db < 4; ++db) {
-            acc[b][db] = mfma_pv(vt[db][0], pb0, acc[b][db]);
-            acc[b][db] = mfma_pv(vt[db][1], pb1, acc[b][db]);
-          }
-        }
-      }
-      // Hand the next tile over and reload its register set with the tile three ahead.  Every
-      // iteration issues the same loads in the same order (tiles past the end re-read the last
-      // page and are never stored), so the counted waits for the oldest loads leave the younger
-      // ones in flight; the index load goes first so that its consumer, one iteration later,
-      // does not wait for the data loads issued after it.
-      ids_load = fetch_page_ids(t + 4);
-      if (t + 1 < n_tiles) store_tile(set_c, t + 1);
-      fetch_tile(set_c, ids_use);
-      __syncthreads();  // tile t + 1 is visible; nobody reads tile t any more
-    };
-    if (n_tiles > 0) {  // one region, so that the loop is entered with this work item's Q loads known complete
-      const int ids0 = fetch_page_ids(0), ids1 = fetch_page_ids(1);
-      int ids_even = fetch_page_ids(2), ids_odd = fetch_page_ids(3);  // ids of the next even / odd tile to request
-      fetch_tile(set0_t{}, ids0);
-      fetch_tile(set1_t{}, ids1);
-      store_tile(set0_t{}, 0);
-      fetch_tile(set0_t{}, ids_even);
-      __syncthreads();
-      // A single-exit loop: with an odd tile count the last call finds no visible step and stores
-      // nothing, which is cheaper than a second exit that would make every counted wait assume
-      // the emptiest pipeline.
-      for (int t = 0; t < n_tiles; t += 2) {
-        do_tile(set1_t{}, t, ids_even, ids_odd);
-        do_tile(set0_t{}, t + 1, ids_odd, ids_even);
-      }
-    }
-
-    // ---- epilogue: o = O / l, lse = ln(sum exp) (Sec. 2.2) ----
-#pragma unroll
-    for (int b = 0; b < kRowBlocks; ++b) {
-      const float l = halves_sum(l_run[b]);
-      const bool live = l > 0.f;
-      const float inv = live ? 1.0f / l : 0.f;
-      const float lse_val =
-          live ? (m_run[b] * p.scale_log2 + __builtin_amdgcn_logf(l)) * 0.6931471805599453f : NEG_INF;
-      if (row_ok[b]) {
-        const int head = kvh * g + hh[b];
-        const int64_t final_row = static_cast<int64_t>(q_row0 + pos[b]) * H + head;
-        float* dst_o;
-        float* dst_lse;
-        if (out_slot < 0) {  // write-through (App. D.2)
-          dst_o = p.o + final_row * kHeadDim;
-          dst_lse = p.lse + final_row;
-        } else {
-          const int64_t row = (static_cast<int64_t>(out_slot) * p.t_pos + pos[b]) * H + head;
-          dst_o = p.part_o + row * kHeadDim;
-          dst_lse = p.part_lse + row;
-        }
-#pragma unroll
-        for (int db = 0; db < 4; ++db)
-#pragma unroll
-          for (int q = 0; q < 4; ++q) {
-            const int d0 = 32 * db + 8 * q + 4 * c;
-            const f32x4_t v = {acc[b][db][4 * q] * inv, acc[b][db][4 * q + 1] * inv, acc[b][db][4 * q + 2] * inv,
-                               acc[b][db][4 * q + 3] * inv};
-            *reinterpret_cast<f32x4_t*>(dst_o + d0) = v;
-            if (out_slot < 0 && p.o_cast != nullptr) {
-              uint16_t* dc = static_cast<uint16_t*>(p.o_cast) + final_row * kHeadDim + d0;
-              *reinterpret_cast<u32x2_t*>(dc) = u32x2_t{pack_out<BF>(v[0], v[1]), pack_out<BF>(v[2], v[3])};
-            }
-          }
-        if (c == 0) *dst_lse = lse_val;
-      }
-    }
+    __syncthreads();  // the previous work item is done with the tile buffers
+    // (the kernel's only argument sits at the start of its argument segment)
+    generic_work_item<BF>(reinterpret_cast<uint64_t>(__builtin_amdgcn_kernarg_segment_ptr()), q_row0, n_pos, kv_page0,
+                          kv_start, kv_len, diag0, out_slot);
   }
 }
 

@@ -384,11 +384,12 @@ def write(path, lines, name):
 
 if __name__ == '__main__':
     here = os.path.dirname(os.path.abspath(__file__))
+    out_dir = sys.argv[1] if len(sys.argv) > 1 else os.path.join(here, '..')
     for bf, name in ((True, 'bf16'), (False, 'f16')):
         lines = Gen(bf).program()
-        write(os.path.join(here, '..', 'append_loop_%s.inc' % name), lines, name)
+        write(os.path.join(out_dir, 'append_loop_%s.inc' % name), lines, name)
         n_mfma = sum(1 for l in lines if l.startswith('v_mfma'))
         print('%s: %d lines, %d matrix instructions, %d waits' % (name, len(lines), n_mfma, sum(1 for l in lines if l.startswith('s_waitcnt'))))
-    with open(os.path.join(here, '..', 'append_loop_clobbers.inc'), 'w') as f:
+    with open(os.path.join(out_dir, 'append_loop_clobbers.inc'), 'w') as f:
         f.write('// Generated by gen/gen_append_loop.py; do not edit by hand.\n')
         f.write(', '.join(clobbers()) + '\n')
