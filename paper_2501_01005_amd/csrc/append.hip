@@ -141,7 +141,8 @@ template <bool BF>
 __device__ __forceinline__ void run_scheduled_loop(int n_full, int n_tiles, int kv_len, int cap, int st_tok, int ids_clamp, const int32_t* page_ids, uint32_t k_lo,
                                                    uint32_t k_hi, uint32_t v_lo, uint32_t v_hi, uint32_t page_bytes,
                                                    float scale_log2, int st_page, uint64_t q_addr, uint32_t st_off_bytes,
-                                                   uint32_t k_read, uint32_t v_read, uint32_t k_write, uint32_t v_write,
+                                                   uint32_t k_off_bytes, uint32_t k_read, uint32_t k_swizzle,
+                                                   uint32_t v_read, uint32_t k_dma, uint32_t v_write,
                                                    uint32_t o_off, int row_flags, float* o_base, float* lse_base,
                                                    void* cast_base, int has_cast) {
   if constexpr (BF) {
@@ -150,8 +151,8 @@ __device__ __forceinline__ void run_scheduled_loop(int n_full, int n_tiles, int 
         :
         : [nf] "s"(n_full), [nt] "s"(n_tiles), [kvl] "s"(kv_len), [cap] "v"(cap), [stk] "v"(st_tok), [npg1] "s"(ids_clamp), [idp] "s"(page_ids), [kblo] "s"(k_lo), [kbhi] "s"(k_hi),
           [vblo] "s"(v_lo), [vbhi] "s"(v_hi), [sp] "s"(page_bytes), [sc] "s"(scale_log2), [stp] "s"(st_page),
-          [qp] "v"(q_addr), [so] "v"(st_off_bytes), [ka] "v"(k_read), [va] "v"(v_read), [wk] "v"(k_write),
-          [wv] "v"(v_write), [ooff] "v"(o_off), [rok] "v"(row_flags), [ob] "s"(o_base), [lb] "s"(lse_base),
+          [qp] "v"(q_addr), [so] "v"(st_off_bytes), [sok] "v"(k_off_bytes), [kb] "v"(k_read), [kxs] "v"(k_swizzle),
+          [va] "v"(v_read), [kd] "s"(k_dma), [wv] "v"(v_write), [ooff] "v"(o_off), [rok] "v"(row_flags), [ob] "s"(o_base), [lb] "s"(lse_base),
           [cb] "s"(cast_base), [oc] "s"(has_cast)
         :
 #include "append_loop_clobbers.inc"
@@ -162,8 +163,8 @@ __device__ __forceinline__ void run_scheduled_loop(int n_full, int n_tiles, int 
         :
         : [nf] "s"(n_full), [nt] "s"(n_tiles), [kvl] "s"(kv_len), [cap] "v"(cap), [stk] "v"(st_tok), [npg1] "s"(ids_clamp), [idp] "s"(page_ids), [kblo] "s"(k_lo), [kbhi] "s"(k_hi),
           [vblo] "s"(v_lo), [vbhi] "s"(v_hi), [sp] "s"(page_bytes), [sc] "s"(scale_log2), [stp] "s"(st_page),
-          [qp] "v"(q_addr), [so] "v"(st_off_bytes), [ka] "v"(k_read), [va] "v"(v_read), [wk] "v"(k_write),
-          [wv] "v"(v_write), [ooff] "v"(o_off), [rok] "v"(row_flags), [ob] "s"(o_base), [lb] "s"(lse_base),
+          [qp] "v"(q_addr), [so] "v"(st_off_bytes), [sok] "v"(k_off_bytes), [kb] "v"(k_read), [kxs] "v"(k_swizzle),
+          [va] "v"(v_read), [kd] "s"(k_dma), [wv] "v"(v_write), [ooff] "v"(o_off), [rok] "v"(row_flags), [ob] "s"(o_base), [lb] "s"(lse_base),
           [cb] "s"(cast_base), [oc] "s"(has_cast)
         :
 #include "append_loop_clobbers.inc"
@@ -580,15 +581,20 @@ append_kernel(const RunParams p) {
         const int64_t out_row = (final_out ? static_cast<int64_t>(q_row0 + pos_r)
                                            : static_cast<int64_t>(out_slot) * p.t_pos + pos_r) * H + head;
         const uint32_t st_off_bytes = static_cast<uint32_t>((st_tok_o & 15) * p.stride_tok + st_chunk_o * 8) * 2;
+        // K goes straight to LDS in packed 256-byte rows whose 16-byte chunks are XOR-swizzled by the
+        // row index (conflict-free operand reads without padding): LDS slot st_chunk of row st_tok
+        // holds chunk st_chunk ^ (st_tok % 16) of that token
+        const uint32_t k_off_bytes =
+            static_cast<uint32_t>((st_tok_o & 15) * p.stride_tok + ((st_chunk_o ^ st_tok_o) & 15) * 8) * 2;
         __syncthreads();  // the previous work item is done with the tile buffers
         run_scheduled_loop<BF>(n_full, (kv_len + kTileKv - 1) / kTileKv, kv_len, last_seen - 4 * c_o, st_tok_o,
                                (chunk_pages - 1) * 4, p.kv_indices + kv_page0, static_cast<uint32_t>(k_base),
                                static_cast<uint32_t>(k_base >> 32), static_cast<uint32_t>(v_base),
                                static_cast<uint32_t>(v_base >> 32), static_cast<uint32_t>(page_bytes), p.scale_log2,
-                               __builtin_amdgcn_readfirstlane(wave_o >> 2), q_addr, st_off_bytes,
-                               lds0 + n_o * (kRowElems * 2) + c_o * 16,
+                               __builtin_amdgcn_readfirstlane(wave_o >> 2), q_addr, st_off_bytes, k_off_bytes,
+                               lds0 + n_o * 256 + ((c_o ^ n_o) & 1) * 16, ((n_o >> 1) & 7) * 32,
                                lds0 + kLdsVOffset + (4 * c_o + tr_row_o) * (kRowElemsV * 2) + tr_col_o * 2,
-                               lds0 + st_tok_o * (kRowElems * 2) + st_chunk_o * 16,
+                               lds0 + __builtin_amdgcn_readfirstlane(wave_o) * 1024,
                                lds0 + kLdsVOffset + st_tok_o * (kRowElemsV * 2) + st_chunk_o * 16,
                                static_cast<uint32_t>(out_row * (kHeadDim * 4) + c_o * 16),
                                pos_r < n_pos ? (c_o == 0 ? 3 : 1) : 0, final_out ? p.o : p.part_o,

@@ -61,6 +61,10 @@ class Emitter:
             self._wait_for(used)
             self.out.append(text)
             self.lgkm.append(set())
+        elif op.startswith('global_load_lds'):  # lands in LDS, not in registers: waited for by wait_lds_loads()
+            self._wait_for(used)
+            self.out.append(text)
+            self.vm.append({('lds', len(self.out))})
         elif op.startswith('global_load'):
             self._wait_for(used)
             self.out.append(text)
@@ -71,6 +75,14 @@ class Emitter:
         else:
             self._wait_for(used)
             self.out.append(text)
+
+    def wait_lds_loads(self):
+        """counted wait for every global load in flight whose destination is LDS"""
+        pending = set()
+        for d in self.vm:
+            pending |= set(x for x in d if x[0] == 'lds')
+        if pending:
+            self._wait_for(pending)
 
     def drain(self, lgkm=True, vm=True):
         parts = []

@@ -32,6 +32,7 @@ from emit import Emitter  # noqa: E402
 NINF = 16
 NEGMS, MRUN, LSUM, ONES, MAXT, X0, X1 = 17, 18, 19, 20, 21, 22, 23
 ACC, Q, KA, VT, S0, S1, H, T, ST = 24, 88, 120, 152, 184, 200, 216, 224, 240
+KAD = ST                       # ST..ST+7: LDS addresses of this lane's eight K operand reads; ST+8..ST+15: staged V
 FIRST_FIXED_VGPR = 16
 # ---- fixed scalar registers ----
 S_T, S_TMP = 64, 65
@@ -40,10 +41,13 @@ S_IDS, S_IDN = 68, 72          # page ids of the tile to fetch next / of the one
 S_PG0, S_PG1, S_LO, S_HI, S_KA, S_VA, S_THR, S_REM = 76, 77, 78, 79, 80, 82, 84, 85
 S_IDA, S_IDB = 88, 92          # two more page id groups, start-up only
 S_EXEC = 96
-FIXED_SGPRS = list(range(64, 98))
+S_IDK = 98                     # page ids of the tile whose K goes to LDS next
+S_M0 = 97                      # saved m0 (the register doubles as half of S_EXEC, which is used only after m0 is restored)
+FIXED_SGPRS = list(range(64, 102))
 
-KROW, VROW = 272, 288          # LDS row pitch in bytes (K, V)
+KROW, VROW = 256, 288          # LDS row pitch in bytes: K rows are packed (16-byte chunks XOR-swizzled by row), V rows padded
 KTILE, VTILE = 64 * KROW, 64 * VROW
+V_BASE = 3 * 64 * 272          # V buffers start where the generic path has them
 NBUF = 3
 LAZY_THR = 0x5C005C00          # fp16 2^8 in both halves: P above it raises the reference
 
@@ -127,7 +131,7 @@ class Gen:
         return ['v_dot2_f32_f16 v%d, v%d, v%d, v%d' % (LSUM, H + j, ONES, LSUM) for j in range(8)]
 
     def k_reads(self, buf, u):
-        return ['ds_read_b128 %s, %%[ka] offset:%d' % (vr(KA + 4 * s, 4), buf * KTILE + u * 32 * KROW + 32 * s)
+        return ['ds_read_b128 %s, v%d offset:%d' % (vr(KA + 4 * s, 4), KAD + s, buf * KTILE + u * 32 * KROW)
                 for s in range(8)]
 
     def v_reads(self, buf, u):
@@ -152,7 +156,6 @@ class Gen:
     def stores(self, buf, base=ST):
         ops = []
         for r in range(2):
-            ops.append('ds_write_b128 %%[wk], %s offset:%d' % (vr(base + 4 * r, 4), buf * KTILE + r * 32 * KROW))
             ops.append('ds_write_b128 %%[wv], %s offset:%d' % (vr(base + 8 + 4 * r, 4), buf * VTILE + r * 32 * VROW))
         return ops
 
@@ -169,18 +172,31 @@ class Gen:
                 ops.append('v_cndmask_b32 v%d, 0, v%d, vcc' % (x, x))
         return ops
 
+    def page_select(self, ids):
+        return ['s_cmp_eq_u32 %[stp], 0',
+                's_cselect_b32 s%d, s%d, s%d' % (S_PG0, ids, ids + 1),
+                's_cselect_b32 s%d, s%d, s%d' % (S_PG1, ids + 2, ids + 3)]
+
     def fetch(self, ids=S_IDS, base=ST):
-        """global loads of the tile whose four page ids are in s[ids..+3]; this thread's two
-        pages are 2 r + st_page, r = 0, 1"""
-        ops = ['s_cmp_eq_u32 %[stp], 0',
-               's_cselect_b32 s%d, s%d, s%d' % (S_PG0, ids, ids + 1),
-               's_cselect_b32 s%d, s%d, s%d' % (S_PG1, ids + 2, ids + 3)]
+        """global loads of the V rows of the tile whose four page ids are in s[ids..+3]; this
+        thread's two pages are 2 r + st_page, r = 0, 1"""
+        ops = self.page_select(ids)
+        for r, pg in enumerate((S_PG0, S_PG1)):
+            ops += ['s_mul_hi_u32 s%d, s%d, %%[sp]' % (S_HI, pg), 's_mul_i32 s%d, s%d, %%[sp]' % (S_LO, pg),
+                    's_add_u32 s%d, %%[vblo], s%d' % (S_VA, S_LO), 's_addc_u32 s%d, %%[vbhi], s%d' % (S_VA + 1, S_HI),
+                    'global_load_dwordx4 %s, %%[so], s[%d:%d]' % (vr(base + 8 + 4 * r, 4), S_VA, S_VA + 1)]
+        return ops
+
+    def k_to_lds(self, ids, buf):
+        """K rows of that tile straight into LDS buffer `buf` (no registers, no LDS store
+        instruction): a wavefront's load lands as 1 KB = its four consecutive 256-byte rows at m0,
+        lane l at m0 + 16 l, and each lane fetches the chunk that the swizzle puts there"""
+        ops = self.page_select(ids)
         for r, pg in enumerate((S_PG0, S_PG1)):
             ops += ['s_mul_hi_u32 s%d, s%d, %%[sp]' % (S_HI, pg), 's_mul_i32 s%d, s%d, %%[sp]' % (S_LO, pg),
                     's_add_u32 s%d, %%[kblo], s%d' % (S_KA, S_LO), 's_addc_u32 s%d, %%[kbhi], s%d' % (S_KA + 1, S_HI),
-                    's_add_u32 s%d, %%[vblo], s%d' % (S_VA, S_LO), 's_addc_u32 s%d, %%[vbhi], s%d' % (S_VA + 1, S_HI),
-                    'global_load_dwordx4 %s, %%[so], s[%d:%d]' % (vr(base + 4 * r, 4), S_KA, S_KA + 1),
-                    'global_load_dwordx4 %s, %%[so], s[%d:%d]' % (vr(base + 8 + 4 * r, 4), S_VA, S_VA + 1)]
+                    's_add_u32 m0, %%[kd], %d' % (buf * KTILE + r * 32 * KROW), 's_nop 0',
+                    'global_load_lds_dwordx4 %%[sok], s[%d:%d]' % (S_KA, S_KA + 1)]
         return ops
 
     def ids_load(self, ahead, dst=S_IDN):
@@ -202,7 +218,9 @@ class Gen:
         return ops
 
     def ids_take(self):
-        return ['s_mov_b64 s[%d:%d], s[%d:%d]' % (S_IDS, S_IDS + 1, S_IDN, S_IDN + 1),
+        return ['s_mov_b64 s[%d:%d], s[%d:%d]' % (S_IDK, S_IDK + 1, S_IDS, S_IDS + 1),
+                's_mov_b64 s[%d:%d], s[%d:%d]' % (S_IDK + 2, S_IDK + 3, S_IDS + 2, S_IDS + 3),
+                's_mov_b64 s[%d:%d], s[%d:%d]' % (S_IDS, S_IDS + 1, S_IDN, S_IDN + 1),
                 's_mov_b64 s[%d:%d], s[%d:%d]' % (S_IDS + 2, S_IDS + 3, S_IDN + 2, S_IDN + 3)]
 
     def row_max(self, Sc):
@@ -242,11 +260,12 @@ class Gen:
         # canonical state after the barrier: no LDS operation in flight, the four loads of the
         # staged tile (K0, V0, K1, V1) possibly still in flight
         e.lgkm = []
-        e.vm = [set(('v', ST + 4 * r + i) for i in range(4)) for r in (0, 2, 1, 3)]
+        e.vm = [set(('v', ST + 8 + 4 * r + i) for i in range(4)) for r in (0, 1)]
         for u in range(2):
             Sc, Sn = (S0, S1) if u == 0 else (S1, S0)
             # block 1
-            head = self.ids_load(4) if u == 0 else []  # consumed after the barrier: long there by then
+            # the tile after next: its K goes to the LDS buffer that the barrier before this tile freed
+            head = self.k_to_lds(S_IDK, wr) + self.ids_load(4) if u == 0 else []
             soft = (self.mask(Sc, u) if masked else []) + self.exps(Sc) + self.lazy_check()
             spread(e, [self.qk(Sn, s) for s in range(8)], head + merge_even(self.v_reads(cur, u), soft))
             e.raw('s_cbranch_vccnz raise_%s%d%d_%s' % (kind, k, u, lbl))
@@ -258,6 +277,7 @@ class Gen:
             else:
                 rest = merge_even(kn, self.rowsum() + self.v_zero_tail(2)) + self.stores(wr) + self.fetch()
             spread(e, [self.pv(db, j) for j in range(2) for db in range(4)], rest)
+        e.wait_lds_loads()
         e.emit('s_barrier')
         for o in self.ids_take():
             e.raw(o)
@@ -277,6 +297,7 @@ class Gen:
         e = self.e
         lbl = '%='
         # constants and zero state
+        e.raw('s_mov_b32 s%d, m0' % S_M0)
         e.raw('s_mov_b32 s%d, 0' % S_T)
         e.raw('s_mov_b32 s%d, 0x%x' % (S_THR, LAZY_THR))
         e.raw('v_mov_b32 v%d, 0x3c003c00' % ONES)
@@ -287,21 +308,27 @@ class Gen:
             e.raw('v_mov_b32 v%d, 0' % (ACC + i))
         for s in range(8):
             e.emit('global_load_dwordx4 %s, %%[qp], off offset:%d' % (vr(Q + 4 * s, 4), 32 * s))
-        # start-up: the page ids of tiles 0..3 in one go, then tiles 0, 1, 2 in flight together (tiles
-        # 0 and 1 borrow the operand registers as staging), tiles 0 and 1 into LDS
-        for t, dst in enumerate((S_IDA, S_IDB, S_IDS, S_IDN)):
+        # the eight K operand reads of a lane: row n, chunk (2 s + c) ^ (n % 16) -> kb + (32 s ^ kxs)
+        for s_ in range(8):
+            e.raw('v_xor_b32 v%d, %d, %%[kxs]' % (KAD + s_, 32 * s_))
+            e.raw('v_add_u32 v%d, v%d, %%[kb]' % (KAD + s_, KAD + s_))
+        # start-up: the page ids of tiles 0..3 in one go, then K of tiles 0 and 1 straight into LDS and V of
+        # tiles 0, 1, 2 in flight together (tiles 0 and 1 borrow operand registers as staging)
+        for t, dst in enumerate((S_IDA, S_IDB, S_IDK, S_IDS)):
             for o in self.ids_load(t, dst):
                 e.raw(o)
         e.raw('s_waitcnt lgkmcnt(0)')
-        for ids, base in ((S_IDA, VT), (S_IDB, KA), (S_IDS, ST)):
+        for t, ids in ((0, S_IDA), (1, S_IDB)):
+            for o in self.k_to_lds(ids, t):
+                e.emit(o)
+        for ids, base in ((S_IDA, VT), (S_IDB, KA), (S_IDK, ST)):
             for o in self.fetch(ids, base):
                 e.emit(o)
         for t, base in ((0, VT), (1, KA)):
             for o in self.v_convert(base) + self.v_zero_tail(t, base) + self.stores(t, base):
                 e.emit(o)
+        e.wait_lds_loads()
         e.emit('s_barrier')
-        for o in self.ids_take():
-            e.raw(o)
         # first step: S^T(0, 0), the K operands of step (0, 1), the first reference
         for o in self.k_reads(0, 0):
             e.emit(o)
@@ -333,6 +360,7 @@ class Gen:
         # o = O / l, lse = ln(sum exp) = (reference * scale_log2 + log2 l) * ln 2
         e.label('exit_%s' % lbl)
         e.raw('s_waitcnt vmcnt(0)')
+        e.raw('s_mov_b32 m0, s%d' % S_M0)
         e.raw('s_nop 15')
         e.raw('s_nop 15')
         for o in ['v_mov_b32 v%d, v%d' % (X0, LSUM), 'v_mov_b32 v%d, v%d' % (X1, LSUM), 's_nop 1',
