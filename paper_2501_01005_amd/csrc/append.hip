@@ -36,7 +36,7 @@ typedef __attribute__((ext_vector_type(4))) uint32_t u32x4_t;
 
 constexpr int kTileKv = 64;        // tokens per LDS tile
 constexpr int kRowElems = 136;     // K tile row pitch in 16-bit elements (272 B): rows 4 banks apart, conflict-free b128 reads
-constexpr int kRowElemsV = 144;    // V tile row pitch (288 B): rows 8 banks apart, conflict-free transpose reads
+constexpr int kRowElemsV = 160;    // V tile row pitch (320 B): rows 16 banks apart, conflict-free transpose reads
 constexpr int kCtaThreads = 512;   // 8 wavefronts, 32 query rows each
 constexpr int kRowBlocks = 1;       // 32-row blocks per wavefront; CTA tile = 8 * 32 * kRowBlocks fused rows
 constexpr int kLoopBuffers = 3;                                 // LDS tile buffers of the scheduled loop

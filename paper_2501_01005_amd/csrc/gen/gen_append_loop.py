@@ -45,7 +45,7 @@ S_IDK = 98                     # page ids of the tile whose K goes to LDS next
 S_M0 = 97                      # saved m0 (the register doubles as half of S_EXEC, which is used only after m0 is restored)
 FIXED_SGPRS = list(range(64, 102))
 
-KROW, VROW = 256, 288          # LDS row pitch in bytes: K rows are packed (16-byte chunks XOR-swizzled by row), V rows padded
+KROW, VROW = 256, 320          # LDS row pitch in bytes: K rows are packed (16-byte chunks XOR-swizzled by row), V rows padded
 KTILE, VTILE = 64 * KROW, 64 * VROW
 V_BASE = 3 * 64 * 272          # V buffers start where the generic path has them
 NBUF = 3
