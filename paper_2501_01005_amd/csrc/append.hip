@@ -1,9 +1,8 @@
 // Paged append / prefill attention for gfx950 (causal or not): query tile = 256 fused rows
 // (256/g consecutive positions x g query heads of one kv head, App. A), one CTA of eight
 // wavefronts per CU, each wavefront owning 32 rows.  K/V tiles of 64 tokens (four 16-token
-// pages, gathered through kv_indices, Sec. 3.2.1) are staged in a double-buffered LDS tile and
-// shared by the eight wavefronts (one CTA barrier per tile, loads issued two tiles ahead); both
-// products run on the matrix cores:
+// pages, gathered through kv_indices, Sec. 3.2.1) are staged in LDS and shared by the eight
+// wavefronts; both products run on the matrix cores:
 //   S^T[token][row] = K . Q^T      v_mfma_f32_32x32x16   A = K rows from LDS, B = Q^T in registers
 //   O^T[d][row]    += V^T . P^T    v_mfma_f32_32x32x16   A = V^T read from the row-major V tile with
 //                                                        the LDS transpose read ds_read_b64_tr_b16,
@@ -12,9 +11,15 @@
 // of the step's 32 tokens in each half of the wavefront: the row maximum (needed only when the
 // reference is raised) is an in-lane reduction plus one cross-lane exchange, and P never
 // moves between lanes.  The contraction index of the second product is (lane half, register)
-// on both operands, so its order inside the instruction does not matter.  The 32x32x16 shape
-// is used because a single wavefront issues it at ~90 % of the matrix pipe's peak, against
-// ~55 % for 16x16x32 (measured), which leaves issue slots for the softmax.
+// on both operands, so its order inside the instruction does not matter.
+//
+// A work item (one query tile x one KV chunk of the plan, Sec. 3.3.1) runs on one of two paths:
+//   * the scheduled loop: generated assembly (gen/gen_append_loop.py -> append_loop_*.inc) that
+//     interleaves, inside every wavefront, the matrix instructions of one step with the softmax
+//     and the LDS traffic of its neighbours, over triple-buffered tiles; it takes every chunk
+//     of at least 128 tokens whose first tile all rows of the CTA see, and does the whole item
+//     including masked tiles, epilogue and stores;
+//   * the generic path (generic_work_item): compiler-scheduled, any length and masking.
 //
 // P is rounded to fp16 (11 significant bits).  For bf16 inputs V is converted to fp16 while it
 // is staged into LDS (exact for 2^-14 <= |v| <= 65504, saturating above, absolute error
