@@ -47,6 +47,9 @@ constexpr int kRowBlocks = 1;       // 32-row blocks per wavefront; CTA tile = 8
 constexpr int kLoopBuffers = 3;                                 // LDS tile buffers of the scheduled loop
 constexpr int kLdsVOffset = kLoopBuffers * kTileKv * kRowElems * 2;
 constexpr int kLdsBytes = kLdsVOffset + kLoopBuffers * kTileKv * kRowElemsV * 2;
+constexpr int kEpilogueRowBytes = 288;                          // row pitch of the loop's output transpose area
+constexpr int kEpilogueLdsBytes = 32 * kEpilogueRowBytes;       // per wavefront; aliases the tile buffers
+static_assert((kCtaThreads / 64) * kEpilogueLdsBytes <= kLdsBytes, "output transpose area fits");
 constexpr int kLoopMinTokens = 2 * kTileKv;                     // shorter chunks: generic path only (its start-up is cheaper)
 constexpr int kLazyLog2 = 8;                                    // P may reach 2^8 before the reference is raised
 constexpr uint16_t kLazyF16Bits = (15 + kLazyLog2) << 10;       // fp16 bit pattern of 2^kLazyLog2
@@ -138,10 +141,12 @@ __device__ __forceinline__ uint32_t lds_offset(const void* p) {
 // register map and schedule).  `cap` = chunk-local index of the last token this lane's row sees,
 // minus 4 * (lane / 32).  Starts from the empty attention state, reads Q through `q_addr`,
 // gathers pages through `page_ids` (the chunk's ids; `ids_clamp` = byte offset of the chunk's
-// last one) and finishes the work item: this lane's 64 values of o go to o_base + o_off bytes
-// (o_off = 512 * output row + 16 * (lane / 32)) if row_flags & 1, lse to lse_base[output row] if
-// row_flags & 2, and, if has_cast, o in the input type to cast_base + o_off / 2.  Every
-// wavefront of the CTA must call it with the same tile counts (it contains CTA barriers).
+// last one) and finishes the work item.  Output row of tile row R (position R >> g_log2, head
+// R % g) is row_base + position * num_qo_heads + head, written if position < n_pos: o (512 B per
+// row) to o_base, and, if has_cast, o in the input type to cast_base; the rows pass through the
+// wavefront's LDS area (epi_write: this lane's accumulator column, epi_read / epi_chunk: the
+// 16-byte piece it stores).  lse goes to lse_base[o_off / 512] from lanes with row_flags & 2.
+// Every wavefront of the CTA must call it with the same tile counts (it contains CTA barriers).
 template <bool BF>
 __device__ __forceinline__ void run_scheduled_loop(int n_full, int n_tiles, int kv_len, int cap, int st_tok, int ids_clamp, const int32_t* page_ids, uint32_t k_lo,
                                                    uint32_t k_hi, uint32_t v_lo, uint32_t v_hi, uint32_t page_bytes,
@@ -149,7 +154,9 @@ __device__ __forceinline__ void run_scheduled_loop(int n_full, int n_tiles, int 
                                                    uint32_t k_off_bytes, uint32_t k_read, uint32_t k_swizzle,
                                                    uint32_t v_read, uint32_t k_dma, uint32_t v_write,
                                                    uint32_t o_off, int row_flags, float* o_base, float* lse_base,
-                                                   void* cast_base, int has_cast) {
+                                                   void* cast_base, int has_cast, uint32_t epi_write, uint32_t epi_read,
+                                                   uint32_t epi_chunk, int g_log2, int num_qo_heads, int row_base,
+                                                   int n_pos) {
   if constexpr (BF) {
     asm volatile(
 #include "append_loop_bf16.inc"
@@ -158,7 +165,8 @@ __device__ __forceinline__ void run_scheduled_loop(int n_full, int n_tiles, int 
           [vblo] "s"(v_lo), [vbhi] "s"(v_hi), [sp] "s"(page_bytes), [sc] "s"(scale_log2), [stp] "s"(st_page),
           [qp] "v"(q_addr), [so] "v"(st_off_bytes), [sok] "v"(k_off_bytes), [kb] "v"(k_read), [kxs] "v"(k_swizzle),
           [va] "v"(v_read), [kd] "s"(k_dma), [wv] "v"(v_write), [ooff] "v"(o_off), [rok] "v"(row_flags), [ob] "s"(o_base), [lb] "s"(lse_base),
-          [cb] "s"(cast_base), [oc] "s"(has_cast)
+          [cb] "s"(cast_base), [oc] "s"(has_cast), [ew] "v"(epi_write), [er] "v"(epi_read), [l16] "v"(epi_chunk),
+          [gl] "s"(g_log2), [hq] "s"(num_qo_heads), [rb] "s"(row_base), [np] "s"(n_pos)
         :
 #include "append_loop_clobbers.inc"
     );
@@ -170,7 +178,8 @@ __device__ __forceinline__ void run_scheduled_loop(int n_full, int n_tiles, int 
           [vblo] "s"(v_lo), [vbhi] "s"(v_hi), [sp] "s"(page_bytes), [sc] "s"(scale_log2), [stp] "s"(st_page),
           [qp] "v"(q_addr), [so] "v"(st_off_bytes), [sok] "v"(k_off_bytes), [kb] "v"(k_read), [kxs] "v"(k_swizzle),
           [va] "v"(v_read), [kd] "s"(k_dma), [wv] "v"(v_write), [ooff] "v"(o_off), [rok] "v"(row_flags), [ob] "s"(o_base), [lb] "s"(lse_base),
-          [cb] "s"(cast_base), [oc] "s"(has_cast)
+          [cb] "s"(cast_base), [oc] "s"(has_cast), [ew] "v"(epi_write), [er] "v"(epi_read), [l16] "v"(epi_chunk),
+          [gl] "s"(g_log2), [hq] "s"(num_qo_heads), [rb] "s"(row_base), [np] "s"(n_pos)
         :
 #include "append_loop_clobbers.inc"
     );
@@ -604,7 +613,13 @@ append_kernel(const RunParams p) {
                                static_cast<uint32_t>(out_row * (kHeadDim * 4) + c_o * 16),
                                pos_r < n_pos ? (c_o == 0 ? 3 : 1) : 0, final_out ? p.o : p.part_o,
                                final_out ? p.lse : p.part_lse, p.o_cast,
-                               __builtin_amdgcn_readfirstlane(final_out && p.o_cast != nullptr ? 1 : 0));
+                               __builtin_amdgcn_readfirstlane(final_out && p.o_cast != nullptr ? 1 : 0),
+                               lds0 + wave_o * kEpilogueLdsBytes + n_o * kEpilogueRowBytes + c_o * 16,
+                               lds0 + wave_o * kEpilogueLdsBytes + ((tid_o >> 4) & 3) * kEpilogueRowBytes + st_chunk_o * 16,
+                               st_chunk_o * 16, g_log2, H,
+                               static_cast<int>((final_out ? static_cast<int64_t>(q_row0)
+                                                           : static_cast<int64_t>(out_slot) * p.t_pos) * H + kvh * g),
+                               n_pos);
         continue;  // the work item is finished
       }
     }

@@ -41,9 +41,9 @@ S_IDS, S_IDN = 68, 72          # page ids of the tile to fetch next / of the one
 S_PG0, S_PG1, S_LO, S_HI, S_KA, S_VA, S_THR, S_REM = 76, 77, 78, 79, 80, 82, 84, 85
 S_IDA, S_IDB = 88, 92          # two more page id groups, start-up only
 S_EXEC = 96
-S_IDK = 98                     # page ids of the tile whose K goes to LDS next
+S_IDK = 88                     # page ids of the tile whose K goes to LDS next (takes over S_IDA after start-up)
 S_M0 = 97                      # saved m0 (the register doubles as half of S_EXEC, which is used only after m0 is restored)
-FIXED_SGPRS = list(range(64, 102))
+FIXED_SGPRS = list(range(64, 98))
 
 KROW, VROW = 256, 320          # LDS row pitch in bytes: K rows are packed (16-byte chunks XOR-swizzled by row), V rows padded
 KTILE, VTILE = 64 * KROW, 64 * VROW
@@ -314,20 +314,22 @@ class Gen:
             e.raw('v_add_u32 v%d, v%d, %%[kb]' % (KAD + s_, KAD + s_))
         # start-up: the page ids of tiles 0..3 in one go, then K of tiles 0 and 1 straight into LDS and V of
         # tiles 0, 1, 2 in flight together (tiles 0 and 1 borrow operand registers as staging)
-        for t, dst in enumerate((S_IDA, S_IDB, S_IDK, S_IDS)):
+        for t, dst in enumerate((S_IDA, S_IDB, S_IDN, S_IDS)):
             for o in self.ids_load(t, dst):
                 e.raw(o)
         e.raw('s_waitcnt lgkmcnt(0)')
         for t, ids in ((0, S_IDA), (1, S_IDB)):
             for o in self.k_to_lds(ids, t):
                 e.emit(o)
-        for ids, base in ((S_IDA, VT), (S_IDB, KA), (S_IDK, ST)):
+        for ids, base in ((S_IDA, VT), (S_IDB, KA), (S_IDN, ST)):
             for o in self.fetch(ids, base):
                 e.emit(o)
         for t, base in ((0, VT), (1, KA)):
             for o in self.v_convert(base) + self.v_zero_tail(t, base) + self.stores(t, base):
                 e.emit(o)
         e.wait_lds_loads()
+        e.raw('s_mov_b64 s[%d:%d], s[%d:%d]' % (S_IDK, S_IDK + 1, S_IDN, S_IDN + 1))
+        e.raw('s_mov_b64 s[%d:%d], s[%d:%d]' % (S_IDK + 2, S_IDK + 3, S_IDN + 2, S_IDN + 3))
         e.emit('s_barrier')
         # first step: S^T(0, 0), the K operands of step (0, 1), the first reference
         for o in self.k_reads(0, 0):
@@ -357,7 +359,12 @@ class Gen:
                         e.raw(o)
                     e.raw('s_branch back_%s%d%d_%s' % (kind, k, u, lbl))
         # epilogue (every wavefront is past its last tile read: the exit follows a barrier):
-        # o = O / l, lse = ln(sum exp) = (reference * scale_log2 + log2 l) * ln 2
+        # o = O / l, lse = ln(sum exp) = (reference * scale_log2 + log2 l) * ln 2.  The accumulators
+        # hold 16-byte pieces of 32 different rows per lane column, which would make every output
+        # store touch 32 rows; they go through a wavefront-private LDS area (32 rows x 288 B, one
+        # half of the head dimension at a time) so that a store instruction writes four rows of
+        # 256 contiguous bytes.
+        EPITCH = 288
         e.label('exit_%s' % lbl)
         e.raw('s_waitcnt vmcnt(0)')
         e.raw('s_mov_b32 m0, s%d' % S_M0)
@@ -368,33 +375,56 @@ class Gen:
                   # (a transcendental result needs a wait state before an ordinary vector instruction reads it)
                   'v_log_f32 v%d, v%d' % (X1, LSUM), 'v_rcp_f32 v%d, v%d' % (X0, LSUM), 's_nop 1',
                   'v_fma_f32 v%d, v%d, %%[sc], v%d' % (X1, MRUN, X1), 'v_mul_f32 v%d, 0x3f317218, v%d' % (X1, X1),
-                  # rows past the end of the query tile are not stored
-                  'v_and_b32 v%d, 1, %%[rok]' % MAXT, 'v_cmp_ne_u32 vcc, 0, v%d' % MAXT,
-                  's_and_saveexec_b64 s[%d:%d], vcc' % (S_EXEC, S_EXEC + 1)]:
+                  's_mov_b64 s[%d:%d], exec' % (S_EXEC, S_EXEC + 1),
+                  # one lane per live row writes lse
+                  'v_and_b32 v%d, 2, %%[rok]' % MAXT, 'v_cmp_ne_u32 vcc, 0, v%d' % MAXT, 's_and_b64 exec, exec, vcc',
+                  'v_lshrrev_b32 v%d, 9, %%[ooff]' % T, 'v_lshlrev_b32 v%d, 2, v%d' % (T, T),
+                  'global_store_dword v%d, v%d, %%[lb] nt' % (T, X1), 's_mov_b64 exec, s[%d:%d]' % (S_EXEC, S_EXEC + 1)]:
             e.raw(o)
         for i in range(64):
             e.raw('v_mul_f32 v%d, v%d, v%d' % (ACC + i, ACC + i, X0))
-        for db in range(4):
-            for q in range(4):
-                e.raw('global_store_dwordx4 %%[ooff], %s, %%[ob] offset:%d' % (vr(ACC + 16 * db + 4 * q, 4), 128 * db + 32 * q))
-        e.raw('s_cmp_eq_u32 %[oc], 0')
-        e.raw('s_cbranch_scc1 nocast_%s' % lbl)
-        e.raw('v_lshrrev_b32 v%d, 1, %%[ooff]' % T)
-        cvt = 'v_cvt_pk_bf16_f32' if self.bf else 'v_cvt_pk_f16_f32'
-        for db in range(4):
-            for q in range(4):
-                a = ACC + 16 * db + 4 * q
-                t = T + 2 + 2 * ((4 * db + q) % 7)
-                e.raw('%s v%d, v%d, v%d' % (cvt, t, a, a + 1))
-                e.raw('%s v%d, v%d, v%d' % (cvt, t + 1, a + 2, a + 3))
-                e.raw('global_store_dwordx2 v%d, %s, %%[cb] offset:%d' % (T, vr(t, 2), 64 * db + 16 * q))
-        e.label('nocast_%s' % lbl)
-        # one lane per row writes lse
-        for o in ['s_mov_b64 exec, s[%d:%d]' % (S_EXEC, S_EXEC + 1), 'v_and_b32 v%d, 2, %%[rok]' % MAXT,
-                  'v_cmp_ne_u32 vcc, 0, v%d' % MAXT, 's_and_saveexec_b64 s[%d:%d], vcc' % (S_EXEC, S_EXEC + 1),
-                  'v_lshrrev_b32 v%d, 9, %%[ooff]' % T, 'v_lshlrev_b32 v%d, 2, v%d' % (T, T),
-                  'global_store_dword v%d, v%d, %%[lb]' % (T, X1), 's_mov_b64 exec, s[%d:%d]' % (S_EXEC, S_EXEC + 1)]:
+        # store instruction k of a half covers tile rows 32 w + 4 k + lane / 16: their output byte offsets (KA + k),
+        # halved for the rounded copy (S0 + k), and whether the row exists (scalar masks)
+        OFF, COFF, ROW0 = KA, S0, T
+        masks = [S_IDA, S_IDA + 2, S_IDB, S_IDB + 2, S_IDS, S_IDS + 2, S_IDN, S_IDN + 2]
+        for o in ['v_lshrrev_b32 v%d, 2, %%[stk]' % ROW0, 'v_lshlrev_b32 v%d, 5, v%d' % (ROW0, ROW0),
+                  'v_and_b32 v%d, 3, %%[stk]' % (T + 1), 'v_or_b32 v%d, v%d, v%d' % (ROW0, ROW0, T + 1)]:
             e.raw(o)
+        for k in range(8):
+            R, P, B = T + 2, T + 3, T + 4
+            for o in ['v_add_u32 v%d, %d, v%d' % (R, 4 * k, ROW0), 'v_lshrrev_b32 v%d, %%[gl], v%d' % (P, R),
+                      'v_lshlrev_b32 v%d, %%[gl], v%d' % (B, P), 'v_sub_u32 v%d, v%d, v%d' % (B, R, B),
+                      'v_mad_u32_u24 v%d, v%d, %%[hq], v%d' % (B, P, B), 'v_add_u32 v%d, %%[rb], v%d' % (B, B),
+                      'v_lshlrev_b32 v%d, 9, v%d' % (B, B), 'v_add_u32 v%d, v%d, %%[l16]' % (OFF + k, B),
+                      'v_lshrrev_b32 v%d, 1, v%d' % (COFF + k, OFF + k),
+                      'v_cmp_gt_i32 s[%d:%d], %%[np], v%d' % (masks[k], masks[k] + 1, P)]:
+                e.raw(o)
+        cvt = 'v_cvt_pk_bf16_f32' if self.bf else 'v_cvt_pk_f16_f32'
+        for h in range(2):
+            for db in (2 * h, 2 * h + 1):
+                for q in range(4):
+                    e.raw('ds_write_b128 %%[ew], %s offset:%d' % (vr(ACC + 16 * db + 4 * q, 4), 128 * (db - 2 * h) + 32 * q))
+            e.raw('s_waitcnt lgkmcnt(0)')
+            for k in range(8):
+                e.raw('ds_read_b128 %s, %%[er] offset:%d' % (vr(VT + 4 * k, 4), 4 * k * EPITCH))
+            e.raw('s_cmp_eq_u32 %[oc], 0')
+            e.raw('s_cbranch_scc0 cast%d_%s' % (h, lbl))
+            for with_cast in (False, True):
+                if with_cast:
+                    e.label('cast%d_%s' % (h, lbl))
+                for k in range(8):
+                    e.raw('s_waitcnt lgkmcnt(%d)' % (7 - k))
+                    e.raw('s_mov_b64 exec, s[%d:%d]' % (masks[k], masks[k] + 1))
+                    e.raw('global_store_dwordx4 v%d, %s, %%[ob] offset:%d nt' % (OFF + k, vr(VT + 4 * k, 4), 256 * h))
+                    if with_cast:
+                        t = S1 + 2 * k
+                        e.raw('%s v%d, v%d, v%d' % (cvt, t, VT + 4 * k, VT + 4 * k + 1))
+                        e.raw('%s v%d, v%d, v%d' % (cvt, t + 1, VT + 4 * k + 2, VT + 4 * k + 3))
+                        e.raw('global_store_dwordx2 v%d, %s, %%[cb] offset:%d nt' % (COFF + k, vr(t, 2), 128 * h))
+                e.raw('s_mov_b64 exec, s[%d:%d]' % (S_EXEC, S_EXEC + 1))
+                if not with_cast:
+                    e.raw('s_branch half%d_%s' % (h, lbl))
+            e.label('half%d_%s' % (h, lbl))
         return e.out
 
 
