@@ -156,7 +156,7 @@ __device__ __forceinline__ void run_scheduled_loop(int n_full, int n_tiles, int 
                                                    uint32_t o_off, int row_flags, float* o_base, float* lse_base,
                                                    void* cast_base, int has_cast, uint32_t epi_write, uint32_t epi_read,
                                                    uint32_t epi_chunk, int g_log2, int num_qo_heads, int row_base,
-                                                   int n_pos) {
+                                                   int n_pos, int wave_index) {
   if constexpr (BF) {
     asm volatile(
 #include "append_loop_bf16.inc"
@@ -166,7 +166,7 @@ __device__ __forceinline__ void run_scheduled_loop(int n_full, int n_tiles, int 
           [qp] "v"(q_addr), [so] "v"(st_off_bytes), [sok] "v"(k_off_bytes), [kb] "v"(k_read), [kxs] "v"(k_swizzle),
           [va] "v"(v_read), [kd] "s"(k_dma), [wv] "v"(v_write), [ooff] "v"(o_off), [rok] "v"(row_flags), [ob] "s"(o_base), [lb] "s"(lse_base),
           [cb] "s"(cast_base), [oc] "s"(has_cast), [ew] "v"(epi_write), [er] "v"(epi_read), [l16] "v"(epi_chunk),
-          [gl] "s"(g_log2), [hq] "s"(num_qo_heads), [rb] "s"(row_base), [np] "s"(n_pos)
+          [gl] "s"(g_log2), [hq] "s"(num_qo_heads), [rb] "s"(row_base), [np] "s"(n_pos), [stp8] "s"(wave_index)
         :
 #include "append_loop_clobbers.inc"
     );
@@ -179,7 +179,7 @@ __device__ __forceinline__ void run_scheduled_loop(int n_full, int n_tiles, int 
           [qp] "v"(q_addr), [so] "v"(st_off_bytes), [sok] "v"(k_off_bytes), [kb] "v"(k_read), [kxs] "v"(k_swizzle),
           [va] "v"(v_read), [kd] "s"(k_dma), [wv] "v"(v_write), [ooff] "v"(o_off), [rok] "v"(row_flags), [ob] "s"(o_base), [lb] "s"(lse_base),
           [cb] "s"(cast_base), [oc] "s"(has_cast), [ew] "v"(epi_write), [er] "v"(epi_read), [l16] "v"(epi_chunk),
-          [gl] "s"(g_log2), [hq] "s"(num_qo_heads), [rb] "s"(row_base), [np] "s"(n_pos)
+          [gl] "s"(g_log2), [hq] "s"(num_qo_heads), [rb] "s"(row_base), [np] "s"(n_pos), [stp8] "s"(wave_index)
         :
 #include "append_loop_clobbers.inc"
     );
@@ -619,7 +619,7 @@ append_kernel(const RunParams p) {
                                st_chunk_o * 16, g_log2, H,
                                static_cast<int>((final_out ? static_cast<int64_t>(q_row0)
                                                            : static_cast<int64_t>(out_slot) * p.t_pos) * H + kvh * g),
-                               n_pos);
+                               n_pos, __builtin_amdgcn_readfirstlane(wave_o));
         continue;  // the work item is finished
       }
     }

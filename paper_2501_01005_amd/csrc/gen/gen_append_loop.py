@@ -293,6 +293,28 @@ class Gen:
             if kn == 0:
                 e.raw('s_branch tile_p0_%s' % lbl)
 
+    def idle_tile(self, k, lbl):
+        """a tile for a wavefront none of whose rows exists (the query tile is shorter than the CTA's
+        256 rows): it only does its share of the staging, then waits at the barrier, which leaves
+        the SIMD to the wavefront it shares it with"""
+        e = self.e
+        wr = (k + 2) % NBUF
+        e.label('tile_i%d_%s' % (k, lbl))
+        e.lgkm = []
+        e.vm = [set(('v', ST + 8 + 4 * r + i) for i in range(4)) for r in (0, 1)]
+        for o in (self.k_to_lds(S_IDK, wr) + self.ids_load(4) + self.v_convert() + self.v_zero_tail(2) + self.stores(wr) +
+                  self.fetch()):
+            e.emit(o)
+        e.wait_lds_loads()
+        e.emit('s_barrier')
+        for o in self.ids_take():
+            e.raw(o)
+        e.raw('s_add_u32 s%d, s%d, 1' % (S_T, S_T))
+        e.raw('s_cmp_ge_u32 s%d, %%[nt]' % S_T)
+        e.raw('s_cbranch_scc1 done_%s' % lbl)
+        if (k + 1) % NBUF == 0:
+            e.raw('s_branch tile_i0_%s' % lbl)
+
     def program(self):
         e = self.e
         lbl = '%='
@@ -331,6 +353,11 @@ class Gen:
         e.raw('s_mov_b64 s[%d:%d], s[%d:%d]' % (S_IDK, S_IDK + 1, S_IDN, S_IDN + 1))
         e.raw('s_mov_b64 s[%d:%d], s[%d:%d]' % (S_IDK + 2, S_IDK + 3, S_IDN + 2, S_IDN + 3))
         e.emit('s_barrier')
+        # a wavefront whose first row is past the end of the query tile only helps with the staging
+        e.raw('s_lshl_b32 s%d, %%[stp8], 5' % S_TMP)           # first tile row of this wavefront
+        e.raw('s_lshr_b32 s%d, s%d, %%[gl]' % (S_TMP, S_TMP))  # its position
+        e.raw('s_cmp_ge_u32 s%d, %%[np]' % S_TMP)
+        e.raw('s_cbranch_scc1 tile_i0_%s' % lbl)
         # first step: S^T(0, 0), the K operands of step (0, 1), the first reference
         for o in self.k_reads(0, 0):
             e.emit(o)
@@ -350,6 +377,8 @@ class Gen:
             for k in range(NBUF):
                 self.tile(k, lbl, masked)
         e.raw('s_branch exit_%s' % lbl)
+        for k in range(NBUF):
+            self.idle_tile(k, lbl)
         # out-of-line reference raises
         for kind in 'pm':
             for k in range(NBUF):
@@ -425,6 +454,11 @@ class Gen:
                 if not with_cast:
                     e.raw('s_branch half%d_%s' % (h, lbl))
             e.label('half%d_%s' % (h, lbl))
+        e.raw('s_branch end_%s' % lbl)
+        e.label('done_%s' % lbl)  # idle wavefronts: nothing to write
+        e.raw('s_waitcnt vmcnt(0)')
+        e.raw('s_mov_b32 m0, s%d' % S_M0)
+        e.label('end_%s' % lbl)
         return e.out
 
 
