@@ -235,7 +235,7 @@ __device__ __attribute__((noinline)) void generic_work_item(uint64_t params_addr
   const int lane = tid & 63;
   const int n = lane & 31;   // K: token of the 32-token step; V: column within a 32-wide block; S/O: query row
   const int c = lane >> 5;   // wavefront half
-  const int kvh = blockIdx.y;
+  const int kvh = static_cast<int>(blockIdx.x) % p.num_kv_heads;
   const int g = p.group;
   const int g_log2 = 31 - __builtin_clz(g);
   const int H = p.num_qo_heads;
@@ -545,8 +545,10 @@ template <bool BF>
 __global__ void __launch_bounds__(kCtaThreads) __attribute__((amdgpu_waves_per_eu(2, 2)))
 append_kernel(const RunParams p) {
   const int tid = threadIdx.x;
-  const int cta = blockIdx.x;
-  const int kvh = blockIdx.y;
+  // Workgroups are handed to the eight XCDs round-robin: with the kv head as the fast index all
+  // CTAs of a kv head (which re-read the same K/V) share one XCD's L2 when num_kv_heads is 8.
+  const int cta = static_cast<int>(blockIdx.x) / p.num_kv_heads;
+  const int kvh = static_cast<int>(blockIdx.x) % p.num_kv_heads;
   const int g = p.group;
   const int g_log2 = 31 - __builtin_clz(g);
   const int H = p.num_qo_heads;
@@ -635,7 +637,7 @@ append_kernel(const RunParams p) {
 int append_tile_rows() { return (kCtaThreads / 64) * 32 * kRowBlocks; }
 
 hipError_t launch_append(const RunParams& p, bool is_bf16, hipStream_t stream) {
-  const dim3 grid(static_cast<unsigned>(p.ctas_per_head), static_cast<unsigned>(p.num_kv_heads), 1);
+  const dim3 grid(static_cast<unsigned>(p.ctas_per_head) * static_cast<unsigned>(p.num_kv_heads), 1, 1);
   const dim3 block(kCtaThreads, 1, 1);
   if (is_bf16)
     hipLaunchKernelGGL(append_kernel<true>, grid, block, 0, stream, p);
