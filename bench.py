@@ -194,6 +194,11 @@ def main() -> int:
     ap.add_argument("--event-stride", type=int, default=5,
                     help="bracket every n-th attention launch of the timed region with HIP events (recording a pair "
                          "costs the step about 10 us on this box, so not every launch carries one)")
+    ap.add_argument("--page-order", default="random", choices=["random", "identity"],
+                    help="identity: every request's pages are consecutive in the pool (with --kv-layout NHD that is a "
+                         "contiguous ragged KV tensor); c2, c3, c4 only")
+    ap.add_argument("--kv-layout", default="HND", choices=["HND", "NHD"],
+                    help="pool layout in memory: [page, head, slot, D] (default, tuned) or [page, slot, head, D]")
     ap.add_argument("--num-ctas", type=int, default=0)
     ap.add_argument("--min-chunk", type=int, default=0)
     args = ap.parse_args()
@@ -222,9 +227,10 @@ def main() -> int:
         return 0
     if args.workload == "c5":
         return bench_shared_prefix(args)
-    batch = getattr(workloads, "config" + args.workload[1])(small=args.small)
+    cfg_kw = {"permute_pages": False} if args.page_order == "identity" and args.workload in ("c2", "c3", "c4") else {}
+    batch = getattr(workloads, "config" + args.workload[1])(small=args.small, **cfg_kw)
     mode = "append" if args.workload == "c3" else "decode"
-    dev = DeviceBatch(batch)
+    dev = DeviceBatch(batch, kv_layout=args.kv_layout)
     w = make_wrapper(batch, mode, num_ctas=args.num_ctas, min_chunk=args.min_chunk)
     nnz = dev.q.shape[0]
     o = torch.empty((nnz, batch.num_qo_heads, batch.head_dim), dtype=torch.float32, device=dev.device)
@@ -297,7 +303,7 @@ def main() -> int:
         "ms_per_step": ms_per_step, "us_per_batch": ms_per_step * 1e3, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": batch.dtype, "data": "synthetic",
         "config": {"workload": batch.name, "batch": batch.batch, "num_qo_heads": batch.num_qo_heads,
-                   "num_kv_heads": batch.num_kv_heads, "head_dim": batch.head_dim, "page_size": batch.page_size,
+                   "num_kv_heads": batch.num_kv_heads, "head_dim": batch.head_dim, "page_size": batch.page_size, "page_order": args.page_order, "kv_layout": args.kv_layout,
                    "step": "fi_run only (plan reused)" if args.no_plan else "fi_plan + fi_run",
                    "ctas_per_head": int(view["ctas_per_head"]), "l_kv_chunk": int(view["l_kv_chunk"]),
                    "n_work": int(view["n_work"]), "n_split_tiles": int(view["n_merge"])},

@@ -215,7 +215,7 @@ def config1(small: bool = False) -> PagedBatch:
     return make_batch("c1_mha_decode", 1001, F16, 8, 8, 128, 16, [1] * 4, kv, causal=False, num_pages=256)
 
 
-def config2(small: bool = False) -> PagedBatch:
+def config2(small: bool = False, permute_pages: bool = True) -> PagedBatch:
     """GQA decode (Llama-3-8B layer shape): batch 128, 32/8 heads, D 128, bf16,
     page 16, l_kv Zipf(s=1.2) over [256, 32768], request 0 forced to 32768.
     small: batch 12, range [64, 2048], request 0 forced to 2048."""
@@ -229,10 +229,10 @@ def config2(small: bool = False) -> PagedBatch:
     need = int(((kv + 15) // 16).sum())
     return make_batch("c2_gqa_decode_zipf" + ("_small" if small else ""), 1002, BF16, 32, 8, 128, 16,
                       [1] * len(kv), kv, causal=False, num_pages=need + need // 10,
-                      poison=small)
+                      poison=small, permute_pages=permute_pages)
 
 
-def config3(small: bool = False) -> PagedBatch:
+def config3(small: bool = False, permute_pages: bool = True) -> PagedBatch:
     """Causal append/prefill: batch 16, GQA 32/8, D 128, bf16, page 16,
     l_qo ~ U{128..1024}, cached prefix ~ U{0..4096}, l_kv = prefix + l_qo.
     One request has prefix 0, one has l_qo not a multiple of 128.
@@ -249,15 +249,15 @@ def config3(small: bool = False) -> PagedBatch:
         qo[2] += 37
     kv = qo + pre
     return make_batch("c3_causal_append" + ("_small" if small else ""), 1003, BF16, 32, 8, 128, 16,
-                      qo, kv, causal=True)
+                      qo, kv, causal=True, permute_pages=permute_pages)
 
 
-def config4(small: bool = False) -> PagedBatch:
+def config4(small: bool = False, permute_pages: bool = True) -> PagedBatch:
     """Long-context decode with split-KV: batch 2, GQA 32/8, D 128, bf16,
     l_kv = [131072, 65536], values 0.5*N(0,1).  small: [8192, 4096]."""
     kv = [8192, 4096] if small else [131072, 65536]
     return make_batch("c4_long_decode" + ("_small" if small else ""), 1004, BF16, 32, 8, 128, 16,
-                      [1, 1], kv, causal=False, value_scale=0.5, poison=small)
+                      [1, 1], kv, causal=False, value_scale=0.5, poison=small, permute_pages=permute_pages)
 
 
 @dataclasses.dataclass
