@@ -1,7 +1,7 @@
 """CPU oracle package: TEST INFRASTRUCTURE ONLY.
 
 `attention` holds the fp64 definition of paged attention states and their
-merge; `plan_replica` the step-by-step replica of the paper's scheduling
+merge; `fp8` the decoding of the 8-bit KV cache format; `plan_replica` the step-by-step replica of the paper's scheduling
 algorithm.  Nothing in the GPU library imports this package; only tests, the
 smoke check and the benchmark's CPU-baseline leg do.
 """
@@ -11,7 +11,7 @@ from typing import Sequence, Tuple
 
 import numpy as np
 
-from . import attention, plan_replica  # noqa: F401
+from . import attention, fp8, plan_replica  # noqa: F401
 
 
 def run_batch(batch, requests: Sequence[int] | None = None,
@@ -23,11 +23,18 @@ def run_batch(batch, requests: Sequence[int] | None = None,
     dt = batch.dtype
     q = widen(batch.q_bits, dt)
 
-    def k_of(pages, h):
-        return widen(batch.k_bits[pages, h], dt)
+    if getattr(batch, "kv_dtype", "") == "fp8_e4m3":   # 8-bit KV cache (App. F): value = decoded code * scale
+        def k_of(pages, h):
+            return fp8.e4m3_to_f64(batch.k_bits[pages, h]) * batch.k_scale
 
-    def v_of(pages, h):
-        return widen(batch.v_bits[pages, h], dt)
+        def v_of(pages, h):
+            return fp8.e4m3_to_f64(batch.v_bits[pages, h]) * batch.v_scale
+    else:
+        def k_of(pages, h):
+            return widen(batch.k_bits[pages, h], dt)
+
+        def v_of(pages, h):
+            return widen(batch.v_bits[pages, h], dt)
 
     return attention.batch_attention(
         q, k_of, v_of, batch.qo_indptr, batch.kv_indptr, batch.kv_indices, batch.last_page_len,

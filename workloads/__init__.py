@@ -7,7 +7,9 @@ and the GPU library can be fed from it without sharing any logic.
 
 Storage convention: 16-bit values are carried as ``numpy.uint16`` bit patterns
 (``*_bits`` fields) so that fp16 and bf16 travel through NumPy unchanged;
-``widen`` turns them into exact float64 values.
+``widen`` turns them into exact float64 values.  An 8-bit KV cache (App. F: fp8 K/V with
+16-bit queries) carries ``numpy.uint8`` codes of the OCP E4M3 format, produced here by
+``f32_to_e4m3_bits``; their values are ``code value * k_scale`` (``v_scale``).
 
 Layouts (Sec. 3.1.1 of the paper: ragged query/output, BSR KV-cache):
   q_bits        [nnz_qo, H_qo, D]
@@ -28,6 +30,8 @@ import numpy as np
 
 F16 = "f16"
 BF16 = "bf16"
+FP8 = "fp8_e4m3"   # OCP 8-bit float: 1 sign, 4 exponent (bias 7), 3 mantissa bits; no infinities, 0x7f / 0xff = NaN
+E4M3_NAN = np.uint8(0x7F)
 
 _NAN_BITS = {F16: np.uint16(0x7E00), BF16: np.uint16(0x7FC0)}
 
@@ -50,6 +54,23 @@ def f32_to_bits(x: np.ndarray, dtype: str) -> np.ndarray:
             out[nan] = _NAN_BITS[BF16]
         return out
     raise ValueError(f"unknown dtype {dtype!r}")
+
+
+def f32_to_e4m3_bits(x: np.ndarray) -> np.ndarray:
+    """Round float32 values to E4M3 codes: nearest, ties to even, magnitudes above 448 saturate
+    to 448 (the format has no infinity).  NaN inputs are not expected here."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    sign = np.signbit(x).astype(np.uint8) << np.uint8(7)
+    a = np.minimum(np.abs(x).astype(np.float64), 448.0)
+    _, ex = np.frexp(a)                     # a = f * 2**ex, f in [0.5, 1)
+    e = np.maximum(ex - 1, -6)              # exponent of the binade; subnormals share the smallest one
+    q = np.rint(a / np.exp2(e.astype(np.float64)) * 8.0).astype(np.int64)   # value in eighths of 2**e: 0..16
+    # q = 16: rounded up into the next binade; q < 8: subnormal (only at e = -6)
+    up = q == 16
+    e = np.where(up, e + 1, e)
+    q = np.where(up, 8, q)
+    code = np.where(q < 8, q, ((e + 7) << 3) | (q - 8))
+    return (code.astype(np.uint8) | sign).astype(np.uint8)
 
 
 def widen(bits: np.ndarray, dtype: str) -> np.ndarray:
@@ -80,8 +101,11 @@ class PagedBatch:
     kv_indices: np.ndarray     # int32 [nnz_pages]
     last_page_len: np.ndarray  # int32 [B]
     q_bits: np.ndarray         # uint16 [nnz_qo, H_qo, D]
-    k_bits: np.ndarray         # uint16 [P, H_kv, page_size, D]
+    k_bits: np.ndarray         # uint16 [P, H_kv, page_size, D]  (uint8 E4M3 codes when kv_dtype is FP8)
     v_bits: np.ndarray         # uint16 [P, H_kv, page_size, D]
+    kv_dtype: str = ""         # "" = same as dtype; FP8 = 8-bit KV cache
+    k_scale: float = 1.0       # value of a stored K element = decoded code * k_scale (FP8 only)
+    v_scale: float = 1.0
 
     @property
     def batch(self) -> int:
@@ -100,12 +124,12 @@ class PagedBatch:
 
     def kv_bytes(self) -> int:
         """K+V bytes of all tokens the batch attends to (each kv-head once)."""
-        return int(self.kv_lens().sum()) * self.num_kv_heads * self.head_dim * 2 * 2
+        return int(self.kv_lens().sum()) * self.num_kv_heads * self.head_dim * 2 * (1 if self.kv_dtype == FP8 else 2)
 
 
 def _fill_normal_bits(out: np.ndarray, seed_seq: np.random.SeedSequence, dtype: str,
                       scale: float, threads: int = 8, slab: int = 1 << 22) -> None:
-    """out.flat[:] = bits(round(scale * N(0,1))), drawn slab by slab.
+    """out.flat[:] = bits(round(scale * N(0,1))), drawn slab by slab (dtype FP8: E4M3 codes).
 
     Every slab has its own child seed, so the result does not depend on the
     number of threads."""
@@ -120,7 +144,7 @@ def _fill_normal_bits(out: np.ndarray, seed_seq: np.random.SeedSequence, dtype: 
         x = g.standard_normal(hi - lo, dtype=np.float32)
         if scale != 1.0:
             x *= np.float32(scale)
-        flat[lo:hi] = f32_to_bits(x, dtype)
+        flat[lo:hi] = f32_to_e4m3_bits(x) if dtype == FP8 else f32_to_bits(x, dtype)
 
     if n_slabs <= 1 or threads <= 1:
         for s in range(n_slabs):
@@ -134,7 +158,8 @@ def make_batch(name: str, seed: int, dtype: str, num_qo_heads: int, num_kv_heads
                head_dim: int, page_size: int, qo_lens: Sequence[int], kv_lens: Sequence[int],
                causal: bool, *, num_pages: Optional[int] = None, value_scale: float = 1.0,
                permute_pages: bool = True, poison: bool = True,
-               sm_scale: Optional[float] = None) -> PagedBatch:
+               sm_scale: Optional[float] = None, kv_dtype: str = "", k_scale: float = 1.0,
+               v_scale: float = 1.0) -> PagedBatch:
     """Build one paged batch: random page placement, N(0,1)*value_scale data.
 
     Pages are handed to requests as consecutive slices of one random
@@ -166,13 +191,20 @@ def make_batch(name: str, seed: int, dtype: str, num_qo_heads: int, num_kv_heads
 
     q_bits = np.empty((nnz, num_qo_heads, head_dim), dtype=np.uint16)
     _fill_normal_bits(q_bits, s_q, dtype, value_scale)
-    k_bits = np.empty((P, num_kv_heads, page_size, head_dim), dtype=np.uint16)
-    v_bits = np.empty((P, num_kv_heads, page_size, head_dim), dtype=np.uint16)
-    _fill_normal_bits(k_bits, s_k, dtype, value_scale)
-    _fill_normal_bits(v_bits, s_v, dtype, value_scale)
+    if kv_dtype == FP8:   # stored code = round(value / scale); the values themselves are scale * N(0,1) * value_scale
+        k_bits = np.empty((P, num_kv_heads, page_size, head_dim), dtype=np.uint8)
+        v_bits = np.empty((P, num_kv_heads, page_size, head_dim), dtype=np.uint8)
+        _fill_normal_bits(k_bits, s_k, FP8, value_scale)
+        _fill_normal_bits(v_bits, s_v, FP8, value_scale)
+    else:
+        assert kv_dtype in ("", dtype), "the KV cache is stored in the query type or in FP8"
+        k_bits = np.empty((P, num_kv_heads, page_size, head_dim), dtype=np.uint16)
+        v_bits = np.empty((P, num_kv_heads, page_size, head_dim), dtype=np.uint16)
+        _fill_normal_bits(k_bits, s_k, dtype, value_scale)
+        _fill_normal_bits(v_bits, s_v, dtype, value_scale)
 
     if poison:
-        nanb = _NAN_BITS[dtype]
+        nanb = E4M3_NAN if kv_dtype == FP8 else _NAN_BITS[dtype]
         if P > need:
             unused = perm[need:]
             k_bits[unused] = nanb
@@ -188,7 +220,8 @@ def make_batch(name: str, seed: int, dtype: str, num_qo_heads: int, num_kv_heads
     return PagedBatch(name=name, dtype=dtype, num_qo_heads=num_qo_heads, num_kv_heads=num_kv_heads,
                       head_dim=head_dim, page_size=page_size, causal=causal, sm_scale=float(sm_scale),
                       qo_indptr=qo_indptr, kv_indptr=kv_indptr, kv_indices=kv_indices,
-                      last_page_len=last_page_len, q_bits=q_bits, k_bits=k_bits, v_bits=v_bits)
+                      last_page_len=last_page_len, q_bits=q_bits, k_bits=k_bits, v_bits=v_bits,
+                      kv_dtype=FP8 if kv_dtype == FP8 else "", k_scale=float(k_scale), v_scale=float(v_scale))
 
 
 # --------------------------------------------------------------------------
@@ -215,7 +248,7 @@ def config1(small: bool = False) -> PagedBatch:
     return make_batch("c1_mha_decode", 1001, F16, 8, 8, 128, 16, [1] * 4, kv, causal=False, num_pages=256)
 
 
-def config2(small: bool = False, permute_pages: bool = True) -> PagedBatch:
+def config2(small: bool = False, permute_pages: bool = True, kv_dtype: str = "") -> PagedBatch:
     """GQA decode (Llama-3-8B layer shape): batch 128, 32/8 heads, D 128, bf16,
     page 16, l_kv Zipf(s=1.2) over [256, 32768], request 0 forced to 32768.
     small: batch 12, range [64, 2048], request 0 forced to 2048."""
@@ -229,7 +262,8 @@ def config2(small: bool = False, permute_pages: bool = True) -> PagedBatch:
     need = int(((kv + 15) // 16).sum())
     return make_batch("c2_gqa_decode_zipf" + ("_small" if small else ""), 1002, BF16, 32, 8, 128, 16,
                       [1] * len(kv), kv, causal=False, num_pages=need + need // 10,
-                      poison=small, permute_pages=permute_pages)
+                      poison=small, permute_pages=permute_pages, kv_dtype=kv_dtype,
+                      k_scale=0.5 if kv_dtype == FP8 else 1.0, v_scale=2.0 if kv_dtype == FP8 else 1.0)
 
 
 def config3(small: bool = False, permute_pages: bool = True) -> PagedBatch:
@@ -252,12 +286,13 @@ def config3(small: bool = False, permute_pages: bool = True) -> PagedBatch:
                       qo, kv, causal=True, permute_pages=permute_pages)
 
 
-def config4(small: bool = False, permute_pages: bool = True) -> PagedBatch:
+def config4(small: bool = False, permute_pages: bool = True, kv_dtype: str = "") -> PagedBatch:
     """Long-context decode with split-KV: batch 2, GQA 32/8, D 128, bf16,
     l_kv = [131072, 65536], values 0.5*N(0,1).  small: [8192, 4096]."""
     kv = [8192, 4096] if small else [131072, 65536]
     return make_batch("c4_long_decode" + ("_small" if small else ""), 1004, BF16, 32, 8, 128, 16,
-                      [1, 1], kv, causal=False, value_scale=0.5, poison=small, permute_pages=permute_pages)
+                      [1, 1], kv, causal=False, value_scale=0.5, poison=small, permute_pages=permute_pages,
+                      kv_dtype=kv_dtype, k_scale=0.5 if kv_dtype == FP8 else 1.0, v_scale=2.0 if kv_dtype == FP8 else 1.0)
 
 
 @dataclasses.dataclass
@@ -317,7 +352,8 @@ def config5(small: bool = False) -> SharedPrefixCase:
 def random_case(seed: int, *, dtype: str = BF16, num_qo_heads: int = 32, num_kv_heads: int = 8,
                 head_dim: int = 128, page_size: int = 16, batch: int = 5, max_qo: int = 1,
                 max_kv: int = 300, causal: bool = False, allow_empty: bool = True,
-                value_scale: float = 1.0) -> PagedBatch:
+                value_scale: float = 1.0, kv_dtype: str = "", k_scale: float = 1.0,
+                v_scale: float = 1.0) -> PagedBatch:
     """Small adversarial batch: ragged lengths, optional empty requests, spare pages."""
     g = np.random.Generator(np.random.PCG64(seed))
     qo = g.integers(1, max_qo + 1, size=batch) if max_qo > 1 else np.ones(batch, dtype=np.int64)
@@ -330,4 +366,5 @@ def random_case(seed: int, *, dtype: str = BF16, num_qo_heads: int = 32, num_kv_
             kv[g.integers(0, batch)] = 0
     need = int(((kv + page_size - 1) // page_size).sum())
     return make_batch(f"rand{seed}", seed, dtype, num_qo_heads, num_kv_heads, head_dim, page_size,
-                      qo, kv, causal=causal, num_pages=need + 3, value_scale=value_scale)
+                      qo, kv, causal=causal, num_pages=need + 3, value_scale=value_scale, kv_dtype=kv_dtype,
+                      k_scale=k_scale, v_scale=v_scale)
