@@ -70,7 +70,7 @@ def decode_algorithmic_bytes(batch, plan_view) -> dict:
     again by the merge."""
     H, Hk, D = batch.num_qo_heads, batch.num_kv_heads, batch.head_dim
     tokens = int(batch.kv_lens().sum())
-    kv = tokens * Hk * D * 2 * 2
+    kv = tokens * Hk * D * 2 * (1 if batch.kv_dtype else 2)   # an 8-bit KV cache stores one byte per element
     n_rows = int(batch.qo_indptr[-1]) * H
     q = n_rows * D * 2
     out = n_rows * (D + 1) * 4
@@ -199,6 +199,8 @@ def main() -> int:
                          "contiguous ragged KV tensor); c2, c3, c4 only")
     ap.add_argument("--kv-layout", default="HND", choices=["HND", "NHD"],
                     help="pool layout in memory: [page, head, slot, D] (default, tuned) or [page, slot, head, D]")
+    ap.add_argument("--kv-dtype", default="same", choices=["same", "fp8"],
+                    help="fp8: K/V stored as E4M3 codes with scales (App. F), decode workloads c2 and c4 only")
     ap.add_argument("--num-ctas", type=int, default=0)
     ap.add_argument("--min-chunk", type=int, default=0)
     args = ap.parse_args()
@@ -228,6 +230,11 @@ def main() -> int:
     if args.workload == "c5":
         return bench_shared_prefix(args)
     cfg_kw = {"permute_pages": False} if args.page_order == "identity" and args.workload in ("c2", "c3", "c4") else {}
+    if args.kv_dtype == "fp8":
+        if args.workload not in ("c2", "c4"):
+            print("bench.py: --kv-dtype fp8 is for the decode workloads c2 and c4", file=sys.stderr)
+            return 2
+        cfg_kw["kv_dtype"] = workloads.FP8
     batch = getattr(workloads, "config" + args.workload[1])(small=args.small, **cfg_kw)
     mode = "append" if args.workload == "c3" else "decode"
     dev = DeviceBatch(batch, kv_layout=args.kv_layout)
@@ -246,7 +253,7 @@ def main() -> int:
         sampled = i_timed >= 0 and i_timed % stride == 0
         if sampled:
             fi.lib.fi_set_timing_events(w.handle, ev.start[i_timed // stride], ev.stop[i_timed // stride])
-        w.run(dev.q, dev.k_pool, dev.v_pool, dev.kv_indices, batch.sm_scale, o=o, lse=lse)
+        w.run(dev.q, dev.k_pool, dev.v_pool, dev.kv_indices, batch.sm_scale, o=o, lse=lse, **dev.scales)
         if sampled:
             fi.lib.fi_set_timing_events(w.handle, None, None)
 
@@ -273,7 +280,8 @@ def main() -> int:
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "traffic.json")
     if os.path.exists(tpath):
-        traffic = json.load(open(tpath)).get(args.workload + ("_small" if args.small else ""))
+        traffic = json.load(open(tpath)).get(args.workload + ("_fp8" if batch.kv_dtype else "") +
+                                             ("_small" if args.small else ""))
 
     if mode == "decode":
         ab = decode_algorithmic_bytes(batch, view)
@@ -304,6 +312,7 @@ def main() -> int:
         "vs_baseline": None, "dtype": batch.dtype, "data": "synthetic",
         "config": {"workload": batch.name, "batch": batch.batch, "num_qo_heads": batch.num_qo_heads,
                    "num_kv_heads": batch.num_kv_heads, "head_dim": batch.head_dim, "page_size": batch.page_size, "page_order": args.page_order, "kv_layout": args.kv_layout,
+                   "kv_dtype": batch.kv_dtype or batch.dtype,
                    "step": "fi_run only (plan reused)" if args.no_plan else "fi_plan + fi_run",
                    "ctas_per_head": int(view["ctas_per_head"]), "l_kv_chunk": int(view["l_kv_chunk"]),
                    "n_work": int(view["n_work"]), "n_split_tiles": int(view["n_merge"])},

@@ -150,6 +150,18 @@ int32_t fi_run(fi_handle* h, const void* q, const void* k_pool, const void* v_po
                const int64_t* kv_strides, const int32_t* kv_indices, float sm_scale,
                float* o, float* lse, void* o_cast, fi_stream stream);
 
+/* fi_run over an 8-bit KV cache (App. F: fp8 K/V with 16-bit queries and wider arithmetic):
+ * k_pool and v_pool DEVICE hold one OCP E4M3 code per element (1 sign, 4 exponent bits with
+ * bias 7, 3 mantissa bits; 0x7f / 0xff are NaN, no infinities); an element's value is its
+ * decoded code times k_scale (v_scale), both > 0.  kv_strides are in elements, i.e. bytes, and
+ * multiples of 8.  The codes are widened to the query type on the fly (exact), all arithmetic
+ * is that of fi_run.  Decode mode only (FI_ERR_UNSUPPORTED for an append handle); otherwise
+ * arguments, ownership and errors as for fi_run. */
+int32_t fi_run_kv8(fi_handle* h, const void* q, const void* k_pool, const void* v_pool,
+                   const int64_t* kv_strides, const int32_t* kv_indices, float sm_scale,
+                   float k_scale, float v_scale, float* o, float* lse, void* o_cast,
+                   fi_stream stream);
+
 /* Measurement hook: with two hipEvent_t handles set, every later fi_run records `before`
  * right before and `after` right after the launch of its attention kernel (the merge launch
  * comes after `after`) on the run's stream, so a caller can time that kernel alone.

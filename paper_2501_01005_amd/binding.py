@@ -13,7 +13,7 @@ __all__ = [
     "FI_OK", "FI_ERR_INVALID_ARG", "FI_ERR_UNSUPPORTED", "FI_ERR_WORKSPACE_TOO_SMALL", "FI_ERR_NOT_PLANNED",
     "FI_ERR_HIP", "FI_DTYPE_F16", "FI_DTYPE_BF16", "FI_MODE_DECODE", "FI_MODE_APPEND",
     "Fi355Error", "fi_config", "fi_plan_arrays", "lib", "library_path",
-    "fi_create", "fi_destroy", "fi_workspace_bytes", "fi_plan", "fi_plan_view", "fi_run",
+    "fi_create", "fi_destroy", "fi_workspace_bytes", "fi_plan", "fi_plan_view", "fi_run", "fi_run_kv8",
     "fi_merge_states", "fi_merge_state_pair", "fi_check_indices", "fi_set_timing_events", "fi_last_error",
     "PagedAttention",
 ]
@@ -79,13 +79,15 @@ def _load() -> ctypes.CDLL:
     L.fi_plan.argtypes = [vp, vp, vp, vp, i32, i32, vp, sz, vp, sz, vp]
     L.fi_plan_view.argtypes = [vp, ctypes.POINTER(fi_plan_arrays)]
     L.fi_run.argtypes = [vp, vp, vp, vp, ctypes.POINTER(i64), vp, ctypes.c_float, vp, vp, vp, vp]
+    L.fi_run_kv8.argtypes = [vp, vp, vp, vp, ctypes.POINTER(i64), vp, ctypes.c_float, ctypes.c_float, ctypes.c_float,
+                             vp, vp, vp, vp]
     L.fi_merge_states.argtypes = [vp, vp, i64, i32, i32, vp, vp, vp]
     L.fi_merge_state_pair.argtypes = [vp, vp, vp, vp, i64, i32, vp, vp, vp]
     L.fi_check_indices.argtypes = [vp, i64, i32]
     L.fi_set_timing_events.argtypes = [vp, vp, vp]
     L.fi_last_error.argtypes = []
     L.fi_last_error.restype = ctypes.c_char_p
-    for name in ("fi_create", "fi_destroy", "fi_workspace_bytes", "fi_plan", "fi_plan_view", "fi_run",
+    for name in ("fi_create", "fi_destroy", "fi_workspace_bytes", "fi_plan", "fi_plan_view", "fi_run", "fi_run_kv8",
                  "fi_merge_states", "fi_merge_state_pair", "fi_check_indices", "fi_set_timing_events"):
         getattr(L, name).restype = i32
     return L
@@ -173,6 +175,13 @@ def fi_run(handle: int, q, k_pool, v_pool, kv_strides: Sequence[int], kv_indices
                       _ptr(o), _ptr(lse), _ptr(o_cast), stream or None))
 
 
+def fi_run_kv8(handle: int, q, k_pool, v_pool, kv_strides: Sequence[int], kv_indices, sm_scale: float,
+               k_scale: float, v_scale: float, o, lse, o_cast=None, stream: int = 0) -> None:
+    st = (ctypes.c_int64 * 3)(*[int(s) for s in kv_strides])
+    _check(lib.fi_run_kv8(handle, _ptr(q), _ptr(k_pool), _ptr(v_pool), st, _ptr(kv_indices), float(sm_scale),
+                          float(k_scale), float(v_scale), _ptr(o), _ptr(lse), _ptr(o_cast), stream or None))
+
+
 def fi_merge_states(o_parts, lse_parts, n_rows: int, n_states: int, head_dim: int, o, lse, stream: int = 0) -> None:
     _check(lib.fi_merge_states(_ptr(o_parts), _ptr(lse_parts), n_rows, n_states, head_dim, _ptr(o), _ptr(lse),
                                stream or None))
@@ -250,9 +259,13 @@ class PagedAttention:
         ev.record(self.torch.cuda.current_stream(self.device))
         self._ring_events[i] = ev
 
-    def run(self, q, k_pool, v_pool, kv_indices, sm_scale: float, o=None, lse=None, o_cast=None):
+    def run(self, q, k_pool, v_pool, kv_indices, sm_scale: float, o=None, lse=None, o_cast=None,
+            k_scale: Optional[float] = None, v_scale: Optional[float] = None):
+        """k_scale / v_scale given: the pools are an 8-bit KV cache (uint8 tensors of E4M3 codes)."""
         torch = self.torch
-        assert q.dtype == self.torch_dtype and k_pool.dtype == self.torch_dtype and v_pool.dtype == self.torch_dtype
+        kv8 = k_scale is not None or v_scale is not None
+        kv_dtype = torch.uint8 if kv8 else self.torch_dtype
+        assert q.dtype == self.torch_dtype and k_pool.dtype == kv_dtype and v_pool.dtype == kv_dtype
         assert q.is_contiguous() and q.shape[1:] == (self.num_qo_heads, self.head_dim)
         assert k_pool.dim() == 4 and k_pool.stride(3) == 1 and k_pool.stride() == v_pool.stride()
         assert kv_indices.dtype == torch.int32 and kv_indices.is_contiguous()
@@ -263,5 +276,10 @@ class PagedAttention:
             lse = torch.empty((nnz, self.num_qo_heads), dtype=torch.float32, device=q.device)
         # k_pool is [pages, kv_heads, page_size, D] (or any permutation of the first three through strides)
         strides = (k_pool.stride(0), k_pool.stride(1), k_pool.stride(2))
-        fi_run(self.handle, q, k_pool, v_pool, strides, kv_indices, sm_scale, o, lse, o_cast, self._stream())
+        if kv8:
+            fi_run_kv8(self.handle, q, k_pool, v_pool, strides, kv_indices, sm_scale,
+                       1.0 if k_scale is None else k_scale, 1.0 if v_scale is None else v_scale, o, lse, o_cast,
+                       self._stream())
+        else:
+            fi_run(self.handle, q, k_pool, v_pool, strides, kv_indices, sm_scale, o, lse, o_cast, self._stream())
         return o, lse

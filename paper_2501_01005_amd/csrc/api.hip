@@ -185,9 +185,18 @@ int32_t fi_plan_view(const fi_handle* h, fi_plan_arrays* out) {
   return FI_OK;
 }
 
-int32_t fi_run(fi_handle* h, const void* q, const void* k_pool, const void* v_pool, const int64_t* kv_strides,
-               const int32_t* kv_indices, float sm_scale, float* o, float* lse, void* o_cast, fi_stream stream) {
+}  // extern "C"
+
+namespace {
+// fi_run and fi_run_kv8: kv8 = the pools hold E4M3 codes whose values are code * k_scale (v_scale)
+int32_t run_impl(fi_handle* h, const void* q, const void* k_pool, const void* v_pool, const int64_t* kv_strides,
+                 const int32_t* kv_indices, float sm_scale, bool kv8, float k_scale, float v_scale, float* o,
+                 float* lse, void* o_cast, fi_stream stream) {
   if (!h) return set_error(FI_ERR_INVALID_ARG, "fi_run: null handle");
+  if (kv8 && h->cfg.mode != FI_MODE_DECODE)
+    return set_error(FI_ERR_UNSUPPORTED, "fi_run_kv8: the 8-bit KV cache is built for decode mode only");
+  if (kv8 && !(k_scale > 0.f && v_scale > 0.f))
+    return set_error(FI_ERR_INVALID_ARG, "fi_run_kv8: k_scale and v_scale must be > 0");
   if (!h->planned_dev) return set_error(FI_ERR_NOT_PLANNED, "fi_run: call fi_plan with a device workspace first");
   if (!q || !k_pool || !v_pool || !kv_strides || !kv_indices || !o || !lse)
     return set_error(FI_ERR_INVALID_ARG, "fi_run: null pointer");
@@ -224,7 +233,8 @@ int32_t fi_run(fi_handle* h, const void* q, const void* k_pool, const void* v_po
   p.o_cast = o_cast;
   p.part_lse = reinterpret_cast<float*>(ws + L.off_part_lse);
   p.part_o = reinterpret_cast<float*>(ws + L.off_part_o);
-  p.scale_log2 = sm_scale * 1.4426950408889634f;
+  p.scale_log2 = sm_scale * 1.4426950408889634f * (kv8 ? k_scale : 1.f);
+  p.out_scale = kv8 ? v_scale : 1.f;
   p.num_qo_heads = h->cfg.num_qo_heads;
   p.num_kv_heads = h->cfg.num_kv_heads;
   p.group = h->pp.group;
@@ -234,7 +244,7 @@ int32_t fi_run(fi_handle* h, const void* q, const void* k_pool, const void* v_po
   hipStream_t s = static_cast<hipStream_t>(stream);
   hipError_t e;
   if (h->ev_before && (e = hipEventRecord(h->ev_before, s)) != hipSuccess) return hip_error("fi_run: hipEventRecord", e);
-  e = h->cfg.mode == FI_MODE_DECODE ? launch_decode(p, bf, s) : launch_append(p, bf, s);
+  e = h->cfg.mode == FI_MODE_DECODE ? launch_decode(p, bf, kv8, s) : launch_append(p, bf, s);
   if (e != hipSuccess) return hip_error("fi_run: attention launch", e);
   if (h->ev_after && (e = hipEventRecord(h->ev_after, s)) != hipSuccess) return hip_error("fi_run: hipEventRecord", e);
 
@@ -255,6 +265,21 @@ int32_t fi_run(fi_handle* h, const void* q, const void* k_pool, const void* v_po
   e = launch_merge_planned(mp, kMergeGrid, s);
   if (e != hipSuccess) return hip_error("fi_run: merge launch", e);
   return FI_OK;
+}
+}  // namespace
+
+extern "C" {
+
+int32_t fi_run(fi_handle* h, const void* q, const void* k_pool, const void* v_pool, const int64_t* kv_strides,
+               const int32_t* kv_indices, float sm_scale, float* o, float* lse, void* o_cast, fi_stream stream) {
+  return run_impl(h, q, k_pool, v_pool, kv_strides, kv_indices, sm_scale, false, 1.f, 1.f, o, lse, o_cast, stream);
+}
+
+int32_t fi_run_kv8(fi_handle* h, const void* q, const void* k_pool, const void* v_pool, const int64_t* kv_strides,
+                   const int32_t* kv_indices, float sm_scale, float k_scale, float v_scale, float* o, float* lse,
+                   void* o_cast, fi_stream stream) {
+  return run_impl(h, q, k_pool, v_pool, kv_strides, kv_indices, sm_scale, true, k_scale, v_scale, o, lse, o_cast,
+                  stream);
 }
 
 int32_t fi_set_timing_events(fi_handle* h, void* before, void* after) {

@@ -19,6 +19,16 @@
 // bf16 inputs: P is split into a bf16 head and a bf16 remainder and the second product is
 // issued twice; the matrix pipe has an order of magnitude of slack on this path and it keeps
 // P to ~16 significant bits without restricting the range of V.
+//
+// 8-bit KV cache (App. F: fp8 K/V, 16-bit queries, wider arithmetic): the pools hold OCP E4M3
+// codes; a lane loads the same (token, 8 columns) piece as above in 8 bytes instead of 16 and
+// widens it to the query type (exact: E4M3 is a subset of both) when the tile is consumed, so
+// everything after the load is shared; for V the codes of a token pair are interleaved
+// byte-wise first, so that the conversion instruction delivers the pair the V^T operand needs.
+// Four tiles are in flight instead of two, which keeps the bytes in flight per wavefront.  The
+// K and V scales are folded into the softmax scale and into the final normalisation.
+#include <type_traits>
+
 #include "kernels.h"
 
 namespace fi355 {
@@ -30,6 +40,7 @@ typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
 typedef __attribute__((ext_vector_type(2))) _Float16 f16x2_t;
 typedef __attribute__((ext_vector_type(4))) float f32x4_t;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4_t;
+typedef __attribute__((ext_vector_type(2))) uint32_t u32x2_t;
 
 template <bool BF>
 __device__ __forceinline__ f32x4_t mfma_16x16x32(u32x4_t a, u32x4_t b, f32x4_t c) {
@@ -66,12 +77,35 @@ __device__ __forceinline__ u32x4_t ld16_stream(const uint16_t* p) {
   return __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(p));
 }
 
+__device__ __forceinline__ u32x2_t ld8_stream(const uint8_t* p) {
+  return __builtin_nontemporal_load(reinterpret_cast<const u32x2_t*>(p));
+}
+
+// eight E4M3 codes (byte i = column i) -> eight values of the query type, column i in 16-bit slot i
+// (one conversion instruction per pair: the scaled fp8 conversions of gfx950 with scale 1)
+template <bool BF>
+__device__ __forceinline__ u32x4_t widen8(u32x2_t w) {
+  if constexpr (BF) {
+    return u32x4_t{__builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w[0], 1.0f, false)),
+                   __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w[0], 1.0f, true)),
+                   __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w[1], 1.0f, false)),
+                   __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w[1], 1.0f, true))};
+  } else {
+    return u32x4_t{__builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(w[0], 1.0f, false)),
+                   __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(w[0], 1.0f, true)),
+                   __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(w[1], 1.0f, false)),
+                   __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(w[1], 1.0f, true))};
+  }
+}
+
+template <bool KV8>
 struct KvTile {
-  u32x4_t k[2][4];  // [page][j]:        K[token 4 j + c][d = 8 m .. +8]   (as loaded, row-coalesced)
-  u32x4_t v[2][4];  // [page][i]:        V[token 4 c + i][d = 8 m .. +8]
+  using Piece = typename std::conditional<KV8, u32x2_t, u32x4_t>::type;  // 8 columns as stored
+  Piece k[2][4];  // [page][j]:        K[token 4 j + c][d = 8 m .. +8]   (as loaded, row-coalesced)
+  Piece v[2][4];  // [page][i]:        V[token 4 c + i][d = 8 m .. +8]
 };
 
-template <bool BF>
+template <bool BF, bool KV8>
 __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2))) decode_kernel(const RunParams p) {
   const int lane = threadIdx.x;
   const int m = lane & 15;  // K: token in page; V: 16-byte column block; S/O: query head
@@ -82,12 +116,23 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2)))
   const int H = p.num_qo_heads;
   const float NEG_INF = -__builtin_inff();
 
-  const uint16_t* kbase = static_cast<const uint16_t*>(p.k_pool) + kvh * p.stride_head + c * p.stride_tok + m * 8;
+  constexpr int kElem = KV8 ? 1 : 2;  // bytes per stored K/V element
+  using Tile = KvTile<KV8>;
+  const uint8_t* kbase =
+      static_cast<const uint8_t*>(p.k_pool) + (kvh * p.stride_head + c * p.stride_tok + m * 8) * kElem;
   // K relayout buffer: block (page pg, token t, 16-byte block x) lives at pg*4096 + t*256 + ((x ^ t) & 15)*16
   __shared__ __attribute__((aligned(16))) u32x4_t k_lds[2 * 16 * 16];
-  const uint16_t* vbase = static_cast<const uint16_t*>(p.v_pool) + kvh * p.stride_head + (4 * c) * p.stride_tok + m * 8;
-  const int64_t stride_tok = p.stride_tok;
-  const int64_t stride_page = p.stride_page;
+  const uint8_t* vbase =
+      static_cast<const uint8_t*>(p.v_pool) + (kvh * p.stride_head + (4 * c) * p.stride_tok + m * 8) * kElem;
+  const int64_t stride_tok = p.stride_tok * kElem;    // bytes from here on
+  const int64_t stride_page = p.stride_page * kElem;
+  auto ld_piece = [](const uint8_t* ptr) {
+    if constexpr (KV8) {
+      return ld8_stream(ptr);
+    } else {
+      return ld16_stream(reinterpret_cast<const uint16_t*>(ptr));
+    }
+  };
 
   const int w_begin = __builtin_amdgcn_readfirstlane(p.cta_indptr[cta]);
   const int w_end = __builtin_amdgcn_readfirstlane(p.cta_indptr[cta + 1]);
@@ -118,27 +163,27 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2)))
     float m_run = NEG_INF;  // running max of the scaled logits in log2 units (same in all 4 lane groups)
     float l_run = 0.f;      // this lane's share of the running sum
 
-    auto load_tile = [&](KvTile& T, int t) {
+    auto load_tile = [&](Tile& T, int t) {
       const int pi = kv_page0 + 2 * t;
       const int pg0 = __builtin_amdgcn_readfirstlane(p.kv_indices[pi]);
       const int pg1 = (2 * t + 1 < n_pages) ? __builtin_amdgcn_readfirstlane(p.kv_indices[pi + 1]) : pg0;
-      const uint16_t* k0 = kbase + pg0 * stride_page;
-      const uint16_t* k1 = kbase + pg1 * stride_page;
-      const uint16_t* v0 = vbase + pg0 * stride_page;
-      const uint16_t* v1 = vbase + pg1 * stride_page;
+      const uint8_t* k0 = kbase + pg0 * stride_page;
+      const uint8_t* k1 = kbase + pg1 * stride_page;
+      const uint8_t* v0 = vbase + pg0 * stride_page;
+      const uint8_t* v1 = vbase + pg1 * stride_page;
 #pragma unroll
       for (int s = 0; s < 4; ++s) {
-        T.k[0][s] = ld16_stream(k0 + 4 * s * stride_tok);
-        T.k[1][s] = ld16_stream(k1 + 4 * s * stride_tok);
+        T.k[0][s] = ld_piece(k0 + 4 * s * stride_tok);
+        T.k[1][s] = ld_piece(k1 + 4 * s * stride_tok);
       }
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
-        T.v[0][i] = ld16_stream(v0 + i * stride_tok);
-        T.v[1][i] = ld16_stream(v1 + i * stride_tok);
+        T.v[0][i] = ld_piece(v0 + i * stride_tok);
+        T.v[1][i] = ld_piece(v1 + i * stride_tok);
       }
     };
 
-    auto compute_tile = [&](KvTile& T, int t) {
+    auto compute_tile = [&](Tile& T, int t) {
       // ---- S^T = K . Q^T ----
       // K rows -> LDS (token 4 j + c, block m), then back as A operands (token m, block 4 s + c)
 #pragma unroll
@@ -146,7 +191,11 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2)))
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
           const int tk = 4 * j + c;
-          k_lds[pg * 256 + tk * 16 + ((m ^ tk) & 15)] = T.k[pg][j];
+          if constexpr (KV8) {
+            k_lds[pg * 256 + tk * 16 + ((m ^ tk) & 15)] = widen8<BF>(T.k[pg][j]);
+          } else {
+            k_lds[pg * 256 + tk * 16 + ((m ^ tk) & 15)] = T.k[pg][j];
+          }
         }
       f32x4_t s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
@@ -171,8 +220,8 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2)))
           const bool ok1 = tok0 + 16 + i < kv_len;
           sv[i] = ok0 ? sv[i] : NEG_INF;
           sv[4 + i] = ok1 ? sv[4 + i] : NEG_INF;
-          if (!ok0) T.v[0][i] = u32x4_t{0u, 0u, 0u, 0u};
-          if (!ok1) T.v[1][i] = u32x4_t{0u, 0u, 0u, 0u};
+          if (!ok0) T.v[0][i] = typename Tile::Piece(0u);  // all-zero bits are 0.0 in every stored type
+          if (!ok1) T.v[1][i] = typename Tile::Piece(0u);
         }
       }
       // ---- online softmax ----
@@ -204,30 +253,76 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2)))
         pb_lo = u32x4_t{pack2<BF>(r[0], r[1]), pack2<BF>(r[2], r[3]), pack2<BF>(r[4], r[5]), pack2<BF>(r[6], r[7])};
       }
       // ---- O^T += V^T . P^T, one product per column e of the lane's 8-wide block ----
+      // vt[e][pg * 2 + pr] = column e of tokens (2 pr, 2 pr + 1) of page pg, as a pair of 16-bit values
+      u32x4_t vt[8];
+      if constexpr (KV8) {
+        // the codes of a token pair are interleaved byte-wise first, so that one conversion yields the pair
+#pragma unroll
+        for (int pg = 0; pg < 2; ++pg)
+#pragma unroll
+          for (int pr = 0; pr < 2; ++pr)
+#pragma unroll
+            for (int w2 = 0; w2 < 2; ++w2) {
+              const uint32_t x = T.v[pg][2 * pr][w2], y = T.v[pg][2 * pr + 1][w2];  // columns 4 w2 .. 4 w2 + 3
+              const uint32_t z01 = __builtin_amdgcn_perm(y, x, 0x05010400u);        // x.b0 y.b0 x.b1 y.b1
+              const uint32_t z23 = __builtin_amdgcn_perm(y, x, 0x07030602u);        // x.b2 y.b2 x.b3 y.b3
+              const u32x4_t four = widen8<BF>(u32x2_t{z01, z23});
+#pragma unroll
+              for (int e = 0; e < 4; ++e) vt[4 * w2 + e][pg * 2 + pr] = four[e];
+            }
+      } else {
+#pragma unroll
+        for (int wd = 0; wd < 4; ++wd) {
+          const uint32_t a0 = T.v[0][0][wd], a1 = T.v[0][1][wd], a2 = T.v[0][2][wd], a3 = T.v[0][3][wd];
+          const uint32_t b0 = T.v[1][0][wd], b1 = T.v[1][1][wd], b2 = T.v[1][2][wd], b3 = T.v[1][3][wd];
+          vt[2 * wd] = u32x4_t{lo_halves(a0, a1), lo_halves(a2, a3), lo_halves(b0, b1), lo_halves(b2, b3)};
+          vt[2 * wd + 1] = u32x4_t{hi_halves(a0, a1), hi_halves(a2, a3), hi_halves(b0, b1), hi_halves(b2, b3)};
+        }
+      }
 #pragma unroll
       for (int wd = 0; wd < 4; ++wd) {
-        const uint32_t a0 = T.v[0][0][wd], a1 = T.v[0][1][wd], a2 = T.v[0][2][wd], a3 = T.v[0][3][wd];
-        const uint32_t b0 = T.v[1][0][wd], b1 = T.v[1][1][wd], b2 = T.v[1][2][wd], b3 = T.v[1][3][wd];
-        const u32x4_t vt_even = {lo_halves(a0, a1), lo_halves(a2, a3), lo_halves(b0, b1), lo_halves(b2, b3)};
-        const u32x4_t vt_odd = {hi_halves(a0, a1), hi_halves(a2, a3), hi_halves(b0, b1), hi_halves(b2, b3)};
-        acc[2 * wd] = mfma_16x16x32<BF>(vt_even, pb, acc[2 * wd]);
-        acc[2 * wd + 1] = mfma_16x16x32<BF>(vt_odd, pb, acc[2 * wd + 1]);
+        acc[2 * wd] = mfma_16x16x32<BF>(vt[2 * wd], pb, acc[2 * wd]);
+        acc[2 * wd + 1] = mfma_16x16x32<BF>(vt[2 * wd + 1], pb, acc[2 * wd + 1]);
         if constexpr (BF) {
-          acc[2 * wd] = mfma_16x16x32<BF>(vt_even, pb_lo, acc[2 * wd]);
-          acc[2 * wd + 1] = mfma_16x16x32<BF>(vt_odd, pb_lo, acc[2 * wd + 1]);
+          acc[2 * wd] = mfma_16x16x32<BF>(vt[2 * wd], pb_lo, acc[2 * wd]);
+          acc[2 * wd + 1] = mfma_16x16x32<BF>(vt[2 * wd + 1], pb_lo, acc[2 * wd + 1]);
         }
       }
     };
 
-    KvTile TA, TB;
-    if (n_tiles > 0) load_tile(TA, 0);
-    if (n_tiles > 1) load_tile(TB, 1);
-    for (int t = 0; t < n_tiles; t += 2) {
-      compute_tile(TA, t);
-      if (t + 2 < n_tiles) load_tile(TA, t + 2);
-      if (t + 1 < n_tiles) {
-        compute_tile(TB, t + 1);
-        if (t + 3 < n_tiles) load_tile(TB, t + 3);
+    if constexpr (!KV8) {
+      Tile TA, TB;
+      if (n_tiles > 0) load_tile(TA, 0);
+      if (n_tiles > 1) load_tile(TB, 1);
+      for (int t = 0; t < n_tiles; t += 2) {
+        compute_tile(TA, t);
+        if (t + 2 < n_tiles) load_tile(TA, t + 2);
+        if (t + 1 < n_tiles) {
+          compute_tile(TB, t + 1);
+          if (t + 3 < n_tiles) load_tile(TB, t + 3);
+        }
+      }
+    } else {  // half the bytes per tile: twice the tiles in flight
+      Tile TA, TB, TC, TD;
+      if (n_tiles > 0) load_tile(TA, 0);
+      if (n_tiles > 1) load_tile(TB, 1);
+      if (n_tiles > 2) load_tile(TC, 2);
+      if (n_tiles > 3) load_tile(TD, 3);
+      for (int t = 0; t < n_tiles; t += 4) {
+        compute_tile(TA, t);
+        if (t + 4 < n_tiles) load_tile(TA, t + 4);
+        if (t + 1 < n_tiles) {
+          compute_tile(TB, t + 1);
+          if (t + 5 < n_tiles) load_tile(TB, t + 5);
+        }
+        if (t + 2 < n_tiles) {
+          compute_tile(TC, t + 2);
+          if (t + 6 < n_tiles) load_tile(TC, t + 6);
+        }
+        if (t + 3 < n_tiles) {
+          compute_tile(TD, t + 3);
+          if (t + 7 < n_tiles) load_tile(TD, t + 7);
+        }
       }
     }
 
@@ -235,7 +330,8 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2)))
     l_run += __shfl_xor(l_run, 16);
     l_run += __shfl_xor(l_run, 32);
     const bool live = l_run > 0.f;
-    const float inv = live ? 1.0f / l_run : 0.f;
+    float inv = live ? 1.0f / l_run : 0.f;
+    if constexpr (KV8) inv *= p.out_scale;  // the V scale
     const float lse_val = live ? (m_run + __builtin_amdgcn_logf(l_run)) * 0.6931471805599453f : NEG_INF;
     if (m < g) {
       const int head = kvh * g + m;
@@ -272,13 +368,20 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2)))
 
 }  // namespace
 
-hipError_t launch_decode(const RunParams& p, bool is_bf16, hipStream_t stream) {
+hipError_t launch_decode(const RunParams& p, bool is_bf16, bool kv8, hipStream_t stream) {
   const dim3 grid(static_cast<unsigned>(p.ctas_per_head), static_cast<unsigned>(p.num_kv_heads), 1);
   const dim3 block(64, 1, 1);
-  if (is_bf16)
-    hipLaunchKernelGGL(decode_kernel<true>, grid, block, 0, stream, p);
-  else
-    hipLaunchKernelGGL(decode_kernel<false>, grid, block, 0, stream, p);
+  if (kv8) {
+    if (is_bf16)
+      hipLaunchKernelGGL((decode_kernel<true, true>), grid, block, 0, stream, p);
+    else
+      hipLaunchKernelGGL((decode_kernel<false, true>), grid, block, 0, stream, p);
+  } else {
+    if (is_bf16)
+      hipLaunchKernelGGL((decode_kernel<true, false>), grid, block, 0, stream, p);
+    else
+      hipLaunchKernelGGL((decode_kernel<false, false>), grid, block, 0, stream, p);
+  }
   return hipGetLastError();
 }
 

@@ -27,7 +27,8 @@ struct RunParams {
   void* o_cast;     // may be null
   float* part_o;    // [max_slots * t_pos * H_qo, D]
   float* part_lse;  // [max_slots * t_pos * H_qo]
-  float scale_log2; // sm_scale * log2(e)
+  float scale_log2; // sm_scale * log2(e) (times the K scale of an 8-bit KV cache)
+  float out_scale;  // 8-bit KV cache: the V scale; 1 otherwise
   int32_t num_qo_heads, num_kv_heads, group, t_pos;
   int32_t ctas_per_head;
 };
@@ -47,7 +48,8 @@ struct MergeParams {
 };
 
 // decode.hip: query tile = 1 position x g fused heads, one wavefront per CTA.
-hipError_t launch_decode(const RunParams& p, bool is_bf16, hipStream_t stream);
+// kv8: the pools hold OCP E4M3 codes (App. F) instead of the query type.
+hipError_t launch_decode(const RunParams& p, bool is_bf16, bool kv8, hipStream_t stream);
 // append.hip: query tile = append_tile_rows()/g positions x g fused heads, 4 wavefronts per CTA.
 hipError_t launch_append(const RunParams& p, bool is_bf16, hipStream_t stream);
 int append_tile_rows();  // fused rows (positions x group) of one append query tile

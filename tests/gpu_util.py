@@ -21,8 +21,14 @@ class DeviceBatch:
         self.batch = batch
         self.device = torch.device(device)
         self.q = bits_to_torch(batch.q_bits, batch.dtype, self.device)
-        k = bits_to_torch(batch.k_bits, batch.dtype, self.device)
-        v = bits_to_torch(batch.v_bits, batch.dtype, self.device)
+        if getattr(batch, "kv_dtype", "") == "fp8_e4m3":   # 8-bit KV cache: uint8 tensors of E4M3 codes
+            k = torch.from_numpy(np.ascontiguousarray(batch.k_bits)).to(self.device)
+            v = torch.from_numpy(np.ascontiguousarray(batch.v_bits)).to(self.device)
+            self.scales = {"k_scale": batch.k_scale, "v_scale": batch.v_scale}
+        else:
+            k = bits_to_torch(batch.k_bits, batch.dtype, self.device)
+            v = bits_to_torch(batch.v_bits, batch.dtype, self.device)
+            self.scales = {}
         if kv_layout == "NHD":   # [pages, page_size, kv_heads, D] in memory, presented through strides
             k = k.permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3)
             v = v.permute(0, 2, 1, 3).contiguous().permute(0, 2, 1, 3)
@@ -54,7 +60,7 @@ def run_gpu(batch, mode="decode", dev: DeviceBatch | None = None, wrapper=None, 
     o = torch.full((nnz, batch.num_qo_heads, batch.head_dim), float("nan"), dtype=torch.float32, device=dev.device)
     lse = torch.full((nnz, batch.num_qo_heads), float("nan"), dtype=torch.float32, device=dev.device)
     oc = torch.zeros((nnz, batch.num_qo_heads, batch.head_dim), dtype=dev.q.dtype, device=dev.device) if with_cast else None
-    w.run(dev.q, dev.k_pool, dev.v_pool, dev.kv_indices, batch.sm_scale, o=o, lse=lse, o_cast=oc)
+    w.run(dev.q, dev.k_pool, dev.v_pool, dev.kv_indices, batch.sm_scale, o=o, lse=lse, o_cast=oc, **dev.scales)
     torch.cuda.synchronize()
     res = (o.double().cpu().numpy(), lse.double().cpu().numpy())
     if with_cast:
