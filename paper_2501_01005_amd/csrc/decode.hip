@@ -134,14 +134,25 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2)))
     }
   };
 
-  const int w_begin = __builtin_amdgcn_readfirstlane(p.cta_indptr[cta]);
-  const int w_end = __builtin_amdgcn_readfirstlane(p.cta_indptr[cta + 1]);
+  // The plan arrays and the page table are only read while the kernel runs: viewed through the
+  // constant address space their (wavefront-uniform) loads become scalar loads, which do not
+  // share a counter with the K/V loads in flight; a vector load of a page id waits for every
+  // K/V load issued before it.  Measured on the two decode workloads: with 8-bit K/V scalar
+  // page ids are 8 % faster (half the bytes per tile leave less to hide that wait behind), with
+  // 16-bit K/V the vector loads are 1 % faster, and issuing the tile loads unconditionally, so
+  // that every wait is counted with the later tiles still in flight, is 4-7 % slower for both.
+  using ConstInts = const __attribute__((address_space(4))) int32_t*;
+  auto as_const = [](const int32_t* ptr) { return (ConstInts)(reinterpret_cast<uintptr_t>(ptr)); };
+  ConstInts cta_indptr = as_const(p.cta_indptr), w_q_row0 = as_const(p.w_q_row0), w_kv_page0 = as_const(p.w_kv_page0),
+            w_kv_len = as_const(p.w_kv_len), w_out_slot = as_const(p.w_out_slot), page_ids = as_const(p.kv_indices);
+  const int w_begin = cta_indptr[cta];
+  const int w_end = cta_indptr[cta + 1];
 
   for (int w = w_begin; w < w_end; ++w) {
-    const int q_row0 = __builtin_amdgcn_readfirstlane(p.w_q_row0[w]);
-    const int kv_page0 = __builtin_amdgcn_readfirstlane(p.w_kv_page0[w]);
-    const int kv_len = __builtin_amdgcn_readfirstlane(p.w_kv_len[w]);
-    const int out_slot = __builtin_amdgcn_readfirstlane(p.w_out_slot[w]);
+    const int q_row0 = w_q_row0[w];
+    const int kv_page0 = w_kv_page0[w];
+    const int kv_len = w_kv_len[w];
+    const int out_slot = w_out_slot[w];
     const int n_pages = (kv_len + kPageSize - 1) / kPageSize;
     const int n_tiles = (kv_len + 31) / 32;
 
@@ -165,8 +176,14 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2)))
 
     auto load_tile = [&](Tile& T, int t) {
       const int pi = kv_page0 + 2 * t;
-      const int pg0 = __builtin_amdgcn_readfirstlane(p.kv_indices[pi]);
-      const int pg1 = (2 * t + 1 < n_pages) ? __builtin_amdgcn_readfirstlane(p.kv_indices[pi + 1]) : pg0;
+      int pg0, pg1;
+      if constexpr (KV8) {
+        pg0 = page_ids[pi];
+        pg1 = (2 * t + 1 < n_pages) ? page_ids[pi + 1] : pg0;
+      } else {
+        pg0 = __builtin_amdgcn_readfirstlane(p.kv_indices[pi]);
+        pg1 = (2 * t + 1 < n_pages) ? __builtin_amdgcn_readfirstlane(p.kv_indices[pi + 1]) : pg0;
+      }
       const uint8_t* k0 = kbase + pg0 * stride_page;
       const uint8_t* k1 = kbase + pg1 * stride_page;
       const uint8_t* v0 = vbase + pg0 * stride_page;
