@@ -35,6 +35,17 @@ def test_config4_full_long_context_decode():
     sampled_check(b, "decode", [0, 1], "c4 full")
 
 
+def test_config2_full_with_8_bit_kv_cache():
+    b = workloads.config2(kv_dtype=workloads.FP8)
+    order = np.argsort(b.kv_lens())
+    sample = sorted({0, int(order[0]), int(order[-2]), int(order[len(order) // 2]), 17, 64, 127})
+    sampled_check(b, "decode", sample, "c2 full, E4M3 K/V")
+
+
+def test_config4_full_with_8_bit_kv_cache():
+    sampled_check(workloads.config4(kv_dtype=workloads.FP8), "decode", [0, 1], "c4 full, E4M3 K/V")
+
+
 def test_config3_full_causal_append():
     b = workloads.config3()
     # request 1 has no cached prefix, request 2 a ragged last tile; plus the longest one
