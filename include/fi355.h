@@ -71,13 +71,19 @@ typedef struct fi_config {
   int32_t max_batch;    /* upper bound on `batch` of any later fi_plan                         */
   int32_t max_qo_tiles; /* upper bound on the number of query tiles of any later fi_plan
                            (decode: = max_batch; append: sum_i ceil(l_qo(i) / T_pos))           */
-  int32_t alpha;        /* cost(l_q, l_kv) = alpha*l_q + beta*l_kv of Algorithm 1; 0,0 = 1,1   */
+  int32_t alpha;        /* cost(l_q, l_kv) = alpha*l_q + beta*l_kv of Algorithm 1; 0,0 = 1,1
+                           (8,5 for the refined append assignment, see `balance`)              */
   int32_t beta;
   int32_t min_chunk;    /* smallest KV chunk the planner may create, tokens; 0 = default       */
   int32_t literal_lkv;  /* 1: use l_kv(i) for every query tile in the chunk-size formula as
                            printed in Algorithm 1 even under causal masking; 0: use what the
                            tile can see                                                         */
-  int32_t reserved[3];  /* must be 0                                                           */
+  int32_t balance;      /* assignment of work items to CTAs.  1: Algorithm 1 as printed (greedy,
+                           least-loaded CTA first).  2: the same, then items are moved or swapped
+                           out of the most loaded CTA while that lowers the maximum; in append mode
+                           a tile of at most half the fused rows counts 64 % of its per-token cost
+                           (it leaves wavefronts idle).  0: default = 1 for decode, 2 for append   */
+  int32_t reserved[2];  /* must be 0                                                           */
 } fi_config;
 
 /* Borrowed HOST views of the last plan, for bit-exact checks against a replica of

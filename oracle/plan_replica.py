@@ -38,6 +38,18 @@ design notes):
   * split tiles are numbered in (request, tile) order, slot_base is the running
     sum of their chunk counts, chunk c of a split tile owns slot slot_base + c,
     the merge folds slots in ascending c.
+
+Refinement (``refine=True``; an addition of this build, not in the paper, used for
+append where a CTA gets only a handful of long items): costs are taken in percent
+(``unit = 100``); the chunk length is rounded up to whole tiles of ``kv_quantum``
+tokens; an item whose fused rows ``n_pos * group`` fit in ``light_rows`` counts
+``light_pct`` percent of its per-token term; after the greedy pass, up to
+``4 * #CTA + 64`` times: take the most loaded CTA (lowest index on ties), and among
+all (other CTA, item of the loaded CTA, optional cheaper partner item of the other
+CTA) candidates in that nesting order take the first one that gives the smallest new
+maximum of the two loads, if it is below the current maximum; move (or swap) it;
+stop when there is none.  Moved items go to the end of a queue; at the end every
+queue is ordered by (-length, w) again.
 """
 from __future__ import annotations
 
@@ -50,7 +62,8 @@ NO_DIAG = 0x3FFFFFFF   # "row sees everything" marker for non-causal work items
 def plan_replica(qo_indptr: Sequence[int], kv_indptr: Sequence[int], last_page_len: Sequence[int],
                  *, page_size: int, t_pos: int, group: int, num_ctas: int, causal: bool,
                  alpha: int = 1, beta: int = 1, min_chunk: int | None = None,
-                 literal_lkv: bool = False) -> Dict[str, object]:
+                 literal_lkv: bool = False, refine: bool = False, light_rows: int = 0,
+                 light_pct: int = 100, kv_quantum: int = 1) -> Dict[str, object]:
     B = len(last_page_len)
     if min_chunk is None:
         min_chunk = page_size
@@ -117,16 +130,60 @@ def plan_replica(qo_indptr: Sequence[int], kv_indptr: Sequence[int], last_page_l
 
     # -- sort by descending length, assign to the least-loaded CTA ------------
     order = sorted(range(len(work)), key=lambda w: (-work[w]["kv_len"], w))
+    unit = 100 if refine else 1
+
+    def item_cost(w):
+        light = refine and light_rows > 0 and work[w]["n_pos"] * group <= light_rows
+        l_kv = work[w]["kv_len"]
+        if refine:   # the kernel works in whole tiles of kv_quantum tokens
+            l_kv = -(-l_kv // kv_quantum) * kv_quantum
+        return unit * alpha * T_q + beta * l_kv * (light_pct if light else unit)
+
     heap = [(0, c) for c in range(num_ctas)]
     heapq.heapify(heap)
     queues: List[List[int]] = [[] for _ in range(num_ctas)]
     for w in order:
         cost, c = heapq.heappop(heap)
         queues[c].append(w)
-        heapq.heappush(heap, (cost + alpha * T_q + beta * work[w]["kv_len"], c))
+        heapq.heappush(heap, (cost + item_cost(w), c))
     cta_cost = [0] * num_ctas
     for cost, c in heap:
         cta_cost[c] = cost
+
+    # -- refinement (not in the paper; see the module header) ------------------
+    if refine:
+        for _ in range(4 * num_ctas + 64):
+            hi = max(range(num_ctas), key=lambda c: (cta_cost[c], -c))     # most loaded, lowest index on ties
+            best_new, best = cta_cost[hi], None
+            for lo in range(num_ctas):
+                if lo == hi:
+                    continue
+                for ia, a in enumerate(queues[hi]):
+                    ca = item_cost(a)
+                    moved = max(cta_cost[hi] - ca, cta_cost[lo] + ca)
+                    if moved < best_new:
+                        best_new, best = moved, (lo, ia, -1)
+                    for ib, b_ in enumerate(queues[lo]):
+                        cb = item_cost(b_)
+                        if cb >= ca:
+                            continue
+                        swapped = max(cta_cost[hi] - ca + cb, cta_cost[lo] + ca - cb)
+                        if swapped < best_new:
+                            best_new, best = swapped, (lo, ia, ib)
+            if best is None:
+                break
+            lo, ia, ib = best
+            wa = queues[hi].pop(ia)
+            cta_cost[hi] -= item_cost(wa)
+            cta_cost[lo] += item_cost(wa)
+            if ib >= 0:
+                wb = queues[lo].pop(ib)
+                cta_cost[lo] -= item_cost(wb)
+                cta_cost[hi] += item_cost(wb)
+                queues[hi].append(wb)
+            queues[lo].append(wa)
+        for q in queues:
+            q.sort(key=lambda w: (-work[w]["kv_len"], w))
 
     cta_indptr = [0]
     flat = []

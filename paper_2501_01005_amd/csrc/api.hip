@@ -54,6 +54,8 @@ int32_t fi_create(const fi_config* cfg, fi_handle** out) {
   if (cfg->max_batch <= 0 || cfg->max_qo_tiles <= 0 || cfg->num_ctas < 0 || cfg->alpha < 0 || cfg->beta < 0 ||
       cfg->min_chunk < 0)
     return set_error(FI_ERR_INVALID_ARG, "fi_create: max_batch/max_qo_tiles must be > 0, the rest >= 0");
+  if (cfg->balance < 0 || cfg->balance > 2)
+    return set_error(FI_ERR_INVALID_ARG, "fi_create: balance must be 0 (default), 1 (as printed) or 2 (refined)");
   for (int r : cfg->reserved)
     if (r != 0) return set_error(FI_ERR_INVALID_ARG, "fi_create: reserved fields must be 0");
   if (cfg->head_dim != kHeadDim) return set_error(FI_ERR_UNSUPPORTED, "fi_create: only head_dim = 128 is built");
@@ -84,8 +86,17 @@ int32_t fi_create(const fi_config* cfg, fi_handle** out) {
   pp.group = g;
   pp.t_pos = cfg->mode == FI_MODE_DECODE ? 1 : append_tile_rows() / g;
   pp.ctas_per_head = num_ctas / cfg->num_kv_heads > 0 ? num_ctas / cfg->num_kv_heads : 1;
-  pp.alpha = (cfg->alpha == 0 && cfg->beta == 0) ? 1 : cfg->alpha;
-  pp.beta = (cfg->alpha == 0 && cfg->beta == 0) ? 1 : cfg->beta;
+  // Decode items are short and many: the greedy pass of Algorithm 1 balances them to about 1 %.  Append
+  // items are few and long (C3: 4.8 per CTA): there the refined assignment is the default, with the cost
+  // measured on this kernel: 19 800 cycles per item + 48 per token, 64 % of that per token for a tile of at most
+  // 128 fused rows (at most one live wavefront per SIMD), i.e. alpha : beta = 8 : 5 with T_q = 256.
+  pp.refine = cfg->balance == 2 || (cfg->balance == 0 && cfg->mode == FI_MODE_APPEND);
+  const bool default_cost = cfg->alpha == 0 && cfg->beta == 0;
+  pp.alpha = default_cost ? (pp.refine && cfg->mode == FI_MODE_APPEND ? 8 : 1) : cfg->alpha;
+  pp.beta = default_cost ? (pp.refine && cfg->mode == FI_MODE_APPEND ? 5 : 1) : cfg->beta;
+  pp.light_rows = (pp.refine && cfg->mode == FI_MODE_APPEND) ? append_tile_rows() / 2 : 0;
+  pp.light_pct = 64;
+  pp.kv_quantum = (pp.refine && cfg->mode == FI_MODE_APPEND) ? 64 : 1;  // the append kernel's KV tile
   // default: decode chunks of at least 128 tokens (4 steps of a wavefront), append chunks of 256
   pp.min_chunk = cfg->min_chunk > 0 ? cfg->min_chunk : (cfg->mode == FI_MODE_DECODE ? 128 : 256);
   pp.literal_lkv = cfg->literal_lkv != 0;

@@ -50,7 +50,7 @@ struct MergeParams {
 // decode.hip: query tile = 1 position x g fused heads, one wavefront per CTA.
 // kv8: the pools hold OCP E4M3 codes (App. F) instead of the query type.
 hipError_t launch_decode(const RunParams& p, bool is_bf16, bool kv8, hipStream_t stream);
-// append.hip: query tile = append_tile_rows()/g positions x g fused heads, 4 wavefronts per CTA.
+// append.hip: query tile = append_tile_rows()/g positions x g fused heads, 8 wavefronts per CTA.
 hipError_t launch_append(const RunParams& p, bool is_bf16, hipStream_t stream);
 int append_tile_rows();  // fused rows (positions x group) of one append query tile
 // upload.hip: staging (device view of page-locked host memory) -> plan section

@@ -150,12 +150,79 @@ int32_t make_plan(const PlanParams& pp, const WorkspaceLayout& L, const int32_t*
   for (int32_t c = 0; c < C; ++c) heap.push({0, c});
   std::vector<std::vector<int32_t>> queues(static_cast<size_t>(C));
   const int64_t t_q = static_cast<int64_t>(pp.t_pos) * pp.group;
+  // cost(l_q, l_kv) = alpha * T_q + beta * l_kv; with the refinement in percent, the per-token term of a
+  // light tile weighted by light_pct
+  const int64_t unit = pp.refine ? 100 : 1;
+  std::vector<int64_t> cost(static_cast<size_t>(n_work));
+  for (int32_t w = 0; w < n_work; ++w) {
+    const Tile& tl = tiles[chunks[w].tile];
+    const bool light = pp.refine && pp.light_rows > 0 && static_cast<int64_t>(tl.n_pos) * pp.group <= pp.light_rows;
+    int64_t l_kv = chunks[w].kv_len;
+    if (pp.refine) l_kv = (l_kv + pp.kv_quantum - 1) / pp.kv_quantum * pp.kv_quantum;
+    cost[w] = unit * pp.alpha * t_q + static_cast<int64_t>(pp.beta) * l_kv * (light ? pp.light_pct : unit);
+  }
+  std::vector<int64_t> load(static_cast<size_t>(C), 0);
   for (int32_t w : order) {
     Entry e = heap.top();
     heap.pop();
     queues[e.second].push_back(w);
-    e.first += pp.alpha * t_q + static_cast<int64_t>(pp.beta) * chunks[w].kv_len;
+    e.first += cost[w];
+    load[e.second] = e.first;
     heap.push(e);
+  }
+
+  // ---- refinement: while it lowers the maximum, move one item out of the most loaded CTA or swap it for a
+  //      cheaper one (first best candidate in (cta, item, partner) order; a fixed number of rounds at most) ----
+  if (pp.refine) {
+    for (int32_t round = 0; round < 4 * C + 64; ++round) {
+      int32_t hi = 0;
+      for (int32_t c = 1; c < C; ++c)
+        if (load[c] > load[hi]) hi = c;
+      int64_t best_new = load[hi];
+      int32_t best_lo = -1, best_a = -1, best_b = -1;  // positions in the queues
+      for (int32_t lo = 0; lo < C; ++lo) {
+        if (lo == hi) continue;
+        for (size_t ia = 0; ia < queues[hi].size(); ++ia) {
+          const int64_t ca = cost[queues[hi][ia]];
+          const int64_t moved = std::max(load[hi] - ca, load[lo] + ca);
+          if (moved < best_new) {
+            best_new = moved;
+            best_lo = lo;
+            best_a = static_cast<int32_t>(ia);
+            best_b = -1;
+          }
+          for (size_t ib = 0; ib < queues[lo].size(); ++ib) {
+            const int64_t cb = cost[queues[lo][ib]];
+            if (cb >= ca) continue;
+            const int64_t swapped = std::max(load[hi] - ca + cb, load[lo] + ca - cb);
+            if (swapped < best_new) {
+              best_new = swapped;
+              best_lo = lo;
+              best_a = static_cast<int32_t>(ia);
+              best_b = static_cast<int32_t>(ib);
+            }
+          }
+        }
+      }
+      if (best_lo < 0) break;
+      const int32_t wa = queues[hi][best_a];
+      queues[hi].erase(queues[hi].begin() + best_a);
+      load[hi] -= cost[wa];
+      load[best_lo] += cost[wa];
+      if (best_b >= 0) {
+        const int32_t wb = queues[best_lo][best_b];
+        queues[best_lo].erase(queues[best_lo].begin() + best_b);
+        load[best_lo] -= cost[wb];
+        load[hi] += cost[wb];
+        queues[hi].push_back(wb);
+      }
+      queues[best_lo].push_back(wa);
+    }
+    // a queue runs its longest chunk first, as the greedy pass left it
+    for (auto& q : queues)
+      std::stable_sort(q.begin(), q.end(), [&](int32_t a, int32_t b) {
+        return chunks[a].kv_len != chunks[b].kv_len ? chunks[a].kv_len > chunks[b].kv_len : a < b;
+      });
   }
 
   // ---- emit the plan section ----

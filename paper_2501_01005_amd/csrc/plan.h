@@ -47,6 +47,15 @@ struct PlanParams {
   int32_t min_chunk = 16;
   bool causal = false;
   bool literal_lkv = false;
+  // Load balance beyond the greedy assignment of Algorithm 1 (off = the algorithm as printed):
+  // a work item whose fused rows (n_pos * group) fit in `light_rows` costs `light_pct` percent of
+  // the per-token term (such a tile leaves wavefronts of the append kernel idle), and after the
+  // greedy pass items are moved or swapped out of the most loaded CTA while that lowers the maximum.
+  // With the refinement the chunk length is also rounded up to whole tiles of kv_quantum tokens.
+  bool refine = false;
+  int32_t light_rows = 0;
+  int32_t light_pct = 100;
+  int32_t kv_quantum = 1;
   int32_t max_batch = 0;
   int32_t max_qo_tiles = 0;
 };

@@ -40,12 +40,13 @@ def indptrs(qo, kv, ps=16):
     return qo_indptr, kv_indptr, last
 
 
-def compare(h, qo, kv, causal, t_pos, g, C, alpha, beta, min_chunk, literal=False):
+def compare(h, qo, kv, causal, t_pos, g, C, alpha, beta, min_chunk, literal=False, refine=False, light_rows=0):
     qo_indptr, kv_indptr, last = indptrs(qo, kv)
     fi.fi_plan(h, qo_indptr, kv_indptr, last, causal)
     got = fi.fi_plan_view(h)
     want = plan_replica(qo_indptr, kv_indptr, last, page_size=16, t_pos=t_pos, group=g, num_ctas=C, causal=causal,
-                        alpha=alpha, beta=beta, min_chunk=min_chunk, literal_lkv=literal)
+                        alpha=alpha, beta=beta, min_chunk=min_chunk, literal_lkv=literal, refine=refine,
+                        light_rows=light_rows, light_pct=64, kv_quantum=64 if light_rows else 1)
     assert got["l_kv_chunk"] == want["L_kv"] and got["n_work"] == want["n_work"]
     assert got["n_merge"] == want["n_merge"] and got["n_slots"] == want["n_slots"]
     assert got["t_pos"] == t_pos and got["group"] == g and got["ctas_per_head"] == C
@@ -60,11 +61,14 @@ def test_planner_equals_replica_on_random_length_sets(mode):
     n_cases = 0
     for g in (1, 4):
         for C in (1, 5, 32, 256):
-            for (alpha, beta, min_chunk) in ((1, 1, 16), (0, 1, 256), (3, 2, 64)):
+            # (alpha, beta, min_chunk, balance): 1 = Algorithm 1 as printed, 2 = with the refinement
+            for (alpha, beta, min_chunk, balance) in ((1, 1, 16, 1), (0, 1, 256, 1), (3, 2, 64, 2), (8, 5, 128, 2)):
                 t_pos = 1 if mode == "decode" else 256 // g
                 h = make(fi.FI_MODE_DECODE if mode == "decode" else fi.FI_MODE_APPEND, g, C, alpha=alpha, beta=beta,
-                         min_chunk=min_chunk)
-                for trial in range(25):
+                         min_chunk=min_chunk, balance=balance)
+                refine = balance == 2
+                light_rows = 128 if (refine and mode == "append") else 0
+                for trial in range(20):
                     B = int(rng.integers(1, 48))
                     if mode == "decode":
                         qo = np.ones(B, dtype=np.int64)
@@ -81,7 +85,8 @@ def test_planner_equals_replica_on_random_length_sets(mode):
                         kv = qo + rng.integers(0, 3000, size=B)
                         if rng.random() < 0.2:
                             kv = np.maximum(kv - rng.integers(0, 100, size=B), 0)
-                    compare(h, qo, kv, mode == "append", t_pos, g, C, alpha, beta, min_chunk)
+                    compare(h, qo, kv, mode == "append", t_pos, g, C, alpha, beta, min_chunk, refine=refine,
+                            light_rows=light_rows)
                     n_cases += 1
                 fi.fi_destroy(h)
     assert n_cases >= 600
@@ -97,10 +102,15 @@ def test_planner_equals_replica_on_the_benchmark_length_sets():
     fi.fi_destroy(h)
     g3 = np.random.Generator(np.random.PCG64(1003))
     qo = g3.integers(128, 1025, size=16); pre = g3.integers(0, 4097, size=16)
-    h = make(fi.FI_MODE_APPEND, 4, 64, Hkv=8, max_batch=16, max_tiles=1024, min_chunk=256)
+    # append defaults: refined assignment with the measured cost (alpha, beta) = (8, 5), light tiles at 64 %
+    for C in (32, 64):
+        h = make(fi.FI_MODE_APPEND, 4, C, Hkv=8, max_batch=16, max_tiles=1024, min_chunk=256)
+        compare(h, qo, qo + pre, True, 64, 4, C, 8, 5, 256, refine=True, light_rows=128)
+        fi.fi_destroy(h)
+    h = make(fi.FI_MODE_APPEND, 4, 64, Hkv=8, max_batch=16, max_tiles=1024, min_chunk=256, balance=1)
     compare(h, qo, qo + pre, True, 64, 4, 64, 1, 1, 256)
     fi.fi_destroy(h)
-    h = make(fi.FI_MODE_APPEND, 4, 64, Hkv=8, max_batch=16, max_tiles=1024, min_chunk=256, literal_lkv=1)
+    h = make(fi.FI_MODE_APPEND, 4, 64, Hkv=8, max_batch=16, max_tiles=1024, min_chunk=256, literal_lkv=1, balance=1)
     compare(h, qo, qo + pre, True, 64, 4, 64, 1, 1, 256, literal=True)
     fi.fi_destroy(h)
 
