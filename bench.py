@@ -206,6 +206,9 @@ def main() -> int:
                     help="fp8: K/V stored as E4M3 codes with scales (App. F), decode workloads c2 and c4 only")
     ap.add_argument("--num-ctas", type=int, default=0)
     ap.add_argument("--min-chunk", type=int, default=0)
+    ap.add_argument("--balance", type=int, default=0, help="fi_config.balance (0 = default of the mode)")
+    ap.add_argument("--alpha", type=int, default=0, help="fi_config.alpha (with --beta; 0, 0 = default)")
+    ap.add_argument("--beta", type=int, default=0)
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (no multi-GPU path exists); use --gpus 1", file=sys.stderr)
@@ -241,7 +244,8 @@ def main() -> int:
     batch = getattr(workloads, "config" + args.workload[1])(small=args.small, **cfg_kw)
     mode = "append" if args.workload == "c3" else "decode"
     dev = DeviceBatch(batch, kv_layout=args.kv_layout)
-    w = make_wrapper(batch, mode, num_ctas=args.num_ctas, min_chunk=args.min_chunk)
+    w = make_wrapper(batch, mode, num_ctas=args.num_ctas, min_chunk=args.min_chunk, balance=args.balance,
+                     alpha=args.alpha, beta=args.beta)
     nnz = dev.q.shape[0]
     o = torch.empty((nnz, batch.num_qo_heads, batch.head_dim), dtype=torch.float32, device=dev.device)
     lse = torch.empty((nnz, batch.num_qo_heads), dtype=torch.float32, device=dev.device)
