@@ -161,6 +161,12 @@ def test_argument_errors():
     # fi_run needs a plan that went to a device workspace
     dummy = np.zeros(64, dtype=np.uint8)
     expect(fi.FI_ERR_NOT_PLANNED, fi.fi_run, h, dummy, dummy, dummy, (1, 1, 1), dummy, 1.0, dummy, dummy)
+    expect(fi.FI_ERR_NOT_PLANNED, fi.fi_run_kv8, h, dummy, dummy, dummy, (8, 8, 8), dummy, 1.0, 1.0, 1.0, dummy, dummy)
+    expect(fi.FI_ERR_INVALID_ARG, fi.fi_run_kv8, h, dummy, dummy, dummy, (8, 8, 8), dummy, 1.0, 0.0, 1.0, dummy, dummy)
+    expect(fi.FI_ERR_INVALID_ARG, fi.fi_create, **{**ok, "balance": 3})
+    ha = fi.fi_create(**{**ok, "mode": fi.FI_MODE_APPEND})
+    expect(fi.FI_ERR_UNSUPPORTED, fi.fi_run_kv8, ha, dummy, dummy, dummy, (8, 8, 8), dummy, 1.0, 1.0, 1.0, dummy, dummy)
+    fi.fi_destroy(ha)
     # workspace too small is detected before anything is touched
     expect(fi.FI_ERR_WORKSPACE_TOO_SMALL, fi.fi_plan, h, [0, 1], [0, 1], [3], False, workspace=dummy,
            workspace_bytes=64)
