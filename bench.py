@@ -204,6 +204,7 @@ def main() -> int:
                     help="pool layout in memory: [page, head, slot, D] (default, tuned) or [page, slot, head, D]")
     ap.add_argument("--kv-dtype", default="same", choices=["same", "fp8"],
                     help="fp8: K/V stored as E4M3 codes with scales (App. F), decode workloads c2 and c4 only")
+    ap.add_argument("--page-size", type=int, default=16, help="tokens per page (c2 and c3; 16 is the tuned size)")
     ap.add_argument("--num-ctas", type=int, default=0)
     ap.add_argument("--min-chunk", type=int, default=0)
     ap.add_argument("--balance", type=int, default=0, help="fi_config.balance (0 = default of the mode)")
@@ -241,6 +242,11 @@ def main() -> int:
             print("bench.py: --kv-dtype fp8 is for the decode workloads c2 and c4", file=sys.stderr)
             return 2
         cfg_kw["kv_dtype"] = workloads.FP8
+    if args.page_size != 16:
+        if args.workload not in ("c2", "c3"):
+            print("bench.py: --page-size is for c2 and c3", file=sys.stderr)
+            return 2
+        cfg_kw["page_size"] = args.page_size
     batch = getattr(workloads, "config" + args.workload[1])(small=args.small, **cfg_kw)
     mode = "append" if args.workload == "c3" else "decode"
     dev = DeviceBatch(batch, kv_layout=args.kv_layout)

@@ -64,7 +64,8 @@ typedef struct fi_config {
   int32_t num_qo_heads; /* H_qo                                                                */
   int32_t num_kv_heads; /* H_kv; g = H_qo / H_kv must be an integer                            */
   int32_t head_dim;     /* D (128)                                                             */
-  int32_t page_size;    /* B_c of the BSR cache (16)                                           */
+  int32_t page_size;    /* B_c of the BSR cache: a power of two in 1..64.  16 is the size the
+                           kernels are tuned for; the others run general code paths (slower)   */
   int32_t mode;         /* FI_MODE_*                                                           */
   int32_t num_ctas;     /* total persistent CTAs over all kv heads; 0 = library default for
                            the current device (needs a GPU); CTAs per kv head = num_ctas/H_kv   */
@@ -116,7 +117,7 @@ typedef struct fi_plan_arrays {
 } fi_plan_arrays;
 
 /* Create / destroy a handle.  cfg HOST.  FI_ERR_UNSUPPORTED unless head_dim = 128,
- * page_size = 16, g in {1,2,4} (decode) / g in {1,2,4,8} (append).  With num_ctas = 0 the
+ * page_size a power of two in 1..64, g in {1,2,4} (decode) / g in {1,2,4,8} (append).  With num_ctas = 0 the
  * current HIP device is queried (FI_ERR_HIP without one). */
 int32_t fi_create(const fi_config* cfg, fi_handle** out);
 int32_t fi_destroy(fi_handle* h);

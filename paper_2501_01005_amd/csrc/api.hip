@@ -59,7 +59,8 @@ int32_t fi_create(const fi_config* cfg, fi_handle** out) {
   for (int r : cfg->reserved)
     if (r != 0) return set_error(FI_ERR_INVALID_ARG, "fi_create: reserved fields must be 0");
   if (cfg->head_dim != kHeadDim) return set_error(FI_ERR_UNSUPPORTED, "fi_create: only head_dim = 128 is built");
-  if (cfg->page_size != kPageSize) return set_error(FI_ERR_UNSUPPORTED, "fi_create: only page_size = 16 is built");
+  if (cfg->page_size < 1 || cfg->page_size > 64 || (cfg->page_size & (cfg->page_size - 1)) != 0)
+    return set_error(FI_ERR_UNSUPPORTED, "fi_create: page_size must be a power of two between 1 and 64");
   const int g = cfg->num_qo_heads / cfg->num_kv_heads;
   if (cfg->mode == FI_MODE_DECODE && !(g == 1 || g == 2 || g == 4))
     return set_error(FI_ERR_UNSUPPORTED, "fi_create: decode mode is built for group size 1, 2, 4");
@@ -251,6 +252,8 @@ int32_t run_impl(fi_handle* h, const void* q, const void* k_pool, const void* v_
   p.group = h->pp.group;
   p.t_pos = h->pp.t_pos;
   p.ctas_per_head = h->pp.ctas_per_head;
+  p.page_log2 = 0;
+  while ((1 << p.page_log2) < h->cfg.page_size) ++p.page_log2;
   const bool bf = h->cfg.dtype == FI_DTYPE_BF16;
   hipStream_t s = static_cast<hipStream_t>(stream);
   hipError_t e;

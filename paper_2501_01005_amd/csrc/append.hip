@@ -263,7 +263,8 @@ __device__ __attribute__((noinline)) void generic_work_item(uint64_t params_addr
   const int kv_len = __builtin_amdgcn_readfirstlane(a_kv_len), diag0 = __builtin_amdgcn_readfirstlane(a_diag0);
   const int out_slot = __builtin_amdgcn_readfirstlane(a_out_slot);
   const bool causal = diag0 != kNoDiagMarker;
-  const int n_pages = (kv_len + kPageSize - 1) / kPageSize;
+  const int ps_log2 = p.page_log2;  // 4 on the tuned path; any power of two up to 64 here (64 % page_size == 0)
+  const int n_pages = (kv_len + (1 << ps_log2) - 1) >> ps_log2;
   const int n_tiles = (kv_len + kTileKv - 1) / kTileKv;
 
   // ---- this lane's query rows, one per 32-row block ----
@@ -317,19 +318,36 @@ __device__ __attribute__((noinline)) void generic_work_item(uint64_t params_addr
   u32x4_t stage_k[2][2], stage_v[2][2];
   // Page ids are fetched one tile ahead of the data they address (lane r holds page r of the
   // tile), so that the data loads never wait behind an index load.
-  auto fetch_page_ids = [&](int t) -> int {
+  // (page size 16: lane r holds page r of the tile; other page sizes: every thread holds the pages of its own
+  // two staging rows, in the low and the high half)
+  auto fetch_page_ids = [&](int t) -> int64_t {
+    if (ps_log2 != 4) {
+      const int pa = min((kTileKv * t + st_tok) >> ps_log2, n_pages - 1);
+      const int pb = min((kTileKv * t + 32 + st_tok) >> ps_log2, n_pages - 1);
+      const uint32_t ia = static_cast<uint32_t>(p.kv_indices[kv_page0 + pa]);
+      const uint32_t ib = static_cast<uint32_t>(p.kv_indices[kv_page0 + pb]);
+      return static_cast<int64_t>(ia | (static_cast<uint64_t>(ib) << 32));
+    }
     int pi = 4 * t + (lane & 3);
     pi = pi < n_pages ? pi : n_pages - 1;  // never index past the chunk's pages
     return p.kv_indices[kv_page0 + pi];
   };
-  auto fetch_tile = [&](auto set_c, int ids) {
+  auto fetch_tile = [&](auto set_c, int64_t ids) {
     constexpr int SET = decltype(set_c)::value;
 #pragma unroll
     for (int r = 0; r < 2; ++r) {
-      const int pg = __builtin_amdgcn_readlane(ids, 2 * r + st_page);
-      const int64_t page_off = pg * p.stride_page + kvh * p.stride_head;  // wave-uniform
-      stage_k[SET][r] = *reinterpret_cast<const u32x4_t*>(kpool + page_off + st_off);
-      stage_v[SET][r] = *reinterpret_cast<const u32x4_t*>(vpool + page_off + st_off);
+      if (ps_log2 != 4) {  // CTA-uniform
+        const int64_t pg = static_cast<int32_t>(r == 0 ? ids : (ids >> 32));
+        const int slot = (32 * r + st_tok) & ((1 << ps_log2) - 1);  // a tile starts on a page boundary
+        const int64_t off = pg * p.stride_page + kvh * p.stride_head + slot * p.stride_tok + st_chunk * 8;
+        stage_k[SET][r] = *reinterpret_cast<const u32x4_t*>(kpool + off);
+        stage_v[SET][r] = *reinterpret_cast<const u32x4_t*>(vpool + off);
+      } else {
+        const int pg = __builtin_amdgcn_readlane(static_cast<int>(ids), 2 * r + st_page);
+        const int64_t page_off = pg * p.stride_page + kvh * p.stride_head;  // wave-uniform
+        stage_k[SET][r] = *reinterpret_cast<const u32x4_t*>(kpool + page_off + st_off);
+        stage_v[SET][r] = *reinterpret_cast<const u32x4_t*>(vpool + page_off + st_off);
+      }
     }
   };
   auto store_tile = [&](auto set_c, int t) {
@@ -363,7 +381,7 @@ __device__ __attribute__((noinline)) void generic_work_item(uint64_t params_addr
   __syncthreads();   // the previous work item's last tile is no longer being read
   // One tile: consume tile t, then hand tile t + 1 over from staging set SET = (t + 1) % 2.  The
   // tile loop below is unrolled by two so that SET is a compile-time constant.
-  auto do_tile = [&](auto set_c, int t, int& ids_load, const int& ids_use) {
+  auto do_tile = [&](auto set_c, int t, int64_t& ids_load, const int64_t& ids_use) {
     const uint16_t* tk = lds_k + (t & 1) * (kTileKv * kRowElems);
     const uint16_t* tv = lds_v + (t & 1) * (kTileKv * kRowElemsV);
 #pragma unroll
@@ -486,8 +504,8 @@ __device__ __attribute__((noinline)) void generic_work_item(uint64_t params_addr
     __syncthreads();  // tile t + 1 is visible; nobody reads tile t any more
   };
   if (n_tiles > 0) {  // one region, so that the loop is entered with this work item's Q loads known complete
-    const int ids0 = fetch_page_ids(0), ids1 = fetch_page_ids(1);
-    int ids_even = fetch_page_ids(2), ids_odd = fetch_page_ids(3);  // ids of the next even / odd tile to request
+    const int64_t ids0 = fetch_page_ids(0), ids1 = fetch_page_ids(1);
+    int64_t ids_even = fetch_page_ids(2), ids_odd = fetch_page_ids(3);  // ids of the next even / odd tile to request
     fetch_tile(set0_t{}, ids0);
     fetch_tile(set1_t{}, ids1);
     store_tile(set0_t{}, 0);
@@ -571,7 +589,7 @@ append_kernel(const RunParams p) {
       const int64_t page_bytes = p.stride_page * 2;
       // (the loop addresses its outputs with 32-bit byte offsets)
       const int64_t out_rows_bound = (out_slot < 0 ? static_cast<int64_t>(q_row0) + p.t_pos : (static_cast<int64_t>(out_slot) + 1) * p.t_pos) * H;
-      if (n_full >= 1 && kv_len >= kLoopMinTokens && page_bytes > 0 && page_bytes < (int64_t(1) << 32) &&
+      if (p.page_log2 == 4 && n_full >= 1 && kv_len >= kLoopMinTokens && page_bytes > 0 && page_bytes < (int64_t(1) << 32) &&
           out_rows_bound * (kHeadDim * 4) < (int64_t(1) << 32)) {
         // The loop clobbers nearly every vector register, so its lane-dependent operands are
         // derived here from an opaque copy of the thread index: the compiler cannot hoist them out

@@ -105,7 +105,9 @@ struct KvTile {
   Piece v[2][4];  // [page][i]:        V[token 4 c + i][d = 8 m .. +8]
 };
 
-template <bool BF, bool KV8>
+// ANYPS: the page size is a run-time power of two instead of 16 (Sec. 3.1.1: the block size B_c of the
+// BSR cache is a free parameter); every lane then looks up the page of each token row it loads.
+template <bool BF, bool KV8, bool ANYPS>
 __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2))) decode_kernel(const RunParams p) {
   const int lane = threadIdx.x;
   const int m = lane & 15;  // K: token in page; V: 16-byte column block; S/O: query head
@@ -126,6 +128,9 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2)))
       static_cast<const uint8_t*>(p.v_pool) + (kvh * p.stride_head + (4 * c) * p.stride_tok + m * 8) * kElem;
   const int64_t stride_tok = p.stride_tok * kElem;    // bytes from here on
   const int64_t stride_page = p.stride_page * kElem;
+  // this lane's 8 columns of slot 0 of page 0 of the kv head (ANYPS adds page and slot per row)
+  const uint8_t* khead = static_cast<const uint8_t*>(p.k_pool) + (kvh * p.stride_head + m * 8) * kElem;
+  const uint8_t* vhead = static_cast<const uint8_t*>(p.v_pool) + (kvh * p.stride_head + m * 8) * kElem;
   auto ld_piece = [](const uint8_t* ptr) {
     if constexpr (KV8) {
       return ld8_stream(ptr);
@@ -153,7 +158,8 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2)))
     const int kv_page0 = w_kv_page0[w];
     const int kv_len = w_kv_len[w];
     const int out_slot = w_out_slot[w];
-    const int n_pages = (kv_len + kPageSize - 1) / kPageSize;
+    const int ps_log2 = ANYPS ? p.page_log2 : 4;
+    const int n_pages = (kv_len + (1 << ps_log2) - 1) >> ps_log2;
     const int n_tiles = (kv_len + 31) / 32;
 
     // Q^T as the B operand of the first product: lane (m, c) holds head m, d = 32 s + 8 c .. +8
@@ -175,6 +181,24 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2)))
     float l_run = 0.f;      // this lane's share of the running sum
 
     auto load_tile = [&](Tile& T, int t) {
+      if constexpr (ANYPS) {
+        // row of chunk-local token tok: page tok >> ps_log2 (clamped to the chunk's last page: rows past the
+        // end are masked later), slot tok % page_size
+        auto row = [&](const uint8_t* base, int tok) {
+          const int pg = min(tok >> ps_log2, n_pages - 1);
+          const int64_t id = p.kv_indices[kv_page0 + pg];
+          return base + id * stride_page + (tok & ((1 << ps_log2) - 1)) * stride_tok;
+        };
+#pragma unroll
+        for (int pg = 0; pg < 2; ++pg)
+#pragma unroll
+          for (int s = 0; s < 4; ++s) T.k[pg][s] = ld_piece(row(khead, 32 * t + 16 * pg + 4 * s + c));
+#pragma unroll
+        for (int pg = 0; pg < 2; ++pg)
+#pragma unroll
+          for (int i = 0; i < 4; ++i) T.v[pg][i] = ld_piece(row(vhead, 32 * t + 16 * pg + 4 * c + i));
+        return;
+      }
       const int pi = kv_page0 + 2 * t;
       int pg0, pg1;
       if constexpr (KV8) {
@@ -385,20 +409,30 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2)))
 
 }  // namespace
 
-hipError_t launch_decode(const RunParams& p, bool is_bf16, bool kv8, hipStream_t stream) {
+namespace {
+template <bool ANYPS>
+void launch_decode_ps(const RunParams& p, bool is_bf16, bool kv8, hipStream_t stream) {
   const dim3 grid(static_cast<unsigned>(p.ctas_per_head), static_cast<unsigned>(p.num_kv_heads), 1);
   const dim3 block(64, 1, 1);
   if (kv8) {
     if (is_bf16)
-      hipLaunchKernelGGL((decode_kernel<true, true>), grid, block, 0, stream, p);
+      hipLaunchKernelGGL((decode_kernel<true, true, ANYPS>), grid, block, 0, stream, p);
     else
-      hipLaunchKernelGGL((decode_kernel<false, true>), grid, block, 0, stream, p);
+      hipLaunchKernelGGL((decode_kernel<false, true, ANYPS>), grid, block, 0, stream, p);
   } else {
     if (is_bf16)
-      hipLaunchKernelGGL((decode_kernel<true, false>), grid, block, 0, stream, p);
+      hipLaunchKernelGGL((decode_kernel<true, false, ANYPS>), grid, block, 0, stream, p);
     else
-      hipLaunchKernelGGL((decode_kernel<false, false>), grid, block, 0, stream, p);
+      hipLaunchKernelGGL((decode_kernel<false, false, ANYPS>), grid, block, 0, stream, p);
   }
+}
+}  // namespace
+
+hipError_t launch_decode(const RunParams& p, bool is_bf16, bool kv8, hipStream_t stream) {
+  if (p.page_log2 == 4)
+    launch_decode_ps<false>(p, is_bf16, kv8, stream);
+  else
+    launch_decode_ps<true>(p, is_bf16, kv8, stream);
   return hipGetLastError();
 }
 

@@ -31,6 +31,7 @@ struct RunParams {
   float out_scale;  // 8-bit KV cache: the V scale; 1 otherwise
   int32_t num_qo_heads, num_kv_heads, group, t_pos;
   int32_t ctas_per_head;
+  int32_t page_log2;  // log2 of the page size (tokens per page)
 };
 
 struct MergeParams {
@@ -65,7 +66,7 @@ hipError_t launch_merge_pair(const float* o_a, const float* lse_a, const float* 
 
 constexpr int kNoDiagMarker = 0x3FFFFFFF;  // w_diag0 of a non-causal work item
 constexpr int kHeadDim = 128;
-constexpr int kPageSize = 16;
+constexpr int kPageSize = 16;  // the page size the fast paths are specialised for
 constexpr int kMergeGrid = 1024;  // fixed grid of the planned merge launch
 
 }  // namespace fi355

@@ -1,0 +1,48 @@
+"""GPU parity for page sizes other than the tuned 16 (Sec. 3.1.1: the block size of the BSR cache is a free
+parameter; App. B compares page sizes): decode and append go through their general code paths, where every
+lane or staging thread looks up the page of the token row it loads."""
+import numpy as np
+import pytest
+
+import oracle
+import workloads
+from gpu_util import DeviceBatch, assert_close, run_gpu
+
+pytestmark = pytest.mark.gpu
+
+
+def check(batch, mode, what, dev=None, **kw):
+    print(f"[case] {what}: {batch.name} mode={mode} page_size={batch.page_size} dtype={batch.dtype} kv={batch.kv_dtype} "
+          f"qo={batch.qo_lens()[:8].tolist()} kv_len={batch.kv_lens()[:8].tolist()} kw={kw}", flush=True)
+    o_ref, lse_ref = oracle.run_batch(batch)
+    o, lse = run_gpu(batch, mode, dev=dev, **kw)
+    e = assert_close(o, lse, o_ref, lse_ref, what)
+    print(f"[ok] {what}: err_o={e[0]:.2e} err_lse={e[1]:.2e}", flush=True)
+
+
+@pytest.mark.parametrize("ps", [1, 2, 8, 32, 64])
+def test_decode(ps):
+    for seed, dtype, kv_dtype in ((301, workloads.BF16, ""), (302, workloads.F16, ""), (303, workloads.BF16, workloads.FP8)):
+        b = workloads.random_case(seed + ps, dtype=dtype, num_qo_heads=8, num_kv_heads=2, page_size=ps, batch=6,
+                                  max_kv=400, kv_dtype=kv_dtype, k_scale=0.5 if kv_dtype else 1.0,
+                                  v_scale=2.0 if kv_dtype else 1.0)
+        check(b, "decode", f"decode ps={ps}")
+    # long requests split over many CTAs (partial slots + merge), chunk boundaries on page boundaries
+    b = workloads.make_batch("long", 310 + ps, workloads.BF16, 8, 2, 128, ps, [1, 1, 1], [2500, 77, 600], False)
+    check(b, "decode", f"decode split ps={ps}", num_ctas=2 * 16, min_chunk=64)
+
+
+@pytest.mark.parametrize("ps", [1, 8, 32, 64])
+def test_append(ps):
+    for seed, dtype, causal in ((321, workloads.BF16, True), (322, workloads.F16, False)):
+        b = workloads.make_batch("app", seed + ps, dtype, 8, 2, 128, ps, [70, 9, 130, 1], [400, 9, 333, 64], causal)
+        check(b, "append", f"append ps={ps} causal={causal}", num_ctas=2 * 4, min_chunk=128)
+    b = workloads.make_batch("appsplit", 330 + ps, workloads.BF16, 8, 2, 128, ps, [64, 30], [1000, 777], True)
+    check(b, "append", f"append split ps={ps}", num_ctas=2 * 16, min_chunk=128)
+
+
+def test_strided_layout_with_small_pages():
+    b = workloads.make_batch("nhd_ps8", 340, workloads.BF16, 8, 2, 128, 8, [1, 1, 1], [333, 64, 200], False)
+    check(b, "decode", "decode NHD ps=8", dev=DeviceBatch(b, kv_layout="NHD"))
+    b = workloads.make_batch("nhd_ps8a", 341, workloads.BF16, 8, 2, 128, 8, [40, 3], [300, 64], True)
+    check(b, "append", "append NHD ps=8", dev=DeviceBatch(b, kv_layout="NHD"), num_ctas=2 * 4, min_chunk=128)

@@ -142,7 +142,8 @@ def test_argument_errors():
     ok = dict(dtype=fi.FI_DTYPE_BF16, num_qo_heads=32, num_kv_heads=8, head_dim=128, page_size=16,
               mode=fi.FI_MODE_DECODE, num_ctas=64, max_batch=4, max_qo_tiles=4)
     expect(fi.FI_ERR_UNSUPPORTED, fi.fi_create, **{**ok, "head_dim": 64})
-    expect(fi.FI_ERR_UNSUPPORTED, fi.fi_create, **{**ok, "page_size": 8})
+    expect(fi.FI_ERR_UNSUPPORTED, fi.fi_create, **{**ok, "page_size": 12})
+    expect(fi.FI_ERR_UNSUPPORTED, fi.fi_create, **{**ok, "page_size": 128})
     expect(fi.FI_ERR_UNSUPPORTED, fi.fi_create, **{**ok, "num_qo_heads": 64})       # g = 8 in decode mode
     expect(fi.FI_ERR_INVALID_ARG, fi.fi_create, **{**ok, "num_qo_heads": 30})
     expect(fi.FI_ERR_INVALID_ARG, fi.fi_create, **{**ok, "dtype": 7})

@@ -248,7 +248,7 @@ def config1(small: bool = False) -> PagedBatch:
     return make_batch("c1_mha_decode", 1001, F16, 8, 8, 128, 16, [1] * 4, kv, causal=False, num_pages=256)
 
 
-def config2(small: bool = False, permute_pages: bool = True, kv_dtype: str = "") -> PagedBatch:
+def config2(small: bool = False, permute_pages: bool = True, kv_dtype: str = "", page_size: int = 16) -> PagedBatch:
     """GQA decode (Llama-3-8B layer shape): batch 128, 32/8 heads, D 128, bf16,
     page 16, l_kv Zipf(s=1.2) over [256, 32768], request 0 forced to 32768.
     small: batch 12, range [64, 2048], request 0 forced to 2048."""
@@ -259,14 +259,14 @@ def config2(small: bool = False, permute_pages: bool = True, kv_dtype: str = "")
     else:
         kv = zipf_lengths(g, 128, 256, 32768, 1.2)
         kv[0] = 32768
-    need = int(((kv + 15) // 16).sum())
-    return make_batch("c2_gqa_decode_zipf" + ("_small" if small else ""), 1002, BF16, 32, 8, 128, 16,
+    need = int(((kv + page_size - 1) // page_size).sum())
+    return make_batch("c2_gqa_decode_zipf" + ("_small" if small else ""), 1002, BF16, 32, 8, 128, page_size,
                       [1] * len(kv), kv, causal=False, num_pages=need + need // 10,
                       poison=small, permute_pages=permute_pages, kv_dtype=kv_dtype,
                       k_scale=0.5 if kv_dtype == FP8 else 1.0, v_scale=2.0 if kv_dtype == FP8 else 1.0)
 
 
-def config3(small: bool = False, permute_pages: bool = True) -> PagedBatch:
+def config3(small: bool = False, permute_pages: bool = True, page_size: int = 16) -> PagedBatch:
     """Causal append/prefill: batch 16, GQA 32/8, D 128, bf16, page 16,
     l_qo ~ U{128..1024}, cached prefix ~ U{0..4096}, l_kv = prefix + l_qo.
     One request has prefix 0, one has l_qo not a multiple of 128.
@@ -282,7 +282,7 @@ def config3(small: bool = False, permute_pages: bool = True) -> PagedBatch:
     if qo[2] % 128 == 0:
         qo[2] += 37
     kv = qo + pre
-    return make_batch("c3_causal_append" + ("_small" if small else ""), 1003, BF16, 32, 8, 128, 16,
+    return make_batch("c3_causal_append" + ("_small" if small else ""), 1003, BF16, 32, 8, 128, page_size,
                       qo, kv, causal=True, permute_pages=permute_pages)
 
 
