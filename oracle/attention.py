@@ -55,16 +55,23 @@ def gather_rows(pool_f64_of, kv_indices, kv_indptr, last_page_len, page_size: in
 
 
 def attention_state(q: np.ndarray, K: np.ndarray, V: np.ndarray, sm_scale: float,
-                    visible: np.ndarray | None = None) -> Tuple[np.ndarray, np.ndarray]:
+                    visible: np.ndarray | None = None, logits_soft_cap: float = 0.0,
+                    bias: np.ndarray | None = None) -> Tuple[np.ndarray, np.ndarray]:
     """Attention states of m queries against n keys.
 
     q [m, D], K [n, D], V [n, D] float64; visible: optional bool [m, n].
-    Returns o [m, D], lse [m].  Rows with no visible key: o = 0, lse = -inf."""
+    Returns o [m, D], lse [m].  Rows with no visible key: o = 0, lse = -inf.
+    Variants of Sec. 3.2.3 (logits transform / mask): with logits_soft_cap = c > 0 the scaled logits
+    become c * tanh(s / c); `bias` [m, n] is added after that (ALiBi); a window is part of `visible`."""
     q = np.asarray(q, dtype=np.float64)
     K = np.asarray(K, dtype=np.float64)
     V = np.asarray(V, dtype=np.float64)
     m, n = q.shape[0], K.shape[0]
     s = sm_scale * (q @ K.T)                            # [m, n]
+    if logits_soft_cap > 0.0:
+        s = logits_soft_cap * np.tanh(s / logits_soft_cap)
+    if bias is not None:
+        s = s + bias
     if visible is not None:
         s = np.where(visible, s, -np.inf)
     o = np.zeros((m, V.shape[1] if V.ndim == 2 else q.shape[1]), dtype=np.float64)
@@ -88,13 +95,30 @@ def causal_visible(l_qo: int, l_kv: int) -> np.ndarray:
     return t <= (l_kv - l_qo + j)
 
 
+def variant_mask_and_bias(l_qo: int, l_kv: int, causal: bool, window_left: int = -1,
+                          alibi_slope: float | None = None):
+    """Visibility and additive bias of one (request, head) under the variants: query j sits at absolute
+    position pos = l_kv - l_qo + j (the appended tokens are already in the cache); a window of
+    `window_left` >= 0 hides tokens t < pos - window_left; ALiBi adds slope * (t - pos)."""
+    j = np.arange(l_qo)[:, None]
+    t = np.arange(l_kv)[None, :]
+    pos = l_kv - l_qo + j
+    vis = (t <= pos) if causal else np.ones((l_qo, l_kv), dtype=bool)
+    if window_left >= 0:
+        vis = vis & (t >= pos - window_left)
+    bias = None if alibi_slope is None else alibi_slope * (t - pos).astype(np.float64)
+    return vis, bias
+
+
 def batch_attention(q_f64: np.ndarray, k_pool_of, v_pool_of, qo_indptr, kv_indptr, kv_indices,
                     last_page_len, page_size: int, num_kv_heads: int, sm_scale: float,
                     causal: bool, requests: Sequence[int] | None = None,
-                    heads: Sequence[int] | None = None) -> Tuple[np.ndarray, np.ndarray]:
+                    heads: Sequence[int] | None = None, logits_soft_cap: float = 0.0,
+                    window_left: int = -1, alibi_slopes=None) -> Tuple[np.ndarray, np.ndarray]:
     """o [nnz_qo, H_qo, D], lse [nnz_qo, H_qo] (float64).
 
-    Entries for requests / heads outside the optional selections are NaN."""
+    Entries for requests / heads outside the optional selections are NaN.  The last three arguments are the
+    attention variants (soft cap of the logits, sliding window, per-head ALiBi slopes)."""
     nnz, H, D = q_f64.shape
     g = H // num_kv_heads
     assert g * num_kv_heads == H
@@ -117,7 +141,12 @@ def batch_attention(q_f64: np.ndarray, k_pool_of, v_pool_of, qo_indptr, kv_indpt
                 cache = {kvh: (gather_rows(k_pool_of, kv_indices, kv_indptr, last_page_len, page_size, i, kvh),
                                gather_rows(v_pool_of, kv_indices, kv_indptr, last_page_len, page_size, i, kvh))}
             K, V = cache[kvh]
-            oo, ll = attention_state(q_f64[r0:r1, h, :], K, V, sm_scale, vis)
+            bias = None
+            vis_h = vis
+            if window_left >= 0 or alibi_slopes is not None:
+                vis_h, bias = variant_mask_and_bias(l_qo, l_kv, causal, window_left,
+                                                    None if alibi_slopes is None else float(alibi_slopes[h]))
+            oo, ll = attention_state(q_f64[r0:r1, h, :], K, V, sm_scale, vis_h, logits_soft_cap, bias)
             o[r0:r1, h, :] = oo
             lse[r0:r1, h] = ll
     return o, lse
