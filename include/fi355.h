@@ -169,6 +169,28 @@ int32_t fi_run_kv8(fi_handle* h, const void* q, const void* k_pool, const void* 
                    float k_scale, float v_scale, float* o, float* lse, void* o_cast,
                    fi_stream stream);
 
+/* Attention variants (Sec. 3.2.3: logits transform and logits mask), applied to the scaled logits
+ * s = sm_scale * q.k of query position pos and key position t in this order:
+ *   logits_soft_cap c > 0:  s <- c * tanh(s / c)                       (0 = off)
+ *   alibi_slopes != NULL:   s <- s + alibi_slopes[query head] * (t - pos)   DEVICE float [num_qo_heads]
+ *   window_left W >= 0:     keys with t < pos - W are hidden            (-1 = off)
+ * pos = l_kv - l_qo + j for query j of a request (the appended tokens are in the cache). */
+typedef struct fi_variant {
+  float logits_soft_cap;
+  int32_t window_left;
+  const float* alibi_slopes;
+} fi_variant;
+
+/* fi_run with a variant.  kv_indptr [batch+1] and last_page_len [batch] are DEVICE copies of the arrays
+ * the batch was planned with (the kernel derives pos from them).  Built for decode mode with 16-bit
+ * pools and page_size 16 (FI_ERR_UNSUPPORTED otherwise); every key of the request is still read, a
+ * window only masks.  variant HOST, read during the call.  Otherwise as fi_run. */
+int32_t fi_run_variant(fi_handle* h, const void* q, const void* k_pool, const void* v_pool,
+                       const int64_t* kv_strides, const int32_t* kv_indices,
+                       const int32_t* kv_indptr, const int32_t* last_page_len, float sm_scale,
+                       const fi_variant* variant, float* o, float* lse, void* o_cast,
+                       fi_stream stream);
+
 /* Measurement hook: with two hipEvent_t handles set, every later fi_run records `before`
  * right before and `after` right after the launch of its attention kernel (the merge launch
  * comes after `after`) on the run's stream, so a caller can time that kernel alone.

@@ -14,7 +14,7 @@ __all__ = [
     "FI_ERR_HIP", "FI_DTYPE_F16", "FI_DTYPE_BF16", "FI_MODE_DECODE", "FI_MODE_APPEND",
     "Fi355Error", "fi_config", "fi_plan_arrays", "lib", "library_path",
     "fi_create", "fi_destroy", "fi_workspace_bytes", "fi_plan", "fi_plan_view", "fi_run", "fi_run_kv8",
-    "fi_merge_states", "fi_merge_state_pair", "fi_check_indices", "fi_set_timing_events", "fi_last_error",
+    "fi_run_variant", "fi_variant", "fi_merge_states", "fi_merge_state_pair", "fi_check_indices", "fi_set_timing_events", "fi_last_error",
     "PagedAttention",
 ]
 
@@ -53,6 +53,10 @@ class fi_config(ctypes.Structure):
 _I32P = ctypes.POINTER(ctypes.c_int32)
 
 
+class fi_variant(ctypes.Structure):
+    _fields_ = [("logits_soft_cap", ctypes.c_float), ("window_left", ctypes.c_int32), ("alibi_slopes", ctypes.c_void_p)]
+
+
 class fi_plan_arrays(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int32) for n in (
         "t_pos", "group", "ctas_per_head", "l_kv_chunk", "n_work", "n_merge", "n_slots", "pad_")] + [
@@ -79,6 +83,8 @@ def _load() -> ctypes.CDLL:
     L.fi_plan.argtypes = [vp, vp, vp, vp, i32, i32, vp, sz, vp, sz, vp]
     L.fi_plan_view.argtypes = [vp, ctypes.POINTER(fi_plan_arrays)]
     L.fi_run.argtypes = [vp, vp, vp, vp, ctypes.POINTER(i64), vp, ctypes.c_float, vp, vp, vp, vp]
+    L.fi_run_variant.argtypes = [vp, vp, vp, vp, ctypes.POINTER(i64), vp, vp, vp, ctypes.c_float,
+                                 ctypes.POINTER(fi_variant), vp, vp, vp, vp]
     L.fi_run_kv8.argtypes = [vp, vp, vp, vp, ctypes.POINTER(i64), vp, ctypes.c_float, ctypes.c_float, ctypes.c_float,
                              vp, vp, vp, vp]
     L.fi_merge_states.argtypes = [vp, vp, i64, i32, i32, vp, vp, vp]
@@ -88,7 +94,7 @@ def _load() -> ctypes.CDLL:
     L.fi_last_error.argtypes = []
     L.fi_last_error.restype = ctypes.c_char_p
     for name in ("fi_create", "fi_destroy", "fi_workspace_bytes", "fi_plan", "fi_plan_view", "fi_run", "fi_run_kv8",
-                 "fi_merge_states", "fi_merge_state_pair", "fi_check_indices", "fi_set_timing_events"):
+                 "fi_run_variant", "fi_merge_states", "fi_merge_state_pair", "fi_check_indices", "fi_set_timing_events"):
         getattr(L, name).restype = i32
     return L
 
@@ -173,6 +179,16 @@ def fi_run(handle: int, q, k_pool, v_pool, kv_strides: Sequence[int], kv_indices
     st = (ctypes.c_int64 * 3)(*[int(s) for s in kv_strides])
     _check(lib.fi_run(handle, _ptr(q), _ptr(k_pool), _ptr(v_pool), st, _ptr(kv_indices), float(sm_scale),
                       _ptr(o), _ptr(lse), _ptr(o_cast), stream or None))
+
+
+def fi_run_variant(handle: int, q, k_pool, v_pool, kv_strides: Sequence[int], kv_indices, kv_indptr, last_page_len,
+                   sm_scale: float, o, lse, o_cast=None, stream: int = 0, *, logits_soft_cap: float = 0.0,
+                   window_left: int = -1, alibi_slopes=None) -> None:
+    st = (ctypes.c_int64 * 3)(*[int(s) for s in kv_strides])
+    var = fi_variant(float(logits_soft_cap), int(window_left), _ptr(alibi_slopes))
+    _check(lib.fi_run_variant(handle, _ptr(q), _ptr(k_pool), _ptr(v_pool), st, _ptr(kv_indices), _ptr(kv_indptr),
+                              _ptr(last_page_len), float(sm_scale), ctypes.byref(var), _ptr(o), _ptr(lse),
+                              _ptr(o_cast), stream or None))
 
 
 def fi_run_kv8(handle: int, q, k_pool, v_pool, kv_strides: Sequence[int], kv_indices, sm_scale: float,
@@ -261,8 +277,10 @@ class PagedAttention:
         self._ring_events[i] = ev
 
     def run(self, q, k_pool, v_pool, kv_indices, sm_scale: float, o=None, lse=None, o_cast=None,
-            k_scale: Optional[float] = None, v_scale: Optional[float] = None):
-        """k_scale / v_scale given: the pools are an 8-bit KV cache (uint8 tensors of E4M3 codes)."""
+            k_scale: Optional[float] = None, v_scale: Optional[float] = None, variant: Optional[dict] = None):
+        """k_scale / v_scale given: the pools are an 8-bit KV cache (uint8 tensors of E4M3 codes).
+        variant: dict(kv_indptr=, last_page_len= (device int32 tensors), logits_soft_cap=, window_left=,
+        alibi_slopes= (device float32 tensor)) runs fi_run_variant."""
         torch = self.torch
         kv8 = k_scale is not None or v_scale is not None
         kv_dtype = torch.uint8 if kv8 else self.torch_dtype
@@ -277,7 +295,12 @@ class PagedAttention:
             lse = torch.empty((nnz, self.num_qo_heads), dtype=torch.float32, device=q.device)
         # k_pool is [pages, kv_heads, page_size, D] (or any permutation of the first three through strides)
         strides = (k_pool.stride(0), k_pool.stride(1), k_pool.stride(2))
-        if kv8:
+        if variant is not None:
+            fi_run_variant(self.handle, q, k_pool, v_pool, strides, kv_indices, variant["kv_indptr"],
+                           variant["last_page_len"], sm_scale, o, lse, o_cast, self._stream(),
+                           logits_soft_cap=variant.get("logits_soft_cap", 0.0),
+                           window_left=variant.get("window_left", -1), alibi_slopes=variant.get("alibi_slopes"))
+        elif kv8:
             fi_run_kv8(self.handle, q, k_pool, v_pool, strides, kv_indices, sm_scale,
                        1.0 if k_scale is None else k_scale, 1.0 if v_scale is None else v_scale, o, lse, o_cast,
                        self._stream())

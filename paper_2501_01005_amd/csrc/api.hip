@@ -203,8 +203,16 @@ namespace {
 // fi_run and fi_run_kv8: kv8 = the pools hold E4M3 codes whose values are code * k_scale (v_scale)
 int32_t run_impl(fi_handle* h, const void* q, const void* k_pool, const void* v_pool, const int64_t* kv_strides,
                  const int32_t* kv_indices, float sm_scale, bool kv8, float k_scale, float v_scale, float* o,
-                 float* lse, void* o_cast, fi_stream stream) {
+                 float* lse, void* o_cast, fi_stream stream, const fi_variant* variant = nullptr,
+                 const int32_t* kv_indptr_dev = nullptr, const int32_t* last_page_len_dev = nullptr) {
   if (!h) return set_error(FI_ERR_INVALID_ARG, "fi_run: null handle");
+  if (variant) {
+    if (h->cfg.mode != FI_MODE_DECODE || h->cfg.page_size != kPageSize)
+      return set_error(FI_ERR_UNSUPPORTED, "fi_run_variant: built for decode mode with page_size 16");
+    if (!kv_indptr_dev || !last_page_len_dev) return set_error(FI_ERR_INVALID_ARG, "fi_run_variant: null pointer");
+    if (!(variant->logits_soft_cap >= 0.f) || variant->window_left < -1)
+      return set_error(FI_ERR_INVALID_ARG, "fi_run_variant: logits_soft_cap must be >= 0 and window_left >= -1");
+  }
   if (kv8 && h->cfg.mode != FI_MODE_DECODE)
     return set_error(FI_ERR_UNSUPPORTED, "fi_run_kv8: the 8-bit KV cache is built for decode mode only");
   if (kv8 && !(k_scale > 0.f && v_scale > 0.f))
@@ -252,13 +260,19 @@ int32_t run_impl(fi_handle* h, const void* q, const void* k_pool, const void* v_
   p.group = h->pp.group;
   p.t_pos = h->pp.t_pos;
   p.ctas_per_head = h->pp.ctas_per_head;
+  p.w_request = plan + L.off_work[W_REQUEST];
+  p.kv_indptr = kv_indptr_dev;
+  p.last_page_len = last_page_len_dev;
+  p.alibi_slopes = variant ? variant->alibi_slopes : nullptr;
+  p.soft_cap = variant ? variant->logits_soft_cap : 0.f;
+  p.window_left = variant ? variant->window_left : -1;
   p.page_log2 = 0;
   while ((1 << p.page_log2) < h->cfg.page_size) ++p.page_log2;
   const bool bf = h->cfg.dtype == FI_DTYPE_BF16;
   hipStream_t s = static_cast<hipStream_t>(stream);
   hipError_t e;
   if (h->ev_before && (e = hipEventRecord(h->ev_before, s)) != hipSuccess) return hip_error("fi_run: hipEventRecord", e);
-  e = h->cfg.mode == FI_MODE_DECODE ? launch_decode(p, bf, kv8, s) : launch_append(p, bf, s);
+  e = h->cfg.mode == FI_MODE_DECODE ? launch_decode(p, bf, kv8, variant != nullptr, s) : launch_append(p, bf, s);
   if (e != hipSuccess) return hip_error("fi_run: attention launch", e);
   if (h->ev_after && (e = hipEventRecord(h->ev_after, s)) != hipSuccess) return hip_error("fi_run: hipEventRecord", e);
 
@@ -287,6 +301,15 @@ extern "C" {
 int32_t fi_run(fi_handle* h, const void* q, const void* k_pool, const void* v_pool, const int64_t* kv_strides,
                const int32_t* kv_indices, float sm_scale, float* o, float* lse, void* o_cast, fi_stream stream) {
   return run_impl(h, q, k_pool, v_pool, kv_strides, kv_indices, sm_scale, false, 1.f, 1.f, o, lse, o_cast, stream);
+}
+
+int32_t fi_run_variant(fi_handle* h, const void* q, const void* k_pool, const void* v_pool, const int64_t* kv_strides,
+                       const int32_t* kv_indices, const int32_t* kv_indptr, const int32_t* last_page_len,
+                       float sm_scale, const fi_variant* variant, float* o, float* lse, void* o_cast,
+                       fi_stream stream) {
+  if (!variant) return set_error(FI_ERR_INVALID_ARG, "fi_run_variant: null variant");
+  return run_impl(h, q, k_pool, v_pool, kv_strides, kv_indices, sm_scale, false, 1.f, 1.f, o, lse, o_cast, stream,
+                  variant, kv_indptr, last_page_len);
 }
 
 int32_t fi_run_kv8(fi_handle* h, const void* q, const void* k_pool, const void* v_pool, const int64_t* kv_strides,

@@ -107,7 +107,10 @@ struct KvTile {
 
 // ANYPS: the page size is a run-time power of two instead of 16 (Sec. 3.1.1: the block size B_c of the
 // BSR cache is a free parameter); every lane then looks up the page of each token row it loads.
-template <bool BF, bool KV8, bool ANYPS>
+// VAR: attention variants (Sec. 3.2.3, logits transform and logits mask) on the scaled logits, in this order:
+// soft cap c * tanh(s / c), ALiBi bias slope[head] * (t - pos), sliding window (tokens t < pos - window hidden);
+// pos = l_kv - 1 is the absolute position of the request's query.  A step may then hold no visible token.
+template <bool BF, bool KV8, bool ANYPS, bool VAR = false>
 __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2))) decode_kernel(const RunParams p) {
   const int lane = threadIdx.x;
   const int m = lane & 15;  // K: token in page; V: 16-byte column block; S/O: query head
@@ -159,6 +162,17 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2)))
     const int kv_len = w_kv_len[w];
     const int out_slot = w_out_slot[w];
     const int ps_log2 = ANYPS ? p.page_log2 : 4;
+    // variants: chunk-local token index -> distance to the query
+    int tok_minus_pos = 0;  // (absolute index of the chunk's first token) - pos
+    float slope_log2 = 0.f;
+    if constexpr (VAR) {
+      const int req = as_const(p.w_request)[w];
+      ConstInts indptr = as_const(p.kv_indptr);
+      const int n_pg = indptr[req + 1] - indptr[req];
+      const int l_kv = n_pg > 0 ? (n_pg - 1) * kPageSize + as_const(p.last_page_len)[req] : 0;
+      tok_minus_pos = as_const(p.w_kv_start)[w] - (l_kv - 1);
+      if (p.alibi_slopes != nullptr && m < g) slope_log2 = p.alibi_slopes[kvh * g + m] * 1.4426950408889634f;
+    }
     const int n_pages = (kv_len + (1 << ps_log2) - 1) >> ps_log2;
     const int n_tiles = (kv_len + 31) / 32;
 
@@ -254,6 +268,21 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2)))
         sv[i] = s0[i] * p.scale_log2;
         sv[4 + i] = s1[i] * p.scale_log2;
       }
+      if constexpr (VAR) {
+        const float cap = p.soft_cap;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+          const int dist = tok_minus_pos + tok0 + 16 * (j >> 2) + (j & 3);  // t - pos, <= 0
+          float s = sv[j];
+          if (cap > 0.f) {  // cap * tanh(s / cap), s in log2 units: tanh(x) = 1 - 2 / (1 + exp(2 x))
+            const float e2x = __builtin_amdgcn_exp2f(s * (2.0f / cap));
+            s = cap * 1.4426950408889634f * (1.0f - 2.0f / (1.0f + e2x));
+          }
+          s += slope_log2 * static_cast<float>(dist);
+          if (p.window_left >= 0 && dist < -p.window_left) s = NEG_INF;
+          sv[j] = s;
+        }
+      }
       if (32 * t + 32 > kv_len) {  // ragged tail: hide tokens past the chunk, and zero their V rows
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
@@ -269,14 +298,15 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2)))
       float tmax = fmaxf(fmaxf(fmaxf(sv[0], sv[1]), fmaxf(sv[2], sv[3])), fmaxf(fmaxf(sv[4], sv[5]), fmaxf(sv[6], sv[7])));
       tmax = fmaxf(tmax, __shfl_xor(tmax, 16));
       tmax = fmaxf(tmax, __shfl_xor(tmax, 32));
-      const float m_new = fmaxf(m_run, tmax);  // finite: a tile always holds at least one valid token
-      const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+      const float m_new = fmaxf(m_run, tmax);  // finite: a tile always holds at least one valid token (VAR: may not)
+      const bool none_yet = VAR && m_new == NEG_INF;
+      const float alpha = none_yet ? 1.0f : __builtin_amdgcn_exp2f(m_run - m_new);
       m_run = m_new;
       float pv[8];
       float psum = 0.f;
 #pragma unroll
       for (int j = 0; j < 8; ++j) {
-        pv[j] = __builtin_amdgcn_exp2f(sv[j] - m_new);
+        pv[j] = none_yet ? 0.f : __builtin_amdgcn_exp2f(sv[j] - m_new);
         psum += pv[j];
       }
       l_run = l_run * alpha + psum;
@@ -428,7 +458,15 @@ void launch_decode_ps(const RunParams& p, bool is_bf16, bool kv8, hipStream_t st
 }
 }  // namespace
 
-hipError_t launch_decode(const RunParams& p, bool is_bf16, bool kv8, hipStream_t stream) {
+hipError_t launch_decode(const RunParams& p, bool is_bf16, bool kv8, bool variant, hipStream_t stream) {
+  if (variant) {
+    const dim3 grid(static_cast<unsigned>(p.ctas_per_head), static_cast<unsigned>(p.num_kv_heads), 1);
+    if (is_bf16)
+      hipLaunchKernelGGL((decode_kernel<true, false, false, true>), grid, dim3(64, 1, 1), 0, stream, p);
+    else
+      hipLaunchKernelGGL((decode_kernel<false, false, false, true>), grid, dim3(64, 1, 1), 0, stream, p);
+    return hipGetLastError();
+  }
   if (p.page_log2 == 4)
     launch_decode_ps<false>(p, is_bf16, kv8, stream);
   else

@@ -32,6 +32,13 @@ struct RunParams {
   int32_t num_qo_heads, num_kv_heads, group, t_pos;
   int32_t ctas_per_head;
   int32_t page_log2;  // log2 of the page size (tokens per page)
+  // attention variants (Sec. 3.2.3), read by the variant kernels only
+  const int32_t* w_request;      // request of each work item
+  const int32_t* kv_indptr;      // DEVICE copies of the plan inputs: a request's total KV length gives the
+  const int32_t* last_page_len;  //   absolute position of its query
+  const float* alibi_slopes;     // [num_qo_heads] or null
+  float soft_cap;                // > 0: logits <- cap * tanh(logits / cap)
+  int32_t window_left;           // >= 0: tokens more than this far behind the query are hidden
 };
 
 struct MergeParams {
@@ -49,8 +56,9 @@ struct MergeParams {
 };
 
 // decode.hip: query tile = 1 position x g fused heads, one wavefront per CTA.
-// kv8: the pools hold OCP E4M3 codes (App. F) instead of the query type.
-hipError_t launch_decode(const RunParams& p, bool is_bf16, bool kv8, hipStream_t stream);
+// kv8: the pools hold OCP E4M3 codes (App. F) instead of the query type.  variant: the logits hooks of
+// RunParams are applied (16-bit pools, page size 16 only).
+hipError_t launch_decode(const RunParams& p, bool is_bf16, bool kv8, bool variant, hipStream_t stream);
 // append.hip: query tile = append_tile_rows()/g positions x g fused heads, 8 wavefronts per CTA.
 hipError_t launch_append(const RunParams& p, bool is_bf16, hipStream_t stream);
 int append_tile_rows();  // fused rows (positions x group) of one append query tile

@@ -1,0 +1,81 @@
+"""GPU parity of decode with attention variants (Sec. 3.2.3: soft cap of the logits, ALiBi bias, sliding
+window) against the oracle: each variant alone, all together, windows that hide whole steps and whole
+split chunks (whose partial state is then the identity of the merge), both query types."""
+import numpy as np
+import pytest
+
+import oracle
+import workloads
+from gpu_util import DeviceBatch, assert_close, make_wrapper
+
+pytestmark = pytest.mark.gpu
+
+
+def run_variant(batch, num_ctas=0, min_chunk=0, **var):
+    import torch
+    dev = DeviceBatch(batch)
+    w = make_wrapper(batch, "decode", num_ctas=num_ctas, min_chunk=min_chunk)
+    w.plan(batch.qo_indptr, batch.kv_indptr, batch.last_page_len, causal=False)
+    nnz = dev.q.shape[0]
+    o = torch.full((nnz, batch.num_qo_heads, batch.head_dim), float("nan"), dtype=torch.float32, device=dev.device)
+    lse = torch.full((nnz, batch.num_qo_heads), float("nan"), dtype=torch.float32, device=dev.device)
+    v = dict(kv_indptr=torch.from_numpy(np.ascontiguousarray(batch.kv_indptr, dtype=np.int32)).to(dev.device),
+             last_page_len=torch.from_numpy(np.ascontiguousarray(batch.last_page_len, dtype=np.int32)).to(dev.device))
+    if "alibi_slopes" in var:
+        v["alibi_slopes"] = torch.from_numpy(np.asarray(var["alibi_slopes"], dtype=np.float32)).to(dev.device)
+    v.update({k: var[k] for k in ("logits_soft_cap", "window_left") if k in var})
+    w.run(dev.q, dev.k_pool, dev.v_pool, dev.kv_indices, batch.sm_scale, o=o, lse=lse, variant=v)
+    torch.cuda.synchronize()
+    w.close()
+    return o.double().cpu().numpy(), lse.double().cpu().numpy()
+
+
+def check(batch, what, num_ctas=0, min_chunk=0, **var):
+    print(f"[case] {what}: {batch.name} dtype={batch.dtype} heads={batch.num_qo_heads}/{batch.num_kv_heads} "
+          f"kv={batch.kv_lens()[:8].tolist()} variant={ {k: (v if np.isscalar(v) else 'array') for k, v in var.items()} }",
+          flush=True)
+    o_ref, lse_ref = oracle.run_batch(batch, **var)
+    o, lse = run_variant(batch, num_ctas=num_ctas, min_chunk=min_chunk, **var)
+    e = assert_close(o, lse, o_ref, lse_ref, what)
+    print(f"[ok] {what}: err_o={e[0]:.2e} err_lse={e[1]:.2e}", flush=True)
+
+
+def slopes(h):
+    return np.array([2.0 ** (-(i + 1) * 8.0 / h) for i in range(h)])
+
+
+@pytest.mark.parametrize("dtype", [workloads.BF16, workloads.F16])
+@pytest.mark.parametrize("g", [1, 4])
+def test_each_variant_and_all_together(dtype, g):
+    b = workloads.random_case(400 + g, dtype=dtype, num_qo_heads=2 * g, num_kv_heads=2, batch=6, max_kv=500,
+                              value_scale=2.0)
+    check(b, "no variant in effect", logits_soft_cap=0.0, window_left=-1)
+    check(b, "soft cap", logits_soft_cap=3.0)
+    check(b, "alibi", alibi_slopes=slopes(2 * g))
+    check(b, "window", window_left=70)
+    check(b, "all", logits_soft_cap=5.0, window_left=33, alibi_slopes=slopes(2 * g))
+
+
+def test_window_hides_whole_steps_and_whole_chunks():
+    # long requests split into many chunks; a short window leaves most chunks without a visible token
+    b = workloads.make_batch("win", 410, workloads.BF16, 8, 2, 128, 16, [1, 1, 1, 1], [3000, 700, 40, 1], False)
+    for W in (0, 1, 31, 32, 100, 5000):
+        check(b, f"window {W}", num_ctas=2 * 16, min_chunk=64, window_left=W)
+
+
+def test_refused_where_not_built():
+    import paper_2501_01005_amd as fi
+    dummy = np.zeros(64, dtype=np.uint8)
+    ok = dict(dtype=fi.FI_DTYPE_BF16, num_qo_heads=8, num_kv_heads=2, head_dim=128, page_size=16, mode=fi.FI_MODE_DECODE,
+              num_ctas=8, max_batch=4, max_qo_tiles=4)
+    for bad in ({"mode": fi.FI_MODE_APPEND}, {"page_size": 8}):
+        h = fi.fi_create(**{**ok, **bad})
+        with pytest.raises(fi.Fi355Error) as e:
+            fi.fi_run_variant(h, dummy, dummy, dummy, (8, 8, 8), dummy, dummy, dummy, 1.0, dummy, dummy, window_left=3)
+        assert e.value.code == fi.FI_ERR_UNSUPPORTED
+        fi.fi_destroy(h)
+    h = fi.fi_create(**ok)
+    with pytest.raises(fi.Fi355Error) as e:
+        fi.fi_run_variant(h, dummy, dummy, dummy, (8, 8, 8), dummy, dummy, dummy, 1.0, dummy, dummy, window_left=-5)
+    assert e.value.code == fi.FI_ERR_INVALID_ARG
+    fi.fi_destroy(h)
