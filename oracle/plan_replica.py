@@ -43,7 +43,8 @@ Refinement (``refine=True``; an addition of this build, not in the paper, used f
 append where a CTA gets only a handful of long items): costs are taken in percent
 (``unit = 100``); the chunk length is rounded up to whole tiles of ``kv_quantum``
 tokens; an item whose fused rows ``n_pos * group`` fit in ``light_rows`` counts
-``light_pct`` percent of its per-token term; after the greedy pass, up to
+``light_pct`` percent of its per-token term; after the greedy pass, unless there
+are more than ``8 * #CTA`` work items (then the greedy result is kept), up to
 ``4 * #CTA + 64`` times: take the most loaded CTA (lowest index on ties), and among
 all (other CTA, item of the loaded CTA, optional cheaper partner item of the other
 CTA) candidates in that nesting order take the first one that gives the smallest new
@@ -151,7 +152,7 @@ def plan_replica(qo_indptr: Sequence[int], kv_indptr: Sequence[int], last_page_l
         cta_cost[c] = cost
 
     # -- refinement (not in the paper; see the module header) ------------------
-    if refine:
+    if refine and len(work) <= 8 * num_ctas:
         for _ in range(4 * num_ctas + 64):
             hi = max(range(num_ctas), key=lambda c: (cta_cost[c], -c))     # most loaded, lowest index on ties
             best_new, best = cta_cost[hi], None
@@ -182,6 +183,7 @@ def plan_replica(qo_indptr: Sequence[int], kv_indptr: Sequence[int], last_page_l
                 cta_cost[hi] += item_cost(wb)
                 queues[hi].append(wb)
             queues[lo].append(wa)
+    if refine:
         for q in queues:
             q.sort(key=lambda w: (-work[w]["kv_len"], w))
 

@@ -173,7 +173,9 @@ int32_t make_plan(const PlanParams& pp, const WorkspaceLayout& L, const int32_t*
 
   // ---- refinement: while it lowers the maximum, move one item out of the most loaded CTA or swap it for a
   //      cheaper one (first best candidate in (cta, item, partner) order; a fixed number of rounds at most) ----
-  if (pp.refine) {
+  // (with more than 8 items per CTA on average the greedy pass is fine-grained enough, and the search, which
+  // is quadratic in the queue lengths, is skipped)
+  if (pp.refine && n_work <= 8 * C) {
     for (int32_t round = 0; round < 4 * C + 64; ++round) {
       int32_t hi = 0;
       for (int32_t c = 1; c < C; ++c)
@@ -218,6 +220,8 @@ int32_t make_plan(const PlanParams& pp, const WorkspaceLayout& L, const int32_t*
       }
       queues[best_lo].push_back(wa);
     }
+  }
+  if (pp.refine) {
     // a queue runs its longest chunk first, as the greedy pass left it
     for (auto& q : queues)
       std::stable_sort(q.begin(), q.end(), [&](int32_t a, int32_t b) {
