@@ -179,6 +179,9 @@ def bench_shared_prefix(args) -> int:
     return 0
 
 
+E2_WORKLOADS = [f"e2-{k}-{d}" for k in ("decode", "prefill") for d in ("constant", "uniform", "zipf")]
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -187,7 +190,9 @@ def main() -> int:
     # first 15 ms and settles near 329 us)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=50)
-    ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4", "c5"])
+    ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4", "c5"] + E2_WORKLOADS,
+                    help="c1..c5: the benchmark configurations; e2-<decode|prefill>-<constant|uniform|zipf>: batch 16 "
+                         "with the three length distributions of the paper's kernel experiment (Sec. 4.2)")
     ap.add_argument("--small", action="store_true", help="small variant of the workload (debug)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-plan", action="store_true", help="time fi_run only (plan once, as for layers 2..L)")
@@ -247,8 +252,13 @@ def main() -> int:
             print("bench.py: --page-size is for c2 and c3", file=sys.stderr)
             return 2
         cfg_kw["page_size"] = args.page_size
-    batch = getattr(workloads, "config" + args.workload[1])(small=args.small, **cfg_kw)
-    mode = "append" if args.workload == "c3" else "decode"
+    if args.workload in E2_WORKLOADS:
+        _, kind, dist = args.workload.split("-")
+        batch = workloads.config_e2(kind, dist)
+        mode = "append" if kind == "prefill" else "decode"
+    else:
+        batch = getattr(workloads, "config" + args.workload[1])(small=args.small, **cfg_kw)
+        mode = "append" if args.workload == "c3" else "decode"
     dev = DeviceBatch(batch, kv_layout=args.kv_layout)
     w = make_wrapper(batch, mode, num_ctas=args.num_ctas, min_chunk=args.min_chunk, balance=args.balance,
                      alpha=args.alpha, beta=args.beta)

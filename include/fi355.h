@@ -75,7 +75,8 @@ typedef struct fi_config {
   int32_t alpha;        /* cost(l_q, l_kv) = alpha*l_q + beta*l_kv of Algorithm 1; 0,0 = 1,1
                            (8,5 for the refined append assignment, see `balance`)              */
   int32_t beta;
-  int32_t min_chunk;    /* smallest KV chunk the planner may create, tokens; 0 = default       */
+  int32_t min_chunk;    /* smallest KV chunk the planner may create, tokens; 0 = default
+                           (decode 32, append 256)                                              */
   int32_t literal_lkv;  /* 1: use l_kv(i) for every query tile in the chunk-size formula as
                            printed in Algorithm 1 even under causal masking; 0: use what the
                            tile can see                                                         */

@@ -272,9 +272,9 @@ class PagedAttention:
             self._ring_events[i].synchronize()
         fi_plan(self.handle, qo_indptr, kv_indptr, last_page_len, causal, self.workspace, self.ws_bytes,
                 self._ring[i], self.pin_bytes, self._stream())
-        ev = self.torch.cuda.Event()
-        ev.record(self.torch.cuda.current_stream(self.device))
-        self._ring_events[i] = ev
+        if self._ring_events[i] is None:
+            self._ring_events[i] = self.torch.cuda.Event()
+        self._ring_events[i].record(self.torch.cuda.current_stream(self.device))
 
     def run(self, q, k_pool, v_pool, kv_indices, sm_scale: float, o=None, lse=None, o_cast=None,
             k_scale: Optional[float] = None, v_scale: Optional[float] = None, variant: Optional[dict] = None):

@@ -99,7 +99,9 @@ int32_t fi_create(const fi_config* cfg, fi_handle** out) {
   pp.light_pct = 64;
   pp.kv_quantum = (pp.refine && cfg->mode == FI_MODE_APPEND) ? 64 : 1;  // the append kernel's KV tile
   // default: decode chunks of at least 128 tokens (4 steps of a wavefront), append chunks of 256
-  pp.min_chunk = cfg->min_chunk > 0 ? cfg->min_chunk : (cfg->mode == FI_MODE_DECODE ? 128 : 256);
+  // decode: one 32-token step of the kernel; with fewer tokens than that per CTA the chip is not filled, and a
+  // wavefront that walks 128 tokens alone takes longer than four that walk 32 each plus their merge
+  pp.min_chunk = cfg->min_chunk > 0 ? cfg->min_chunk : (cfg->mode == FI_MODE_DECODE ? 32 : 256);
   pp.literal_lkv = cfg->literal_lkv != 0;
   pp.max_batch = cfg->max_batch;
   pp.max_qo_tiles = cfg->max_qo_tiles;

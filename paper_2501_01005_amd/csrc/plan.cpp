@@ -5,9 +5,8 @@
 #include "plan.h"
 
 #include <algorithm>
-#include <functional>
-#include <queue>
 #include <utility>
+#include <vector>
 
 #include "../../include/fi355.h"
 
@@ -51,6 +50,36 @@ struct Tile {
 struct Chunk {
   int32_t tile, kv_start, kv_len, in_tile;
 };
+using Entry = std::pair<int64_t, int32_t>;  // (accumulated cost, cta)
+
+// Working arrays of make_plan, kept per thread between calls: planning runs once per generation step on the
+// host (Sec. 3.3.1), in front of every layer's launches, so it does not allocate once the sizes have settled.
+struct Scratch {
+  std::vector<Tile> tiles;
+  std::vector<Chunk> chunks;
+  std::vector<int32_t> order, cta_of, fill;
+  std::vector<int64_t> cost, load;
+  std::vector<uint64_t> keys;
+  std::vector<Entry> heap;
+  std::vector<std::vector<int32_t>> queues;
+};
+thread_local Scratch scratch;
+
+// the root of a binary min-heap has grown: restore the heap order
+void sift_down(std::vector<Entry>& heap) {
+  const size_t n = heap.size();
+  const Entry e = heap[0];
+  size_t i = 0;
+  for (;;) {
+    size_t c = 2 * i + 1;
+    if (c >= n) break;
+    if (c + 1 < n && heap[c + 1] < heap[c]) ++c;
+    if (!(heap[c] < e)) break;
+    heap[i] = heap[c];
+    i = c;
+  }
+  heap[i] = e;
+}
 }  // namespace
 
 int32_t make_plan(const PlanParams& pp, const WorkspaceLayout& L, const int32_t* qo_indptr,
@@ -71,7 +100,8 @@ int32_t make_plan(const PlanParams& pp, const WorkspaceLayout& L, const int32_t*
   const int64_t C = pp.ctas_per_head;
 
   // ---- lengths, query tiles, and the KV range each tile needs ----
-  std::vector<Tile> tiles;
+  std::vector<Tile>& tiles = scratch.tiles;
+  tiles.clear();
   int64_t S = 0;
   for (int32_t i = 0; i < batch; ++i) {
     const int64_t l_qo = static_cast<int64_t>(qo_indptr[i + 1]) - qo_indptr[i];
@@ -115,7 +145,8 @@ int32_t make_plan(const PlanParams& pp, const WorkspaceLayout& L, const int32_t*
   Lkv = std::max(min_chunk, Lkv);
 
   // ---- split every tile's KV range into chunks of at most L_kv; number the chunks ----
-  std::vector<Chunk> chunks;
+  std::vector<Chunk>& chunks = scratch.chunks;
+  chunks.clear();
   int32_t next_slot = 0, n_merge = 0;
   for (size_t ti = 0; ti < tiles.size(); ++ti) {
     Tile& tl = tiles[ti];
@@ -139,21 +170,25 @@ int32_t make_plan(const PlanParams& pp, const WorkspaceLayout& L, const int32_t*
     return fail(FI_ERR_WORKSPACE_TOO_SMALL, "fi_plan: plan exceeds the workspace sections (internal bound)");
 
   // ---- descending length (ties: lower work index first) ----
-  std::vector<int32_t> order(n_work);
-  for (int32_t w = 0; w < n_work; ++w) order[w] = w;
-  std::stable_sort(order.begin(), order.end(),
-                   [&](int32_t a, int32_t b) { return chunks[a].kv_len > chunks[b].kv_len; });
+  std::vector<uint64_t>& keys = scratch.keys;  // (largest length first, then the work index) as one integer
+  keys.resize(n_work);
+  for (int32_t w = 0; w < n_work; ++w)
+    keys[w] = (static_cast<uint64_t>(0x7fffffff - chunks[w].kv_len) << 32) | static_cast<uint32_t>(w);
+  std::sort(keys.begin(), keys.end());
+  std::vector<int32_t>& order = scratch.order;
+  order.resize(n_work);
+  for (int32_t i = 0; i < n_work; ++i) order[i] = static_cast<int32_t>(keys[i] & 0xffffffffu);
 
   // ---- least-loaded CTA first (ties: lower CTA index) ----
-  using Entry = std::pair<int64_t, int32_t>;  // (accumulated cost, cta)
-  std::priority_queue<Entry, std::vector<Entry>, std::greater<Entry>> heap;
-  for (int32_t c = 0; c < C; ++c) heap.push({0, c});
-  std::vector<std::vector<int32_t>> queues(static_cast<size_t>(C));
+  std::vector<Entry>& heap = scratch.heap;  // binary min-heap, least (cost, cta) at the root
+  heap.resize(static_cast<size_t>(C));
+  for (int32_t c = 0; c < C; ++c) heap[c] = {0, c};  // ascending, hence already in heap order
   const int64_t t_q = static_cast<int64_t>(pp.t_pos) * pp.group;
   // cost(l_q, l_kv) = alpha * T_q + beta * l_kv; with the refinement in percent, the per-token term of a
   // light tile weighted by light_pct
   const int64_t unit = pp.refine ? 100 : 1;
-  std::vector<int64_t> cost(static_cast<size_t>(n_work));
+  std::vector<int64_t>& cost = scratch.cost;
+  cost.resize(static_cast<size_t>(n_work));
   for (int32_t w = 0; w < n_work; ++w) {
     const Tile& tl = tiles[chunks[w].tile];
     const bool light = pp.refine && pp.light_rows > 0 && static_cast<int64_t>(tl.n_pos) * pp.group <= pp.light_rows;
@@ -161,21 +196,28 @@ int32_t make_plan(const PlanParams& pp, const WorkspaceLayout& L, const int32_t*
     if (pp.refine) l_kv = (l_kv + pp.kv_quantum - 1) / pp.kv_quantum * pp.kv_quantum;
     cost[w] = unit * pp.alpha * t_q + static_cast<int64_t>(pp.beta) * l_kv * (light ? pp.light_pct : unit);
   }
-  std::vector<int64_t> load(static_cast<size_t>(C), 0);
+  std::vector<int64_t>& load = scratch.load;
+  load.assign(static_cast<size_t>(C), 0);
+  std::vector<int32_t>& cta_of = scratch.cta_of;  // the CTA of work item w; a queue keeps the order of assignment
+  cta_of.resize(static_cast<size_t>(n_work));
   for (int32_t w : order) {
-    Entry e = heap.top();
-    heap.pop();
-    queues[e.second].push_back(w);
+    Entry& e = heap[0];
+    cta_of[w] = e.second;
     e.first += cost[w];
     load[e.second] = e.first;
-    heap.push(e);
+    sift_down(heap);
   }
 
   // ---- refinement: while it lowers the maximum, move one item out of the most loaded CTA or swap it for a
   //      cheaper one (first best candidate in (cta, item, partner) order; a fixed number of rounds at most) ----
   // (with more than 8 items per CTA on average the greedy pass is fine-grained enough, and the search, which
   // is quadratic in the queue lengths, is skipped)
-  if (pp.refine && n_work <= 8 * C) {
+  const bool refined = pp.refine && n_work <= 8 * C;
+  std::vector<std::vector<int32_t>>& queues = scratch.queues;
+  if (refined) {
+    if (queues.size() < static_cast<size_t>(C)) queues.resize(static_cast<size_t>(C));
+    for (int32_t c = 0; c < C; ++c) queues[c].clear();
+    for (int32_t w : order) queues[cta_of[w]].push_back(w);
     for (int32_t round = 0; round < 4 * C + 64; ++round) {
       int32_t hi = 0;
       for (int32_t c = 1; c < C; ++c)
@@ -220,14 +262,11 @@ int32_t make_plan(const PlanParams& pp, const WorkspaceLayout& L, const int32_t*
       }
       queues[best_lo].push_back(wa);
     }
+    for (int32_t c = 0; c < C; ++c)
+      for (int32_t w : queues[c]) cta_of[w] = c;
   }
-  if (pp.refine) {
-    // a queue runs its longest chunk first, as the greedy pass left it
-    for (auto& q : queues)
-      std::stable_sort(q.begin(), q.end(), [&](int32_t a, int32_t b) {
-        return chunks[a].kv_len != chunks[b].kv_len ? chunks[a].kv_len > chunks[b].kv_len : a < b;
-      });
-  }
+  // A queue runs its longest chunk first, the lower work index first among equals: the items of its CTA in the
+  // sequence of `order` (which is also the order in which the greedy pass assigned them).
 
   // ---- emit the plan section ----
   std::fill(plan, plan + L.plan_ints, 0);
@@ -239,24 +278,23 @@ int32_t make_plan(const PlanParams& pp, const WorkspaceLayout& L, const int32_t*
   hdr[H_T_POS] = pp.t_pos;
   hdr[H_CTAS] = static_cast<int32_t>(C);
   int32_t* cta_indptr = plan + L.off_cta_indptr;
-  int32_t k = 0;
-  for (int32_t c = 0; c < C; ++c) {
-    cta_indptr[c] = k;
-    for (int32_t w : queues[c]) {
-      const Chunk& ch = chunks[w];
-      const Tile& tl = tiles[ch.tile];
-      plan[L.off_work[W_REQUEST] + k] = tl.request;
-      plan[L.off_work[W_Q_ROW0] + k] = tl.q_row0;
-      plan[L.off_work[W_N_POS] + k] = tl.n_pos;
-      plan[L.off_work[W_KV_PAGE0] + k] = tl.kv_page_base + ch.kv_start / ps;
-      plan[L.off_work[W_KV_START] + k] = ch.kv_start;
-      plan[L.off_work[W_KV_LEN] + k] = ch.kv_len;
-      plan[L.off_work[W_DIAG0] + k] = tl.diag0;
-      plan[L.off_work[W_OUT_SLOT] + k] = tl.slot_base < 0 ? -1 : tl.slot_base + ch.in_tile;
-      ++k;
-    }
+  for (int32_t w = 0; w < n_work; ++w) ++cta_indptr[cta_of[w] + 1];
+  for (int32_t c = 0; c < C; ++c) cta_indptr[c + 1] += cta_indptr[c];
+  std::vector<int32_t>& fill = scratch.fill;  // next free position of each CTA's queue
+  fill.assign(cta_indptr, cta_indptr + C);
+  for (int32_t w : order) {
+    const int32_t k = fill[cta_of[w]]++;
+    const Chunk& ch = chunks[w];
+    const Tile& tl = tiles[ch.tile];
+    plan[L.off_work[W_REQUEST] + k] = tl.request;
+    plan[L.off_work[W_Q_ROW0] + k] = tl.q_row0;
+    plan[L.off_work[W_N_POS] + k] = tl.n_pos;
+    plan[L.off_work[W_KV_PAGE0] + k] = tl.kv_page_base + ch.kv_start / ps;
+    plan[L.off_work[W_KV_START] + k] = ch.kv_start;
+    plan[L.off_work[W_KV_LEN] + k] = ch.kv_len;
+    plan[L.off_work[W_DIAG0] + k] = tl.diag0;
+    plan[L.off_work[W_OUT_SLOT] + k] = tl.slot_base < 0 ? -1 : tl.slot_base + ch.in_tile;
   }
-  cta_indptr[C] = k;
   int32_t mi = 0;
   for (const Tile& tl : tiles) {
     if (tl.slot_base < 0) continue;

@@ -73,3 +73,16 @@ def test_config5_full_shared_prefix():
     e1 = assert_close(o1, l1, o_ref, lse_ref, "c5 single")
     print(f"[ok] c5 full: composed err_o={e[0]:.2e} err_lse={e[1]:.2e}; single err_o={e1[0]:.2e}", flush=True)
     wp.close(); ws.close()
+
+
+@pytest.mark.parametrize("kind", ["decode", "prefill"])
+@pytest.mark.parametrize("dist", ["constant", "uniform", "zipf"])
+def test_input_dynamism_workloads(kind, dist):
+    """Batch 16 with constant, uniform and skewed lengths, decode and causal prefill (Sec. 4.2's kernel experiment)."""
+    b = workloads.config_e2(kind, dist)
+    kv = b.kv_lens()
+    if kind == "decode":
+        sample = list(range(b.batch))
+    else:
+        sample = sorted({int(np.argmin(kv)), int(np.argmax(kv))})
+    sampled_check(b, "decode" if kind == "decode" else "append", sample, f"e2 {kind} {dist}")
