@@ -45,11 +45,20 @@ constexpr int kRowElemsV = 160;    // V tile row pitch (320 B): rows 16 banks ap
 constexpr int kCtaThreads = 512;   // 8 wavefronts, 32 query rows each
 constexpr int kRowBlocks = 1;       // 32-row blocks per wavefront; CTA tile = 8 * 32 * kRowBlocks fused rows
 constexpr int kLoopBuffers = 3;                                 // LDS tile buffers of the scheduled loop
-constexpr int kLdsVOffset = kLoopBuffers * kTileKv * kRowElems * 2;
-constexpr int kLdsBytes = kLdsVOffset + kLoopBuffers * kTileKv * kRowElemsV * 2;
+// LDS map.  K tiles from 0 (the scheduled loop: three packed 16 KB buffers; the generic path: two of 17 KB);
+// behind the loop's K buffers, up to 64 KB, 16 KB that together with K buffer 2 stage the V tiles requested for
+// the CTA's next work item; V tiles from 64 KB (three buffers of 20 KB); the loop's output transpose area also
+// from 64 KB, so that it leaves K buffers 0 and 1 and the staging area to the next work item's tiles, which are
+// on their way while the outputs are written.  Everything a load writes directly lies below 64 KB.
+constexpr int kLdsVOffset = 65536;
+static_assert(kLoopBuffers * kTileKv * kRowElems * 2 <= kLdsVOffset, "K tiles end before the V tiles");
 constexpr int kEpilogueRowBytes = 288;                          // row pitch of the loop's output transpose area
-constexpr int kEpilogueLdsBytes = 32 * kEpilogueRowBytes;       // per wavefront; aliases the tile buffers
-static_assert((kCtaThreads / 64) * kEpilogueLdsBytes <= kLdsBytes, "output transpose area fits");
+constexpr int kEpilogueLdsBytes = 32 * kEpilogueRowBytes;       // per wavefront
+constexpr int kEpilogueBase = kLdsVOffset;
+constexpr int kLdsTileEnd = kLdsVOffset + kLoopBuffers * kTileKv * kRowElemsV * 2;
+constexpr int kLdsEpilogueEnd = kEpilogueBase + (kCtaThreads / 64) * kEpilogueLdsBytes;
+constexpr int kLdsBytes = kLdsTileEnd > kLdsEpilogueEnd ? kLdsTileEnd : kLdsEpilogueEnd;
+static_assert(kLdsBytes <= 160 * 1024, "fits the CU's LDS");
 constexpr int kLoopMinTokens = 2 * kTileKv;                     // shorter chunks: generic path only (its start-up is cheaper)
 constexpr int kLazyLog2 = 8;                                    // P may reach 2^8 before the reference is raised
 constexpr uint16_t kLazyF16Bits = (15 + kLazyLog2) << 10;       // fp16 bit pattern of 2^kLazyLog2
@@ -136,56 +145,6 @@ __device__ __forceinline__ uint32_t lds_offset(const void* p) {
       (__attribute__((address_space(3))) const uint8_t*)(static_cast<const uint8_t*>(p))));
 }
 
-// The hand-scheduled loop over the `n_tiles` KV tiles of a chunk of `kv_len` tokens, of which the
-// first `n_full` >= 1 need no masking (gen/gen_append_loop.py writes it and documents its
-// register map and schedule).  `cap` = chunk-local index of the last token this lane's row sees,
-// minus 4 * (lane / 32).  Starts from the empty attention state, reads Q through `q_addr`,
-// gathers pages through `page_ids` (the chunk's ids; `ids_clamp` = byte offset of the chunk's
-// last one) and finishes the work item.  Output row of tile row R (position R >> g_log2, head
-// R % g) is row_base + position * num_qo_heads + head, written if position < n_pos: o (512 B per
-// row) to o_base, and, if has_cast, o in the input type to cast_base; the rows pass through the
-// wavefront's LDS area (epi_write: this lane's accumulator column, epi_read / epi_chunk: the
-// 16-byte piece it stores).  lse goes to lse_base[o_off / 512] from lanes with row_flags & 2.
-// Every wavefront of the CTA must call it with the same tile counts (it contains CTA barriers).
-template <bool BF>
-__device__ __forceinline__ void run_scheduled_loop(int n_full, int n_tiles, int kv_len, int cap, int st_tok, int ids_clamp, const int32_t* page_ids, uint32_t k_lo,
-                                                   uint32_t k_hi, uint32_t v_lo, uint32_t v_hi, uint32_t page_bytes,
-                                                   float scale_log2, int st_page, uint64_t q_addr, uint32_t st_off_bytes,
-                                                   uint32_t k_off_bytes, uint32_t k_read, uint32_t k_swizzle,
-                                                   uint32_t v_read, uint32_t k_dma, uint32_t v_write,
-                                                   uint32_t o_off, int row_flags, float* o_base, float* lse_base,
-                                                   void* cast_base, int has_cast, uint32_t epi_write, uint32_t epi_read,
-                                                   uint32_t epi_chunk, int g_log2, int num_qo_heads, int row_base,
-                                                   int n_pos, int wave_index) {
-  if constexpr (BF) {
-    asm volatile(
-#include "append_loop_bf16.inc"
-        :
-        : [nf] "s"(n_full), [nt] "s"(n_tiles), [kvl] "s"(kv_len), [cap] "v"(cap), [stk] "v"(st_tok), [npg1] "s"(ids_clamp), [idp] "s"(page_ids), [kblo] "s"(k_lo), [kbhi] "s"(k_hi),
-          [vblo] "s"(v_lo), [vbhi] "s"(v_hi), [sp] "s"(page_bytes), [sc] "s"(scale_log2), [stp] "s"(st_page),
-          [qp] "v"(q_addr), [so] "v"(st_off_bytes), [sok] "v"(k_off_bytes), [kb] "v"(k_read), [kxs] "v"(k_swizzle),
-          [va] "v"(v_read), [kd] "s"(k_dma), [wv] "v"(v_write), [ooff] "v"(o_off), [rok] "v"(row_flags), [ob] "s"(o_base), [lb] "s"(lse_base),
-          [cb] "s"(cast_base), [oc] "s"(has_cast), [ew] "v"(epi_write), [er] "v"(epi_read), [l16] "v"(epi_chunk),
-          [gl] "s"(g_log2), [hq] "s"(num_qo_heads), [rb] "s"(row_base), [np] "s"(n_pos), [stp8] "s"(wave_index)
-        :
-#include "append_loop_clobbers.inc"
-    );
-  } else {
-    asm volatile(
-#include "append_loop_f16.inc"
-        :
-        : [nf] "s"(n_full), [nt] "s"(n_tiles), [kvl] "s"(kv_len), [cap] "v"(cap), [stk] "v"(st_tok), [npg1] "s"(ids_clamp), [idp] "s"(page_ids), [kblo] "s"(k_lo), [kbhi] "s"(k_hi),
-          [vblo] "s"(v_lo), [vbhi] "s"(v_hi), [sp] "s"(page_bytes), [sc] "s"(scale_log2), [stp] "s"(st_page),
-          [qp] "v"(q_addr), [so] "v"(st_off_bytes), [sok] "v"(k_off_bytes), [kb] "v"(k_read), [kxs] "v"(k_swizzle),
-          [va] "v"(v_read), [kd] "s"(k_dma), [wv] "v"(v_write), [ooff] "v"(o_off), [rok] "v"(row_flags), [ob] "s"(o_base), [lb] "s"(lse_base),
-          [cb] "s"(cast_base), [oc] "s"(has_cast), [ew] "v"(epi_write), [er] "v"(epi_read), [l16] "v"(epi_chunk),
-          [gl] "s"(g_log2), [hq] "s"(num_qo_heads), [rb] "s"(row_base), [np] "s"(n_pos), [stp8] "s"(wave_index)
-        :
-#include "append_loop_clobbers.inc"
-    );
-  }
-}
-
 // One entry of the plan's work list (Sec. 3.3.1), in scalar registers.  The fields are read with
 // scalar loads (the plan arrays were written by an earlier kernel): the scalar path does not
 // queue behind the previous item's output stores the way a vector load would.  Loads and wait
@@ -209,6 +168,66 @@ struct WorkItem {
         : "memory");
   }
 };
+
+// The hand-scheduled loop over the `n_tiles` KV tiles of a chunk of `kv_len` tokens, of which the
+// first `n_full` >= 1 need no masking (gen/gen_append_loop.py writes it and documents its
+// register map and schedule).  `cap` = chunk-local index of the last token this lane's row sees,
+// minus 4 * (lane / 32).  Starts from the empty attention state, reads Q through `q_addr`,
+// gathers pages through `page_ids` (the chunk's ids; `ids_clamp` = byte offset of the chunk's
+// last one) and finishes the work item.  Output row of tile row R (position R >> g_log2, head
+// R % g) is row_base + position * num_qo_heads + head, written if position < n_pos: o (512 B per
+// row) to o_base, and, if has_cast, o in the input type to cast_base; the rows pass through the
+// wavefront's LDS area (epi_write: this lane's accumulator column, epi_read / epi_chunk: the
+// 16-byte piece it stores).  lse goes to lse_base[o_off / 512] from lanes with row_flags & 2.
+// Every wavefront of the CTA must call it with the same tile counts (it contains CTA barriers).
+//
+// Seam to the next work item: the block reads the plan entry at byte offset `next_off & ~3` of
+// the work arrays (`w_fields` = the q_row0 array, the others follow `w_stride` bytes apart) into
+// `next`; if bit 0 of `next_off` is set (there is a next item) and that item will run this loop
+// too, it requests the item's first two K and V tiles into LDS (page ids from `all_ids`, the whole
+// page table) before it writes its own outputs, and sets `prefetched_out`.  The next call is then
+// made with bit 1 of `next_off` set.  Whoever uses the LDS otherwise after a block that set
+// `prefetched_out` waits for vmcnt(0) first.
+template <bool BF>
+__device__ __forceinline__ void run_scheduled_loop(int n_full, int n_tiles, int kv_len, int cap, int st_tok, int ids_clamp, const int32_t* page_ids, uint32_t k_lo,
+                                                   uint32_t k_hi, uint32_t v_lo, uint32_t v_hi, uint32_t page_bytes,
+                                                   float scale_log2, uint64_t q_addr, uint32_t st_off_bytes,
+                                                   uint32_t k_off_bytes, uint32_t k_read, uint32_t k_swizzle,
+                                                   uint32_t v_read, uint32_t k_dma, uint32_t v_write,
+                                                   uint32_t o_off, int row_flags, float* o_base, float* lse_base,
+                                                   void* cast_base, int has_cast, uint32_t epi_write, uint32_t epi_read,
+                                                   uint32_t epi_chunk, int g_log2, int num_qo_heads, int row_base,
+                                                   int n_pos, int wave_index, int next_off,
+                                                   const int32_t* w_fields, int w_stride, uint32_t all_ids_lo,
+                                                   uint32_t all_ids_hi, WorkItem& next, int& prefetched_out) {
+#define FI355_LOOP_OPERANDS                                                                                              \
+        : [nq] "=&s"(next.q_row0), [nn] "=&s"(next.n_pos), [npg] "=&s"(next.kv_page0), [nks] "=&s"(next.kv_start),          \
+          [nkl] "=&s"(next.kv_len), [ndg] "=&s"(next.diag0), [nos] "=&s"(next.out_slot), [preo] "=&s"(prefetched_out)        \
+        : [nf] "s"(n_full), [nt] "s"(n_tiles), [kvl] "s"(kv_len), [cap] "v"(cap), [stk] "v"(st_tok), [npg1] "s"(ids_clamp), [idp] "s"(page_ids), [kblo] "s"(k_lo), [kbhi] "s"(k_hi), \
+          [vblo] "s"(v_lo), [vbhi] "s"(v_hi), [sp] "s"(page_bytes), [sc] "s"(scale_log2),                                 \
+          [qp] "v"(q_addr), [so] "v"(st_off_bytes), [sok] "v"(k_off_bytes), [kb] "v"(k_read), [kxs] "v"(k_swizzle),        \
+          [va] "v"(v_read), [kd] "s"(k_dma), [wv] "v"(v_write), [ooff] "v"(o_off), [rok] "v"(row_flags), [ob] "s"(o_base), [lb] "s"(lse_base), \
+          [cb] "s"(cast_base), [oc] "s"(has_cast), [ew] "v"(epi_write), [er] "v"(epi_read), [l16] "v"(epi_chunk),          \
+          [gl] "s"(g_log2), [hq] "s"(num_qo_heads), [rb] "s"(row_base), [np] "s"(n_pos), [stp8] "s"(wave_index),           \
+          [woff] "s"(next_off), [wq0] "s"(w_fields), [wstr] "s"(w_stride),                                                  \
+          [idblo] "s"(all_ids_lo), [idbhi] "s"(all_ids_hi)
+  if constexpr (BF) {
+    asm volatile(
+#include "append_loop_bf16.inc"
+        FI355_LOOP_OPERANDS
+        :
+#include "append_loop_clobbers.inc"
+    );
+  } else {
+    asm volatile(
+#include "append_loop_f16.inc"
+        FI355_LOOP_OPERANDS
+        :
+#include "append_loop_clobbers.inc"
+    );
+  }
+#undef FI355_LOOP_OPERANDS
+}
 
 // K tiles, then V tiles (three buffers each: the scheduled loop rotates over three, the generic
 // path over the first two).
@@ -574,9 +593,12 @@ append_kernel(const RunParams p) {
   const int w_begin = __builtin_amdgcn_readfirstlane(p.cta_indptr[cta]);
   const int w_end = __builtin_amdgcn_readfirstlane(p.cta_indptr[cta + 1]);
 
+  // The plan entry of a work item is read while the item before it runs (by the scheduled loop's block, or
+  // here); `prefetched`: that block has also requested this item's first tiles into LDS.
+  WorkItem item;
+  if (w_begin < w_end) item.load(p, w_begin);
+  int prefetched = 0;
   for (int w = w_begin; w < w_end; ++w) {
-    WorkItem item;
-    item.load(p, w);
     const int q_row0 = item.q_row0, n_pos = item.n_pos, kv_page0 = item.kv_page0, kv_start = item.kv_start;
     const int kv_len = item.kv_len, diag0 = item.diag0, out_slot = item.out_slot;
     const bool causal = diag0 != kNoDiagMarker;
@@ -607,6 +629,7 @@ append_kernel(const RunParams p) {
                                 (static_cast<int64_t>(q_row0 + pos_c) * H + head) * kHeadDim + c_o * 8);
         const uint64_t k_base = reinterpret_cast<uint64_t>(static_cast<const uint16_t*>(p.k_pool) + kvh * p.stride_head);
         const uint64_t v_base = reinterpret_cast<uint64_t>(static_cast<const uint16_t*>(p.v_pool) + kvh * p.stride_head);
+        const uint64_t all_ids = reinterpret_cast<uint64_t>(p.kv_indices);
         const uint32_t lds0 = lds_offset(lds_raw);
         const int chunk_pages = (kv_len + kPageSize - 1) / kPageSize;
         const int last_seen = causal ? min(diag0 + pos_r - kv_start, kv_len - 1) : kv_len - 1;
@@ -620,12 +643,15 @@ append_kernel(const RunParams p) {
         // holds chunk st_chunk ^ (st_tok % 16) of that token
         const uint32_t k_off_bytes =
             static_cast<uint32_t>((st_tok_o & 15) * p.stride_tok + ((st_chunk_o ^ st_tok_o) & 15) * 8) * 2;
-        __syncthreads();  // the previous work item is done with the tile buffers
+        const uint32_t epi0 = lds0 + kEpilogueBase + wave_o * kEpilogueLdsBytes;
+        WorkItem next;
+        int prefetched_next;
+        __syncthreads();  // the previous work item is done with the tile buffers and the transpose area
         run_scheduled_loop<BF>(n_full, (kv_len + kTileKv - 1) / kTileKv, kv_len, last_seen - 4 * c_o, st_tok_o,
                                (chunk_pages - 1) * 4, p.kv_indices + kv_page0, static_cast<uint32_t>(k_base),
                                static_cast<uint32_t>(k_base >> 32), static_cast<uint32_t>(v_base),
                                static_cast<uint32_t>(v_base >> 32), static_cast<uint32_t>(page_bytes), p.scale_log2,
-                               __builtin_amdgcn_readfirstlane(wave_o >> 2), q_addr, st_off_bytes, k_off_bytes,
+                               q_addr, st_off_bytes, k_off_bytes,
                                lds0 + n_o * 256 + ((c_o ^ n_o) & 1) * 16, ((n_o >> 1) & 7) * 32,
                                lds0 + kLdsVOffset + (4 * c_o + tr_row_o) * (kRowElemsV * 2) + tr_col_o * 2,
                                lds0 + __builtin_amdgcn_readfirstlane(wave_o) * 1024,
@@ -634,19 +660,28 @@ append_kernel(const RunParams p) {
                                pos_r < n_pos ? (c_o == 0 ? 3 : 1) : 0, final_out ? p.o : p.part_o,
                                final_out ? p.lse : p.part_lse, p.o_cast,
                                __builtin_amdgcn_readfirstlane(final_out && p.o_cast != nullptr ? 1 : 0),
-                               lds0 + wave_o * kEpilogueLdsBytes + n_o * kEpilogueRowBytes + c_o * 16,
-                               lds0 + wave_o * kEpilogueLdsBytes + ((tid_o >> 4) & 3) * kEpilogueRowBytes + st_chunk_o * 16,
+                               epi0 + n_o * kEpilogueRowBytes + c_o * 16,
+                               epi0 + ((tid_o >> 4) & 3) * kEpilogueRowBytes + st_chunk_o * 16,
                                st_chunk_o * 16, g_log2, H,
                                static_cast<int>((final_out ? static_cast<int64_t>(q_row0)
                                                            : static_cast<int64_t>(out_slot) * p.t_pos) * H + kvh * g),
-                               n_pos, __builtin_amdgcn_readfirstlane(wave_o));
+                               n_pos, __builtin_amdgcn_readfirstlane(wave_o),
+                               __builtin_amdgcn_readfirstlane(min(w + 1, w_end - 1) * 4 + (w + 1 < w_end ? 1 : 0) + 2 * prefetched), p.w_q_row0,
+                               static_cast<int>((p.w_n_pos - p.w_q_row0) * static_cast<int64_t>(sizeof(int32_t))),
+                               static_cast<uint32_t>(all_ids), static_cast<uint32_t>(all_ids >> 32), next,
+                               prefetched_next);
+        item = next;
+        prefetched = prefetched_next;
         continue;  // the work item is finished
       }
     }
+    if (prefetched) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // tiles requested for this item: not used, but on their way into LDS
+    prefetched = 0;
     __syncthreads();  // the previous work item is done with the tile buffers
     // (the kernel's only argument sits at the start of its argument segment)
     generic_work_item<BF>(reinterpret_cast<uint64_t>(__builtin_amdgcn_kernarg_segment_ptr()), q_row0, n_pos, kv_page0,
                           kv_start, kv_len, diag0, out_slot);
+    if (w + 1 < w_end) item.load(p, w + 1);
   }
 }
 

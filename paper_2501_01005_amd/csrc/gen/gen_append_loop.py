@@ -20,6 +20,14 @@ All working registers are fixed (see the map below) and listed as clobbers; the 
 passes only addresses and scalars in, and the loop ends with the epilogue: it writes o, lse
 and the optional cast of o itself.
 
+Work items overlap at their seams.  The block reads the plan entry of the CTA's next work item
+while it runs (outputs of the asm statement), and if that item will run this loop too, it
+requests, right before its epilogue, the first two K tiles of that item into LDS buffers 0 and 1
+and the first two V tiles, as stored, into a staging area (both with loads that write LDS
+directly: nothing is held in registers across the C++ code between two work items).  The next
+block is then entered with `pre` set and starts from LDS instead of waiting for its page ids and
+for the tiles one after the other.  The epilogue's transpose area lies clear of those regions.
+
 Run this script after changing it; the .inc files it writes are committed with it.
 """
 import os
@@ -43,11 +51,16 @@ S_IDA, S_IDB = 88, 92          # two more page id groups, start-up only
 S_EXEC = 96
 S_IDK = 88                     # page ids of the tile whose K goes to LDS next (takes over S_IDA after start-up)
 S_M0 = 97                      # saved m0 (the register doubles as half of S_EXEC, which is used only after m0 is restored)
+S_NX = 92                      # this wavefront's page ids of tiles 0 and 1 of the CTA's next work item (takes over S_IDB after start-up)
+S_STP = 96                     # which page of a 32-token half this thread's staging rows are in (wavefront / 4); the epilogue reuses the register
 FIXED_SGPRS = list(range(64, 98))
+NO_DIAG = 0x3FFFFFFF           # w_diag0 of a non-causal work item
+LOOP_MIN_TOKENS = 128          # shorter chunks never run this loop
 
 KROW, VROW = 256, 320          # LDS row pitch in bytes: K rows are packed (16-byte chunks XOR-swizzled by row), V rows padded
 KTILE, VTILE = 64 * KROW, 64 * VROW
-V_BASE = 3 * 64 * 272          # V buffers start where the generic path has them
+V_BASE = 65536                 # V buffers start where the generic path has them
+STAGE = 2 * KTILE              # the next item's V tiles 0 and 1 as stored: K buffer 2 and the 16 KB after the K buffers
 NBUF = 3
 LAZY_THR = 0x5C005C00          # fp16 2^8 in both halves: P above it raises the reference
 
@@ -173,7 +186,7 @@ class Gen:
         return ops
 
     def page_select(self, ids):
-        return ['s_cmp_eq_u32 %[stp], 0',
+        return ['s_cmp_eq_u32 s%d, 0' % S_STP,
                 's_cselect_b32 s%d, s%d, s%d' % (S_PG0, ids, ids + 1),
                 's_cselect_b32 s%d, s%d, s%d' % (S_PG1, ids + 2, ids + 3)]
 
@@ -215,6 +228,92 @@ class Gen:
             else:
                 ops.append('s_min_u32 s%d, s%d, %%[npg1]' % (off, S_TMP))
             ops.append('s_load_dword s%d, %%[idp], s%d' % (dst + r, off))
+        return ops
+
+    def header_next(self):
+        """request the plan entry of the CTA's next work item (of this one again if it is the last): the seven
+        fields are consecutive arrays, wstr bytes apart; the results are outputs of the asm statement"""
+        ops = ['s_and_b32 s%d, %%[woff], -4' % S_TMP]  # (the two low bits of woff are flags)
+        for k, out in enumerate(('nq', 'nn', 'npg', 'nks', 'nkl', 'ndg', 'nos')):
+            if k:
+                ops.append('s_add_u32 s%d, s%d, %%[wstr]' % (S_TMP, S_TMP))
+            ops.append('s_load_dword %%[%s], %%[wq0], s%d' % (out, S_TMP))
+        return ops
+
+    def next_decision_and_ids(self, tag, lbl):
+        """the next item's plan entry has arrived: will it run this loop (the item-dependent part of the C++ side's
+        test: at least LOOP_MIN_TOKENS tokens, first tile seen in full by every row)?  If so, request the page ids
+        of its tiles 0 and 1, each clamped to the chunk's last page"""
+        no = 'nopre_%s_%s' % (tag, lbl)
+        vis = 'vis_%s_%s' % (tag, lbl)
+        ops = ['s_mov_b32 %[preo], 0',
+               's_bitcmp0_b32 %[woff], 0', 's_cbranch_scc1 ' + no,
+               's_cmp_lt_u32 %%[nkl], %d' % LOOP_MIN_TOKENS, 's_cbranch_scc1 ' + no,
+               's_mov_b32 s%d, %%[nkl]' % S_REM,
+               's_cmp_eq_u32 %%[ndg], 0x%x' % NO_DIAG, 's_cbranch_scc1 ' + vis,
+               # tokens the tile's first position sees: diag0 - kv_start + 1, at least 0
+               's_sub_i32 s%d, %%[ndg], %%[nks]' % S_LO, 's_add_i32 s%d, s%d, 1' % (S_LO, S_LO),
+               's_max_i32 s%d, s%d, 0' % (S_LO, S_LO), 's_min_i32 s%d, s%d, s%d' % (S_REM, S_REM, S_LO),
+               vis + ':',
+               's_cmp_lt_u32 s%d, 64' % S_REM, 's_cbranch_scc1 ' + no,
+               's_mov_b32 %[preo], 1',
+               # byte offset of the chunk's last page id (S_REM); address of its first one (S_KA pair)
+               's_add_u32 s%d, %%[nkl], 15' % S_REM, 's_lshr_b32 s%d, s%d, 4' % (S_REM, S_REM),
+               's_sub_u32 s%d, s%d, 1' % (S_REM, S_REM), 's_lshl_b32 s%d, s%d, 2' % (S_REM, S_REM),
+               's_mov_b32 s%d, %%[npg]' % S_LO, 's_mov_b32 s%d, 0' % S_HI,
+               's_lshl_b64 s[%d:%d], s[%d:%d], 2' % (S_LO, S_HI, S_LO, S_HI),
+               's_add_u32 s%d, %%[idblo], s%d' % (S_KA, S_LO), 's_addc_u32 s%d, %%[idbhi], s%d' % (S_KA + 1, S_HI)]
+        # of a tile's four pages this thread's rows are in pages S_STP and 2 + S_STP
+        ops.append('s_lshl_b32 s%d, s%d, 2' % (S_LO, S_STP))
+        for i in range(4):
+            ops += ['s_add_u32 s%d, s%d, %d' % (S_TMP, S_LO, 8 * i), 's_min_u32 s%d, s%d, s%d' % (S_TMP, S_TMP, S_REM),
+                    's_load_dword s%d, s[%d:%d], s%d' % (S_NX + i, S_KA, S_KA + 1, S_TMP)]
+        ops.append(no + ':')
+        return ops
+
+    def k_next_to_lds(self, pages, buf):
+        """as k_to_lds, for the two pages whose ids are in s[pages], s[pages + 1]"""
+        ops = []
+        for r, pg in enumerate((pages, pages + 1)):
+            ops += ['s_mul_hi_u32 s%d, s%d, %%[sp]' % (S_HI, pg), 's_mul_i32 s%d, s%d, %%[sp]' % (S_LO, pg),
+                    's_add_u32 s%d, %%[kblo], s%d' % (S_KA, S_LO), 's_addc_u32 s%d, %%[kbhi], s%d' % (S_KA + 1, S_HI),
+                    's_add_u32 m0, %%[kd], %d' % (buf * KTILE + r * 32 * KROW), 's_nop 0',
+                    'global_load_lds_dwordx4 %%[sok], s[%d:%d]' % (S_KA, S_KA + 1)]
+        return ops
+
+    def v_to_stage(self, pages, st):
+        """V rows of that tile of the next work item, as stored, straight into the staging area: a wavefront's
+        load lands as its four consecutive 256-byte rows, lane l at m0 + 16 l, each lane its own chunk"""
+        ops = []
+        for r, pg in enumerate((pages, pages + 1)):
+            ops += ['s_mul_hi_u32 s%d, s%d, %%[sp]' % (S_HI, pg), 's_mul_i32 s%d, s%d, %%[sp]' % (S_LO, pg),
+                    's_add_u32 s%d, %%[vblo], s%d' % (S_VA, S_LO), 's_addc_u32 s%d, %%[vbhi], s%d' % (S_VA + 1, S_HI),
+                    's_add_u32 m0, %%[kd], %d' % (STAGE + st * KTILE + r * 32 * KROW), 's_nop 0',
+                    'global_load_lds_dwordx4 %%[so], s[%d:%d]' % (S_VA, S_VA + 1)]
+        return ops
+
+    def prefetch_next(self, tag, lbl):
+        """at the end of a work item (every wavefront is past its last tile read and has no load in flight): if the
+        next item runs this loop, request its K tiles 0 and 1 into buffers 0 and 1 and its V tiles 0 and 1 into the
+        staging area"""
+        skip = 'nopf_%s_%s' % (tag, lbl)
+        ops = ['s_waitcnt lgkmcnt(0)', 's_cmp_eq_u32 %[preo], 0', 's_cbranch_scc1 ' + skip]
+        for t in range(2):
+            ops += self.k_next_to_lds(S_NX + 2 * t, t)
+        for t in range(2):
+            ops += self.v_to_stage(S_NX + 2 * t, t)
+        ops.append(skip + ':')
+        return ops
+
+    def stage_reads(self, lbl):
+        """this thread's pieces of the staged V tiles 0 and 1 (the ones it requested itself at the end of the
+        previous work item) into the registers the start-up converts them from"""
+        ops = ['s_lshl_b32 s%d, %%[stp8], 10' % S_TMP, 's_sub_u32 s%d, %%[kd], s%d' % (S_TMP, S_TMP),  # LDS offset of the tile area
+               'v_lshlrev_b32 v%d, 8, %%[stk]' % X0, 'v_add_u32 v%d, v%d, %%[l16]' % (X0, X0),
+               'v_add_u32 v%d, s%d, v%d' % (X0, S_TMP, X0)]
+        for t, base in ((0, VT), (1, KA)):
+            for r in range(2):
+                ops.append('ds_read_b128 %s, v%d offset:%d' % (vr(base + 8 + 4 * r, 4), X0, STAGE + t * KTILE + r * 32 * KROW))
         return ops
 
     def ids_take(self):
@@ -322,20 +421,26 @@ class Gen:
         e.raw('s_mov_b32 s%d, m0' % S_M0)
         e.raw('s_mov_b32 s%d, 0' % S_T)
         e.raw('s_mov_b32 s%d, 0x%x' % (S_THR, LAZY_THR))
+        e.raw('s_lshr_b32 s%d, %%[stp8], 2' % S_STP)
+        for s in range(8):
+            e.emit('global_load_dwordx4 %s, %%[qp], off offset:%d' % (vr(Q + 4 * s, 4), 32 * s))
+        for o in self.header_next():
+            e.raw(o)
         e.raw('v_mov_b32 v%d, 0x3c003c00' % ONES)
         e.raw('v_mov_b32 v%d, 0' % LSUM)
         e.raw('v_mov_b32 v%d, 0xff800000' % MRUN)
         e.raw('v_mov_b32 v%d, 0xff800000' % NINF)
         for i in range(64):
             e.raw('v_mov_b32 v%d, 0' % (ACC + i))
-        for s in range(8):
-            e.emit('global_load_dwordx4 %s, %%[qp], off offset:%d' % (vr(Q + 4 * s, 4), 32 * s))
         # the eight K operand reads of a lane: row n, chunk (2 s + c) ^ (n % 16) -> kb + (32 s ^ kxs)
         for s_ in range(8):
             e.raw('v_xor_b32 v%d, %d, %%[kxs]' % (KAD + s_, 32 * s_))
             e.raw('v_add_u32 v%d, v%d, %%[kb]' % (KAD + s_, KAD + s_))
-        # start-up: the page ids of tiles 0..3 in one go, then K of tiles 0 and 1 straight into LDS and V of
-        # tiles 0, 1, 2 in flight together (tiles 0 and 1 borrow operand registers as staging)
+        q_loads = list(e.vm)
+        e.raw('s_bitcmp0_b32 %[woff], 1')
+        e.raw('s_cbranch_scc0 staged_%s' % lbl)
+        # start-up from memory: the page ids of tiles 0..3 in one go, then K of tiles 0 and 1 straight into LDS and
+        # V of tiles 0, 1, 2 in flight together (tiles 0 and 1 borrow operand registers as staging)
         for t, dst in enumerate((S_IDA, S_IDB, S_IDN, S_IDS)):
             for o in self.ids_load(t, dst):
                 e.raw(o)
@@ -346,6 +451,8 @@ class Gen:
         for ids, base in ((S_IDA, VT), (S_IDB, KA), (S_IDN, ST)):
             for o in self.fetch(ids, base):
                 e.emit(o)
+        for o in self.next_decision_and_ids('a', lbl):
+            e.raw(o)
         for t, base in ((0, VT), (1, KA)):
             for o in self.v_convert(base) + self.v_zero_tail(t, base) + self.stores(t, base):
                 e.emit(o)
@@ -353,6 +460,31 @@ class Gen:
         e.raw('s_mov_b64 s[%d:%d], s[%d:%d]' % (S_IDK, S_IDK + 1, S_IDN, S_IDN + 1))
         e.raw('s_mov_b64 s[%d:%d], s[%d:%d]' % (S_IDK + 2, S_IDK + 3, S_IDN + 2, S_IDN + 3))
         e.emit('s_barrier')
+        e.raw('s_branch started_%s' % lbl)
+        # start-up from LDS: K of tiles 0 and 1 is in its buffers, V of tiles 0 and 1 in the staging area
+        e.label('staged_%s' % lbl)
+        e.lgkm = []
+        e.vm = list(q_loads)
+        for t, dst in ((2, S_IDN), (3, S_IDS)):
+            for o in self.ids_load(t, dst):
+                e.raw(o)
+        for o in self.stage_reads(lbl):
+            e.emit(o)
+        e.drain(lgkm=True, vm=False)
+        for o in self.fetch(S_IDN, ST):
+            e.emit(o)
+        for o in self.next_decision_and_ids('b', lbl):
+            e.raw(o)
+        for t, base in ((0, VT), (1, KA)):
+            for o in self.v_convert(base) + self.v_zero_tail(t, base) + self.stores(t, base):
+                e.emit(o)
+        e.raw('s_mov_b64 s[%d:%d], s[%d:%d]' % (S_IDK, S_IDK + 1, S_IDN, S_IDN + 1))
+        e.raw('s_mov_b64 s[%d:%d], s[%d:%d]' % (S_IDK + 2, S_IDK + 3, S_IDN + 2, S_IDN + 3))
+        e.emit('s_barrier')
+        e.label('started_%s' % lbl)
+        # either way: nothing of LDS in flight; of the loads, at most Q and the V rows of tile 2, in this order
+        e.lgkm = []
+        e.vm = list(q_loads) + [set(('v', ST + 8 + 4 * r + i) for i in range(4)) for r in (0, 1)]
         # a wavefront whose first row is past the end of the query tile only helps with the staging
         e.raw('s_lshl_b32 s%d, %%[stp8], 5' % S_TMP)           # first tile row of this wavefront
         e.raw('s_lshr_b32 s%d, s%d, %%[gl]' % (S_TMP, S_TMP))  # its position
@@ -396,6 +528,8 @@ class Gen:
         EPITCH = 288
         e.label('exit_%s' % lbl)
         e.raw('s_waitcnt vmcnt(0)')
+        for o in self.prefetch_next('x', lbl):
+            e.raw(o)
         e.raw('s_mov_b32 m0, s%d' % S_M0)
         e.raw('s_nop 15')
         e.raw('s_nop 15')
@@ -436,6 +570,10 @@ class Gen:
             e.raw('s_waitcnt lgkmcnt(0)')
             for k in range(8):
                 e.raw('ds_read_b128 %s, %%[er] offset:%d' % (vr(VT + 4 * k, 4), 4 * k * EPITCH))
+            if h == 0:
+                # the tiles requested for the next work item have landed before the output stores go out: loads and
+                # stores share one counter and return out of order, so later they could not be waited for apart
+                e.raw('s_waitcnt vmcnt(0)')
             e.raw('s_cmp_eq_u32 %[oc], 0')
             e.raw('s_cbranch_scc0 cast%d_%s' % (h, lbl))
             for with_cast in (False, True):
@@ -456,6 +594,9 @@ class Gen:
             e.label('half%d_%s' % (h, lbl))
         e.raw('s_branch end_%s' % lbl)
         e.label('done_%s' % lbl)  # idle wavefronts: nothing to write
+        e.raw('s_waitcnt vmcnt(0)')
+        for o in self.prefetch_next('i', lbl):
+            e.raw(o)
         e.raw('s_waitcnt vmcnt(0)')
         e.raw('s_mov_b32 m0, s%d' % S_M0)
         e.label('end_%s' % lbl)

@@ -77,3 +77,17 @@ def test_strided_pool_layout_and_rounded_output():
         o_ref, lse_ref = oracle.run_batch(b)
         assert_close(o, lse, o_ref, lse_ref, f"cast {dtype}")
         assert np.abs(oc - o_ref).max() <= O_TOL + np.abs(o_ref).max() * ulp
+
+
+@pytest.mark.parametrize("dtype", [workloads.BF16, workloads.F16])
+def test_seams_between_work_items_of_one_cta(dtype):
+    """A single CTA per kv head walks the whole work list, so every kind of neighbour meets: an item of the
+    scheduled loop after another one (its first tiles are requested into LDS while the one before writes its
+    outputs), after a generic-path item, before one (the requested tiles are dropped), idle wavefronts (query tiles
+    of less than 256 rows) on either side, chunks that end inside their second tile, and the last item."""
+    qo = [64, 3, 64, 130, 1, 64, 40, 64, 64, 7, 200]
+    kv = [300, 50, 128, 700, 100, 129, 140, 64, 191, 400, 260]
+    for causal in (True, False):
+        b = workloads.make_batch("seams", 70 + int(causal), dtype, 8, 2, 128, 16, qo, kv, causal)
+        check(b, f"seams causal={causal}", num_ctas=2 * 1, min_chunk=1024)
+        check(b, f"seams causal={causal}, split chunks", num_ctas=2 * 2, min_chunk=128)
