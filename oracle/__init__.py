@@ -16,7 +16,7 @@ from . import attention, fp8, plan_replica  # noqa: F401
 
 def run_batch(batch, requests: Sequence[int] | None = None,
               heads: Sequence[int] | None = None, logits_soft_cap: float = 0.0, window_left: int = -1,
-              alibi_slopes=None) -> Tuple[np.ndarray, np.ndarray]:
+              alibi_slopes=None, rope_theta: float = 0.0, rope_scale: float = 1.0) -> Tuple[np.ndarray, np.ndarray]:
     """Oracle (o, lse) of a `workloads.PagedBatch` (exact widening of the stored
     16-bit inputs to float64, then `attention.batch_attention`)."""
     from workloads import widen
@@ -41,4 +41,4 @@ def run_batch(batch, requests: Sequence[int] | None = None,
         q, k_of, v_of, batch.qo_indptr, batch.kv_indptr, batch.kv_indices, batch.last_page_len,
         batch.page_size, batch.num_kv_heads, batch.sm_scale, batch.causal,
         requests=requests, heads=heads, logits_soft_cap=logits_soft_cap, window_left=window_left,
-        alibi_slopes=alibi_slopes)
+        alibi_slopes=alibi_slopes, rope_theta=rope_theta, rope_scale=rope_scale)

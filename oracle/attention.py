@@ -110,15 +110,32 @@ def variant_mask_and_bias(l_qo: int, l_kv: int, causal: bool, window_left: int =
     return vis, bias
 
 
+def rope(x: np.ndarray, pos: np.ndarray, theta: float, scale: float = 1.0) -> np.ndarray:
+    """Rotary position embedding as a query / key transform (Sec. 3.2.3; the fused-RoPE kernels of Sec. 4.4):
+    x [n, D] at positions pos [n].  Component pair (d, d + D/2), d < D/2, is rotated by the angle
+    (pos / scale) * theta ** (-2 d / D) (the "rotate half" pairing; the paper does not fix the pairing)."""
+    n, D = x.shape
+    half = D // 2
+    assert 2 * half == D
+    freq = theta ** (-2.0 * np.arange(half, dtype=np.float64) / D)
+    ang = (np.asarray(pos, dtype=np.float64)[:, None] / scale) * freq[None, :]
+    c, s = np.cos(ang), np.sin(ang)
+    lo, hi = x[:, :half], x[:, half:]
+    return np.concatenate([lo * c - hi * s, hi * c + lo * s], axis=1)
+
+
 def batch_attention(q_f64: np.ndarray, k_pool_of, v_pool_of, qo_indptr, kv_indptr, kv_indices,
                     last_page_len, page_size: int, num_kv_heads: int, sm_scale: float,
                     causal: bool, requests: Sequence[int] | None = None,
                     heads: Sequence[int] | None = None, logits_soft_cap: float = 0.0,
-                    window_left: int = -1, alibi_slopes=None) -> Tuple[np.ndarray, np.ndarray]:
+                    window_left: int = -1, alibi_slopes=None, rope_theta: float = 0.0,
+                    rope_scale: float = 1.0) -> Tuple[np.ndarray, np.ndarray]:
     """o [nnz_qo, H_qo, D], lse [nnz_qo, H_qo] (float64).
 
-    Entries for requests / heads outside the optional selections are NaN.  The last three arguments are the
-    attention variants (soft cap of the logits, sliding window, per-head ALiBi slopes)."""
+    Entries for requests / heads outside the optional selections are NaN.  The last arguments are the
+    attention variants (soft cap of the logits, sliding window, per-head ALiBi slopes; rope_theta > 0: queries
+    and keys are rotated by their positions first: key t of a request at position t, query j at
+    l_kv - l_qo + j)."""
     nnz, H, D = q_f64.shape
     g = H // num_kv_heads
     assert g * num_kv_heads == H
@@ -141,12 +158,16 @@ def batch_attention(q_f64: np.ndarray, k_pool_of, v_pool_of, qo_indptr, kv_indpt
                 cache = {kvh: (gather_rows(k_pool_of, kv_indices, kv_indptr, last_page_len, page_size, i, kvh),
                                gather_rows(v_pool_of, kv_indices, kv_indptr, last_page_len, page_size, i, kvh))}
             K, V = cache[kvh]
+            qh = q_f64[r0:r1, h, :]
+            if rope_theta > 0.0:
+                K = rope(K, np.arange(l_kv), rope_theta, rope_scale)
+                qh = rope(qh, l_kv - l_qo + np.arange(l_qo), rope_theta, rope_scale)
             bias = None
             vis_h = vis
             if window_left >= 0 or alibi_slopes is not None:
                 vis_h, bias = variant_mask_and_bias(l_qo, l_kv, causal, window_left,
                                                     None if alibi_slopes is None else float(alibi_slopes[h]))
-            oo, ll = attention_state(q_f64[r0:r1, h, :], K, V, sm_scale, vis_h, logits_soft_cap, bias)
+            oo, ll = attention_state(qh, K, V, sm_scale, vis_h, logits_soft_cap, bias)
             o[r0:r1, h, :] = oo
             lse[r0:r1, h] = ll
     return o, lse
