@@ -210,6 +210,9 @@ def main() -> int:
     ap.add_argument("--kv-dtype", default="same", choices=["same", "fp8"],
                     help="fp8: K/V stored as E4M3 codes with scales (App. F), decode workloads c2 and c4 only")
     ap.add_argument("--page-size", type=int, default=16, help="tokens per page (c2 and c3; 16 is the tuned size)")
+    ap.add_argument("--rope-theta", type=float, default=0.0,
+                    help="> 0: decode with the rotary embedding fused into the kernel (fi_run_variant; the cache holds "
+                         "unrotated keys, Sec. 4.4); 16-bit decode workloads only")
     ap.add_argument("--num-ctas", type=int, default=0)
     ap.add_argument("--min-chunk", type=int, default=0)
     ap.add_argument("--balance", type=int, default=0, help="fi_config.balance (0 = default of the mode)")
@@ -266,6 +269,16 @@ def main() -> int:
     o = torch.empty((nnz, batch.num_qo_heads, batch.head_dim), dtype=torch.float32, device=dev.device)
     lse = torch.empty((nnz, batch.num_qo_heads), dtype=torch.float32, device=dev.device)
 
+    run_kw = dict(dev.scales)
+    if args.rope_theta > 0:
+        if mode != "decode" or batch.kv_dtype or args.page_size != 16:
+            print("bench.py: --rope-theta is for the 16-bit decode workloads with page size 16", file=sys.stderr)
+            return 2
+        run_kw["variant"] = dict(
+            kv_indptr=torch.from_numpy(np.ascontiguousarray(batch.kv_indptr, dtype=np.int32)).to(dev.device),
+            last_page_len=torch.from_numpy(np.ascontiguousarray(batch.last_page_len, dtype=np.int32)).to(dev.device),
+            rope_theta=args.rope_theta)
+
     stride = max(1, args.event_stride)
     n_samples = (args.steps + stride - 1) // stride
     ev = HipEvents(n_samples)
@@ -276,7 +289,7 @@ def main() -> int:
         sampled = i_timed >= 0 and i_timed % stride == 0
         if sampled:
             fi.lib.fi_set_timing_events(w.handle, ev.start[i_timed // stride], ev.stop[i_timed // stride])
-        w.run(dev.q, dev.k_pool, dev.v_pool, dev.kv_indices, batch.sm_scale, o=o, lse=lse, **dev.scales)
+        w.run(dev.q, dev.k_pool, dev.v_pool, dev.kv_indices, batch.sm_scale, o=o, lse=lse, **run_kw)
         if sampled:
             fi.lib.fi_set_timing_events(w.handle, None, None)
 
@@ -336,6 +349,7 @@ def main() -> int:
         "config": {"workload": batch.name, "batch": batch.batch, "num_qo_heads": batch.num_qo_heads,
                    "num_kv_heads": batch.num_kv_heads, "head_dim": batch.head_dim, "page_size": batch.page_size, "page_order": args.page_order, "kv_layout": args.kv_layout,
                    "kv_dtype": batch.kv_dtype or batch.dtype,
+                   **({"fused_rope_theta": args.rope_theta} if args.rope_theta > 0 else {}),
                    "step": "fi_run only (plan reused)" if args.no_plan else "fi_plan + fi_run",
                    "ctas_per_head": int(view["ctas_per_head"]), "l_kv_chunk": int(view["l_kv_chunk"]),
                    "n_work": int(view["n_work"]), "n_split_tiles": int(view["n_merge"])},

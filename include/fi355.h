@@ -180,6 +180,11 @@ typedef struct fi_variant {
   float logits_soft_cap;
   int32_t window_left;
   const float* alibi_slopes;
+  float rope_theta; /* > 0: rotary position embedding fused into the kernel (query / key transform, Sec. 3.2.3;
+                       Sec. 4.4): before the logits, key t is rotated by its position t and the query by pos;
+                       component pair (d, d + D/2) turns by (position / rope_scale) * rope_theta^(-2d/D) radians.
+                       The cache holds the keys unrotated.  0 = off */
+  float rope_scale; /* position divisor of the rotary embedding; 0 = 1 */
 } fi_variant;
 
 /* fi_run with a variant.  kv_indptr [batch+1] and last_page_len [batch] are DEVICE copies of the arrays

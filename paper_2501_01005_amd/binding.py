@@ -54,7 +54,8 @@ _I32P = ctypes.POINTER(ctypes.c_int32)
 
 
 class fi_variant(ctypes.Structure):
-    _fields_ = [("logits_soft_cap", ctypes.c_float), ("window_left", ctypes.c_int32), ("alibi_slopes", ctypes.c_void_p)]
+    _fields_ = [("logits_soft_cap", ctypes.c_float), ("window_left", ctypes.c_int32), ("alibi_slopes", ctypes.c_void_p),
+                ("rope_theta", ctypes.c_float), ("rope_scale", ctypes.c_float)]
 
 
 class fi_plan_arrays(ctypes.Structure):
@@ -183,9 +184,10 @@ def fi_run(handle: int, q, k_pool, v_pool, kv_strides: Sequence[int], kv_indices
 
 def fi_run_variant(handle: int, q, k_pool, v_pool, kv_strides: Sequence[int], kv_indices, kv_indptr, last_page_len,
                    sm_scale: float, o, lse, o_cast=None, stream: int = 0, *, logits_soft_cap: float = 0.0,
-                   window_left: int = -1, alibi_slopes=None) -> None:
+                   window_left: int = -1, alibi_slopes=None, rope_theta: float = 0.0,
+                   rope_scale: float = 0.0) -> None:
     st = (ctypes.c_int64 * 3)(*[int(s) for s in kv_strides])
-    var = fi_variant(float(logits_soft_cap), int(window_left), _ptr(alibi_slopes))
+    var = fi_variant(float(logits_soft_cap), int(window_left), _ptr(alibi_slopes), float(rope_theta), float(rope_scale))
     _check(lib.fi_run_variant(handle, _ptr(q), _ptr(k_pool), _ptr(v_pool), st, _ptr(kv_indices), _ptr(kv_indptr),
                               _ptr(last_page_len), float(sm_scale), ctypes.byref(var), _ptr(o), _ptr(lse),
                               _ptr(o_cast), stream or None))
@@ -280,7 +282,7 @@ class PagedAttention:
             k_scale: Optional[float] = None, v_scale: Optional[float] = None, variant: Optional[dict] = None):
         """k_scale / v_scale given: the pools are an 8-bit KV cache (uint8 tensors of E4M3 codes).
         variant: dict(kv_indptr=, last_page_len= (device int32 tensors), logits_soft_cap=, window_left=,
-        alibi_slopes= (device float32 tensor)) runs fi_run_variant."""
+        alibi_slopes= (device float32 tensor), rope_theta=, rope_scale=) runs fi_run_variant."""
         torch = self.torch
         kv8 = k_scale is not None or v_scale is not None
         kv_dtype = torch.uint8 if kv8 else self.torch_dtype
@@ -299,7 +301,8 @@ class PagedAttention:
             fi_run_variant(self.handle, q, k_pool, v_pool, strides, kv_indices, variant["kv_indptr"],
                            variant["last_page_len"], sm_scale, o, lse, o_cast, self._stream(),
                            logits_soft_cap=variant.get("logits_soft_cap", 0.0),
-                           window_left=variant.get("window_left", -1), alibi_slopes=variant.get("alibi_slopes"))
+                           window_left=variant.get("window_left", -1), alibi_slopes=variant.get("alibi_slopes"),
+                           rope_theta=variant.get("rope_theta", 0.0), rope_scale=variant.get("rope_scale", 0.0))
         elif kv8:
             fi_run_kv8(self.handle, q, k_pool, v_pool, strides, kv_indices, sm_scale,
                        1.0 if k_scale is None else k_scale, 1.0 if v_scale is None else v_scale, o, lse, o_cast,

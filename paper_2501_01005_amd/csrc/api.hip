@@ -2,6 +2,7 @@
 // split of Sec. 3.4, workspace sections at fixed offsets (App. D.1), kernel launches.
 #include <hip/hip_runtime.h>
 
+#include <cmath>
 #include <cstring>
 #include <new>
 #include <string>
@@ -214,6 +215,9 @@ int32_t run_impl(fi_handle* h, const void* q, const void* k_pool, const void* v_
     if (!kv_indptr_dev || !last_page_len_dev) return set_error(FI_ERR_INVALID_ARG, "fi_run_variant: null pointer");
     if (!(variant->logits_soft_cap >= 0.f) || variant->window_left < -1)
       return set_error(FI_ERR_INVALID_ARG, "fi_run_variant: logits_soft_cap must be >= 0 and window_left >= -1");
+    if (!(variant->rope_theta >= 0.f) || !(variant->rope_scale >= 0.f) || std::isinf(variant->rope_theta) ||
+        std::isinf(variant->rope_scale))
+      return set_error(FI_ERR_INVALID_ARG, "fi_run_variant: rope_theta and rope_scale must be finite and >= 0");
   }
   if (kv8 && h->cfg.mode != FI_MODE_DECODE)
     return set_error(FI_ERR_UNSUPPORTED, "fi_run_kv8: the 8-bit KV cache is built for decode mode only");
@@ -274,7 +278,21 @@ int32_t run_impl(fi_handle* h, const void* q, const void* k_pool, const void* v_
   hipStream_t s = static_cast<hipStream_t>(stream);
   hipError_t e;
   if (h->ev_before && (e = hipEventRecord(h->ev_before, s)) != hipSuccess) return hip_error("fi_run: hipEventRecord", e);
-  e = h->cfg.mode == FI_MODE_DECODE ? launch_decode(p, bf, kv8, variant != nullptr, s) : launch_append(p, bf, s);
+  RopeTable rope;
+  const bool with_rope = variant && variant->rope_theta > 0.f;
+  if (with_rope) {
+    // revolutions per position of pair d, in double precision; the kernel reduces 256 * t1 + t0 positions with
+    // the fraction of 256 times that
+    const double scale = variant->rope_scale > 0.f ? static_cast<double>(variant->rope_scale) : 1.0;
+    for (int d = 0; d < kHeadDim / 2; ++d) {
+      const double rev = std::pow(static_cast<double>(variant->rope_theta), -2.0 * d / kHeadDim) /
+                         (2.0 * 3.14159265358979323846) / scale;
+      rope.rev[d] = static_cast<float>(rev);
+      rope.rev256[d] = static_cast<float>(256.0 * rev - std::floor(256.0 * rev));
+    }
+  }
+  e = h->cfg.mode == FI_MODE_DECODE ? launch_decode(p, bf, kv8, variant != nullptr, with_rope ? &rope : nullptr, s)
+                                    : launch_append(p, bf, s);
   if (e != hipSuccess) return hip_error("fi_run: attention launch", e);
   if (h->ev_after && (e = hipEventRecord(h->ev_after, s)) != hipSuccess) return hip_error("fi_run: hipEventRecord", e);
 

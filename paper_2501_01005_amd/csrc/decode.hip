@@ -110,8 +110,57 @@ struct KvTile {
 // VAR: attention variants (Sec. 3.2.3, logits transform and logits mask) on the scaled logits, in this order:
 // soft cap c * tanh(s / c), ALiBi bias slope[head] * (t - pos), sliding window (tokens t < pos - window hidden);
 // pos = l_kv - 1 is the absolute position of the request's query.  A step may then hold no visible token.
-template <bool BF, bool KV8, bool ANYPS, bool VAR = false>
-__global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2))) decode_kernel(const RunParams p) {
+// ROPE (with VAR): rotary position embedding as query and key transform (Sec. 3.2.3; the fused-RoPE kernels of
+// Sec. 4.4): key t of a request is rotated by its position t, the query by pos, pairing components (d, d + 64).
+// The rotated values are formed in fp32 from the K operands as they come back from LDS (a lane holds both
+// components of a pair there).  With bf16 inputs they are split into a bf16 head and remainder, as P is, and the
+// first product takes three instructions per operand pair (head x head, remainder x head, head x remainder).
+struct NoRope {};
+template <bool ROPE>
+using RopeArg = typename std::conditional<ROPE, RopeTable, NoRope>::type;
+
+template <bool BF>
+__device__ __forceinline__ float elem16(uint32_t word, int odd) {
+  if constexpr (BF) {
+    return __builtin_bit_cast(float, odd ? (word & 0xffff0000u) : (word << 16));
+  } else {
+    const f16x2_t h = __builtin_bit_cast(f16x2_t, word);
+    return static_cast<float>(odd ? h[1] : h[0]);
+  }
+}
+
+// (x, y) = the lane's eight components of the blocks d and d + 64 of one row; cs / sn = cosine / sine of the
+// row's angle for each of the eight pairs.  Rotated values -> MFMA operands: head, and for bf16 the remainder.
+template <bool BF>
+__device__ __forceinline__ void rotate_blocks(const u32x4_t x, const u32x4_t y, const float* cs, const float* sn,
+                                              u32x4_t* xh, u32x4_t* yh, u32x4_t* xl, u32x4_t* yl) {
+  float xr[8], yr[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    const float xe = elem16<BF>(x[e >> 1], e & 1), ye = elem16<BF>(y[e >> 1], e & 1);
+    xr[e] = xe * cs[e] - ye * sn[e];
+    yr[e] = ye * cs[e] + xe * sn[e];
+  }
+  *xh = u32x4_t{pack2<BF>(xr[0], xr[1]), pack2<BF>(xr[2], xr[3]), pack2<BF>(xr[4], xr[5]), pack2<BF>(xr[6], xr[7])};
+  *yh = u32x4_t{pack2<BF>(yr[0], yr[1]), pack2<BF>(yr[2], yr[3]), pack2<BF>(yr[4], yr[5]), pack2<BF>(yr[6], yr[7])};
+  if constexpr (BF) {
+    // remainder = value - head; the head's value is its 16 bits in the upper half of a float
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      xr[e] -= elem16<BF>((*xh)[e >> 1], e & 1);
+      yr[e] -= elem16<BF>((*yh)[e >> 1], e & 1);
+    }
+    *xl = u32x4_t{pack2<BF>(xr[0], xr[1]), pack2<BF>(xr[2], xr[3]), pack2<BF>(xr[4], xr[5]), pack2<BF>(xr[6], xr[7])};
+    *yl = u32x4_t{pack2<BF>(yr[0], yr[1]), pack2<BF>(yr[2], yr[3]), pack2<BF>(yr[4], yr[5]), pack2<BF>(yr[6], yr[7])};
+  }
+}
+
+// (The rotary variant runs one wavefront per SIMD with up to 512 registers: at two it spills 130 registers into
+// scratch memory inside the tile loop and takes 1.7 times as long.)
+template <bool BF, bool KV8, bool ANYPS, bool VAR = false, bool ROPE = false>
+__global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(ROPE ? 1 : 2, ROPE ? 1 : 2)))
+decode_kernel(const RunParams p, const RopeArg<ROPE> rope) {
+  static_assert(!ROPE || (VAR && !KV8 && !ANYPS), "the rotary transform is built into the 16-bit variant kernel");
   const int lane = threadIdx.x;
   const int m = lane & 15;  // K: token in page; V: 16-byte column block; S/O: query head
   const int c = lane >> 4;  // lane group
@@ -156,6 +205,28 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2)))
   const int w_begin = cta_indptr[cta];
   const int w_end = cta_indptr[cta + 1];
 
+  // the frequency tables, one entry per lane, in LDS: a lane later reads the eight entries of each of its blocks
+  // (the CTA is one wavefront: its LDS operations execute in program order)
+  __shared__ __attribute__((aligned(16))) float rope_lds[ROPE ? 128 : 4];
+  if constexpr (ROPE) {
+    rope_lds[lane] = rope.rev[lane];
+    rope_lds[64 + lane] = rope.rev256[lane];
+  }
+  // cosines and sines of the lane's eight pairs of block pair sp (components 32 sp + 8 c + e and + 64) at position t
+  auto angles = [&](int t, int sp, float* cs, float* sn) {
+    const float t1 = static_cast<float>(t >> 8), t0 = static_cast<float>(t & 255);
+    const f32x4_t* fr = reinterpret_cast<const f32x4_t*>(&rope_lds[32 * sp + 8 * c]);
+    const f32x4_t* gr = reinterpret_cast<const f32x4_t*>(&rope_lds[64 + 32 * sp + 8 * c]);
+    const f32x4_t f0 = fr[0], f1 = fr[1], g0 = gr[0], g1 = gr[1];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const float f = e < 4 ? f0[e & 3] : f1[e & 3], g = e < 4 ? g0[e & 3] : g1[e & 3];
+      const float rev = __builtin_amdgcn_fractf(t1 * g + t0 * f);
+      cs[e] = __builtin_amdgcn_cosf(rev);
+      sn[e] = __builtin_amdgcn_sinf(rev);
+    }
+  };
+
   for (int w = w_begin; w < w_end; ++w) {
     const int q_row0 = w_q_row0[w];
     const int kv_page0 = w_kv_page0[w];
@@ -164,13 +235,17 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2)))
     const int ps_log2 = ANYPS ? p.page_log2 : 4;
     // variants: chunk-local token index -> distance to the query
     int tok_minus_pos = 0;  // (absolute index of the chunk's first token) - pos
+    int tok_abs0 = 0;       // absolute index of the chunk's first token
+    int pos = 0;
     float slope_log2 = 0.f;
     if constexpr (VAR) {
       const int req = as_const(p.w_request)[w];
       ConstInts indptr = as_const(p.kv_indptr);
       const int n_pg = indptr[req + 1] - indptr[req];
       const int l_kv = n_pg > 0 ? (n_pg - 1) * kPageSize + as_const(p.last_page_len)[req] : 0;
-      tok_minus_pos = as_const(p.w_kv_start)[w] - (l_kv - 1);
+      tok_abs0 = as_const(p.w_kv_start)[w];
+      pos = l_kv - 1;
+      tok_minus_pos = tok_abs0 - pos;
       if (p.alibi_slopes != nullptr && m < g) slope_log2 = p.alibi_slopes[kvh * g + m] * 1.4426950408889634f;
     }
     const int n_pages = (kv_len + (1 << ps_log2) - 1) >> ps_log2;
@@ -186,6 +261,23 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2)))
     } else {
 #pragma unroll
       for (int s = 0; s < 4; ++s) qreg[s] = u32x4_t{0u, 0u, 0u, 0u};
+    }
+
+    u32x4_t qlo[ROPE && BF ? 4 : 1];  // bf16: remainder of the rotated query
+    if constexpr (ROPE) {
+#pragma unroll
+      for (int sp = 0; sp < 2; ++sp) {
+        float cs[8], sn[8];
+        angles(pos, sp, cs, sn);
+        u32x4_t xh, yh, xl, yl;
+        rotate_blocks<BF>(qreg[sp], qreg[sp + 2], cs, sn, &xh, &yh, &xl, &yl);
+        qreg[sp] = xh;
+        qreg[sp + 2] = yh;
+        if constexpr (BF) {
+          qlo[sp] = xl;
+          qlo[sp + 2] = yl;
+        }
+      }
     }
 
     f32x4_t acc[8];  // acc[e][i] = O^T[d = 32 c + 8 i + e][head m]
@@ -253,12 +345,37 @@ __global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(2, 2)))
           }
         }
       f32x4_t s0 = {0.f, 0.f, 0.f, 0.f}, s1 = {0.f, 0.f, 0.f, 0.f};
+      if constexpr (ROPE) {
 #pragma unroll
-      for (int s = 0; s < 4; ++s) {
-        const u32x4_t ka0 = k_lds[m * 16 + (((4 * s + c) ^ m) & 15)];
-        const u32x4_t ka1 = k_lds[256 + m * 16 + (((4 * s + c) ^ m) & 15)];
-        s0 = mfma_16x16x32<BF>(ka0, qreg[s], s0);
-        s1 = mfma_16x16x32<BF>(ka1, qreg[s], s1);
+        for (int pg = 0; pg < 2; ++pg) {
+          f32x4_t sacc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+          for (int sp = 0; sp < 2; ++sp) {
+            float cs[8], sn[8];
+            angles(tok_abs0 + 32 * t + 16 * pg + m, sp, cs, sn);  // this lane's K row is token m of the page
+            const u32x4_t x = k_lds[pg * 256 + m * 16 + (((4 * sp + c) ^ m) & 15)];
+            const u32x4_t y = k_lds[pg * 256 + m * 16 + (((4 * (sp + 2) + c) ^ m) & 15)];
+            u32x4_t xh, yh, xl, yl;
+            rotate_blocks<BF>(x, y, cs, sn, &xh, &yh, &xl, &yl);
+            sacc = mfma_16x16x32<BF>(xh, qreg[sp], sacc);
+            sacc = mfma_16x16x32<BF>(yh, qreg[sp + 2], sacc);
+            if constexpr (BF) {
+              sacc = mfma_16x16x32<BF>(xl, qreg[sp], sacc);
+              sacc = mfma_16x16x32<BF>(yl, qreg[sp + 2], sacc);
+              sacc = mfma_16x16x32<BF>(xh, qlo[sp], sacc);
+              sacc = mfma_16x16x32<BF>(yh, qlo[sp + 2], sacc);
+            }
+          }
+          if (pg == 0) s0 = sacc; else s1 = sacc;
+        }
+      } else {
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+          const u32x4_t ka0 = k_lds[m * 16 + (((4 * s + c) ^ m) & 15)];
+          const u32x4_t ka1 = k_lds[256 + m * 16 + (((4 * s + c) ^ m) & 15)];
+          s0 = mfma_16x16x32<BF>(ka0, qreg[s], s0);
+          s1 = mfma_16x16x32<BF>(ka1, qreg[s], s1);
+        }
       }
       // lane (m, c) now holds S^T[token 16 pg + 4 c + i][head m]
       const int tok0 = 32 * t + 4 * c;
@@ -446,25 +563,32 @@ void launch_decode_ps(const RunParams& p, bool is_bf16, bool kv8, hipStream_t st
   const dim3 block(64, 1, 1);
   if (kv8) {
     if (is_bf16)
-      hipLaunchKernelGGL((decode_kernel<true, true, ANYPS>), grid, block, 0, stream, p);
+      hipLaunchKernelGGL((decode_kernel<true, true, ANYPS>), grid, block, 0, stream, p, NoRope{});
     else
-      hipLaunchKernelGGL((decode_kernel<false, true, ANYPS>), grid, block, 0, stream, p);
+      hipLaunchKernelGGL((decode_kernel<false, true, ANYPS>), grid, block, 0, stream, p, NoRope{});
   } else {
     if (is_bf16)
-      hipLaunchKernelGGL((decode_kernel<true, false, ANYPS>), grid, block, 0, stream, p);
+      hipLaunchKernelGGL((decode_kernel<true, false, ANYPS>), grid, block, 0, stream, p, NoRope{});
     else
-      hipLaunchKernelGGL((decode_kernel<false, false, ANYPS>), grid, block, 0, stream, p);
+      hipLaunchKernelGGL((decode_kernel<false, false, ANYPS>), grid, block, 0, stream, p, NoRope{});
   }
 }
 }  // namespace
 
-hipError_t launch_decode(const RunParams& p, bool is_bf16, bool kv8, bool variant, hipStream_t stream) {
+hipError_t launch_decode(const RunParams& p, bool is_bf16, bool kv8, bool variant, const RopeTable* rope,
+                         hipStream_t stream) {
   if (variant) {
     const dim3 grid(static_cast<unsigned>(p.ctas_per_head), static_cast<unsigned>(p.num_kv_heads), 1);
-    if (is_bf16)
-      hipLaunchKernelGGL((decode_kernel<true, false, false, true>), grid, dim3(64, 1, 1), 0, stream, p);
-    else
-      hipLaunchKernelGGL((decode_kernel<false, false, false, true>), grid, dim3(64, 1, 1), 0, stream, p);
+    if (rope) {
+      if (is_bf16)
+        hipLaunchKernelGGL((decode_kernel<true, false, false, true, true>), grid, dim3(64, 1, 1), 0, stream, p, *rope);
+      else
+        hipLaunchKernelGGL((decode_kernel<false, false, false, true, true>), grid, dim3(64, 1, 1), 0, stream, p, *rope);
+    } else if (is_bf16) {
+      hipLaunchKernelGGL((decode_kernel<true, false, false, true>), grid, dim3(64, 1, 1), 0, stream, p, NoRope{});
+    } else {
+      hipLaunchKernelGGL((decode_kernel<false, false, false, true>), grid, dim3(64, 1, 1), 0, stream, p, NoRope{});
+    }
     return hipGetLastError();
   }
   if (p.page_log2 == 4)

@@ -41,6 +41,15 @@ struct RunParams {
   int32_t window_left;           // >= 0: tokens more than this far behind the query are hidden
 };
 
+// Rotary position embedding fused into the decode kernel (query / key transform, Sec. 3.2.3): the angle of
+// component pair (d, d + 64) at position t is t * rev[d] revolutions.  A second table holds fract(256 * rev[d]),
+// rounded from double precision, so that the kernel can reduce t = 256 t1 + t0 to a fraction of a revolution
+// without losing the low bits of large positions: fract(t1 * rev256[d] + t0 * rev[d]).
+struct RopeTable {
+  float rev[64];
+  float rev256[64];
+};
+
 struct MergeParams {
   const int32_t* header;  // plan header: [H_N_MERGE] read on the device
   const int32_t* m_q_row0;
@@ -58,7 +67,9 @@ struct MergeParams {
 // decode.hip: query tile = 1 position x g fused heads, one wavefront per CTA.
 // kv8: the pools hold OCP E4M3 codes (App. F) instead of the query type.  variant: the logits hooks of
 // RunParams are applied (16-bit pools, page size 16 only).
-hipError_t launch_decode(const RunParams& p, bool is_bf16, bool kv8, bool variant, hipStream_t stream);
+// rope != null (variant launches only): queries and keys are rotated by their positions first.
+hipError_t launch_decode(const RunParams& p, bool is_bf16, bool kv8, bool variant, const RopeTable* rope,
+                         hipStream_t stream);
 // append.hip: query tile = append_tile_rows()/g positions x g fused heads, 8 wavefronts per CTA.
 hipError_t launch_append(const RunParams& p, bool is_bf16, hipStream_t stream);
 int append_tile_rows();  // fused rows (positions x group) of one append query tile

@@ -23,7 +23,7 @@ def run_variant(batch, num_ctas=0, min_chunk=0, **var):
              last_page_len=torch.from_numpy(np.ascontiguousarray(batch.last_page_len, dtype=np.int32)).to(dev.device))
     if "alibi_slopes" in var:
         v["alibi_slopes"] = torch.from_numpy(np.asarray(var["alibi_slopes"], dtype=np.float32)).to(dev.device)
-    v.update({k: var[k] for k in ("logits_soft_cap", "window_left") if k in var})
+    v.update({k: var[k] for k in ("logits_soft_cap", "window_left", "rope_theta", "rope_scale") if k in var})
     w.run(dev.q, dev.k_pool, dev.v_pool, dev.kv_indices, batch.sm_scale, o=o, lse=lse, variant=v)
     torch.cuda.synchronize()
     w.close()
@@ -54,6 +54,20 @@ def test_each_variant_and_all_together(dtype, g):
     check(b, "alibi", alibi_slopes=slopes(2 * g))
     check(b, "window", window_left=70)
     check(b, "all", logits_soft_cap=5.0, window_left=33, alibi_slopes=slopes(2 * g))
+
+
+@pytest.mark.parametrize("dtype", [workloads.BF16, workloads.F16])
+def test_fused_rotary_embedding(dtype):
+    """Keys are stored unrotated; the kernel rotates key t by t and the query by l_kv - 1 (Sec. 4.4's fused
+    kernel).  Short and long requests, split chunks (a chunk's first token is not token 0), positions beyond
+    65536 (where a single-precision angle would have lost its low bits), a position divisor, other variants on top."""
+    b = workloads.random_case(430, dtype=dtype, num_qo_heads=8, num_kv_heads=2, batch=6, max_kv=700, value_scale=1.0)
+    check(b, "rope", rope_theta=1e4)
+    check(b, "rope, split chunks", num_ctas=2 * 16, min_chunk=32, rope_theta=1e4)
+    check(b, "rope, other base and divisor", rope_theta=5e5, rope_scale=4.0)
+    check(b, "rope + cap + window + alibi", rope_theta=1e4, logits_soft_cap=4.0, window_left=100, alibi_slopes=slopes(8))
+    far = workloads.make_batch("far", 431, dtype, 4, 1, 128, 16, [1, 1, 1], [70000, 1, 255], False, poison=False)
+    check(far, "rope at positions up to 70000", rope_theta=1e4)
 
 
 def test_window_hides_whole_steps_and_whole_chunks():
