@@ -317,6 +317,7 @@ def main() -> int:
     tpath = os.path.join(ROOT, "profiles", "traffic.json")
     if os.path.exists(tpath):
         traffic = json.load(open(tpath)).get(args.workload + ("_fp8" if batch.kv_dtype else "") +
+                                             ("_rope" if args.rope_theta > 0 else "") +
                                              ("_small" if args.small else ""))
 
     if mode == "decode":
