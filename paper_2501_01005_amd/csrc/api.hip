@@ -33,6 +33,7 @@ struct fi_handle {
   std::vector<int32_t> host_plan;  // last plan section (also the pageable staging buffer)
   bool planned_host = false;
   bool planned_dev = false;
+  bool pp_causal_last = false;  // `causal` of the last successful fi_plan
   void* workspace_dev = nullptr;
   size_t workspace_bytes = 0;
   hipEvent_t ev_before = nullptr;
@@ -142,6 +143,7 @@ int32_t fi_plan(fi_handle* h, const int32_t* qo_indptr, const int32_t* kv_indptr
   const int32_t rc = make_plan(pp, h->layout, qo_indptr, kv_indptr, last_page_len, batch, h->host_plan.data(), &err);
   if (rc != FI_OK) return set_error(rc, err);
   h->planned_host = true;
+  h->pp_causal_last = causal != 0;
   if (!workspace_dev) return FI_OK;
   const size_t bytes = h->layout.plan_ints * sizeof(int32_t);
   hipStream_t s = static_cast<hipStream_t>(stream);
@@ -210,8 +212,12 @@ int32_t run_impl(fi_handle* h, const void* q, const void* k_pool, const void* v_
                  const int32_t* kv_indptr_dev = nullptr, const int32_t* last_page_len_dev = nullptr) {
   if (!h) return set_error(FI_ERR_INVALID_ARG, "fi_run: null handle");
   if (variant) {
-    if (h->cfg.mode != FI_MODE_DECODE || h->cfg.page_size != kPageSize)
-      return set_error(FI_ERR_UNSUPPORTED, "fi_run_variant: built for decode mode with page_size 16");
+    if (h->cfg.page_size != kPageSize)
+      return set_error(FI_ERR_UNSUPPORTED, "fi_run_variant: built for page_size 16");
+    if (h->cfg.mode != FI_MODE_DECODE && !h->pp_causal_last)
+      return set_error(FI_ERR_UNSUPPORTED, "fi_run_variant: in append mode the batch must be planned with causal = 1");
+    if (h->cfg.mode != FI_MODE_DECODE && variant->rope_theta > 0.f)
+      return set_error(FI_ERR_UNSUPPORTED, "fi_run_variant: the fused rotary embedding is built for decode mode only");
     if (!kv_indptr_dev || !last_page_len_dev) return set_error(FI_ERR_INVALID_ARG, "fi_run_variant: null pointer");
     if (!(variant->logits_soft_cap >= 0.f) || variant->window_left < -1)
       return set_error(FI_ERR_INVALID_ARG, "fi_run_variant: logits_soft_cap must be >= 0 and window_left >= -1");
@@ -292,7 +298,7 @@ int32_t run_impl(fi_handle* h, const void* q, const void* k_pool, const void* v_
     }
   }
   e = h->cfg.mode == FI_MODE_DECODE ? launch_decode(p, bf, kv8, variant != nullptr, with_rope ? &rope : nullptr, s)
-                                    : launch_append(p, bf, s);
+                                    : launch_append(p, bf, variant != nullptr, s);
   if (e != hipSuccess) return hip_error("fi_run: attention launch", e);
   if (h->ev_after && (e = hipEventRecord(h->ev_after, s)) != hipSuccess) return hip_error("fi_run: hipEventRecord", e);
 

@@ -239,7 +239,12 @@ __shared__ __attribute__((aligned(16))) uint8_t lds_raw[kLdsBytes];
 // (Arguments of a device function travel in vector registers: the item's fields and the address
 // of the launch parameters, which the kernel takes from its argument segment, are made scalar
 // again here.)
-template <bool BF>
+//
+// VAR: attention variants (Sec. 3.2.3, logits transform and logits mask) for causal batches, where the item's
+// diagonal gives every row its absolute position pos = diag0 + (row's position in the tile).  On the scaled
+// logits, in this order: soft cap c * tanh(s / c), ALiBi bias slope[head] * (t - pos), sliding window (tokens
+// t < pos - window hidden).  A window only masks: the tiles it hides are still read.
+template <bool BF, bool VAR>
 __device__ __attribute__((noinline)) void generic_work_item(uint64_t params_addr, int a_q_row0, int a_n_pos,
                                                             int a_kv_page0, int a_kv_start, int a_kv_len, int a_diag0,
                                                             int a_out_slot) {
@@ -288,6 +293,7 @@ __device__ __attribute__((noinline)) void generic_work_item(uint64_t params_addr
 
   // ---- this lane's query rows, one per 32-row block ----
   int pos[kRowBlocks], hh[kRowBlocks], lim[kRowBlocks];
+  float slope_log2[kRowBlocks];  // VAR: ALiBi slope of the row's head, times log2(e)
   bool row_ok[kRowBlocks];
   u32x4_t qreg[kRowBlocks][8];  // Q^T as B operand: row n of the block, d = 16 s + 8 c .. + 8
 #pragma unroll
@@ -298,6 +304,10 @@ __device__ __attribute__((noinline)) void generic_work_item(uint64_t params_addr
     row_ok[b] = pos[b] < n_pos;
     // the row sees request tokens <= diag0 + pos; in chunk-local terms: local index <= lim
     lim[b] = causal ? diag0 + pos[b] - kv_start : 0x3FFFFFFF;
+    slope_log2[b] = 0.f;
+    if constexpr (VAR) {
+      if (p.alibi_slopes != nullptr) slope_log2[b] = p.alibi_slopes[kvh * g + hh[b]] * 1.4426950408889634f;
+    }
     if (row_ok[b]) {
       const uint16_t* qp = static_cast<const uint16_t*>(p.q) +
                            (static_cast<int64_t>(q_row0 + pos[b]) * H + kvh * g + hh[b]) * kHeadDim + c * 8;
@@ -447,6 +457,23 @@ __device__ __attribute__((noinline)) void generic_work_item(uint64_t params_addr
         float sv[16];  // raw logits q.k; the softmax scale is folded into the exponent below
 #pragma unroll
         for (int r = 0; r < 16; ++r) sv[r] = sacc[b][r];
+        // the factor that turns sv into the exponent's units: the variants leave sv in log2 units already
+        const float to_log2 = VAR ? 1.0f : p.scale_log2;
+        if constexpr (VAR) {
+          const float cap = p.soft_cap;
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            const int dist = tok_base + 8 * (r >> 2) + 4 * c + (r & 3) - lim[b];  // t - pos (chunk-local on both sides)
+            float s = sv[r] * p.scale_log2;
+            if (cap > 0.f) {  // cap * tanh(s / cap), s in log2 units: tanh(x) = 1 - 2 / (1 + exp(2 x))
+              const float e2x = __builtin_amdgcn_exp2f(s * (2.0f / cap));
+              s = cap * 1.4426950408889634f * (1.0f - 2.0f / (1.0f + e2x));
+            }
+            s += slope_log2[b] * static_cast<float>(dist);
+            if (p.window_left >= 0 && dist < -p.window_left) s = NEG_INF;
+            sv[r] = s;
+          }
+        }
         const bool need_mask = (tok_base + 32 > kv_len) || (tok_base + 31 > blk_lim_lo[b]);
         if (need_mask) {
           const int cap = min(lim[b], kv_len - 1);
@@ -465,8 +492,8 @@ __device__ __attribute__((noinline)) void generic_work_item(uint64_t params_addr
         auto exponentiate = [&]() {
 #pragma unroll
           for (int j = 0; j < 8; ++j) {
-            const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(sv[2 * j], p.scale_log2, neg_ms[b]));
-            const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(sv[2 * j + 1], p.scale_log2, neg_ms[b]));
+            const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(sv[2 * j], to_log2, neg_ms[b]));
+            const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(sv[2 * j + 1], to_log2, neg_ms[b]));
             h[j] = __builtin_convertvector(f32x2_t{p0, p1}, f16x2_t);  // one v_cvt_pk_f16_f32
           }
         };
@@ -483,9 +510,9 @@ __device__ __attribute__((noinline)) void generic_work_item(uint64_t params_addr
           tmax = halves_max(tmax);
           const float m_new = fmaxf(m_run[b], tmax);
           const float m_use = (m_new == NEG_INF) ? 0.f : m_new;  // row has seen nothing yet
-          const float alpha = __builtin_amdgcn_exp2f((m_run[b] - m_use) * p.scale_log2);
+          const float alpha = __builtin_amdgcn_exp2f((m_run[b] - m_use) * to_log2);
           m_run[b] = m_new;
-          neg_ms[b] = -m_use * p.scale_log2;
+          neg_ms[b] = -m_use * to_log2;
           l_run[b] *= alpha;
 #pragma unroll
           for (int db = 0; db < 4; ++db) acc[b][db] *= alpha;
@@ -546,7 +573,7 @@ __device__ __attribute__((noinline)) void generic_work_item(uint64_t params_addr
     const bool live = l > 0.f;
     const float inv = live ? 1.0f / l : 0.f;
     const float lse_val =
-        live ? (m_run[b] * p.scale_log2 + __builtin_amdgcn_logf(l)) * 0.6931471805599453f : NEG_INF;
+        live ? (m_run[b] * (VAR ? 1.0f : p.scale_log2) + __builtin_amdgcn_logf(l)) * 0.6931471805599453f : NEG_INF;
     if (row_ok[b]) {
       const int head = kvh * g + hh[b];
       const int64_t final_row = static_cast<int64_t>(q_row0 + pos[b]) * H + head;
@@ -578,7 +605,7 @@ __device__ __attribute__((noinline)) void generic_work_item(uint64_t params_addr
   }
 }
 
-template <bool BF>
+template <bool BF, bool VAR = false>
 __global__ void __launch_bounds__(kCtaThreads) __attribute__((amdgpu_waves_per_eu(2, 2)))
 append_kernel(const RunParams p) {
   const int tid = threadIdx.x;
@@ -604,7 +631,7 @@ append_kernel(const RunParams p) {
     const bool causal = diag0 != kNoDiagMarker;
 
     // ---- work items whose first tile every row of the CTA sees in full: the scheduled loop ----
-    if constexpr (kUseScheduledLoop) {
+    if constexpr (kUseScheduledLoop && !VAR) {  // (the variants run every item on the generic path)
       int vis = kv_len;  // tokens visible to the CTA's first position, which sees the fewest
       if (causal) vis = min(vis, max(0, diag0 - kv_start + 1));
       const int n_full = __builtin_amdgcn_readfirstlane(vis / kTileKv);
@@ -679,7 +706,7 @@ append_kernel(const RunParams p) {
     prefetched = 0;
     __syncthreads();  // the previous work item is done with the tile buffers
     // (the kernel's only argument sits at the start of its argument segment)
-    generic_work_item<BF>(reinterpret_cast<uint64_t>(__builtin_amdgcn_kernarg_segment_ptr()), q_row0, n_pos, kv_page0,
+    generic_work_item<BF, VAR>(reinterpret_cast<uint64_t>(__builtin_amdgcn_kernarg_segment_ptr()), q_row0, n_pos, kv_page0,
                           kv_start, kv_len, diag0, out_slot);
     if (w + 1 < w_end) item.load(p, w + 1);
   }
@@ -689,9 +716,16 @@ append_kernel(const RunParams p) {
 
 int append_tile_rows() { return (kCtaThreads / 64) * 32 * kRowBlocks; }
 
-hipError_t launch_append(const RunParams& p, bool is_bf16, hipStream_t stream) {
+hipError_t launch_append(const RunParams& p, bool is_bf16, bool variant, hipStream_t stream) {
   const dim3 grid(static_cast<unsigned>(p.ctas_per_head) * static_cast<unsigned>(p.num_kv_heads), 1, 1);
   const dim3 block(kCtaThreads, 1, 1);
+  if (variant) {
+    if (is_bf16)
+      hipLaunchKernelGGL((append_kernel<true, true>), grid, block, 0, stream, p);
+    else
+      hipLaunchKernelGGL((append_kernel<false, true>), grid, block, 0, stream, p);
+    return hipGetLastError();
+  }
   if (is_bf16)
     hipLaunchKernelGGL(append_kernel<true>, grid, block, 0, stream, p);
   else

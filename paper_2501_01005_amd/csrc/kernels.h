@@ -71,7 +71,8 @@ struct MergeParams {
 hipError_t launch_decode(const RunParams& p, bool is_bf16, bool kv8, bool variant, const RopeTable* rope,
                          hipStream_t stream);
 // append.hip: query tile = append_tile_rows()/g positions x g fused heads, 8 wavefronts per CTA.
-hipError_t launch_append(const RunParams& p, bool is_bf16, hipStream_t stream);
+// variant: the logits hooks of RunParams are applied (causal batches only; every item takes the generic path).
+hipError_t launch_append(const RunParams& p, bool is_bf16, bool variant, hipStream_t stream);
 int append_tile_rows();  // fused rows (positions x group) of one append query tile
 // upload.hip: staging (device view of page-locked host memory) -> plan section
 hipError_t launch_plan_upload(const int32_t* staging_dev_view, int32_t* plan_section, int32_t n_ints,

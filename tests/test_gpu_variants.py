@@ -1,6 +1,7 @@
-"""GPU parity of decode with attention variants (Sec. 3.2.3: soft cap of the logits, ALiBi bias, sliding
-window) against the oracle: each variant alone, all together, windows that hide whole steps and whole
-split chunks (whose partial state is then the identity of the merge), both query types."""
+"""GPU parity of decode and causal append with attention variants (Sec. 3.2.3: soft cap of the logits, ALiBi
+bias, sliding window; decode also the fused rotary embedding) against the oracle: each variant alone, all
+together, windows that hide whole steps and whole split chunks (whose partial state is then the identity of
+the merge), both query types."""
 import numpy as np
 import pytest
 
@@ -11,11 +12,11 @@ from gpu_util import DeviceBatch, assert_close, make_wrapper
 pytestmark = pytest.mark.gpu
 
 
-def run_variant(batch, num_ctas=0, min_chunk=0, **var):
+def run_variant(batch, num_ctas=0, min_chunk=0, mode="decode", **var):
     import torch
     dev = DeviceBatch(batch)
-    w = make_wrapper(batch, "decode", num_ctas=num_ctas, min_chunk=min_chunk)
-    w.plan(batch.qo_indptr, batch.kv_indptr, batch.last_page_len, causal=False)
+    w = make_wrapper(batch, mode, num_ctas=num_ctas, min_chunk=min_chunk)
+    w.plan(batch.qo_indptr, batch.kv_indptr, batch.last_page_len, causal=batch.causal)
     nnz = dev.q.shape[0]
     o = torch.full((nnz, batch.num_qo_heads, batch.head_dim), float("nan"), dtype=torch.float32, device=dev.device)
     lse = torch.full((nnz, batch.num_qo_heads), float("nan"), dtype=torch.float32, device=dev.device)
@@ -30,12 +31,12 @@ def run_variant(batch, num_ctas=0, min_chunk=0, **var):
     return o.double().cpu().numpy(), lse.double().cpu().numpy()
 
 
-def check(batch, what, num_ctas=0, min_chunk=0, **var):
-    print(f"[case] {what}: {batch.name} dtype={batch.dtype} heads={batch.num_qo_heads}/{batch.num_kv_heads} "
-          f"kv={batch.kv_lens()[:8].tolist()} variant={ {k: (v if np.isscalar(v) else 'array') for k, v in var.items()} }",
-          flush=True)
+def check(batch, what, num_ctas=0, min_chunk=0, mode="decode", **var):
+    print(f"[case] {what}: {batch.name} {mode} dtype={batch.dtype} heads={batch.num_qo_heads}/{batch.num_kv_heads} "
+          f"qo={batch.qo_lens()[:8].tolist()} kv={batch.kv_lens()[:8].tolist()} "
+          f"variant={ {k: (v if np.isscalar(v) else 'array') for k, v in var.items()} }", flush=True)
     o_ref, lse_ref = oracle.run_batch(batch, **var)
-    o, lse = run_variant(batch, num_ctas=num_ctas, min_chunk=min_chunk, **var)
+    o, lse = run_variant(batch, num_ctas=num_ctas, min_chunk=min_chunk, mode=mode, **var)
     e = assert_close(o, lse, o_ref, lse_ref, what)
     print(f"[ok] {what}: err_o={e[0]:.2e} err_lse={e[1]:.2e}", flush=True)
 
@@ -77,15 +78,39 @@ def test_window_hides_whole_steps_and_whole_chunks():
         check(b, f"window {W}", num_ctas=2 * 16, min_chunk=64, window_left=W)
 
 
+@pytest.mark.parametrize("dtype", [workloads.BF16, workloads.F16])
+@pytest.mark.parametrize("g", [1, 4])
+def test_causal_append_with_variants(dtype, g):
+    """Query tiles of several positions: every row has its own position, so bias and window differ from row to
+    row; chunks long enough for the scheduled loop run on the general path here; split chunks; a window that
+    hides whole tiles and, for the early rows of a split tile, whole chunks."""
+    qo = [70, 9, 130, 1, 64]
+    kv = [400, 9, 260, 300, 64]
+    b = workloads.make_batch("appvar", 440 + g, dtype, 2 * g, 2, 128, 16, qo, kv, True)
+    kw = dict(mode="append", num_ctas=2 * 4, min_chunk=1024)
+    check(b, "append, no variant in effect", logits_soft_cap=0.0, window_left=-1, **kw)
+    check(b, "append, soft cap", logits_soft_cap=3.0, **kw)
+    check(b, "append, alibi", alibi_slopes=slopes(2 * g), **kw)
+    check(b, "append, window", window_left=50, **kw)
+    check(b, "append, all", logits_soft_cap=5.0, window_left=33, alibi_slopes=slopes(2 * g), **kw)
+    check(b, "append, all, split chunks", logits_soft_cap=5.0, window_left=100, alibi_slopes=slopes(2 * g),
+          mode="append", num_ctas=2 * 16, min_chunk=64)
+
+
 def test_refused_where_not_built():
     import paper_2501_01005_amd as fi
     dummy = np.zeros(64, dtype=np.uint8)
     ok = dict(dtype=fi.FI_DTYPE_BF16, num_qo_heads=8, num_kv_heads=2, head_dim=128, page_size=16, mode=fi.FI_MODE_DECODE,
               num_ctas=8, max_batch=4, max_qo_tiles=4)
-    for bad in ({"mode": fi.FI_MODE_APPEND}, {"page_size": 8}):
+    # other page sizes; append mode without a causal plan; the rotary embedding in append mode
+    for bad, var in (({"page_size": 8}, dict(window_left=3)), ({"mode": fi.FI_MODE_APPEND}, dict(window_left=3)),
+                     ({"mode": fi.FI_MODE_APPEND, "causal_plan": True}, dict(rope_theta=1e4))):
+        causal_plan = bad.pop("causal_plan", False)
         h = fi.fi_create(**{**ok, **bad})
+        if causal_plan:
+            fi.fi_plan(h, np.array([0, 2], dtype=np.int32), np.array([0, 1], dtype=np.int32), np.array([5], dtype=np.int32), True)
         with pytest.raises(fi.Fi355Error) as e:
-            fi.fi_run_variant(h, dummy, dummy, dummy, (8, 8, 8), dummy, dummy, dummy, 1.0, dummy, dummy, window_left=3)
+            fi.fi_run_variant(h, dummy, dummy, dummy, (8, 8, 8), dummy, dummy, dummy, 1.0, dummy, dummy, **var)
         assert e.value.code == fi.FI_ERR_UNSUPPORTED
         fi.fi_destroy(h)
     h = fi.fi_create(**ok)
