@@ -124,18 +124,30 @@ def bench_shared_prefix(args) -> int:
     c = workloads.config5(small=args.small)
     dev_p, dev_s, dev_1 = DeviceBatch(c.prefix), DeviceBatch(c.suffix), DeviceBatch(c.single)
     wp = make_wrapper(c.prefix, "append", num_ctas=args.num_ctas, min_chunk=args.min_chunk)
-    ws = make_wrapper(c.suffix, "decode")
-    w1 = make_wrapper(c.single, "decode")
+    ws = make_wrapper(c.suffix, "decode", merge=args.merge)
+    w1 = make_wrapper(c.single, "decode", merge=args.merge)
     n, H, D = dev_p.q.shape[0], c.prefix.num_qo_heads, c.prefix.head_dim
     o_p = torch.empty((n, H, D), dtype=torch.float32, device="cuda:0"); l_p = torch.empty((n, H), dtype=torch.float32, device="cuda:0")
     o_s = torch.empty_like(o_p); l_s = torch.empty_like(l_p)
     o_1 = torch.empty_like(o_p); l_1 = torch.empty_like(l_p)
     stream = torch.cuda.current_stream().cuda_stream
 
+    side = torch.cuda.Stream() if args.graph else None  # default priority
+
     def composed(plan=True):
         if plan:
             wp.plan(c.prefix.qo_indptr, c.prefix.kv_indptr, c.prefix.last_page_len, causal=False)
             ws.plan(c.suffix.qo_indptr, c.suffix.kv_indptr, c.suffix.last_page_len, causal=False)
+        if side is not None:
+            # the two passes do not depend on each other: in the captured graph they are parallel branches
+            main = torch.cuda.current_stream()
+            side.wait_stream(main)
+            with torch.cuda.stream(side):
+                wp.run(dev_p.q, dev_p.k_pool, dev_p.v_pool, dev_p.kv_indices, c.prefix.sm_scale, o=o_p, lse=l_p)
+            ws.run(dev_s.q, dev_s.k_pool, dev_s.v_pool, dev_s.kv_indices, c.suffix.sm_scale, o=o_s, lse=l_s)
+            main.wait_stream(side)
+            fi.fi_merge_state_pair(o_p, l_p, o_s, l_s, n * H, D, o_p, l_p, main.cuda_stream)
+            return
         wp.run(dev_p.q, dev_p.k_pool, dev_p.v_pool, dev_p.kv_indices, c.prefix.sm_scale, o=o_p, lse=l_p)
         ws.run(dev_s.q, dev_s.k_pool, dev_s.v_pool, dev_s.kv_indices, c.suffix.sm_scale, o=o_s, lse=l_s)
         fi.fi_merge_state_pair(o_p, l_p, o_s, l_s, n * H, D, o_p, l_p, stream)
@@ -150,9 +162,18 @@ def bench_shared_prefix(args) -> int:
         for _ in range(args.warmup):
             fn(plan)
         torch.cuda.synchronize()
+        step = lambda: fn(plan)
+        if args.graph:
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph):
+                fn(False)
+            step = graph.replay
+            for _ in range(args.warmup):
+                step()
+            torch.cuda.synchronize()
         t0 = time.perf_counter()
         for _ in range(args.steps):
-            fn(plan)
+            step()
         torch.cuda.synchronize()
         return (time.perf_counter() - t0) / args.steps * 1e6
 
@@ -166,7 +187,9 @@ def bench_shared_prefix(args) -> int:
         "ms_per_step": us_comp * 1e-3, "us_per_batch": us_comp, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": c.prefix.dtype, "data": "synthetic",
         "config": {"workload": "c5_shared_prefix" + ("_small" if args.small else ""), "requests": n,
-                   "prefix_tokens": int(c.prefix.kv_lens()[0]), "step": "3 launches + merge" if args.no_plan else "2 plans + 3 launches + merge"},
+                   "prefix_tokens": int(c.prefix.kv_lens()[0]),
+                   "step": ("one captured graph, the two passes as parallel branches, replayed" if args.graph else
+                            "3 launches + merge" if args.no_plan else "2 plans + 3 launches + merge")},
         "frac_of_peak": bytes_comp / (us_comp * 1e-6) / 1e9 / HBM_PEAK_GBS,
         "composable_us": us_comp, "single_format_us": us_single, "speedup_vs_single_format": us_single / us_comp,
         "algorithmic_bytes_composable": bytes_comp, "algorithmic_bytes_single_format": bytes_single,
@@ -213,12 +236,21 @@ def main() -> int:
     ap.add_argument("--rope-theta", type=float, default=0.0,
                     help="> 0: decode with the rotary embedding fused into the kernel (fi_run_variant; the cache holds "
                          "unrotated keys, Sec. 4.4); 16-bit decode workloads only")
+    ap.add_argument("--graph", action="store_true",
+                    help="with --no-plan: capture fi_run (attention + merge launches) in a HIP graph once and time its "
+                         "replays; c5: the prefix and the suffix pass become parallel branches of the graph")
     ap.add_argument("--num-ctas", type=int, default=0)
     ap.add_argument("--min-chunk", type=int, default=0)
     ap.add_argument("--balance", type=int, default=0, help="fi_config.balance (0 = default of the mode)")
+    ap.add_argument("--merge", type=int, default=0,
+                    help="fi_config.merge: 1 = partial states folded by a second launch, 2 = inside the attention launch "
+                         "(decode), 0 = default")
     ap.add_argument("--alpha", type=int, default=0, help="fi_config.alpha (with --beta; 0, 0 = default)")
     ap.add_argument("--beta", type=int, default=0)
     args = ap.parse_args()
+    if args.graph and not args.no_plan:
+        print("bench.py: --graph times replays of a captured fi_run and needs --no-plan", file=sys.stderr)
+        return 2
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (no multi-GPU path exists); use --gpus 1", file=sys.stderr)
         return 2
@@ -264,7 +296,7 @@ def main() -> int:
         mode = "append" if args.workload == "c3" else "decode"
     dev = DeviceBatch(batch, kv_layout=args.kv_layout)
     w = make_wrapper(batch, mode, num_ctas=args.num_ctas, min_chunk=args.min_chunk, balance=args.balance,
-                     alpha=args.alpha, beta=args.beta)
+                     alpha=args.alpha, beta=args.beta, merge=args.merge)
     nnz = dev.q.shape[0]
     o = torch.empty((nnz, batch.num_qo_heads, batch.head_dim), dtype=torch.float32, device=dev.device)
     lse = torch.empty((nnz, batch.num_qo_heads), dtype=torch.float32, device=dev.device)
@@ -298,11 +330,28 @@ def main() -> int:
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for i in range(args.steps):
-        step(i)
-    torch.cuda.synchronize()
-    wall = time.perf_counter() - t0
+    if args.graph:
+        # one captured launch sequence, replayed; two more graphs carry the event pair around the attention kernel
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            step()
+        for _ in range(args.warmup):
+            graph.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(args.steps):
+            graph.replay()
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t0
+        for i in range(n_samples):  # kernel time: eager launches with events, outside the timed region
+            step(i * stride)
+        torch.cuda.synchronize()
+    else:
+        t0 = time.perf_counter()
+        for i in range(args.steps):
+            step(i)
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t0
     ms_per_step = wall * 1e3 / args.steps
     kern_ms = [ev.elapsed_ms(i) for i in range(n_samples)]
     kern_avg_ms = float(np.mean(kern_ms))
@@ -351,7 +400,8 @@ def main() -> int:
                    "num_kv_heads": batch.num_kv_heads, "head_dim": batch.head_dim, "page_size": batch.page_size, "page_order": args.page_order, "kv_layout": args.kv_layout,
                    "kv_dtype": batch.kv_dtype or batch.dtype,
                    **({"fused_rope_theta": args.rope_theta} if args.rope_theta > 0 else {}),
-                   "step": "fi_run only (plan reused)" if args.no_plan else "fi_plan + fi_run",
+                   "step": ("fi_run captured in a HIP graph, replayed (plan reused)" if args.graph else
+                            "fi_run only (plan reused)" if args.no_plan else "fi_plan + fi_run"),
                    "ctas_per_head": int(view["ctas_per_head"]), "l_kv_chunk": int(view["l_kv_chunk"]),
                    "n_work": int(view["n_work"]), "n_split_tiles": int(view["n_merge"])},
         "frac_of_peak": (value / HBM_PEAK_GBS) if mode == "decode" else (value / MFMA_PEAK_TFLOPS),

@@ -85,7 +85,13 @@ typedef struct fi_config {
                            out of the most loaded CTA while that lowers the maximum; in append mode
                            a tile of at most half the fused rows counts 64 % of its per-token cost
                            (it leaves wavefronts idle).  0: default = 1 for decode, 2 for append   */
-  int32_t reserved[2];  /* must be 0                                                           */
+  int32_t merge;        /* where the partial states of split tiles are contracted (Sec. 3.3.1: the paper
+                           fuses the contraction into the attention launch).  1: in a second launch.
+                           2: in the attention launch: the CTA that delivers a tile's last partial
+                           state folds them all (decode mode only; on MI355X slower than 1, because
+                           partial states cross between the XCDs' L2 caches through memory).
+                           0: default = 1                                                       */
+  int32_t reserved[1];  /* must be 0                                                           */
 } fi_config;
 
 /* Borrowed HOST views of the last plan, for bit-exact checks against a replica of
@@ -111,6 +117,8 @@ typedef struct fi_plan_arrays {
                                  non-causal: 0x3FFFFFFF                                        */
   const int32_t* w_out_slot;  /* [n_work] -1 = write the final output directly (App. D.2),
                                  else partial-output slot                                      */
+  const int32_t* w_merge;     /* [n_work] index of the item's tile in the m_* arrays, -1 if the
+                                 tile was not split                                            */
   const int32_t* m_q_row0;    /* [n_merge] first query row of the split tile                   */
   const int32_t* m_n_pos;     /* [n_merge]                                                     */
   const int32_t* m_slot_base; /* [n_merge] first slot; chunk c of the tile is slot base + c    */

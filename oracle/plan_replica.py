@@ -116,18 +116,22 @@ def plan_replica(qo_indptr: Sequence[int], kv_indptr: Sequence[int], last_page_l
 
     # -- output index map ------------------------------------------------------
     slot_base_of_tile = []
+    merge_index_of_tile = []
     merge = []        # per split tile: (q_row0, n_pos, slot_base, n_chunks)
     next_slot = 0
     for ti, (i, start, n_pos, kv_eff, diag0) in enumerate(tiles):
         if tile_chunks[ti] > 1:
             slot_base_of_tile.append(next_slot)
+            merge_index_of_tile.append(len(merge))
             merge.append((int(qo_indptr[i]) + start, n_pos, next_slot, tile_chunks[ti]))
             next_slot += tile_chunks[ti]
         else:
             slot_base_of_tile.append(-1)
+            merge_index_of_tile.append(-1)
     for w in work:
         base = slot_base_of_tile[w["tile"]]
         w["out_slot"] = -1 if base < 0 else base + w["chunk"]
+        w["merge"] = merge_index_of_tile[w["tile"]]     # the split tile this chunk belongs to, for whoever folds it
 
     # -- sort by descending length, assign to the least-loaded CTA ------------
     order = sorted(range(len(work)), key=lambda w: (-work[w]["kv_len"], w))
@@ -201,7 +205,7 @@ def plan_replica(qo_indptr: Sequence[int], kv_indptr: Sequence[int], last_page_l
         cta_indptr=cta_indptr,
         w_request=col("request"), w_q_row0=col("q_row0"), w_n_pos=col("n_pos"),
         w_kv_page0=col("kv_page0"), w_kv_start=col("kv_start"), w_kv_len=col("kv_len"),
-        w_diag0=col("diag0"), w_out_slot=col("out_slot"),
+        w_diag0=col("diag0"), w_out_slot=col("out_slot"), w_merge=col("merge"),
         m_q_row0=[m[0] for m in merge], m_n_pos=[m[1] for m in merge],
         m_slot_base=[m[2] for m in merge], m_n_chunks=[m[3] for m in merge],
         cta_cost=cta_cost, work_order=flat,

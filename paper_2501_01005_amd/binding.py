@@ -47,7 +47,7 @@ class Fi355Error(RuntimeError):
 class fi_config(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int32) for n in (
         "dtype", "num_qo_heads", "num_kv_heads", "head_dim", "page_size", "mode", "num_ctas", "max_batch",
-        "max_qo_tiles", "alpha", "beta", "min_chunk", "literal_lkv", "balance")] + [("reserved", ctypes.c_int32 * 2)]
+        "max_qo_tiles", "alpha", "beta", "min_chunk", "literal_lkv", "balance", "merge")] + [("reserved", ctypes.c_int32 * 1)]
 
 
 _I32P = ctypes.POINTER(ctypes.c_int32)
@@ -63,7 +63,7 @@ class fi_plan_arrays(ctypes.Structure):
         "t_pos", "group", "ctas_per_head", "l_kv_chunk", "n_work", "n_merge", "n_slots", "pad_")] + [
         (n, _I32P) for n in (
             "cta_indptr", "w_request", "w_q_row0", "w_n_pos", "w_kv_page0", "w_kv_start", "w_kv_len", "w_diag0",
-            "w_out_slot", "m_q_row0", "m_n_pos", "m_slot_base", "m_n_chunks")]
+            "w_out_slot", "w_merge", "m_q_row0", "m_n_pos", "m_slot_base", "m_n_chunks")]
 
 
 def _load() -> ctypes.CDLL:
@@ -168,7 +168,8 @@ def fi_plan_view(handle: int) -> dict:
         return np.ctypeslib.as_array(p, shape=(n,)).copy() if n > 0 else np.zeros(0, dtype=np.int32)
 
     out["cta_indptr"] = arr(pa.cta_indptr, pa.ctas_per_head + 1)
-    for k in ("w_request", "w_q_row0", "w_n_pos", "w_kv_page0", "w_kv_start", "w_kv_len", "w_diag0", "w_out_slot"):
+    for k in ("w_request", "w_q_row0", "w_n_pos", "w_kv_page0", "w_kv_start", "w_kv_len", "w_diag0", "w_out_slot",
+              "w_merge"):
         out[k] = arr(getattr(pa, k), pa.n_work)
     for k in ("m_q_row0", "m_n_pos", "m_slot_base", "m_n_chunks"):
         out[k] = arr(getattr(pa, k), pa.n_merge)
@@ -228,7 +229,7 @@ class PagedAttention:
     def __init__(self, *, dtype: str, num_qo_heads: int, num_kv_heads: int, head_dim: int = 128,
                  page_size: int = 16, mode: str = "decode", max_batch: int, max_qo_tiles: Optional[int] = None,
                  num_ctas: int = 0, min_chunk: int = 0, alpha: int = 0, beta: int = 0, literal_lkv: bool = False,
-                 balance: int = 0,
+                 balance: int = 0, merge: int = 0,
                  device: str = "cuda:0"):
         import torch
 
@@ -243,7 +244,8 @@ class PagedAttention:
                 num_kv_heads=num_kv_heads, head_dim=head_dim, page_size=page_size,
                 mode={"decode": FI_MODE_DECODE, "append": FI_MODE_APPEND}[mode], num_ctas=num_ctas,
                 max_batch=max_batch, max_qo_tiles=max_qo_tiles if max_qo_tiles is not None else max_batch,
-                alpha=alpha, beta=beta, min_chunk=min_chunk, literal_lkv=1 if literal_lkv else 0, balance=balance)
+                alpha=alpha, beta=beta, min_chunk=min_chunk, literal_lkv=1 if literal_lkv else 0, balance=balance,
+                merge=merge)
         self.num_qo_heads, self.num_kv_heads, self.head_dim = num_qo_heads, num_kv_heads, head_dim
         dev_bytes, pin_bytes = fi_workspace_bytes(self.handle)
         self.workspace = torch.empty(dev_bytes, dtype=torch.uint8, device=self.device)

@@ -58,6 +58,10 @@ int32_t fi_create(const fi_config* cfg, fi_handle** out) {
     return set_error(FI_ERR_INVALID_ARG, "fi_create: max_batch/max_qo_tiles must be > 0, the rest >= 0");
   if (cfg->balance < 0 || cfg->balance > 2)
     return set_error(FI_ERR_INVALID_ARG, "fi_create: balance must be 0 (default), 1 (as printed) or 2 (refined)");
+  if (cfg->merge < 0 || cfg->merge > 2)
+    return set_error(FI_ERR_INVALID_ARG, "fi_create: merge must be 0 (default), 1 (second launch) or 2 (in the attention launch)");
+  if (cfg->merge == 2 && cfg->mode != FI_MODE_DECODE)
+    return set_error(FI_ERR_UNSUPPORTED, "fi_create: the contraction inside the attention launch is built for decode mode");
   for (int r : cfg->reserved)
     if (r != 0) return set_error(FI_ERR_INVALID_ARG, "fi_create: reserved fields must be 0");
   if (cfg->head_dim != kHeadDim) return set_error(FI_ERR_UNSUPPORTED, "fi_create: only head_dim = 128 is built");
@@ -107,7 +111,7 @@ int32_t fi_create(const fi_config* cfg, fi_handle** out) {
   pp.literal_lkv = cfg->literal_lkv != 0;
   pp.max_batch = cfg->max_batch;
   pp.max_qo_tiles = cfg->max_qo_tiles;
-  h->layout.init(pp.ctas_per_head, cfg->max_qo_tiles, pp.t_pos, cfg->num_qo_heads, cfg->head_dim);
+  h->layout.init(pp.ctas_per_head, cfg->max_qo_tiles, pp.t_pos, cfg->num_qo_heads, cfg->num_kv_heads, cfg->head_dim);
   h->host_plan.assign(h->layout.plan_ints, 0);
   *out = h;
   return FI_OK;
@@ -195,6 +199,7 @@ int32_t fi_plan_view(const fi_handle* h, fi_plan_arrays* out) {
   out->w_kv_len = base + L.off_work[W_KV_LEN];
   out->w_diag0 = base + L.off_work[W_DIAG0];
   out->w_out_slot = base + L.off_work[W_OUT_SLOT];
+  out->w_merge = base + L.off_work[W_MERGE];
   out->m_q_row0 = base + L.off_merge[M_Q_ROW0];
   out->m_n_pos = base + L.off_merge[M_N_POS];
   out->m_slot_base = base + L.off_merge[M_SLOT_BASE];
@@ -253,6 +258,12 @@ int32_t run_impl(fi_handle* h, const void* q, const void* k_pool, const void* v_
   p.w_kv_len = plan + L.off_work[W_KV_LEN];
   p.w_diag0 = plan + L.off_work[W_DIAG0];
   p.w_out_slot = plan + L.off_work[W_OUT_SLOT];
+  const bool fused_merge = h->cfg.mode == FI_MODE_DECODE && h->cfg.merge == 2;
+  p.w_merge = fused_merge ? plan + L.off_work[W_MERGE] : nullptr;
+  p.m_slot_base = plan + L.off_merge[M_SLOT_BASE];
+  p.m_n_chunks = plan + L.off_merge[M_N_CHUNKS];
+  p.merge_counters = const_cast<int32_t*>(plan) + L.off_counters;
+  p.is_bf16 = h->cfg.dtype == FI_DTYPE_BF16 ? 1 : 0;
   p.kv_indices = kv_indices;
   p.q = q;
   p.k_pool = k_pool;
@@ -302,6 +313,7 @@ int32_t run_impl(fi_handle* h, const void* q, const void* k_pool, const void* v_
   if (e != hipSuccess) return hip_error("fi_run: attention launch", e);
   if (h->ev_after && (e = hipEventRecord(h->ev_after, s)) != hipSuccess) return hip_error("fi_run: hipEventRecord", e);
 
+  if (fused_merge) return FI_OK;  // the attention launch has folded the partial states itself
   MergeParams mp{};
   mp.header = plan + L.off_header;
   mp.m_q_row0 = plan + L.off_merge[M_Q_ROW0];

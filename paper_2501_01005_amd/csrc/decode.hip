@@ -39,6 +39,7 @@ typedef __attribute__((ext_vector_type(8))) _Float16 f16x8_t;
 typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
 typedef __attribute__((ext_vector_type(2))) _Float16 f16x2_t;
 typedef __attribute__((ext_vector_type(4))) float f32x4_t;
+typedef __attribute__((ext_vector_type(2))) float f32x2_t;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4_t;
 typedef __attribute__((ext_vector_type(2))) uint32_t u32x2_t;
 
@@ -534,11 +535,22 @@ decode_kernel(const RunParams p, const RopeArg<ROPE> rope) {
         dst_o = p.part_o + row * kHeadDim;
         dst_lse = p.part_lse + row;
       }
+      // a partial state that another CU's wavefront will fold inside this launch goes through the L2 to memory
+      const bool through = p.w_merge != nullptr && out_slot >= 0;
+      auto dev_store = [](float* ptr, float v) { __hip_atomic_store(ptr, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); };
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
         float* d = dst_o + 32 * c + 8 * i;
         const f32x4_t lo = {acc[0][i] * inv, acc[1][i] * inv, acc[2][i] * inv, acc[3][i] * inv};
         const f32x4_t hi = {acc[4][i] * inv, acc[5][i] * inv, acc[6][i] * inv, acc[7][i] * inv};
+        if (through) {
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            dev_store(d + e, lo[e]);
+            dev_store(d + 4 + e, hi[e]);
+          }
+          continue;
+        }
         *reinterpret_cast<f32x4_t*>(d) = lo;
         *reinterpret_cast<f32x4_t*>(d + 4) = hi;
         if (out_slot < 0 && p.o_cast != nullptr) {
@@ -549,7 +561,86 @@ decode_kernel(const RunParams p, const RopeArg<ROPE> rope) {
           *reinterpret_cast<u32x4_t*>(dc) = pk;
         }
       }
-      if (c == 0) *dst_lse = lse_val;
+      if (c == 0) {
+        if (through)
+          dev_store(dst_lse, lse_val);
+        else
+          *dst_lse = lse_val;
+      }
+    }
+
+    // ---- contraction inside the launch (Sec. 3.3.1): the wavefront that delivers a split tile's last partial
+    //      state folds all of them, in chunk order, whichever wavefront that is: the result does not depend on
+    //      the order of arrival.  The partial states come from other CUs, possibly behind another L2.  They were
+    //      written with device-scope stores (through the L2, see above), the arrival is counted after those stores
+    //      have completed, and they are read with device-scope loads: no cache is written back or invalidated as a
+    //      whole, which a release / acquire fence pair would do for every split work item. ----
+    if (p.w_merge != nullptr && out_slot >= 0) {
+      const int mi = as_const(p.w_merge)[w];
+      const int n_chunks = as_const(p.m_n_chunks)[mi];
+      const int slot_base = as_const(p.m_slot_base)[mi];
+      int32_t* counter = p.merge_counters + mi * p.num_kv_heads + kvh;
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // this wavefront's partial state has reached memory
+      int arrived = 0;
+      if (lane == 0) arrived = __hip_atomic_fetch_add(counter, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      arrived = __builtin_amdgcn_readfirstlane(arrived);
+      if (arrived == n_chunks - 1) {
+        // lanes: head hd = lane / lanes_per_head, floats [fl * sub, fl * (sub + 1)) of its 128, fl = 2 g
+        const int lanes_per_head = 64 / g;
+        const int hd = lane / lanes_per_head, sub = lane % lanes_per_head;
+        const int head = kvh * g + hd;
+        const int fl = 2 * g;
+        auto dev_load = [](const float* ptr) { return __hip_atomic_load(ptr, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); };
+        auto lse_of = [&](int ch) { return dev_load(p.part_lse + static_cast<int64_t>(slot_base + ch) * H + head); };
+        float mx = NEG_INF;
+        for (int ch = sub; ch < n_chunks; ch += lanes_per_head) mx = fmaxf(mx, lse_of(ch));
+        for (int off = lanes_per_head >> 1; off >= 1; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off));
+        float den = 0.f;
+        if (mx != NEG_INF)
+          for (int ch = sub; ch < n_chunks; ch += lanes_per_head)
+            den += __builtin_amdgcn_exp2f((lse_of(ch) - mx) * 1.4426950408889634f);
+        for (int off = lanes_per_head >> 1; off >= 1; off >>= 1) den += __shfl_xor(den, off);
+        float acc_o[8];  // fl <= 8 values
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc_o[e] = 0.f;
+        if (mx != NEG_INF) {
+          const float inv_den = 1.0f / den;
+          // chunks in order, four at a time so that their loads are in flight together
+          for (int ch0 = 0; ch0 < n_chunks; ch0 += 4) {
+            float wgt[4], val[4][8];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+              const int ch = min(ch0 + u, n_chunks - 1);
+              const float* src = p.part_o + (static_cast<int64_t>(slot_base + ch) * H + head) * kHeadDim + fl * sub;
+              wgt[u] = lse_of(ch);
+#pragma unroll
+              for (int e = 0; e < 8; ++e) val[u][e] = e < fl ? dev_load(src + e) : 0.f;
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+              const float wu = ch0 + u < n_chunks ? __builtin_amdgcn_exp2f((wgt[u] - mx) * 1.4426950408889634f) * inv_den : 0.f;
+              if (wu != 0.f) {  // a state with lse = -inf is the identity, whatever its o holds
+#pragma unroll
+                for (int e = 0; e < 8; ++e) acc_o[e] += wu * val[u][e];
+              }
+            }
+          }
+        }
+        const int64_t out_row = static_cast<int64_t>(q_row0) * H + head;
+        float* dst = p.o + out_row * kHeadDim + fl * sub;
+#pragma unroll
+        for (int e = 0; e < 8; e += 2)
+          if (e < fl) *reinterpret_cast<f32x2_t*>(dst + e) = f32x2_t{acc_o[e], acc_o[e + 1]};
+        if (sub == 0) p.lse[out_row] = mx != NEG_INF ? mx + __builtin_amdgcn_logf(den) * 0.6931471805599453f : NEG_INF;
+        if (p.o_cast != nullptr) {
+          uint32_t* dc = static_cast<uint32_t*>(p.o_cast) + (out_row * kHeadDim + fl * sub) / 2;
+#pragma unroll
+          for (int e = 0; e < 8; e += 2)
+            if (e < fl) dc[e / 2] = pack2<BF>(acc_o[e], acc_o[e + 1]);
+        }
+        // ready for the next launch with this plan (a new plan brings zeros anyway)
+        if (lane == 0) __hip_atomic_store(counter, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      }
     }
   }
 }

@@ -32,6 +32,12 @@ struct RunParams {
   int32_t num_qo_heads, num_kv_heads, group, t_pos;
   int32_t ctas_per_head;
   int32_t page_log2;  // log2 of the page size (tokens per page)
+  // contraction inside the decode launch (Sec. 3.3.1): w_merge != null switches it on
+  const int32_t* w_merge;      // per work item: index of its split tile in the m_* arrays, -1 if not split
+  const int32_t* m_slot_base;  // per split tile: first partial slot
+  const int32_t* m_n_chunks;   //                 number of partial states
+  int32_t* merge_counters;     // [split tile][kv head] partial states delivered so far; zero between launches
+  int32_t is_bf16;             // type of o_cast
   // attention variants (Sec. 3.2.3), read by the variant kernels only
   const int32_t* w_request;      // request of each work item
   const int32_t* kv_indptr;      // DEVICE copies of the plan inputs: a request's total KV length gives the

@@ -15,7 +15,7 @@ namespace fi355 {
 static size_t round_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 void WorkspaceLayout::init(int32_t ctas, int32_t max_qo_tiles, int32_t t_pos, int32_t num_qo_heads,
-                           int32_t head_dim) {
+                           int32_t num_kv_heads, int32_t head_dim) {
   ctas_per_head = ctas;
   // sum_t ceil(kv_eff(t) / L_kv) <= n_tiles + S / L_kv <= n_tiles + #CTA
   max_work = max_qo_tiles + ctas;
@@ -34,6 +34,8 @@ void WorkspaceLayout::init(int32_t ctas, int32_t max_qo_tiles, int32_t t_pos, in
     off_merge[a] = o;
     o += static_cast<size_t>(max_merge);
   }
+  off_counters = o;
+  o += static_cast<size_t>(max_merge) * num_kv_heads;
   plan_ints = o;
   plan_bytes = round_up(o * sizeof(int32_t), 256);
   const size_t rows = static_cast<size_t>(max_slots) * t_pos * num_qo_heads;
@@ -45,7 +47,7 @@ void WorkspaceLayout::init(int32_t ctas, int32_t max_qo_tiles, int32_t t_pos, in
 namespace {
 struct Tile {
   int32_t request, start, n_pos, kv_eff, diag0, q_row0, kv_page_base;
-  int32_t n_chunks, slot_base;
+  int32_t n_chunks, slot_base, merge_index;
 };
 struct Chunk {
   int32_t tile, kv_start, kv_len, in_tile;
@@ -133,6 +135,7 @@ int32_t make_plan(const PlanParams& pp, const WorkspaceLayout& L, const int32_t*
       tl.kv_page_base = kv_indptr[i];
       tl.n_chunks = 1;
       tl.slot_base = -1;
+      tl.merge_index = -1;
       tiles.push_back(tl);
       S += pp.literal_lkv ? l_kv : tl.kv_eff;
     }
@@ -154,7 +157,7 @@ int32_t make_plan(const PlanParams& pp, const WorkspaceLayout& L, const int32_t*
     if (tl.n_chunks > 1) {
       tl.slot_base = next_slot;
       next_slot += tl.n_chunks;
-      ++n_merge;
+      tl.merge_index = n_merge++;
     }
     for (int32_t c = 0; c < tl.n_chunks; ++c) {
       Chunk ch;
@@ -294,6 +297,7 @@ int32_t make_plan(const PlanParams& pp, const WorkspaceLayout& L, const int32_t*
     plan[L.off_work[W_KV_LEN] + k] = ch.kv_len;
     plan[L.off_work[W_DIAG0] + k] = tl.diag0;
     plan[L.off_work[W_OUT_SLOT] + k] = tl.slot_base < 0 ? -1 : tl.slot_base + ch.in_tile;
+    plan[L.off_work[W_MERGE] + k] = tl.merge_index;
   }
   int32_t mi = 0;
   for (const Tile& tl : tiles) {

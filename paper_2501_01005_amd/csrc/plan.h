@@ -10,11 +10,11 @@ namespace fi355 {
 
 constexpr int32_t kNoDiag = 0x3FFFFFFF;
 constexpr int kHeaderInts = 16;
-constexpr int kWorkArrays = 8;   // request, q_row0, n_pos, kv_page0, kv_start, kv_len, diag0, out_slot
+constexpr int kWorkArrays = 9;   // request, q_row0, n_pos, kv_page0, kv_start, kv_len, diag0, out_slot, merge
 constexpr int kMergeArrays = 4;  // q_row0, n_pos, slot_base, n_chunks
 
 // Indices of the per-work-item arrays inside the plan section.
-enum WorkField { W_REQUEST = 0, W_Q_ROW0, W_N_POS, W_KV_PAGE0, W_KV_START, W_KV_LEN, W_DIAG0, W_OUT_SLOT };
+enum WorkField { W_REQUEST = 0, W_Q_ROW0, W_N_POS, W_KV_PAGE0, W_KV_START, W_KV_LEN, W_DIAG0, W_OUT_SLOT, W_MERGE };
 enum MergeField { M_Q_ROW0 = 0, M_N_POS, M_SLOT_BASE, M_N_CHUNKS };
 enum HeaderField { H_N_WORK = 0, H_N_MERGE, H_N_SLOTS, H_L_KV, H_T_POS, H_CTAS };
 
@@ -29,13 +29,15 @@ struct WorkspaceLayout {
   size_t off_cta_indptr = 0;
   size_t off_work[kWorkArrays] = {};
   size_t off_merge[kMergeArrays] = {};
+  size_t off_counters = 0;    // max_merge * num_kv_heads arrival counters of the split tiles, zero in every plan
   size_t plan_ints = 0;       // ints in the plan section
   size_t plan_bytes = 0;      // rounded up to 256
   size_t off_part_lse = 0;    // byte offsets in the device workspace
   size_t off_part_o = 0;
   size_t total_bytes = 0;
 
-  void init(int32_t ctas, int32_t max_qo_tiles, int32_t t_pos, int32_t num_qo_heads, int32_t head_dim);
+  void init(int32_t ctas, int32_t max_qo_tiles, int32_t t_pos, int32_t num_qo_heads, int32_t num_kv_heads,
+            int32_t head_dim);
 };
 
 struct PlanParams {

@@ -103,3 +103,32 @@ def test_permuted_pool_gives_identical_bits():
     o1, l1 = run_gpu(b, "decode")
     o2, l2 = run_gpu(b2, "decode")
     assert np.array_equal(o1, o2) and np.array_equal(l1, l2)
+
+
+@pytest.mark.parametrize("dtype,g", [(workloads.BF16, 4), (workloads.F16, 1), (workloads.BF16, 2)])
+def test_contraction_inside_the_attention_launch(dtype, g):
+    """fi_config.merge = 2 (Sec. 3.3.1: one launch): the wavefront that delivers a split tile's last partial state
+    folds them all.  Many chunks per request, spread over all CUs; two runs with one plan (the arrival counters must
+    be back at zero), then a new plan; the rounded copy of the output is written by the folding wavefront too."""
+    import torch
+    b = workloads.make_batch("fold", 95 + g, dtype, 2 * g, 2, 128, 16, [1] * 5, [3000, 700, 40, 1, 0], False)
+    o_ref, lse_ref = oracle.run_batch(b)
+    dev = DeviceBatch(b)
+    w = make_wrapper(b, "decode", merge=2, min_chunk=32)
+    for rep in range(3):
+        print(f"[case] fold in launch: g={g} {dtype} rep={rep}", flush=True)
+        if rep != 1:
+            w.plan(b.qo_indptr, b.kv_indptr, b.last_page_len, causal=False)
+        o = torch.full((5, 2 * g, 128), float("nan"), dtype=torch.float32, device=dev.device)
+        lse = torch.full((5, 2 * g), float("nan"), dtype=torch.float32, device=dev.device)
+        oc = torch.zeros((5, 2 * g, 128), dtype=dev.q.dtype, device=dev.device)
+        w.run(dev.q, dev.k_pool, dev.v_pool, dev.kv_indices, b.sm_scale, o=o, lse=lse, o_cast=oc)
+        torch.cuda.synchronize()
+        e = assert_close(o.double().cpu().numpy(), lse.double().cpu().numpy(), o_ref, lse_ref, f"fold rep {rep}")
+        ulp = 2.0 ** -8 if dtype == workloads.BF16 else 2.0 ** -11
+        assert np.all(np.abs(oc.double().cpu().numpy() - o.double().cpu().numpy())
+                      <= np.maximum(np.abs(o.double().cpu().numpy()), 2.0 ** -14) * ulp)
+        print(f"[ok] fold rep {rep}: err_o={e[0]:.2e} err_lse={e[1]:.2e}", flush=True)
+    view = __import__("paper_2501_01005_amd").fi_plan_view(w.handle)
+    assert int(view["n_merge"]) >= 2 and max(view["m_n_chunks"]) > 16
+    w.close()

@@ -41,7 +41,7 @@ def test_hand_worked_examples(name):
                      alpha=fx.get("alpha", [1])[0], beta=fx.get("beta", [1])[0], min_chunk=ps)
     assert p["L_kv"] == fx["L_kv"][0]
     for key in ("cta_indptr", "w_request", "w_q_row0", "w_n_pos", "w_kv_start", "w_kv_len", "w_diag0",
-                "w_out_slot", "cta_cost", "m_q_row0", "m_n_pos", "m_slot_base", "m_n_chunks"):
+                "w_out_slot", "w_merge", "cta_cost", "m_q_row0", "m_n_pos", "m_slot_base", "m_n_chunks"):
         if key in fx:
             assert list(p[key]) == fx[key], key
 

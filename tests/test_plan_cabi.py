@@ -12,7 +12,7 @@ from oracle.plan_replica import plan_replica
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 PLAN_KEYS = ("cta_indptr", "w_request", "w_q_row0", "w_n_pos", "w_kv_page0", "w_kv_start", "w_kv_len", "w_diag0",
-             "w_out_slot", "m_q_row0", "m_n_pos", "m_slot_base", "m_n_chunks")
+             "w_out_slot", "w_merge", "m_q_row0", "m_n_pos", "m_slot_base", "m_n_chunks")
 
 
 def test_library_exports_every_declared_symbol():
@@ -165,6 +165,8 @@ def test_argument_errors():
     expect(fi.FI_ERR_NOT_PLANNED, fi.fi_run_kv8, h, dummy, dummy, dummy, (8, 8, 8), dummy, 1.0, 1.0, 1.0, dummy, dummy)
     expect(fi.FI_ERR_INVALID_ARG, fi.fi_run_kv8, h, dummy, dummy, dummy, (8, 8, 8), dummy, 1.0, 0.0, 1.0, dummy, dummy)
     expect(fi.FI_ERR_INVALID_ARG, fi.fi_create, **{**ok, "balance": 3})
+    expect(fi.FI_ERR_INVALID_ARG, fi.fi_create, **{**ok, "merge": 3})
+    expect(fi.FI_ERR_UNSUPPORTED, fi.fi_create, **{**ok, "merge": 2, "mode": fi.FI_MODE_APPEND})   # in-launch contraction: decode only
     ha = fi.fi_create(**{**ok, "mode": fi.FI_MODE_APPEND})
     expect(fi.FI_ERR_UNSUPPORTED, fi.fi_run_kv8, ha, dummy, dummy, dummy, (8, 8, 8), dummy, 1.0, 1.0, 1.0, dummy, dummy)
     fi.fi_destroy(ha)
