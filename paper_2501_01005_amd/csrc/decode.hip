@@ -114,8 +114,9 @@ struct KvTile {
 // ROPE (with VAR): rotary position embedding as query and key transform (Sec. 3.2.3; the fused-RoPE kernels of
 // Sec. 4.4): key t of a request is rotated by its position t, the query by pos, pairing components (d, d + 64).
 // The rotated values are formed in fp32 from the K operands as they come back from LDS (a lane holds both
-// components of a pair there).  With bf16 inputs they are split into a bf16 head and remainder, as P is, and the
-// first product takes three instructions per operand pair (head x head, remainder x head, head x remainder).
+// components of a pair there) and enter the first product as fp16, also when the inputs are bf16: a rotated value
+// rounded to bf16 would cost 2^-9 of relative accuracy per operand (a bf16 head + remainder pair, as P uses, costs
+// 20 % of the kernel's time instead).  Rotated magnitudes above 65504 saturate, below 2^-14 lose relative accuracy.
 struct NoRope {};
 template <bool ROPE>
 using RopeArg = typename std::conditional<ROPE, RopeTable, NoRope>::type;
@@ -131,10 +132,10 @@ __device__ __forceinline__ float elem16(uint32_t word, int odd) {
 }
 
 // (x, y) = the lane's eight components of the blocks d and d + 64 of one row; cs / sn = cosine / sine of the
-// row's angle for each of the eight pairs.  Rotated values -> MFMA operands: head, and for bf16 the remainder.
+// row's angle for each of the eight pairs.  Rotated values -> fp16 MFMA operands.
 template <bool BF>
 __device__ __forceinline__ void rotate_blocks(const u32x4_t x, const u32x4_t y, const float* cs, const float* sn,
-                                              u32x4_t* xh, u32x4_t* yh, u32x4_t* xl, u32x4_t* yl) {
+                                              u32x4_t* xh, u32x4_t* yh) {
   float xr[8], yr[8];
 #pragma unroll
   for (int e = 0; e < 8; ++e) {
@@ -142,18 +143,8 @@ __device__ __forceinline__ void rotate_blocks(const u32x4_t x, const u32x4_t y, 
     xr[e] = xe * cs[e] - ye * sn[e];
     yr[e] = ye * cs[e] + xe * sn[e];
   }
-  *xh = u32x4_t{pack2<BF>(xr[0], xr[1]), pack2<BF>(xr[2], xr[3]), pack2<BF>(xr[4], xr[5]), pack2<BF>(xr[6], xr[7])};
-  *yh = u32x4_t{pack2<BF>(yr[0], yr[1]), pack2<BF>(yr[2], yr[3]), pack2<BF>(yr[4], yr[5]), pack2<BF>(yr[6], yr[7])};
-  if constexpr (BF) {
-    // remainder = value - head; the head's value is its 16 bits in the upper half of a float
-#pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      xr[e] -= elem16<BF>((*xh)[e >> 1], e & 1);
-      yr[e] -= elem16<BF>((*yh)[e >> 1], e & 1);
-    }
-    *xl = u32x4_t{pack2<BF>(xr[0], xr[1]), pack2<BF>(xr[2], xr[3]), pack2<BF>(xr[4], xr[5]), pack2<BF>(xr[6], xr[7])};
-    *yl = u32x4_t{pack2<BF>(yr[0], yr[1]), pack2<BF>(yr[2], yr[3]), pack2<BF>(yr[4], yr[5]), pack2<BF>(yr[6], yr[7])};
-  }
+  *xh = u32x4_t{pack2<false>(xr[0], xr[1]), pack2<false>(xr[2], xr[3]), pack2<false>(xr[4], xr[5]), pack2<false>(xr[6], xr[7])};
+  *yh = u32x4_t{pack2<false>(yr[0], yr[1]), pack2<false>(yr[2], yr[3]), pack2<false>(yr[4], yr[5]), pack2<false>(yr[6], yr[7])};
 }
 
 // (The rotary variant runs one wavefront per SIMD with up to 512 registers: at two it spills 130 registers into
@@ -264,20 +255,15 @@ decode_kernel(const RunParams p, const RopeArg<ROPE> rope) {
       for (int s = 0; s < 4; ++s) qreg[s] = u32x4_t{0u, 0u, 0u, 0u};
     }
 
-    u32x4_t qlo[ROPE && BF ? 4 : 1];  // bf16: remainder of the rotated query
-    if constexpr (ROPE) {
+    if constexpr (ROPE) {  // the query at its position, as fp16
 #pragma unroll
       for (int sp = 0; sp < 2; ++sp) {
         float cs[8], sn[8];
         angles(pos, sp, cs, sn);
-        u32x4_t xh, yh, xl, yl;
-        rotate_blocks<BF>(qreg[sp], qreg[sp + 2], cs, sn, &xh, &yh, &xl, &yl);
+        u32x4_t xh, yh;
+        rotate_blocks<BF>(qreg[sp], qreg[sp + 2], cs, sn, &xh, &yh);
         qreg[sp] = xh;
         qreg[sp + 2] = yh;
-        if constexpr (BF) {
-          qlo[sp] = xl;
-          qlo[sp + 2] = yl;
-        }
       }
     }
 
@@ -356,16 +342,10 @@ decode_kernel(const RunParams p, const RopeArg<ROPE> rope) {
             angles(tok_abs0 + 32 * t + 16 * pg + m, sp, cs, sn);  // this lane's K row is token m of the page
             const u32x4_t x = k_lds[pg * 256 + m * 16 + (((4 * sp + c) ^ m) & 15)];
             const u32x4_t y = k_lds[pg * 256 + m * 16 + (((4 * (sp + 2) + c) ^ m) & 15)];
-            u32x4_t xh, yh, xl, yl;
-            rotate_blocks<BF>(x, y, cs, sn, &xh, &yh, &xl, &yl);
-            sacc = mfma_16x16x32<BF>(xh, qreg[sp], sacc);
-            sacc = mfma_16x16x32<BF>(yh, qreg[sp + 2], sacc);
-            if constexpr (BF) {
-              sacc = mfma_16x16x32<BF>(xl, qreg[sp], sacc);
-              sacc = mfma_16x16x32<BF>(yl, qreg[sp + 2], sacc);
-              sacc = mfma_16x16x32<BF>(xh, qlo[sp], sacc);
-              sacc = mfma_16x16x32<BF>(yh, qlo[sp + 2], sacc);
-            }
+            u32x4_t xh, yh;
+            rotate_blocks<BF>(x, y, cs, sn, &xh, &yh);
+            sacc = mfma_16x16x32<false>(xh, qreg[sp], sacc);
+            sacc = mfma_16x16x32<false>(yh, qreg[sp + 2], sacc);
           }
           if (pg == 0) s0 = sacc; else s1 = sacc;
         }
