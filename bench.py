@@ -236,6 +236,11 @@ def main() -> int:
     ap.add_argument("--rope-theta", type=float, default=0.0,
                     help="> 0: decode with the rotary embedding fused into the kernel (fi_run_variant; the cache holds "
                          "unrotated keys, Sec. 4.4); 16-bit decode workloads only")
+    ap.add_argument("--window-left", type=int, default=-1,
+                    help=">= 0: decode with a sliding window of that many tokens behind the query (fi_run_variant)")
+    ap.add_argument("--plan-window", action="store_true",
+                    help="with --window-left: the planner knows the window (fi_config.plan_window) and leaves the hidden "
+                         "keys out of the work items")
     ap.add_argument("--graph", action="store_true",
                     help="with --no-plan: capture fi_run (attention + merge launches) in a HIP graph once and time its "
                          "replays; c5: the prefix and the suffix pass become parallel branches of the graph")
@@ -296,20 +301,22 @@ def main() -> int:
         mode = "append" if args.workload == "c3" else "decode"
     dev = DeviceBatch(batch, kv_layout=args.kv_layout)
     w = make_wrapper(batch, mode, num_ctas=args.num_ctas, min_chunk=args.min_chunk, balance=args.balance,
-                     alpha=args.alpha, beta=args.beta, merge=args.merge)
+                     alpha=args.alpha, beta=args.beta, merge=args.merge,
+                     plan_window=args.window_left + 1 if args.plan_window and args.window_left >= 0 else 0)
     nnz = dev.q.shape[0]
     o = torch.empty((nnz, batch.num_qo_heads, batch.head_dim), dtype=torch.float32, device=dev.device)
     lse = torch.empty((nnz, batch.num_qo_heads), dtype=torch.float32, device=dev.device)
 
     run_kw = dict(dev.scales)
-    if args.rope_theta > 0:
+    if args.rope_theta > 0 or args.window_left >= 0:
         if mode != "decode" or batch.kv_dtype or args.page_size != 16:
-            print("bench.py: --rope-theta is for the 16-bit decode workloads with page size 16", file=sys.stderr)
+            print("bench.py: --rope-theta / --window-left are for the 16-bit decode workloads with page size 16",
+                  file=sys.stderr)
             return 2
         run_kw["variant"] = dict(
             kv_indptr=torch.from_numpy(np.ascontiguousarray(batch.kv_indptr, dtype=np.int32)).to(dev.device),
             last_page_len=torch.from_numpy(np.ascontiguousarray(batch.last_page_len, dtype=np.int32)).to(dev.device),
-            rope_theta=args.rope_theta)
+            rope_theta=args.rope_theta, window_left=args.window_left)
 
     stride = max(1, args.event_stride)
     n_samples = (args.steps + stride - 1) // stride
@@ -400,6 +407,7 @@ def main() -> int:
                    "num_kv_heads": batch.num_kv_heads, "head_dim": batch.head_dim, "page_size": batch.page_size, "page_order": args.page_order, "kv_layout": args.kv_layout,
                    "kv_dtype": batch.kv_dtype or batch.dtype,
                    **({"fused_rope_theta": args.rope_theta} if args.rope_theta > 0 else {}),
+                   **({"window_left": args.window_left, "planned": bool(args.plan_window)} if args.window_left >= 0 else {}),
                    "step": ("fi_run captured in a HIP graph, replayed (plan reused)" if args.graph else
                             "fi_run only (plan reused)" if args.no_plan else "fi_plan + fi_run"),
                    "ctas_per_head": int(view["ctas_per_head"]), "l_kv_chunk": int(view["l_kv_chunk"]),

@@ -91,7 +91,12 @@ typedef struct fi_config {
                            state folds them all (decode mode only; on MI355X slower than 1, because
                            partial states cross between the XCDs' L2 caches through memory).
                            0: default = 1                                                       */
-  int32_t reserved[1];  /* must be 0                                                           */
+  int32_t plan_window;  /* sliding-window attention: 0 = every key a query may see is planned and read;
+                           n > 0: a query at position pos sees keys pos - (n - 1) .. pos only, and fi_plan
+                           leaves the keys before a tile's window (rounded down to a page) out of its
+                           work items, so that the time follows the window, not the context length.
+                           Such a plan must be run with fi_run_variant and 0 <= window_left <= n - 1
+                           (the kernel masks token by token; FI_ERR_INVALID_ARG otherwise)        */
 } fi_config;
 
 /* Borrowed HOST views of the last plan, for bit-exact checks against a replica of
@@ -195,7 +200,8 @@ typedef struct fi_variant {
   float rope_scale; /* position divisor of the rotary embedding; 0 = 1 */
 } fi_variant;
 
-/* fi_run with a variant.  kv_indptr [batch+1] and last_page_len [batch] are DEVICE copies of the arrays
+/* fi_run with a variant.  (A window alone only masks: to skip the hidden keys, create the handle with
+ * fi_config.plan_window.)  kv_indptr [batch+1] and last_page_len [batch] are DEVICE copies of the arrays
  * the batch was planned with (the decode kernel derives pos from them).  Built for 16-bit pools and
  * page_size 16; decode mode: every field of fi_variant; append mode: soft cap, ALiBi and window for
  * batches planned with causal = 1 (all work items then take the kernel's general path), no rotary

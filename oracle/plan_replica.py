@@ -64,7 +64,7 @@ def plan_replica(qo_indptr: Sequence[int], kv_indptr: Sequence[int], last_page_l
                  *, page_size: int, t_pos: int, group: int, num_ctas: int, causal: bool,
                  alpha: int = 1, beta: int = 1, min_chunk: int | None = None,
                  literal_lkv: bool = False, refine: bool = False, light_rows: int = 0,
-                 light_pct: int = 100, kv_quantum: int = 1) -> Dict[str, object]:
+                 light_pct: int = 100, kv_quantum: int = 1, plan_window: int = 0) -> Dict[str, object]:
     B = len(last_page_len)
     if min_chunk is None:
         min_chunk = page_size
@@ -92,8 +92,15 @@ def plan_replica(qo_indptr: Sequence[int], kv_indptr: Sequence[int], last_page_l
             else:
                 kv_eff = l_kv[i]
                 diag0 = NO_DIAG
-            tiles.append((i, start, end - start, kv_eff, diag0))
-            S += l_kv[i] if literal_lkv else kv_eff
+            # sliding window (not in the paper's algorithm): with plan_window = W + 1 > 0 a query at position pos sees
+            # keys pos - W .. pos only; the tile's first row sits at l_kv - l_qo + start, so no row of the tile sees
+            # a key before kv_begin, which is rounded down to a page boundary (chunks start on pages)
+            kv_begin = 0
+            if plan_window > 0:
+                kv_begin = max(0, l_kv[i] - l_qo[i] + start - (plan_window - 1))
+                kv_begin = min(kv_begin, kv_eff) // page_size * page_size
+            tiles.append((i, start, end - start, kv_eff, diag0, kv_begin))
+            S += l_kv[i] if literal_lkv else kv_eff - kv_begin
 
     # -- maximum chunk size --------------------------------------------------
     L_kv = -(-S // num_ctas)
@@ -103,11 +110,11 @@ def plan_replica(qo_indptr: Sequence[int], kv_indptr: Sequence[int], last_page_l
     # -- split ---------------------------------------------------------------
     work = []         # per w: dict
     tile_chunks = []  # per tile: number of chunks
-    for (i, start, n_pos, kv_eff, diag0) in tiles:
-        n_chunks = max(1, -(-kv_eff // L_kv))
+    for (i, start, n_pos, kv_eff, diag0, kv_begin) in tiles:
+        n_chunks = max(1, -(-(kv_eff - kv_begin) // L_kv))
         tile_chunks.append(n_chunks)
         for c in range(n_chunks):
-            lo = c * L_kv
+            lo = kv_begin + c * L_kv
             hi = min(lo + L_kv, kv_eff)
             work.append(dict(request=i, q_row0=int(qo_indptr[i]) + start, n_pos=n_pos,
                              kv_start=lo, kv_len=hi - lo,
@@ -119,7 +126,7 @@ def plan_replica(qo_indptr: Sequence[int], kv_indptr: Sequence[int], last_page_l
     merge_index_of_tile = []
     merge = []        # per split tile: (q_row0, n_pos, slot_base, n_chunks)
     next_slot = 0
-    for ti, (i, start, n_pos, kv_eff, diag0) in enumerate(tiles):
+    for ti, (i, start, n_pos, kv_eff, diag0, kv_begin) in enumerate(tiles):
         if tile_chunks[ti] > 1:
             slot_base_of_tile.append(next_slot)
             merge_index_of_tile.append(len(merge))

@@ -62,8 +62,7 @@ int32_t fi_create(const fi_config* cfg, fi_handle** out) {
     return set_error(FI_ERR_INVALID_ARG, "fi_create: merge must be 0 (default), 1 (second launch) or 2 (in the attention launch)");
   if (cfg->merge == 2 && cfg->mode != FI_MODE_DECODE)
     return set_error(FI_ERR_UNSUPPORTED, "fi_create: the contraction inside the attention launch is built for decode mode");
-  for (int r : cfg->reserved)
-    if (r != 0) return set_error(FI_ERR_INVALID_ARG, "fi_create: reserved fields must be 0");
+  if (cfg->plan_window < 0) return set_error(FI_ERR_INVALID_ARG, "fi_create: plan_window must be >= 0");
   if (cfg->head_dim != kHeadDim) return set_error(FI_ERR_UNSUPPORTED, "fi_create: only head_dim = 128 is built");
   if (cfg->page_size < 1 || cfg->page_size > 64 || (cfg->page_size & (cfg->page_size - 1)) != 0)
     return set_error(FI_ERR_UNSUPPORTED, "fi_create: page_size must be a power of two between 1 and 64");
@@ -97,6 +96,7 @@ int32_t fi_create(const fi_config* cfg, fi_handle** out) {
   // items are few and long (C3: 4.8 per CTA): there the refined assignment is the default, with the cost
   // measured on this kernel: 19 800 cycles per item + 48 per token, 64 % of that per token for a tile of at most
   // 128 fused rows (at most one live wavefront per SIMD), i.e. alpha : beta = 8 : 5 with T_q = 256.
+  pp.plan_window = cfg->plan_window;
   pp.refine = cfg->balance == 2 || (cfg->balance == 0 && cfg->mode == FI_MODE_APPEND);
   const bool default_cost = cfg->alpha == 0 && cfg->beta == 0;
   pp.alpha = default_cost ? (pp.refine && cfg->mode == FI_MODE_APPEND ? 8 : 1) : cfg->alpha;
@@ -230,6 +230,9 @@ int32_t run_impl(fi_handle* h, const void* q, const void* k_pool, const void* v_
         std::isinf(variant->rope_scale))
       return set_error(FI_ERR_INVALID_ARG, "fi_run_variant: rope_theta and rope_scale must be finite and >= 0");
   }
+  if (h->pp.plan_window > 0 && !(variant && variant->window_left >= 0 && variant->window_left < h->pp.plan_window))
+    return set_error(FI_ERR_INVALID_ARG, "fi_run: the handle plans a sliding window of " + std::to_string(h->pp.plan_window) +
+                                             " keys: run it with fi_run_variant and 0 <= window_left <= plan_window - 1");
   if (kv8 && h->cfg.mode != FI_MODE_DECODE)
     return set_error(FI_ERR_UNSUPPORTED, "fi_run_kv8: the 8-bit KV cache is built for decode mode only");
   if (kv8 && !(k_scale > 0.f && v_scale > 0.f))

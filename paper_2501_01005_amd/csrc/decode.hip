@@ -110,7 +110,8 @@ struct KvTile {
 // BSR cache is a free parameter); every lane then looks up the page of each token row it loads.
 // VAR: attention variants (Sec. 3.2.3, logits transform and logits mask) on the scaled logits, in this order:
 // soft cap c * tanh(s / c), ALiBi bias slope[head] * (t - pos), sliding window (tokens t < pos - window hidden);
-// pos = l_kv - 1 is the absolute position of the request's query.  A step may then hold no visible token.
+// pos = l_kv - 1 is the absolute position of the request's query.  A step may then hold no visible token; steps
+// wholly before the window are skipped without being read.
 // ROPE (with VAR): rotary position embedding as query and key transform (Sec. 3.2.3; the fused-RoPE kernels of
 // Sec. 4.4): key t of a request is rotated by its position t, the query by pos, pairing components (d, d + 64).
 // The rotated values are formed in fp32 from the K operands as they come back from LDS (a lane holds both
@@ -461,9 +462,15 @@ decode_kernel(const RunParams p, const RopeArg<ROPE> rope) {
 
     if constexpr (!KV8) {
       Tile TA, TB;
-      if (n_tiles > 0) load_tile(TA, 0);
-      if (n_tiles > 1) load_tile(TB, 1);
-      for (int t = 0; t < n_tiles; t += 2) {
+      // a sliding window hides the chunk's tokens before local index -window_left - tok_minus_pos: the steps that
+      // lie wholly before it are not even loaded (a chunk wholly outside the window yields the empty state)
+      int t_first = 0;
+      if constexpr (VAR) {
+        if (p.window_left >= 0) t_first = min(max(0, -p.window_left - tok_minus_pos) >> 5, n_tiles) & ~1;
+      }
+      if (n_tiles > t_first) load_tile(TA, t_first);
+      if (n_tiles > t_first + 1) load_tile(TB, t_first + 1);
+      for (int t = t_first; t < n_tiles; t += 2) {
         compute_tile(TA, t);
         if (t + 2 < n_tiles) load_tile(TA, t + 2);
         if (t + 1 < n_tiles) {

@@ -46,7 +46,7 @@ void WorkspaceLayout::init(int32_t ctas, int32_t max_qo_tiles, int32_t t_pos, in
 
 namespace {
 struct Tile {
-  int32_t request, start, n_pos, kv_eff, diag0, q_row0, kv_page_base;
+  int32_t request, start, n_pos, kv_eff, kv_begin, diag0, q_row0, kv_page_base;
   int32_t n_chunks, slot_base, merge_index;
 };
 struct Chunk {
@@ -131,13 +131,18 @@ int32_t make_plan(const PlanParams& pp, const WorkspaceLayout& L, const int32_t*
         tl.kv_eff = static_cast<int32_t>(l_kv);
         tl.diag0 = kNoDiag;
       }
+      tl.kv_begin = 0;
+      if (pp.plan_window > 0) {
+        const int64_t first_seen = std::max<int64_t>(0, l_kv - l_qo + tl.start - (pp.plan_window - 1));
+        tl.kv_begin = static_cast<int32_t>(std::min<int64_t>(first_seen, tl.kv_eff) / ps * ps);
+      }
       tl.q_row0 = qo_indptr[i] + tl.start;
       tl.kv_page_base = kv_indptr[i];
       tl.n_chunks = 1;
       tl.slot_base = -1;
       tl.merge_index = -1;
       tiles.push_back(tl);
-      S += pp.literal_lkv ? l_kv : tl.kv_eff;
+      S += pp.literal_lkv ? l_kv : tl.kv_eff - tl.kv_begin;
     }
   }
 
@@ -153,7 +158,7 @@ int32_t make_plan(const PlanParams& pp, const WorkspaceLayout& L, const int32_t*
   int32_t next_slot = 0, n_merge = 0;
   for (size_t ti = 0; ti < tiles.size(); ++ti) {
     Tile& tl = tiles[ti];
-    tl.n_chunks = static_cast<int32_t>(std::max<int64_t>(1, (tl.kv_eff + Lkv - 1) / Lkv));
+    tl.n_chunks = static_cast<int32_t>(std::max<int64_t>(1, (tl.kv_eff - tl.kv_begin + Lkv - 1) / Lkv));
     if (tl.n_chunks > 1) {
       tl.slot_base = next_slot;
       next_slot += tl.n_chunks;
@@ -162,7 +167,7 @@ int32_t make_plan(const PlanParams& pp, const WorkspaceLayout& L, const int32_t*
     for (int32_t c = 0; c < tl.n_chunks; ++c) {
       Chunk ch;
       ch.tile = static_cast<int32_t>(ti);
-      ch.kv_start = static_cast<int32_t>(c * Lkv);
+      ch.kv_start = static_cast<int32_t>(tl.kv_begin + c * Lkv);
       ch.kv_len = static_cast<int32_t>(std::min<int64_t>(ch.kv_start + Lkv, tl.kv_eff) - ch.kv_start);
       ch.in_tile = c;
       chunks.push_back(ch);

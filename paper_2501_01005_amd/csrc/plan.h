@@ -60,6 +60,9 @@ struct PlanParams {
   int32_t kv_quantum = 1;
   int32_t max_batch = 0;
   int32_t max_qo_tiles = 0;
+  // Sliding window: > 0 = W + 1, a query at position pos sees keys pos - W .. pos only, and the keys that no row
+  // of a tile sees (before its first row's window, rounded down to a page) are left out of the tile's KV range.
+  int32_t plan_window = 0;
 };
 
 // Runs the partition and writes the plan section (header, queues, work items, merge list)

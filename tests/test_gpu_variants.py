@@ -12,10 +12,10 @@ from gpu_util import DeviceBatch, assert_close, make_wrapper
 pytestmark = pytest.mark.gpu
 
 
-def run_variant(batch, num_ctas=0, min_chunk=0, mode="decode", **var):
+def run_variant(batch, num_ctas=0, min_chunk=0, mode="decode", plan_window=0, **var):
     import torch
     dev = DeviceBatch(batch)
-    w = make_wrapper(batch, mode, num_ctas=num_ctas, min_chunk=min_chunk)
+    w = make_wrapper(batch, mode, num_ctas=num_ctas, min_chunk=min_chunk, plan_window=plan_window)
     w.plan(batch.qo_indptr, batch.kv_indptr, batch.last_page_len, causal=batch.causal)
     nnz = dev.q.shape[0]
     o = torch.full((nnz, batch.num_qo_heads, batch.head_dim), float("nan"), dtype=torch.float32, device=dev.device)
@@ -31,12 +31,12 @@ def run_variant(batch, num_ctas=0, min_chunk=0, mode="decode", **var):
     return o.double().cpu().numpy(), lse.double().cpu().numpy()
 
 
-def check(batch, what, num_ctas=0, min_chunk=0, mode="decode", **var):
+def check(batch, what, num_ctas=0, min_chunk=0, mode="decode", plan_window=0, **var):
     print(f"[case] {what}: {batch.name} {mode} dtype={batch.dtype} heads={batch.num_qo_heads}/{batch.num_kv_heads} "
           f"qo={batch.qo_lens()[:8].tolist()} kv={batch.kv_lens()[:8].tolist()} "
           f"variant={ {k: (v if np.isscalar(v) else 'array') for k, v in var.items()} }", flush=True)
     o_ref, lse_ref = oracle.run_batch(batch, **var)
-    o, lse = run_variant(batch, num_ctas=num_ctas, min_chunk=min_chunk, mode=mode, **var)
+    o, lse = run_variant(batch, num_ctas=num_ctas, min_chunk=min_chunk, mode=mode, plan_window=plan_window, **var)
     e = assert_close(o, lse, o_ref, lse_ref, what)
     print(f"[ok] {what}: err_o={e[0]:.2e} err_lse={e[1]:.2e}", flush=True)
 
@@ -95,6 +95,26 @@ def test_causal_append_with_variants(dtype, g):
     check(b, "append, all", logits_soft_cap=5.0, window_left=33, alibi_slopes=slopes(2 * g), **kw)
     check(b, "append, all, split chunks", logits_soft_cap=5.0, window_left=100, alibi_slopes=slopes(2 * g),
           mode="append", num_ctas=2 * 16, min_chunk=64)
+
+
+@pytest.mark.parametrize("mode", ["decode", "append"])
+def test_window_known_to_the_planner(mode):
+    """fi_config.plan_window: the keys before a tile's window are not in its work items at all (chunks start in
+    the middle of a request), the kernel masks the rest token by token.  Windows narrower than the plan's are
+    allowed; rotary embedding on top (decode): positions stay absolute."""
+    if mode == "decode":
+        b = workloads.make_batch("pw", 450, workloads.BF16, 8, 2, 128, 16, [1] * 5, [3000, 700, 40, 1, 0], False)
+        kw = dict(num_ctas=2 * 16, min_chunk=32)
+    else:
+        b = workloads.make_batch("pw", 451, workloads.F16, 8, 2, 128, 16, [70, 9, 130, 1, 64], [900, 9, 260, 300, 64], True)
+        kw = dict(mode="append", num_ctas=2 * 4, min_chunk=64)
+    for W in (0, 5, 31, 100, 1000, 5000):
+        check(b, f"{mode}, planned window {W}", plan_window=W + 1, window_left=W, **kw)
+    check(b, f"{mode}, planned window 200, run with 77", plan_window=201, window_left=77, **kw)
+    check(b, f"{mode}, planned window 100 + cap + alibi", plan_window=101, window_left=100, logits_soft_cap=4.0,
+          alibi_slopes=slopes(8), **kw)
+    if mode == "decode":
+        check(b, "decode, planned window 100 + rope", plan_window=101, window_left=100, rope_theta=1e4, **kw)
 
 
 def test_refused_where_not_built():

@@ -237,3 +237,39 @@ def test_empty_and_degenerate_inputs():
     # a request with no pages still gets one empty work item (its rows must be written)
     p = plan_replica([0, 1], [0, 0], [0], page_size=16, t_pos=1, group=1, num_ctas=2, causal=False)
     assert p["n_work"] == 1 and p["w_kv_len"] == [0] and p["w_out_slot"] == [-1]
+
+
+def test_sliding_window_leaves_out_exactly_the_pages_no_row_sees():
+    """plan_window = W + 1: the chunks of a tile cover [kv_begin, kv_eff) without gaps, kv_begin is a page boundary, no
+    row of the tile sees a key before it, and it is the last page boundary with that property; a window wider
+    than the context changes nothing."""
+    rng = np.random.default_rng(23)
+    for causal, t_pos in ((False, 1), (True, 64)):
+        for trial in range(40):
+            B = int(rng.integers(1, 12))
+            qo = np.ones(B, dtype=np.int64) if not causal else rng.integers(1, 300, size=B)
+            kv = qo + rng.integers(0, 3000, size=B)
+            W = int(rng.integers(0, 1500))
+            qo_indptr, kv_indptr, last = indptrs_from_lengths([int(x) for x in qo], [int(x) for x in kv], 16)
+            kw = dict(page_size=16, t_pos=t_pos, group=4, num_ctas=int(rng.integers(1, 40)), causal=causal, min_chunk=32)
+            p = plan_replica(qo_indptr, kv_indptr, last, plan_window=W + 1, **kw)
+            by_tile = {}
+            for k in range(p["n_work"]):
+                by_tile.setdefault((p["w_request"][k], p["w_q_row0"][k]), []).append(k)
+            for (i, q_row0), items in by_tile.items():
+                items.sort(key=lambda k: p["w_kv_start"][k])
+                start = q_row0 - int(qo_indptr[i])
+                first_pos = int(kv[i]) - int(qo[i]) + start              # position of the tile's first row
+                kv_begin = p["w_kv_start"][items[0]]
+                assert kv_begin % 16 == 0 and kv_begin <= max(0, first_pos - W)
+                assert kv_begin + 16 > max(0, first_pos - W) or p["w_kv_len"][items[0]] == 0
+                end = kv_begin
+                for k in items:
+                    assert p["w_kv_start"][k] == end
+                    assert p["w_kv_page0"][k] == int(kv_indptr[i]) + end // 16
+                    end += p["w_kv_len"][k]
+                n_pos = p["w_n_pos"][items[0]]
+                assert end == (min(int(kv[i]), first_pos + n_pos) if causal else int(kv[i]))
+            wide = plan_replica(qo_indptr, kv_indptr, last, plan_window=10 ** 7, **kw)
+            none = plan_replica(qo_indptr, kv_indptr, last, **kw)
+            assert all(wide[k] == none[k] for k in none)

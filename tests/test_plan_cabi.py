@@ -40,13 +40,15 @@ def indptrs(qo, kv, ps=16):
     return qo_indptr, kv_indptr, last
 
 
-def compare(h, qo, kv, causal, t_pos, g, C, alpha, beta, min_chunk, literal=False, refine=False, light_rows=0):
+def compare(h, qo, kv, causal, t_pos, g, C, alpha, beta, min_chunk, literal=False, refine=False, light_rows=0,
+            plan_window=0):
     qo_indptr, kv_indptr, last = indptrs(qo, kv)
     fi.fi_plan(h, qo_indptr, kv_indptr, last, causal)
     got = fi.fi_plan_view(h)
     want = plan_replica(qo_indptr, kv_indptr, last, page_size=16, t_pos=t_pos, group=g, num_ctas=C, causal=causal,
                         alpha=alpha, beta=beta, min_chunk=min_chunk, literal_lkv=literal, refine=refine,
-                        light_rows=light_rows, light_pct=64, kv_quantum=64 if light_rows else 1)
+                        light_rows=light_rows, light_pct=64, kv_quantum=64 if light_rows else 1,
+                        plan_window=plan_window)
     assert got["l_kv_chunk"] == want["L_kv"] and got["n_work"] == want["n_work"]
     assert got["n_merge"] == want["n_merge"] and got["n_slots"] == want["n_slots"]
     assert got["t_pos"] == t_pos and got["group"] == g and got["ctas_per_head"] == C
@@ -90,6 +92,29 @@ def test_planner_equals_replica_on_random_length_sets(mode):
                     n_cases += 1
                 fi.fi_destroy(h)
     assert n_cases >= 600
+
+
+@pytest.mark.parametrize("mode", ["decode", "append"])
+def test_planner_equals_replica_with_a_sliding_window(mode):
+    rng = np.random.default_rng(17 if mode == "decode" else 18)
+    for g in (1, 4):
+        t_pos = 1 if mode == "decode" else 256 // g
+        for C in (3, 32, 256):
+            for window in (1, 16, 100, 1025, 100000):
+                h = make(fi.FI_MODE_DECODE if mode == "decode" else fi.FI_MODE_APPEND, g, C, min_chunk=32, balance=1,
+                         plan_window=window)
+                for trial in range(8):
+                    B = int(rng.integers(1, 24))
+                    if mode == "decode":
+                        qo = np.ones(B, dtype=np.int64)
+                        kv = rng.integers(0, 5000, size=B)
+                        if trial % 3 == 0:
+                            kv[0] = int(rng.integers(30000, 200000))
+                    else:
+                        qo = rng.integers(0, 600, size=B)
+                        kv = qo + rng.integers(0, 3000, size=B)
+                    compare(h, qo, kv, mode == "append", t_pos, g, C, 1, 1, 32, plan_window=window)
+                fi.fi_destroy(h)
 
 
 def test_planner_equals_replica_on_the_benchmark_length_sets():
@@ -166,6 +191,13 @@ def test_argument_errors():
     expect(fi.FI_ERR_INVALID_ARG, fi.fi_run_kv8, h, dummy, dummy, dummy, (8, 8, 8), dummy, 1.0, 0.0, 1.0, dummy, dummy)
     expect(fi.FI_ERR_INVALID_ARG, fi.fi_create, **{**ok, "balance": 3})
     expect(fi.FI_ERR_INVALID_ARG, fi.fi_create, **{**ok, "merge": 3})
+    expect(fi.FI_ERR_INVALID_ARG, fi.fi_create, **{**ok, "plan_window": -1})
+    hw = fi.fi_create(**{**ok, "plan_window": 65})          # a window-planned handle runs with a matching window only
+    dummy = np.zeros(64, dtype=np.uint8)
+    expect(fi.FI_ERR_INVALID_ARG, fi.fi_run, hw, dummy, dummy, dummy, (8, 8, 8), dummy, 1.0, dummy, dummy)
+    expect(fi.FI_ERR_INVALID_ARG, fi.fi_run_variant, hw, dummy, dummy, dummy, (8, 8, 8), dummy, dummy, dummy, 1.0, dummy, dummy,
+           window_left=65)
+    fi.fi_destroy(hw)
     expect(fi.FI_ERR_UNSUPPORTED, fi.fi_create, **{**ok, "merge": 2, "mode": fi.FI_MODE_APPEND})   # in-launch contraction: decode only
     ha = fi.fi_create(**{**ok, "mode": fi.FI_MODE_APPEND})
     expect(fi.FI_ERR_UNSUPPORTED, fi.fi_run_kv8, ha, dummy, dummy, dummy, (8, 8, 8), dummy, 1.0, 1.0, 1.0, dummy, dummy)
