@@ -148,10 +148,12 @@ __device__ __forceinline__ void rotate_blocks(const u32x4_t x, const u32x4_t y, 
   *yh = u32x4_t{pack2<false>(yr[0], yr[1]), pack2<false>(yr[2], yr[3]), pack2<false>(yr[4], yr[5]), pack2<false>(yr[6], yr[7])};
 }
 
-// (The rotary variant runs one wavefront per SIMD with up to 512 registers: at two it spills 130 registers into
-// scratch memory inside the tile loop and takes 1.7 times as long.)
+// (The rotary variant and the any-page-size variants run one wavefront per SIMD with up to 512 registers: at two
+// they spill 70-180 registers into scratch memory inside the tile loop; the rotary kernel then takes 1.7 times as
+// long, the any-page-size kernels 3-7 % longer.)
 template <bool BF, bool KV8, bool ANYPS, bool VAR = false, bool ROPE = false>
-__global__ void __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(ROPE ? 1 : 2, ROPE ? 1 : 2)))
+__global__ void __launch_bounds__(64)
+    __attribute__((amdgpu_waves_per_eu((ROPE || ANYPS) ? 1 : 2, (ROPE || ANYPS) ? 1 : 2)))
 decode_kernel(const RunParams p, const RopeArg<ROPE> rope) {
   static_assert(!ROPE || (VAR && !KV8 && !ANYPS), "the rotary transform is built into the 16-bit variant kernel");
   const int lane = threadIdx.x;
@@ -274,13 +276,21 @@ decode_kernel(const RunParams p, const RopeArg<ROPE> rope) {
     float m_run = NEG_INF;  // running max of the scaled logits in log2 units (same in all 4 lane groups)
     float l_run = 0.f;      // this lane's share of the running sum
 
-    auto load_tile = [&](Tile& T, int t) {
+    // ANYPS: the page ids of a 32-token step (at most 32 pages), one per lane, fetched with one load two (8-bit
+    // K/V: four) steps before the step's rows are requested; a lane then takes the id of each of its rows from the
+    // lane that holds it.  (An index load per row would put a memory round trip in front of every row's load.)
+    auto step_ids = [&](int t) {
+      const int first = (32 * t) >> ps_log2;
+      return n_pages > 0 ? p.kv_indices[kv_page0 + min(first + (lane & 31), n_pages - 1)] : 0;
+    };
+    auto load_tile = [&](Tile& T, int& idv, int t) {
       if constexpr (ANYPS) {
         // row of chunk-local token tok: page tok >> ps_log2 (clamped to the chunk's last page: rows past the
         // end are masked later), slot tok % page_size
+        const int first = (32 * t) >> ps_log2;
         auto row = [&](const uint8_t* base, int tok) {
           const int pg = min(tok >> ps_log2, n_pages - 1);
-          const int64_t id = p.kv_indices[kv_page0 + pg];
+          const int64_t id = __builtin_amdgcn_ds_bpermute((pg - first) << 2, idv);
           return base + id * stride_page + (tok & ((1 << ps_log2) - 1)) * stride_tok;
         };
 #pragma unroll
@@ -291,6 +301,7 @@ decode_kernel(const RunParams p, const RopeArg<ROPE> rope) {
         for (int pg = 0; pg < 2; ++pg)
 #pragma unroll
           for (int i = 0; i < 4; ++i) T.v[pg][i] = ld_piece(row(vhead, 32 * t + 16 * pg + 4 * c + i));
+        idv = step_ids(t + (KV8 ? 4 : 2));  // for the step that reuses this tile's registers
         return;
       }
       const int pi = kv_page0 + 2 * t;
@@ -468,36 +479,48 @@ decode_kernel(const RunParams p, const RopeArg<ROPE> rope) {
       if constexpr (VAR) {
         if (p.window_left >= 0) t_first = min(max(0, -p.window_left - tok_minus_pos) >> 5, n_tiles) & ~1;
       }
-      if (n_tiles > t_first) load_tile(TA, t_first);
-      if (n_tiles > t_first + 1) load_tile(TB, t_first + 1);
+      int idA = 0, idB = 0;
+      if constexpr (ANYPS) {
+        idA = step_ids(0);
+        idB = step_ids(1);
+      }
+      if (n_tiles > t_first) load_tile(TA, idA, t_first);
+      if (n_tiles > t_first + 1) load_tile(TB, idB, t_first + 1);
       for (int t = t_first; t < n_tiles; t += 2) {
         compute_tile(TA, t);
-        if (t + 2 < n_tiles) load_tile(TA, t + 2);
+        if (t + 2 < n_tiles) load_tile(TA, idA, t + 2);
         if (t + 1 < n_tiles) {
           compute_tile(TB, t + 1);
-          if (t + 3 < n_tiles) load_tile(TB, t + 3);
+          if (t + 3 < n_tiles) load_tile(TB, idB, t + 3);
         }
       }
     } else {  // half the bytes per tile: twice the tiles in flight
       Tile TA, TB, TC, TD;
-      if (n_tiles > 0) load_tile(TA, 0);
-      if (n_tiles > 1) load_tile(TB, 1);
-      if (n_tiles > 2) load_tile(TC, 2);
-      if (n_tiles > 3) load_tile(TD, 3);
+      int idA = 0, idB = 0, idC = 0, idD = 0;
+      if constexpr (ANYPS) {
+        idA = step_ids(0);
+        idB = step_ids(1);
+        idC = step_ids(2);
+        idD = step_ids(3);
+      }
+      if (n_tiles > 0) load_tile(TA, idA, 0);
+      if (n_tiles > 1) load_tile(TB, idB, 1);
+      if (n_tiles > 2) load_tile(TC, idC, 2);
+      if (n_tiles > 3) load_tile(TD, idD, 3);
       for (int t = 0; t < n_tiles; t += 4) {
         compute_tile(TA, t);
-        if (t + 4 < n_tiles) load_tile(TA, t + 4);
+        if (t + 4 < n_tiles) load_tile(TA, idA, t + 4);
         if (t + 1 < n_tiles) {
           compute_tile(TB, t + 1);
-          if (t + 5 < n_tiles) load_tile(TB, t + 5);
+          if (t + 5 < n_tiles) load_tile(TB, idB, t + 5);
         }
         if (t + 2 < n_tiles) {
           compute_tile(TC, t + 2);
-          if (t + 6 < n_tiles) load_tile(TC, t + 6);
+          if (t + 6 < n_tiles) load_tile(TC, idC, t + 6);
         }
         if (t + 3 < n_tiles) {
           compute_tile(TD, t + 3);
-          if (t + 7 < n_tiles) load_tile(TD, t + 7);
+          if (t + 7 < n_tiles) load_tile(TD, idD, t + 7);
         }
       }
     }
