@@ -338,7 +338,7 @@ def main() -> int:
         step()
     torch.cuda.synchronize()
     if args.graph:
-        # one captured launch sequence, replayed; two more graphs carry the event pair around the attention kernel
+        # one captured launch sequence, replayed (the kernel's own time is taken from eager launches afterwards)
         graph = torch.cuda.CUDAGraph()
         with torch.cuda.graph(graph):
             step()
@@ -371,7 +371,9 @@ def main() -> int:
 
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "traffic.json")
-    if os.path.exists(tpath):
+    measured_setup = (args.page_size == 16 and args.page_order == "random" and args.kv_layout == "HND" and
+                      args.window_left < 0 and not args.small)  # the counters were taken on these settings only
+    if os.path.exists(tpath) and measured_setup:
         traffic = json.load(open(tpath)).get(args.workload + ("_fp8" if batch.kv_dtype else "") +
                                              ("_rope" if args.rope_theta > 0 else "") +
                                              ("_small" if args.small else ""))
