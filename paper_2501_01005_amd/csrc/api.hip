@@ -266,7 +266,6 @@ int32_t run_impl(fi_handle* h, const void* q, const void* k_pool, const void* v_
   p.m_slot_base = plan + L.off_merge[M_SLOT_BASE];
   p.m_n_chunks = plan + L.off_merge[M_N_CHUNKS];
   p.merge_counters = const_cast<int32_t*>(plan) + L.off_counters;
-  p.is_bf16 = h->cfg.dtype == FI_DTYPE_BF16 ? 1 : 0;
   p.kv_indices = kv_indices;
   p.q = q;
   p.k_pool = k_pool;

@@ -37,7 +37,6 @@ struct RunParams {
   const int32_t* m_slot_base;  // per split tile: first partial slot
   const int32_t* m_n_chunks;   //                 number of partial states
   int32_t* merge_counters;     // [split tile][kv head] partial states delivered so far; zero between launches
-  int32_t is_bf16;             // type of o_cast
   // attention variants (Sec. 3.2.3), read by the variant kernels only
   const int32_t* w_request;      // request of each work item
   const int32_t* kv_indptr;      // DEVICE copies of the plan inputs: a request's total KV length gives the

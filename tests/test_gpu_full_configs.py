@@ -11,10 +11,10 @@ from gpu_util import DeviceBatch, assert_close, make_wrapper, run_gpu
 pytestmark = pytest.mark.gpu
 
 
-def sampled_check(batch, mode, requests, what):
+def sampled_check(batch, mode, requests, what, **kw):
     print(f"[case] {what}: {batch.name} batch={batch.batch} tokens={int(batch.kv_lens().sum())} sample={list(requests)}",
           flush=True)
-    o, lse = run_gpu(batch, mode)
+    o, lse = run_gpu(batch, mode, **kw)
     assert not np.isnan(o).any() and not np.isnan(lse).any(), "NaN in GPU output"
     o_ref, lse_ref = oracle.run_batch(batch, requests=requests)
     e = assert_close(o, lse, o_ref, lse_ref, what)
@@ -33,6 +33,11 @@ def test_config2_full_gqa_decode_zipf():
 def test_config4_full_long_context_decode():
     b = workloads.config4()
     sampled_check(b, "decode", [0, 1], "c4 full")
+
+
+def test_config4_full_with_the_contraction_inside_the_launch():
+    # 171 and 86 partial states per request, written by wavefronts on every XCD and folded by whichever comes last
+    sampled_check(workloads.config4(), "decode", [0, 1], "c4 full, merge = 2", merge=2)
 
 
 def test_config2_full_with_8_bit_kv_cache():
