@@ -356,6 +356,13 @@ class Gen:
         cur, nxt, wr = k % NBUF, (k + 1) % NBUF, (k + 2) % NBUF
         kind = 'm' if masked else 'p'
         e.label('tile_%s%d_%s' % (kind, k, lbl))
+        if masked:
+            # none of this wavefront's rows sees a token of this tile or of any later one (its last row, lane 31,
+            # sees the most): from here on it only helps with the staging, then writes its outputs
+            e.raw('v_readlane_b32 s%d, %%[cap], 31' % S_TMP)
+            e.raw('s_lshl_b32 s%d, s%d, 6' % (S_REM, S_T))
+            e.raw('s_cmp_gt_i32 s%d, s%d' % (S_REM, S_TMP))
+            e.raw('s_cbranch_scc1 tile_j%d_%s' % (k, lbl))
         # canonical state after the barrier: no LDS operation in flight, the four loads of the
         # staged tile (K0, V0, K1, V1) possibly still in flight
         e.lgkm = []
@@ -392,13 +399,14 @@ class Gen:
             if kn == 0:
                 e.raw('s_branch tile_p0_%s' % lbl)
 
-    def idle_tile(self, k, lbl):
+    def idle_tile(self, k, lbl, tag='i', leave='done'):
         """a tile for a wavefront none of whose rows exists (the query tile is shorter than the CTA's
-        256 rows): it only does its share of the staging, then waits at the barrier, which leaves
-        the SIMD to the wavefront it shares it with"""
+        256 rows; tag i, leaves without outputs), or whose rows are all past their last visible token
+        (tag j, leaves through the epilogue): it only does its share of the staging, then waits at the
+        barrier, which leaves the SIMD to the wavefront it shares it with"""
         e = self.e
         wr = (k + 2) % NBUF
-        e.label('tile_i%d_%s' % (k, lbl))
+        e.label('tile_%s%d_%s' % (tag, k, lbl))
         e.lgkm = []
         e.vm = [set(('v', ST + 8 + 4 * r + i) for i in range(4)) for r in (0, 1)]
         for o in (self.k_to_lds(S_IDK, wr) + self.ids_load(4) + self.v_convert() + self.v_zero_tail(2) + self.stores(wr) +
@@ -410,9 +418,9 @@ class Gen:
             e.raw(o)
         e.raw('s_add_u32 s%d, s%d, 1' % (S_T, S_T))
         e.raw('s_cmp_ge_u32 s%d, %%[nt]' % S_T)
-        e.raw('s_cbranch_scc1 done_%s' % lbl)
+        e.raw('s_cbranch_scc1 %s_%s' % (leave, lbl))
         if (k + 1) % NBUF == 0:
-            e.raw('s_branch tile_i0_%s' % lbl)
+            e.raw('s_branch tile_%s0_%s' % (tag, lbl))
 
     def program(self):
         e = self.e
@@ -511,6 +519,8 @@ class Gen:
         e.raw('s_branch exit_%s' % lbl)
         for k in range(NBUF):
             self.idle_tile(k, lbl)
+        for k in range(NBUF):
+            self.idle_tile(k, lbl, 'j', 'exit')
         # out-of-line reference raises
         for kind in 'pm':
             for k in range(NBUF):
