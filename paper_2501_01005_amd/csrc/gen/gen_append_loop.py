@@ -97,6 +97,7 @@ class Gen:
     def __init__(self, bf16):
         self.bf = bf16
         self.e = Emitter()
+        self.mid_state = {}  # per masked tile of the rotation: loads in flight between its two steps
 
     # ---- building blocks ----
     def qk(self, Sn, s):
@@ -369,6 +370,15 @@ class Gen:
         e.vm = [set(('v', ST + 8 + 4 * r + i) for i in range(4)) for r in (0, 1)]
         for u in range(2):
             Sc, Sn = (S0, S1) if u == 0 else (S1, S0)
+            if masked and u == 1:
+                # the same test for the tile's second 32-token step: the wavefront leaves the tile half way and
+                # does the rest of its staging share in half_j
+                self.mid_state[k] = ([set(d) for d in e.lgkm], [set(d) for d in e.vm])
+                e.raw('v_readlane_b32 s%d, %%[cap], 31' % S_TMP)
+                e.raw('s_lshl_b32 s%d, s%d, 6' % (S_REM, S_T))
+                e.raw('s_add_u32 s%d, s%d, 32' % (S_REM, S_REM))
+                e.raw('s_cmp_gt_i32 s%d, s%d' % (S_REM, S_TMP))
+                e.raw('s_cbranch_scc1 half_j%d_%s' % (k, lbl))
             # block 1
             # the tile after next: its K goes to the LDS buffer that the barrier before this tile freed
             head = self.k_to_lds(S_IDK, wr) + self.ids_load(4) if u == 0 else []
@@ -398,6 +408,24 @@ class Gen:
             e.raw('s_cbranch_scc0 tile_m%d_%s' % (kn, lbl))
             if kn == 0:
                 e.raw('s_branch tile_p0_%s' % lbl)
+
+    def idle_half(self, k, lbl):
+        """second half of tile k for a wavefront that left it after the first 32-token step: what is left of its
+        staging share, the barrier, then idle tiles up to the epilogue"""
+        e = self.e
+        wr = (k + 2) % NBUF
+        e.label('half_j%d_%s' % (k, lbl))
+        e.lgkm, e.vm = [set(d) for d in self.mid_state[k][0]], [set(d) for d in self.mid_state[k][1]]
+        for o in self.v_zero_tail(2) + self.stores(wr) + self.fetch():
+            e.emit(o)
+        e.wait_lds_loads()
+        e.emit('s_barrier')
+        for o in self.ids_take():
+            e.raw(o)
+        e.raw('s_add_u32 s%d, s%d, 1' % (S_T, S_T))
+        e.raw('s_cmp_ge_u32 s%d, %%[nt]' % S_T)
+        e.raw('s_cbranch_scc1 exit_%s' % lbl)
+        e.raw('s_branch tile_j%d_%s' % ((k + 1) % NBUF, lbl))
 
     def idle_tile(self, k, lbl, tag='i', leave='done'):
         """a tile for a wavefront none of whose rows exists (the query tile is shorter than the CTA's
@@ -521,6 +549,8 @@ class Gen:
             self.idle_tile(k, lbl)
         for k in range(NBUF):
             self.idle_tile(k, lbl, 'j', 'exit')
+        for k in range(NBUF):
+            self.idle_half(k, lbl)
         # out-of-line reference raises
         for kind in 'pm':
             for k in range(NBUF):
