@@ -30,12 +30,14 @@ def _batches(mode):
                                  num_pages=POOL_PAGES) for i, (qo, kv) in enumerate(shapes)]
 
 
-@pytest.mark.parametrize("mode", ["decode", "append"])
+@pytest.mark.parametrize("mode", ["decode", "append", "decode, contraction inside the launch"])
 def test_one_captured_run_serves_every_plan(mode):
     import torch
     import paper_2501_01005_amd as fi
 
     dev = torch.device("cuda:0")
+    merge = 2 if "inside" in mode else 0   # then the captured graph holds one kernel, and its arrival counters
+    mode = mode.split(",")[0]              # must be back at zero after every replay
     batches = _batches(mode)
     t_pos = 1 if mode == "decode" else 256 // (HQ // HKV)
     max_batch = max(b.batch for b in batches)
@@ -44,7 +46,7 @@ def test_one_captured_run_serves_every_plan(mode):
     idx_max = max(len(b.kv_indices) for b in batches)
     # few CTAs and a small minimum chunk: long requests are split, so the replays also cover partial slots and merge
     w = fi.PagedAttention(dtype=workloads.BF16, num_qo_heads=HQ, num_kv_heads=HKV, head_dim=D, page_size=PS, mode=mode,
-                          max_batch=max_batch, max_qo_tiles=max_tiles, num_ctas=HKV * 6, min_chunk=128)
+                          max_batch=max_batch, max_qo_tiles=max_tiles, num_ctas=HKV * 6, min_chunk=128, merge=merge)
     q_s = torch.zeros((nnz_max, HQ, D), dtype=torch.bfloat16, device=dev)
     k_s = torch.zeros((POOL_PAGES, HKV, PS, D), dtype=torch.bfloat16, device=dev)
     v_s = torch.zeros_like(k_s)
