@@ -210,3 +210,15 @@ def test_argument_errors():
     expect(fi.FI_ERR_INVALID_ARG, fi.fi_check_indices, [0, -1], 5)
     fi.fi_check_indices([0, 4, 2], 5)
     expect(fi.FI_ERR_UNSUPPORTED, fi.fi_merge_states, dummy, dummy, 1, 1, 64, dummy, dummy)
+
+
+def test_header_is_plain_c():
+    """The boundary is a C ABI: the header must compile as C99 on its own (no C++, no HIP types)."""
+    import shutil
+    import subprocess
+    gcc = shutil.which("gcc")
+    if gcc is None:
+        pytest.skip("no gcc")
+    header = os.path.join(os.path.dirname(__file__), "..", "include", "fi355.h")
+    r = subprocess.run([gcc, "-fsyntax-only", "-x", "c", "-std=c99", "-Wall", "-Werror", header], capture_output=True, text=True)
+    assert r.returncode == 0, r.stderr
