@@ -12,10 +12,10 @@ from gpu_util import DeviceBatch, assert_close, make_wrapper
 pytestmark = pytest.mark.gpu
 
 
-def run_variant(batch, num_ctas=0, min_chunk=0, mode="decode", plan_window=0, **var):
+def run_variant(batch, num_ctas=0, min_chunk=0, mode="decode", plan_window=0, merge=0, **var):
     import torch
     dev = DeviceBatch(batch)
-    w = make_wrapper(batch, mode, num_ctas=num_ctas, min_chunk=min_chunk, plan_window=plan_window)
+    w = make_wrapper(batch, mode, num_ctas=num_ctas, min_chunk=min_chunk, plan_window=plan_window, merge=merge)
     w.plan(batch.qo_indptr, batch.kv_indptr, batch.last_page_len, causal=batch.causal)
     nnz = dev.q.shape[0]
     o = torch.full((nnz, batch.num_qo_heads, batch.head_dim), float("nan"), dtype=torch.float32, device=dev.device)
@@ -31,12 +31,13 @@ def run_variant(batch, num_ctas=0, min_chunk=0, mode="decode", plan_window=0, **
     return o.double().cpu().numpy(), lse.double().cpu().numpy()
 
 
-def check(batch, what, num_ctas=0, min_chunk=0, mode="decode", plan_window=0, **var):
+def check(batch, what, num_ctas=0, min_chunk=0, mode="decode", plan_window=0, merge=0, **var):
     print(f"[case] {what}: {batch.name} {mode} dtype={batch.dtype} heads={batch.num_qo_heads}/{batch.num_kv_heads} "
           f"qo={batch.qo_lens()[:8].tolist()} kv={batch.kv_lens()[:8].tolist()} "
           f"variant={ {k: (v if np.isscalar(v) else 'array') for k, v in var.items()} }", flush=True)
     o_ref, lse_ref = oracle.run_batch(batch, **var)
-    o, lse = run_variant(batch, num_ctas=num_ctas, min_chunk=min_chunk, mode=mode, plan_window=plan_window, **var)
+    o, lse = run_variant(batch, num_ctas=num_ctas, min_chunk=min_chunk, mode=mode, plan_window=plan_window, merge=merge,
+                         **var)
     e = assert_close(o, lse, o_ref, lse_ref, what)
     print(f"[ok] {what}: err_o={e[0]:.2e} err_lse={e[1]:.2e}", flush=True)
 
@@ -76,6 +77,10 @@ def test_window_hides_whole_steps_and_whole_chunks():
     b = workloads.make_batch("win", 410, workloads.BF16, 8, 2, 128, 16, [1, 1, 1, 1], [3000, 700, 40, 1], False)
     for W in (0, 1, 31, 32, 100, 5000):
         check(b, f"window {W}", num_ctas=2 * 16, min_chunk=64, window_left=W)
+    # the same with the partial states folded inside the launch: most of them are empty (lse = -inf)
+    for W in (0, 100):
+        check(b, f"window {W}, contraction inside the launch", num_ctas=2 * 16, min_chunk=64, window_left=W, merge=2)
+    check(b, "rope, contraction inside the launch", num_ctas=2 * 16, min_chunk=64, rope_theta=1e4, merge=2)
 
 
 @pytest.mark.parametrize("dtype", [workloads.BF16, workloads.F16])
