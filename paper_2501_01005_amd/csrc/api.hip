@@ -67,8 +67,10 @@ int32_t fi_create(const fi_config* cfg, fi_handle** out) {
   if (cfg->page_size < 1 || cfg->page_size > 64 || (cfg->page_size & (cfg->page_size - 1)) != 0)
     return set_error(FI_ERR_UNSUPPORTED, "fi_create: page_size must be a power of two between 1 and 64");
   const int g = cfg->num_qo_heads / cfg->num_kv_heads;
-  if (cfg->mode == FI_MODE_DECODE && !(g == 1 || g == 2 || g == 4))
-    return set_error(FI_ERR_UNSUPPORTED, "fi_create: decode mode is built for group size 1, 2, 4");
+  if (cfg->mode == FI_MODE_DECODE && !(g == 1 || g == 2 || g == 4 || g == 8 || g == 16))
+    return set_error(FI_ERR_UNSUPPORTED, "fi_create: decode mode is built for group size 1, 2, 4, 8, 16");
+  if (cfg->mode == FI_MODE_DECODE && cfg->merge == 2 && g > 4)
+    return set_error(FI_ERR_UNSUPPORTED, "fi_create: the contraction inside the attention launch is built for group size 1, 2, 4");
   if (cfg->mode == FI_MODE_APPEND && !(g == 1 || g == 2 || g == 4 || g == 8))
     return set_error(FI_ERR_UNSUPPORTED, "fi_create: append mode is built for group size 1, 2, 4, 8");
 

@@ -115,9 +115,11 @@ struct KvTile {
 // ROPE (with VAR): rotary position embedding as query and key transform (Sec. 3.2.3; the fused-RoPE kernels of
 // Sec. 4.4): key t of a request is rotated by its position t, the query by pos, pairing components (d, d + 64).
 // The rotated values are formed in fp32 from the K operands as they come back from LDS (a lane holds both
-// components of a pair there) and enter the first product as fp16, also when the inputs are bf16: a rotated value
-// rounded to bf16 would cost 2^-9 of relative accuracy per operand (a bf16 head + remainder pair, as P uses, costs
-// 20 % of the kernel's time instead).  Rotated magnitudes above 65504 saturate, below 2^-14 lose relative accuracy.
+// components of a pair there).  They enter the first product as a head and a remainder in the input type, as P
+// does in the second (three instructions per operand pair: head x head, remainder x head, head x remainder): a
+// rotated value rounded once costs 2^-9 (bf16) or 2^-12 (fp16) of relative accuracy per operand, which on peaked
+// distributions over large values reaches the comparison bound (measured 2.2e-3 on o with fp16 operands, V ~ 2 N(0,1),
+// ALiBi and a soft cap; 3e-6 with the remainder).
 struct NoRope {};
 template <bool ROPE>
 using RopeArg = typename std::conditional<ROPE, RopeTable, NoRope>::type;
@@ -133,10 +135,10 @@ __device__ __forceinline__ float elem16(uint32_t word, int odd) {
 }
 
 // (x, y) = the lane's eight components of the blocks d and d + 64 of one row; cs / sn = cosine / sine of the
-// row's angle for each of the eight pairs.  Rotated values -> fp16 MFMA operands.
+// row's angle for each of the eight pairs.  Rotated values -> MFMA operands: head and remainder.
 template <bool BF>
 __device__ __forceinline__ void rotate_blocks(const u32x4_t x, const u32x4_t y, const float* cs, const float* sn,
-                                              u32x4_t* xh, u32x4_t* yh) {
+                                              u32x4_t* xh, u32x4_t* yh, u32x4_t* xl, u32x4_t* yl) {
   float xr[8], yr[8];
 #pragma unroll
   for (int e = 0; e < 8; ++e) {
@@ -144,8 +146,16 @@ __device__ __forceinline__ void rotate_blocks(const u32x4_t x, const u32x4_t y, 
     xr[e] = xe * cs[e] - ye * sn[e];
     yr[e] = ye * cs[e] + xe * sn[e];
   }
-  *xh = u32x4_t{pack2<false>(xr[0], xr[1]), pack2<false>(xr[2], xr[3]), pack2<false>(xr[4], xr[5]), pack2<false>(xr[6], xr[7])};
-  *yh = u32x4_t{pack2<false>(yr[0], yr[1]), pack2<false>(yr[2], yr[3]), pack2<false>(yr[4], yr[5]), pack2<false>(yr[6], yr[7])};
+  *xh = u32x4_t{pack2<BF>(xr[0], xr[1]), pack2<BF>(xr[2], xr[3]), pack2<BF>(xr[4], xr[5]), pack2<BF>(xr[6], xr[7])};
+  *yh = u32x4_t{pack2<BF>(yr[0], yr[1]), pack2<BF>(yr[2], yr[3]), pack2<BF>(yr[4], yr[5]), pack2<BF>(yr[6], yr[7])};
+  // remainder = value - head (the head's value read back from its 16 bits)
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    xr[e] -= elem16<BF>((*xh)[e >> 1], e & 1);
+    yr[e] -= elem16<BF>((*yh)[e >> 1], e & 1);
+  }
+  *xl = u32x4_t{pack2<BF>(xr[0], xr[1]), pack2<BF>(xr[2], xr[3]), pack2<BF>(xr[4], xr[5]), pack2<BF>(xr[6], xr[7])};
+  *yl = u32x4_t{pack2<BF>(yr[0], yr[1]), pack2<BF>(yr[2], yr[3]), pack2<BF>(yr[4], yr[5]), pack2<BF>(yr[6], yr[7])};
 }
 
 // (The rotary variant and the any-page-size variants run one wavefront per SIMD with up to 512 registers: at two
@@ -258,15 +268,18 @@ decode_kernel(const RunParams p, const RopeArg<ROPE> rope) {
       for (int s = 0; s < 4; ++s) qreg[s] = u32x4_t{0u, 0u, 0u, 0u};
     }
 
-    if constexpr (ROPE) {  // the query at its position, as fp16
+    u32x4_t qlo[ROPE ? 4 : 1];  // remainder of the rotated query
+    if constexpr (ROPE) {
 #pragma unroll
       for (int sp = 0; sp < 2; ++sp) {
         float cs[8], sn[8];
         angles(pos, sp, cs, sn);
-        u32x4_t xh, yh;
-        rotate_blocks<BF>(qreg[sp], qreg[sp + 2], cs, sn, &xh, &yh);
+        u32x4_t xh, yh, xl, yl;
+        rotate_blocks<BF>(qreg[sp], qreg[sp + 2], cs, sn, &xh, &yh, &xl, &yl);
         qreg[sp] = xh;
         qreg[sp + 2] = yh;
+        qlo[sp] = xl;
+        qlo[sp + 2] = yl;
       }
     }
 
@@ -354,10 +367,14 @@ decode_kernel(const RunParams p, const RopeArg<ROPE> rope) {
             angles(tok_abs0 + 32 * t + 16 * pg + m, sp, cs, sn);  // this lane's K row is token m of the page
             const u32x4_t x = k_lds[pg * 256 + m * 16 + (((4 * sp + c) ^ m) & 15)];
             const u32x4_t y = k_lds[pg * 256 + m * 16 + (((4 * (sp + 2) + c) ^ m) & 15)];
-            u32x4_t xh, yh;
-            rotate_blocks<BF>(x, y, cs, sn, &xh, &yh);
-            sacc = mfma_16x16x32<false>(xh, qreg[sp], sacc);
-            sacc = mfma_16x16x32<false>(yh, qreg[sp + 2], sacc);
+            u32x4_t xh, yh, xl, yl;
+            rotate_blocks<BF>(x, y, cs, sn, &xh, &yh, &xl, &yl);
+            sacc = mfma_16x16x32<BF>(xh, qreg[sp], sacc);
+            sacc = mfma_16x16x32<BF>(yh, qreg[sp + 2], sacc);
+            sacc = mfma_16x16x32<BF>(xl, qreg[sp], sacc);
+            sacc = mfma_16x16x32<BF>(yl, qreg[sp + 2], sacc);
+            sacc = mfma_16x16x32<BF>(xh, qlo[sp], sacc);
+            sacc = mfma_16x16x32<BF>(yh, qlo[sp + 2], sacc);
           }
           if (pg == 0) s0 = sacc; else s1 = sacc;
         }

@@ -132,3 +132,34 @@ def test_contraction_inside_the_attention_launch(dtype, g):
     view = __import__("paper_2501_01005_amd").fi_plan_view(w.handle)
     assert int(view["n_merge"]) >= 2 and max(view["m_n_chunks"]) > 16
     w.close()
+
+
+@pytest.mark.parametrize("g", [8, 16])
+@pytest.mark.parametrize("dtype", [workloads.BF16, workloads.F16])
+def test_wide_head_groups(g, dtype):
+    """8 and 16 query heads per kv head (the fused tile's 16 columns half or completely filled): split and unsplit
+    chunks, the 8-bit KV cache, another page size, the variants with the rotary embedding."""
+    import torch
+    b = workloads.random_case(300 + g, dtype=dtype, num_qo_heads=2 * g, num_kv_heads=2, batch=5, max_kv=600, value_scale=2.0)
+    check(b, f"g={g} {dtype}", num_ctas=2 * 16, min_chunk=32)
+    check(b, f"g={g} {dtype}, unsplit", num_ctas=2 * 2, min_chunk=1024)
+    b8 = workloads.random_case(310 + g, dtype=dtype, num_qo_heads=2 * g, num_kv_heads=2, batch=5, max_kv=600,
+                               kv_dtype=workloads.FP8, k_scale=0.5, v_scale=2.0)
+    check(b8, f"g={g} {dtype}, 8-bit KV", num_ctas=2 * 16, min_chunk=32)
+    bp = workloads.random_case(320 + g, dtype=dtype, num_qo_heads=2 * g, num_kv_heads=2, batch=5, max_kv=600, page_size=4)
+    check(bp, f"g={g} {dtype}, page size 4", num_ctas=2 * 16, min_chunk=32)
+    # variants: through the wrapper directly
+    dev = DeviceBatch(b)
+    w = make_wrapper(b, "decode", num_ctas=2 * 16, min_chunk=32)
+    w.plan(b.qo_indptr, b.kv_indptr, b.last_page_len, causal=False)
+    var = dict(kv_indptr=torch.from_numpy(np.ascontiguousarray(b.kv_indptr, dtype=np.int32)).to(dev.device),
+               last_page_len=torch.from_numpy(np.ascontiguousarray(b.last_page_len, dtype=np.int32)).to(dev.device),
+               logits_soft_cap=6.0, window_left=200, rope_theta=1e4,
+               alibi_slopes=torch.tensor([2.0 ** (-(i + 1) * 8.0 / (2 * g)) for i in range(2 * g)], dtype=torch.float32,
+                                         device=dev.device))
+    o, lse = w.run(dev.q, dev.k_pool, dev.v_pool, dev.kv_indices, b.sm_scale, variant=var)
+    torch.cuda.synchronize()
+    o_ref, lse_ref = oracle.run_batch(b, logits_soft_cap=6.0, window_left=200, rope_theta=1e4,
+                                      alibi_slopes=np.array([2.0 ** (-(i + 1) * 8.0 / (2 * g)) for i in range(2 * g)]))
+    assert_close(o.double().cpu().numpy(), lse.double().cpu().numpy(), o_ref, lse_ref, f"g={g} variants")
+    w.close()

@@ -169,7 +169,8 @@ def test_argument_errors():
     expect(fi.FI_ERR_UNSUPPORTED, fi.fi_create, **{**ok, "head_dim": 64})
     expect(fi.FI_ERR_UNSUPPORTED, fi.fi_create, **{**ok, "page_size": 12})
     expect(fi.FI_ERR_UNSUPPORTED, fi.fi_create, **{**ok, "page_size": 128})
-    expect(fi.FI_ERR_UNSUPPORTED, fi.fi_create, **{**ok, "num_qo_heads": 64})       # g = 8 in decode mode
+    expect(fi.FI_ERR_UNSUPPORTED, fi.fi_create, **{**ok, "num_qo_heads": 24})       # g = 3
+    expect(fi.FI_ERR_UNSUPPORTED, fi.fi_create, **{**ok, "num_qo_heads": 64, "merge": 2})   # in-launch contraction: g <= 4
     expect(fi.FI_ERR_INVALID_ARG, fi.fi_create, **{**ok, "num_qo_heads": 30})
     expect(fi.FI_ERR_INVALID_ARG, fi.fi_create, **{**ok, "dtype": 7})
     expect(fi.FI_ERR_INVALID_ARG, fi.fi_create, **{**ok, "max_batch": 0})
