@@ -131,7 +131,7 @@ typedef struct fi_plan_arrays {
 } fi_plan_arrays;
 
 /* Create / destroy a handle.  cfg HOST.  FI_ERR_UNSUPPORTED unless head_dim = 128,
- * page_size a power of two in 1..64, g in {1,2,4,8,16} (decode) / g in {1,2,4,8} (append).  With num_ctas = 0 the
+ * page_size a power of two in 1..64, g in {1,2,4,8,16}.  With num_ctas = 0 the
  * current HIP device is queried (FI_ERR_HIP without one). */
 int32_t fi_create(const fi_config* cfg, fi_handle** out);
 int32_t fi_destroy(fi_handle* h);

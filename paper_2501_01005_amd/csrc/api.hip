@@ -71,8 +71,8 @@ int32_t fi_create(const fi_config* cfg, fi_handle** out) {
     return set_error(FI_ERR_UNSUPPORTED, "fi_create: decode mode is built for group size 1, 2, 4, 8, 16");
   if (cfg->mode == FI_MODE_DECODE && cfg->merge == 2 && g > 4)
     return set_error(FI_ERR_UNSUPPORTED, "fi_create: the contraction inside the attention launch is built for group size 1, 2, 4");
-  if (cfg->mode == FI_MODE_APPEND && !(g == 1 || g == 2 || g == 4 || g == 8))
-    return set_error(FI_ERR_UNSUPPORTED, "fi_create: append mode is built for group size 1, 2, 4, 8");
+  if (cfg->mode == FI_MODE_APPEND && !(g == 1 || g == 2 || g == 4 || g == 8 || g == 16))
+    return set_error(FI_ERR_UNSUPPORTED, "fi_create: append mode is built for group size 1, 2, 4, 8, 16");
 
   int num_ctas = cfg->num_ctas;
   if (num_ctas == 0) {

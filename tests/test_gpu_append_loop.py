@@ -31,7 +31,7 @@ def test_chunk_lengths_around_the_loop_thresholds(causal):
         check(b, f"thresholds qo={qo}", num_ctas=4, min_chunk=1024)
 
 
-@pytest.mark.parametrize("g", [1, 2, 4, 8])
+@pytest.mark.parametrize("g", [1, 2, 4, 8, 16])
 @pytest.mark.parametrize("dtype", [workloads.BF16, workloads.F16])
 def test_group_sizes_and_input_types(g, dtype):
     b = workloads.make_batch("gq", 50 + g, dtype, 2 * g, 2, 128, 16, [256 // g + 3, 40, 9], [500, 333, 200], True)
