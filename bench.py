@@ -250,6 +250,8 @@ def main() -> int:
     ap.add_argument("--merge", type=int, default=0,
                     help="fi_config.merge: 1 = partial states folded by a second launch, 2 = inside the attention launch "
                          "(decode), 0 = default")
+    ap.add_argument("--out16", action="store_true",
+                    help="append workloads: write the output in the input type only (fi_run with o = NULL), not as fp32 rows")
     ap.add_argument("--alpha", type=int, default=0, help="fi_config.alpha (with --beta; 0, 0 = default)")
     ap.add_argument("--beta", type=int, default=0)
     args = ap.parse_args()
@@ -308,6 +310,12 @@ def main() -> int:
     lse = torch.empty((nnz, batch.num_qo_heads), dtype=torch.float32, device=dev.device)
 
     run_kw = dict(dev.scales)
+    if args.out16:
+        if mode != "append":
+            print("bench.py: --out16 is for the append workloads (the decode byte counts assume fp32 rows)", file=sys.stderr)
+            return 2
+        run_kw["o_cast"] = torch.empty((nnz, batch.num_qo_heads, batch.head_dim), dtype=dev.q.dtype, device=dev.device)
+        o = False
     if args.rope_theta > 0 or args.window_left >= 0:
         if mode != "decode" or batch.kv_dtype or args.page_size != 16:
             print("bench.py: --rope-theta / --window-left are for the 16-bit decode workloads with page size 16",
@@ -407,7 +415,7 @@ def main() -> int:
         "vs_baseline": None, "dtype": batch.dtype, "data": "synthetic",
         "config": {"workload": batch.name, "batch": batch.batch, "num_qo_heads": batch.num_qo_heads,
                    "num_kv_heads": batch.num_kv_heads, "head_dim": batch.head_dim, "page_size": batch.page_size, "page_order": args.page_order, "kv_layout": args.kv_layout,
-                   "kv_dtype": batch.kv_dtype or batch.dtype,
+                   "kv_dtype": batch.kv_dtype or batch.dtype, "o_dtype": batch.dtype if args.out16 else "f32",
                    **({"fused_rope_theta": args.rope_theta} if args.rope_theta > 0 else {}),
                    **({"window_left": args.window_left, "planned": bool(args.plan_window)} if args.window_left >= 0 else {}),
                    "step": ("fi_run captured in a HIP graph, replayed (plan reused)" if args.graph else

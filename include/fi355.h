@@ -165,7 +165,10 @@ int32_t fi_plan_view(const fi_handle* h, fi_plan_arrays* out);
  * directly or partial states into the workspace, then one fixed-grid merge launch for the
  * split tiles.  All pointers DEVICE.  kv_strides HOST [3] = element strides of
  * (page, kv head, slot-in-page).  sm_scale (> 0) multiplies q.k before the softmax.
- * o_cast (may be NULL): the output also rounded to the input dtype, [nnz_qo, H_qo, D].
+ * o_cast (may be NULL): the output also rounded to the input dtype (nearest even), [nnz_qo, H_qo, D].
+ * o may be NULL when o_cast is not: the output is then written in the input dtype only, which
+ * halves the output bytes of an append step (partial states stay fp32 in the workspace; lse is
+ * always written).
  * Asynchronous on `stream`; uses the workspace given to the last fi_plan. */
 int32_t fi_run(fi_handle* h, const void* q, const void* k_pool, const void* v_pool,
                const int64_t* kv_strides, const int32_t* kv_indices, float sm_scale,

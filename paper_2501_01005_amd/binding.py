@@ -284,7 +284,8 @@ class PagedAttention:
             k_scale: Optional[float] = None, v_scale: Optional[float] = None, variant: Optional[dict] = None):
         """k_scale / v_scale given: the pools are an 8-bit KV cache (uint8 tensors of E4M3 codes).
         variant: dict(kv_indptr=, last_page_len= (device int32 tensors), logits_soft_cap=, window_left=,
-        alibi_slopes= (device float32 tensor), rope_theta=, rope_scale=) runs fi_run_variant."""
+        alibi_slopes= (device float32 tensor), rope_theta=, rope_scale=) runs fi_run_variant.
+        o=False with an o_cast tensor: the output is written in the input type only (returns o_cast, lse)."""
         torch = self.torch
         kv8 = k_scale is not None or v_scale is not None
         kv_dtype = torch.uint8 if kv8 else self.torch_dtype
@@ -293,7 +294,10 @@ class PagedAttention:
         assert k_pool.dim() == 4 and k_pool.stride(3) == 1 and k_pool.stride() == v_pool.stride()
         assert kv_indices.dtype == torch.int32 and kv_indices.is_contiguous()
         nnz = q.shape[0]
-        if o is None:
+        if o is False:
+            assert o_cast is not None
+            o = None
+        elif o is None:
             o = torch.empty((nnz, self.num_qo_heads, self.head_dim), dtype=torch.float32, device=q.device)
         if lse is None:
             lse = torch.empty((nnz, self.num_qo_heads), dtype=torch.float32, device=q.device)
@@ -311,4 +315,4 @@ class PagedAttention:
                        self._stream())
         else:
             fi_run(self.handle, q, k_pool, v_pool, strides, kv_indices, sm_scale, o, lse, o_cast, self._stream())
-        return o, lse
+        return (o_cast if o is None else o), lse

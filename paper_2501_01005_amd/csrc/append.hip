@@ -594,7 +594,7 @@ __device__ __attribute__((noinline)) void generic_work_item(uint64_t params_addr
           const int d0 = 32 * db + 8 * q + 4 * c;
           const f32x4_t v = {acc[b][db][4 * q] * inv, acc[b][db][4 * q + 1] * inv, acc[b][db][4 * q + 2] * inv,
                              acc[b][db][4 * q + 3] * inv};
-          *reinterpret_cast<f32x4_t*>(dst_o + d0) = v;
+          if (out_slot >= 0 || p.o != nullptr) *reinterpret_cast<f32x4_t*>(dst_o + d0) = v;
           if (out_slot < 0 && p.o_cast != nullptr) {
             uint16_t* dc = static_cast<uint16_t*>(p.o_cast) + final_row * kHeadDim + d0;
             *reinterpret_cast<u32x2_t*>(dc) = u32x2_t{pack_out<BF>(v[0], v[1]), pack_out<BF>(v[2], v[3])};
@@ -686,7 +686,7 @@ append_kernel(const RunParams p) {
                                static_cast<uint32_t>(out_row * (kHeadDim * 4) + c_o * 16),
                                pos_r < n_pos ? (c_o == 0 ? 3 : 1) : 0, final_out ? p.o : p.part_o,
                                final_out ? p.lse : p.part_lse, p.o_cast,
-                               __builtin_amdgcn_readfirstlane(final_out && p.o_cast != nullptr ? 1 : 0),
+                               __builtin_amdgcn_readfirstlane(final_out && p.o_cast != nullptr ? (p.o != nullptr ? 1 : 2) : 0),
                                epi0 + n_o * kEpilogueRowBytes + c_o * 16,
                                epi0 + ((tid_o >> 4) & 3) * kEpilogueRowBytes + st_chunk_o * 16,
                                st_chunk_o * 16, g_log2, H,

@@ -578,8 +578,10 @@ decode_kernel(const RunParams p, const RopeArg<ROPE> rope) {
           }
           continue;
         }
-        *reinterpret_cast<f32x4_t*>(d) = lo;
-        *reinterpret_cast<f32x4_t*>(d + 4) = hi;
+        if (out_slot >= 0 || p.o != nullptr) {  // final rows may be wanted in the input type only
+          *reinterpret_cast<f32x4_t*>(d) = lo;
+          *reinterpret_cast<f32x4_t*>(d + 4) = hi;
+        }
         if (out_slot < 0 && p.o_cast != nullptr) {
           uint16_t* dc = static_cast<uint16_t*>(p.o_cast) +
                          (static_cast<int64_t>(q_row0) * H + head) * kHeadDim + 32 * c + 8 * i;
@@ -657,7 +659,7 @@ decode_kernel(const RunParams p, const RopeArg<ROPE> rope) {
         float* dst = p.o + out_row * kHeadDim + fl * sub;
 #pragma unroll
         for (int e = 0; e < 8; e += 2)
-          if (e < fl) *reinterpret_cast<f32x2_t*>(dst + e) = f32x2_t{acc_o[e], acc_o[e + 1]};
+          if (e < fl && p.o != nullptr) *reinterpret_cast<f32x2_t*>(dst + e) = f32x2_t{acc_o[e], acc_o[e + 1]};
         if (sub == 0) p.lse[out_row] = mx != NEG_INF ? mx + __builtin_amdgcn_logf(den) * 0.6931471805599453f : NEG_INF;
         if (p.o_cast != nullptr) {
           uint32_t* dc = static_cast<uint32_t*>(p.o_cast) + (out_row * kHeadDim + fl * sub) / 2;

@@ -614,22 +614,27 @@ class Gen:
                 # the tiles requested for the next work item have landed before the output stores go out: loads and
                 # stores share one counter and return out of order, so later they could not be waited for apart
                 e.raw('s_waitcnt vmcnt(0)')
+            # %[oc]: 0 = the fp32 rows only, 1 = those and the copy rounded to the input type, 2 = the rounded copy only
             e.raw('s_cmp_eq_u32 %[oc], 0')
             e.raw('s_cbranch_scc0 cast%d_%s' % (h, lbl))
-            for with_cast in (False, True):
+            for wide, with_cast in ((True, False), (True, True), (False, True)):
                 if with_cast:
-                    e.label('cast%d_%s' % (h, lbl))
+                    e.label('%s%d_%s' % ('cast' if wide else 'only', h, lbl))
+                    if wide:
+                        e.raw('s_cmp_eq_u32 %[oc], 2')
+                        e.raw('s_cbranch_scc1 only%d_%s' % (h, lbl))
                 for k in range(8):
                     e.raw('s_waitcnt lgkmcnt(%d)' % (7 - k))
                     e.raw('s_mov_b64 exec, s[%d:%d]' % (masks[k], masks[k] + 1))
-                    e.raw('global_store_dwordx4 v%d, %s, %%[ob] offset:%d nt' % (OFF + k, vr(VT + 4 * k, 4), 256 * h))
+                    if wide:
+                        e.raw('global_store_dwordx4 v%d, %s, %%[ob] offset:%d nt' % (OFF + k, vr(VT + 4 * k, 4), 256 * h))
                     if with_cast:
                         t = S1 + 2 * k
                         e.raw('%s v%d, v%d, v%d' % (cvt, t, VT + 4 * k, VT + 4 * k + 1))
                         e.raw('%s v%d, v%d, v%d' % (cvt, t + 1, VT + 4 * k + 2, VT + 4 * k + 3))
                         e.raw('global_store_dwordx2 v%d, %s, %%[cb] offset:%d nt' % (COFF + k, vr(t, 2), 128 * h))
                 e.raw('s_mov_b64 exec, s[%d:%d]' % (S_EXEC, S_EXEC + 1))
-                if not with_cast:
+                if wide:
                     e.raw('s_branch half%d_%s' % (h, lbl))
             e.label('half%d_%s' % (h, lbl))
         e.raw('s_branch end_%s' % lbl)

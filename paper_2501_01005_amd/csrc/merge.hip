@@ -125,7 +125,7 @@ __global__ void __launch_bounds__(64 * kMergeWaves) merge_planned_kernel(const M
              lane, red_acc, red_den, &o2, &l);
     if (wave == 0) {
       const int64_t out_row = (static_cast<int64_t>(p.m_q_row0[mt]) + pos) * H + head;
-      *reinterpret_cast<f32x2_t*>(p.o + out_row * kHeadDim + 2 * lane) = o2;
+      if (p.o != nullptr) *reinterpret_cast<f32x2_t*>(p.o + out_row * kHeadDim + 2 * lane) = o2;
       if (lane == 0) p.lse[out_row] = l;
       if (p.o_cast != nullptr) store_cast(p.o_cast, out_row, lane, o2, p.is_bf16);
     }
