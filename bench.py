@@ -148,6 +148,11 @@ def bench_shared_prefix(args) -> int:
             main.wait_stream(side)
             fi.fi_merge_state_pair(o_p, l_p, o_s, l_s, n * H, D, o_p, l_p, main.cuda_stream)
             return
+        if not args.separate_merges:
+            # both attention launches, then one contraction launch over the partial states of both passes
+            wp.run_composed(ws, dev_p.q, dev_p.k_pool, dev_p.v_pool, dev_p.kv_indices, dev_s.kv_indices, c.prefix.sm_scale,
+                            o=o_p, lse=l_p)
+            return
         wp.run(dev_p.q, dev_p.k_pool, dev_p.v_pool, dev_p.kv_indices, c.prefix.sm_scale, o=o_p, lse=l_p)
         ws.run(dev_s.q, dev_s.k_pool, dev_s.v_pool, dev_s.kv_indices, c.suffix.sm_scale, o=o_s, lse=l_s)
         fi.fi_merge_state_pair(o_p, l_p, o_s, l_s, n * H, D, o_p, l_p, stream)
@@ -189,7 +194,9 @@ def bench_shared_prefix(args) -> int:
         "config": {"workload": "c5_shared_prefix" + ("_small" if args.small else ""), "requests": n,
                    "prefix_tokens": int(c.prefix.kv_lens()[0]),
                    "step": ("one captured graph, the two passes as parallel branches, replayed" if args.graph else
-                            "3 launches + merge" if args.no_plan else "2 plans + 3 launches + merge")},
+                            ("2 attention launches + 3 merge launches" if args.separate_merges else
+                             "2 attention launches + 1 contraction launch (fi_run_composed)") +
+                            ("" if args.no_plan else ", 2 plans"))},
         "frac_of_peak": bytes_comp / (us_comp * 1e-6) / 1e9 / HBM_PEAK_GBS,
         "composable_us": us_comp, "single_format_us": us_single, "speedup_vs_single_format": us_single / us_comp,
         "algorithmic_bytes_composable": bytes_comp, "algorithmic_bytes_single_format": bytes_single,
@@ -250,6 +257,8 @@ def main() -> int:
     ap.add_argument("--merge", type=int, default=0,
                     help="fi_config.merge: 1 = partial states folded by a second launch, 2 = inside the attention launch "
                          "(decode), 0 = default")
+    ap.add_argument("--separate-merges", action="store_true",
+                    help="c5: fi_run on each format and fi_merge_state_pair (five launches) instead of fi_run_composed (three)")
     ap.add_argument("--out16", action="store_true",
                     help="append workloads: write the output in the input type only (fi_run with o = NULL), not as fp32 rows")
     ap.add_argument("--alpha", type=int, default=0, help="fi_config.alpha (with --beta; 0, 0 = default)")

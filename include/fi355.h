@@ -235,6 +235,24 @@ int32_t fi_merge_state_pair(const float* o_a, const float* lse_a, const float* o
                             const float* lse_b, int64_t n_rows, int32_t head_dim,
                             float* o, float* lse, fi_stream stream);
 
+/* Composable formats (Sec. 3.1.2) in three launches instead of five: the attention kernels of two
+ * planned handles over the SAME nnz_qo query rows (say a shared-prefix format in append mode and a
+ * per-request format in decode mode, each with its own handle, plan, workspace and page ids over the
+ * same pools), then ONE contraction launch that, per output row, folds each pass's partial states
+ * where its tile was split and merges the two states (Sec. 2.2).  The result equals, bit for bit,
+ * fi_run on each handle followed by fi_merge_state_pair.
+ * o_a, lse_a, o_b, lse_b DEVICE fp32 [nnz_qo, H_qo, D] / [nnz_qo, H_qo]: state rows of each pass that
+ * the caller owns (the attention kernels write the states of unsplit tiles there; contents after the
+ * call are unspecified).  o / lse / o_cast as in fi_run (o may be NULL when o_cast is not); they may
+ * alias neither pass's rows.  Both handles: same dtype and head counts, merge != 2, no plan_window;
+ * 16-bit pools.  Errors as fi_run, plus FI_ERR_INVALID_ARG when the plans' query rows differ from
+ * nnz_qo.  Asynchronous on `stream`. */
+int32_t fi_run_composed(fi_handle* h_a, fi_handle* h_b, const void* q, const void* k_pool,
+                        const void* v_pool, const int64_t* kv_strides, const int32_t* kv_indices_a,
+                        const int32_t* kv_indices_b, float sm_scale, float* o_a, float* lse_a,
+                        float* o_b, float* lse_b, int64_t nnz_qo, float* o, float* lse, void* o_cast,
+                        fi_stream stream);
+
 /* HOST helper for tests: FI_OK iff every indices[i] is in [0, num_pages). */
 int32_t fi_check_indices(const int32_t* indices_host, int64_t n, int32_t num_pages);
 

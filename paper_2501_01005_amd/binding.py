@@ -14,7 +14,7 @@ __all__ = [
     "FI_ERR_HIP", "FI_DTYPE_F16", "FI_DTYPE_BF16", "FI_MODE_DECODE", "FI_MODE_APPEND",
     "Fi355Error", "fi_config", "fi_plan_arrays", "lib", "library_path",
     "fi_create", "fi_destroy", "fi_workspace_bytes", "fi_plan", "fi_plan_view", "fi_run", "fi_run_kv8",
-    "fi_run_variant", "fi_variant", "fi_merge_states", "fi_merge_state_pair", "fi_check_indices", "fi_set_timing_events", "fi_last_error",
+    "fi_run_variant", "fi_run_composed", "fi_variant", "fi_merge_states", "fi_merge_state_pair", "fi_check_indices", "fi_set_timing_events", "fi_last_error",
     "PagedAttention",
 ]
 
@@ -90,12 +90,14 @@ def _load() -> ctypes.CDLL:
                              vp, vp, vp, vp]
     L.fi_merge_states.argtypes = [vp, vp, i64, i32, i32, vp, vp, vp]
     L.fi_merge_state_pair.argtypes = [vp, vp, vp, vp, i64, i32, vp, vp, vp]
+    L.fi_run_composed.argtypes = [vp, vp, vp, vp, vp, ctypes.POINTER(i64), vp, vp, ctypes.c_float, vp, vp, vp, vp, i64,
+                                  vp, vp, vp, vp]
     L.fi_check_indices.argtypes = [vp, i64, i32]
     L.fi_set_timing_events.argtypes = [vp, vp, vp]
     L.fi_last_error.argtypes = []
     L.fi_last_error.restype = ctypes.c_char_p
     for name in ("fi_create", "fi_destroy", "fi_workspace_bytes", "fi_plan", "fi_plan_view", "fi_run", "fi_run_kv8",
-                 "fi_run_variant", "fi_merge_states", "fi_merge_state_pair", "fi_check_indices", "fi_set_timing_events"):
+                 "fi_run_variant", "fi_run_composed", "fi_merge_states", "fi_merge_state_pair", "fi_check_indices", "fi_set_timing_events"):
         getattr(L, name).restype = i32
     return L
 
@@ -211,6 +213,15 @@ def fi_merge_state_pair(o_a, lse_a, o_b, lse_b, n_rows: int, head_dim: int, o, l
                                    _ptr(lse), stream or None))
 
 
+def fi_run_composed(handle_a: int, handle_b: int, q, k_pool, v_pool, kv_strides: Sequence[int], kv_indices_a,
+                    kv_indices_b, sm_scale: float, o_a, lse_a, o_b, lse_b, nnz_qo: int, o, lse, o_cast=None,
+                    stream: int = 0) -> None:
+    strides = (ctypes.c_int64 * 3)(*[int(s) for s in kv_strides])
+    _check(lib.fi_run_composed(handle_a, handle_b, _ptr(q), _ptr(k_pool), _ptr(v_pool), strides, _ptr(kv_indices_a),
+                               _ptr(kv_indices_b), float(sm_scale), _ptr(o_a), _ptr(lse_a), _ptr(o_b), _ptr(lse_b),
+                               int(nnz_qo), _ptr(o), _ptr(lse), _ptr(o_cast), stream or None))
+
+
 def fi_set_timing_events(handle: int, before, after) -> None:
     _check(lib.fi_set_timing_events(handle, before, after))
 
@@ -315,4 +326,28 @@ class PagedAttention:
                        self._stream())
         else:
             fi_run(self.handle, q, k_pool, v_pool, strides, kv_indices, sm_scale, o, lse, o_cast, self._stream())
+        return (o_cast if o is None else o), lse
+
+    def run_composed(self, other: "PagedAttention", q, k_pool, v_pool, kv_indices, kv_indices_other, sm_scale: float,
+                     o=None, lse=None, o_cast=None):
+        """This handle's format and `other`'s over the same query rows, composed by one contraction launch
+        (fi_run_composed).  The per-pass state rows are kept on the handles between calls."""
+        torch = self.torch
+        nnz = q.shape[0]
+        for w in (self, other):
+            rows = getattr(w, "_pass_rows", None)
+            if rows is None or rows[0].shape[0] < nnz:
+                w._pass_rows = (torch.empty((nnz, self.num_qo_heads, self.head_dim), dtype=torch.float32, device=q.device),
+                                torch.empty((nnz, self.num_qo_heads), dtype=torch.float32, device=q.device))
+        if o is False:
+            assert o_cast is not None
+            o = None
+        elif o is None:
+            o = torch.empty((nnz, self.num_qo_heads, self.head_dim), dtype=torch.float32, device=q.device)
+        if lse is None:
+            lse = torch.empty((nnz, self.num_qo_heads), dtype=torch.float32, device=q.device)
+        strides = (k_pool.stride(0), k_pool.stride(1), k_pool.stride(2))
+        fi_run_composed(self.handle, other.handle, q, k_pool, v_pool, strides, kv_indices, kv_indices_other, sm_scale,
+                        self._pass_rows[0], self._pass_rows[1], other._pass_rows[0], other._pass_rows[1], nnz, o, lse,
+                        o_cast, self._stream())
         return (o_cast if o is None else o), lse

@@ -34,6 +34,7 @@ struct fi_handle {
   bool planned_host = false;
   bool planned_dev = false;
   bool pp_causal_last = false;  // `causal` of the last successful fi_plan
+  int64_t nnz_qo_last = 0;      // query rows of the last successful fi_plan
   void* workspace_dev = nullptr;
   size_t workspace_bytes = 0;
   hipEvent_t ev_before = nullptr;
@@ -150,6 +151,7 @@ int32_t fi_plan(fi_handle* h, const int32_t* qo_indptr, const int32_t* kv_indptr
   if (rc != FI_OK) return set_error(rc, err);
   h->planned_host = true;
   h->pp_causal_last = causal != 0;
+  h->nnz_qo_last = batch > 0 ? qo_indptr[batch] : 0;
   if (!workspace_dev) return FI_OK;
   const size_t bytes = h->layout.plan_ints * sizeof(int32_t);
   hipStream_t s = static_cast<hipStream_t>(stream);
@@ -216,7 +218,9 @@ namespace {
 int32_t run_impl(fi_handle* h, const void* q, const void* k_pool, const void* v_pool, const int64_t* kv_strides,
                  const int32_t* kv_indices, float sm_scale, bool kv8, float k_scale, float v_scale, float* o,
                  float* lse, void* o_cast, fi_stream stream, const fi_variant* variant = nullptr,
-                 const int32_t* kv_indptr_dev = nullptr, const int32_t* last_page_len_dev = nullptr) {
+                 const int32_t* kv_indptr_dev = nullptr, const int32_t* last_page_len_dev = nullptr,
+                 MergeParams* deferred = nullptr) {
+  // deferred != null: the contraction launch is left to the caller, who gets its parameters
   if (!h) return set_error(FI_ERR_INVALID_ARG, "fi_run: null handle");
   if (variant) {
     if (h->cfg.page_size != kPageSize)
@@ -333,6 +337,11 @@ int32_t run_impl(fi_handle* h, const void* q, const void* k_pool, const void* v_
   mp.num_qo_heads = h->cfg.num_qo_heads;
   mp.t_pos = h->pp.t_pos;
   mp.is_bf16 = bf ? 1 : 0;
+  mp.max_merge = L.max_merge;
+  if (deferred) {
+    *deferred = mp;
+    return FI_OK;
+  }
   e = launch_merge_planned(mp, kMergeGrid, s);
   if (e != hipSuccess) return hip_error("fi_run: merge launch", e);
   return FI_OK;
@@ -360,6 +369,48 @@ int32_t fi_run_kv8(fi_handle* h, const void* q, const void* k_pool, const void* 
                    void* o_cast, fi_stream stream) {
   return run_impl(h, q, k_pool, v_pool, kv_strides, kv_indices, sm_scale, true, k_scale, v_scale, o, lse, o_cast,
                   stream);
+}
+
+int32_t fi_run_composed(fi_handle* h_a, fi_handle* h_b, const void* q, const void* k_pool, const void* v_pool,
+                        const int64_t* kv_strides, const int32_t* kv_indices_a, const int32_t* kv_indices_b,
+                        float sm_scale, float* o_a, float* lse_a, float* o_b, float* lse_b, int64_t nnz_qo, float* o,
+                        float* lse, void* o_cast, fi_stream stream) {
+  if (!h_a || !h_b) return set_error(FI_ERR_INVALID_ARG, "fi_run_composed: null handle");
+  if (h_a == h_b) return set_error(FI_ERR_INVALID_ARG, "fi_run_composed: the two passes need a handle (and workspace) each");
+  if (h_a->cfg.dtype != h_b->cfg.dtype || h_a->cfg.num_qo_heads != h_b->cfg.num_qo_heads ||
+      h_a->cfg.num_kv_heads != h_b->cfg.num_kv_heads)
+    return set_error(FI_ERR_INVALID_ARG, "fi_run_composed: the two handles differ in dtype or head counts");
+  if (h_a->cfg.merge == 2 || h_b->cfg.merge == 2)
+    return set_error(FI_ERR_UNSUPPORTED, "fi_run_composed: handles with the contraction inside the attention launch (merge = 2)");
+  if (h_a->cfg.plan_window > 0 || h_b->cfg.plan_window > 0)
+    return set_error(FI_ERR_UNSUPPORTED, "fi_run_composed: handles that plan a sliding window");
+  if (!h_a->planned_dev || !h_b->planned_dev)
+    return set_error(FI_ERR_NOT_PLANNED, "fi_run_composed: call fi_plan with a device workspace on both handles first");
+  if (h_a->workspace_dev == h_b->workspace_dev)
+    return set_error(FI_ERR_INVALID_ARG, "fi_run_composed: the two passes share one workspace");
+  if (nnz_qo != h_a->nnz_qo_last || nnz_qo != h_b->nnz_qo_last)
+    return set_error(FI_ERR_INVALID_ARG, "fi_run_composed: both plans must cover the same nnz_qo query rows (" +
+                                             std::to_string(h_a->nnz_qo_last) + ", " + std::to_string(h_b->nnz_qo_last) +
+                                             " planned, " + std::to_string(nnz_qo) + " given)");
+  if (!o_a || !lse_a || !o_b || !lse_b || !lse || (!o && !o_cast))
+    return set_error(FI_ERR_INVALID_ARG, "fi_run_composed: null pointer");
+  if (o_a == o_b || lse_a == lse_b) return set_error(FI_ERR_INVALID_ARG, "fi_run_composed: the passes need state rows of their own");
+  if ((reinterpret_cast<uintptr_t>(o) | reinterpret_cast<uintptr_t>(o_cast)) & 15)
+    return set_error(FI_ERR_INVALID_ARG, "fi_run_composed: o, o_cast must be 16-byte aligned");
+  ComposeParams cp{};
+  int32_t rc = run_impl(h_a, q, k_pool, v_pool, kv_strides, kv_indices_a, sm_scale, false, 1.f, 1.f, o_a, lse_a, nullptr,
+                        stream, nullptr, nullptr, nullptr, &cp.a);
+  if (rc != FI_OK) return rc;
+  rc = run_impl(h_b, q, k_pool, v_pool, kv_strides, kv_indices_b, sm_scale, false, 1.f, 1.f, o_b, lse_b, nullptr, stream,
+                nullptr, nullptr, nullptr, &cp.b);
+  if (rc != FI_OK) return rc;
+  cp.o = o;
+  cp.lse = lse;
+  cp.o_cast = o_cast;
+  cp.nnz_qo = nnz_qo;
+  const hipError_t e = launch_compose(cp, static_cast<hipStream_t>(stream));
+  if (e != hipSuccess) return hip_error("fi_run_composed: contraction launch", e);
+  return FI_OK;
 }
 
 int32_t fi_set_timing_events(fi_handle* h, void* before, void* after) {

@@ -67,6 +67,16 @@ struct MergeParams {
   float* lse;
   void* o_cast;
   int32_t num_qo_heads, t_pos, is_bf16;
+  int32_t max_merge;  // entries the merge list arrays hold (readable past n_merge)
+};
+
+// Two passes over the same query rows: a.o / a.lse (b.o / b.lse) hold the states of the pass's unsplit tiles.
+struct ComposeParams {
+  MergeParams a, b;
+  float* o;  // may be null when o_cast is not
+  float* lse;
+  void* o_cast;
+  int64_t nnz_qo;
 };
 
 // decode.hip: query tile = 1 position x g fused heads, one wavefront per CTA.
@@ -84,6 +94,7 @@ hipError_t launch_plan_upload(const int32_t* staging_dev_view, int32_t* plan_sec
                               hipStream_t stream);
 // merge.hip
 hipError_t launch_merge_planned(const MergeParams& p, int32_t grid, hipStream_t stream);
+hipError_t launch_compose(const ComposeParams& p, hipStream_t stream);
 hipError_t launch_merge_states(const float* o_parts, const float* lse_parts, int64_t n_rows, int32_t n_states,
                                float* o, float* lse, hipStream_t stream);
 hipError_t launch_merge_pair(const float* o_a, const float* lse_a, const float* o_b, const float* lse_b,

@@ -88,6 +88,121 @@ __device__ __forceinline__ void fold_row(const float* lse_ptr, int64_t lse_strid
   }
 }
 
+// ---- fold_row by a single wavefront.  The same sums in the same order (eight contiguous ranges of states, each
+// folded in ascending order, the range sums added in ascending order: a running sum per range that is added to
+// the total when the next range starts), so the result is bit-identical to fold_row's; no LDS, no barriers, and
+// all loads of the row's states go out at once.
+
+// The loads of up to T states of a row (n >= 1; indices past n - 1 re-read the last state), issued back to back.
+template <int T>
+struct RowStates {
+  float l_raw;  // lse of state min(lane, n - 1)
+  f32x2_t v[T];
+};
+template <int T>
+__device__ __forceinline__ void load_states(RowStates<T>* rs, const float* lse_ptr, int64_t lse_stride, const float* o_ptr,
+                                            int64_t o_stride, int n, int lane) {
+  rs->l_raw = lse_ptr[min(lane, n - 1) * lse_stride];
+#pragma unroll
+  for (int u = 0; u < T; ++u)
+    rs->v[u] = *reinterpret_cast<const f32x2_t*>(o_ptr + min(u, n - 1) * o_stride + 2 * lane);
+}
+template <int T>
+__device__ __forceinline__ void reduce_states(const RowStates<T>& rs, int n, int lane, f32x2_t* o_out, float* lse_out) {
+  const float NEG_INF = -__builtin_inff();
+  const float l_mine = lane < n ? rs.l_raw : NEG_INF;
+  float mx = l_mine;
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off));
+  const float mx_safe = (mx == NEG_INF) ? 0.f : mx;
+  const float w_mine = lane < n ? __builtin_amdgcn_exp2f((l_mine - mx_safe) * kLog2e) : 0.f;
+  const int per = (n + kMergeWaves - 1) / kMergeWaves;
+  int next = per;  // first state of the next range
+  f32x2_t tot = {0.f, 0.f}, cur = {0.f, 0.f};
+  float dtot = 0.f, dcur = 0.f;
+#pragma unroll
+  for (int u = 0; u < T; ++u) {
+    if (u < n) {  // wavefront-uniform
+      if (u == next) {
+        tot += cur;
+        dtot += dcur;
+        cur = f32x2_t{0.f, 0.f};
+        dcur = 0.f;
+        next += per;
+      }
+      const float w = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, w_mine), u));
+      if (w != 0.f) {  // an empty state contributes nothing, whatever rides on it
+        cur += w * rs.v[u];
+        dcur += w;
+      }
+    }
+  }
+  tot += cur;
+  dtot += dcur;
+  if (dtot > 0.f) {
+    const float inv = 1.0f / dtot;
+    *o_out = tot * inv;
+    *lse_out = mx_safe + __builtin_amdgcn_logf(dtot) * kLn2;
+  } else {
+    *o_out = f32x2_t{0.f, 0.f};
+    *lse_out = NEG_INF;
+  }
+}
+
+// Any number of states, 32 loads in flight at a time.
+__device__ __forceinline__ void fold_row_wave(const float* lse_ptr, int64_t lse_stride, const float* o_ptr,
+                                              int64_t o_stride, int n, int lane, f32x2_t* o_out, float* lse_out) {
+  const float NEG_INF = -__builtin_inff();
+  float mx = NEG_INF;
+  for (int s = lane; s < n; s += 64) mx = fmaxf(mx, lse_ptr[s * lse_stride]);
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off));
+  const float mx_safe = (mx == NEG_INF) ? 0.f : mx;
+  const int per = (n + kMergeWaves - 1) / kMergeWaves;
+  int next = per;
+  f32x2_t tot = {0.f, 0.f}, cur = {0.f, 0.f};
+  float dtot = 0.f, dcur = 0.f;
+  for (int s0 = 0; s0 < n; s0 += 64) {
+    const float w_mine =
+        (s0 + lane < n) ? __builtin_amdgcn_exp2f((lse_ptr[(s0 + lane) * lse_stride] - mx_safe) * kLog2e) : 0.f;
+    const int cnt = min(64, n - s0);
+    for (int j0 = 0; j0 < cnt; j0 += 32) {
+      f32x2_t v[32];
+#pragma unroll
+      for (int u = 0; u < 32; ++u)
+        v[u] = *reinterpret_cast<const f32x2_t*>(o_ptr + min(s0 + j0 + u, n - 1) * o_stride + 2 * lane);
+#pragma unroll
+      for (int u = 0; u < 32; ++u) {
+        const int st = s0 + j0 + u;
+        if (st < n) {
+          if (st == next) {
+            tot += cur;
+            dtot += dcur;
+            cur = f32x2_t{0.f, 0.f};
+            dcur = 0.f;
+            next += per;
+          }
+          const float w = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, w_mine), (j0 + u) & 63));
+          if (w != 0.f) {
+            cur += w * v[u];
+            dcur += w;
+          }
+        }
+      }
+    }
+  }
+  tot += cur;
+  dtot += dcur;
+  if (dtot > 0.f) {
+    const float inv = 1.0f / dtot;
+    *o_out = tot * inv;
+    *lse_out = mx_safe + __builtin_amdgcn_logf(dtot) * kLn2;
+  } else {
+    *o_out = f32x2_t{0.f, 0.f};
+    *lse_out = NEG_INF;
+  }
+}
+
 __device__ __forceinline__ void store_cast(void* o_cast, int64_t row, int lane, f32x2_t v, int is_bf16) {
   uint32_t* dst = static_cast<uint32_t*>(o_cast) + row * (kHeadDim / 2) + lane;
   if (is_bf16) {
@@ -99,8 +214,16 @@ __device__ __forceinline__ void store_cast(void* o_cast, int64_t row, int lane, 
   }
 }
 
+__device__ __forceinline__ void planned_store(const MergeParams& p, int64_t out_row, int lane, f32x2_t o2, float l) {
+  if (p.o != nullptr) *reinterpret_cast<f32x2_t*>(p.o + out_row * kHeadDim + 2 * lane) = o2;
+  if (lane == 0) p.lse[out_row] = l;
+  if (p.o_cast != nullptr) store_cast(p.o_cast, out_row, lane, o2, p.is_bf16);
+}
+
 // Fixed grid; the number of split tiles is read from the plan header on the device.
-// One CTA (kMergeWaves wavefronts) per output row, grid-stride over rows.
+// One CTA (kMergeWaves wavefronts) per output row, grid-stride over rows.  (One row per wavefront with all of
+// its loads in flight at once is not faster here, neither with eight consecutive rows per CTA nor with the
+// rows dealt out over the CTAs: measured 2-4 us slower on batches of 16 requests, 1-2 us on the large ones.)
 __global__ void __launch_bounds__(64 * kMergeWaves) merge_planned_kernel(const MergeParams p) {
   __shared__ float red_acc[kMergeWaves * kHeadDim];
   __shared__ float red_den[kMergeWaves];
@@ -123,12 +246,7 @@ __global__ void __launch_bounds__(64 * kMergeWaves) merge_planned_kernel(const M
     float l;
     fold_row(p.part_lse + slot_row0, slot_stride, p.part_o + slot_row0 * kHeadDim, slot_stride * kHeadDim, n, wave,
              lane, red_acc, red_den, &o2, &l);
-    if (wave == 0) {
-      const int64_t out_row = (static_cast<int64_t>(p.m_q_row0[mt]) + pos) * H + head;
-      if (p.o != nullptr) *reinterpret_cast<f32x2_t*>(p.o + out_row * kHeadDim + 2 * lane) = o2;
-      if (lane == 0) p.lse[out_row] = l;
-      if (p.o_cast != nullptr) store_cast(p.o_cast, out_row, lane, o2, p.is_bf16);
-    }
+    if (wave == 0) planned_store(p, (static_cast<int64_t>(p.m_q_row0[mt]) + pos) * H + head, lane, o2, l);
   }
 }
 
@@ -151,9 +269,128 @@ __global__ void __launch_bounds__(64 * kMergeWaves) merge_states_kernel(const fl
   }
 }
 
+// Merge of two states (Sec. 2.2) for this lane's two columns.
+__device__ __forceinline__ void merge_two(float la, f32x2_t va, float lb, f32x2_t vb, f32x2_t* res_out, float* l_out) {
+  const float NEG_INF = -__builtin_inff();
+  const float mx = fmaxf(la, lb);
+  f32x2_t res = {0.f, 0.f};
+  float l = NEG_INF;
+  if (mx != NEG_INF) {
+    const float wa = __builtin_amdgcn_exp2f((la - mx) * kLog2e);
+    const float wb = __builtin_amdgcn_exp2f((lb - mx) * kLog2e);
+    const float den = wa + wb;
+    const float inv = 1.0f / den;
+    if (wa != 0.f) res += (wa * inv) * va;
+    if (wb != 0.f) res += (wb * inv) * vb;
+    l = mx + __builtin_amdgcn_logf(den) * kLn2;
+  }
+  *res_out = res;
+  *l_out = l;
+}
+
+// Where the states of one pass for output row (pos, head) are: the partial states of the split tile of that
+// pass's plan that holds the position, else the one row the attention kernel wrote (a single state, which folds
+// to itself).  The first 64 entries of the merge list are read one per lane together with the header.
+struct StateRun {
+  const float* lse_ptr;
+  const float* o_ptr;
+  int64_t lse_stride, o_stride;
+  int n;
+};
+__device__ __forceinline__ StateRun find_states(const MergeParams& m, int pos, int head, int lane) {
+  const int n_merge = m.header[H_N_MERGE];
+  const int mine = min(lane, m.max_merge - 1);
+  int q0 = m.m_q_row0[mine], np = m.m_n_pos[mine], nc = m.m_n_chunks[mine], sb = m.m_slot_base[mine];
+  int found_lane = -1;
+  uint64_t mask = __ballot(lane < n_merge && pos >= q0 && pos < q0 + np);
+  if (mask != 0) {
+    found_lane = __builtin_ctzll(mask);
+  } else {
+    for (int base = 64; base < n_merge && found_lane < 0; base += 64) {
+      const int mt = min(base + lane, m.max_merge - 1);
+      q0 = m.m_q_row0[mt], np = m.m_n_pos[mt], nc = m.m_n_chunks[mt], sb = m.m_slot_base[mt];
+      mask = __ballot(base + lane < n_merge && pos >= q0 && pos < q0 + np);
+      if (mask != 0) found_lane = __builtin_ctzll(mask);
+    }
+  }
+  const int H = m.num_qo_heads;
+  StateRun run;
+  if (found_lane >= 0) {
+    const int f_q0 = __builtin_amdgcn_readlane(q0, found_lane);
+    const int f_sb = __builtin_amdgcn_readlane(sb, found_lane);
+    run.n = __builtin_amdgcn_readlane(nc, found_lane);
+    const int64_t slot_row0 = (static_cast<int64_t>(f_sb) * m.t_pos + (pos - f_q0)) * H + head;
+    run.lse_stride = static_cast<int64_t>(m.t_pos) * H;
+    run.o_stride = run.lse_stride * kHeadDim;
+    run.lse_ptr = m.part_lse + slot_row0;
+    run.o_ptr = m.part_o + slot_row0 * kHeadDim;
+  } else {
+    const int64_t r = static_cast<int64_t>(pos) * H + head;
+    run.n = 1;
+    run.lse_stride = 0;
+    run.o_stride = 0;
+    run.lse_ptr = m.lse + r;
+    run.o_ptr = m.o + r * kHeadDim;
+  }
+  return run;
+}
+
+template <int T>
+__device__ __forceinline__ void compose_row_alone(const StateRun& a, const StateRun& b, int lane, f32x2_t* oa, float* la,
+                                                  f32x2_t* ob, float* lb) {
+  RowStates<T> ra, rb;  // the loads of both passes go out before either is reduced
+  load_states<T>(&ra, a.lse_ptr, a.lse_stride, a.o_ptr, a.o_stride, a.n, lane);
+  load_states<T>(&rb, b.lse_ptr, b.lse_stride, b.o_ptr, b.o_stride, b.n, lane);
+  reduce_states<T>(ra, a.n, lane, oa, la);
+  reduce_states<T>(rb, b.n, lane, ob, lb);
+}
+
+__device__ __forceinline__ void compose_store(const ComposeParams& p, int64_t r, int lane, float la, f32x2_t oa, float lb,
+                                              f32x2_t ob) {
+  f32x2_t res;
+  float l;
+  merge_two(la, oa, lb, ob, &res, &l);
+  if (p.o != nullptr) *reinterpret_cast<f32x2_t*>(p.o + r * kHeadDim + 2 * lane) = res;
+  if (lane == 0) p.lse[r] = l;
+  if (p.o_cast != nullptr) store_cast(p.o_cast, r, lane, res, p.a.is_bf16);
+}
+
+// Composition of two passes over the same query rows (Sec. 3.1.2) in one launch: per output row the state of
+// pass a and the state of pass b, each folded from its partial states where its tile was split, then merged.
+// The arithmetic is that of the two contraction launches followed by the two-state merge.  One row per
+// wavefront (eight consecutive rows per CTA), no barriers; the loads of both passes' states go out together.
+__global__ void __launch_bounds__(64 * kMergeWaves) compose_kernel(const ComposeParams p) {
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int H = p.a.num_qo_heads;
+  const int64_t total = p.nnz_qo * H;
+  for (int64_t r = static_cast<int64_t>(blockIdx.x) * kMergeWaves + wave; r < total;
+       r += static_cast<int64_t>(gridDim.x) * kMergeWaves) {
+    const int pos = static_cast<int>(r / H);
+    const int head = static_cast<int>(r % H);
+    const StateRun a = find_states(p.a, pos, head, lane);
+    const StateRun b = find_states(p.b, pos, head, lane);
+    f32x2_t oa, ob;
+    float la, lb;
+    const int n = max(a.n, b.n);
+    if (n <= 4) {
+      compose_row_alone<4>(a, b, lane, &oa, &la, &ob, &lb);
+    } else if (n <= 8) {
+      compose_row_alone<8>(a, b, lane, &oa, &la, &ob, &lb);
+    } else if (n <= 16) {
+      compose_row_alone<16>(a, b, lane, &oa, &la, &ob, &lb);
+    } else if (n <= 32) {
+      compose_row_alone<32>(a, b, lane, &oa, &la, &ob, &lb);
+    } else {
+      fold_row_wave(a.lse_ptr, a.lse_stride, a.o_ptr, a.o_stride, a.n, lane, &oa, &la);
+      fold_row_wave(b.lse_ptr, b.lse_stride, b.o_ptr, b.o_stride, b.n, lane, &ob, &lb);
+    }
+    compose_store(p, r, lane, la, oa, lb, ob);
+  }
+}
+
 __global__ void __launch_bounds__(256) merge_pair_kernel(const float* o_a, const float* lse_a, const float* o_b,
                                                          const float* lse_b, int64_t n_rows, float* o, float* lse) {
-  const float NEG_INF = -__builtin_inff();
   const int lane = threadIdx.x & 63;
   const int64_t wave = static_cast<int64_t>(blockIdx.x) * 4 + (threadIdx.x >> 6);
   const int64_t n_waves = static_cast<int64_t>(gridDim.x) * 4;
@@ -161,18 +398,9 @@ __global__ void __launch_bounds__(256) merge_pair_kernel(const float* o_a, const
     const float la = lse_a[r], lb = lse_b[r];
     const f32x2_t va = *reinterpret_cast<const f32x2_t*>(o_a + r * kHeadDim + 2 * lane);
     const f32x2_t vb = *reinterpret_cast<const f32x2_t*>(o_b + r * kHeadDim + 2 * lane);
-    const float mx = fmaxf(la, lb);
-    f32x2_t res = {0.f, 0.f};
-    float l = NEG_INF;
-    if (mx != NEG_INF) {
-      const float wa = __builtin_amdgcn_exp2f((la - mx) * kLog2e);
-      const float wb = __builtin_amdgcn_exp2f((lb - mx) * kLog2e);
-      const float den = wa + wb;
-      const float inv = 1.0f / den;
-      if (wa != 0.f) res += (wa * inv) * va;
-      if (wb != 0.f) res += (wb * inv) * vb;
-      l = mx + __builtin_amdgcn_logf(den) * kLn2;
-    }
+    f32x2_t res;
+    float l;
+    merge_two(la, va, lb, vb, &res, &l);
     *reinterpret_cast<f32x2_t*>(o + r * kHeadDim + 2 * lane) = res;
     if (lane == 0) lse[r] = l;
   }
@@ -189,6 +417,15 @@ int grid_for_rows(int64_t n_rows) {
 
 hipError_t launch_merge_planned(const MergeParams& p, int32_t grid, hipStream_t stream) {
   hipLaunchKernelGGL(merge_planned_kernel, dim3(grid), dim3(64 * kMergeWaves), 0, stream, p);
+  return hipGetLastError();
+}
+
+hipError_t launch_compose(const ComposeParams& p, hipStream_t stream) {
+  const int64_t rows = p.nnz_qo * p.a.num_qo_heads;
+  if (rows == 0) return hipSuccess;
+  int64_t blocks = (rows + kMergeWaves - 1) / kMergeWaves;
+  if (blocks > 8192) blocks = 8192;
+  hipLaunchKernelGGL(compose_kernel, dim3(static_cast<unsigned>(blocks)), dim3(64 * kMergeWaves), 0, stream, p);
   return hipGetLastError();
 }
 

@@ -1,0 +1,109 @@
+"""GPU parity for fi_run_composed (Sec. 3.1.2 composable formats, Sec. 2.2 merge): two planned passes over the
+same query rows and one contraction launch.  Checked against the oracle on the single-format problem and, bit for
+bit, against fi_run on each handle followed by fi_merge_state_pair."""
+import numpy as np
+import pytest
+
+import oracle
+import workloads
+from gpu_util import DeviceBatch, assert_close, make_wrapper
+
+pytestmark = pytest.mark.gpu
+
+
+def separate(wa, wb, dev_a, dev_b, sm_scale):
+    import torch
+    import paper_2501_01005_amd as fi
+    o_a, l_a = wa.run(dev_a.q, dev_a.k_pool, dev_a.v_pool, dev_a.kv_indices, sm_scale)
+    o_b, l_b = wb.run(dev_b.q, dev_b.k_pool, dev_b.v_pool, dev_b.kv_indices, sm_scale)
+    o = torch.empty_like(o_a); l = torch.empty_like(l_a)
+    fi.fi_merge_state_pair(o_a, l_a, o_b, l_b, l_a.numel(), 128, o, l, torch.cuda.current_stream().cuda_stream)
+    return o, l
+
+
+@pytest.mark.parametrize("kw_p,kw_s", [(dict(min_chunk=64), dict(min_chunk=32)),        # split tiles in both passes
+                                       (dict(min_chunk=4096), dict(num_ctas=8, min_chunk=4096)),   # none split
+                                       (dict(min_chunk=64), dict(num_ctas=8, min_chunk=4096))])
+def test_shared_prefix_in_three_launches(kw_p, kw_s):
+    import torch
+    c = workloads.config5(small=True)
+    print(f"[case] c5 small composed: prefix {kw_p} suffix {kw_s}", flush=True)
+    o_ref, lse_ref = oracle.run_batch(c.single)
+    dev_p, dev_s = DeviceBatch(c.prefix), DeviceBatch(c.suffix)
+    wp = make_wrapper(c.prefix, "append", **kw_p)
+    ws = make_wrapper(c.suffix, "decode", **kw_s)
+    wp.plan(c.prefix.qo_indptr, c.prefix.kv_indptr, c.prefix.last_page_len, causal=False)
+    ws.plan(c.suffix.qo_indptr, c.suffix.kv_indptr, c.suffix.last_page_len, causal=False)
+    o_sep, l_sep = separate(wp, ws, dev_p, dev_s, c.prefix.sm_scale)
+    for first, second, ia, ib in ((wp, ws, dev_p.kv_indices, dev_s.kv_indices), (ws, wp, dev_s.kv_indices, dev_p.kv_indices)):
+        o = torch.full_like(o_sep, float("nan")); l = torch.full_like(l_sep, float("nan"))
+        oc = torch.zeros(o.shape, dtype=dev_p.q.dtype, device=o.device)
+        first.run_composed(second, dev_p.q, dev_p.k_pool, dev_p.v_pool, ia, ib, c.prefix.sm_scale, o=o, lse=l, o_cast=oc)
+        torch.cuda.synchronize()
+        e = assert_close(o.double().cpu().numpy(), l.double().cpu().numpy(), o_ref, lse_ref, "c5 composed in one contraction")
+        if first is wp:
+            assert torch.equal(o.view(torch.int32), o_sep.view(torch.int32)) and torch.equal(l.view(torch.int32), l_sep.view(torch.int32))
+        assert torch.equal(oc.view(torch.int16), o.to(oc.dtype).view(torch.int16))
+        # the rounded rows alone
+        oc2 = torch.zeros_like(oc); l2 = torch.full_like(l, float("nan"))
+        first.run_composed(second, dev_p.q, dev_p.k_pool, dev_p.v_pool, ia, ib, c.prefix.sm_scale, o=False, lse=l2, o_cast=oc2)
+        torch.cuda.synchronize()
+        assert torch.equal(oc2.view(torch.int16), oc.view(torch.int16)) and torch.equal(l2.view(torch.int32), l.view(torch.int32))
+        print(f"[ok] c5 small composed: err_o={e[0]:.2e} err_lse={e[1]:.2e}", flush=True)
+    view_p = __import__("paper_2501_01005_amd").fi_plan_view(wp.handle)
+    assert (int(view_p["n_merge"]) > 0) == (kw_p["min_chunk"] == 64)
+    wp.close(); ws.close()
+
+
+@pytest.mark.parametrize("dtype", [workloads.BF16, workloads.F16])
+def test_two_decode_passes_over_halves_of_the_cache(dtype):
+    """Each request's pages cut in two formats (the first k pages, the rest); requests whose second part is empty
+    contribute the identity state there; long parts are split into chunks, short ones are not."""
+    import torch
+    kv = [3000, 700, 40, 16, 1, 333]
+    cut_pages = [100, 20, 1, 1, 1, 0]          # pages of each request that go to the first format
+    b = workloads.make_batch("halves", 400, dtype, 8, 2, 128, 16, [1] * len(kv), kv, False)
+    o_ref, lse_ref = oracle.run_batch(b)
+    ia, ib, pa, pb, la, lb = [], [], [0], [0], [], []
+    for r in range(b.batch):
+        pages = b.kv_indices[b.kv_indptr[r]:b.kv_indptr[r + 1]]
+        k = min(cut_pages[r], len(pages))
+        ia.append(pages[:k]); ib.append(pages[k:])
+        pa.append(pa[-1] + k); pb.append(pb[-1] + len(pages) - k)
+        # a format that holds the request's last page inherits its fill; full pages elsewhere
+        la.append(int(b.last_page_len[r]) if k == len(pages) and k > 0 else (16 if k > 0 else 1))
+        lb.append(int(b.last_page_len[r]) if len(pages) > k else 1)
+    print(f"[case] two decode formats: dtype={dtype} kv={kv} first-format pages={cut_pages}", flush=True)
+    dev = DeviceBatch(b)
+    idx_a = torch.from_numpy(np.concatenate(ia).astype(np.int32)).to(dev.device)
+    idx_b = torch.from_numpy(np.concatenate(ib).astype(np.int32)).to(dev.device)
+    wa = make_wrapper(b, "decode", min_chunk=32)
+    wb = make_wrapper(b, "decode", min_chunk=64)
+    wa.plan(b.qo_indptr, np.asarray(pa, dtype=np.int32), np.asarray(la, dtype=np.int32), causal=False)
+    wb.plan(b.qo_indptr, np.asarray(pb, dtype=np.int32), np.asarray(lb, dtype=np.int32), causal=False)
+    for rep in range(2):
+        o, l = wa.run_composed(wb, dev.q, dev.k_pool, dev.v_pool, idx_a, idx_b, b.sm_scale)
+        torch.cuda.synchronize()
+        e = assert_close(o.double().cpu().numpy(), l.double().cpu().numpy(), o_ref, lse_ref, f"two formats rep {rep}")
+    print(f"[ok] two decode formats: err_o={e[0]:.2e} err_lse={e[1]:.2e}", flush=True)
+    wa.close(); wb.close()
+
+
+def test_composed_argument_errors():
+    import torch
+    import paper_2501_01005_amd as fi
+    b = workloads.make_batch("cerr", 410, workloads.BF16, 8, 2, 128, 16, [1, 1], [40, 20], False)
+    b3 = workloads.make_batch("cerr3", 411, workloads.BF16, 8, 2, 128, 16, [1, 1, 1], [40, 20, 16], False)
+    dev = DeviceBatch(b)
+    wa, wb, wc = make_wrapper(b, "decode"), make_wrapper(b, "decode"), make_wrapper(b3, "decode")
+    for w, x in ((wa, b), (wb, b), (wc, b3)):
+        w.plan(x.qo_indptr, x.kv_indptr, x.last_page_len, causal=False)
+    with pytest.raises(fi.Fi355Error) as ei:
+        wa.run_composed(wa, dev.q, dev.k_pool, dev.v_pool, dev.kv_indices, dev.kv_indices, b.sm_scale)
+    assert ei.value.code == fi.FI_ERR_INVALID_ARG
+    with pytest.raises(fi.Fi355Error) as ei:   # the plans cover 2 and 3 query rows
+        wa.run_composed(wc, dev.q, dev.k_pool, dev.v_pool, dev.kv_indices, dev.kv_indices, b.sm_scale)
+    assert ei.value.code == fi.FI_ERR_INVALID_ARG and "query rows" in ei.value.message
+    torch.cuda.synchronize()
+    for w in (wa, wb, wc):
+        w.close()

@@ -73,6 +73,10 @@ def test_config5_full_shared_prefix():
                            torch.cuda.current_stream().cuda_stream)
     torch.cuda.synchronize()
     e = assert_close(o_p.double().cpu().numpy(), l_p.double().cpu().numpy(), o_ref, lse_ref, "c5 composed")
+    # the same composition with one contraction launch for both passes: the same bits
+    o_c, l_c = wp.run_composed(ws, dev_p.q, dev_p.k_pool, dev_p.v_pool, dev_p.kv_indices, dev_s.kv_indices, c.prefix.sm_scale)
+    torch.cuda.synchronize()
+    assert torch.equal(o_c.view(torch.int32), o_p.view(torch.int32)) and torch.equal(l_c.view(torch.int32), l_p.view(torch.int32))
     o1, l1 = run_gpu(c.single, "decode")
     e1 = assert_close(o1, l1, o_ref, lse_ref, "c5 single")
     print(f"[ok] c5 full: composed err_o={e[0]:.2e} err_lse={e[1]:.2e}; single err_o={e1[0]:.2e}", flush=True)

@@ -20,7 +20,7 @@ def test_library_exports_every_declared_symbol():
     header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
     names = set(re.findall(r"\b(fi_[a-z0-9_]+)\s*\(", header))
     assert {"fi_create", "fi_destroy", "fi_workspace_bytes", "fi_plan", "fi_plan_view", "fi_run", "fi_run_kv8", "fi_run_variant",
-            "fi_merge_states", "fi_merge_state_pair", "fi_check_indices", "fi_set_timing_events",
+            "fi_run_composed", "fi_merge_states", "fi_merge_state_pair", "fi_check_indices", "fi_set_timing_events",
             "fi_last_error"} <= names
     L = ctypes.CDLL(fi.library_path())
     for n in names:
