@@ -124,7 +124,7 @@ def bench_shared_prefix(args) -> int:
     c = workloads.config5(small=args.small)
     dev_p, dev_s, dev_1 = DeviceBatch(c.prefix), DeviceBatch(c.suffix), DeviceBatch(c.single)
     wp = make_wrapper(c.prefix, "append", num_ctas=args.num_ctas, min_chunk=args.min_chunk)
-    ws = make_wrapper(c.suffix, "decode", merge=args.merge)
+    ws = make_wrapper(c.suffix, "decode", merge=args.merge, min_chunk=args.suffix_min_chunk)
     w1 = make_wrapper(c.single, "decode", merge=args.merge)
     n, H, D = dev_p.q.shape[0], c.prefix.num_qo_heads, c.prefix.head_dim
     o_p = torch.empty((n, H, D), dtype=torch.float32, device="cuda:0"); l_p = torch.empty((n, H), dtype=torch.float32, device="cuda:0")
@@ -257,6 +257,7 @@ def main() -> int:
     ap.add_argument("--merge", type=int, default=0,
                     help="fi_config.merge: 1 = partial states folded by a second launch, 2 = inside the attention launch "
                          "(decode), 0 = default")
+    ap.add_argument("--suffix-min-chunk", type=int, default=0, help="c5: fi_config.min_chunk of the suffix (decode) handle")
     ap.add_argument("--separate-merges", action="store_true",
                     help="c5: fi_run on each format and fi_merge_state_pair (five launches) instead of fi_run_composed (three)")
     ap.add_argument("--out16", action="store_true",

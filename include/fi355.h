@@ -84,7 +84,11 @@ typedef struct fi_config {
                            least-loaded CTA first).  2: the same, then items are moved or swapped
                            out of the most loaded CTA while that lowers the maximum; in append mode
                            a tile of at most half the fused rows counts 64 % of its per-token cost
-                           (it leaves wavefronts idle).  0: default = 1 for decode, 2 for append   */
+                           (it leaves wavefronts idle).  0: default = 2 for append; for decode 1,
+                           except that in a batch so small that Algorithm 1's chunk length is at
+                           most 256 tokens a chunk length up to twice that is taken when it lowers
+                           ceil(#chunks / #CTA) * (64 + chunk length): a work item has a fixed cost,
+                           and a slightly longer chunk can save every CTA a second item            */
   int32_t merge;        /* where the partial states of split tiles are contracted (Sec. 3.3.1: the paper
                            fuses the contraction into the attention launch).  1: in a second launch.
                            2: in the attention launch: the CTA that delivers a tile's last partial

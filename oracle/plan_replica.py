@@ -64,7 +64,8 @@ def plan_replica(qo_indptr: Sequence[int], kv_indptr: Sequence[int], last_page_l
                  *, page_size: int, t_pos: int, group: int, num_ctas: int, causal: bool,
                  alpha: int = 1, beta: int = 1, min_chunk: int | None = None,
                  literal_lkv: bool = False, refine: bool = False, light_rows: int = 0,
-                 light_pct: int = 100, kv_quantum: int = 1, plan_window: int = 0) -> Dict[str, object]:
+                 light_pct: int = 100, kv_quantum: int = 1, plan_window: int = 0,
+                 item_cost: int = 0) -> Dict[str, object]:
     B = len(last_page_len)
     if min_chunk is None:
         min_chunk = page_size
@@ -106,6 +107,19 @@ def plan_replica(qo_indptr: Sequence[int], kv_indptr: Sequence[int], last_page_l
     L_kv = -(-S // num_ctas)
     L_kv = ((L_kv + page_size - 1) // page_size) * page_size
     L_kv = max(min_chunk, L_kv)
+    # fixed cost per work item (not in the paper's algorithm): in a batch so small that the chunk length is at most
+    # 4 * item_cost tokens, a longer chunk (up to twice, whole pages) is taken when it lowers
+    # ceil(#chunks / #CTA) * (item_cost + L); ties keep the shorter chunk
+    if item_cost > 0 and L_kv <= 4 * item_cost:
+        def estimate(length):
+            n = sum(max(1, -(-(t[3] - t[5]) // length)) for t in tiles)
+            return -(-n // num_ctas) * (item_cost + length)
+        best, best_est = L_kv, estimate(L_kv)
+        for length in range(L_kv + page_size, 2 * L_kv + 1, page_size):
+            est = estimate(length)
+            if est < best_est:
+                best, best_est = length, est
+        L_kv = best
 
     # -- split ---------------------------------------------------------------
     work = []         # per w: dict

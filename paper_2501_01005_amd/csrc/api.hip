@@ -101,6 +101,8 @@ int32_t fi_create(const fi_config* cfg, fi_handle** out) {
   // 128 fused rows (at most one live wavefront per SIMD), i.e. alpha : beta = 8 : 5 with T_q = 256.
   pp.plan_window = cfg->plan_window;
   pp.refine = cfg->balance == 2 || (cfg->balance == 0 && cfg->mode == FI_MODE_APPEND);
+  // decode: a work item costs a wavefront about as much as 64 more tokens before its first tile arrives
+  pp.item_cost = (cfg->balance == 0 && cfg->mode == FI_MODE_DECODE) ? 64 : 0;
   const bool default_cost = cfg->alpha == 0 && cfg->beta == 0;
   pp.alpha = default_cost ? (pp.refine && cfg->mode == FI_MODE_APPEND ? 8 : 1) : cfg->alpha;
   pp.beta = default_cost ? (pp.refine && cfg->mode == FI_MODE_APPEND ? 5 : 1) : cfg->beta;

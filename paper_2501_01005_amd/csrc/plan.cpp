@@ -151,6 +151,22 @@ int32_t make_plan(const PlanParams& pp, const WorkspaceLayout& L, const int32_t*
   int64_t Lkv = (S + C - 1) / C;
   Lkv = (Lkv + ps - 1) / ps * ps;
   Lkv = std::max(min_chunk, Lkv);
+  if (pp.item_cost > 0 && Lkv <= 4 * static_cast<int64_t>(pp.item_cost)) {
+    auto estimate = [&](int64_t len) {
+      int64_t n = 0;
+      for (const Tile& tl : tiles) n += std::max<int64_t>(1, (tl.kv_eff - tl.kv_begin + len - 1) / len);
+      return (n + C - 1) / C * (pp.item_cost + len);
+    };
+    int64_t best = Lkv, best_est = estimate(Lkv);
+    for (int64_t len = Lkv + ps; len <= 2 * Lkv; len += ps) {
+      const int64_t est = estimate(len);
+      if (est < best_est) {
+        best = len;
+        best_est = est;
+      }
+    }
+    Lkv = best;
+  }
 
   // ---- split every tile's KV range into chunks of at most L_kv; number the chunks ----
   std::vector<Chunk>& chunks = scratch.chunks;

@@ -63,6 +63,11 @@ struct PlanParams {
   // Sliding window: > 0 = W + 1, a query at position pos sees keys pos - W .. pos only, and the keys that no row
   // of a tile sees (before its first row's window, rounded down to a page) are left out of the tile's KV range.
   int32_t plan_window = 0;
+  // Fixed cost of a work item in tokens (0 = off, the chunk length as printed).  When the chunk length of
+  // Algorithm 1 is at most 4 * item_cost (a batch so small that a CTA gets about one short chunk), chunk lengths
+  // L up to twice that, in whole pages, are tried and the one with the smallest ceil(#chunks / #CTA) * (item_cost + L)
+  // is taken (ties: the shorter): a slightly longer chunk can save every CTA a second work item.
+  int32_t item_cost = 0;
 };
 
 // Runs the partition and writes the plan section (header, queues, work items, merge list)

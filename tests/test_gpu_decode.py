@@ -87,7 +87,7 @@ def test_plan_on_device_box_equals_replica_with_default_grid():
     w.plan(b.qo_indptr, b.kv_indptr, b.last_page_len, causal=False)
     got = fi.fi_plan_view(w.handle)
     want = plan_replica(b.qo_indptr, b.kv_indptr, b.last_page_len, page_size=16, t_pos=1, group=4,
-                        num_ctas=got["ctas_per_head"], causal=False, min_chunk=32)
+                        num_ctas=got["ctas_per_head"], causal=False, min_chunk=32, item_cost=64)
     for k in ("cta_indptr", "w_q_row0", "w_kv_page0", "w_kv_start", "w_kv_len", "w_out_slot", "m_slot_base", "m_n_chunks"):
         assert got[k].tobytes() == np.asarray(want[k], dtype=np.int32).tobytes(), k
     w.close()

@@ -79,6 +79,16 @@ def test_invariants_random(kind):
         qo_indptr, kv_indptr, last = indptrs_from_lengths(qo, kv, ps)
         kw = dict(page_size=ps, t_pos=t_pos, group=g, num_ctas=C, causal=causal, alpha=alpha, beta=beta,
                   min_chunk=min_chunk)
+        if trial % 3 == 2:
+            # a fixed cost per work item may lengthen the chunks of a small batch, never beyond twice the length
+            # of Algorithm 1 and never to more rounds of work items; everything below holds for that plan too
+            kw["item_cost"] = int(rng.choice([16, 64, 1000]))
+            printed = plan_replica(qo_indptr, kv_indptr, last, **{**kw, "item_cost": 0})
+            longer = plan_replica(qo_indptr, kv_indptr, last, **kw)
+            assert printed["L_kv"] <= longer["L_kv"] <= 2 * printed["L_kv"]
+            assert -(-longer["n_work"] // C) <= -(-printed["n_work"] // C)
+            if printed["L_kv"] > 4 * kw["item_cost"]:
+                assert longer == printed
         p = plan_replica(qo_indptr, kv_indptr, last, **kw)
         assert p == plan_replica(qo_indptr, kv_indptr, last, **kw)          # deterministic (Sec. 3.3.1)
         L = p["L_kv"]

@@ -41,14 +41,14 @@ def indptrs(qo, kv, ps=16):
 
 
 def compare(h, qo, kv, causal, t_pos, g, C, alpha, beta, min_chunk, literal=False, refine=False, light_rows=0,
-            plan_window=0):
+            plan_window=0, item_cost=0):
     qo_indptr, kv_indptr, last = indptrs(qo, kv)
     fi.fi_plan(h, qo_indptr, kv_indptr, last, causal)
     got = fi.fi_plan_view(h)
     want = plan_replica(qo_indptr, kv_indptr, last, page_size=16, t_pos=t_pos, group=g, num_ctas=C, causal=causal,
                         alpha=alpha, beta=beta, min_chunk=min_chunk, literal_lkv=literal, refine=refine,
                         light_rows=light_rows, light_pct=64, kv_quantum=64 if light_rows else 1,
-                        plan_window=plan_window)
+                        plan_window=plan_window, item_cost=item_cost)
     assert got["l_kv_chunk"] == want["L_kv"] and got["n_work"] == want["n_work"]
     assert got["n_merge"] == want["n_merge"] and got["n_slots"] == want["n_slots"]
     assert got["t_pos"] == t_pos and got["group"] == g and got["ctas_per_head"] == C
@@ -115,6 +115,30 @@ def test_planner_equals_replica_with_a_sliding_window(mode):
                         kv = qo + rng.integers(0, 3000, size=B)
                     compare(h, qo, kv, mode == "append", t_pos, g, C, 1, 1, 32, plan_window=window)
                 fi.fi_destroy(h)
+
+
+def test_default_decode_plan_weighs_the_fixed_cost_of_a_work_item():
+    """balance = 0 in decode mode: Algorithm 1's chunk length, unless the batch is so small that a slightly longer
+    chunk saves every CTA a second work item (64 requests of 64..512 tokens on 256 CTAs: 80 -> 96 tokens)."""
+    rng = np.random.default_rng(23)
+    for C in (8, 64, 256):
+        h = make(fi.FI_MODE_DECODE, 4, C, max_batch=128)
+        h1 = make(fi.FI_MODE_DECODE, 4, C, max_batch=128, balance=1)
+        for trial in range(12):
+            B = int(rng.integers(1, 100))
+            kv = rng.integers(0, (64, 513, 3000)[trial % 3], size=B)
+            compare(h, np.ones(B, dtype=np.int64), kv, False, 1, 4, C, 1, 1, 32, item_cost=64)
+            compare(h1, np.ones(B, dtype=np.int64), kv, False, 1, 4, C, 1, 1, 32)
+        fi.fi_destroy(h); fi.fi_destroy(h1)
+    g5 = np.random.Generator(np.random.PCG64(1005))
+    kv = g5.integers(64, 513, size=64)
+    h = make(fi.FI_MODE_DECODE, 4, 256, Hkv=8, max_batch=64)
+    qo_indptr, kv_indptr, last = indptrs(np.ones(64, dtype=np.int64), kv)
+    fi.fi_plan(h, qo_indptr, kv_indptr, last, False)
+    got = fi.fi_plan_view(h)
+    as_printed = plan_replica(qo_indptr, kv_indptr, last, page_size=16, t_pos=1, group=4, num_ctas=256, causal=False, min_chunk=32)
+    assert as_printed["n_work"] > 256 and got["n_work"] <= 256 and got["l_kv_chunk"] > as_printed["L_kv"]
+    fi.fi_destroy(h)
 
 
 def test_planner_equals_replica_on_the_benchmark_length_sets():
