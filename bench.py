@@ -243,6 +243,8 @@ def main() -> int:
     ap.add_argument("--rope-theta", type=float, default=0.0,
                     help="> 0: decode with the rotary embedding fused into the kernel (fi_run_variant; the cache holds "
                          "unrotated keys, Sec. 4.4); 16-bit decode workloads only")
+    ap.add_argument("--soft-cap", type=float, default=0.0,
+                    help="> 0: logits soft cap c * tanh(s / c) (fi_run_variant, Sec. 3.2.3); 16-bit decode and causal append workloads")
     ap.add_argument("--window-left", type=int, default=-1,
                     help=">= 0: decode with a sliding window of that many tokens behind the query (fi_run_variant)")
     ap.add_argument("--plan-window", action="store_true",
@@ -326,15 +328,15 @@ def main() -> int:
             return 2
         run_kw["o_cast"] = torch.empty((nnz, batch.num_qo_heads, batch.head_dim), dtype=dev.q.dtype, device=dev.device)
         o = False
-    if args.rope_theta > 0 or args.window_left >= 0:
-        if mode != "decode" or batch.kv_dtype or args.page_size != 16:
-            print("bench.py: --rope-theta / --window-left are for the 16-bit decode workloads with page size 16",
-                  file=sys.stderr)
+    if args.rope_theta > 0 or args.window_left >= 0 or args.soft_cap > 0:
+        if batch.kv_dtype or args.page_size != 16 or (mode != "decode" and (args.rope_theta > 0 or args.window_left >= 0 or not batch.causal)):
+            print("bench.py: --rope-theta / --window-left are for the 16-bit decode workloads with page size 16, "
+                  "--soft-cap for those and the causal append workloads", file=sys.stderr)
             return 2
         run_kw["variant"] = dict(
             kv_indptr=torch.from_numpy(np.ascontiguousarray(batch.kv_indptr, dtype=np.int32)).to(dev.device),
             last_page_len=torch.from_numpy(np.ascontiguousarray(batch.last_page_len, dtype=np.int32)).to(dev.device),
-            rope_theta=args.rope_theta, window_left=args.window_left)
+            rope_theta=args.rope_theta, window_left=args.window_left, logits_soft_cap=args.soft_cap)
 
     stride = max(1, args.event_stride)
     n_samples = (args.steps + stride - 1) // stride
@@ -390,7 +392,7 @@ def main() -> int:
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "traffic.json")
     measured_setup = (args.page_size == 16 and args.page_order == "random" and args.kv_layout == "HND" and
-                      args.window_left < 0 and not args.small)  # the counters were taken on these settings only
+                      args.window_left < 0 and args.soft_cap == 0 and not args.small)  # the counters were taken on these settings only
     if os.path.exists(tpath) and measured_setup:
         traffic = json.load(open(tpath)).get(args.workload + ("_fp8" if batch.kv_dtype else "") +
                                              ("_rope" if args.rope_theta > 0 else "") +
@@ -427,6 +429,7 @@ def main() -> int:
                    "num_kv_heads": batch.num_kv_heads, "head_dim": batch.head_dim, "page_size": batch.page_size, "page_order": args.page_order, "kv_layout": args.kv_layout,
                    "kv_dtype": batch.kv_dtype or batch.dtype, "o_dtype": batch.dtype if args.out16 else "f32",
                    **({"fused_rope_theta": args.rope_theta} if args.rope_theta > 0 else {}),
+                   **({"logits_soft_cap": args.soft_cap} if args.soft_cap > 0 else {}),
                    **({"window_left": args.window_left, "planned": bool(args.plan_window)} if args.window_left >= 0 else {}),
                    "step": ("fi_run captured in a HIP graph, replayed (plan reused)" if args.graph else
                             "fi_run only (plan reused)" if args.no_plan else "fi_plan + fi_run"),

@@ -211,8 +211,9 @@ typedef struct fi_variant {
  * fi_config.plan_window.)  kv_indptr [batch+1] and last_page_len [batch] are DEVICE copies of the arrays
  * the batch was planned with (the decode kernel derives pos from them).  Built for 16-bit pools and
  * page_size 16; decode mode: every field of fi_variant; append mode: soft cap, ALiBi and window for
- * batches planned with causal = 1 (all work items then take the kernel's general path), no rotary
- * embedding.  FI_ERR_UNSUPPORTED otherwise.  Every key of the request is still read, a window only
+ * batches planned with causal = 1 (with ALiBi or a window all work items take the kernel's general
+ * path, about 3x slower than fi_run; the soft cap alone runs the scheduled tile loop, about 1.3x), no
+ * rotary embedding.  FI_ERR_UNSUPPORTED otherwise.  Every key of the request is still read, a window only
  * masks.  variant HOST, read during the call.  Otherwise as fi_run. */
 int32_t fi_run_variant(fi_handle* h, const void* q, const void* k_pool, const void* v_pool,
                        const int64_t* kv_strides, const int32_t* kv_indices,

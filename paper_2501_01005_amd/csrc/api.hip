@@ -299,6 +299,8 @@ int32_t run_impl(fi_handle* h, const void* q, const void* k_pool, const void* v_
   p.last_page_len = last_page_len_dev;
   p.alibi_slopes = variant ? variant->alibi_slopes : nullptr;
   p.soft_cap = variant ? variant->logits_soft_cap : 0.f;
+  p.cap_k1 = p.soft_cap > 0.f ? 2.0f * p.scale_log2 / p.soft_cap : 0.f;
+  p.cap_a = p.soft_cap * 1.4426950408889634f;
   p.window_left = variant ? variant->window_left : -1;
   p.page_log2 = 0;
   while ((1 << p.page_log2) < h->cfg.page_size) ++p.page_log2;

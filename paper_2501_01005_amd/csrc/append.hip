@@ -188,7 +188,11 @@ struct WorkItem {
 // page table) before it writes its own outputs, and sets `prefetched_out`.  The next call is then
 // made with bit 1 of `next_off` set.  Whoever uses the LDS otherwise after a block that set
 // `prefetched_out` waits for vmcnt(0) first.
-template <bool BF>
+// CAP: the variant of the loop with the logits soft cap (Sec. 3.2.3).  The capped logits are in log2 units, the
+// softmax scale after the transform is 1, and the block has no scalar register to spare: `scale_log2` then
+// carries 2 * sm_scale * log2(e) / c, `wave_index` the bits of c * log2(e), and `g_log2` the wavefront index in
+// bits 8.. above log2 of the group size.
+template <bool BF, bool CAP>
 __device__ __forceinline__ void run_scheduled_loop(int n_full, int n_tiles, int kv_len, int cap, int st_tok, int ids_clamp, const int32_t* page_ids, uint32_t k_lo,
                                                    uint32_t k_hi, uint32_t v_lo, uint32_t v_hi, uint32_t page_bytes,
                                                    float scale_log2, uint64_t q_addr, uint32_t st_off_bytes,
@@ -211,7 +215,21 @@ __device__ __forceinline__ void run_scheduled_loop(int n_full, int n_tiles, int 
           [gl] "s"(g_log2), [hq] "s"(num_qo_heads), [rb] "s"(row_base), [np] "s"(n_pos), [stp8] "s"(wave_index),           \
           [woff] "s"(next_off), [wq0] "s"(w_fields), [wstr] "s"(w_stride),                                                  \
           [idblo] "s"(all_ids_lo), [idbhi] "s"(all_ids_hi)
-  if constexpr (BF) {
+  if constexpr (CAP && BF) {
+    asm volatile(
+#include "append_loop_bf16_cap.inc"
+        FI355_LOOP_OPERANDS
+        :
+#include "append_loop_clobbers.inc"
+    );
+  } else if constexpr (CAP) {
+    asm volatile(
+#include "append_loop_f16_cap.inc"
+        FI355_LOOP_OPERANDS
+        :
+#include "append_loop_clobbers.inc"
+    );
+  } else if constexpr (BF) {
     asm volatile(
 #include "append_loop_bf16.inc"
         FI355_LOOP_OPERANDS
@@ -605,7 +623,9 @@ __device__ __attribute__((noinline)) void generic_work_item(uint64_t params_addr
   }
 }
 
-template <bool BF, bool VAR = false>
+// VAR: the logits hooks of RunParams are applied.  CAPLOOP (with VAR): the only hook in use is the soft cap, which
+// the scheduled loop has a variant for; the other hooks run every item on the generic path.
+template <bool BF, bool VAR = false, bool CAPLOOP = false>
 __global__ void __launch_bounds__(kCtaThreads) __attribute__((amdgpu_waves_per_eu(2, 2)))
 append_kernel(const RunParams p) {
   const int tid = threadIdx.x;
@@ -631,7 +651,7 @@ append_kernel(const RunParams p) {
     const bool causal = diag0 != kNoDiagMarker;
 
     // ---- work items whose first tile every row of the CTA sees in full: the scheduled loop ----
-    if constexpr (kUseScheduledLoop && !VAR) {  // (the variants run every item on the generic path)
+    if constexpr (kUseScheduledLoop && (!VAR || CAPLOOP)) {
       int vis = kv_len;  // tokens visible to the CTA's first position, which sees the fewest
       if (causal) vis = min(vis, max(0, diag0 - kv_start + 1));
       const int n_full = __builtin_amdgcn_readfirstlane(vis / kTileKv);
@@ -674,10 +694,11 @@ append_kernel(const RunParams p) {
         WorkItem next;
         int prefetched_next;
         __syncthreads();  // the previous work item is done with the tile buffers and the transpose area
-        run_scheduled_loop<BF>(n_full, (kv_len + kTileKv - 1) / kTileKv, kv_len, last_seen - 4 * c_o, st_tok_o,
+        run_scheduled_loop<BF, CAPLOOP>(n_full, (kv_len + kTileKv - 1) / kTileKv, kv_len, last_seen - 4 * c_o, st_tok_o,
                                (chunk_pages - 1) * 4, p.kv_indices + kv_page0, static_cast<uint32_t>(k_base),
                                static_cast<uint32_t>(k_base >> 32), static_cast<uint32_t>(v_base),
-                               static_cast<uint32_t>(v_base >> 32), static_cast<uint32_t>(page_bytes), p.scale_log2,
+                               static_cast<uint32_t>(v_base >> 32), static_cast<uint32_t>(page_bytes),
+                               CAPLOOP ? p.cap_k1 : p.scale_log2,
                                q_addr, st_off_bytes, k_off_bytes,
                                lds0 + n_o * 256 + ((c_o ^ n_o) & 1) * 16, ((n_o >> 1) & 7) * 32,
                                lds0 + kLdsVOffset + (4 * c_o + tr_row_o) * (kRowElemsV * 2) + tr_col_o * 2,
@@ -689,10 +710,12 @@ append_kernel(const RunParams p) {
                                __builtin_amdgcn_readfirstlane(final_out && p.o_cast != nullptr ? (p.o != nullptr ? 1 : 2) : 0),
                                epi0 + n_o * kEpilogueRowBytes + c_o * 16,
                                epi0 + ((tid_o >> 4) & 3) * kEpilogueRowBytes + st_chunk_o * 16,
-                               st_chunk_o * 16, g_log2, H,
+                               st_chunk_o * 16,
+                               CAPLOOP ? g_log2 | (__builtin_amdgcn_readfirstlane(wave_o) << 8) : g_log2, H,
                                static_cast<int>((final_out ? static_cast<int64_t>(q_row0)
                                                            : static_cast<int64_t>(out_slot) * p.t_pos) * H + kvh * g),
-                               n_pos, __builtin_amdgcn_readfirstlane(wave_o),
+                               n_pos,
+                               CAPLOOP ? __builtin_bit_cast(int, p.cap_a) : __builtin_amdgcn_readfirstlane(wave_o),
                                __builtin_amdgcn_readfirstlane(min(w + 1, w_end - 1) * 4 + (w + 1 < w_end ? 1 : 0) + 2 * prefetched), p.w_q_row0,
                                static_cast<int>((p.w_n_pos - p.w_q_row0) * static_cast<int64_t>(sizeof(int32_t))),
                                static_cast<uint32_t>(all_ids), static_cast<uint32_t>(all_ids >> 32), next,
@@ -719,6 +742,13 @@ int append_tile_rows() { return (kCtaThreads / 64) * 32 * kRowBlocks; }
 hipError_t launch_append(const RunParams& p, bool is_bf16, bool variant, hipStream_t stream) {
   const dim3 grid(static_cast<unsigned>(p.ctas_per_head) * static_cast<unsigned>(p.num_kv_heads), 1, 1);
   const dim3 block(kCtaThreads, 1, 1);
+  if (variant && p.soft_cap > 0.f && p.alibi_slopes == nullptr && p.window_left < 0) {
+    if (is_bf16)
+      hipLaunchKernelGGL((append_kernel<true, true, true>), grid, block, 0, stream, p);
+    else
+      hipLaunchKernelGGL((append_kernel<false, true, true>), grid, block, 0, stream, p);
+    return hipGetLastError();
+  }
   if (variant) {
     if (is_bf16)
       hipLaunchKernelGGL((append_kernel<true, true>), grid, block, 0, stream, p);

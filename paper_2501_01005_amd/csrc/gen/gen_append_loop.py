@@ -94,10 +94,24 @@ def merge_even(*lists):
 
 
 class Gen:
-    def __init__(self, bf16):
+    def __init__(self, bf16, cap=False):
         self.bf = bf16
+        # logits soft cap (Sec. 3.2.3): the logits are transformed in place as soon as they are complete.  The block
+        # has no scalar register to spare for the two constants of the transform, so in this variant the operand
+        # of the softmax scale (which is 1 after the transform) carries the first and the operand of the wavefront
+        # index the second; the wavefront index then rides in bits 8.. of the operand that holds log2 of the group
+        # size, which is only ever used as a shift amount (the hardware takes the low five bits).
+        self.cap = cap
         self.e = Emitter()
         self.mid_state = {}  # per masked tile of the rotation: loads in flight between its two steps
+
+    def wave_shift(self, dst, op, amount):
+        """s<dst> <- wavefront index shifted left (lshl) or right (lshr) by amount"""
+        if not self.cap:
+            return ['s_%s_b32 s%d, %%[stp8], %d' % (op, dst, amount)]
+        if op == 'lshr':
+            return ['s_lshr_b32 s%d, %%[gl], %d' % (dst, 8 + amount)]
+        return ['s_lshr_b32 s%d, %%[gl], 8' % dst, 's_lshl_b32 s%d, s%d, %d' % (dst, dst, amount)]
 
     # ---- building blocks ----
     def qk(self, Sn, s):
@@ -113,11 +127,29 @@ class Gen:
         ops = []
         for j in range(8):
             a, b = T + 2 * j, T + 2 * j + 1
-            ops += ['v_fma_f32 v%d, v%d, %%[sc], v%d' % (a, Sc + 2 * j, NEGMS),
-                    'v_fma_f32 v%d, v%d, %%[sc], v%d' % (b, Sc + 2 * j + 1, NEGMS),
-                    'v_exp_f32 v%d, v%d' % (a, a), 'v_exp_f32 v%d, v%d' % (b, b)]
+            if self.cap:
+                ops += ['v_add_f32 v%d, v%d, v%d' % (a, Sc + 2 * j, NEGMS), 'v_add_f32 v%d, v%d, v%d' % (b, Sc + 2 * j + 1, NEGMS)]
+            else:
+                ops += ['v_fma_f32 v%d, v%d, %%[sc], v%d' % (a, Sc + 2 * j, NEGMS),
+                        'v_fma_f32 v%d, v%d, %%[sc], v%d' % (b, Sc + 2 * j + 1, NEGMS)]
+            ops += ['v_exp_f32 v%d, v%d' % (a, a), 'v_exp_f32 v%d, v%d' % (b, b)]
         for j in range(8):
             ops.append('v_cvt_pk_f16_f32 v%d, v%d, v%d' % (H + j, T + 2 * j, T + 2 * j + 1))
+        return ops
+
+    def soft_cap(self, Sx):
+        """s <- c * tanh(s * sm_scale / c) in log2 units, in place on the 16 logits of a step:
+        tanh(x) = 1 - 2 / (exp(2 x) + 1); %[sc] holds 2 * sm_scale * log2(e) / c, %[stp8] holds c * log2(e).  Afterwards the
+        softmax scale of the loop is 1.  Stage by stage over the 16 registers, so that no instruction reads the
+        result of the one before it."""
+        if not self.cap:
+            return []
+        ops = ['v_mul_f32 v%d, %%[sc], v%d' % (T + r, Sx + r) for r in range(16)]
+        ops += ['v_exp_f32 v%d, v%d' % (T + r, T + r) for r in range(16)]
+        ops += ['v_add_f32 v%d, 1.0, v%d' % (T + r, T + r) for r in range(16)]
+        ops += ['v_rcp_f32 v%d, v%d' % (T + r, T + r) for r in range(16)]
+        ops += ['v_fma_f32 v%d, v%d, -2.0, 1.0' % (T + r, T + r) for r in range(16)]
+        ops += ['v_mul_f32 v%d, %%[stp8], v%d' % (Sx + r, T + r) for r in range(16)]
         return ops
 
     def mask(self, Sc, u):
@@ -309,7 +341,7 @@ class Gen:
     def stage_reads(self, lbl):
         """this thread's pieces of the staged V tiles 0 and 1 (the ones it requested itself at the end of the
         previous work item) into the registers the start-up converts them from"""
-        ops = ['s_lshl_b32 s%d, %%[stp8], 10' % S_TMP, 's_sub_u32 s%d, %%[kd], s%d' % (S_TMP, S_TMP),  # LDS offset of the tile area
+        ops = self.wave_shift(S_TMP, 'lshl', 10) + ['s_sub_u32 s%d, %%[kd], s%d' % (S_TMP, S_TMP),  # LDS offset of the tile area
                'v_lshlrev_b32 v%d, 8, %%[stk]' % X0, 'v_add_u32 v%d, v%d, %%[l16]' % (X0, X0),
                'v_add_u32 v%d, s%d, v%d' % (X0, S_TMP, X0)]
         for t, base in ((0, VT), (1, KA)):
@@ -335,13 +367,14 @@ class Gen:
         return ops
 
     def set_reference(self):
-        return ['v_mov_b32 v%d, v%d' % (MRUN, X0), 'v_mul_f32 v%d, v%d, %%[sc]' % (NEGMS, X0),
+        return ['v_mov_b32 v%d, v%d' % (MRUN, X0),
+                'v_mov_b32 v%d, v%d' % (NEGMS, X0) if self.cap else 'v_mul_f32 v%d, v%d, %%[sc]' % (NEGMS, X0),
                 'v_xor_b32 v%d, 0x80000000, v%d' % (NEGMS, NEGMS)]
 
     def raise_reference(self, Sc):
         """out-of-line: raise the reference to the row maximum, rescale the state, redo P"""
         ops = self.row_max(Sc)
-        ops += ['v_sub_f32 v%d, v%d, v%d' % (X1, MRUN, X0), 'v_mul_f32 v%d, v%d, %%[sc]' % (X1, X1),
+        ops += ['v_sub_f32 v%d, v%d, v%d' % (X1, MRUN, X0)] + ([] if self.cap else ['v_mul_f32 v%d, v%d, %%[sc]' % (X1, X1)]) + [
                 'v_exp_f32 v%d, v%d' % (X1, X1)]
         ops += self.set_reference()
         ops.append('v_mul_f32 v%d, v%d, v%d' % (LSUM, LSUM, X1))
@@ -388,10 +421,12 @@ class Gen:
             e.label('back_%s%d%d_%s' % (kind, k, u, lbl))
             # block 2
             kn = self.k_reads(nxt, u)
+            # (with the soft cap: the next step's logits, complete since the matrix instructions of block 1, are
+            # transformed behind the last products of this block; the temporaries of the exponentials are free here)
             if u == 0:
-                rest = merge_even(kn, self.rowsum() + self.v_convert())
+                rest = merge_even(kn, self.rowsum() + self.v_convert()) + self.soft_cap(Sn)
             else:
-                rest = merge_even(kn, self.rowsum() + self.v_zero_tail(2)) + self.stores(wr) + self.fetch()
+                rest = merge_even(kn, self.rowsum() + self.v_zero_tail(2)) + self.stores(wr) + self.fetch() + self.soft_cap(Sn)
             spread(e, [self.pv(db, j) for j in range(2) for db in range(4)], rest)
         e.wait_lds_loads()
         e.emit('s_barrier')
@@ -457,7 +492,8 @@ class Gen:
         e.raw('s_mov_b32 s%d, m0' % S_M0)
         e.raw('s_mov_b32 s%d, 0' % S_T)
         e.raw('s_mov_b32 s%d, 0x%x' % (S_THR, LAZY_THR))
-        e.raw('s_lshr_b32 s%d, %%[stp8], 2' % S_STP)
+        for o in self.wave_shift(S_STP, 'lshr', 2):
+            e.raw(o)
         for s in range(8):
             e.emit('global_load_dwordx4 %s, %%[qp], off offset:%d' % (vr(Q + 4 * s, 4), 32 * s))
         for o in self.header_next():
@@ -522,7 +558,8 @@ class Gen:
         e.lgkm = []
         e.vm = list(q_loads) + [set(('v', ST + 8 + 4 * r + i) for i in range(4)) for r in (0, 1)]
         # a wavefront whose first row is past the end of the query tile only helps with the staging
-        e.raw('s_lshl_b32 s%d, %%[stp8], 5' % S_TMP)           # first tile row of this wavefront
+        for o in self.wave_shift(S_TMP, 'lshl', 5):            # first tile row of this wavefront
+            e.raw(o)
         e.raw('s_lshr_b32 s%d, s%d, %%[gl]' % (S_TMP, S_TMP))  # its position
         e.raw('s_cmp_ge_u32 s%d, %%[np]' % S_TMP)
         e.raw('s_cbranch_scc1 tile_i0_%s' % lbl)
@@ -535,7 +572,7 @@ class Gen:
             e.emit(o)
         e.raw('s_nop 15')
         e.raw('s_nop 15')
-        for o in self.row_max(S0) + self.set_reference():
+        for o in self.soft_cap(S0) + self.row_max(S0) + self.set_reference():
             e.emit(o)
         e.drain(lgkm=True, vm=False)
         e.raw('s_cmp_lt_u32 s%d, %%[nf]' % S_T)  # t = 0: a first tile that needs masking is possible when nf = 0
@@ -577,7 +614,8 @@ class Gen:
                   'v_permlane32_swap_b32 v%d, v%d' % (X0, X1), 's_nop 1', 'v_add_f32 v%d, v%d, v%d' % (LSUM, X0, X1),
                   # (a transcendental result needs a wait state before an ordinary vector instruction reads it)
                   'v_log_f32 v%d, v%d' % (X1, LSUM), 'v_rcp_f32 v%d, v%d' % (X0, LSUM), 's_nop 1',
-                  'v_fma_f32 v%d, v%d, %%[sc], v%d' % (X1, MRUN, X1), 'v_mul_f32 v%d, 0x3f317218, v%d' % (X1, X1),
+                  'v_add_f32 v%d, v%d, v%d' % (X1, MRUN, X1) if self.cap else 'v_fma_f32 v%d, v%d, %%[sc], v%d' % (X1, MRUN, X1),
+                  'v_mul_f32 v%d, 0x3f317218, v%d' % (X1, X1),
                   's_mov_b64 s[%d:%d], exec' % (S_EXEC, S_EXEC + 1),
                   # one lane per live row writes lse
                   'v_and_b32 v%d, 2, %%[rok]' % MAXT, 'v_cmp_ne_u32 vcc, 0, v%d' % MAXT, 's_and_b64 exec, exec, vcc',
@@ -663,8 +701,8 @@ def write(path, lines, name):
 if __name__ == '__main__':
     here = os.path.dirname(os.path.abspath(__file__))
     out_dir = sys.argv[1] if len(sys.argv) > 1 else os.path.join(here, '..')
-    for bf, name in ((True, 'bf16'), (False, 'f16')):
-        lines = Gen(bf).program()
+    for bf, cap, name in ((True, False, 'bf16'), (False, False, 'f16'), (True, True, 'bf16_cap'), (False, True, 'f16_cap')):
+        lines = Gen(bf, cap).program()
         write(os.path.join(out_dir, 'append_loop_%s.inc' % name), lines, name)
         n_mfma = sum(1 for l in lines if l.startswith('v_mfma'))
         print('%s: %d lines, %d matrix instructions, %d waits' % (name, len(lines), n_mfma, sum(1 for l in lines if l.startswith('s_waitcnt'))))

@@ -43,6 +43,7 @@ struct RunParams {
   const int32_t* last_page_len;  //   absolute position of its query
   const float* alibi_slopes;     // [num_qo_heads] or null
   float soft_cap;                // > 0: logits <- cap * tanh(logits / cap)
+  float cap_k1, cap_a;           // with a soft cap: 2 * scale_log2 / cap and cap * log2(e) (the append loop's constants)
   int32_t window_left;           // >= 0: tokens more than this far behind the query are hidden
 };
 
@@ -86,7 +87,8 @@ struct ComposeParams {
 hipError_t launch_decode(const RunParams& p, bool is_bf16, bool kv8, bool variant, const RopeTable* rope,
                          hipStream_t stream);
 // append.hip: query tile = append_tile_rows()/g positions x g fused heads, 8 wavefronts per CTA.
-// variant: the logits hooks of RunParams are applied (causal batches only; every item takes the generic path).
+// variant: the logits hooks of RunParams are applied (causal batches only; with ALiBi or a window every item takes
+// the generic path, the soft cap alone has a variant of the scheduled loop).
 hipError_t launch_append(const RunParams& p, bool is_bf16, bool variant, hipStream_t stream);
 int append_tile_rows();  // fused rows (positions x group) of one append query tile
 // upload.hip: staging (device view of page-locked host memory) -> plan section

@@ -87,7 +87,7 @@ def test_window_hides_whole_steps_and_whole_chunks():
 @pytest.mark.parametrize("g", [1, 4])
 def test_causal_append_with_variants(dtype, g):
     """Query tiles of several positions: every row has its own position, so bias and window differ from row to
-    row; chunks long enough for the scheduled loop run on the general path here; split chunks; a window that
+    row; chunks long enough for the scheduled loop run on the general path with ALiBi or a window; split chunks; a window that
     hides whole tiles and, for the early rows of a split tile, whole chunks."""
     qo = [70, 9, 130, 1, 64]
     kv = [400, 9, 260, 300, 64]
@@ -100,6 +100,21 @@ def test_causal_append_with_variants(dtype, g):
     check(b, "append, all", logits_soft_cap=5.0, window_left=33, alibi_slopes=slopes(2 * g), **kw)
     check(b, "append, all, split chunks", logits_soft_cap=5.0, window_left=100, alibi_slopes=slopes(2 * g),
           mode="append", num_ctas=2 * 16, min_chunk=64)
+
+
+@pytest.mark.parametrize("dtype", [workloads.BF16, workloads.F16])
+@pytest.mark.parametrize("g", [1, 4, 16])
+def test_soft_cap_inside_the_scheduled_append_loop(dtype, g):
+    """The soft cap alone has a variant of the append kernel's scheduled loop (the other hooks run on the general
+    path): one CTA per kv head walks items of both paths (seams, idle wavefronts, chunks that end inside a tile,
+    tiles cut by the diagonal); a cap that bites hard with large logits (the reference is raised on the capped
+    values) and one that barely does; split chunks."""
+    qo = [64, 3, 64, 130, 1, 64, 40, 64, 64, 7, 200]
+    kv = [300, 50, 128, 700, 100, 129, 140, 64, 191, 400, 260]
+    for scale, cap in ((3.0, 2.0), (1.0, 30.0)):
+        b = workloads.make_batch("caploop", 460 + g, dtype, 2 * g, 2, 128, 16, qo, kv, True, value_scale=scale)
+        check(b, f"append loop, soft cap {cap}, one CTA per head", mode="append", num_ctas=2, min_chunk=1024, logits_soft_cap=cap)
+    check(b, "append loop, soft cap, split chunks", mode="append", num_ctas=2 * 16, min_chunk=128, logits_soft_cap=4.0)
 
 
 @pytest.mark.parametrize("mode", ["decode", "append"])
