@@ -89,6 +89,31 @@ def test_two_decode_passes_over_halves_of_the_cache(dtype):
     wa.close(); wb.close()
 
 
+def test_an_empty_format_is_the_identity():
+    """A format in which no request has keys contributes the identity state: the composition equals fi_run on the
+    other format bit for bit; two empty formats give zero rows with lse = -inf."""
+    import torch
+    kv = [900, 40, 1, 0, 333]
+    b = workloads.make_batch("idstate", 420, workloads.BF16, 8, 2, 128, 16, [1] * len(kv), kv, False)
+    dev = DeviceBatch(b)
+    wa = make_wrapper(b, "decode", min_chunk=32)
+    wb = make_wrapper(b, "decode")
+    zeros = np.zeros(len(kv) + 1, dtype=np.int32)
+    wa.plan(b.qo_indptr, b.kv_indptr, b.last_page_len, causal=False)
+    wb.plan(b.qo_indptr, zeros, np.ones(len(kv), dtype=np.int32), causal=False)
+    no_pages = torch.zeros(1, dtype=torch.int32, device=dev.device)
+    o_a, l_a = wa.run(dev.q, dev.k_pool, dev.v_pool, dev.kv_indices, b.sm_scale)
+    for first, second, ia, ib in ((wa, wb, dev.kv_indices, no_pages), (wb, wa, no_pages, dev.kv_indices)):
+        o, l = first.run_composed(second, dev.q, dev.k_pool, dev.v_pool, ia, ib, b.sm_scale)
+        torch.cuda.synchronize()
+        assert torch.equal(o.view(torch.int32), o_a.view(torch.int32)) and torch.equal(l.view(torch.int32), l_a.view(torch.int32))
+    wa.plan(b.qo_indptr, zeros, np.ones(len(kv), dtype=np.int32), causal=False)
+    o, l = wa.run_composed(wb, dev.q, dev.k_pool, dev.v_pool, no_pages, no_pages, b.sm_scale)
+    torch.cuda.synchronize()
+    assert torch.count_nonzero(o).item() == 0 and torch.isneginf(l).all().item()
+    wa.close(); wb.close()
+
+
 def test_composed_argument_errors():
     import torch
     import paper_2501_01005_amd as fi
