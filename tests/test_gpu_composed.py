@@ -89,6 +89,46 @@ def test_two_decode_passes_over_halves_of_the_cache(dtype):
     wa.close(); wb.close()
 
 
+def test_merge_lists_longer_than_a_wavefront():
+    """150 requests, most of them split in both formats: the contraction looks a row's tile up in merge lists of
+    more than 64 entries (searched 64 at a time).  Checked against the oracle and, bit for bit, against the
+    separate launches."""
+    import torch
+    import paper_2501_01005_amd as fi
+    rng = np.random.default_rng(77)
+    B = 150
+    kv = rng.integers(0, 1500, size=B)
+    b = workloads.make_batch("longlists", 430, workloads.BF16, 8, 2, 128, 16, [1] * B, kv.tolist(), False)
+    ia, ib, pa, pb, la, lb = [], [], [0], [0], [], []
+    for r in range(B):
+        pages = b.kv_indices[b.kv_indptr[r]:b.kv_indptr[r + 1]]
+        k = int(rng.integers(0, len(pages) + 1))
+        ia.append(pages[:k]); ib.append(pages[k:])
+        pa.append(pa[-1] + k); pb.append(pb[-1] + len(pages) - k)
+        la.append(int(b.last_page_len[r]) if k == len(pages) and k > 0 else (16 if k > 0 else 1))
+        lb.append(int(b.last_page_len[r]) if len(pages) > k else 1)
+    dev = DeviceBatch(b)
+    cat = lambda xs: torch.from_numpy(np.concatenate(xs + [np.zeros(1, dtype=np.int32)]).astype(np.int32)).to(dev.device)
+    idx_a, idx_b = cat(ia), cat(ib)
+    wa, wb = make_wrapper(b, "decode", min_chunk=16), make_wrapper(b, "decode", min_chunk=16)
+    wa.plan(b.qo_indptr, np.asarray(pa, dtype=np.int32), np.asarray(la, dtype=np.int32), causal=False)
+    wb.plan(b.qo_indptr, np.asarray(pb, dtype=np.int32), np.asarray(lb, dtype=np.int32), causal=False)
+    n_a, n_b = int(fi.fi_plan_view(wa.handle)["n_merge"]), int(fi.fi_plan_view(wb.handle)["n_merge"])
+    print(f"[case] long merge lists: split tiles {n_a}, {n_b}", flush=True)
+    assert n_a > 64 and n_b > 64
+    o_ref, lse_ref = oracle.run_batch(b)
+    o, l = wa.run_composed(wb, dev.q, dev.k_pool, dev.v_pool, idx_a, idx_b, b.sm_scale)
+    torch.cuda.synchronize()
+    assert_close(o.double().cpu().numpy(), l.double().cpu().numpy(), o_ref, lse_ref, "long merge lists")
+    o_a, l_a = wa.run(dev.q, dev.k_pool, dev.v_pool, idx_a, b.sm_scale)
+    o_b, l_b = wb.run(dev.q, dev.k_pool, dev.v_pool, idx_b, b.sm_scale)
+    o2 = torch.empty_like(o_a); l2 = torch.empty_like(l_a)
+    fi.fi_merge_state_pair(o_a, l_a, o_b, l_b, l_a.numel(), 128, o2, l2, torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    assert torch.equal(o2.view(torch.int32), o.view(torch.int32)) and torch.equal(l2.view(torch.int32), l.view(torch.int32))
+    wa.close(); wb.close()
+
+
 def test_an_empty_format_is_the_identity():
     """A format in which no request has keys contributes the identity state: the composition equals fi_run on the
     other format bit for bit; two empty formats give zero rows with lse = -inf."""
