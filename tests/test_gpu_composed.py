@@ -89,6 +89,46 @@ def test_two_decode_passes_over_halves_of_the_cache(dtype):
     wa.close(); wb.close()
 
 
+@pytest.mark.parametrize("dtype", [workloads.BF16, workloads.F16])
+def test_prefill_over_a_shared_prefix(dtype):
+    """Two append-mode formats (Sec. 3.1.2 with multi-token queries): every request appends its own tokens after a
+    common prefix.  Format a: all query rows as one row block over the prefix pages, not causal; format b: each
+    request's own tokens, causal.  The single format (every request: prefix + own tokens, causal) is what the
+    oracle computes; its copies of the prefix hold the same values as the shared pages."""
+    import dataclasses
+    import torch
+    prefix, qo = 304, [70, 9, 130, 1, 64]
+    n_pre = prefix // 16
+    single = workloads.make_batch("sharedprefill", 450, dtype, 8, 2, 128, 16, qo, [prefix + q for q in qo], True)
+    k_bits, v_bits = single.k_bits.copy(), single.v_bits.copy()
+    shared = single.kv_indices[single.kv_indptr[0]:single.kv_indptr[0] + n_pre]
+    own, own_indptr = [], [0]
+    for r in range(len(qo)):
+        pages = single.kv_indices[single.kv_indptr[r]:single.kv_indptr[r + 1]]
+        k_bits[pages[:n_pre]] = k_bits[shared]
+        v_bits[pages[:n_pre]] = v_bits[shared]
+        own.append(pages[n_pre:])
+        own_indptr.append(own_indptr[-1] + len(pages) - n_pre)
+    single = dataclasses.replace(single, k_bits=k_bits, v_bits=v_bits)
+    print(f"[case] prefill over a shared prefix: {dtype} prefix={prefix} qo={qo}", flush=True)
+    o_ref, lse_ref = oracle.run_batch(single)
+    dev = DeviceBatch(single)
+    nnz = int(single.qo_indptr[-1])
+    fmt_a = dataclasses.replace(single, qo_indptr=np.array([0, nnz], dtype=np.int32), kv_indptr=np.array([0, n_pre], dtype=np.int32),
+                                kv_indices=shared.copy(), last_page_len=np.array([16], dtype=np.int32), causal=False)
+    wa = make_wrapper(fmt_a, "append", num_ctas=2 * 4, min_chunk=64)
+    wb = make_wrapper(single, "append", num_ctas=2 * 4, min_chunk=64)
+    wa.plan(fmt_a.qo_indptr, fmt_a.kv_indptr, fmt_a.last_page_len, causal=False)
+    wb.plan(single.qo_indptr, np.asarray(own_indptr, dtype=np.int32), single.last_page_len, causal=True)
+    idx_a = torch.from_numpy(shared.astype(np.int32)).to(dev.device)
+    idx_b = torch.from_numpy(np.concatenate(own).astype(np.int32)).to(dev.device)
+    o, l = wa.run_composed(wb, dev.q, dev.k_pool, dev.v_pool, idx_a, idx_b, single.sm_scale)
+    torch.cuda.synchronize()
+    e = assert_close(o.double().cpu().numpy(), l.double().cpu().numpy(), o_ref, lse_ref, "prefill over a shared prefix")
+    print(f"[ok] prefill over a shared prefix: err_o={e[0]:.2e} err_lse={e[1]:.2e}", flush=True)
+    wa.close(); wb.close()
+
+
 def test_merge_lists_longer_than_a_wavefront():
     """150 requests, most of them split in both formats: the contraction looks a row's tile up in merge lists of
     more than 64 entries (searched 64 at a time).  Checked against the oracle and, bit for bit, against the
