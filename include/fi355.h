@@ -251,7 +251,8 @@ int32_t fi_merge_state_pair(const float* o_a, const float* lse_a, const float* o
  * call are unspecified).  o / lse / o_cast as in fi_run (o may be NULL when o_cast is not); they may
  * alias neither pass's rows.  Both handles: same dtype and head counts, merge != 2, no plan_window;
  * 16-bit pools.  Errors as fi_run, plus FI_ERR_INVALID_ARG when the plans' query rows differ from
- * nnz_qo.  Asynchronous on `stream`. */
+ * nnz_qo.  Asynchronous on `stream`.  Allocates nothing; the launch geometry depends on the two
+ * configurations and on nnz_qo only, so a captured call serves later plans over as many query rows. */
 int32_t fi_run_composed(fi_handle* h_a, fi_handle* h_b, const void* q, const void* k_pool,
                         const void* v_pool, const int64_t* kv_strides, const int32_t* kv_indices_a,
                         const int32_t* kv_indices_b, float sm_scale, float* o_a, float* lse_a,

@@ -93,3 +93,68 @@ def test_one_captured_run_serves_every_plan(mode):
                          f"replay {rep}")
         print(f"[ok] replay {rep}: err_o={e[0]:.2e} err_lse={e[1]:.2e}", flush=True)
     w.close()
+
+
+def test_one_captured_composed_run_serves_every_plan():
+    """fi_run_composed under capture: two decode formats over the same five query rows (each request's pages cut in
+    two), both re-planned between the replays; the launch geometry depends on the configuration and on the number
+    of query rows only."""
+    import torch
+    import paper_2501_01005_amd as fi
+
+    dev = torch.device("cuda:0")
+    shapes = [[700, 33, 1, 260, 129], [64, 0, 500, 16, 301], [1500, 17, 5, 600, 40], [700, 33, 1, 260, 129]]
+    batches = [workloads.make_batch(f"graph_comp_{i}", 950 + i, workloads.BF16, HQ, HKV, D, PS, [1] * 5, kv, False,
+                                    num_pages=POOL_PAGES) for i, kv in enumerate(shapes)]
+    mk = lambda: fi.PagedAttention(dtype=workloads.BF16, num_qo_heads=HQ, num_kv_heads=HKV, head_dim=D, page_size=PS,
+                                   mode="decode", max_batch=5, max_qo_tiles=5, num_ctas=HKV * 6, min_chunk=64)
+    wa, wb = mk(), mk()
+    q_s = torch.zeros((5, HQ, D), dtype=torch.bfloat16, device=dev)
+    k_s = torch.zeros((POOL_PAGES, HKV, PS, D), dtype=torch.bfloat16, device=dev)
+    v_s = torch.zeros_like(k_s)
+    ia_s = torch.zeros(POOL_PAGES, dtype=torch.int32, device=dev)
+    ib_s = torch.zeros(POOL_PAGES, dtype=torch.int32, device=dev)
+    o_s = torch.zeros((5, HQ, D), dtype=torch.float32, device=dev)
+    lse_s = torch.zeros((5, HQ), dtype=torch.float32, device=dev)
+    sm_scale = batches[0].sm_scale
+
+    def load(b):
+        ia, ib, pa, pb, la, lb = [], [], [0], [0], [], []
+        for r in range(b.batch):
+            pages = b.kv_indices[b.kv_indptr[r]:b.kv_indptr[r + 1]]
+            k = len(pages) // 2
+            ia.append(pages[:k]); ib.append(pages[k:])
+            pa.append(pa[-1] + k); pb.append(pb[-1] + len(pages) - k)
+            la.append(16 if k > 0 else 1)
+            lb.append(int(b.last_page_len[r]) if len(pages) > k else 1)
+        for dst, parts in ((ia_s, ia), (ib_s, ib)):
+            flat = np.concatenate(parts).astype(np.int32) if parts else np.zeros(0, dtype=np.int32)
+            if len(flat):
+                dst[:len(flat)].copy_(torch.from_numpy(flat))
+        q_s.copy_(bits_to_torch(b.q_bits, b.dtype, dev))
+        k_s.copy_(bits_to_torch(b.k_bits, b.dtype, dev))
+        v_s.copy_(bits_to_torch(b.v_bits, b.dtype, dev))
+        o_s.fill_(float("nan")); lse_s.fill_(float("nan"))
+        wa.plan(b.qo_indptr, np.asarray(pa, dtype=np.int32), np.asarray(la, dtype=np.int32), causal=False)
+        wb.plan(b.qo_indptr, np.asarray(pb, dtype=np.int32), np.asarray(lb, dtype=np.int32), causal=False)
+
+    load(batches[0])
+    wa.run_composed(wb, q_s, k_s, v_s, ia_s, ib_s, sm_scale, o=o_s, lse=lse_s)   # eager once: code objects, pass rows
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        wa.run_composed(wb, q_s, k_s, v_s, ia_s, ib_s, sm_scale, o=o_s, lse=lse_s)
+    torch.cuda.synchronize()
+    for rep, b in enumerate(batches):
+        print(f"[case] composed graph replay {rep}: kv={b.kv_lens().tolist()}", flush=True)
+        load(b)
+        graph.replay()
+        torch.cuda.synchronize()
+        o_g, l_g = o_s.clone(), lse_s.clone()
+        o_ref, lse_ref = oracle.run_batch(b)
+        assert_close(o_g.double().cpu().numpy(), l_g.double().cpu().numpy(), o_ref, lse_ref, f"composed replay {rep}")
+        o_s.fill_(float("nan")); lse_s.fill_(float("nan"))
+        wa.run_composed(wb, q_s, k_s, v_s, ia_s, ib_s, sm_scale, o=o_s, lse=lse_s)
+        torch.cuda.synchronize()
+        assert torch.equal(o_g.view(torch.int32), o_s.view(torch.int32)) and torch.equal(l_g.view(torch.int32), lse_s.view(torch.int32))
+    wa.close(); wb.close()
