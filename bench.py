@@ -118,8 +118,7 @@ def bench_shared_prefix(args) -> int:
     import torch
     import workloads
     import paper_2501_01005_amd as fi
-    sys.path.insert(0, os.path.join(ROOT, "tests"))
-    from gpu_util import DeviceBatch, make_wrapper
+    from paper_2501_01005_amd.device import DeviceBatch, make_wrapper
 
     c = workloads.config5(small=args.small)
     dev_p, dev_s, dev_1 = DeviceBatch(c.prefix), DeviceBatch(c.suffix), DeviceBatch(c.single)
@@ -242,7 +241,7 @@ def main() -> int:
     ap.add_argument("--page-size", type=int, default=16, help="tokens per page (c2 and c3; 16 is the tuned size)")
     ap.add_argument("--rope-theta", type=float, default=0.0,
                     help="> 0: decode with the rotary embedding fused into the kernel (fi_run_variant; the cache holds "
-                         "unrotated keys, Sec. 4.4); 16-bit decode workloads only")
+                         "unrotated keys, Sec. 4.3); 16-bit decode workloads only")
     ap.add_argument("--soft-cap", type=float, default=0.0,
                     help="> 0: logits soft cap c * tanh(s / c) (fi_run_variant, Sec. 3.2.3); 16-bit decode and causal append workloads")
     ap.add_argument("--window-left", type=int, default=-1,
@@ -277,8 +276,7 @@ def main() -> int:
     import torch
     import workloads
     import paper_2501_01005_amd as fi
-    sys.path.insert(0, os.path.join(ROOT, "tests"))
-    from gpu_util import DeviceBatch, make_wrapper
+    from paper_2501_01005_amd.device import DeviceBatch, make_wrapper
 
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)

@@ -3,7 +3,8 @@
  *
  * C ABI of the library: plain pointers and sizes only.  Every pointer is marked
  * HOST or DEVICE.  All functions return an int32 status (FI_OK = 0, negative = error,
- * message through fi_last_error()); nothing throws, nothing aborts.
+ * message through fi_last_error()); no exception leaves the library (a host allocation that
+ * fails inside it comes back as FI_ERR_HOST_MEMORY), nothing aborts.
  *
  * Method (FlashInfer, arXiv 2501.01005):
  *   - storage: ragged query/output + block-sparse-row KV cache, Sec. 3.1.1;
@@ -47,6 +48,7 @@ extern "C" {
 #define FI_ERR_WORKSPACE_TOO_SMALL (-3)
 #define FI_ERR_NOT_PLANNED (-4)          /* fi_run before a successful fi_plan with a workspace     */
 #define FI_ERR_HIP (-5)                  /* a HIP runtime call failed; message has its string       */
+#define FI_ERR_HOST_MEMORY (-6)          /* a host-side allocation inside the library failed         */
 
 #define FI_DTYPE_F16 0
 #define FI_DTYPE_BF16 1
@@ -92,8 +94,9 @@ typedef struct fi_config {
   int32_t merge;        /* where the partial states of split tiles are contracted (Sec. 3.3.1: the paper
                            fuses the contraction into the attention launch).  1: in a second launch.
                            2: in the attention launch: the CTA that delivers a tile's last partial
-                           state folds them all (decode mode only; on MI355X slower than 1, because
-                           partial states cross between the XCDs' L2 caches through memory).
+                           state folds them all (decode mode with g = 1, 2 or 4 only, FI_ERR_UNSUPPORTED
+                           otherwise; on MI355X slower than 1, because partial states cross between the
+                           XCDs' L2 caches through memory).
                            0: default = 1                                                       */
   int32_t plan_window;  /* sliding-window attention: 0 = every key a query may see is planned and read;
                            n > 0: a query at position pos sees keys pos - (n - 1) .. pos only, and fi_plan
@@ -173,6 +176,12 @@ int32_t fi_plan_view(const fi_handle* h, fi_plan_arrays* out);
  * o may be NULL when o_cast is not: the output is then written in the input dtype only, which
  * halves the output bytes of an append step (partial states stay fp32 in the workspace; lse is
  * always written).
+ * Range of V in append mode with bf16 pools: the tile kernel multiplies P by V on the matrix cores in
+ * fp16 (P needs fp16's 11 significant bits to meet the output tolerance) and converts every bf16 V
+ * element to fp16 on its way from the pool: exact for 2^-14 <= |v| <= 65504; a larger magnitude enters
+ * the product as +-65504 (no infinity is produced); a smaller one is rounded toward zero to a multiple
+ * of 2^-24 (absolute error below 2^-24).  No error is reported for such values.  Decode mode and fp16
+ * pools use V as stored.  (tests/test_gpu_append.py feeds such values and asserts exactly this.)
  * Asynchronous on `stream`; uses the workspace given to the last fi_plan. */
 int32_t fi_run(fi_handle* h, const void* q, const void* k_pool, const void* v_pool,
                const int64_t* kv_strides, const int32_t* kv_indices, float sm_scale,
@@ -201,7 +210,7 @@ typedef struct fi_variant {
   int32_t window_left;
   const float* alibi_slopes;
   float rope_theta; /* > 0: rotary position embedding fused into the kernel (query / key transform, Sec. 3.2.3;
-                       Sec. 4.4): before the logits, key t is rotated by its position t and the query by pos;
+                       Sec. 4.3): before the logits, key t is rotated by its position t and the query by pos;
                        component pair (d, d + D/2) turns by (position / rope_scale) * rope_theta^(-2d/D) radians.
                        The cache holds the keys unrotated.  0 = off */
   float rope_scale; /* position divisor of the rotary embedding; 0 = 1 */

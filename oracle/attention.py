@@ -111,7 +111,7 @@ def variant_mask_and_bias(l_qo: int, l_kv: int, causal: bool, window_left: int =
 
 
 def rope(x: np.ndarray, pos: np.ndarray, theta: float, scale: float = 1.0) -> np.ndarray:
-    """Rotary position embedding as a query / key transform (Sec. 3.2.3; the fused-RoPE kernels of Sec. 4.4):
+    """Rotary position embedding as a query / key transform (Sec. 3.2.3; the fused-RoPE kernels of Sec. 4.3):
     x [n, D] at positions pos [n].  Component pair (d, d + D/2), d < D/2, is rotated by the angle
     (pos / scale) * theta ** (-2 d / D) (the "rotate half" pairing; the paper does not fix the pairing)."""
     n, D = x.shape

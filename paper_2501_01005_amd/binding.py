@@ -11,7 +11,7 @@ import numpy as np
 
 __all__ = [
     "FI_OK", "FI_ERR_INVALID_ARG", "FI_ERR_UNSUPPORTED", "FI_ERR_WORKSPACE_TOO_SMALL", "FI_ERR_NOT_PLANNED",
-    "FI_ERR_HIP", "FI_DTYPE_F16", "FI_DTYPE_BF16", "FI_MODE_DECODE", "FI_MODE_APPEND",
+    "FI_ERR_HIP", "FI_ERR_HOST_MEMORY", "FI_DTYPE_F16", "FI_DTYPE_BF16", "FI_MODE_DECODE", "FI_MODE_APPEND",
     "Fi355Error", "fi_config", "fi_plan_arrays", "lib", "library_path",
     "fi_create", "fi_destroy", "fi_workspace_bytes", "fi_plan", "fi_plan_view", "fi_run", "fi_run_kv8",
     "fi_run_variant", "fi_run_composed", "fi_variant", "fi_merge_states", "fi_merge_state_pair", "fi_check_indices", "fi_set_timing_events", "fi_last_error",
@@ -24,6 +24,7 @@ FI_ERR_UNSUPPORTED = -2
 FI_ERR_WORKSPACE_TOO_SMALL = -3
 FI_ERR_NOT_PLANNED = -4
 FI_ERR_HIP = -5
+FI_ERR_HOST_MEMORY = -6
 FI_DTYPE_F16 = 0
 FI_DTYPE_BF16 = 1
 FI_MODE_DECODE = 0

@@ -16,10 +16,27 @@ using namespace fi355;
 
 namespace {
 thread_local std::string g_last_error;
+thread_local const char* g_fixed_error = nullptr;  // a message that needed no allocation (set when one failed)
 
 int32_t set_error(int32_t code, const std::string& msg) {
+  g_fixed_error = nullptr;
   g_last_error = msg;
   return code;
+}
+
+// Every entry point runs inside this: the planner's vectors and the error strings allocate host memory, and
+// no C++ exception may cross the C boundary.
+template <class Body>
+int32_t guarded(Body&& body) noexcept {
+  try {
+    return body();
+  } catch (const std::bad_alloc&) {
+    g_fixed_error = "out of host memory inside the library";
+    return FI_ERR_HOST_MEMORY;
+  } catch (...) {
+    g_fixed_error = "unexpected C++ exception inside the library";
+    return FI_ERR_HOST_MEMORY;
+  }
 }
 int32_t hip_error(const char* what, hipError_t e) {
   return set_error(FI_ERR_HIP, std::string(what) + ": " + hipGetErrorString(e));
@@ -41,9 +58,8 @@ struct fi_handle {
   hipEvent_t ev_after = nullptr;
 };
 
-extern "C" {
+namespace impl {
 
-const char* fi_last_error(void) { return g_last_error.c_str(); }
 
 int32_t fi_create(const fi_config* cfg, fi_handle** out) {
   if (!cfg || !out) return set_error(FI_ERR_INVALID_ARG, "fi_create: null argument");
@@ -87,7 +103,7 @@ int32_t fi_create(const fi_config* cfg, fi_handle** out) {
     num_ctas = cfg->mode == FI_MODE_DECODE ? 8 * cus : cus;
   }
   fi_handle* h = new (std::nothrow) fi_handle();
-  if (!h) return set_error(FI_ERR_INVALID_ARG, "fi_create: out of host memory");
+  if (!h) return set_error(FI_ERR_HOST_MEMORY, "fi_create: out of host memory");
   h->cfg = *cfg;
   h->cfg.num_ctas = num_ctas;
   PlanParams& pp = h->pp;
@@ -109,8 +125,7 @@ int32_t fi_create(const fi_config* cfg, fi_handle** out) {
   pp.light_rows = (pp.refine && cfg->mode == FI_MODE_APPEND) ? append_tile_rows() / 2 : 0;
   pp.light_pct = 64;
   pp.kv_quantum = (pp.refine && cfg->mode == FI_MODE_APPEND) ? 64 : 1;  // the append kernel's KV tile
-  // default: decode chunks of at least 128 tokens (4 steps of a wavefront), append chunks of 256
-  // decode: one 32-token step of the kernel; with fewer tokens than that per CTA the chip is not filled, and a
+  // default smallest chunk: append 256 tokens; decode one 32-token step of the kernel: with fewer tokens than that per CTA the chip is not filled, and a
   // wavefront that walks 128 tokens alone takes longer than four that walk 32 each plus their merge
   pp.min_chunk = cfg->min_chunk > 0 ? cfg->min_chunk : (cfg->mode == FI_MODE_DECODE ? 32 : 256);
   pp.literal_lkv = cfg->literal_lkv != 0;
@@ -213,7 +228,7 @@ int32_t fi_plan_view(const fi_handle* h, fi_plan_arrays* out) {
   return FI_OK;
 }
 
-}  // extern "C"
+}  // namespace impl
 
 namespace {
 // fi_run and fi_run_kv8: kv8 = the pools hold E4M3 codes whose values are code * k_scale (v_scale)
@@ -352,7 +367,7 @@ int32_t run_impl(fi_handle* h, const void* q, const void* k_pool, const void* v_
 }
 }  // namespace
 
-extern "C" {
+namespace impl {
 
 int32_t fi_run(fi_handle* h, const void* q, const void* k_pool, const void* v_pool, const int64_t* kv_strides,
                const int32_t* kv_indices, float sm_scale, float* o, float* lse, void* o_cast, fi_stream stream) {
@@ -457,5 +472,65 @@ int32_t fi_check_indices(const int32_t* indices_host, int64_t n, int32_t num_pag
                                                std::to_string(num_pages) + ")");
   return FI_OK;
 }
+
+}  // namespace impl
+
+// ---- the exported C symbols: the functions above, with every C++ exception turned into a status ----
+extern "C" {
+
+const char* fi_last_error(void) { return g_fixed_error ? g_fixed_error : g_last_error.c_str(); }
+
+int32_t fi_create(const fi_config* cfg, fi_handle** out) {
+  return guarded([&]() -> int32_t { return impl::fi_create(cfg, out); });
+}
+
+int32_t fi_destroy(fi_handle* h) {
+  return guarded([&]() -> int32_t { return impl::fi_destroy(h); });
+}
+
+int32_t fi_workspace_bytes(const fi_handle* h, size_t* device_bytes, size_t* pinned_host_bytes) {
+  return guarded([&]() -> int32_t { return impl::fi_workspace_bytes(h, device_bytes, pinned_host_bytes); });
+}
+
+int32_t fi_plan(fi_handle* h, const int32_t* qo_indptr, const int32_t* kv_indptr, const int32_t* last_page_len, int32_t batch, int32_t causal, void* workspace_dev, size_t workspace_bytes, void* pinned_host, size_t pinned_bytes, fi_stream stream) {
+  return guarded([&]() -> int32_t { return impl::fi_plan(h, qo_indptr, kv_indptr, last_page_len, batch, causal, workspace_dev, workspace_bytes, pinned_host, pinned_bytes, stream); });
+}
+
+int32_t fi_plan_view(const fi_handle* h, fi_plan_arrays* out) {
+  return guarded([&]() -> int32_t { return impl::fi_plan_view(h, out); });
+}
+
+int32_t fi_run(fi_handle* h, const void* q, const void* k_pool, const void* v_pool, const int64_t* kv_strides, const int32_t* kv_indices, float sm_scale, float* o, float* lse, void* o_cast, fi_stream stream) {
+  return guarded([&]() -> int32_t { return impl::fi_run(h, q, k_pool, v_pool, kv_strides, kv_indices, sm_scale, o, lse, o_cast, stream); });
+}
+
+int32_t fi_run_variant(fi_handle* h, const void* q, const void* k_pool, const void* v_pool, const int64_t* kv_strides, const int32_t* kv_indices, const int32_t* kv_indptr, const int32_t* last_page_len, float sm_scale, const fi_variant* variant, float* o, float* lse, void* o_cast, fi_stream stream) {
+  return guarded([&]() -> int32_t { return impl::fi_run_variant(h, q, k_pool, v_pool, kv_strides, kv_indices, kv_indptr, last_page_len, sm_scale, variant, o, lse, o_cast, stream); });
+}
+
+int32_t fi_run_kv8(fi_handle* h, const void* q, const void* k_pool, const void* v_pool, const int64_t* kv_strides, const int32_t* kv_indices, float sm_scale, float k_scale, float v_scale, float* o, float* lse, void* o_cast, fi_stream stream) {
+  return guarded([&]() -> int32_t { return impl::fi_run_kv8(h, q, k_pool, v_pool, kv_strides, kv_indices, sm_scale, k_scale, v_scale, o, lse, o_cast, stream); });
+}
+
+int32_t fi_run_composed(fi_handle* h_a, fi_handle* h_b, const void* q, const void* k_pool, const void* v_pool, const int64_t* kv_strides, const int32_t* kv_indices_a, const int32_t* kv_indices_b, float sm_scale, float* o_a, float* lse_a, float* o_b, float* lse_b, int64_t nnz_qo, float* o, float* lse, void* o_cast, fi_stream stream) {
+  return guarded([&]() -> int32_t { return impl::fi_run_composed(h_a, h_b, q, k_pool, v_pool, kv_strides, kv_indices_a, kv_indices_b, sm_scale, o_a, lse_a, o_b, lse_b, nnz_qo, o, lse, o_cast, stream); });
+}
+
+int32_t fi_set_timing_events(fi_handle* h, void* before, void* after) {
+  return guarded([&]() -> int32_t { return impl::fi_set_timing_events(h, before, after); });
+}
+
+int32_t fi_merge_states(const float* o_parts, const float* lse_parts, int64_t n_rows, int32_t n_states, int32_t head_dim, float* o, float* lse, fi_stream stream) {
+  return guarded([&]() -> int32_t { return impl::fi_merge_states(o_parts, lse_parts, n_rows, n_states, head_dim, o, lse, stream); });
+}
+
+int32_t fi_merge_state_pair(const float* o_a, const float* lse_a, const float* o_b, const float* lse_b, int64_t n_rows, int32_t head_dim, float* o, float* lse, fi_stream stream) {
+  return guarded([&]() -> int32_t { return impl::fi_merge_state_pair(o_a, lse_a, o_b, lse_b, n_rows, head_dim, o, lse, stream); });
+}
+
+int32_t fi_check_indices(const int32_t* indices_host, int64_t n, int32_t num_pages) {
+  return guarded([&]() -> int32_t { return impl::fi_check_indices(indices_host, n, num_pages); });
+}
+
 
 }  // extern "C"

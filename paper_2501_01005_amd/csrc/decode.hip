@@ -113,7 +113,7 @@ struct KvTile {
 // pos = l_kv - 1 is the absolute position of the request's query.  A step may then hold no visible token; steps
 // wholly before the window are skipped without being read.
 // ROPE (with VAR): rotary position embedding as query and key transform (Sec. 3.2.3; the fused-RoPE kernels of
-// Sec. 4.4): key t of a request is rotated by its position t, the query by pos, pairing components (d, d + 64).
+// Sec. 4.3): key t of a request is rotated by its position t, the query by pos, pairing components (d, d + 64).
 // The rotated values are formed in fp32 from the K operands as they come back from LDS (a lane holds both
 // components of a pair there).  They enter the first product as a head and a remainder in the input type, as P
 // does in the second (three instructions per operand pair: head x head, remainder x head, head x remainder): a

@@ -84,3 +84,35 @@ def test_plan_for_append_equals_replica_with_default_grid():
     for k in ("cta_indptr", "w_q_row0", "w_n_pos", "w_kv_page0", "w_kv_start", "w_kv_len", "w_diag0", "w_out_slot"):
         assert got[k].tobytes() == np.asarray(want[k], dtype=np.int32).tobytes(), k
     w.close()
+
+
+def test_bf16_v_outside_the_fp16_range_behaves_as_documented():
+    """Append mode converts bf16 V to fp16 on its way into LDS (include/fi355.h, fi_run): exact for
+    2^-14 <= |v| <= 65504, larger magnitudes become +-65504, smaller ones are rounded toward zero to a multiple of
+    2^-24.  Every V row of a request holds the same vector here, so that o equals that vector whatever the
+    softmax weights are: the oracle on the in-range columns, the documented conversion on the others."""
+    b = workloads.make_batch("vrange", 77, workloads.BF16, 8, 2, 128, 16, [200, 20], [300, 50], True, num_pages=24,
+                             poison=False)
+    special = np.array([65280.0, 65536.0, 99840.0, -65536.0, -3.0e38, 2.0 ** -14, 2.0 ** -20, 2.0 ** -20 * (1 + 1 / 128),
+                        -(2.0 ** -15) * 1.5, 3 * 2.0 ** -26, 1.0, -2.5, 1000.0, 2.0 ** -24, 0.0, 6.1e-5], dtype=np.float32)
+    vstar = np.tile(special, 128 // len(special))
+    bits = workloads.f32_to_bits(vstar, workloads.BF16)
+    vstar = workloads.widen(bits, workloads.BF16)                      # what the cache really holds
+    b.v_bits[:] = bits[None, None, None, :]
+    # documented conversion: clamp, then toward zero onto the fp16 grid (spacing 2^-24 below 2^-14)
+    clamped = np.clip(vstar, -65504.0, 65504.0)
+    with np.errstate(divide="ignore"):
+        ulp = np.exp2(np.maximum(np.floor(np.log2(np.abs(clamped))), -14.0) - 10.0)
+    expected = np.where(clamped == 0, 0.0, np.trunc(clamped / ulp) * ulp)
+    in_range = (np.abs(vstar) >= 2.0 ** -14) & (np.abs(vstar) <= 65504.0) | (vstar == 0)
+    assert np.array_equal(expected[in_range], vstar[in_range]) and (~in_range).sum() >= 40
+    print(f"[case] bf16 V outside the fp16 range: {b.name}, {(~in_range).sum()} of 128 columns out of range", flush=True)
+    o_ref, lse_ref = oracle.run_batch(b)
+    assert np.allclose(o_ref[..., in_range], vstar[in_range], rtol=1e-12, atol=0)   # a convex combination of equal rows
+    for kw in (dict(num_ctas=2 * 4, min_chunk=16), dict()):       # both paths: short chunks and the scheduled loop
+        o, lse = run_gpu(b, "append", **kw)
+        assert not np.isnan(o).any()
+        assert np.abs(lse - lse_ref).max() <= 1e-3
+        rel = np.abs(o - expected) / np.maximum(np.abs(expected), 2.0 ** -24)
+        print(f"[ok] kw={kw}: max relative deviation from the documented conversion {rel.max():.2e}", flush=True)
+        assert rel.max() <= 1e-5, rel.max()

@@ -1,6 +1,6 @@
 """GPU parity at the full benchmark sizes, in the launch configuration bench.py times
-(library-default grid and chunk size).  Where the fp64 oracle would take minutes, it is
-run on a sample of requests; every sampled output element is compared."""
+(library-default grid and chunk size).  Every output element of every request is compared with
+the fp64 oracle (the long-context workload has two requests, both compared)."""
 import numpy as np
 import pytest
 
@@ -22,12 +22,10 @@ def sampled_check(batch, mode, requests, what, **kw):
 
 
 def test_config2_full_gqa_decode_zipf():
+    # the benchmarked workload: all 128 requests, i.e. every row that the 256 CTAs per kv head and the merge of
+    # the split tiles write
     b = workloads.config2()
-    kv = b.kv_lens()
-    # the forced 32768-token request (split over many CTAs), the shortest, the longest unsplit ones, a few more
-    order = np.argsort(kv)
-    sample = sorted({0, int(order[0]), int(order[-2]), int(order[len(order) // 2]), 17, 64, 127})
-    sampled_check(b, "decode", sample, "c2 full")
+    sampled_check(b, "decode", list(range(b.batch)), "c2 full")
 
 
 def test_config4_full_long_context_decode():
@@ -42,9 +40,7 @@ def test_config4_full_with_the_contraction_inside_the_launch():
 
 def test_config2_full_with_8_bit_kv_cache():
     b = workloads.config2(kv_dtype=workloads.FP8)
-    order = np.argsort(b.kv_lens())
-    sample = sorted({0, int(order[0]), int(order[-2]), int(order[len(order) // 2]), 17, 64, 127})
-    sampled_check(b, "decode", sample, "c2 full, E4M3 K/V")
+    sampled_check(b, "decode", list(range(b.batch)), "c2 full, E4M3 K/V")
 
 
 def test_config4_full_with_8_bit_kv_cache():
@@ -88,9 +84,4 @@ def test_config5_full_shared_prefix():
 def test_input_dynamism_workloads(kind, dist):
     """Batch 16 with constant, uniform and skewed lengths, decode and causal prefill (Sec. 4.2's kernel experiment)."""
     b = workloads.config_e2(kind, dist)
-    kv = b.kv_lens()
-    if kind == "decode":
-        sample = list(range(b.batch))
-    else:
-        sample = sorted({int(np.argmin(kv)), int(np.argmax(kv))})
-    sampled_check(b, "decode" if kind == "decode" else "append", sample, f"e2 {kind} {dist}")
+    sampled_check(b, "decode" if kind == "decode" else "append", list(range(b.batch)), f"e2 {kind} {dist}")

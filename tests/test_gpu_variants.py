@@ -60,7 +60,7 @@ def test_each_variant_and_all_together(dtype, g):
 
 @pytest.mark.parametrize("dtype", [workloads.BF16, workloads.F16])
 def test_fused_rotary_embedding(dtype):
-    """Keys are stored unrotated; the kernel rotates key t by t and the query by l_kv - 1 (Sec. 4.4's fused
+    """Keys are stored unrotated; the kernel rotates key t by t and the query by l_kv - 1 (Sec. 4.3's fused
     kernel).  Short and long requests, split chunks (a chunk's first token is not token 0), positions beyond
     65536 (where a single-precision angle would have lost its low bits), a position divisor, other variants on top."""
     b = workloads.random_case(430, dtype=dtype, num_qo_heads=8, num_kv_heads=2, batch=6, max_kv=700, value_scale=1.0)

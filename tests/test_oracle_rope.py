@@ -1,5 +1,5 @@
 """Pins for the oracle's rotary position embedding (query / key transform of Sec. 3.2.3; fused-RoPE attention,
-Sec. 4.4): what a rotation must satisfy, a closed form, a pure-Python brute force with explicit 2 x 2 rotations,
+Sec. 4.3): what a rotation must satisfy, a closed form, a pure-Python brute force with explicit 2 x 2 rotations,
 and the equivalence of the fused form with rotating the stored keys first and running plain attention."""
 import cmath
 import math

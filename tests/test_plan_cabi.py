@@ -247,3 +247,19 @@ def test_header_is_plain_c():
     header = os.path.join(os.path.dirname(__file__), "..", "include", "fi355.h")
     r = subprocess.run([gcc, "-fsyntax-only", "-x", "c", "-std=c99", "-Wall", "-Werror", header], capture_output=True, text=True)
     assert r.returncode == 0, r.stderr
+
+
+def test_committed_append_loops_are_what_the_generator_writes(tmp_path):
+    """The scheduled loops of the append kernel (csrc/append_loop_*.inc) are generated assembly that is committed
+    and compiled as is: regenerate them and compare, so that an edit by hand, or a generator change without
+    regeneration, fails here."""
+    import subprocess
+    import sys
+    csrc = os.path.join(ROOT, "paper_2501_01005_amd", "csrc")
+    subprocess.run([sys.executable, os.path.join(csrc, "gen", "gen_append_loop.py"), str(tmp_path)], check=True,
+                   capture_output=True)
+    generated = sorted(os.listdir(tmp_path))
+    committed = sorted(f for f in os.listdir(csrc) if f.startswith("append_loop_") and f.endswith(".inc"))
+    assert generated == committed and len(generated) >= 5
+    for f in generated:
+        assert open(os.path.join(tmp_path, f)).read() == open(os.path.join(csrc, f)).read(), f
