@@ -113,6 +113,10 @@ def test_bf16_v_outside_the_fp16_range_behaves_as_documented():
         o, lse = run_gpu(b, "append", **kw)
         assert not np.isnan(o).any()
         assert np.abs(lse - lse_ref).max() <= 1e-3
-        rel = np.abs(o - expected) / np.maximum(np.abs(expected), 2.0 ** -24)
-        print(f"[ok] kw={kw}: max relative deviation from the documented conversion {rel.max():.2e}", flush=True)
-        assert rel.max() <= 1e-5, rel.max()
+        # fp32 accumulation over up to 300 keys: 1e-5 relative; for the values on the 2^-24 grid a thousandth of a step
+        excess = np.abs(o - expected) - (1e-5 * np.abs(expected) + 1e-3 * 2.0 ** -24)
+        small = np.abs(vstar) < 2.0 ** -14
+        print(f"[ok] kw={kw}: deviation from the documented conversion: max relative {np.abs(o / np.where(expected == 0, 1, expected) - 1)[..., expected != 0].max():.2e}, "
+              f"max |o - v| on the columns below 2^-14: {np.abs(o - vstar)[..., small].max():.2e}", flush=True)
+        assert excess.max() <= 0, excess.max()
+        assert np.abs(o - vstar)[..., small].max() < 2.0 ** -24
