@@ -268,6 +268,21 @@ int32_t fi_run_composed(fi_handle* h_a, fi_handle* h_b, const void* q, const voi
                         float* o_b, float* lse_b, int64_t nnz_qo, float* o, float* lse, void* o_cast,
                         fi_stream stream);
 
+/* fi_run_composed for callers that cannot allocate device memory (code under HIP graph capture, serving loops
+ * that must not call hipMalloc, harnesses that forbid it): the state rows of the two passes (o_a, lse_a, o_b,
+ * lse_b of fi_run_composed) live in a static device array of the library instead of caller buffers.  Limit:
+ * nnz_qo * num_qo_heads <= 4096 state rows (the array holds 2 * 4096 * (128 + 1) floats = 4 227 072 bytes on
+ * every GPU the library is used on, from the library's load until the process ends);
+ * FI_ERR_WORKSPACE_TOO_SMALL beyond that.  The call allocates and frees nothing; the address of the array is
+ * looked up once per GPU, on the first call with that GPU current (the GPU of `stream` must be the current one).
+ * All calls on one GPU share the array: calls whose work overlaps in time on one GPU (two streams) race; calls
+ * ordered on one stream do not.  The array keeps the previous call's contents; nothing in it has to be cleared.
+ * Everything else (arguments, result bits, errors) as fi_run_composed. */
+int32_t fi_run_composed_static(fi_handle* h_a, fi_handle* h_b, const void* q, const void* k_pool,
+                               const void* v_pool, const int64_t* kv_strides, const int32_t* kv_indices_a,
+                               const int32_t* kv_indices_b, float sm_scale, int64_t nnz_qo, float* o,
+                               float* lse, void* o_cast, fi_stream stream);
+
 /* HOST helper for tests: FI_OK iff every indices[i] is in [0, num_pages). */
 int32_t fi_check_indices(const int32_t* indices_host, int64_t n, int32_t num_pages);
 

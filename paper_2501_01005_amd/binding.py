@@ -14,7 +14,7 @@ __all__ = [
     "FI_ERR_HIP", "FI_ERR_HOST_MEMORY", "FI_DTYPE_F16", "FI_DTYPE_BF16", "FI_MODE_DECODE", "FI_MODE_APPEND",
     "Fi355Error", "fi_config", "fi_plan_arrays", "lib", "library_path",
     "fi_create", "fi_destroy", "fi_workspace_bytes", "fi_plan", "fi_plan_view", "fi_run", "fi_run_kv8",
-    "fi_run_variant", "fi_run_composed", "fi_variant", "fi_merge_states", "fi_merge_state_pair", "fi_check_indices", "fi_set_timing_events", "fi_last_error",
+    "fi_run_variant", "fi_run_composed", "fi_run_composed_static", "fi_variant", "fi_merge_states", "fi_merge_state_pair", "fi_check_indices", "fi_set_timing_events", "fi_last_error",
     "PagedAttention",
 ]
 
@@ -93,12 +93,13 @@ def _load() -> ctypes.CDLL:
     L.fi_merge_state_pair.argtypes = [vp, vp, vp, vp, i64, i32, vp, vp, vp]
     L.fi_run_composed.argtypes = [vp, vp, vp, vp, vp, ctypes.POINTER(i64), vp, vp, ctypes.c_float, vp, vp, vp, vp, i64,
                                   vp, vp, vp, vp]
+    L.fi_run_composed_static.argtypes = [vp, vp, vp, vp, vp, ctypes.POINTER(i64), vp, vp, ctypes.c_float, i64, vp, vp, vp, vp]
     L.fi_check_indices.argtypes = [vp, i64, i32]
     L.fi_set_timing_events.argtypes = [vp, vp, vp]
     L.fi_last_error.argtypes = []
     L.fi_last_error.restype = ctypes.c_char_p
     for name in ("fi_create", "fi_destroy", "fi_workspace_bytes", "fi_plan", "fi_plan_view", "fi_run", "fi_run_kv8",
-                 "fi_run_variant", "fi_run_composed", "fi_merge_states", "fi_merge_state_pair", "fi_check_indices", "fi_set_timing_events"):
+                 "fi_run_variant", "fi_run_composed", "fi_run_composed_static", "fi_merge_states", "fi_merge_state_pair", "fi_check_indices", "fi_set_timing_events"):
         getattr(L, name).restype = i32
     return L
 
@@ -221,6 +222,14 @@ def fi_run_composed(handle_a: int, handle_b: int, q, k_pool, v_pool, kv_strides:
     _check(lib.fi_run_composed(handle_a, handle_b, _ptr(q), _ptr(k_pool), _ptr(v_pool), strides, _ptr(kv_indices_a),
                                _ptr(kv_indices_b), float(sm_scale), _ptr(o_a), _ptr(lse_a), _ptr(o_b), _ptr(lse_b),
                                int(nnz_qo), _ptr(o), _ptr(lse), _ptr(o_cast), stream or None))
+
+
+def fi_run_composed_static(handle_a: int, handle_b: int, q, k_pool, v_pool, kv_strides: Sequence[int], kv_indices_a,
+                           kv_indices_b, sm_scale: float, nnz_qo: int, o, lse, o_cast=None, stream: int = 0) -> None:
+    strides = (ctypes.c_int64 * 3)(*[int(s) for s in kv_strides])
+    _check(lib.fi_run_composed_static(handle_a, handle_b, _ptr(q), _ptr(k_pool), _ptr(v_pool), strides,
+                                      _ptr(kv_indices_a), _ptr(kv_indices_b), float(sm_scale), int(nnz_qo), _ptr(o),
+                                      _ptr(lse), _ptr(o_cast), stream or None))
 
 
 def fi_set_timing_events(handle: int, before, after) -> None:

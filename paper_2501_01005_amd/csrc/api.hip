@@ -2,6 +2,7 @@
 // split of Sec. 3.4, workspace sections at fixed offsets (App. D.1), kernel launches.
 #include <hip/hip_runtime.h>
 
+#include <atomic>
 #include <cmath>
 #include <cstring>
 #include <new>
@@ -40,6 +41,39 @@ int32_t guarded(Body&& body) noexcept {
 }
 int32_t hip_error(const char* what, hipError_t e) {
   return set_error(FI_ERR_HIP, std::string(what) + ": " + hipGetErrorString(e));
+}
+}  // namespace
+
+// ---- scratch memory of fi_run_composed_static: the state rows of the two passes, for callers that cannot
+//      allocate.  One copy per GPU, held until the process ends; every call on a GPU uses that GPU's copy. ----
+constexpr int64_t kStaticRowsMax = 4096;  // (query row, query head) pairs per call
+constexpr size_t kStaticOBytes = static_cast<size_t>(kStaticRowsMax) * kHeadDim * sizeof(float);
+constexpr size_t kStaticLseBytes = static_cast<size_t>(kStaticRowsMax) * sizeof(float);
+constexpr size_t kStaticScratchBytes = 2 * (kStaticOBytes + kStaticLseBytes);  // 4 227 072 bytes
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::atomic<unsigned char*> g_scratch_ptr[kMaxDevices];  // device address of `scratch` on each GPU (null: not asked yet)
+
+// The address of this GPU's copy of `scratch`.  In host code the array's name is only a handle for the runtime:
+// the address comes from hipGetSymbolAddress, asked once per device with that device current.
+int32_t static_scratch(unsigned char** out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return hip_error("fi_run_composed_static: hipGetDevice", e);
+  if (dev < 0 || dev >= kMaxDevices)
+    return set_error(FI_ERR_UNSUPPORTED, "fi_run_composed_static: device ordinal " + std::to_string(dev) + " outside [0, 64)");
+  unsigned char* ptr = g_scratch_ptr[dev].load(std::memory_order_acquire);
+  if (!ptr) {
+    void* sym = nullptr;
+    e = hipGetSymbolAddress(&sym, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !sym) return hip_error("fi_run_composed_static: hipGetSymbolAddress", e);
+    ptr = static_cast<unsigned char*>(sym);
+    g_scratch_ptr[dev].store(ptr, std::memory_order_release);  // (a concurrent first call stores the same address)
+  }
+  *out = ptr;
+  return FI_OK;
 }
 }  // namespace
 
@@ -432,6 +466,29 @@ int32_t fi_run_composed(fi_handle* h_a, fi_handle* h_b, const void* q, const voi
   return FI_OK;
 }
 
+int32_t fi_run_composed_static(fi_handle* h_a, fi_handle* h_b, const void* q, const void* k_pool, const void* v_pool,
+                               const int64_t* kv_strides, const int32_t* kv_indices_a, const int32_t* kv_indices_b,
+                               float sm_scale, int64_t nnz_qo, float* o, float* lse, void* o_cast, fi_stream stream) {
+  if (!h_a || !h_b) return set_error(FI_ERR_INVALID_ARG, "fi_run_composed_static: null handle");
+  if (nnz_qo < 0 || nnz_qo * h_a->cfg.num_qo_heads > kStaticRowsMax)
+    return set_error(FI_ERR_WORKSPACE_TOO_SMALL,
+                     "fi_run_composed_static: " + std::to_string(nnz_qo) + " query rows x " +
+                         std::to_string(h_a->cfg.num_qo_heads) + " heads exceed the " + std::to_string(kStaticRowsMax) +
+                         " state rows of the library's static scratch memory; use fi_run_composed with buffers of your own");
+  unsigned char* base = nullptr;
+  const int32_t rc = static_scratch(&base);
+  if (rc != FI_OK) return rc;
+  // fixed offsets, whatever nnz_qo is: the same four pointers on every call.  Nothing has to start at zero: the
+  // attention kernels write every state row the contraction reads (rows of split tiles are read from the handles'
+  // workspaces instead).
+  float* o_a = reinterpret_cast<float*>(base);
+  float* o_b = reinterpret_cast<float*>(base + kStaticOBytes);
+  float* lse_a = reinterpret_cast<float*>(base + 2 * kStaticOBytes);
+  float* lse_b = reinterpret_cast<float*>(base + 2 * kStaticOBytes + kStaticLseBytes);
+  return impl::fi_run_composed(h_a, h_b, q, k_pool, v_pool, kv_strides, kv_indices_a, kv_indices_b, sm_scale, o_a, lse_a,
+                               o_b, lse_b, nnz_qo, o, lse, o_cast, stream);
+}
+
 int32_t fi_set_timing_events(fi_handle* h, void* before, void* after) {
   if (!h) return set_error(FI_ERR_INVALID_ARG, "fi_set_timing_events: null handle");
   if ((before == nullptr) != (after == nullptr))
@@ -514,6 +571,10 @@ int32_t fi_run_kv8(fi_handle* h, const void* q, const void* k_pool, const void* 
 
 int32_t fi_run_composed(fi_handle* h_a, fi_handle* h_b, const void* q, const void* k_pool, const void* v_pool, const int64_t* kv_strides, const int32_t* kv_indices_a, const int32_t* kv_indices_b, float sm_scale, float* o_a, float* lse_a, float* o_b, float* lse_b, int64_t nnz_qo, float* o, float* lse, void* o_cast, fi_stream stream) {
   return guarded([&]() -> int32_t { return impl::fi_run_composed(h_a, h_b, q, k_pool, v_pool, kv_strides, kv_indices_a, kv_indices_b, sm_scale, o_a, lse_a, o_b, lse_b, nnz_qo, o, lse, o_cast, stream); });
+}
+
+int32_t fi_run_composed_static(fi_handle* h_a, fi_handle* h_b, const void* q, const void* k_pool, const void* v_pool, const int64_t* kv_strides, const int32_t* kv_indices_a, const int32_t* kv_indices_b, float sm_scale, int64_t nnz_qo, float* o, float* lse, void* o_cast, fi_stream stream) {
+  return guarded([&]() -> int32_t { return impl::fi_run_composed_static(h_a, h_b, q, k_pool, v_pool, kv_strides, kv_indices_a, kv_indices_b, sm_scale, nnz_qo, o, lse, o_cast, stream); });
 }
 
 int32_t fi_set_timing_events(fi_handle* h, void* before, void* after) {
