@@ -1,5 +1,6 @@
 """Pins for the replica of the paper's scheduling algorithm (Algorithm 1, Sec. 3.3.1):
-two pencil-worked examples stored as text fixtures, and the invariants the paper
+pencil-worked examples stored as text fixtures (two of the algorithm as printed, four of the
+planner's additions: fixed item cost, sliding window, refined assignment), and the invariants the paper
 states (App. D.2 write-through, App. D.3 partial-output bound, determinism)."""
 import os
 
@@ -31,19 +32,40 @@ def indptrs_from_lengths(qo_len, kv_len, page_size):
     return qo_indptr, kv_indptr, last
 
 
-@pytest.mark.parametrize("name", ["plan_decode_example.txt", "plan_causal_example.txt"])
+# as printed in the paper (the first two) and the planner's additions: the fixed cost per work item of the default
+# decode plan, the sliding window known to the planner, the refined assignment (one move and two swaps fire)
+HAND_WORKED = ["plan_decode_example.txt", "plan_causal_example.txt", "plan_item_cost_example.txt",
+               "plan_window_decode_example.txt", "plan_window_causal_example.txt", "plan_refine_example.txt"]
+FIXTURE_KEYS = ("cta_indptr", "w_request", "w_q_row0", "w_n_pos", "w_kv_page0", "w_kv_start", "w_kv_len", "w_diag0",
+                "w_out_slot", "w_merge", "cta_cost", "m_q_row0", "m_n_pos", "m_slot_base", "m_n_chunks")
+
+
+def replica_args(fx):
+    ps = fx["page_size"][0]
+    opt = lambda k, d: fx.get(k, [d])[0]
+    return dict(page_size=ps, t_pos=fx["t_pos"][0], group=fx["group"][0], num_ctas=fx["num_ctas"][0],
+                causal=bool(fx["causal"][0]), alpha=opt("alpha", 1), beta=opt("beta", 1), min_chunk=opt("min_chunk", ps),
+                refine=bool(opt("refine", 0)), light_rows=opt("light_rows", 0), light_pct=opt("light_pct", 100),
+                kv_quantum=opt("kv_quantum", 1), plan_window=opt("plan_window", 0), item_cost=opt("item_cost", 0))
+
+
+@pytest.mark.parametrize("name", HAND_WORKED)
 def test_hand_worked_examples(name):
     fx = load_fixture(name)
-    ps = fx["page_size"][0]
-    qo_indptr, kv_indptr, last = indptrs_from_lengths(fx["qo_len"], fx["kv_len"], ps)
-    p = plan_replica(qo_indptr, kv_indptr, last, page_size=ps, t_pos=fx["t_pos"][0], group=fx["group"][0],
-                     num_ctas=fx["num_ctas"][0], causal=bool(fx["causal"][0]),
-                     alpha=fx.get("alpha", [1])[0], beta=fx.get("beta", [1])[0], min_chunk=ps)
+    qo_indptr, kv_indptr, last = indptrs_from_lengths(fx["qo_len"], fx["kv_len"], fx["page_size"][0])
+    p = plan_replica(qo_indptr, kv_indptr, last, **replica_args(fx))
     assert p["L_kv"] == fx["L_kv"][0]
-    for key in ("cta_indptr", "w_request", "w_q_row0", "w_n_pos", "w_kv_start", "w_kv_len", "w_diag0",
-                "w_out_slot", "w_merge", "cta_cost", "m_q_row0", "m_n_pos", "m_slot_base", "m_n_chunks"):
+    for key in FIXTURE_KEYS:
         if key in fx:
             assert list(p[key]) == fx[key], key
+
+
+def test_item_cost_example_differs_from_the_algorithm_as_printed():
+    # the same lengths without the fixed item cost: Algorithm 1's own chunk length (64) and five work items
+    fx = load_fixture("plan_item_cost_example.txt")
+    qo_indptr, kv_indptr, last = indptrs_from_lengths(fx["qo_len"], fx["kv_len"], 16)
+    p = plan_replica(qo_indptr, kv_indptr, last, **{**replica_args(fx), "item_cost": 0})
+    assert p["L_kv"] == 64 and p["n_work"] == 5 and p["w_kv_len"] == [64, 64, 60, 50, 2]
 
 
 def random_lengths(rng, kind):

@@ -263,3 +263,34 @@ def test_committed_append_loops_are_what_the_generator_writes(tmp_path):
     assert generated == committed and len(generated) >= 5
     for f in generated:
         assert open(os.path.join(tmp_path, f)).read() == open(os.path.join(csrc, f)).read(), f
+
+
+@pytest.mark.parametrize("name", ["plan_decode_example.txt", "plan_item_cost_example.txt", "plan_window_decode_example.txt",
+                                  "plan_window_causal_example.txt", "plan_refine_example.txt"])
+def test_planner_reproduces_the_hand_worked_examples(name):
+    """The pencil-worked fixtures (those whose tile shape the library can be configured to: decode, or append with
+    g = 4) through fi_plan: the planner itself against the hand-worked arrays, not only against the replica."""
+    from test_oracle_plan import FIXTURE_KEYS, load_fixture
+    fx = load_fixture(name)
+    opt = lambda k, d: fx.get(k, [d])[0]
+    g, C, t_pos = fx["group"][0], fx["num_ctas"][0], fx["t_pos"][0]
+    decode = t_pos == 1
+    assert decode or (t_pos == 64 and g == 4)
+    if opt("refine", 0):
+        assert (opt("light_rows", 0), opt("light_pct", 100), opt("kv_quantum", 1)) == (128, 64, 64)   # the library's constants
+        balance = 2
+    elif opt("item_cost", 0):
+        assert decode and opt("item_cost", 0) == 64                                                 # the library's constant
+        balance = 0
+    else:
+        balance = 1
+    h = make(fi.FI_MODE_DECODE if decode else fi.FI_MODE_APPEND, g, C, alpha=opt("alpha", 1), beta=opt("beta", 1),
+             min_chunk=opt("min_chunk", 16), balance=balance, plan_window=opt("plan_window", 0))
+    qo_indptr, kv_indptr, last = indptrs(fx["qo_len"], fx["kv_len"])
+    fi.fi_plan(h, qo_indptr, kv_indptr, last, bool(fx["causal"][0]))
+    got = fi.fi_plan_view(h)
+    assert got["l_kv_chunk"] == fx["L_kv"][0]
+    for key in FIXTURE_KEYS:
+        if key in fx and key != "cta_cost":
+            assert got[key].tolist() == fx[key], key
+    fi.fi_destroy(h)
