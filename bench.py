@@ -118,7 +118,7 @@ def bench_shared_prefix(args) -> int:
     import torch
     import workloads
     import paper_2501_01005_amd as fi
-    from paper_2501_01005_amd.device import DeviceBatch, make_wrapper
+    from paper_2501_01005_amd.device import DeviceBatch, formats_of, make_formats_wrapper, make_wrapper
 
     c = workloads.config5(small=args.small)
     dev_p, dev_s, dev_1 = DeviceBatch(c.prefix), DeviceBatch(c.suffix), DeviceBatch(c.single)
@@ -131,9 +131,18 @@ def bench_shared_prefix(args) -> int:
     o_1 = torch.empty_like(o_p); l_1 = torch.empty_like(l_p)
     stream = torch.cuda.current_stream().cuda_stream
 
-    side = torch.cuda.Stream() if args.graph else None  # default priority
+    side = torch.cuda.Stream() if args.graph and args.c5_path != "formats" else None  # default priority
+    # both formats as one plan of one handle (fi_plan_formats): one attention launch + one contraction launch
+    formats, ids = formats_of([c.prefix, c.suffix])
+    wf = make_formats_wrapper([c.prefix, c.suffix], num_ctas=args.num_ctas, min_chunk=args.min_chunk)
+    ids_dev = torch.from_numpy(ids).to("cuda:0")
 
     def composed(plan=True):
+        if args.c5_path == "formats":
+            if plan:
+                wf.plan_formats(formats)
+            wf.run(dev_p.q, dev_p.k_pool, dev_p.v_pool, ids_dev, c.prefix.sm_scale, o=o_p, lse=l_p)
+            return
         if plan:
             wp.plan(c.prefix.qo_indptr, c.prefix.kv_indptr, c.prefix.last_page_len, causal=False)
             ws.plan(c.suffix.qo_indptr, c.suffix.kv_indptr, c.suffix.last_page_len, causal=False)
@@ -147,7 +156,7 @@ def bench_shared_prefix(args) -> int:
             main.wait_stream(side)
             fi.fi_merge_state_pair(o_p, l_p, o_s, l_s, n * H, D, o_p, l_p, main.cuda_stream)
             return
-        if not args.separate_merges:
+        if args.c5_path == "composed":
             # both attention launches, then one contraction launch over the partial states of both passes
             wp.run_composed(ws, dev_p.q, dev_p.k_pool, dev_p.v_pool, dev_p.kv_indices, dev_s.kv_indices, c.prefix.sm_scale,
                             o=o_p, lse=l_p)
@@ -192,15 +201,16 @@ def bench_shared_prefix(args) -> int:
         "vs_baseline": None, "dtype": c.prefix.dtype, "data": "synthetic",
         "config": {"workload": "c5_shared_prefix" + ("_small" if args.small else ""), "requests": n,
                    "prefix_tokens": int(c.prefix.kv_lens()[0]),
-                   "step": ("one captured graph, the two passes as parallel branches, replayed" if args.graph else
-                            ("2 attention launches + 3 merge launches" if args.separate_merges else
-                             "2 attention launches + 1 contraction launch (fi_run_composed)") +
-                            ("" if args.no_plan else ", 2 plans"))},
+                   "step": (("one captured graph, replayed: " if args.graph else "") +
+                            {"formats": "both formats in one plan: 1 attention launch + 1 contraction launch (fi_plan_formats, fi_run)",
+                             "composed": "2 attention launches + 1 contraction launch (fi_run_composed)",
+                             "separate": "2 attention launches + 3 merge launches"}[args.c5_path] +
+                            ("" if args.no_plan else ", planned every step"))},
         "frac_of_peak": bytes_comp / (us_comp * 1e-6) / 1e9 / HBM_PEAK_GBS,
         "composable_us": us_comp, "single_format_us": us_single, "speedup_vs_single_format": us_single / us_comp,
         "algorithmic_bytes_composable": bytes_comp, "algorithmic_bytes_single_format": bytes_single,
         "single_format_GBps": bytes_single / (us_single * 1e-6) / 1e9,
-        "roofline": {"bound": "hbm", "kernel": "latency-bound (3 dependent launches); see single_format_GBps for the streaming rate",
+        "roofline": {"bound": "hbm", "kernel": "latency-bound (dependent small launches); see single_format_GBps for the streaming rate",
                      "achieved": bytes_comp / (us_comp * 1e-6) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": bytes_comp / (us_comp * 1e-6) / 1e9 / HBM_PEAK_GBS, "traffic": None},
     }
@@ -259,8 +269,10 @@ def main() -> int:
                     help="fi_config.merge: 1 = partial states folded by a second launch, 2 = inside the attention launch "
                          "(decode), 0 = default")
     ap.add_argument("--suffix-min-chunk", type=int, default=0, help="c5: fi_config.min_chunk of the suffix (decode) handle")
-    ap.add_argument("--separate-merges", action="store_true",
-                    help="c5: fi_run on each format and fi_merge_state_pair (five launches) instead of fi_run_composed (three)")
+    ap.add_argument("--c5-path", default="formats", choices=["formats", "composed", "separate"],
+                    help="c5: formats = both formats planned as one work list on one 16-row-tile handle (fi_plan_formats; one "
+                         "attention launch + one contraction launch); composed = a handle per format, fi_run_composed (two "
+                         "attention launches + one contraction launch); separate = fi_run on each and fi_merge_state_pair (five)")
     ap.add_argument("--out16", action="store_true",
                     help="append workloads: write the output in the input type only (fi_run with o = NULL), not as fp32 rows")
     ap.add_argument("--alpha", type=int, default=0, help="fi_config.alpha (with --beta; 0, 0 = default)")
@@ -281,6 +293,8 @@ def main() -> int:
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         return 2
+    # the driver's invocation (no workload or variant flag): the headline workload plus an "also" block
+    plain_default = all(getattr(args, k) == ap.get_default(k) for k in vars(args) if k not in ("gpus", "steps", "warmup"))
     if args.calibrate_copy:
         n = (1 << 30) // 4
         src = torch.ones(n, dtype=torch.float32, device="cuda:0")
@@ -293,6 +307,33 @@ def main() -> int:
         return 0
     if args.workload == "c5":
         return bench_shared_prefix(args)
+    line = run_workload(args)
+    if isinstance(line, int):
+        return line
+    if plain_default:
+        # the other two roofline-bound workloads in the same process, each with its own settled warm-up: the
+        # matrix-bound append kernel (c3) and the long-context decode with split KV and merge (c4)
+        line["also"] = []
+        for wl in ("c3", "c4"):
+            sub = argparse.Namespace(**vars(args))
+            sub.workload, sub.no_cpu_baseline = wl, True
+            sub.warmup, sub.steps = max(args.warmup, 50), max(args.steps, 100)
+            extra = run_workload(sub)
+            if isinstance(extra, int):
+                return extra
+            line["also"].append({k: extra[k] for k in ("metric", "value", "unit", "steps", "warmup", "us_per_batch", "dtype",
+                                                       "config", "frac_of_peak", "host_plan_us", "roofline")})
+    print(json.dumps(line))
+    return 0
+
+
+def run_workload(args):
+    """One workload: set-up, warm-up, timed steps; returns the JSON line as a dict (or an exit code)."""
+    import torch
+    import workloads
+    import paper_2501_01005_amd as fi
+    from paper_2501_01005_amd.device import DeviceBatch, make_wrapper
+
     cfg_kw = {"permute_pages": False} if args.page_order == "identity" and args.workload in ("c2", "c3", "c4") else {}
     if args.kv_dtype == "fp8":
         if args.workload not in ("c2", "c4"):
@@ -387,7 +428,7 @@ def main() -> int:
         fi.fi_plan(w.handle, batch.qo_indptr, batch.kv_indptr, batch.last_page_len, batch.causal)
     plan_us = (time.perf_counter() - tp) / 20 * 1e6
 
-    traffic = None
+    traffic = None  # HBM bytes per launch by hardware counters: taken in an earlier profiled run of this command, not live
     tpath = os.path.join(ROOT, "profiles", "traffic.json")
     measured_setup = (args.page_size == 16 and args.page_order == "random" and args.kv_layout == "HND" and
                       args.window_left < 0 and args.soft_cap == 0 and not args.small)  # the counters were taken on these settings only
@@ -403,6 +444,7 @@ def main() -> int:
         metric, unit = "achieved HBM bandwidth, paged GQA decode step (algorithmic bytes / step time)", "GB/s"
         roof = {"bound": "hbm", "kernel": "decode_kernel", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
+                "traffic_source": "profiles/traffic.json: rocprofv3 FETCH_SIZE + WRITE_SIZE of an earlier run of this workload, not of this run",
                 "algorithmic_bytes_per_launch": ab["attention_kernel"], "avg_kernel_us": kern_avg_ms * 1e3,
                 "min_kernel_us": float(np.min(kern_ms)) * 1e3, "timed_launches": n_samples}
         base_work, base_unit = ab["step"] / 1e9, "GB/s"
@@ -414,6 +456,7 @@ def main() -> int:
         metric, unit = "achieved MFMA throughput, causal paged append step (algorithmic flop / step time)", "TFLOP/s"
         roof = {"bound": "mfma", "kernel": "append_kernel", "achieved": achieved, "peak": MFMA_PEAK_TFLOPS,
                 "unit": "TFLOP/s", "frac": achieved / MFMA_PEAK_TFLOPS, "traffic": traffic,
+                "traffic_source": "profiles/traffic.json: rocprofv3 FETCH_SIZE + WRITE_SIZE of an earlier run of this workload, not of this run",
                 "algorithmic_flop_per_launch": fl, "avg_kernel_us": kern_avg_ms * 1e3,
                 "min_kernel_us": float(np.min(kern_ms)) * 1e3, "timed_launches": n_samples}
         base_work, base_unit = fl / 1e12, "TFLOP/s"
@@ -438,10 +481,9 @@ def main() -> int:
     }
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(batch, base_work, base_unit)
-    print(json.dumps(line))
     ev.close()
     w.close()
-    return 0
+    return line
 
 
 if __name__ == "__main__":

@@ -55,6 +55,11 @@ extern "C" {
 
 #define FI_MODE_DECODE 0 /* query tile = 1 position x g fused heads; one wavefront per CTA   */
 #define FI_MODE_APPEND 1 /* query tile = 256/g positions x g fused heads; MFMA tile kernel     */
+#define FI_MODE_TILE16 2 /* query tile = 16/g positions x g fused heads = the 16 columns of the decode kernel's
+                            matrix tile, one wavefront per CTA (the small query tiles of Sec. 3.2.2): short
+                            appends (causal or not), and several formats over the same query rows planned and
+                            run as ONE work list and ONE attention launch (fi_plan_formats, Sec. 3.1.2).
+                            16-bit pools, page_size 16, no variants                                  */
 
 typedef struct fi_handle fi_handle;
 typedef void* fi_stream; /* a hipStream_t (0 = the null stream) */
@@ -71,9 +76,11 @@ typedef struct fi_config {
   int32_t mode;         /* FI_MODE_*                                                           */
   int32_t num_ctas;     /* total persistent CTAs over all kv heads; 0 = library default for
                            the current device (needs a GPU); CTAs per kv head = num_ctas/H_kv   */
-  int32_t max_batch;    /* upper bound on `batch` of any later fi_plan                         */
+  int32_t max_batch;    /* upper bound on `batch` of any later fi_plan (fi_plan_formats: on the sum
+                           of the formats' batches)                                            */
   int32_t max_qo_tiles; /* upper bound on the number of query tiles of any later fi_plan
-                           (decode: = max_batch; append: sum_i ceil(l_qo(i) / T_pos))           */
+                           (decode: = max_batch; otherwise sum_i ceil(l_qo(i) / T_pos), over all
+                           formats for fi_plan_formats)                                        */
   int32_t alpha;        /* cost(l_q, l_kv) = alpha*l_q + beta*l_kv of Algorithm 1; 0,0 = 1,1
                            (8,5 for the refined append assignment, see `balance`)              */
   int32_t beta;
@@ -135,10 +142,17 @@ typedef struct fi_plan_arrays {
   const int32_t* m_n_pos;     /* [n_merge]                                                     */
   const int32_t* m_slot_base; /* [n_merge] first slot; chunk c of the tile is slot base + c    */
   const int32_t* m_n_chunks;  /* [n_merge]                                                     */
+  /* plans over several formats (fi_plan_formats with n_formats > 1) have no merge list (n_merge = 0) and no
+   * write-through (every w_out_slot >= 0); instead every query row lists the partial states it folds:         */
+  int32_t n_rows;             /* query rows of such a plan, 0 otherwise                            */
+  int32_t pad2_;
+  const int32_t* row_indptr;  /* [n_rows + 1] row r folds row_entry[row_indptr[r] .. row_indptr[r + 1])   */
+  const int32_t* row_entry;   /* partial state = slot * t_pos + position of the row in the slot's tile,
+                                 formats in the order given, chunks of a tile in ascending KV order  */
 } fi_plan_arrays;
 
 /* Create / destroy a handle.  cfg HOST.  FI_ERR_UNSUPPORTED unless head_dim = 128,
- * page_size a power of two in 1..64, g in {1,2,4,8,16}.  With num_ctas = 0 the
+ * page_size a power of two in 1..64 (16 in FI_MODE_TILE16), g in {1,2,4,8,16}.  With num_ctas = 0 the
  * current HIP device is queried (FI_ERR_HIP without one). */
 int32_t fi_create(const fi_config* cfg, fi_handle** out);
 int32_t fi_destroy(fi_handle* h);
@@ -163,6 +177,21 @@ int32_t fi_plan(fi_handle* h, const int32_t* qo_indptr, const int32_t* kv_indptr
                 const int32_t* last_page_len, int32_t batch, int32_t causal,
                 void* workspace_dev, size_t workspace_bytes,
                 void* pinned_host, size_t pinned_bytes, fi_stream stream);
+
+/* Composable formats (Sec. 3.1.2) as one plan: n_formats (1..8) block-sparse-row views of the KV pool over the
+ * SAME nnz_qo query rows (say format 0 = one row block of all queries against the pages of a shared prefix,
+ * format 1 = one row per request against its own pages), each given by its HOST arrays qo_indptr[f] [batch[f] + 1],
+ * kv_indptr[f] [batch[f] + 1], last_page_len[f] [batch[f]], with kv_indptr[f] indexing the page-id array that fi_run
+ * gets from element kv_indices_base[f] on (the caller keeps the formats' page ids one after the other in one
+ * DEVICE array).  Every qo_indptr[f] must end at the same row count.  Algorithm 1 runs over the query tiles of all
+ * formats at once: one chunk size, one set of queues, hence one persistent attention launch in fi_run, followed
+ * by one contraction launch in which every query row folds its partial states (formats in the given order,
+ * chunks in ascending KV order, Sec. 2.2).  Not causal.  Handle: FI_MODE_TILE16 (FI_ERR_UNSUPPORTED otherwise).
+ * With n_formats = 1 this is fi_plan with causal = 0.  Other arguments, staging and errors as fi_plan. */
+int32_t fi_plan_formats(fi_handle* h, int32_t n_formats, const int32_t* const* qo_indptr,
+                        const int32_t* const* kv_indptr, const int32_t* const* last_page_len,
+                        const int32_t* batch, const int32_t* kv_indices_base, void* workspace_dev,
+                        size_t workspace_bytes, void* pinned_host, size_t pinned_bytes, fi_stream stream);
 
 /* Borrowed views of the handle's last plan; valid until the next fi_plan / fi_destroy. */
 int32_t fi_plan_view(const fi_handle* h, fi_plan_arrays* out);

@@ -60,24 +60,54 @@ from typing import Dict, List, Sequence
 NO_DIAG = 0x3FFFFFFF   # "row sees everything" marker for non-causal work items
 
 
-def plan_replica(qo_indptr: Sequence[int], kv_indptr: Sequence[int], last_page_len: Sequence[int],
-                 *, page_size: int, t_pos: int, group: int, num_ctas: int, causal: bool,
-                 alpha: int = 1, beta: int = 1, min_chunk: int | None = None,
-                 literal_lkv: bool = False, refine: bool = False, light_rows: int = 0,
-                 light_pct: int = 100, kv_quantum: int = 1, plan_window: int = 0,
-                 item_cost: int = 0) -> Dict[str, object]:
-    B = len(last_page_len)
+def _requests_of(qo_indptr, kv_indptr, last_page_len, page_size, kv_base=0):
+    """(first query row, l_qo, l_kv, index of the first page id) of every request of one format"""
+    out = []
+    for i in range(len(last_page_len)):
+        n_pg = int(kv_indptr[i + 1]) - int(kv_indptr[i])
+        l_kv = 0 if n_pg == 0 else (n_pg - 1) * page_size + int(last_page_len[i])
+        out.append((int(qo_indptr[i]), int(qo_indptr[i + 1]) - int(qo_indptr[i]), l_kv, kv_base + int(kv_indptr[i])))
+    return out
+
+
+def plan_replica(qo_indptr: Sequence[int], kv_indptr: Sequence[int], last_page_len: Sequence[int], **kw) -> Dict[str, object]:
+    """Algorithm 1 over one format (keyword arguments: see _plan)."""
+    return _plan(_requests_of(qo_indptr, kv_indptr, last_page_len, kw["page_size"]), composed=False, **kw)
+
+
+def plan_replica_formats(formats, **kw) -> Dict[str, object]:
+    """Several formats over the same query rows (Sec. 3.1.2) planned as one work list: `formats` is a sequence of
+    (qo_indptr, kv_indptr, last_page_len, kv_base), kv_base = where the format's page ids start in the one page-id
+    array all formats share.  Requests are numbered through the formats in the given order, Algorithm 1 then runs
+    unchanged over all their query tiles.  With more than one format (a reading of this build; the paper composes
+    formats by merging the states of separate kernels, Sec. 2.2) no tile writes through: every work item writes a
+    partial state into its own slot (slots numbered tile by tile, chunk c of a tile at slot_base + c), the merge
+    list stays empty, and `row_indptr` / `row_entry` list for every query row the partial states it folds, formats
+    in the given order, chunks in ascending KV order, each as slot * t_pos + (row - first row of the tile)."""
+    reqs = []
+    for (qo_indptr, kv_indptr, last_page_len, kv_base) in formats:
+        reqs += _requests_of(qo_indptr, kv_indptr, last_page_len, kw["page_size"], kv_base)
+    n_rows = int(formats[0][0][-1])
+    assert all(int(f[0][-1]) == n_rows for f in formats), "the formats cover different numbers of query rows"
+    return _plan(reqs, composed=len(formats) > 1, n_rows=n_rows, **kw)
+
+
+def _plan(requests, *, composed: bool, n_rows: int = 0, page_size: int, t_pos: int, group: int, num_ctas: int, causal: bool,
+          alpha: int = 1, beta: int = 1, min_chunk: int | None = None,
+          literal_lkv: bool = False, refine: bool = False, light_rows: int = 0,
+          light_pct: int = 100, kv_quantum: int = 1, plan_window: int = 0,
+          item_cost: int = 0) -> Dict[str, object]:
+    B = len(requests)
     if min_chunk is None:
         min_chunk = page_size
     min_chunk = ((min_chunk + page_size - 1) // page_size) * page_size
     T_q = t_pos * group
 
     # -- lengths -----------------------------------------------------------
-    l_qo = [int(qo_indptr[i + 1]) - int(qo_indptr[i]) for i in range(B)]
-    l_kv = []
-    for i in range(B):
-        n_pg = int(kv_indptr[i + 1]) - int(kv_indptr[i])
-        l_kv.append(0 if n_pg == 0 else (n_pg - 1) * page_size + int(last_page_len[i]))
+    q_row0_of = [r[0] for r in requests]
+    l_qo = [r[1] for r in requests]
+    l_kv = [r[2] for r in requests]
+    page0_of = [r[3] for r in requests]
 
     # -- query tiles and the KV range each one needs -------------------------
     tiles = []        # (request, tile_start, n_pos, kv_eff, diag0)
@@ -130,9 +160,9 @@ def plan_replica(qo_indptr: Sequence[int], kv_indptr: Sequence[int], last_page_l
         for c in range(n_chunks):
             lo = kv_begin + c * L_kv
             hi = min(lo + L_kv, kv_eff)
-            work.append(dict(request=i, q_row0=int(qo_indptr[i]) + start, n_pos=n_pos,
+            work.append(dict(request=i, q_row0=q_row0_of[i] + start, n_pos=n_pos,
                              kv_start=lo, kv_len=hi - lo,
-                             kv_page0=int(kv_indptr[i]) + lo // page_size,
+                             kv_page0=page0_of[i] + lo // page_size,
                              diag0=diag0, tile=len(tile_chunks) - 1, chunk=c))
 
     # -- output index map ------------------------------------------------------
@@ -140,11 +170,20 @@ def plan_replica(qo_indptr: Sequence[int], kv_indptr: Sequence[int], last_page_l
     merge_index_of_tile = []
     merge = []        # per split tile: (q_row0, n_pos, slot_base, n_chunks)
     next_slot = 0
+    row_lists: List[List[int]] = [[] for _ in range(n_rows)] if composed else []
     for ti, (i, start, n_pos, kv_eff, diag0, kv_begin) in enumerate(tiles):
-        if tile_chunks[ti] > 1:
+        if composed:
+            # several formats: no write-through, every chunk of every tile owns a slot, and every query row of the
+            # tile notes the partial states it will fold
+            slot_base_of_tile.append(next_slot)
+            merge_index_of_tile.append(-1)
+            for pos in range(n_pos):
+                row_lists[q_row0_of[i] + start + pos] += [(next_slot + c) * t_pos + pos for c in range(tile_chunks[ti])]
+            next_slot += tile_chunks[ti]
+        elif tile_chunks[ti] > 1:
             slot_base_of_tile.append(next_slot)
             merge_index_of_tile.append(len(merge))
-            merge.append((int(qo_indptr[i]) + start, n_pos, next_slot, tile_chunks[ti]))
+            merge.append((q_row0_of[i] + start, n_pos, next_slot, tile_chunks[ti]))
             next_slot += tile_chunks[ti]
         else:
             slot_base_of_tile.append(-1)
@@ -221,7 +260,14 @@ def plan_replica(qo_indptr: Sequence[int], kv_indptr: Sequence[int], last_page_l
     def col(name):
         return [work[w][name] for w in flat]
 
+    rows = {}
+    if composed:
+        row_indptr = [0]
+        for lst in row_lists:
+            row_indptr.append(row_indptr[-1] + len(lst))
+        rows = dict(n_rows=n_rows, row_indptr=row_indptr, row_entry=[e for lst in row_lists for e in lst])
     return dict(
+        **rows,
         L_kv=L_kv, S=S, n_work=len(work), n_merge=len(merge), n_slots=next_slot,
         cta_indptr=cta_indptr,
         w_request=col("request"), w_q_row0=col("q_row0"), w_n_pos=col("n_pos"),

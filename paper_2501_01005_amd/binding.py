@@ -11,9 +11,9 @@ import numpy as np
 
 __all__ = [
     "FI_OK", "FI_ERR_INVALID_ARG", "FI_ERR_UNSUPPORTED", "FI_ERR_WORKSPACE_TOO_SMALL", "FI_ERR_NOT_PLANNED",
-    "FI_ERR_HIP", "FI_ERR_HOST_MEMORY", "FI_DTYPE_F16", "FI_DTYPE_BF16", "FI_MODE_DECODE", "FI_MODE_APPEND",
+    "FI_ERR_HIP", "FI_ERR_HOST_MEMORY", "FI_DTYPE_F16", "FI_DTYPE_BF16", "FI_MODE_DECODE", "FI_MODE_APPEND", "FI_MODE_TILE16",
     "Fi355Error", "fi_config", "fi_plan_arrays", "lib", "library_path",
-    "fi_create", "fi_destroy", "fi_workspace_bytes", "fi_plan", "fi_plan_view", "fi_run", "fi_run_kv8",
+    "fi_create", "fi_destroy", "fi_workspace_bytes", "fi_plan", "fi_plan_formats", "fi_plan_view", "fi_run", "fi_run_kv8",
     "fi_run_variant", "fi_run_composed", "fi_run_composed_static", "fi_variant", "fi_merge_states", "fi_merge_state_pair", "fi_check_indices", "fi_set_timing_events", "fi_last_error",
     "PagedAttention",
 ]
@@ -29,6 +29,7 @@ FI_DTYPE_F16 = 0
 FI_DTYPE_BF16 = 1
 FI_MODE_DECODE = 0
 FI_MODE_APPEND = 1
+FI_MODE_TILE16 = 2
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 
@@ -64,7 +65,8 @@ class fi_plan_arrays(ctypes.Structure):
         "t_pos", "group", "ctas_per_head", "l_kv_chunk", "n_work", "n_merge", "n_slots", "pad_")] + [
         (n, _I32P) for n in (
             "cta_indptr", "w_request", "w_q_row0", "w_n_pos", "w_kv_page0", "w_kv_start", "w_kv_len", "w_diag0",
-            "w_out_slot", "w_merge", "m_q_row0", "m_n_pos", "m_slot_base", "m_n_chunks")]
+            "w_out_slot", "w_merge", "m_q_row0", "m_n_pos", "m_slot_base", "m_n_chunks")] + [
+        ("n_rows", ctypes.c_int32), ("pad2_", ctypes.c_int32), ("row_indptr", _I32P), ("row_entry", _I32P)]
 
 
 def _load() -> ctypes.CDLL:
@@ -83,6 +85,7 @@ def _load() -> ctypes.CDLL:
     L.fi_destroy.argtypes = [vp]
     L.fi_workspace_bytes.argtypes = [vp, ctypes.POINTER(sz), ctypes.POINTER(sz)]
     L.fi_plan.argtypes = [vp, vp, vp, vp, i32, i32, vp, sz, vp, sz, vp]
+    L.fi_plan_formats.argtypes = [vp, i32, ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.POINTER(vp), vp, vp, vp, sz, vp, sz, vp]
     L.fi_plan_view.argtypes = [vp, ctypes.POINTER(fi_plan_arrays)]
     L.fi_run.argtypes = [vp, vp, vp, vp, ctypes.POINTER(i64), vp, ctypes.c_float, vp, vp, vp, vp]
     L.fi_run_variant.argtypes = [vp, vp, vp, vp, ctypes.POINTER(i64), vp, vp, vp, ctypes.c_float,
@@ -98,7 +101,7 @@ def _load() -> ctypes.CDLL:
     L.fi_set_timing_events.argtypes = [vp, vp, vp]
     L.fi_last_error.argtypes = []
     L.fi_last_error.restype = ctypes.c_char_p
-    for name in ("fi_create", "fi_destroy", "fi_workspace_bytes", "fi_plan", "fi_plan_view", "fi_run", "fi_run_kv8",
+    for name in ("fi_create", "fi_destroy", "fi_workspace_bytes", "fi_plan", "fi_plan_formats", "fi_plan_view", "fi_run", "fi_run_kv8",
                  "fi_run_variant", "fi_run_composed", "fi_run_composed_static", "fi_merge_states", "fi_merge_state_pair", "fi_check_indices", "fi_set_timing_events"):
         getattr(L, name).restype = i32
     return L
@@ -163,6 +166,26 @@ def fi_plan(handle: int, qo_indptr, kv_indptr, last_page_len, causal: bool, work
                        stream or None))
 
 
+def fi_plan_formats(handle: int, formats, workspace=None, workspace_bytes: int = 0, pinned=None, pinned_bytes: int = 0,
+                    stream: int = 0) -> None:
+    """formats: sequence of (qo_indptr, kv_indptr, last_page_len, kv_indices_base) per format."""
+    n = len(formats)
+    keep = []
+    ptrs = [(ctypes.c_void_p * n)() for _ in range(3)]
+    batch = np.zeros(n, dtype=np.int32)
+    base = np.zeros(n, dtype=np.int32)
+    for f, (qo, kv, lp, kv_base) in enumerate(formats):
+        arrs = (_host_i32(qo), _host_i32(kv), _host_i32(lp))
+        if len(arrs[0]) != len(arrs[2]) + 1 or len(arrs[1]) != len(arrs[2]) + 1:
+            raise ValueError("indptr arrays must have batch + 1 entries")
+        keep.append(arrs)
+        for k in range(3):
+            ptrs[k][f] = arrs[k].ctypes.data if len(arrs[k]) else None
+        batch[f], base[f] = len(arrs[2]), int(kv_base)
+    _check(lib.fi_plan_formats(handle, n, ptrs[0], ptrs[1], ptrs[2], batch.ctypes.data, base.ctypes.data,
+                               _ptr(workspace), workspace_bytes, _ptr(pinned), pinned_bytes, stream or None))
+
+
 def fi_plan_view(handle: int) -> dict:
     pa = fi_plan_arrays()
     _check(lib.fi_plan_view(handle, ctypes.byref(pa)))
@@ -177,6 +200,10 @@ def fi_plan_view(handle: int) -> dict:
         out[k] = arr(getattr(pa, k), pa.n_work)
     for k in ("m_q_row0", "m_n_pos", "m_slot_base", "m_n_chunks"):
         out[k] = arr(getattr(pa, k), pa.n_merge)
+    out["n_rows"] = pa.n_rows
+    if pa.n_rows > 0:   # a plan over several formats: the partial states every query row folds
+        out["row_indptr"] = arr(pa.row_indptr, pa.n_rows + 1)
+        out["row_entry"] = arr(pa.row_entry, int(out["row_indptr"][-1]))
     return out
 
 
@@ -263,7 +290,7 @@ class PagedAttention:
             self.handle = fi_create(
                 dtype={"f16": FI_DTYPE_F16, "bf16": FI_DTYPE_BF16}[dtype], num_qo_heads=num_qo_heads,
                 num_kv_heads=num_kv_heads, head_dim=head_dim, page_size=page_size,
-                mode={"decode": FI_MODE_DECODE, "append": FI_MODE_APPEND}[mode], num_ctas=num_ctas,
+                mode={"decode": FI_MODE_DECODE, "append": FI_MODE_APPEND, "tile16": FI_MODE_TILE16}[mode], num_ctas=num_ctas,
                 max_batch=max_batch, max_qo_tiles=max_qo_tiles if max_qo_tiles is not None else max_batch,
                 alpha=alpha, beta=beta, min_chunk=min_chunk, literal_lkv=1 if literal_lkv else 0, balance=balance,
                 merge=merge, plan_window=plan_window)
@@ -297,6 +324,17 @@ class PagedAttention:
             self._ring_events[i].synchronize()
         fi_plan(self.handle, qo_indptr, kv_indptr, last_page_len, causal, self.workspace, self.ws_bytes,
                 self._ring[i], self.pin_bytes, self._stream())
+        if self._ring_events[i] is None:
+            self._ring_events[i] = self.torch.cuda.Event()
+        self._ring_events[i].record(self.torch.cuda.current_stream(self.device))
+
+    def plan_formats(self, formats) -> None:
+        """formats: sequence of (qo_indptr, kv_indptr, last_page_len, kv_indices_base); see fi_plan_formats."""
+        i = self._ring_pos
+        self._ring_pos = (i + 1) % len(self._ring)
+        if self._ring_events[i] is not None:
+            self._ring_events[i].synchronize()
+        fi_plan_formats(self.handle, formats, self.workspace, self.ws_bytes, self._ring[i], self.pin_bytes, self._stream())
         if self._ring_events[i] is None:
             self._ring_events[i] = self.torch.cuda.Event()
         self._ring_events[i].record(self.torch.cuda.current_stream(self.device))

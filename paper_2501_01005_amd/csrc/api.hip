@@ -77,6 +77,8 @@ int32_t static_scratch(unsigned char** out) {
 }
 }  // namespace
 
+constexpr int32_t kMaxFormats = 8;  // formats one fi_plan_formats call composes
+
 struct fi_handle {
   fi_config cfg;
   PlanParams pp;
@@ -85,6 +87,7 @@ struct fi_handle {
   bool planned_host = false;
   bool planned_dev = false;
   bool pp_causal_last = false;  // `causal` of the last successful fi_plan
+  int32_t n_formats_last = 1;   // formats of the last successful plan (> 1: every state is partial, rows fold by list)
   int64_t nnz_qo_last = 0;      // query rows of the last successful fi_plan
   void* workspace_dev = nullptr;
   size_t workspace_bytes = 0;
@@ -100,7 +103,7 @@ int32_t fi_create(const fi_config* cfg, fi_handle** out) {
   *out = nullptr;
   if (cfg->dtype != FI_DTYPE_F16 && cfg->dtype != FI_DTYPE_BF16)
     return set_error(FI_ERR_INVALID_ARG, "fi_create: dtype must be FI_DTYPE_F16 or FI_DTYPE_BF16");
-  if (cfg->mode != FI_MODE_DECODE && cfg->mode != FI_MODE_APPEND)
+  if (cfg->mode != FI_MODE_DECODE && cfg->mode != FI_MODE_APPEND && cfg->mode != FI_MODE_TILE16)
     return set_error(FI_ERR_INVALID_ARG, "fi_create: unknown mode");
   if (cfg->num_qo_heads <= 0 || cfg->num_kv_heads <= 0 || cfg->num_qo_heads % cfg->num_kv_heads != 0)
     return set_error(FI_ERR_INVALID_ARG, "fi_create: num_qo_heads must be a positive multiple of num_kv_heads");
@@ -124,6 +127,10 @@ int32_t fi_create(const fi_config* cfg, fi_handle** out) {
     return set_error(FI_ERR_UNSUPPORTED, "fi_create: the contraction inside the attention launch is built for group size 1, 2, 4");
   if (cfg->mode == FI_MODE_APPEND && !(g == 1 || g == 2 || g == 4 || g == 8 || g == 16))
     return set_error(FI_ERR_UNSUPPORTED, "fi_create: append mode is built for group size 1, 2, 4, 8, 16");
+  const bool small_tiles = cfg->mode == FI_MODE_TILE16;
+  if (small_tiles && (!(g == 1 || g == 2 || g == 4 || g == 8 || g == 16) || cfg->page_size != kPageSize || cfg->plan_window > 0))
+    return set_error(FI_ERR_UNSUPPORTED, "fi_create: the 16-row tile mode is built for group size 1, 2, 4, 8, 16, page_size 16, "
+                                         "no planned window");
 
   int num_ctas = cfg->num_ctas;
   if (num_ctas == 0) {
@@ -134,7 +141,7 @@ int32_t fi_create(const fi_config* cfg, fi_handle** out) {
     e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
     if (e != hipSuccess) return hip_error("fi_create: hipDeviceGetAttribute", e);
     // decode: one wavefront per CTA, 8 resident per CU; append: one 8-wavefront CTA per CU
-    num_ctas = cfg->mode == FI_MODE_DECODE ? 8 * cus : cus;
+    num_ctas = cfg->mode == FI_MODE_APPEND ? cus : 8 * cus;
   }
   fi_handle* h = new (std::nothrow) fi_handle();
   if (!h) return set_error(FI_ERR_HOST_MEMORY, "fi_create: out of host memory");
@@ -143,7 +150,7 @@ int32_t fi_create(const fi_config* cfg, fi_handle** out) {
   PlanParams& pp = h->pp;
   pp.page_size = cfg->page_size;
   pp.group = g;
-  pp.t_pos = cfg->mode == FI_MODE_DECODE ? 1 : append_tile_rows() / g;
+  pp.t_pos = cfg->mode == FI_MODE_DECODE ? 1 : cfg->mode == FI_MODE_TILE16 ? 16 / g : append_tile_rows() / g;
   pp.ctas_per_head = num_ctas / cfg->num_kv_heads > 0 ? num_ctas / cfg->num_kv_heads : 1;
   // Decode items are short and many: the greedy pass of Algorithm 1 balances them to about 1 %.  Append
   // items are few and long (C3: 4.8 per CTA): there the refined assignment is the default, with the cost
@@ -152,7 +159,7 @@ int32_t fi_create(const fi_config* cfg, fi_handle** out) {
   pp.plan_window = cfg->plan_window;
   pp.refine = cfg->balance == 2 || (cfg->balance == 0 && cfg->mode == FI_MODE_APPEND);
   // decode: a work item costs a wavefront about as much as 64 more tokens before its first tile arrives
-  pp.item_cost = (cfg->balance == 0 && cfg->mode == FI_MODE_DECODE) ? 64 : 0;
+  pp.item_cost = (cfg->balance == 0 && cfg->mode != FI_MODE_APPEND) ? 64 : 0;
   const bool default_cost = cfg->alpha == 0 && cfg->beta == 0;
   pp.alpha = default_cost ? (pp.refine && cfg->mode == FI_MODE_APPEND ? 8 : 1) : cfg->alpha;
   pp.beta = default_cost ? (pp.refine && cfg->mode == FI_MODE_APPEND ? 5 : 1) : cfg->beta;
@@ -161,11 +168,12 @@ int32_t fi_create(const fi_config* cfg, fi_handle** out) {
   pp.kv_quantum = (pp.refine && cfg->mode == FI_MODE_APPEND) ? 64 : 1;  // the append kernel's KV tile
   // default smallest chunk: append 256 tokens; decode one 32-token step of the kernel: with fewer tokens than that per CTA the chip is not filled, and a
   // wavefront that walks 128 tokens alone takes longer than four that walk 32 each plus their merge
-  pp.min_chunk = cfg->min_chunk > 0 ? cfg->min_chunk : (cfg->mode == FI_MODE_DECODE ? 32 : 256);
+  pp.min_chunk = cfg->min_chunk > 0 ? cfg->min_chunk : (cfg->mode == FI_MODE_APPEND ? 256 : 32);
   pp.literal_lkv = cfg->literal_lkv != 0;
   pp.max_batch = cfg->max_batch;
   pp.max_qo_tiles = cfg->max_qo_tiles;
-  h->layout.init(pp.ctas_per_head, cfg->max_qo_tiles, pp.t_pos, cfg->num_qo_heads, cfg->num_kv_heads, cfg->head_dim);
+  h->layout.init(pp.ctas_per_head, cfg->max_qo_tiles, pp.t_pos, cfg->num_qo_heads, cfg->num_kv_heads, cfg->head_dim,
+                 small_tiles);
   h->host_plan.assign(h->layout.plan_ints, 0);
   *out = h;
   return FI_OK;
@@ -183,10 +191,9 @@ int32_t fi_workspace_bytes(const fi_handle* h, size_t* device_bytes, size_t* pin
   return FI_OK;
 }
 
-int32_t fi_plan(fi_handle* h, const int32_t* qo_indptr, const int32_t* kv_indptr, const int32_t* last_page_len,
-                int32_t batch, int32_t causal, void* workspace_dev, size_t workspace_bytes, void* pinned_host,
-                size_t pinned_bytes, fi_stream stream) {
-  if (!h) return set_error(FI_ERR_INVALID_ARG, "fi_plan: null handle");
+// fi_plan and fi_plan_formats: plan on the host, then one transfer into the plan section of the workspace
+int32_t plan_and_upload(fi_handle* h, const FormatView* formats, int32_t n_formats, int32_t causal, void* workspace_dev,
+                        size_t workspace_bytes, void* pinned_host, size_t pinned_bytes, fi_stream stream) {
   if (workspace_dev && workspace_bytes < h->layout.total_bytes)
     return set_error(FI_ERR_WORKSPACE_TOO_SMALL, "fi_plan: device workspace has " + std::to_string(workspace_bytes) +
                                                      " bytes, needs " + std::to_string(h->layout.total_bytes));
@@ -198,11 +205,12 @@ int32_t fi_plan(fi_handle* h, const int32_t* qo_indptr, const int32_t* kv_indptr
   PlanParams pp = h->pp;
   pp.causal = causal != 0;
   std::string err;
-  const int32_t rc = make_plan(pp, h->layout, qo_indptr, kv_indptr, last_page_len, batch, h->host_plan.data(), &err);
+  const int32_t rc = make_plan_formats(pp, h->layout, formats, n_formats, h->host_plan.data(), &err);
   if (rc != FI_OK) return set_error(rc, err);
   h->planned_host = true;
   h->pp_causal_last = causal != 0;
-  h->nnz_qo_last = batch > 0 ? qo_indptr[batch] : 0;
+  h->n_formats_last = n_formats;
+  h->nnz_qo_last = formats[0].batch > 0 ? formats[0].qo_indptr[formats[0].batch] : 0;
   if (!workspace_dev) return FI_OK;
   const size_t bytes = h->layout.plan_ints * sizeof(int32_t);
   hipStream_t s = static_cast<hipStream_t>(stream);
@@ -229,6 +237,42 @@ int32_t fi_plan(fi_handle* h, const int32_t* qo_indptr, const int32_t* kv_indptr
   h->workspace_bytes = workspace_bytes;
   h->planned_dev = true;
   return FI_OK;
+}
+
+int32_t fi_plan(fi_handle* h, const int32_t* qo_indptr, const int32_t* kv_indptr, const int32_t* last_page_len,
+                int32_t batch, int32_t causal, void* workspace_dev, size_t workspace_bytes, void* pinned_host,
+                size_t pinned_bytes, fi_stream stream) {
+  if (!h) return set_error(FI_ERR_INVALID_ARG, "fi_plan: null handle");
+  FormatView f;
+  f.qo_indptr = qo_indptr;
+  f.kv_indptr = kv_indptr;
+  f.last_page_len = last_page_len;
+  f.batch = batch;
+  if (!qo_indptr || !kv_indptr) return set_error(FI_ERR_INVALID_ARG, "fi_plan: null array");
+  return plan_and_upload(h, &f, 1, causal, workspace_dev, workspace_bytes, pinned_host, pinned_bytes, stream);
+}
+
+int32_t fi_plan_formats(fi_handle* h, int32_t n_formats, const int32_t* const* qo_indptr, const int32_t* const* kv_indptr,
+                        const int32_t* const* last_page_len, const int32_t* batch, const int32_t* kv_indices_base,
+                        void* workspace_dev, size_t workspace_bytes, void* pinned_host, size_t pinned_bytes,
+                        fi_stream stream) {
+  if (!h) return set_error(FI_ERR_INVALID_ARG, "fi_plan_formats: null handle");
+  if (h->cfg.mode != FI_MODE_TILE16)
+    return set_error(FI_ERR_UNSUPPORTED, "fi_plan_formats: needs a handle in FI_MODE_TILE16 (one kernel runs the tiles of every format)");
+  if (n_formats < 1 || n_formats > kMaxFormats)
+    return set_error(FI_ERR_INVALID_ARG, "fi_plan_formats: n_formats must be between 1 and " + std::to_string(kMaxFormats));
+  if (!qo_indptr || !kv_indptr || !last_page_len || !batch || !kv_indices_base)
+    return set_error(FI_ERR_INVALID_ARG, "fi_plan_formats: null array");
+  FormatView f[kMaxFormats];
+  for (int32_t i = 0; i < n_formats; ++i) {
+    if (!qo_indptr[i] || !kv_indptr[i]) return set_error(FI_ERR_INVALID_ARG, "fi_plan_formats: null array");
+    f[i].qo_indptr = qo_indptr[i];
+    f[i].kv_indptr = kv_indptr[i];
+    f[i].last_page_len = last_page_len[i];
+    f[i].batch = batch[i];
+    f[i].kv_base = kv_indices_base[i];
+  }
+  return plan_and_upload(h, f, n_formats, 0, workspace_dev, workspace_bytes, pinned_host, pinned_bytes, stream);
 }
 
 int32_t fi_plan_view(const fi_handle* h, fi_plan_arrays* out) {
@@ -259,6 +303,10 @@ int32_t fi_plan_view(const fi_handle* h, fi_plan_arrays* out) {
   out->m_n_pos = base + L.off_merge[M_N_POS];
   out->m_slot_base = base + L.off_merge[M_SLOT_BASE];
   out->m_n_chunks = base + L.off_merge[M_N_CHUNKS];
+  out->n_rows = hdr[H_N_ROWS];
+  out->pad2_ = 0;
+  out->row_indptr = hdr[H_N_ROWS] > 0 ? base + L.off_row_indptr : nullptr;
+  out->row_entry = hdr[H_N_ROWS] > 0 ? base + L.off_row_entry : nullptr;
   return FI_OK;
 }
 
@@ -274,6 +322,8 @@ int32_t run_impl(fi_handle* h, const void* q, const void* k_pool, const void* v_
   // deferred != null: the contraction launch is left to the caller, who gets its parameters
   if (!h) return set_error(FI_ERR_INVALID_ARG, "fi_run: null handle");
   if (variant) {
+    if (h->cfg.mode == FI_MODE_TILE16)
+      return set_error(FI_ERR_UNSUPPORTED, "fi_run_variant: not built for the 16-row tile mode");
     if (h->cfg.page_size != kPageSize)
       return set_error(FI_ERR_UNSUPPORTED, "fi_run_variant: built for page_size 16");
     if (h->cfg.mode != FI_MODE_DECODE && !h->pp_causal_last)
@@ -292,6 +342,8 @@ int32_t run_impl(fi_handle* h, const void* q, const void* k_pool, const void* v_
                                              " keys: run it with fi_run_variant and 0 <= window_left <= plan_window - 1");
   if (kv8 && h->cfg.mode != FI_MODE_DECODE)
     return set_error(FI_ERR_UNSUPPORTED, "fi_run_kv8: the 8-bit KV cache is built for decode mode only");
+  if (deferred && h->n_formats_last > 1)
+    return set_error(FI_ERR_UNSUPPORTED, "fi_run_composed: a handle planned over several formats composes them by itself (fi_run)");
   if (kv8 && !(k_scale > 0.f && v_scale > 0.f))
     return set_error(FI_ERR_INVALID_ARG, "fi_run_kv8: k_scale and v_scale must be > 0");
   if (!h->planned_dev) return set_error(FI_ERR_NOT_PLANNED, "fi_run: call fi_plan with a device workspace first");
@@ -370,12 +422,29 @@ int32_t run_impl(fi_handle* h, const void* q, const void* k_pool, const void* v_
       rope.rev256[d] = static_cast<float>(256.0 * rev - std::floor(256.0 * rev));
     }
   }
-  e = h->cfg.mode == FI_MODE_DECODE ? launch_decode(p, bf, kv8, variant != nullptr, with_rope ? &rope : nullptr, s)
-                                    : launch_append(p, bf, variant != nullptr, s);
+  e = h->cfg.mode == FI_MODE_DECODE   ? launch_decode(p, bf, kv8, variant != nullptr, with_rope ? &rope : nullptr, s)
+      : h->cfg.mode == FI_MODE_TILE16 ? launch_tiles(p, bf, s)
+                                      : launch_append(p, bf, variant != nullptr, s);
   if (e != hipSuccess) return hip_error("fi_run: attention launch", e);
   if (h->ev_after && (e = hipEventRecord(h->ev_after, s)) != hipSuccess) return hip_error("fi_run: hipEventRecord", e);
 
   if (fused_merge) return FI_OK;  // the attention launch has folded the partial states itself
+  if (h->n_formats_last > 1) {  // several formats: every query row folds the partial states on its list
+    RowMergeParams rp{};
+    rp.header = plan + L.off_header;
+    rp.row_indptr = plan + L.off_row_indptr;
+    rp.row_entry = plan + L.off_row_entry;
+    rp.part_o = p.part_o;
+    rp.part_lse = p.part_lse;
+    rp.o = o;
+    rp.lse = lse;
+    rp.o_cast = o_cast;
+    rp.num_qo_heads = h->cfg.num_qo_heads;
+    rp.is_bf16 = bf ? 1 : 0;
+    e = launch_merge_rows(rp, kMergeGrid, s);
+    if (e != hipSuccess) return hip_error("fi_run: row contraction launch", e);
+    return FI_OK;
+  }
   MergeParams mp{};
   mp.header = plan + L.off_header;
   mp.m_q_row0 = plan + L.off_merge[M_Q_ROW0];
@@ -551,6 +620,10 @@ int32_t fi_workspace_bytes(const fi_handle* h, size_t* device_bytes, size_t* pin
 
 int32_t fi_plan(fi_handle* h, const int32_t* qo_indptr, const int32_t* kv_indptr, const int32_t* last_page_len, int32_t batch, int32_t causal, void* workspace_dev, size_t workspace_bytes, void* pinned_host, size_t pinned_bytes, fi_stream stream) {
   return guarded([&]() -> int32_t { return impl::fi_plan(h, qo_indptr, kv_indptr, last_page_len, batch, causal, workspace_dev, workspace_bytes, pinned_host, pinned_bytes, stream); });
+}
+
+int32_t fi_plan_formats(fi_handle* h, int32_t n_formats, const int32_t* const* qo_indptr, const int32_t* const* kv_indptr, const int32_t* const* last_page_len, const int32_t* batch, const int32_t* kv_indices_base, void* workspace_dev, size_t workspace_bytes, void* pinned_host, size_t pinned_bytes, fi_stream stream) {
+  return guarded([&]() -> int32_t { return impl::fi_plan_formats(h, n_formats, qo_indptr, kv_indptr, last_page_len, batch, kv_indices_base, workspace_dev, workspace_bytes, pinned_host, pinned_bytes, stream); });
 }
 
 int32_t fi_plan_view(const fi_handle* h, fi_plan_arrays* out) {

@@ -86,6 +86,10 @@ struct ComposeParams {
 // rope != null (variant launches only): queries and keys are rotated by their positions first.
 hipError_t launch_decode(const RunParams& p, bool is_bf16, bool kv8, bool variant, const RopeTable* rope,
                          hipStream_t stream);
+// tile.hip: query tiles of up to 16 fused rows = RunParams::t_pos positions x g heads, one wavefront per CTA,
+// causal or not; 16-bit pools, page size 16, no variants; grid = ctas_per_head * num_kv_heads with the kv head as
+// the fast index.
+hipError_t launch_tiles(const RunParams& p, bool is_bf16, hipStream_t stream);
 // append.hip: query tile = append_tile_rows()/g positions x g fused heads, 8 wavefronts per CTA.
 // variant: the logits hooks of RunParams are applied (causal batches only; with ALiBi or a window every item takes
 // the generic path, the soft cap alone has a variant of the scheduled loop).
@@ -97,6 +101,20 @@ hipError_t launch_plan_upload(const int32_t* staging_dev_view, int32_t* plan_sec
 // merge.hip
 hipError_t launch_merge_planned(const MergeParams& p, int32_t grid, hipStream_t stream);
 hipError_t launch_compose(const ComposeParams& p, hipStream_t stream);
+// Contraction of a plan over several formats: query row r folds the partial states listed in
+// row_entry[row_indptr[r] .. row_indptr[r + 1]) (entry = partial row of the state before the head is added).
+struct RowMergeParams {
+  const int32_t* header;  // [H_N_ROWS] read on the device
+  const int32_t* row_indptr;
+  const int32_t* row_entry;
+  const float* part_o;
+  const float* part_lse;
+  float* o;  // may be null when o_cast is not
+  float* lse;
+  void* o_cast;
+  int32_t num_qo_heads, is_bf16;
+};
+hipError_t launch_merge_rows(const RowMergeParams& p, int32_t grid, hipStream_t stream);
 hipError_t launch_merge_states(const float* o_parts, const float* lse_parts, int64_t n_rows, int32_t n_states,
                                float* o, float* lse, hipStream_t stream);
 hipError_t launch_merge_pair(const float* o_a, const float* lse_a, const float* o_b, const float* lse_b,

@@ -389,6 +389,60 @@ __global__ void __launch_bounds__(64 * kMergeWaves) compose_kernel(const Compose
   }
 }
 
+// Contraction of a plan over several formats (Sec. 3.1.2; Sec. 2.2): one wavefront per (query row, head) folds the
+// row's partial states in list order (a left fold with a common reference, the maximum lse: every state weighs
+// exp(lse_s - max)).  Fixed grid; the number of rows is read from the plan header.  Loads go out 16 states at a time.
+__global__ void __launch_bounds__(64 * kMergeWaves) merge_rows_kernel(const RowMergeParams p) {
+  const float NEG_INF = -__builtin_inff();
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int H = p.num_qo_heads;
+  const int64_t total = static_cast<int64_t>(p.header[H_N_ROWS]) * H;
+  for (int64_t r = static_cast<int64_t>(blockIdx.x) * kMergeWaves + wave; r < total;
+       r += static_cast<int64_t>(gridDim.x) * kMergeWaves) {
+    const int row = static_cast<int>(r / H);
+    const int head = static_cast<int>(r % H);
+    const int e0 = p.row_indptr[row];
+    const int n = p.row_indptr[row + 1] - e0;
+    float mx = NEG_INF;
+    for (int s0 = 0; s0 < n; s0 += 64)
+      if (s0 + lane < n) mx = fmaxf(mx, p.part_lse[static_cast<int64_t>(p.row_entry[e0 + s0 + lane]) * H + head]);
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off));
+    f32x2_t acc = {0.f, 0.f};
+    float den = 0.f;
+    if (mx != NEG_INF) {
+      for (int s0 = 0; s0 < n; s0 += 16) {
+        float l[16];
+        f32x2_t v[16];
+#pragma unroll
+        for (int u = 0; u < 16; ++u) {
+          const int64_t prow = static_cast<int64_t>(p.row_entry[e0 + min(s0 + u, n - 1)]) * H + head;
+          l[u] = p.part_lse[prow];
+          v[u] = *reinterpret_cast<const f32x2_t*>(p.part_o + prow * kHeadDim + 2 * lane);
+        }
+#pragma unroll
+        for (int u = 0; u < 16; ++u) {
+          const float w = s0 + u < n ? __builtin_amdgcn_exp2f((l[u] - mx) * kLog2e) : 0.f;
+          if (w != 0.f) {  // an empty state contributes nothing, whatever rides on it
+            acc += w * v[u];
+            den += w;
+          }
+        }
+      }
+    }
+    f32x2_t res = {0.f, 0.f};
+    float lse = NEG_INF;
+    if (den > 0.f) {
+      res = acc * (1.0f / den);
+      lse = mx + __builtin_amdgcn_logf(den) * kLn2;
+    }
+    if (p.o != nullptr) *reinterpret_cast<f32x2_t*>(p.o + r * kHeadDim + 2 * lane) = res;
+    if (lane == 0) p.lse[r] = lse;
+    if (p.o_cast != nullptr) store_cast(p.o_cast, r, lane, res, p.is_bf16);
+  }
+}
+
 __global__ void __launch_bounds__(256) merge_pair_kernel(const float* o_a, const float* lse_a, const float* o_b,
                                                          const float* lse_b, int64_t n_rows, float* o, float* lse) {
   const int lane = threadIdx.x & 63;
@@ -417,6 +471,11 @@ int grid_for_rows(int64_t n_rows) {
 
 hipError_t launch_merge_planned(const MergeParams& p, int32_t grid, hipStream_t stream) {
   hipLaunchKernelGGL(merge_planned_kernel, dim3(grid), dim3(64 * kMergeWaves), 0, stream, p);
+  return hipGetLastError();
+}
+
+hipError_t launch_merge_rows(const RowMergeParams& p, int32_t grid, hipStream_t stream) {
+  hipLaunchKernelGGL(merge_rows_kernel, dim3(grid), dim3(64 * kMergeWaves), 0, stream, p);
   return hipGetLastError();
 }
 

@@ -15,12 +15,14 @@ namespace fi355 {
 static size_t round_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 void WorkspaceLayout::init(int32_t ctas, int32_t max_qo_tiles, int32_t t_pos, int32_t num_qo_heads,
-                           int32_t num_kv_heads, int32_t head_dim) {
+                           int32_t num_kv_heads, int32_t head_dim, bool formats) {
   ctas_per_head = ctas;
   // sum_t ceil(kv_eff(t) / L_kv) <= n_tiles + S / L_kv <= n_tiles + #CTA
   max_work = max_qo_tiles + ctas;
   max_merge = ctas;
-  max_slots = 2 * ctas;
+  // App. D.3: at most 2 * #CTA partial states when unsplit tiles write through; composed formats have no
+  // write-through, there every work item owns a slot
+  max_slots = formats ? max_work : 2 * ctas;
   size_t o = 0;
   off_header = o;
   o += kHeaderInts;
@@ -36,6 +38,14 @@ void WorkspaceLayout::init(int32_t ctas, int32_t max_qo_tiles, int32_t t_pos, in
   }
   off_counters = o;
   o += static_cast<size_t>(max_merge) * num_kv_heads;
+  max_rows = 0;
+  if (formats) {
+    max_rows = max_qo_tiles * t_pos;
+    off_row_indptr = o;
+    o += static_cast<size_t>(max_rows) + 1;
+    off_row_entry = o;
+    o += static_cast<size_t>(max_work) * t_pos;
+  }
   plan_ints = o;
   plan_bytes = round_up(o * sizeof(int32_t), 256);
   const size_t rows = static_cast<size_t>(max_slots) * t_pos * num_qo_heads;
@@ -87,16 +97,41 @@ void sift_down(std::vector<Entry>& heap) {
 int32_t make_plan(const PlanParams& pp, const WorkspaceLayout& L, const int32_t* qo_indptr,
                   const int32_t* kv_indptr, const int32_t* last_page_len, int32_t batch,
                   int32_t* plan, std::string* err) {
+  FormatView f;
+  f.qo_indptr = qo_indptr;
+  f.kv_indptr = kv_indptr;
+  f.last_page_len = last_page_len;
+  f.batch = batch;
+  return make_plan_formats(pp, L, &f, 1, plan, err);
+}
+
+int32_t make_plan_formats(const PlanParams& pp, const WorkspaceLayout& L, const FormatView* formats,
+                          int32_t n_formats, int32_t* plan, std::string* err) {
   auto fail = [&](int32_t code, const std::string& msg) {
     if (err) *err = msg;
     return code;
   };
-  if (!qo_indptr || !kv_indptr || (batch > 0 && !last_page_len) || !plan)
-    return fail(FI_ERR_INVALID_ARG, "fi_plan: null array");
-  if (batch < 0 || batch > pp.max_batch)
-    return fail(FI_ERR_INVALID_ARG, "fi_plan: batch " + std::to_string(batch) + " outside [0, max_batch=" +
+  if (!formats || n_formats < 1 || !plan) return fail(FI_ERR_INVALID_ARG, "fi_plan: null array");
+  const bool composed = n_formats > 1;
+  if (composed && L.max_rows == 0)
+    return fail(FI_ERR_UNSUPPORTED, "fi_plan_formats: the handle's mode plans one format at a time");
+  int64_t batch_total = 0;
+  for (int32_t f = 0; f < n_formats; ++f) {
+    const FormatView& F = formats[f];
+    if (!F.qo_indptr || !F.kv_indptr || (F.batch > 0 && !F.last_page_len)) return fail(FI_ERR_INVALID_ARG, "fi_plan: null array");
+    if (F.batch < 0) return fail(FI_ERR_INVALID_ARG, "fi_plan: negative batch");
+    if (F.qo_indptr[0] != 0 || F.kv_indptr[0] != 0) return fail(FI_ERR_INVALID_ARG, "fi_plan: indptr[0] must be 0");
+    if (F.kv_base < 0) return fail(FI_ERR_INVALID_ARG, "fi_plan_formats: negative kv_indices_base");
+    if (F.qo_indptr[F.batch] != formats[0].qo_indptr[formats[0].batch])
+      return fail(FI_ERR_INVALID_ARG, "fi_plan_formats: the formats cover different numbers of query rows");
+    batch_total += F.batch;
+  }
+  if (batch_total > pp.max_batch)
+    return fail(FI_ERR_INVALID_ARG, "fi_plan: batch " + std::to_string(batch_total) + " outside [0, max_batch=" +
                                         std::to_string(pp.max_batch) + "]");
-  if (qo_indptr[0] != 0 || kv_indptr[0] != 0) return fail(FI_ERR_INVALID_ARG, "fi_plan: indptr[0] must be 0");
+  const int64_t n_rows = formats[0].qo_indptr[formats[0].batch];
+  if (composed && n_rows > L.max_rows)
+    return fail(FI_ERR_INVALID_ARG, "fi_plan_formats: more query rows than max_qo_tiles * tile positions");
 
   const int32_t ps = pp.page_size;
   const int64_t C = pp.ctas_per_head;
@@ -105,44 +140,51 @@ int32_t make_plan(const PlanParams& pp, const WorkspaceLayout& L, const int32_t*
   std::vector<Tile>& tiles = scratch.tiles;
   tiles.clear();
   int64_t S = 0;
-  for (int32_t i = 0; i < batch; ++i) {
-    const int64_t l_qo = static_cast<int64_t>(qo_indptr[i + 1]) - qo_indptr[i];
-    const int64_t n_pg = static_cast<int64_t>(kv_indptr[i + 1]) - kv_indptr[i];
-    if (l_qo < 0 || n_pg < 0)
-      return fail(FI_ERR_INVALID_ARG, "fi_plan: indptr decreases at request " + std::to_string(i));
-    if (n_pg > 0 && (last_page_len[i] < 1 || last_page_len[i] > ps))
-      return fail(FI_ERR_INVALID_ARG, "fi_plan: last_page_len[" + std::to_string(i) + "] = " +
-                                          std::to_string(last_page_len[i]) + " outside [1, page_size]");
-    const int64_t l_kv = n_pg == 0 ? 0 : (n_pg - 1) * ps + last_page_len[i];
-    if (l_kv >= kNoDiag) return fail(FI_ERR_INVALID_ARG, "fi_plan: request too long");
-    const int64_t n_tiles = (l_qo + pp.t_pos - 1) / pp.t_pos;
-    if (static_cast<int64_t>(tiles.size()) + n_tiles > pp.max_qo_tiles)
-      return fail(FI_ERR_INVALID_ARG, "fi_plan: more query tiles than max_qo_tiles=" + std::to_string(pp.max_qo_tiles));
-    for (int64_t t = 0; t < n_tiles; ++t) {
-      Tile tl;
-      tl.request = i;
-      tl.start = static_cast<int32_t>(t * pp.t_pos);
-      const int64_t end = std::min<int64_t>(tl.start + pp.t_pos, l_qo);
-      tl.n_pos = static_cast<int32_t>(end - tl.start);
-      if (pp.causal) {
-        tl.kv_eff = static_cast<int32_t>(std::max<int64_t>(0, std::min<int64_t>(l_kv, l_kv - l_qo + end)));
-        tl.diag0 = static_cast<int32_t>(l_kv - l_qo + tl.start);
-      } else {
-        tl.kv_eff = static_cast<int32_t>(l_kv);
-        tl.diag0 = kNoDiag;
+  int32_t request_base = 0;  // requests are counted through all formats
+  for (int32_t f = 0; f < n_formats; request_base += formats[f].batch, ++f) {
+    const int32_t* qo_indptr = formats[f].qo_indptr;
+    const int32_t* kv_indptr = formats[f].kv_indptr;
+    const int32_t* last_page_len = formats[f].last_page_len;
+    const int32_t batch = formats[f].batch;
+    for (int32_t i = 0; i < batch; ++i) {
+      const int64_t l_qo = static_cast<int64_t>(qo_indptr[i + 1]) - qo_indptr[i];
+      const int64_t n_pg = static_cast<int64_t>(kv_indptr[i + 1]) - kv_indptr[i];
+      if (l_qo < 0 || n_pg < 0)
+        return fail(FI_ERR_INVALID_ARG, "fi_plan: indptr decreases at request " + std::to_string(i));
+      if (n_pg > 0 && (last_page_len[i] < 1 || last_page_len[i] > ps))
+        return fail(FI_ERR_INVALID_ARG, "fi_plan: last_page_len[" + std::to_string(i) + "] = " +
+                                            std::to_string(last_page_len[i]) + " outside [1, page_size]");
+      const int64_t l_kv = n_pg == 0 ? 0 : (n_pg - 1) * ps + last_page_len[i];
+      if (l_kv >= kNoDiag) return fail(FI_ERR_INVALID_ARG, "fi_plan: request too long");
+      const int64_t n_tiles = (l_qo + pp.t_pos - 1) / pp.t_pos;
+      if (static_cast<int64_t>(tiles.size()) + n_tiles > pp.max_qo_tiles)
+        return fail(FI_ERR_INVALID_ARG, "fi_plan: more query tiles than max_qo_tiles=" + std::to_string(pp.max_qo_tiles));
+      for (int64_t t = 0; t < n_tiles; ++t) {
+        Tile tl;
+        tl.request = request_base + i;
+        tl.start = static_cast<int32_t>(t * pp.t_pos);
+        const int64_t end = std::min<int64_t>(tl.start + pp.t_pos, l_qo);
+        tl.n_pos = static_cast<int32_t>(end - tl.start);
+        if (pp.causal) {
+          tl.kv_eff = static_cast<int32_t>(std::max<int64_t>(0, std::min<int64_t>(l_kv, l_kv - l_qo + end)));
+          tl.diag0 = static_cast<int32_t>(l_kv - l_qo + tl.start);
+        } else {
+          tl.kv_eff = static_cast<int32_t>(l_kv);
+          tl.diag0 = kNoDiag;
+        }
+        tl.kv_begin = 0;
+        if (pp.plan_window > 0) {
+          const int64_t first_seen = std::max<int64_t>(0, l_kv - l_qo + tl.start - (pp.plan_window - 1));
+          tl.kv_begin = static_cast<int32_t>(std::min<int64_t>(first_seen, tl.kv_eff) / ps * ps);
+        }
+        tl.q_row0 = qo_indptr[i] + tl.start;
+        tl.kv_page_base = formats[f].kv_base + kv_indptr[i];
+        tl.n_chunks = 1;
+        tl.slot_base = -1;
+        tl.merge_index = -1;
+        tiles.push_back(tl);
+        S += pp.literal_lkv ? l_kv : tl.kv_eff - tl.kv_begin;
       }
-      tl.kv_begin = 0;
-      if (pp.plan_window > 0) {
-        const int64_t first_seen = std::max<int64_t>(0, l_kv - l_qo + tl.start - (pp.plan_window - 1));
-        tl.kv_begin = static_cast<int32_t>(std::min<int64_t>(first_seen, tl.kv_eff) / ps * ps);
-      }
-      tl.q_row0 = qo_indptr[i] + tl.start;
-      tl.kv_page_base = kv_indptr[i];
-      tl.n_chunks = 1;
-      tl.slot_base = -1;
-      tl.merge_index = -1;
-      tiles.push_back(tl);
-      S += pp.literal_lkv ? l_kv : tl.kv_eff - tl.kv_begin;
     }
   }
 
@@ -175,7 +217,10 @@ int32_t make_plan(const PlanParams& pp, const WorkspaceLayout& L, const int32_t*
   for (size_t ti = 0; ti < tiles.size(); ++ti) {
     Tile& tl = tiles[ti];
     tl.n_chunks = static_cast<int32_t>(std::max<int64_t>(1, (tl.kv_eff - tl.kv_begin + Lkv - 1) / Lkv));
-    if (tl.n_chunks > 1) {
+    if (composed) {  // every state is a partial state; the row lists below say who folds what
+      tl.slot_base = next_slot;
+      next_slot += tl.n_chunks;
+    } else if (tl.n_chunks > 1) {
       tl.slot_base = next_slot;
       next_slot += tl.n_chunks;
       tl.merge_index = n_merge++;
@@ -319,6 +364,24 @@ int32_t make_plan(const PlanParams& pp, const WorkspaceLayout& L, const int32_t*
     plan[L.off_work[W_DIAG0] + k] = tl.diag0;
     plan[L.off_work[W_OUT_SLOT] + k] = tl.slot_base < 0 ? -1 : tl.slot_base + ch.in_tile;
     plan[L.off_work[W_MERGE] + k] = tl.merge_index;
+  }
+  if (composed) {
+    // ---- per query row: the partial states it folds; tiles are in (format, request, tile) order, which within a
+    //      format is ascending query rows ----
+    hdr[H_N_ROWS] = static_cast<int32_t>(n_rows);
+    int32_t* row_indptr = plan + L.off_row_indptr;
+    int32_t* row_entry = plan + L.off_row_entry;
+    for (const Tile& tl : tiles)
+      for (int32_t p = 0; p < tl.n_pos; ++p) row_indptr[tl.q_row0 + p + 1] += tl.n_chunks;
+    for (int64_t r = 0; r < n_rows; ++r) row_indptr[r + 1] += row_indptr[r];
+    if (static_cast<size_t>(row_indptr[n_rows]) > static_cast<size_t>(L.max_work) * pp.t_pos)
+      return fail(FI_ERR_WORKSPACE_TOO_SMALL, "fi_plan_formats: row lists exceed the workspace section (internal bound)");
+    std::vector<int32_t>& at = scratch.fill;  // next free entry of each row's list
+    at.assign(row_indptr, row_indptr + n_rows);
+    for (const Tile& tl : tiles)
+      for (int32_t p = 0; p < tl.n_pos; ++p)
+        for (int32_t c = 0; c < tl.n_chunks; ++c) row_entry[at[tl.q_row0 + p]++] = (tl.slot_base + c) * pp.t_pos + p;
+    return FI_OK;
   }
   int32_t mi = 0;
   for (const Tile& tl : tiles) {

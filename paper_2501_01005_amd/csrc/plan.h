@@ -16,7 +16,7 @@ constexpr int kMergeArrays = 4;  // q_row0, n_pos, slot_base, n_chunks
 // Indices of the per-work-item arrays inside the plan section.
 enum WorkField { W_REQUEST = 0, W_Q_ROW0, W_N_POS, W_KV_PAGE0, W_KV_START, W_KV_LEN, W_DIAG0, W_OUT_SLOT, W_MERGE };
 enum MergeField { M_Q_ROW0 = 0, M_N_POS, M_SLOT_BASE, M_N_CHUNKS };
-enum HeaderField { H_N_WORK = 0, H_N_MERGE, H_N_SLOTS, H_L_KV, H_T_POS, H_CTAS };
+enum HeaderField { H_N_WORK = 0, H_N_MERGE, H_N_SLOTS, H_L_KV, H_T_POS, H_CTAS, H_N_ROWS };
 
 // Section offsets depend only on the creation-time configuration, so the pointers a
 // captured launch holds stay valid across plans (App. D.1).
@@ -30,14 +30,21 @@ struct WorkspaceLayout {
   size_t off_work[kWorkArrays] = {};
   size_t off_merge[kMergeArrays] = {};
   size_t off_counters = 0;    // max_merge * num_kv_heads arrival counters of the split tiles, zero in every plan
+  // Handles that can plan several formats over the same query rows (Sec. 3.1.2) also hold, per query row, the list
+  // of partial states to fold: row r owns row_entry[row_indptr[r] .. row_indptr[r + 1]), each entry the partial row
+  // slot * t_pos + position-in-tile of one state, in fold order.  max_rows = 0 without them.
+  int32_t max_rows = 0;       // max_qo_tiles * t_pos
+  size_t off_row_indptr = 0;  // [max_rows + 1]
+  size_t off_row_entry = 0;   // [max_work * t_pos]
   size_t plan_ints = 0;       // ints in the plan section
   size_t plan_bytes = 0;      // rounded up to 256
   size_t off_part_lse = 0;    // byte offsets in the device workspace
   size_t off_part_o = 0;
   size_t total_bytes = 0;
 
+  // formats: the handle may plan several formats at once: every work item then owns a partial slot
   void init(int32_t ctas, int32_t max_qo_tiles, int32_t t_pos, int32_t num_qo_heads, int32_t num_kv_heads,
-            int32_t head_dim);
+            int32_t head_dim, bool formats = false);
 };
 
 struct PlanParams {
@@ -70,10 +77,30 @@ struct PlanParams {
   int32_t item_cost = 0;
 };
 
+// One format (Sec. 3.1.1, Sec. 3.1.2): a block-sparse-row view of the KV pool over the query rows, given by its
+// row partition (qo_indptr), its page lists (kv_indptr into the page-id array, starting at element kv_base of
+// the array the kernels get) and the fill of every request's last page.
+struct FormatView {
+  const int32_t* qo_indptr = nullptr;
+  const int32_t* kv_indptr = nullptr;
+  const int32_t* last_page_len = nullptr;
+  int32_t batch = 0;
+  int32_t kv_base = 0;
+};
+
 // Runs the partition and writes the plan section (header, queues, work items, merge list)
 // into `plan` (layout.plan_ints ints).  Returns 0 or a negative FI_ERR_* with `err` set.
 int32_t make_plan(const PlanParams& pp, const WorkspaceLayout& layout, const int32_t* qo_indptr,
                   const int32_t* kv_indptr, const int32_t* last_page_len, int32_t batch,
                   int32_t* plan, std::string* err);
+
+// The same over n_formats >= 1 formats that cover the same query rows (every qo_indptr ends at the same row count):
+// the work items of all formats share the chunk size, the queues and the launch.  With more than one format every
+// work item writes a partial state (no write-through: a row's final state is the merge of one state per format at
+// least), the merge list is empty and the row lists say which partial states each query row folds, formats in the
+// given order, chunks of a tile in ascending KV order.  Work indices run over (format, request, tile, chunk);
+// w_request counts requests through all formats.  Needs a layout made with formats = true.
+int32_t make_plan_formats(const PlanParams& pp, const WorkspaceLayout& layout, const FormatView* formats,
+                          int32_t n_formats, int32_t* plan, std::string* err);
 
 }  // namespace fi355

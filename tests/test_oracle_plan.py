@@ -305,3 +305,76 @@ def test_sliding_window_leaves_out_exactly_the_pages_no_row_sees():
             wide = plan_replica(qo_indptr, kv_indptr, last, plan_window=10 ** 7, **kw)
             none = plan_replica(qo_indptr, kv_indptr, last, **kw)
             assert all(wide[k] == none[k] for k in none)
+
+
+def formats_of_fixture(fx):
+    out = []
+    for f in range(fx["n_formats"][0]):
+        qo_indptr, kv_indptr, last = indptrs_from_lengths(fx[f"f{f}_qo_len"], fx[f"f{f}_kv_len"], fx["page_size"][0])
+        out.append((qo_indptr, kv_indptr, last, fx[f"f{f}_kv_base"][0]))
+    return out
+
+
+def test_hand_worked_plan_over_two_formats():
+    from oracle.plan_replica import plan_replica_formats
+    fx = load_fixture("plan_formats_example.txt")
+    p = plan_replica_formats(formats_of_fixture(fx), **replica_args(fx))
+    assert p["L_kv"] == fx["L_kv"][0] and p["n_slots"] == fx["n_slots"][0] and p["n_merge"] == 0
+    for key in FIXTURE_KEYS + ("row_indptr", "row_entry"):
+        if key in fx:
+            assert list(p[key]) == fx[key], key
+
+
+def test_plans_over_several_formats_keep_the_invariants():
+    """Random shared-prefix style batches: one work list over all formats; every chunk of every tile owns exactly
+    one slot; every query row lists, per format in order, the chunks of the tile that holds it, in ascending KV
+    order; one format alone is the single-format plan."""
+    from oracle.plan_replica import plan_replica_formats
+    rng = np.random.default_rng(31)
+    for trial in range(60):
+        g = int(rng.choice([1, 2, 4, 8]))
+        t_pos, ps = 16 // g, 16
+        C = int(rng.choice([1, 3, 16, 64]))
+        n_rows = int(rng.integers(1, 40))
+        formats, lens = [], []
+        n_formats = int(rng.integers(1, 4))
+        base = 0
+        for f in range(n_formats):
+            # cut the rows into requests at random places
+            cuts = sorted(set(rng.integers(0, n_rows + 1, size=int(rng.integers(0, n_rows + 1))).tolist()) | {0, n_rows})
+            qo = np.diff(cuts)
+            kv = rng.integers(0, 700, size=len(qo))
+            qo_indptr, kv_indptr, last = indptrs_from_lengths(qo, kv, ps)
+            formats.append((qo_indptr, kv_indptr, last, base))
+            lens.append((qo, kv))
+            base += int(kv_indptr[-1])
+        kw = dict(page_size=ps, t_pos=t_pos, group=g, num_ctas=C, causal=False, min_chunk=16)
+        p = plan_replica_formats(formats, **kw)
+        assert p == plan_replica_formats(formats, **kw)
+        if n_formats == 1:
+            assert p == plan_replica(formats[0][0], formats[0][1], formats[0][2], **kw)
+            continue
+        assert p["n_merge"] == 0 and p["n_slots"] == p["n_work"] and sorted(p["w_out_slot"]) == list(range(p["n_work"]))
+        assert p["n_rows"] == n_rows and len(p["row_indptr"]) == n_rows + 1
+        # state (slot, position) -> the work item that writes it
+        by_slot = {p["w_out_slot"][k]: k for k in range(p["n_work"])}
+        req_base = np.concatenate([[0], np.cumsum([len(f[2]) for f in formats])])
+        for r in range(n_rows):
+            entries = p["row_entry"][p["row_indptr"][r]:p["row_indptr"][r + 1]]
+            seen_formats = []
+            covered = {}
+            for e in entries:
+                k = by_slot[e // t_pos]
+                assert p["w_q_row0"][k] + e % t_pos == r and e % t_pos < p["w_n_pos"][k]
+                f = int(np.searchsorted(req_base, p["w_request"][k], side="right")) - 1
+                seen_formats.append(f)
+                covered.setdefault(f, []).append((p["w_kv_start"][k], p["w_kv_len"][k]))
+            assert seen_formats == sorted(seen_formats) and set(seen_formats) == set(range(n_formats))
+            for f, chunks in covered.items():
+                # the chunks of the row's tile in format f, in ascending order, cover its request's keys exactly
+                i = int(np.searchsorted(formats[f][0], r, side="right")) - 1
+                pos = 0
+                for (start, length) in chunks:
+                    assert start == pos
+                    pos += length
+                assert pos == int(lens[f][1][i])

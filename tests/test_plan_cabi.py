@@ -294,3 +294,96 @@ def test_planner_reproduces_the_hand_worked_examples(name):
         if key in fx and key != "cta_cost":
             assert got[key].tolist() == fx[key], key
     fi.fi_destroy(h)
+
+
+def make_tile16(g, C, Hkv=2, max_batch=256, max_tiles=1024, **kw):
+    return fi.fi_create(dtype=fi.FI_DTYPE_BF16, num_qo_heads=g * Hkv, num_kv_heads=Hkv, head_dim=128, page_size=16,
+                        mode=fi.FI_MODE_TILE16, num_ctas=C * Hkv, max_batch=max_batch, max_qo_tiles=max_tiles, **kw)
+
+
+def compare_formats(h, formats, want):
+    fi.fi_plan_formats(h, formats)
+    got = fi.fi_plan_view(h)
+    assert got["l_kv_chunk"] == want["L_kv"] and got["n_work"] == want["n_work"]
+    assert got["n_merge"] == want["n_merge"] and got["n_slots"] == want["n_slots"]
+    keys = PLAN_KEYS + (("row_indptr", "row_entry") if len(formats) > 1 else ())
+    assert got["n_rows"] == want.get("n_rows", 0)
+    for k in keys:
+        assert got[k].tobytes() == np.asarray(want[k], dtype=np.int32).tobytes(), k
+
+
+def test_planner_reproduces_the_hand_worked_plan_over_two_formats():
+    from test_oracle_plan import FIXTURE_KEYS, formats_of_fixture, load_fixture
+    fx = load_fixture("plan_formats_example.txt")
+    h = make_tile16(fx["group"][0], fx["num_ctas"][0], alpha=1, beta=1, min_chunk=16, balance=1)
+    fi.fi_plan_formats(h, formats_of_fixture(fx))
+    got = fi.fi_plan_view(h)
+    assert got["l_kv_chunk"] == fx["L_kv"][0] and got["n_slots"] == fx["n_slots"][0] and got["n_merge"] == 0
+    assert got["t_pos"] == fx["t_pos"][0] and got["n_rows"] == 6
+    for key in FIXTURE_KEYS + ("row_indptr", "row_entry"):
+        if key in fx and key != "cta_cost":
+            assert got[key].tolist() == fx[key], key
+    fi.fi_destroy(h)
+
+
+def test_planner_equals_replica_over_several_formats():
+    from oracle.plan_replica import plan_replica_formats
+    rng = np.random.default_rng(41)
+    n_cases = 0
+    for g in (1, 4, 16):
+        for C in (1, 7, 256):
+            for (alpha, beta, min_chunk, balance) in ((1, 1, 16, 1), (2, 3, 32, 0)):
+                h = make_tile16(g, C, alpha=alpha, beta=beta, min_chunk=min_chunk, balance=balance)
+                for trial in range(12):
+                    n_rows = int(rng.integers(1, 70))
+                    n_formats = int(rng.integers(1, 4))
+                    formats, base = [], 0
+                    for f in range(n_formats):
+                        if f == 0 and trial % 2 == 0:
+                            cuts = [0, n_rows]                      # a shared prefix: one row block
+                        else:
+                            cuts = sorted(set(rng.integers(0, n_rows + 1, size=int(rng.integers(0, n_rows + 1))).tolist()) | {0, n_rows})
+                        qo = np.diff(cuts)
+                        kv = rng.integers(0, 3000 if f == 0 else 600, size=len(qo))
+                        qo_indptr, kv_indptr, last = indptrs(qo, kv)
+                        formats.append((qo_indptr, kv_indptr, last, base))
+                        base += int(kv_indptr[-1])
+                    want = plan_replica_formats(formats, page_size=16, t_pos=16 // g, group=g, num_ctas=C, causal=False,
+                                                alpha=alpha, beta=beta, min_chunk=min_chunk,
+                                                item_cost=64 if balance == 0 else 0)
+                    compare_formats(h, formats, want)
+                    n_cases += 1
+                fi.fi_destroy(h)
+    assert n_cases >= 200
+
+
+def test_tile16_single_format_plans_equal_the_replica_causal_and_not():
+    rng = np.random.default_rng(43)
+    for g in (2, 4):
+        for C in (3, 64):
+            h = make_tile16(g, C, alpha=1, beta=1, min_chunk=16, balance=1)
+            for trial in range(10):
+                B = int(rng.integers(1, 20))
+                qo = rng.integers(0, 40, size=B)
+                kv = qo + rng.integers(0, 900, size=B)
+                for causal in (False, True):
+                    compare(h, qo, kv, causal, 16 // g, g, C, 1, 1, 16)
+            fi.fi_destroy(h)
+
+
+def test_plan_formats_argument_errors():
+    h = make_tile16(4, 4)
+    qo, kv, last = indptrs([3], [40])
+    qo2, kv2, last2 = indptrs([1, 1], [5, 6])
+    with pytest.raises(fi.Fi355Error) as e:
+        fi.fi_plan_formats(h, [(qo, kv, last, 0), (qo2, kv2, last2, 3)])       # 3 rows against 2
+    assert e.value.code == fi.FI_ERR_INVALID_ARG and "query rows" in e.value.message
+    with pytest.raises(fi.Fi355Error) as e:
+        fi.fi_plan_formats(h, [(qo, kv, last, -1)])
+    assert e.value.code == fi.FI_ERR_INVALID_ARG
+    fi.fi_destroy(h)
+    hd = make(fi.FI_MODE_DECODE, 4, 4)
+    with pytest.raises(fi.Fi355Error) as e:
+        fi.fi_plan_formats(hd, [(qo2, kv2, last2, 0)])
+    assert e.value.code == fi.FI_ERR_UNSUPPORTED
+    fi.fi_destroy(hd)
