@@ -244,6 +244,9 @@ def main() -> int:
     ap.add_argument("--page-order", default="random", choices=["random", "identity"],
                     help="identity: every request's pages are consecutive in the pool (with --kv-layout NHD that is a "
                          "contiguous ragged KV tensor); c2, c3, c4 only")
+    ap.add_argument("--kv-contiguous", action="store_true",
+                    help="with --page-order identity: run without a page table (fi_run with kv_indices = NULL: affine "
+                         "addressing, the dense baseline of App. B's comparison); c2, c3, c4")
     ap.add_argument("--kv-layout", default="HND", choices=["HND", "NHD"],
                     help="pool layout in memory: [page, head, slot, D] (default, tuned) or [page, slot, head, D]")
     ap.add_argument("--kv-dtype", default="same", choices=["same", "fp8"],
@@ -280,6 +283,9 @@ def main() -> int:
     args = ap.parse_args()
     if args.graph and not args.no_plan:
         print("bench.py: --graph times replays of a captured fi_run and needs --no-plan", file=sys.stderr)
+        return 2
+    if args.kv_contiguous and (args.page_order != "identity" or args.workload not in ("c2", "c3", "c4")):
+        print("bench.py: --kv-contiguous needs --page-order identity and one of c2, c3, c4", file=sys.stderr)
         return 2
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (no multi-GPU path exists); use --gpus 1", file=sys.stderr)
@@ -387,7 +393,8 @@ def run_workload(args):
         sampled = i_timed >= 0 and i_timed % stride == 0
         if sampled:
             fi.lib.fi_set_timing_events(w.handle, ev.start[i_timed // stride], ev.stop[i_timed // stride])
-        w.run(dev.q, dev.k_pool, dev.v_pool, dev.kv_indices, batch.sm_scale, o=o, lse=lse, **run_kw)
+        w.run(dev.q, dev.k_pool, dev.v_pool, None if args.kv_contiguous else dev.kv_indices, batch.sm_scale, o=o, lse=lse,
+              **run_kw)
         if sampled:
             fi.lib.fi_set_timing_events(w.handle, None, None)
 
@@ -468,6 +475,7 @@ def run_workload(args):
         "vs_baseline": None, "dtype": batch.dtype, "data": "synthetic",
         "config": {"workload": batch.name, "batch": batch.batch, "num_qo_heads": batch.num_qo_heads,
                    "num_kv_heads": batch.num_kv_heads, "head_dim": batch.head_dim, "page_size": batch.page_size, "page_order": args.page_order, "kv_layout": args.kv_layout,
+                   "page_table": "none (contiguous KV, affine addressing)" if args.kv_contiguous else "kv_indices",
                    "kv_dtype": batch.kv_dtype or batch.dtype, "o_dtype": batch.dtype if args.out16 else "f32",
                    **({"fused_rope_theta": args.rope_theta} if args.rope_theta > 0 else {}),
                    **({"logits_soft_cap": args.soft_cap} if args.soft_cap > 0 else {}),

@@ -201,6 +201,10 @@ int32_t fi_plan_view(const fi_handle* h, fi_plan_arrays* out);
  * directly or partial states into the workspace, then one fixed-grid merge launch for the
  * split tiles.  All pointers DEVICE.  kv_strides HOST [3] = element strides of
  * (page, kv head, slot-in-page).  sm_scale (> 0) multiplies q.k before the softmax.
+ * kv_indices = NULL: contiguous KV (the dense baseline of App. B): the page table is the identity, i.e. request i owns
+ * pages kv_indptr[i] .. kv_indptr[i + 1] - 1 of the pool, rows are addressed affinely and no page id is loaded (with
+ * page_size 1 and strides (H_kv * D, D, anything) the pool is the ragged tensor [tokens, H_kv, D]).  Decode and
+ * append mode, fi_run only (FI_ERR_UNSUPPORTED elsewhere).
  * o_cast (may be NULL): the output also rounded to the input dtype (nearest even), [nnz_qo, H_qo, D].
  * o may be NULL when o_cast is not: the output is then written in the input dtype only, which
  * halves the output bytes of an append step (partial states stay fp32 in the workspace; lse is

@@ -351,7 +351,7 @@ class PagedAttention:
         assert q.dtype == self.torch_dtype and k_pool.dtype == kv_dtype and v_pool.dtype == kv_dtype
         assert q.is_contiguous() and q.shape[1:] == (self.num_qo_heads, self.head_dim)
         assert k_pool.dim() == 4 and k_pool.stride(3) == 1 and k_pool.stride() == v_pool.stride()
-        assert kv_indices.dtype == torch.int32 and kv_indices.is_contiguous()
+        assert kv_indices is None or (kv_indices.dtype == torch.int32 and kv_indices.is_contiguous())  # None: contiguous KV
         nnz = q.shape[0]
         if o is False:
             assert o_cast is not None

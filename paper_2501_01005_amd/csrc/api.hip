@@ -347,8 +347,9 @@ int32_t run_impl(fi_handle* h, const void* q, const void* k_pool, const void* v_
   if (kv8 && !(k_scale > 0.f && v_scale > 0.f))
     return set_error(FI_ERR_INVALID_ARG, "fi_run_kv8: k_scale and v_scale must be > 0");
   if (!h->planned_dev) return set_error(FI_ERR_NOT_PLANNED, "fi_run: call fi_plan with a device workspace first");
-  if (!q || !k_pool || !v_pool || !kv_strides || !kv_indices || !lse)
-    return set_error(FI_ERR_INVALID_ARG, "fi_run: null pointer");
+  if (!q || !k_pool || !v_pool || !kv_strides || !lse) return set_error(FI_ERR_INVALID_ARG, "fi_run: null pointer");
+  if (!kv_indices && (kv8 || variant || h->cfg.mode == FI_MODE_TILE16 || deferred))
+    return set_error(FI_ERR_UNSUPPORTED, "fi_run: contiguous KV (kv_indices = NULL) is built for fi_run in decode and append mode");
   if (!o && !o_cast) return set_error(FI_ERR_INVALID_ARG, "fi_run: o and o_cast are both null: nowhere to write the output");
   if (!(sm_scale > 0.f)) return set_error(FI_ERR_INVALID_ARG, "fi_run: sm_scale must be > 0");
   if (kv_strides[0] <= 0 || kv_strides[1] <= 0 || kv_strides[2] < kHeadDim || kv_strides[0] % 8 != 0 ||

@@ -192,7 +192,9 @@ struct WorkItem {
 // softmax scale after the transform is 1, and the block has no scalar register to spare: `scale_log2` then
 // carries 2 * sm_scale * log2(e) / c, `wave_index` the bits of c * log2(e), and `g_log2` the wavefront index in
 // bits 8.. above log2 of the group size.
-template <bool BF, bool CAP>
+// CONTIG: contiguous KV (page j of the chunk is page kv_page0 + j of the pool): the page ids are computed instead of
+// loaded; `all_ids_lo` then carries the chunk's kv_page0, `page_ids` and `all_ids_hi` are unused.
+template <bool BF, bool CAP, bool CONTIG>
 __device__ __forceinline__ void run_scheduled_loop(int n_full, int n_tiles, int kv_len, int cap, int st_tok, int ids_clamp, const int32_t* page_ids, uint32_t k_lo,
                                                    uint32_t k_hi, uint32_t v_lo, uint32_t v_hi, uint32_t page_bytes,
                                                    float scale_log2, uint64_t q_addr, uint32_t st_off_bytes,
@@ -215,7 +217,21 @@ __device__ __forceinline__ void run_scheduled_loop(int n_full, int n_tiles, int 
           [gl] "s"(g_log2), [hq] "s"(num_qo_heads), [rb] "s"(row_base), [np] "s"(n_pos), [stp8] "s"(wave_index),           \
           [woff] "s"(next_off), [wq0] "s"(w_fields), [wstr] "s"(w_stride),                                                  \
           [idblo] "s"(all_ids_lo), [idbhi] "s"(all_ids_hi)
-  if constexpr (CAP && BF) {
+  if constexpr (CONTIG && BF) {
+    asm volatile(
+#include "append_loop_bf16_contig.inc"
+        FI355_LOOP_OPERANDS
+        :
+#include "append_loop_clobbers.inc"
+    );
+  } else if constexpr (CONTIG) {
+    asm volatile(
+#include "append_loop_f16_contig.inc"
+        FI355_LOOP_OPERANDS
+        :
+#include "append_loop_clobbers.inc"
+    );
+  } else if constexpr (CAP && BF) {
     asm volatile(
 #include "append_loop_bf16_cap.inc"
         FI355_LOOP_OPERANDS
@@ -367,17 +383,19 @@ __device__ __attribute__((noinline)) void generic_work_item(uint64_t params_addr
   // tile), so that the data loads never wait behind an index load.
   // (page size 16: lane r holds page r of the tile; other page sizes: every thread holds the pages of its own
   // two staging rows, in the low and the high half)
+  // (contiguous KV, kv_indices == null: page j of the chunk is page kv_page0 + j of the pool)
+  const bool contig = p.kv_indices == nullptr;
   auto fetch_page_ids = [&](int t) -> int64_t {
     if (ps_log2 != 4) {
       const int pa = min((kTileKv * t + st_tok) >> ps_log2, n_pages - 1);
       const int pb = min((kTileKv * t + 32 + st_tok) >> ps_log2, n_pages - 1);
-      const uint32_t ia = static_cast<uint32_t>(p.kv_indices[kv_page0 + pa]);
-      const uint32_t ib = static_cast<uint32_t>(p.kv_indices[kv_page0 + pb]);
+      const uint32_t ia = static_cast<uint32_t>(contig ? kv_page0 + pa : p.kv_indices[kv_page0 + pa]);
+      const uint32_t ib = static_cast<uint32_t>(contig ? kv_page0 + pb : p.kv_indices[kv_page0 + pb]);
       return static_cast<int64_t>(ia | (static_cast<uint64_t>(ib) << 32));
     }
     int pi = 4 * t + (lane & 3);
     pi = pi < n_pages ? pi : n_pages - 1;  // never index past the chunk's pages
-    return p.kv_indices[kv_page0 + pi];
+    return contig ? kv_page0 + pi : p.kv_indices[kv_page0 + pi];
   };
   auto fetch_tile = [&](auto set_c, int64_t ids) {
     constexpr int SET = decltype(set_c)::value;
@@ -625,9 +643,11 @@ __device__ __attribute__((noinline)) void generic_work_item(uint64_t params_addr
 
 // VAR: the logits hooks of RunParams are applied.  CAPLOOP (with VAR): the only hook in use is the soft cap, which
 // the scheduled loop has a variant for; the other hooks run every item on the generic path.
-template <bool BF, bool VAR = false, bool CAPLOOP = false>
+// CONTIG: contiguous KV (kv_indices == null); the scheduled loop then computes its page ids.
+template <bool BF, bool VAR = false, bool CAPLOOP = false, bool CONTIG = false>
 __global__ void __launch_bounds__(kCtaThreads) __attribute__((amdgpu_waves_per_eu(2, 2)))
 append_kernel(const RunParams p) {
+  static_assert(!CONTIG || !VAR, "affine addressing is built for the plain kernel");
   const int tid = threadIdx.x;
   // Workgroups are handed to the eight XCDs round-robin: with the kv head as the fast index all
   // CTAs of a kv head (which re-read the same K/V) share one XCD's L2 when num_kv_heads is 8.
@@ -694,7 +714,7 @@ append_kernel(const RunParams p) {
         WorkItem next;
         int prefetched_next;
         __syncthreads();  // the previous work item is done with the tile buffers and the transpose area
-        run_scheduled_loop<BF, CAPLOOP>(n_full, (kv_len + kTileKv - 1) / kTileKv, kv_len, last_seen - 4 * c_o, st_tok_o,
+        run_scheduled_loop<BF, CAPLOOP, CONTIG>(n_full, (kv_len + kTileKv - 1) / kTileKv, kv_len, last_seen - 4 * c_o, st_tok_o,
                                (chunk_pages - 1) * 4, p.kv_indices + kv_page0, static_cast<uint32_t>(k_base),
                                static_cast<uint32_t>(k_base >> 32), static_cast<uint32_t>(v_base),
                                static_cast<uint32_t>(v_base >> 32), static_cast<uint32_t>(page_bytes),
@@ -718,8 +738,8 @@ append_kernel(const RunParams p) {
                                CAPLOOP ? __builtin_bit_cast(int, p.cap_a) : __builtin_amdgcn_readfirstlane(wave_o),
                                __builtin_amdgcn_readfirstlane(min(w + 1, w_end - 1) * 4 + (w + 1 < w_end ? 1 : 0) + 2 * prefetched), p.w_q_row0,
                                static_cast<int>((p.w_n_pos - p.w_q_row0) * static_cast<int64_t>(sizeof(int32_t))),
-                               static_cast<uint32_t>(all_ids), static_cast<uint32_t>(all_ids >> 32), next,
-                               prefetched_next);
+                               CONTIG ? static_cast<uint32_t>(kv_page0) : static_cast<uint32_t>(all_ids),
+                               static_cast<uint32_t>(all_ids >> 32), next, prefetched_next);
         item = next;
         prefetched = prefetched_next;
         continue;  // the work item is finished
@@ -754,6 +774,13 @@ hipError_t launch_append(const RunParams& p, bool is_bf16, bool variant, hipStre
       hipLaunchKernelGGL((append_kernel<true, true>), grid, block, 0, stream, p);
     else
       hipLaunchKernelGGL((append_kernel<false, true>), grid, block, 0, stream, p);
+    return hipGetLastError();
+  }
+  if (p.kv_indices == nullptr) {  // contiguous KV (the caller has refused variants)
+    if (is_bf16)
+      hipLaunchKernelGGL((append_kernel<true, false, false, true>), grid, block, 0, stream, p);
+    else
+      hipLaunchKernelGGL((append_kernel<false, false, false, true>), grid, block, 0, stream, p);
     return hipGetLastError();
   }
   if (is_bf16)

@@ -161,11 +161,15 @@ __device__ __forceinline__ void rotate_blocks(const u32x4_t x, const u32x4_t y, 
 // (The rotary variant and the any-page-size variants run one wavefront per SIMD with up to 512 registers: at two
 // they spill 70-180 registers into scratch memory inside the tile loop; the rotary kernel then takes 1.7 times as
 // long, the any-page-size kernels 3-7 % longer.)
-template <bool BF, bool KV8, bool ANYPS, bool VAR = false, bool ROPE = false>
+// CONTIG: contiguous KV (App. B's dense baseline; Sec. 3.1.1 with the identity as page table): page j of a request is
+// page kv_page0 + j of the pool, so that rows are addressed affinely and no page id is ever loaded.  With page size
+// 1 and the [pages, slots, heads, D] layout the pool is the ragged tensor [tokens, H_kv, D].
+template <bool BF, bool KV8, bool ANYPS, bool VAR = false, bool ROPE = false, bool CONTIG = false>
 __global__ void __launch_bounds__(64)
     __attribute__((amdgpu_waves_per_eu((ROPE || ANYPS) ? 1 : 2, (ROPE || ANYPS) ? 1 : 2)))
 decode_kernel(const RunParams p, const RopeArg<ROPE> rope) {
   static_assert(!ROPE || (VAR && !KV8 && !ANYPS), "the rotary transform is built into the 16-bit variant kernel");
+  static_assert(!CONTIG || (!VAR && !KV8), "affine addressing is built for the plain 16-bit kernel");
   const int lane = threadIdx.x;
   const int m = lane & 15;  // K: token in page; V: 16-byte column block; S/O: query head
   const int c = lane >> 4;  // lane group
@@ -293,6 +297,7 @@ decode_kernel(const RunParams p, const RopeArg<ROPE> rope) {
     // K/V: four) steps before the step's rows are requested; a lane then takes the id of each of its rows from the
     // lane that holds it.  (An index load per row would put a memory round trip in front of every row's load.)
     auto step_ids = [&](int t) {
+      if constexpr (CONTIG) return 0;  // a page's id is its index: nothing to fetch
       const int first = (32 * t) >> ps_log2;
       return n_pages > 0 ? p.kv_indices[kv_page0 + min(first + (lane & 31), n_pages - 1)] : 0;
     };
@@ -303,7 +308,7 @@ decode_kernel(const RunParams p, const RopeArg<ROPE> rope) {
         const int first = (32 * t) >> ps_log2;
         auto row = [&](const uint8_t* base, int tok) {
           const int pg = min(tok >> ps_log2, n_pages - 1);
-          const int64_t id = __builtin_amdgcn_ds_bpermute((pg - first) << 2, idv);
+          const int64_t id = CONTIG ? kv_page0 + pg : __builtin_amdgcn_ds_bpermute((pg - first) << 2, idv);
           return base + id * stride_page + (tok & ((1 << ps_log2) - 1)) * stride_tok;
         };
 #pragma unroll
@@ -319,7 +324,10 @@ decode_kernel(const RunParams p, const RopeArg<ROPE> rope) {
       }
       const int pi = kv_page0 + 2 * t;
       int pg0, pg1;
-      if constexpr (KV8) {
+      if constexpr (CONTIG) {
+        pg0 = pi;
+        pg1 = (2 * t + 1 < n_pages) ? pi + 1 : pi;
+      } else if constexpr (KV8) {
         pg0 = page_ids[pi];
         pg1 = (2 * t + 1 < n_pages) ? page_ids[pi + 1] : pg0;
       } else {
@@ -708,6 +716,21 @@ hipError_t launch_decode(const RunParams& p, bool is_bf16, bool kv8, bool varian
       hipLaunchKernelGGL((decode_kernel<true, false, false, true>), grid, dim3(64, 1, 1), 0, stream, p, NoRope{});
     } else {
       hipLaunchKernelGGL((decode_kernel<false, false, false, true>), grid, dim3(64, 1, 1), 0, stream, p, NoRope{});
+    }
+    return hipGetLastError();
+  }
+  if (p.kv_indices == nullptr) {  // contiguous KV: affine addressing (the caller has refused kv8 and variants)
+    const dim3 grid(static_cast<unsigned>(p.ctas_per_head), static_cast<unsigned>(p.num_kv_heads), 1);
+    if (p.page_log2 == 4) {
+      if (is_bf16)
+        hipLaunchKernelGGL((decode_kernel<true, false, false, false, false, true>), grid, dim3(64, 1, 1), 0, stream, p, NoRope{});
+      else
+        hipLaunchKernelGGL((decode_kernel<false, false, false, false, false, true>), grid, dim3(64, 1, 1), 0, stream, p, NoRope{});
+    } else {
+      if (is_bf16)
+        hipLaunchKernelGGL((decode_kernel<true, false, true, false, false, true>), grid, dim3(64, 1, 1), 0, stream, p, NoRope{});
+      else
+        hipLaunchKernelGGL((decode_kernel<false, false, true, false, false, true>), grid, dim3(64, 1, 1), 0, stream, p, NoRope{});
     }
     return hipGetLastError();
   }

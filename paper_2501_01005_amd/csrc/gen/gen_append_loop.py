@@ -1,5 +1,5 @@
 #!/usr/bin/env python3
-"""Writes append_loop_{bf16,f16}.inc: the hand-scheduled steady-state loop of the append kernel.
+"""Writes append_loop_{bf16,f16}[_cap|_contig].inc: the hand-scheduled steady-state loop of the append kernel.
 
 The loop covers all KV tiles of a work item whose first tile every row of the CTA sees in full:
 first the tiles that need no masking, then, with a compare-and-select on the logits in front of
@@ -94,8 +94,11 @@ def merge_even(*lists):
 
 
 class Gen:
-    def __init__(self, bf16, cap=False):
+    def __init__(self, bf16, cap=False, contig=False):
         self.bf = bf16
+        # contiguous KV (App. B's dense baseline): page j of the chunk is page kv_page0 + j of the pool, so the ids are
+        # computed, not loaded; %[idblo] then carries the chunk's kv_page0 (the page-id array does not exist)
+        self.contig = contig
         # logits soft cap (Sec. 3.2.3): the logits are transformed in place as soon as they are complete.  The block
         # has no scalar register to spare for the two constants of the transform, so in this variant the operand
         # of the softmax scale (which is 1 after the transform) carries the first and the operand of the wavefront
@@ -260,7 +263,10 @@ class Gen:
                 ops.append('s_min_u32 s%d, s%d, %%[npg1]' % (off, off))
             else:
                 ops.append('s_min_u32 s%d, s%d, %%[npg1]' % (off, S_TMP))
-            ops.append('s_load_dword s%d, %%[idp], s%d' % (dst + r, off))
+            if self.contig:
+                ops += ['s_lshr_b32 s%d, s%d, 2' % (dst + r, off), 's_add_u32 s%d, s%d, %%[idblo]' % (dst + r, dst + r)]
+            else:
+                ops.append('s_load_dword s%d, %%[idp], s%d' % (dst + r, off))
         return ops
 
     def header_next(self):
@@ -299,8 +305,11 @@ class Gen:
         # of a tile's four pages this thread's rows are in pages S_STP and 2 + S_STP
         ops.append('s_lshl_b32 s%d, s%d, 2' % (S_LO, S_STP))
         for i in range(4):
-            ops += ['s_add_u32 s%d, s%d, %d' % (S_TMP, S_LO, 8 * i), 's_min_u32 s%d, s%d, s%d' % (S_TMP, S_TMP, S_REM),
-                    's_load_dword s%d, s[%d:%d], s%d' % (S_NX + i, S_KA, S_KA + 1, S_TMP)]
+            ops += ['s_add_u32 s%d, s%d, %d' % (S_TMP, S_LO, 8 * i), 's_min_u32 s%d, s%d, s%d' % (S_TMP, S_TMP, S_REM)]
+            if self.contig:  # the next item's page ids follow from its kv_page0
+                ops += ['s_lshr_b32 s%d, s%d, 2' % (S_NX + i, S_TMP), 's_add_u32 s%d, s%d, %%[npg]' % (S_NX + i, S_NX + i)]
+            else:
+                ops.append('s_load_dword s%d, s[%d:%d], s%d' % (S_NX + i, S_KA, S_KA + 1, S_TMP))
         ops.append(no + ':')
         return ops
 
@@ -701,8 +710,10 @@ def write(path, lines, name):
 if __name__ == '__main__':
     here = os.path.dirname(os.path.abspath(__file__))
     out_dir = sys.argv[1] if len(sys.argv) > 1 else os.path.join(here, '..')
-    for bf, cap, name in ((True, False, 'bf16'), (False, False, 'f16'), (True, True, 'bf16_cap'), (False, True, 'f16_cap')):
-        lines = Gen(bf, cap).program()
+    for bf, cap, contig, name in ((True, False, False, 'bf16'), (False, False, False, 'f16'), (True, True, False, 'bf16_cap'),
+                                  (False, True, False, 'f16_cap'), (True, False, True, 'bf16_contig'),
+                                  (False, False, True, 'f16_contig')):
+        lines = Gen(bf, cap, contig).program()
         write(os.path.join(out_dir, 'append_loop_%s.inc' % name), lines, name)
         n_mfma = sum(1 for l in lines if l.startswith('v_mfma'))
         print('%s: %d lines, %d matrix instructions, %d waits' % (name, len(lines), n_mfma, sum(1 for l in lines if l.startswith('s_waitcnt'))))

@@ -51,9 +51,11 @@ def make_wrapper(batch, mode, **kw) -> PagedAttention:
                           max_batch=max(batch.batch, 1), max_qo_tiles=max(tiles, 1), **kw)
 
 
-def run_gpu(batch, mode="decode", dev: DeviceBatch | None = None, wrapper=None, poison=True, with_cast=False, **kw):
+def run_gpu(batch, mode="decode", dev: DeviceBatch | None = None, wrapper=None, poison=True, with_cast=False,
+            contiguous=False, **kw):
     """fi_plan + fi_run of the batch; returns (o, lse) as float64 numpy (and the rounded output when
-    with_cast).  poison: the partial-state sections of the workspace and the outputs start as NaN."""
+    with_cast).  poison: the partial-state sections of the workspace and the outputs start as NaN.
+    contiguous: run without a page table (kv_indices = NULL; the batch's page table must be the identity)."""
     import torch
     dev = dev or DeviceBatch(batch)
     own = wrapper is None
@@ -65,7 +67,10 @@ def run_gpu(batch, mode="decode", dev: DeviceBatch | None = None, wrapper=None, 
     o = torch.full((nnz, batch.num_qo_heads, batch.head_dim), float("nan"), dtype=torch.float32, device=dev.device)
     lse = torch.full((nnz, batch.num_qo_heads), float("nan"), dtype=torch.float32, device=dev.device)
     oc = torch.zeros((nnz, batch.num_qo_heads, batch.head_dim), dtype=dev.q.dtype, device=dev.device) if with_cast else None
-    w.run(dev.q, dev.k_pool, dev.v_pool, dev.kv_indices, batch.sm_scale, o=o, lse=lse, o_cast=oc, **dev.scales)
+    if contiguous:
+        assert np.array_equal(batch.kv_indices, np.arange(len(batch.kv_indices))), "not a contiguous cache"
+    w.run(dev.q, dev.k_pool, dev.v_pool, None if contiguous else dev.kv_indices, batch.sm_scale, o=o, lse=lse, o_cast=oc,
+          **dev.scales)
     torch.cuda.synchronize()
     res = (o.double().cpu().numpy(), lse.double().cpu().numpy())
     if with_cast:
