@@ -257,6 +257,8 @@ def main() -> int:
                          "unrotated keys, Sec. 4.3); 16-bit decode workloads only")
     ap.add_argument("--soft-cap", type=float, default=0.0,
                     help="> 0: logits soft cap c * tanh(s / c) (fi_run_variant, Sec. 3.2.3); 16-bit decode and causal append workloads")
+    ap.add_argument("--alibi", action="store_true",
+                    help="ALiBi bias slope[head] * (t - pos) on the logits (fi_run_variant); 16-bit decode and causal append workloads")
     ap.add_argument("--window-left", type=int, default=-1,
                     help=">= 0: decode with a sliding window of that many tokens behind the query (fi_run_variant)")
     ap.add_argument("--plan-window", action="store_true",
@@ -373,15 +375,19 @@ def run_workload(args):
             return 2
         run_kw["o_cast"] = torch.empty((nnz, batch.num_qo_heads, batch.head_dim), dtype=dev.q.dtype, device=dev.device)
         o = False
-    if args.rope_theta > 0 or args.window_left >= 0 or args.soft_cap > 0:
-        if batch.kv_dtype or args.page_size != 16 or (mode != "decode" and (args.rope_theta > 0 or args.window_left >= 0 or not batch.causal)):
-            print("bench.py: --rope-theta / --window-left are for the 16-bit decode workloads with page size 16, "
+    if args.rope_theta > 0 or args.window_left >= 0 or args.soft_cap > 0 or args.alibi:
+        if batch.kv_dtype or args.page_size != 16 or (mode != "decode" and (args.rope_theta > 0 or not batch.causal)):
+            print("bench.py: --rope-theta is for the 16-bit decode workloads with page size 16, --window-left, --alibi and "
                   "--soft-cap for those and the causal append workloads", file=sys.stderr)
             return 2
         run_kw["variant"] = dict(
             kv_indptr=torch.from_numpy(np.ascontiguousarray(batch.kv_indptr, dtype=np.int32)).to(dev.device),
             last_page_len=torch.from_numpy(np.ascontiguousarray(batch.last_page_len, dtype=np.int32)).to(dev.device),
             rope_theta=args.rope_theta, window_left=args.window_left, logits_soft_cap=args.soft_cap)
+        if args.alibi:   # the usual geometric slopes 2^(-8 (h + 1) / H)
+            h = batch.num_qo_heads
+            run_kw["variant"]["alibi_slopes"] = torch.tensor([2.0 ** (-8.0 * (i + 1) / h) for i in range(h)],
+                                                             dtype=torch.float32, device=dev.device)
 
     stride = max(1, args.event_stride)
     n_samples = (args.steps + stride - 1) // stride
@@ -438,7 +444,7 @@ def run_workload(args):
     traffic = None  # HBM bytes per launch by hardware counters: taken in an earlier profiled run of this command, not live
     tpath = os.path.join(ROOT, "profiles", "traffic.json")
     measured_setup = (args.page_size == 16 and args.page_order == "random" and args.kv_layout == "HND" and
-                      args.window_left < 0 and args.soft_cap == 0 and not args.small)  # the counters were taken on these settings only
+                      args.window_left < 0 and args.soft_cap == 0 and not args.alibi and not args.small)  # the counters were taken on these settings only
     if os.path.exists(tpath) and measured_setup:
         traffic = json.load(open(tpath)).get(args.workload + ("_fp8" if batch.kv_dtype else "") +
                                              ("_rope" if args.rope_theta > 0 else "") +
@@ -479,6 +485,7 @@ def run_workload(args):
                    "kv_dtype": batch.kv_dtype or batch.dtype, "o_dtype": batch.dtype if args.out16 else "f32",
                    **({"fused_rope_theta": args.rope_theta} if args.rope_theta > 0 else {}),
                    **({"logits_soft_cap": args.soft_cap} if args.soft_cap > 0 else {}),
+                   **({"alibi": True} if args.alibi else {}),
                    **({"window_left": args.window_left, "planned": bool(args.plan_window)} if args.window_left >= 0 else {}),
                    "step": ("fi_run captured in a HIP graph, replayed (plan reused)" if args.graph else
                             "fi_run only (plan reused)" if args.no_plan else "fi_plan + fi_run"),

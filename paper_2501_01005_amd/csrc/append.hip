@@ -194,7 +194,10 @@ struct WorkItem {
 // bits 8.. above log2 of the group size.
 // CONTIG: contiguous KV (page j of the chunk is page kv_page0 + j of the pool): the page ids are computed instead of
 // loaded; `all_ids_lo` then carries the chunk's kv_page0, `page_ids` and `all_ids_hi` are unused.
-template <bool BF, bool CAP, bool CONTIG>
+// VARL: the variant of the loop with the ALiBi bias and the sliding window (Sec. 3.2.3; causal items): `cap` then
+// carries lim - 4 * (lane / 32) uncapped, lim = chunk-local index of the row's own token; `slope` = the row's head's
+// slope times log2(e) (0: none), `win` = window_left (a huge value: none).
+template <bool BF, bool CAP, bool CONTIG, bool VARL>
 __device__ __forceinline__ void run_scheduled_loop(int n_full, int n_tiles, int kv_len, int cap, int st_tok, int ids_clamp, const int32_t* page_ids, uint32_t k_lo,
                                                    uint32_t k_hi, uint32_t v_lo, uint32_t v_hi, uint32_t page_bytes,
                                                    float scale_log2, uint64_t q_addr, uint32_t st_off_bytes,
@@ -205,19 +208,44 @@ __device__ __forceinline__ void run_scheduled_loop(int n_full, int n_tiles, int 
                                                    uint32_t epi_chunk, int g_log2, int num_qo_heads, int row_base,
                                                    int n_pos, int wave_index, int next_off,
                                                    const int32_t* w_fields, int w_stride, uint32_t all_ids_lo,
-                                                   uint32_t all_ids_hi, WorkItem& next, int& prefetched_out) {
+                                                   uint32_t all_ids_hi, WorkItem& next, int& prefetched_out,
+                                                   float slope = 0.f, int win = 0) {
 #define FI355_LOOP_OPERANDS                                                                                              \
         : [nq] "=&s"(next.q_row0), [nn] "=&s"(next.n_pos), [npg] "=&s"(next.kv_page0), [nks] "=&s"(next.kv_start),          \
           [nkl] "=&s"(next.kv_len), [ndg] "=&s"(next.diag0), [nos] "=&s"(next.out_slot), [preo] "=&s"(prefetched_out)        \
         : [nf] "s"(n_full), [nt] "s"(n_tiles), [kvl] "s"(kv_len), [cap] "v"(cap), [stk] "v"(st_tok), [npg1] "s"(ids_clamp), [idp] "s"(page_ids), [kblo] "s"(k_lo), [kbhi] "s"(k_hi), \
           [vblo] "s"(v_lo), [vbhi] "s"(v_hi), [sp] "s"(page_bytes), [sc] "s"(scale_log2),                                 \
           [qp] "v"(q_addr), [so] "v"(st_off_bytes), [sok] "v"(k_off_bytes), [kb] "v"(k_read), [kxs] "v"(k_swizzle),        \
-          [va] "v"(v_read), [kd] "s"(k_dma), [wv] "v"(v_write), [ooff] "v"(o_off), [rok] "v"(row_flags), [ob] "s"(o_base), [lb] "s"(lse_base), \
+          [va] "v"(v_read), [kd] "s"(k_dma), [wv] "v"(v_write), [ooff] "v"(o_off), FI355_ROW_FLAGS [ob] "s"(o_base), [lb] "s"(lse_base), \
           [cb] "s"(cast_base), [oc] "s"(has_cast), [ew] "v"(epi_write), [er] "v"(epi_read), [l16] "v"(epi_chunk),          \
-          [gl] "s"(g_log2), [hq] "s"(num_qo_heads), [rb] "s"(row_base), [np] "s"(n_pos), [stp8] "s"(wave_index),           \
+          [gl] "s"(g_log2), FI355_HEADS_AND_POSITIONS [rb] "s"(row_base), [stp8] "s"(wave_index),                          \
           [woff] "s"(next_off), [wq0] "s"(w_fields), [wstr] "s"(w_stride),                                                  \
           [idblo] "s"(all_ids_lo), [idbhi] "s"(all_ids_hi)
-  if constexpr (CONTIG && BF) {
+  // (the bias / window variant has a per-lane and a scalar operand more than there are registers left: it finds the
+  // lanes that write lse itself instead of taking row_flags, and takes n_pos and num_qo_heads packed into g_log2)
+#define FI355_ROW_FLAGS
+#define FI355_HEADS_AND_POSITIONS
+  if constexpr (VARL && BF) {
+    asm volatile(
+#include "append_loop_bf16_var.inc"
+        FI355_LOOP_OPERANDS, [slope] "v"(slope), [win] "s"(win)
+        :
+#include "append_loop_clobbers.inc"
+    );
+  } else if constexpr (VARL) {
+    asm volatile(
+#include "append_loop_f16_var.inc"
+        FI355_LOOP_OPERANDS, [slope] "v"(slope), [win] "s"(win)
+        :
+#include "append_loop_clobbers.inc"
+    );
+  }
+#undef FI355_ROW_FLAGS
+#undef FI355_HEADS_AND_POSITIONS
+#define FI355_ROW_FLAGS [rok] "v"(row_flags),
+#define FI355_HEADS_AND_POSITIONS [hq] "s"(num_qo_heads), [np] "s"(n_pos),
+  if constexpr (VARL) {
+  } else if constexpr (CONTIG && BF) {
     asm volatile(
 #include "append_loop_bf16_contig.inc"
         FI355_LOOP_OPERANDS
@@ -261,6 +289,8 @@ __device__ __forceinline__ void run_scheduled_loop(int n_full, int n_tiles, int 
     );
   }
 #undef FI355_LOOP_OPERANDS
+#undef FI355_ROW_FLAGS
+#undef FI355_HEADS_AND_POSITIONS
 }
 
 // K tiles, then V tiles (three buffers each: the scheduled loop rotates over three, the generic
@@ -644,10 +674,13 @@ __device__ __attribute__((noinline)) void generic_work_item(uint64_t params_addr
 // VAR: the logits hooks of RunParams are applied.  CAPLOOP (with VAR): the only hook in use is the soft cap, which
 // the scheduled loop has a variant for; the other hooks run every item on the generic path.
 // CONTIG: contiguous KV (kv_indices == null); the scheduled loop then computes its page ids.
-template <bool BF, bool VAR = false, bool CAPLOOP = false, bool CONTIG = false>
+// VARLOOP (with VAR): the hooks in use are the ALiBi bias and / or the sliding window, without the soft cap: the
+// scheduled loop has a variant for them too.
+template <bool BF, bool VAR = false, bool CAPLOOP = false, bool CONTIG = false, bool VARLOOP = false>
 __global__ void __launch_bounds__(kCtaThreads) __attribute__((amdgpu_waves_per_eu(2, 2)))
 append_kernel(const RunParams p) {
   static_assert(!CONTIG || !VAR, "affine addressing is built for the plain kernel");
+  static_assert(!(CAPLOOP && VARLOOP) && (!VARLOOP || VAR), "one variant of the loop per instantiation");
   const int tid = threadIdx.x;
   // Workgroups are handed to the eight XCDs round-robin: with the kv head as the fast index all
   // CTAs of a kv head (which re-read the same K/V) share one XCD's L2 when num_kv_heads is 8.
@@ -671,7 +704,7 @@ append_kernel(const RunParams p) {
     const bool causal = diag0 != kNoDiagMarker;
 
     // ---- work items whose first tile every row of the CTA sees in full: the scheduled loop ----
-    if constexpr (kUseScheduledLoop && (!VAR || CAPLOOP)) {
+    if constexpr (kUseScheduledLoop && (!VAR || CAPLOOP || VARLOOP)) {
       int vis = kv_len;  // tokens visible to the CTA's first position, which sees the fewest
       if (causal) vis = min(vis, max(0, diag0 - kv_start + 1));
       const int n_full = __builtin_amdgcn_readfirstlane(vis / kTileKv);
@@ -679,6 +712,7 @@ append_kernel(const RunParams p) {
       // (the loop addresses its outputs with 32-bit byte offsets)
       const int64_t out_rows_bound = (out_slot < 0 ? static_cast<int64_t>(q_row0) + p.t_pos : (static_cast<int64_t>(out_slot) + 1) * p.t_pos) * H;
       if (p.page_log2 == 4 && n_full >= 1 && kv_len >= kLoopMinTokens && page_bytes > 0 && page_bytes < (int64_t(1) << 32) &&
+          (!VARLOOP || H < 65536) &&  // (that variant takes num_qo_heads in 16 bits of an operand)
           out_rows_bound * (kHeadDim * 4) < (int64_t(1) << 32)) {
         // The loop clobbers nearly every vector register, so its lane-dependent operands are
         // derived here from an opaque copy of the thread index: the compiler cannot hoist them out
@@ -714,7 +748,13 @@ append_kernel(const RunParams p) {
         WorkItem next;
         int prefetched_next;
         __syncthreads();  // the previous work item is done with the tile buffers and the transpose area
-        run_scheduled_loop<BF, CAPLOOP, CONTIG>(n_full, (kv_len + kTileKv - 1) / kTileKv, kv_len, last_seen - 4 * c_o, st_tok_o,
+        // (with the bias / window variant the loop caps the bound itself and also needs it uncapped)
+        const int seen_bound = VARLOOP ? diag0 + pos_r - kv_start : last_seen;
+        float slope_o = 0.f;
+        if constexpr (VARLOOP) {
+          if (p.alibi_slopes != nullptr) slope_o = p.alibi_slopes[head] * 1.4426950408889634f;
+        }
+        run_scheduled_loop<BF, CAPLOOP, CONTIG, VARLOOP>(n_full, (kv_len + kTileKv - 1) / kTileKv, kv_len, seen_bound - 4 * c_o, st_tok_o,
                                (chunk_pages - 1) * 4, p.kv_indices + kv_page0, static_cast<uint32_t>(k_base),
                                static_cast<uint32_t>(k_base >> 32), static_cast<uint32_t>(v_base),
                                static_cast<uint32_t>(v_base >> 32), static_cast<uint32_t>(page_bytes),
@@ -731,7 +771,10 @@ append_kernel(const RunParams p) {
                                epi0 + n_o * kEpilogueRowBytes + c_o * 16,
                                epi0 + ((tid_o >> 4) & 3) * kEpilogueRowBytes + st_chunk_o * 16,
                                st_chunk_o * 16,
-                               CAPLOOP ? g_log2 | (__builtin_amdgcn_readfirstlane(wave_o) << 8) : g_log2, H,
+                               CAPLOOP   ? g_log2 | (__builtin_amdgcn_readfirstlane(wave_o) << 8)
+                               : VARLOOP ? g_log2 | (n_pos << 5) | (H << 16)
+                                         : g_log2,
+                               H,
                                static_cast<int>((final_out ? static_cast<int64_t>(q_row0)
                                                            : static_cast<int64_t>(out_slot) * p.t_pos) * H + kvh * g),
                                n_pos,
@@ -739,7 +782,8 @@ append_kernel(const RunParams p) {
                                __builtin_amdgcn_readfirstlane(min(w + 1, w_end - 1) * 4 + (w + 1 < w_end ? 1 : 0) + 2 * prefetched), p.w_q_row0,
                                static_cast<int>((p.w_n_pos - p.w_q_row0) * static_cast<int64_t>(sizeof(int32_t))),
                                CONTIG ? static_cast<uint32_t>(kv_page0) : static_cast<uint32_t>(all_ids),
-                               static_cast<uint32_t>(all_ids >> 32), next, prefetched_next);
+                               static_cast<uint32_t>(all_ids >> 32), next, prefetched_next, slope_o,
+                               p.window_left >= 0 ? p.window_left : 0x3FFFFFFF);
         item = next;
         prefetched = prefetched_next;
         continue;  // the work item is finished
@@ -769,7 +813,14 @@ hipError_t launch_append(const RunParams& p, bool is_bf16, bool variant, hipStre
       hipLaunchKernelGGL((append_kernel<false, true, true>), grid, block, 0, stream, p);
     return hipGetLastError();
   }
-  if (variant) {
+  if (variant && p.soft_cap == 0.f) {  // bias and / or window: their variant of the scheduled loop
+    if (is_bf16)
+      hipLaunchKernelGGL((append_kernel<true, true, false, false, true>), grid, block, 0, stream, p);
+    else
+      hipLaunchKernelGGL((append_kernel<false, true, false, false, true>), grid, block, 0, stream, p);
+    return hipGetLastError();
+  }
+  if (variant) {  // the soft cap together with a bias or a window: every item on the general path
     if (is_bf16)
       hipLaunchKernelGGL((append_kernel<true, true>), grid, block, 0, stream, p);
     else

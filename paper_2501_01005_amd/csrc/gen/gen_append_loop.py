@@ -50,10 +50,14 @@ S_PG0, S_PG1, S_LO, S_HI, S_KA, S_VA, S_THR, S_REM = 76, 77, 78, 79, 80, 82, 84,
 S_IDA, S_IDB = 88, 92          # two more page id groups, start-up only
 S_EXEC = 96
 S_IDK = 88                     # page ids of the tile whose K goes to LDS next (takes over S_IDA after start-up)
+S_ONES = 98                    # var variant: fp16 ones in both halves (the vector register of the constant is needed otherwise)
+S_NP, S_HQ = 99, 100           # var variant: n_pos and num_qo_heads, unpacked from %[gl]
 S_M0 = 97                      # saved m0 (the register doubles as half of S_EXEC, which is used only after m0 is restored)
 S_NX = 92                      # this wavefront's page ids of tiles 0 and 1 of the CTA's next work item (takes over S_IDB after start-up)
 S_STP = 96                     # which page of a 32-token half this thread's staging rows are in (wavefront / 4); the epilogue reuses the register
-FIXED_SGPRS = list(range(64, 98))
+FIXED_SGPRS = list(range(64, 101))
+CAPV, WLO = 20, 21             # var variant: capped upper bound / lower bound of the tokens a lane's row sees, minus 4 c
+FLOOR = 0xf149f2ca             # -1e30: reference of a row that has not seen a key yet (var variant)
 NO_DIAG = 0x3FFFFFFF           # w_diag0 of a non-causal work item
 LOOP_MIN_TOKENS = 128          # shorter chunks never run this loop
 
@@ -63,6 +67,11 @@ V_BASE = 65536                 # V buffers start where the generic path has them
 STAGE = 2 * KTILE              # the next item's V tiles 0 and 1 as stored: K buffer 2 and the 16 KB after the K buffers
 NBUF = 3
 LAZY_THR = 0x5C005C00          # fp16 2^8 in both halves: P above it raises the reference
+
+
+def float_bits(x):
+    import struct
+    return struct.unpack('<I', struct.pack('<f', float(x)))[0]
 
 
 def vr(base, n=1):
@@ -94,8 +103,27 @@ def merge_even(*lists):
 
 
 class Gen:
-    def __init__(self, bf16, cap=False, contig=False):
+    def __init__(self, bf16, cap=False, contig=False, var=False):
         self.bf = bf16
+        # ALiBi bias and sliding window (Sec. 3.2.3) for causal work items: like the soft cap, the logits of a step are
+        # transformed in place as soon as they are complete: s <- s * sm_scale * log2(e) + slope * (t - pos), then -inf
+        # where t < pos - W.  Per lane: %[cap] carries lim - 4 c uncapped (lim = chunk-local index of the row's own
+        # token), %[slope] the head's slope times log2(e) (0 = no bias); %[win] = W (a huge value = no window).  The
+        # capped bound (v20) and the window's lower bound (v21) are derived in the prologue; their registers are taken
+        # from the constant of ones (then a scalar) and from the temporary of the lazy check (then one of the
+        # exponentials' temporaries).  A row may see nothing in a step, a tile or the whole chunk: its reference then
+        # stays at a large negative floor (so that masked logits still give P = 0 and the first visible one raises the
+        # reference), and the epilogue writes o = 0, lse = -inf for a row without any visible key.
+        self.var = var
+        self.inplace = cap or var     # the S registers hold final logits in log2 units; the softmax scale is 1
+        self.capreg = 'v%d' % CAPV if var else '%[cap]'
+        self.maxt = T + 15 if var else MAXT
+        self.ones = 's%d' % S_ONES if var else 'v%d' % ONES
+        # the bias / window variant has one more scalar operand (the window) than scalar registers are left: there
+        # %[gl] carries log2 g (bits 0..4, only ever used as a shift amount), n_pos (bits 5..15) and num_qo_heads
+        # (bits 16..31), unpacked in the prologue
+        self.np = 's%d' % S_NP if var else '%[np]'
+        self.hq = 's%d' % S_HQ if var else '%[hq]'
         # contiguous KV (App. B's dense baseline): page j of the chunk is page kv_page0 + j of the pool, so the ids are
         # computed, not loaded; %[idblo] then carries the chunk's kv_page0 (the page-id array does not exist)
         self.contig = contig
@@ -130,7 +158,7 @@ class Gen:
         ops = []
         for j in range(8):
             a, b = T + 2 * j, T + 2 * j + 1
-            if self.cap:
+            if self.inplace:
                 ops += ['v_add_f32 v%d, v%d, v%d' % (a, Sc + 2 * j, NEGMS), 'v_add_f32 v%d, v%d, v%d' % (b, Sc + 2 * j + 1, NEGMS)]
             else:
                 ops += ['v_fma_f32 v%d, v%d, %%[sc], v%d' % (a, Sc + 2 * j, NEGMS),
@@ -155,13 +183,36 @@ class Gen:
         ops += ['v_mul_f32 v%d, %%[stp8], v%d' % (Sx + r, T + r) for r in range(16)]
         return ops
 
+    def transform(self, Sx, base_add):
+        """the in-place logits transform of a step whose first token is 64 * S_T + base_add (chunk-local)"""
+        if self.cap:
+            return self.soft_cap(Sx)
+        if not self.var:
+            return []
+        ops = ['s_lshl_b32 s%d, s%d, 6' % (S_TMP, S_T)]
+        if base_add:
+            ops.append('s_add_u32 s%d, s%d, %d' % (S_TMP, S_TMP, base_add))
+        # X1 <- slope * (step base - (lim - 4 c)): the bias of the lane's first token of the step
+        ops += ['v_sub_u32 v%d, s%d, %%[cap]' % (X1, S_TMP), 'v_cvt_f32_i32 v%d, v%d' % (X1, X1),
+                'v_mul_f32 v%d, %%[slope], v%d' % (X1, X1)]
+        ops += ['v_fma_f32 v%d, v%d, %%[sc], v%d' % (Sx + r, Sx + r, X1) for r in range(16)]
+        for r in range(1, 16):
+            k = 8 * (r // 4) + r % 4
+            ops.append('v_fmamk_f32 v%d, %%[slope], 0x%08x, v%d' % (Sx + r, float_bits(k), Sx + r))
+        # window: token k of the lane's 16 is visible iff k >= (lim - 4 c - W) - step base
+        ops.append('v_subrev_u32 v%d, s%d, v%d' % (X0, S_TMP, WLO))
+        for r in range(16):
+            ops.append('v_cmp_ge_i32 vcc, %d, v%d' % (8 * (r // 4) + r % 4, X0))
+            ops.append('v_cndmask_b32 v%d, v%d, v%d, vcc' % (Sx + r, NINF, Sx + r))
+        return ops
+
     def mask(self, Sc, u):
         """logits of tokens past this lane's last visible one become -inf: register r holds token
         32 s + 4 c + 8 (r / 4) + r % 4 of the step, and cap = last visible token - 4 c"""
         ops = ['s_lshl_b32 s%d, s%d, 6' % (S_TMP, S_T)]
         if u:
             ops.append('s_add_u32 s%d, s%d, 32' % (S_TMP, S_TMP))
-        ops.append('v_subrev_u32 v%d, s%d, %%[cap]' % (X1, S_TMP))
+        ops.append('v_subrev_u32 v%d, s%d, %s' % (X1, S_TMP, self.capreg))
         for r in range(16):
             ops.append('v_cmp_le_i32 vcc, %d, v%d' % (8 * (r // 4) + r % 4, X1))
             ops.append('v_cndmask_b32 v%d, v%d, v%d, vcc' % (Sc + r, NINF, Sc + r))
@@ -169,15 +220,16 @@ class Gen:
 
     def lazy_check(self):
         # P >= 0, so fp16 order is unsigned order on the bit patterns; any half above 2^8 -> vcc != 0
-        ops = ['v_pk_max_u16 v%d, v%d, v%d' % (MAXT, H, H + 1)]
+        mt = self.maxt
+        ops = ['v_pk_max_u16 v%d, v%d, v%d' % (mt, H, H + 1)]
         for j in range(2, 8):
-            ops.append('v_pk_max_u16 v%d, v%d, v%d' % (MAXT, MAXT, H + j))
-        ops.append('v_pk_min_u16 v%d, v%d, s%d' % (X0, MAXT, S_THR))
-        ops.append('v_cmp_ne_u32 vcc, v%d, v%d' % (X0, MAXT))
+            ops.append('v_pk_max_u16 v%d, v%d, v%d' % (mt, mt, H + j))
+        ops.append('v_pk_min_u16 v%d, v%d, s%d' % (X0, mt, S_THR))
+        ops.append('v_cmp_ne_u32 vcc, v%d, v%d' % (X0, mt))
         return ops
 
     def rowsum(self):
-        return ['v_dot2_f32_f16 v%d, v%d, v%d, v%d' % (LSUM, H + j, ONES, LSUM) for j in range(8)]
+        return ['v_dot2_f32_f16 v%d, v%d, %s, v%d' % (LSUM, H + j, self.ones, LSUM) for j in range(8)]
 
     def k_reads(self, buf, u):
         return ['ds_read_b128 %s, v%d offset:%d' % (vr(KA + 4 * s, 4), KAD + s, buf * KTILE + u * 32 * KROW)
@@ -377,13 +429,13 @@ class Gen:
 
     def set_reference(self):
         return ['v_mov_b32 v%d, v%d' % (MRUN, X0),
-                'v_mov_b32 v%d, v%d' % (NEGMS, X0) if self.cap else 'v_mul_f32 v%d, v%d, %%[sc]' % (NEGMS, X0),
+                'v_mov_b32 v%d, v%d' % (NEGMS, X0) if self.inplace else 'v_mul_f32 v%d, v%d, %%[sc]' % (NEGMS, X0),
                 'v_xor_b32 v%d, 0x80000000, v%d' % (NEGMS, NEGMS)]
 
     def raise_reference(self, Sc):
         """out-of-line: raise the reference to the row maximum, rescale the state, redo P"""
         ops = self.row_max(Sc)
-        ops += ['v_sub_f32 v%d, v%d, v%d' % (X1, MRUN, X0)] + ([] if self.cap else ['v_mul_f32 v%d, v%d, %%[sc]' % (X1, X1)]) + [
+        ops += ['v_sub_f32 v%d, v%d, v%d' % (X1, MRUN, X0)] + ([] if self.inplace else ['v_mul_f32 v%d, v%d, %%[sc]' % (X1, X1)]) + [
                 'v_exp_f32 v%d, v%d' % (X1, X1)]
         ops += self.set_reference()
         ops.append('v_mul_f32 v%d, v%d, v%d' % (LSUM, LSUM, X1))
@@ -402,7 +454,7 @@ class Gen:
         if masked:
             # none of this wavefront's rows sees a token of this tile or of any later one (its last row, lane 31,
             # sees the most): from here on it only helps with the staging, then writes its outputs
-            e.raw('v_readlane_b32 s%d, %%[cap], 31' % S_TMP)
+            e.raw('v_readlane_b32 s%d, %s, 31' % (S_TMP, self.capreg))
             e.raw('s_lshl_b32 s%d, s%d, 6' % (S_REM, S_T))
             e.raw('s_cmp_gt_i32 s%d, s%d' % (S_REM, S_TMP))
             e.raw('s_cbranch_scc1 tile_j%d_%s' % (k, lbl))
@@ -416,7 +468,7 @@ class Gen:
                 # the same test for the tile's second 32-token step: the wavefront leaves the tile half way and
                 # does the rest of its staging share in half_j
                 self.mid_state[k] = ([set(d) for d in e.lgkm], [set(d) for d in e.vm])
-                e.raw('v_readlane_b32 s%d, %%[cap], 31' % S_TMP)
+                e.raw('v_readlane_b32 s%d, %s, 31' % (S_TMP, self.capreg))
                 e.raw('s_lshl_b32 s%d, s%d, 6' % (S_REM, S_T))
                 e.raw('s_add_u32 s%d, s%d, 32' % (S_REM, S_REM))
                 e.raw('s_cmp_gt_i32 s%d, s%d' % (S_REM, S_TMP))
@@ -433,9 +485,9 @@ class Gen:
             # (with the soft cap: the next step's logits, complete since the matrix instructions of block 1, are
             # transformed behind the last products of this block; the temporaries of the exponentials are free here)
             if u == 0:
-                rest = merge_even(kn, self.rowsum() + self.v_convert()) + self.soft_cap(Sn)
+                rest = merge_even(kn, self.rowsum() + self.v_convert()) + self.transform(Sn, 32)
             else:
-                rest = merge_even(kn, self.rowsum() + self.v_zero_tail(2)) + self.stores(wr) + self.fetch() + self.soft_cap(Sn)
+                rest = merge_even(kn, self.rowsum() + self.v_zero_tail(2)) + self.stores(wr) + self.fetch() + self.transform(Sn, 64)
             spread(e, [self.pv(db, j) for j in range(2) for db in range(4)], rest)
         e.wait_lds_loads()
         e.emit('s_barrier')
@@ -507,7 +559,18 @@ class Gen:
             e.emit('global_load_dwordx4 %s, %%[qp], off offset:%d' % (vr(Q + 4 * s, 4), 32 * s))
         for o in self.header_next():
             e.raw(o)
-        e.raw('v_mov_b32 v%d, 0x3c003c00' % ONES)
+        if self.var:
+            e.raw('s_mov_b32 s%d, 0x3c003c00' % S_ONES)
+            e.raw('s_bfe_u32 s%d, %%[gl], 0x%x' % (S_NP, (11 << 16) | 5))
+            e.raw('s_lshr_b32 s%d, %%[gl], 16' % S_HQ)
+            # 4 c of this lane -> upper bound capped at the chunk's last token, lower bound of the window
+            for o in ['v_mbcnt_lo_u32_b32 v%d, -1, 0' % X0, 'v_mbcnt_hi_u32_b32 v%d, -1, v%d' % (X0, X0),
+                      'v_lshrrev_b32 v%d, 5, v%d' % (X0, X0), 'v_lshlrev_b32 v%d, 2, v%d' % (X0, X0),
+                      'v_sub_u32 v%d, %%[kvl], v%d' % (X1, X0), 'v_subrev_u32 v%d, 1, v%d' % (X1, X1),
+                      'v_min_i32 v%d, %%[cap], v%d' % (CAPV, X1), 'v_subrev_u32 v%d, %%[win], %%[cap]' % WLO]:
+                e.raw(o)
+        else:
+            e.raw('v_mov_b32 v%d, 0x3c003c00' % ONES)
         e.raw('v_mov_b32 v%d, 0' % LSUM)
         e.raw('v_mov_b32 v%d, 0xff800000' % MRUN)
         e.raw('v_mov_b32 v%d, 0xff800000' % NINF)
@@ -570,7 +633,7 @@ class Gen:
         for o in self.wave_shift(S_TMP, 'lshl', 5):            # first tile row of this wavefront
             e.raw(o)
         e.raw('s_lshr_b32 s%d, s%d, %%[gl]' % (S_TMP, S_TMP))  # its position
-        e.raw('s_cmp_ge_u32 s%d, %%[np]' % S_TMP)
+        e.raw('s_cmp_ge_u32 s%d, %s' % (S_TMP, self.np))
         e.raw('s_cbranch_scc1 tile_i0_%s' % lbl)
         # first step: S^T(0, 0), the K operands of step (0, 1), the first reference
         for o in self.k_reads(0, 0):
@@ -581,7 +644,8 @@ class Gen:
             e.emit(o)
         e.raw('s_nop 15')
         e.raw('s_nop 15')
-        for o in self.soft_cap(S0) + self.row_max(S0) + self.set_reference():
+        floor = ['v_max_f32 v%d, 0x%08x, v%d' % (X0, FLOOR, X0)] if self.var else []
+        for o in self.transform(S0, 0) + self.row_max(S0) + floor + self.set_reference():
             e.emit(o)
         e.drain(lgkm=True, vm=False)
         e.raw('s_cmp_lt_u32 s%d, %%[nf]' % S_T)  # t = 0: a first tile that needs masking is possible when nf = 0
@@ -622,12 +686,20 @@ class Gen:
         for o in ['v_mov_b32 v%d, v%d' % (X0, LSUM), 'v_mov_b32 v%d, v%d' % (X1, LSUM), 's_nop 1',
                   'v_permlane32_swap_b32 v%d, v%d' % (X0, X1), 's_nop 1', 'v_add_f32 v%d, v%d, v%d' % (LSUM, X0, X1),
                   # (a transcendental result needs a wait state before an ordinary vector instruction reads it)
-                  'v_log_f32 v%d, v%d' % (X1, LSUM), 'v_rcp_f32 v%d, v%d' % (X0, LSUM), 's_nop 1',
-                  'v_add_f32 v%d, v%d, v%d' % (X1, MRUN, X1) if self.cap else 'v_fma_f32 v%d, v%d, %%[sc], v%d' % (X1, MRUN, X1),
+                  'v_log_f32 v%d, v%d' % (X1, LSUM), 'v_rcp_f32 v%d, v%d' % (X0, LSUM), 's_nop 1'] + (
+                  # a row without a visible key: l = 0 -> o = 0 (lse = reference + log2(0) = -inf by itself)
+                  ['v_cmp_neq_f32 vcc, 0, v%d' % LSUM, 'v_cndmask_b32 v%d, 0, v%d, vcc' % (X0, X0)] if self.var else []) + [
+                  'v_add_f32 v%d, v%d, v%d' % (X1, MRUN, X1) if self.inplace else 'v_fma_f32 v%d, v%d, %%[sc], v%d' % (X1, MRUN, X1),
                   'v_mul_f32 v%d, 0x3f317218, v%d' % (X1, X1),
-                  's_mov_b64 s[%d:%d], exec' % (S_EXEC, S_EXEC + 1),
-                  # one lane per live row writes lse
-                  'v_and_b32 v%d, 2, %%[rok]' % MAXT, 'v_cmp_ne_u32 vcc, 0, v%d' % MAXT, 's_and_b64 exec, exec, vcc',
+                  's_mov_b64 s[%d:%d], exec' % (S_EXEC, S_EXEC + 1)] + (
+                  # one lane per live row writes lse: bit 1 of %[rok]; the bias / window variant has no register for
+                  # that operand and finds the lanes itself: lane < 32 and position of row 32 wave + lane % 32 < n_pos
+                  ['v_mbcnt_lo_u32_b32 v%d, -1, 0' % (T + 15), 'v_mbcnt_hi_u32_b32 v%d, -1, v%d' % (T + 15, T + 15),
+                   'v_and_b32 v%d, 31, v%d' % (T + 14, T + 15)] + self.wave_shift(S_TMP, 'lshl', 5) + [
+                   'v_add_u32 v%d, s%d, v%d' % (T + 14, S_TMP, T + 14), 'v_lshrrev_b32 v%d, %%[gl], v%d' % (T + 14, T + 14),
+                   'v_cmp_gt_i32 vcc, %s, v%d' % (self.np, T + 14), 's_and_b64 exec, exec, vcc',
+                   'v_cmp_gt_u32 vcc, 32, v%d' % (T + 15), 's_and_b64 exec, exec, vcc'] if self.var else
+                  ['v_and_b32 v%d, 2, %%[rok]' % self.maxt, 'v_cmp_ne_u32 vcc, 0, v%d' % self.maxt, 's_and_b64 exec, exec, vcc']) + [
                   'v_lshrrev_b32 v%d, 9, %%[ooff]' % T, 'v_lshlrev_b32 v%d, 2, v%d' % (T, T),
                   'global_store_dword v%d, v%d, %%[lb] nt' % (T, X1), 's_mov_b64 exec, s[%d:%d]' % (S_EXEC, S_EXEC + 1)]:
             e.raw(o)
@@ -644,10 +716,10 @@ class Gen:
             R, P, B = T + 2, T + 3, T + 4
             for o in ['v_add_u32 v%d, %d, v%d' % (R, 4 * k, ROW0), 'v_lshrrev_b32 v%d, %%[gl], v%d' % (P, R),
                       'v_lshlrev_b32 v%d, %%[gl], v%d' % (B, P), 'v_sub_u32 v%d, v%d, v%d' % (B, R, B),
-                      'v_mad_u32_u24 v%d, v%d, %%[hq], v%d' % (B, P, B), 'v_add_u32 v%d, %%[rb], v%d' % (B, B),
+                      'v_mad_u32_u24 v%d, v%d, %s, v%d' % (B, P, self.hq, B), 'v_add_u32 v%d, %%[rb], v%d' % (B, B),
                       'v_lshlrev_b32 v%d, 9, v%d' % (B, B), 'v_add_u32 v%d, v%d, %%[l16]' % (OFF + k, B),
                       'v_lshrrev_b32 v%d, 1, v%d' % (COFF + k, OFF + k),
-                      'v_cmp_gt_i32 s[%d:%d], %%[np], v%d' % (masks[k], masks[k] + 1, P)]:
+                      'v_cmp_gt_i32 s[%d:%d], %s, v%d' % (masks[k], masks[k] + 1, self.np, P)]:
                 e.raw(o)
         cvt = 'v_cvt_pk_bf16_f32' if self.bf else 'v_cvt_pk_f16_f32'
         for h in range(2):
@@ -712,8 +784,9 @@ if __name__ == '__main__':
     out_dir = sys.argv[1] if len(sys.argv) > 1 else os.path.join(here, '..')
     for bf, cap, contig, name in ((True, False, False, 'bf16'), (False, False, False, 'f16'), (True, True, False, 'bf16_cap'),
                                   (False, True, False, 'f16_cap'), (True, False, True, 'bf16_contig'),
-                                  (False, False, True, 'f16_contig')):
-        lines = Gen(bf, cap, contig).program()
+                                  (False, False, True, 'f16_contig'), (True, False, False, 'bf16_var'),
+                                  (False, False, False, 'f16_var')):
+        lines = Gen(bf, cap, contig, var=name.endswith('_var')).program()
         write(os.path.join(out_dir, 'append_loop_%s.inc' % name), lines, name)
         n_mfma = sum(1 for l in lines if l.startswith('v_mfma'))
         print('%s: %d lines, %d matrix instructions, %d waits' % (name, len(lines), n_mfma, sum(1 for l in lines if l.startswith('s_waitcnt'))))

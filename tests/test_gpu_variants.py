@@ -117,6 +117,30 @@ def test_soft_cap_inside_the_scheduled_append_loop(dtype, g):
     check(b, "append loop, soft cap, split chunks", mode="append", num_ctas=2 * 16, min_chunk=128, logits_soft_cap=4.0)
 
 
+@pytest.mark.parametrize("dtype", [workloads.BF16, workloads.F16])
+@pytest.mark.parametrize("g", [1, 4, 16])
+def test_bias_and_window_inside_the_scheduled_append_loop(dtype, g):
+    """ALiBi and the sliding window (without the soft cap) have a variant of the append kernel's scheduled loop too:
+    one CTA per kv head walks items of both paths; steep and flat slopes with large logits (the reference is raised
+    on the biased values); windows that hide whole steps, whole tiles and, in split tiles, whole chunks from some
+    rows (their partial state is the empty one) or from every row of a wavefront; windows wider than the context;
+    with and without the window in the plan."""
+    qo = [64, 3, 64, 130, 1, 64, 40, 64, 64, 7, 200]
+    kv = [300, 50, 128, 700, 100, 129, 140, 64, 191, 400, 260]
+    one_cta = dict(mode="append", num_ctas=2, min_chunk=1024)
+    for scale in (3.0, 1.0):
+        b = workloads.make_batch("varloop", 470 + g, dtype, 2 * g, 2, 128, 16, qo, kv, True, value_scale=scale)
+        check(b, f"append loop, alibi, value scale {scale}", alibi_slopes=slopes(2 * g), **one_cta)
+        check(b, f"append loop, steep alibi, value scale {scale}", alibi_slopes=8.0 * slopes(2 * g), **one_cta)
+    for W in (0, 7, 40, 64, 150, 100000):
+        check(b, f"append loop, window {W}", window_left=W, **one_cta)
+    check(b, "append loop, alibi + window", alibi_slopes=slopes(2 * g), window_left=90, **one_cta)
+    for W in (10, 130):
+        check(b, f"append loop, window {W}, split chunks", mode="append", num_ctas=2 * 16, min_chunk=128, window_left=W)
+        check(b, f"append loop, planned window {W}, alibi", mode="append", num_ctas=2 * 8, min_chunk=128, plan_window=W + 1,
+              window_left=W, alibi_slopes=slopes(2 * g))
+
+
 @pytest.mark.parametrize("mode", ["decode", "append"])
 def test_window_known_to_the_planner(mode):
     """fi_config.plan_window: the keys before a tile's window are not in its work items at all (chunks start in
