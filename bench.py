@@ -253,8 +253,8 @@ def main() -> int:
                     help="fp8: K/V stored as E4M3 codes with scales (App. F), decode workloads c2 and c4 only")
     ap.add_argument("--page-size", type=int, default=16, help="tokens per page (c2 and c3; 16 is the tuned size)")
     ap.add_argument("--rope-theta", type=float, default=0.0,
-                    help="> 0: decode with the rotary embedding fused into the kernel (fi_run_variant; the cache holds "
-                         "unrotated keys, Sec. 4.3); 16-bit decode workloads only")
+                    help="> 0: the rotary embedding fused into the kernel (fi_run_variant; the cache holds unrotated keys, "
+                         "Sec. 4.3); 16-bit decode and causal append workloads")
     ap.add_argument("--soft-cap", type=float, default=0.0,
                     help="> 0: logits soft cap c * tanh(s / c) (fi_run_variant, Sec. 3.2.3); 16-bit decode and causal append workloads")
     ap.add_argument("--alibi", action="store_true",
@@ -376,9 +376,9 @@ def run_workload(args):
         run_kw["o_cast"] = torch.empty((nnz, batch.num_qo_heads, batch.head_dim), dtype=dev.q.dtype, device=dev.device)
         o = False
     if args.rope_theta > 0 or args.window_left >= 0 or args.soft_cap > 0 or args.alibi:
-        if batch.kv_dtype or args.page_size != 16 or (mode != "decode" and (args.rope_theta > 0 or not batch.causal)):
-            print("bench.py: --rope-theta is for the 16-bit decode workloads with page size 16, --window-left, --alibi and "
-                  "--soft-cap for those and the causal append workloads", file=sys.stderr)
+        if batch.kv_dtype or args.page_size != 16 or (mode != "decode" and not batch.causal):
+            print("bench.py: --rope-theta, --window-left, --alibi and --soft-cap are for the 16-bit decode workloads with "
+                  "page size 16 and the causal append workloads", file=sys.stderr)
             return 2
         run_kw["variant"] = dict(
             kv_indptr=torch.from_numpy(np.ascontiguousarray(batch.kv_indptr, dtype=np.int32)).to(dev.device),

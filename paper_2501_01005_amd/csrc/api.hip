@@ -328,8 +328,6 @@ int32_t run_impl(fi_handle* h, const void* q, const void* k_pool, const void* v_
       return set_error(FI_ERR_UNSUPPORTED, "fi_run_variant: built for page_size 16");
     if (h->cfg.mode != FI_MODE_DECODE && !h->pp_causal_last)
       return set_error(FI_ERR_UNSUPPORTED, "fi_run_variant: in append mode the batch must be planned with causal = 1");
-    if (h->cfg.mode != FI_MODE_DECODE && variant->rope_theta > 0.f)
-      return set_error(FI_ERR_UNSUPPORTED, "fi_run_variant: the fused rotary embedding is built for decode mode only");
     if (!kv_indptr_dev || !last_page_len_dev) return set_error(FI_ERR_INVALID_ARG, "fi_run_variant: null pointer");
     if (!(variant->logits_soft_cap >= 0.f) || variant->window_left < -1)
       return set_error(FI_ERR_INVALID_ARG, "fi_run_variant: logits_soft_cap must be >= 0 and window_left >= -1");
@@ -425,7 +423,7 @@ int32_t run_impl(fi_handle* h, const void* q, const void* k_pool, const void* v_
   }
   e = h->cfg.mode == FI_MODE_DECODE   ? launch_decode(p, bf, kv8, variant != nullptr, with_rope ? &rope : nullptr, s)
       : h->cfg.mode == FI_MODE_TILE16 ? launch_tiles(p, bf, s)
-                                      : launch_append(p, bf, variant != nullptr, s);
+                                      : launch_append(p, bf, variant != nullptr, with_rope ? &rope : nullptr, s);
   if (e != hipSuccess) return hip_error("fi_run: attention launch", e);
   if (h->ev_after && (e = hipEventRecord(h->ev_after, s)) != hipSuccess) return hip_error("fi_run: hipEventRecord", e);
 

@@ -297,6 +297,55 @@ __device__ __forceinline__ void run_scheduled_loop(int n_full, int n_tiles, int 
 // path over the first two).
 __shared__ __attribute__((aligned(16))) uint8_t lds_raw[kLdsBytes];
 
+// Frequency tables of the rotary embedding (see RopeTable), one entry per pair of components, copied from the
+// kernel's arguments at the start of the launch that rotates.
+__shared__ __attribute__((aligned(16))) float rope_tab_lds[128];
+
+// The second K tile of the rotary variant: the remainders of the rotated keys (the rotated keys enter the first
+// product as head + remainder in the input type).  Buffer 0 behind the general path's two K buffers, buffer 1 in
+// the third V buffer, which only the scheduled loop uses.
+constexpr int kLdsKLo0 = 2 * kTileKv * kRowElems * 2;
+constexpr int kLdsKLo1 = kLdsVOffset + 2 * kTileKv * kRowElemsV * 2;
+static_assert(kLdsKLo0 + kTileKv * kRowElems * 2 <= kLdsVOffset && kLdsKLo1 + kTileKv * kRowElems * 2 <= kLdsBytes,
+              "the remainder tiles fit into the gaps of the LDS map");
+
+template <bool BF>
+__device__ __forceinline__ float elem16(uint32_t word, int odd) {
+  if constexpr (BF) {
+    return __builtin_bit_cast(float, odd ? (word & 0xffff0000u) : (word << 16));
+  } else {
+    const f16x2_t h = __builtin_bit_cast(f16x2_t, word);
+    return static_cast<float>(odd ? h[1] : h[0]);
+  }
+}
+
+// cosines and sines of the eight pairs (d0 + e, d0 + e + 64), e = 0..7, at position t: the angle of pair d is
+// t * rev[d] revolutions, reduced as fract(t1 * fract(256 rev[d]) + t0 * rev[d]) with t = 256 t1 + t0, so that large
+// positions keep their low bits
+__device__ __forceinline__ void rope_angles(int t, int d0, float* cs, float* sn) {
+  const float t1 = static_cast<float>(t >> 8), t0 = static_cast<float>(t & 255);
+  const f32x4_t* fr = reinterpret_cast<const f32x4_t*>(&rope_tab_lds[d0]);
+  const f32x4_t* gr = reinterpret_cast<const f32x4_t*>(&rope_tab_lds[64 + d0]);
+  const f32x4_t f0 = fr[0], f1 = fr[1], g0 = gr[0], g1 = gr[1];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    const float f = e < 4 ? f0[e & 3] : f1[e & 3], g = e < 4 ? g0[e & 3] : g1[e & 3];
+    const float rev = __builtin_amdgcn_fractf(t1 * g + t0 * f);
+    cs[e] = __builtin_amdgcn_cosf(rev);
+    sn[e] = __builtin_amdgcn_sinf(rev);
+  }
+}
+
+// v[e] (fp32) -> head in the input type and remainder v - head, also in the input type
+template <bool BF>
+__device__ __forceinline__ void split_head_remainder(const float* v, u32x4_t* head, u32x4_t* rem) {
+  *head = u32x4_t{pack_out<BF>(v[0], v[1]), pack_out<BF>(v[2], v[3]), pack_out<BF>(v[4], v[5]), pack_out<BF>(v[6], v[7])};
+  float r[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) r[e] = v[e] - elem16<BF>((*head)[e >> 1], e & 1);
+  *rem = u32x4_t{pack_out<BF>(r[0], r[1]), pack_out<BF>(r[2], r[3]), pack_out<BF>(r[4], r[5]), pack_out<BF>(r[6], r[7])};
+}
+
 // One work item on the generic path: any chunk length, any masking.  Kept out of line so that
 // its loop-invariant registers do not have to live across the scheduled loop in the caller.
 // Contains CTA barriers: every wavefront of the CTA calls it with the same item.
@@ -308,7 +357,14 @@ __shared__ __attribute__((aligned(16))) uint8_t lds_raw[kLdsBytes];
 // diagonal gives every row its absolute position pos = diag0 + (row's position in the tile).  On the scaled
 // logits, in this order: soft cap c * tanh(s / c), ALiBi bias slope[head] * (t - pos), sliding window (tokens
 // t < pos - window hidden).  A window only masks: the tiles it hides are still read.
-template <bool BF, bool VAR>
+//
+// ROPE (with VAR): rotary position embedding as query / key transform (Sec. 3.2.3; Sec. 4.3), pairing components
+// (d, d + 64): the queries are rotated by their positions when they are loaded, the keys by theirs on the way from
+// the staging registers into LDS (a thread holds one 8-wide block of a token and gets the partner block from lane
+// ^ 8), once per CTA.  Rotated values are formed in fp32 and enter the first product as head + remainder in the input
+// type (three matrix instructions per operand pair; a value rounded once costs 2^-9 (bf16) of relative accuracy per
+// operand, about 1.6e-3 rms on a logit of N(0,1) data, more than the tolerance of lse).  The cache holds unrotated keys.
+template <bool BF, bool VAR, bool ROPE = false>
 __device__ __attribute__((noinline)) void generic_work_item(uint64_t params_addr, int a_q_row0, int a_n_pos,
                                                             int a_kv_page0, int a_kv_start, int a_kv_len, int a_diag0,
                                                             int a_out_slot) {
@@ -380,6 +436,25 @@ __device__ __attribute__((noinline)) void generic_work_item(uint64_t params_addr
     } else {
 #pragma unroll
       for (int s = 0; s < 8; ++s) qreg[b][s] = u32x4_t{0u, 0u, 0u, 0u};
+    }
+  }
+  u32x4_t qlo[ROPE ? kRowBlocks : 1][8];  // remainders of the rotated queries
+  if constexpr (ROPE) {
+#pragma unroll
+    for (int b = 0; b < kRowBlocks; ++b) {
+#pragma unroll
+      for (int s = 0; s < 4; ++s) {  // blocks s and s + 4 hold the two components of pairs d = 16 s + 8 c .. + 8
+        float cs[8], sn[8], xr[8], yr[8];
+        rope_angles(diag0 + pos[b], 16 * s + 8 * c, cs, sn);  // the row's absolute position (causal plans only)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          const float xe = elem16<BF>(qreg[b][s][e >> 1], e & 1), ye = elem16<BF>(qreg[b][s + 4][e >> 1], e & 1);
+          xr[e] = xe * cs[e] - ye * sn[e];
+          yr[e] = ye * cs[e] + xe * sn[e];
+        }
+        split_head_remainder<BF>(xr, &qreg[b][s], &qlo[b][s]);
+        split_head_remainder<BF>(yr, &qreg[b][s + 4], &qlo[b][s + 4]);
+      }
     }
   }
   // wave-uniform bounds of lim per block (rows are position-major)
@@ -460,6 +535,29 @@ __device__ __attribute__((noinline)) void generic_work_item(uint64_t params_addr
       for (int r = 0; r < 2; ++r)
         if (kTileKv * t + 32 * r + st_tok >= kv_len) stage_v[SET][r] = u32x4_t{0u, 0u, 0u, 0u};  // must not reach P.V
     }
+    if constexpr (ROPE) {
+      uint16_t* dk_lo = reinterpret_cast<uint16_t*>(lds_raw + ((t & 1) ? kLdsKLo1 : kLdsKLo0));
+#pragma unroll
+      for (int r = 0; r < 2; ++r) {
+        // this thread holds components 8 (st_chunk % 8) .. + 8 of the token's first (st_chunk < 8) or second half;
+        // lane ^ 8 holds the other half of the same pairs
+        u32x4_t other;
+#pragma unroll
+        for (int wd = 0; wd < 4; ++wd) other[wd] = __shfl_xor(stage_k[SET][r][wd], 8);
+        float cs[8], sn[8], out[8];
+        rope_angles(kv_start + kTileKv * t + 32 * r + st_tok, 8 * (st_chunk & 7), cs, sn);
+        const bool second = st_chunk >= 8;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          const float mine = elem16<BF>(stage_k[SET][r][e >> 1], e & 1), oth = elem16<BF>(other[e >> 1], e & 1);
+          out[e] = second ? mine * cs[e] + oth * sn[e] : mine * cs[e] - oth * sn[e];
+        }
+        u32x4_t head, rem;
+        split_head_remainder<BF>(out, &head, &rem);
+        stage_k[SET][r] = head;
+        *reinterpret_cast<u32x4_t*>(&dk_lo[st_lds_k + 32 * r * kRowElems]) = rem;
+      }
+    }
 #pragma unroll
     for (int r = 0; r < 2; ++r) {
       *reinterpret_cast<u32x4_t*>(&dk[st_lds_k + 32 * r * kRowElems]) = stage_k[SET][r];
@@ -497,6 +595,20 @@ __device__ __attribute__((noinline)) void generic_work_item(uint64_t params_addr
         for (int r = 0; r < 16; ++r) sacc[b][r] = 0.f;
 #pragma unroll
         for (int s = 0; s < 8; ++s) sacc[b] = mfma_qk<BF>(ka[s], qreg[b][s], sacc[b]);
+      }
+      if constexpr (ROPE) {  // + remainder x head + head x remainder
+        const uint16_t* tk_lo = reinterpret_cast<const uint16_t*>(lds_raw + ((t & 1) ? kLdsKLo1 : kLdsKLo0));
+        const uint16_t* krow_lo = &tk_lo[(32 * u + n) * kRowElems + c * 8];
+        u32x4_t ka_lo[8];
+#pragma unroll
+        for (int s = 0; s < 8; ++s) ka_lo[s] = *reinterpret_cast<const u32x4_t*>(krow_lo + 16 * s);
+#pragma unroll
+        for (int b = 0; b < kRowBlocks; ++b)
+#pragma unroll
+          for (int s = 0; s < 8; ++s) {
+            sacc[b] = mfma_qk<BF>(ka_lo[s], qreg[b][s], sacc[b]);
+            sacc[b] = mfma_qk<BF>(ka[s], qlo[b][s], sacc[b]);
+          }
       }
       // lane (n, c) now holds S^T[token 8 (r / 4) + 4 c + r % 4][row n of block b], r = 0..15
 
@@ -676,12 +788,22 @@ __device__ __attribute__((noinline)) void generic_work_item(uint64_t params_addr
 // CONTIG: contiguous KV (kv_indices == null); the scheduled loop then computes its page ids.
 // VARLOOP (with VAR): the hooks in use are the ALiBi bias and / or the sliding window, without the soft cap: the
 // scheduled loop has a variant for them too.
-template <bool BF, bool VAR = false, bool CAPLOOP = false, bool CONTIG = false, bool VARLOOP = false>
+// ROPE (with VAR, no loop variant): every item on the general path, queries and keys rotated by their positions.
+struct NoRopeTable {};
+template <bool BF, bool VAR = false, bool CAPLOOP = false, bool CONTIG = false, bool VARLOOP = false, bool ROPE = false>
 __global__ void __launch_bounds__(kCtaThreads) __attribute__((amdgpu_waves_per_eu(2, 2)))
-append_kernel(const RunParams p) {
+append_kernel(const RunParams p, const typename std::conditional<ROPE, RopeTable, NoRopeTable>::type rope) {
   static_assert(!CONTIG || !VAR, "affine addressing is built for the plain kernel");
   static_assert(!(CAPLOOP && VARLOOP) && (!VARLOOP || VAR), "one variant of the loop per instantiation");
+  static_assert(!ROPE || (VAR && !CAPLOOP && !VARLOOP), "the rotary transform is built into the general path");
   const int tid = threadIdx.x;
+  if constexpr (ROPE) {
+    if (tid < 64) {
+      rope_tab_lds[tid] = rope.rev[tid];
+      rope_tab_lds[64 + tid] = rope.rev256[tid];
+    }
+    __syncthreads();
+  }
   // Workgroups are handed to the eight XCDs round-robin: with the kv head as the fast index all
   // CTAs of a kv head (which re-read the same K/V) share one XCD's L2 when num_kv_heads is 8.
   const int cta = static_cast<int>(blockIdx.x) / p.num_kv_heads;
@@ -793,8 +915,8 @@ append_kernel(const RunParams p) {
     prefetched = 0;
     __syncthreads();  // the previous work item is done with the tile buffers
     // (the kernel's only argument sits at the start of its argument segment)
-    generic_work_item<BF, VAR>(reinterpret_cast<uint64_t>(__builtin_amdgcn_kernarg_segment_ptr()), q_row0, n_pos, kv_page0,
-                          kv_start, kv_len, diag0, out_slot);
+    generic_work_item<BF, VAR, ROPE>(reinterpret_cast<uint64_t>(__builtin_amdgcn_kernarg_segment_ptr()), q_row0, n_pos,
+                                     kv_page0, kv_start, kv_len, diag0, out_slot);
     if (w + 1 < w_end) item.load(p, w + 1);
   }
 }
@@ -803,41 +925,48 @@ append_kernel(const RunParams p) {
 
 int append_tile_rows() { return (kCtaThreads / 64) * 32 * kRowBlocks; }
 
-hipError_t launch_append(const RunParams& p, bool is_bf16, bool variant, hipStream_t stream) {
+hipError_t launch_append(const RunParams& p, bool is_bf16, bool variant, const RopeTable* rope, hipStream_t stream) {
   const dim3 grid(static_cast<unsigned>(p.ctas_per_head) * static_cast<unsigned>(p.num_kv_heads), 1, 1);
   const dim3 block(kCtaThreads, 1, 1);
+  if (rope) {  // (variant launches only) every item on the general path, with the other hooks on top
+    if (is_bf16)
+      hipLaunchKernelGGL((append_kernel<true, true, false, false, false, true>), grid, block, 0, stream, p, *rope);
+    else
+      hipLaunchKernelGGL((append_kernel<false, true, false, false, false, true>), grid, block, 0, stream, p, *rope);
+    return hipGetLastError();
+  }
   if (variant && p.soft_cap > 0.f && p.alibi_slopes == nullptr && p.window_left < 0) {
     if (is_bf16)
-      hipLaunchKernelGGL((append_kernel<true, true, true>), grid, block, 0, stream, p);
+      hipLaunchKernelGGL((append_kernel<true, true, true>), grid, block, 0, stream, p, NoRopeTable{});
     else
-      hipLaunchKernelGGL((append_kernel<false, true, true>), grid, block, 0, stream, p);
+      hipLaunchKernelGGL((append_kernel<false, true, true>), grid, block, 0, stream, p, NoRopeTable{});
     return hipGetLastError();
   }
   if (variant && p.soft_cap == 0.f) {  // bias and / or window: their variant of the scheduled loop
     if (is_bf16)
-      hipLaunchKernelGGL((append_kernel<true, true, false, false, true>), grid, block, 0, stream, p);
+      hipLaunchKernelGGL((append_kernel<true, true, false, false, true>), grid, block, 0, stream, p, NoRopeTable{});
     else
-      hipLaunchKernelGGL((append_kernel<false, true, false, false, true>), grid, block, 0, stream, p);
+      hipLaunchKernelGGL((append_kernel<false, true, false, false, true>), grid, block, 0, stream, p, NoRopeTable{});
     return hipGetLastError();
   }
   if (variant) {  // the soft cap together with a bias or a window: every item on the general path
     if (is_bf16)
-      hipLaunchKernelGGL((append_kernel<true, true>), grid, block, 0, stream, p);
+      hipLaunchKernelGGL((append_kernel<true, true>), grid, block, 0, stream, p, NoRopeTable{});
     else
-      hipLaunchKernelGGL((append_kernel<false, true>), grid, block, 0, stream, p);
+      hipLaunchKernelGGL((append_kernel<false, true>), grid, block, 0, stream, p, NoRopeTable{});
     return hipGetLastError();
   }
   if (p.kv_indices == nullptr) {  // contiguous KV (the caller has refused variants)
     if (is_bf16)
-      hipLaunchKernelGGL((append_kernel<true, false, false, true>), grid, block, 0, stream, p);
+      hipLaunchKernelGGL((append_kernel<true, false, false, true>), grid, block, 0, stream, p, NoRopeTable{});
     else
-      hipLaunchKernelGGL((append_kernel<false, false, false, true>), grid, block, 0, stream, p);
+      hipLaunchKernelGGL((append_kernel<false, false, false, true>), grid, block, 0, stream, p, NoRopeTable{});
     return hipGetLastError();
   }
   if (is_bf16)
-    hipLaunchKernelGGL(append_kernel<true>, grid, block, 0, stream, p);
+    hipLaunchKernelGGL((append_kernel<true>), grid, block, 0, stream, p, NoRopeTable{});
   else
-    hipLaunchKernelGGL(append_kernel<false>, grid, block, 0, stream, p);
+    hipLaunchKernelGGL((append_kernel<false>), grid, block, 0, stream, p, NoRopeTable{});
   return hipGetLastError();
 }
 

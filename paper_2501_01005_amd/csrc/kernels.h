@@ -93,7 +93,8 @@ hipError_t launch_tiles(const RunParams& p, bool is_bf16, hipStream_t stream);
 // append.hip: query tile = append_tile_rows()/g positions x g fused heads, 8 wavefronts per CTA.
 // variant: the logits hooks of RunParams are applied (causal batches only; with ALiBi or a window every item takes
 // the generic path, the soft cap alone has a variant of the scheduled loop).
-hipError_t launch_append(const RunParams& p, bool is_bf16, bool variant, hipStream_t stream);
+// rope != null (variant launches only): queries and keys are rotated by their positions first (general path).
+hipError_t launch_append(const RunParams& p, bool is_bf16, bool variant, const RopeTable* rope, hipStream_t stream);
 int append_tile_rows();  // fused rows (positions x group) of one append query tile
 // upload.hip: staging (device view of page-locked host memory) -> plan section
 hipError_t launch_plan_upload(const int32_t* staging_dev_view, int32_t* plan_section, int32_t n_ints,

@@ -141,6 +141,27 @@ def test_bias_and_window_inside_the_scheduled_append_loop(dtype, g):
               window_left=W, alibi_slopes=slopes(2 * g))
 
 
+@pytest.mark.parametrize("dtype", [workloads.BF16, workloads.F16])
+@pytest.mark.parametrize("g", [1, 4])
+def test_fused_rotary_embedding_in_causal_append(dtype, g):
+    """Append / prefill with the rotary embedding fused in (Sec. 3.2.3 query / key transform; Sec. 4.3): query j is
+    rotated by its position l_kv - l_qo + j, key t by t, the cache holds unrotated keys.  Prefixes of several tiles,
+    split chunks (a chunk's first key is not key 0), partial tiles, a request with more queries than keys, a position
+    divisor, the other hooks on top, large values (peaked rows are where a rotated operand rounded once would miss
+    the tolerance), positions beyond 65536."""
+    qo = [70, 9, 130, 1, 64, 40]
+    kv = [400, 9, 260, 300, 64, 25]
+    b = workloads.make_batch("approp", 480 + g, dtype, 2 * g, 2, 128, 16, qo, kv, True, value_scale=2.0)
+    kw = dict(mode="append", num_ctas=2 * 4, min_chunk=1024)
+    check(b, "append, rope", rope_theta=1e4, **kw)
+    check(b, "append, rope, split chunks", rope_theta=1e4, mode="append", num_ctas=2 * 16, min_chunk=64)
+    check(b, "append, rope, other base and divisor", rope_theta=5e5, rope_scale=4.0, **kw)
+    check(b, "append, rope + cap + window + alibi", rope_theta=1e4, logits_soft_cap=4.0, window_left=100,
+          alibi_slopes=slopes(2 * g), **kw)
+    far = workloads.make_batch("far", 485, dtype, 2 * g, 2, 128, 16, [40], [70000], True, poison=False)
+    check(far, "append, rope at positions up to 70000", rope_theta=1e4, mode="append", num_ctas=2 * 64, min_chunk=256)
+
+
 @pytest.mark.parametrize("mode", ["decode", "append"])
 def test_window_known_to_the_planner(mode):
     """fi_config.plan_window: the keys before a tile's window are not in its work items at all (chunks start in
@@ -166,9 +187,9 @@ def test_refused_where_not_built():
     dummy = np.zeros(64, dtype=np.uint8)
     ok = dict(dtype=fi.FI_DTYPE_BF16, num_qo_heads=8, num_kv_heads=2, head_dim=128, page_size=16, mode=fi.FI_MODE_DECODE,
               num_ctas=8, max_batch=4, max_qo_tiles=4)
-    # other page sizes; append mode without a causal plan; the rotary embedding in append mode
+    # other page sizes; append mode without a causal plan (also for the rotary embedding)
     for bad, var in (({"page_size": 8}, dict(window_left=3)), ({"mode": fi.FI_MODE_APPEND}, dict(window_left=3)),
-                     ({"mode": fi.FI_MODE_APPEND, "causal_plan": True}, dict(rope_theta=1e4))):
+                     ({"mode": fi.FI_MODE_APPEND}, dict(rope_theta=1e4))):
         causal_plan = bad.pop("causal_plan", False)
         h = fi.fi_create(**{**ok, **bad})
         if causal_plan:
