@@ -134,7 +134,7 @@ def bench_shared_prefix(args) -> int:
     side = torch.cuda.Stream() if args.graph and args.c5_path != "formats" else None  # default priority
     # both formats as one plan of one handle (fi_plan_formats): one attention launch + one contraction launch
     formats, ids = formats_of([c.prefix, c.suffix])
-    wf = make_formats_wrapper([c.prefix, c.suffix], num_ctas=args.num_ctas, min_chunk=args.min_chunk)
+    wf = make_formats_wrapper([c.prefix, c.suffix], mode=args.tile_mode, num_ctas=args.num_ctas, min_chunk=args.min_chunk)
     ids_dev = torch.from_numpy(ids).to("cuda:0")
 
     def composed(plan=True):
@@ -202,7 +202,8 @@ def bench_shared_prefix(args) -> int:
         "config": {"workload": "c5_shared_prefix" + ("_small" if args.small else ""), "requests": n,
                    "prefix_tokens": int(c.prefix.kv_lens()[0]),
                    "step": (("one captured graph, replayed: " if args.graph else "") +
-                            {"formats": "both formats in one plan: 1 attention launch + 1 contraction launch (fi_plan_formats, fi_run)",
+                            {"formats": "both formats in one plan: 1 attention launch + 1 contraction launch (fi_plan_formats, fi_run; "
+                                        + args.tile_mode + ")",
                              "composed": "2 attention launches + 1 contraction launch (fi_run_composed)",
                              "separate": "2 attention launches + 3 merge launches"}[args.c5_path] +
                             ("" if args.no_plan else ", planned every step"))},
@@ -274,6 +275,9 @@ def main() -> int:
                     help="fi_config.merge: 1 = partial states folded by a second launch, 2 = inside the attention launch "
                          "(decode), 0 = default")
     ap.add_argument("--suffix-min-chunk", type=int, default=0, help="c5: fi_config.min_chunk of the suffix (decode) handle")
+    ap.add_argument("--tile-mode", default="tile16", choices=["tile16", "tile64"],
+                    help="c5 with --c5-path formats: the handle's query tile: 16 fused rows, one wavefront per CTA, or 64 "
+                         "fused rows, four wavefronts per CTA that share the K/V rows of a wide tile through LDS")
     ap.add_argument("--c5-path", default="formats", choices=["formats", "composed", "separate"],
                     help="c5: formats = both formats planned as one work list on one 16-row-tile handle (fi_plan_formats; one "
                          "attention launch + one contraction launch); composed = a handle per format, fi_run_composed (two "

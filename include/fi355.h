@@ -60,6 +60,14 @@ extern "C" {
                             appends (causal or not), and several formats over the same query rows planned and
                             run as ONE work list and ONE attention launch (fi_plan_formats, Sec. 3.1.2).
                             16-bit pools, page_size 16, no variants                                  */
+#define FI_MODE_TILE64 3 /* query tile = 64/g positions x g fused heads, CTAs of four wavefronts (Sec. 3.2.2: the
+                            tile size follows the query lengths): a tile of more than 16 fused rows gives each
+                            wavefront 16 of them and the four share every K/V row through LDS (a block of queries
+                            over a shared prefix, Sec. 3.1.2, re-reads it 4x less often than in FI_MODE_TILE16);
+                            a tile of at most 16 rows (a decode step) has its chunk walked by the four wavefronts
+                            side by side and their states merged in the CTA.  The planner counts such a light
+                            tile's tokens at 30 percent, in the work items' costs and in the sum that sets the
+                            chunk length.  Same uses and limits as FI_MODE_TILE16, g in {1, 2, 4, 8, 16}          */
 
 typedef struct fi_handle fi_handle;
 typedef void* fi_stream; /* a hipStream_t (0 = the null stream) */
@@ -152,7 +160,7 @@ typedef struct fi_plan_arrays {
 } fi_plan_arrays;
 
 /* Create / destroy a handle.  cfg HOST.  FI_ERR_UNSUPPORTED unless head_dim = 128,
- * page_size a power of two in 1..64 (16 in FI_MODE_TILE16), g in {1,2,4,8,16}.  With num_ctas = 0 the
+ * page_size a power of two in 1..64 (16 in FI_MODE_TILE16 and FI_MODE_TILE64), g in {1,2,4,8,16}.  With num_ctas = 0 the
  * current HIP device is queried (FI_ERR_HIP without one). */
 int32_t fi_create(const fi_config* cfg, fi_handle** out);
 int32_t fi_destroy(fi_handle* h);
@@ -186,7 +194,7 @@ int32_t fi_plan(fi_handle* h, const int32_t* qo_indptr, const int32_t* kv_indptr
  * DEVICE array).  Every qo_indptr[f] must end at the same row count.  Algorithm 1 runs over the query tiles of all
  * formats at once: one chunk size, one set of queues, hence one persistent attention launch in fi_run, followed
  * by one contraction launch in which every query row folds its partial states (formats in the given order,
- * chunks in ascending KV order, Sec. 2.2).  Not causal.  Handle: FI_MODE_TILE16 (FI_ERR_UNSUPPORTED otherwise).
+ * chunks in ascending KV order, Sec. 2.2).  Not causal.  Handle: FI_MODE_TILE16 or FI_MODE_TILE64 (FI_ERR_UNSUPPORTED otherwise).
  * With n_formats = 1 this is fi_plan with causal = 0.  Other arguments, staging and errors as fi_plan. */
 int32_t fi_plan_formats(fi_handle* h, int32_t n_formats, const int32_t* const* qo_indptr,
                         const int32_t* const* kv_indptr, const int32_t* const* last_page_len,

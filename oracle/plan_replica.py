@@ -50,7 +50,10 @@ all (other CTA, item of the loaded CTA, optional cheaper partner item of the oth
 CTA) candidates in that nesting order take the first one that gives the smallest new
 maximum of the two loads, if it is below the current maximum; move (or swap) it;
 stop when there is none.  Moved items go to the end of a queue; at the end every
-queue is ordered by (-length, w) again.
+queue is ordered by (-length, w) again.  ``weighted_lkv=True`` (with the refinement):
+in the sum S of the L_kv formula a light tile's KV range counts ``light_pct`` percent
+as well (rounded up, tile by tile), so that loads in cost units come out equal when
+light and full tiles are planned together.
 """
 from __future__ import annotations
 
@@ -96,7 +99,7 @@ def _plan(requests, *, composed: bool, n_rows: int = 0, page_size: int, t_pos: i
           alpha: int = 1, beta: int = 1, min_chunk: int | None = None,
           literal_lkv: bool = False, refine: bool = False, light_rows: int = 0,
           light_pct: int = 100, kv_quantum: int = 1, plan_window: int = 0,
-          item_cost: int = 0) -> Dict[str, object]:
+          item_cost: int = 0, weighted_lkv: bool = False) -> Dict[str, object]:
     B = len(requests)
     if min_chunk is None:
         min_chunk = page_size
@@ -131,7 +134,10 @@ def _plan(requests, *, composed: bool, n_rows: int = 0, page_size: int, t_pos: i
                 kv_begin = max(0, l_kv[i] - l_qo[i] + start - (plan_window - 1))
                 kv_begin = min(kv_begin, kv_eff) // page_size * page_size
             tiles.append((i, start, end - start, kv_eff, diag0, kv_begin))
-            S += l_kv[i] if literal_lkv else kv_eff - kv_begin
+            counted = l_kv[i] if literal_lkv else kv_eff - kv_begin
+            if weighted_lkv and refine and light_rows > 0 and (end - start) * group <= light_rows:
+                counted = -(-counted * light_pct // 100)   # a light tile counts light_pct percent, rounded up
+            S += counted
 
     # -- maximum chunk size --------------------------------------------------
     L_kv = -(-S // num_ctas)

@@ -11,7 +11,7 @@ import numpy as np
 
 __all__ = [
     "FI_OK", "FI_ERR_INVALID_ARG", "FI_ERR_UNSUPPORTED", "FI_ERR_WORKSPACE_TOO_SMALL", "FI_ERR_NOT_PLANNED",
-    "FI_ERR_HIP", "FI_ERR_HOST_MEMORY", "FI_DTYPE_F16", "FI_DTYPE_BF16", "FI_MODE_DECODE", "FI_MODE_APPEND", "FI_MODE_TILE16",
+    "FI_ERR_HIP", "FI_ERR_HOST_MEMORY", "FI_DTYPE_F16", "FI_DTYPE_BF16", "FI_MODE_DECODE", "FI_MODE_APPEND", "FI_MODE_TILE16", "FI_MODE_TILE64",
     "Fi355Error", "fi_config", "fi_plan_arrays", "lib", "library_path",
     "fi_create", "fi_destroy", "fi_workspace_bytes", "fi_plan", "fi_plan_formats", "fi_plan_view", "fi_run", "fi_run_kv8",
     "fi_run_variant", "fi_run_composed", "fi_run_composed_static", "fi_variant", "fi_merge_states", "fi_merge_state_pair", "fi_check_indices", "fi_set_timing_events", "fi_last_error",
@@ -30,6 +30,7 @@ FI_DTYPE_BF16 = 1
 FI_MODE_DECODE = 0
 FI_MODE_APPEND = 1
 FI_MODE_TILE16 = 2
+FI_MODE_TILE64 = 3
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 
@@ -290,7 +291,7 @@ class PagedAttention:
             self.handle = fi_create(
                 dtype={"f16": FI_DTYPE_F16, "bf16": FI_DTYPE_BF16}[dtype], num_qo_heads=num_qo_heads,
                 num_kv_heads=num_kv_heads, head_dim=head_dim, page_size=page_size,
-                mode={"decode": FI_MODE_DECODE, "append": FI_MODE_APPEND, "tile16": FI_MODE_TILE16}[mode], num_ctas=num_ctas,
+                mode={"decode": FI_MODE_DECODE, "append": FI_MODE_APPEND, "tile16": FI_MODE_TILE16, "tile64": FI_MODE_TILE64}[mode], num_ctas=num_ctas,
                 max_batch=max_batch, max_qo_tiles=max_qo_tiles if max_qo_tiles is not None else max_batch,
                 alpha=alpha, beta=beta, min_chunk=min_chunk, literal_lkv=1 if literal_lkv else 0, balance=balance,
                 merge=merge, plan_window=plan_window)

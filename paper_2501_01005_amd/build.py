@@ -13,7 +13,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB_DIR = os.path.join(HERE, "lib")
 LIB_PATH = os.path.join(LIB_DIR, "libfi355.so")
-SOURCES = ["plan.cpp", "api.hip", "decode.hip", "tile.hip", "append.hip", "merge.hip", "upload.hip"]
+SOURCES = ["plan.cpp", "api.hip", "decode.hip", "tile.hip", "tile64.hip", "append.hip", "merge.hip", "upload.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 
 DEVICE_FLAGS = ["--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]

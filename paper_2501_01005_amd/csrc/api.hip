@@ -103,7 +103,8 @@ int32_t fi_create(const fi_config* cfg, fi_handle** out) {
   *out = nullptr;
   if (cfg->dtype != FI_DTYPE_F16 && cfg->dtype != FI_DTYPE_BF16)
     return set_error(FI_ERR_INVALID_ARG, "fi_create: dtype must be FI_DTYPE_F16 or FI_DTYPE_BF16");
-  if (cfg->mode != FI_MODE_DECODE && cfg->mode != FI_MODE_APPEND && cfg->mode != FI_MODE_TILE16)
+  if (cfg->mode != FI_MODE_DECODE && cfg->mode != FI_MODE_APPEND && cfg->mode != FI_MODE_TILE16 &&
+      cfg->mode != FI_MODE_TILE64)
     return set_error(FI_ERR_INVALID_ARG, "fi_create: unknown mode");
   if (cfg->num_qo_heads <= 0 || cfg->num_kv_heads <= 0 || cfg->num_qo_heads % cfg->num_kv_heads != 0)
     return set_error(FI_ERR_INVALID_ARG, "fi_create: num_qo_heads must be a positive multiple of num_kv_heads");
@@ -127,9 +128,9 @@ int32_t fi_create(const fi_config* cfg, fi_handle** out) {
     return set_error(FI_ERR_UNSUPPORTED, "fi_create: the contraction inside the attention launch is built for group size 1, 2, 4");
   if (cfg->mode == FI_MODE_APPEND && !(g == 1 || g == 2 || g == 4 || g == 8 || g == 16))
     return set_error(FI_ERR_UNSUPPORTED, "fi_create: append mode is built for group size 1, 2, 4, 8, 16");
-  const bool small_tiles = cfg->mode == FI_MODE_TILE16;
+  const bool small_tiles = cfg->mode == FI_MODE_TILE16 || cfg->mode == FI_MODE_TILE64;
   if (small_tiles && (!(g == 1 || g == 2 || g == 4 || g == 8 || g == 16) || cfg->page_size != kPageSize || cfg->plan_window > 0))
-    return set_error(FI_ERR_UNSUPPORTED, "fi_create: the 16-row tile mode is built for group size 1, 2, 4, 8, 16, page_size 16, "
+    return set_error(FI_ERR_UNSUPPORTED, "fi_create: the 16-row and 64-row tile modes are built for group size 1, 2, 4, 8, 16, page_size 16, "
                                          "no planned window");
 
   int num_ctas = cfg->num_ctas;
@@ -141,7 +142,8 @@ int32_t fi_create(const fi_config* cfg, fi_handle** out) {
     e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
     if (e != hipSuccess) return hip_error("fi_create: hipDeviceGetAttribute", e);
     // decode: one wavefront per CTA, 8 resident per CU; append: one 8-wavefront CTA per CU
-    num_ctas = cfg->mode == FI_MODE_APPEND ? cus : 8 * cus;
+    // (64-row tiles: two CTAs of four wavefronts per CU)
+    num_ctas = cfg->mode == FI_MODE_APPEND ? cus : cfg->mode == FI_MODE_TILE64 ? 2 * cus : 8 * cus;
   }
   fi_handle* h = new (std::nothrow) fi_handle();
   if (!h) return set_error(FI_ERR_HOST_MEMORY, "fi_create: out of host memory");
@@ -150,30 +152,42 @@ int32_t fi_create(const fi_config* cfg, fi_handle** out) {
   PlanParams& pp = h->pp;
   pp.page_size = cfg->page_size;
   pp.group = g;
-  pp.t_pos = cfg->mode == FI_MODE_DECODE ? 1 : cfg->mode == FI_MODE_TILE16 ? 16 / g : append_tile_rows() / g;
+  pp.t_pos = cfg->mode == FI_MODE_DECODE   ? 1
+              : cfg->mode == FI_MODE_TILE16 ? 16 / g
+              : cfg->mode == FI_MODE_TILE64 ? 64 / g
+                                            : append_tile_rows() / g;
   pp.ctas_per_head = num_ctas / cfg->num_kv_heads > 0 ? num_ctas / cfg->num_kv_heads : 1;
   // Decode items are short and many: the greedy pass of Algorithm 1 balances them to about 1 %.  Append
   // items are few and long (C3: 4.8 per CTA): there the refined assignment is the default, with the cost
   // measured on this kernel: 19 800 cycles per item + 48 per token, 64 % of that per token for a tile of at most
   // 128 fused rows (at most one live wavefront per SIMD), i.e. alpha : beta = 8 : 5 with T_q = 256.
   pp.plan_window = cfg->plan_window;
-  pp.refine = cfg->balance == 2 || (cfg->balance == 0 && cfg->mode == FI_MODE_APPEND);
+  const bool tile64 = cfg->mode == FI_MODE_TILE64;
+  pp.refine = cfg->balance == 2 || (cfg->balance == 0 && (cfg->mode == FI_MODE_APPEND || tile64));
   // decode: a work item costs a wavefront about as much as 64 more tokens before its first tile arrives
-  pp.item_cost = (cfg->balance == 0 && cfg->mode != FI_MODE_APPEND) ? 64 : 0;
+  pp.item_cost = (cfg->balance == 0 && cfg->mode != FI_MODE_APPEND && !tile64) ? 64 : 0;
   const bool default_cost = cfg->alpha == 0 && cfg->beta == 0;
   pp.alpha = default_cost ? (pp.refine && cfg->mode == FI_MODE_APPEND ? 8 : 1) : cfg->alpha;
   pp.beta = default_cost ? (pp.refine && cfg->mode == FI_MODE_APPEND ? 5 : 1) : cfg->beta;
   pp.light_rows = (pp.refine && cfg->mode == FI_MODE_APPEND) ? append_tile_rows() / 2 : 0;
   pp.light_pct = 64;
   pp.kv_quantum = (pp.refine && cfg->mode == FI_MODE_APPEND) ? 64 : 1;  // the append kernel's KV tile
+  // 64-row tiles: a tile of at most 16 fused rows has its chunk walked by the CTA's four wavefronts side by side
+  // (30 percent of a full tile's time per token, measured); its tokens count that much in the chunk length too
+  if (pp.refine && tile64) {
+    pp.light_rows = 16;
+    pp.light_pct = 30;
+    pp.kv_quantum = 32;  // the kernel's step
+    pp.weighted_lkv = true;
+  }
   // default smallest chunk: append 256 tokens; decode one 32-token step of the kernel: with fewer tokens than that per CTA the chip is not filled, and a
   // wavefront that walks 128 tokens alone takes longer than four that walk 32 each plus their merge
-  pp.min_chunk = cfg->min_chunk > 0 ? cfg->min_chunk : (cfg->mode == FI_MODE_APPEND ? 256 : 32);
+  pp.min_chunk = cfg->min_chunk > 0 ? cfg->min_chunk : (cfg->mode == FI_MODE_APPEND ? 256 : tile64 ? 128 : 32);
   pp.literal_lkv = cfg->literal_lkv != 0;
   pp.max_batch = cfg->max_batch;
   pp.max_qo_tiles = cfg->max_qo_tiles;
   h->layout.init(pp.ctas_per_head, cfg->max_qo_tiles, pp.t_pos, cfg->num_qo_heads, cfg->num_kv_heads, cfg->head_dim,
-                 small_tiles);
+                 small_tiles, pp.weighted_lkv ? (100 + pp.light_pct - 1) / pp.light_pct : 1);
   h->host_plan.assign(h->layout.plan_ints, 0);
   *out = h;
   return FI_OK;
@@ -257,8 +271,8 @@ int32_t fi_plan_formats(fi_handle* h, int32_t n_formats, const int32_t* const* q
                         void* workspace_dev, size_t workspace_bytes, void* pinned_host, size_t pinned_bytes,
                         fi_stream stream) {
   if (!h) return set_error(FI_ERR_INVALID_ARG, "fi_plan_formats: null handle");
-  if (h->cfg.mode != FI_MODE_TILE16)
-    return set_error(FI_ERR_UNSUPPORTED, "fi_plan_formats: needs a handle in FI_MODE_TILE16 (one kernel runs the tiles of every format)");
+  if (h->cfg.mode != FI_MODE_TILE16 && h->cfg.mode != FI_MODE_TILE64)
+    return set_error(FI_ERR_UNSUPPORTED, "fi_plan_formats: needs a handle in FI_MODE_TILE16 or FI_MODE_TILE64 (one kernel runs the tiles of every format)");
   if (n_formats < 1 || n_formats > kMaxFormats)
     return set_error(FI_ERR_INVALID_ARG, "fi_plan_formats: n_formats must be between 1 and " + std::to_string(kMaxFormats));
   if (!qo_indptr || !kv_indptr || !last_page_len || !batch || !kv_indices_base)
@@ -322,8 +336,8 @@ int32_t run_impl(fi_handle* h, const void* q, const void* k_pool, const void* v_
   // deferred != null: the contraction launch is left to the caller, who gets its parameters
   if (!h) return set_error(FI_ERR_INVALID_ARG, "fi_run: null handle");
   if (variant) {
-    if (h->cfg.mode == FI_MODE_TILE16)
-      return set_error(FI_ERR_UNSUPPORTED, "fi_run_variant: not built for the 16-row tile mode");
+    if (h->cfg.mode == FI_MODE_TILE16 || h->cfg.mode == FI_MODE_TILE64)
+      return set_error(FI_ERR_UNSUPPORTED, "fi_run_variant: not built for the 16-row and 64-row tile modes");
     if (h->cfg.page_size != kPageSize)
       return set_error(FI_ERR_UNSUPPORTED, "fi_run_variant: built for page_size 16");
     if (h->cfg.mode != FI_MODE_DECODE && !h->pp_causal_last)
@@ -346,7 +360,7 @@ int32_t run_impl(fi_handle* h, const void* q, const void* k_pool, const void* v_
     return set_error(FI_ERR_INVALID_ARG, "fi_run_kv8: k_scale and v_scale must be > 0");
   if (!h->planned_dev) return set_error(FI_ERR_NOT_PLANNED, "fi_run: call fi_plan with a device workspace first");
   if (!q || !k_pool || !v_pool || !kv_strides || !lse) return set_error(FI_ERR_INVALID_ARG, "fi_run: null pointer");
-  if (!kv_indices && (kv8 || variant || h->cfg.mode == FI_MODE_TILE16 || deferred))
+  if (!kv_indices && (kv8 || variant || h->cfg.mode == FI_MODE_TILE16 || h->cfg.mode == FI_MODE_TILE64 || deferred))
     return set_error(FI_ERR_UNSUPPORTED, "fi_run: contiguous KV (kv_indices = NULL) is built for fi_run in decode and append mode");
   if (!o && !o_cast) return set_error(FI_ERR_INVALID_ARG, "fi_run: o and o_cast are both null: nowhere to write the output");
   if (!(sm_scale > 0.f)) return set_error(FI_ERR_INVALID_ARG, "fi_run: sm_scale must be > 0");
@@ -423,6 +437,7 @@ int32_t run_impl(fi_handle* h, const void* q, const void* k_pool, const void* v_
   }
   e = h->cfg.mode == FI_MODE_DECODE   ? launch_decode(p, bf, kv8, variant != nullptr, with_rope ? &rope : nullptr, s)
       : h->cfg.mode == FI_MODE_TILE16 ? launch_tiles(p, bf, s)
+      : h->cfg.mode == FI_MODE_TILE64 ? launch_tiles64(p, bf, s)
                                       : launch_append(p, bf, variant != nullptr, with_rope ? &rope : nullptr, s);
   if (e != hipSuccess) return hip_error("fi_run: attention launch", e);
   if (h->ev_after && (e = hipEventRecord(h->ev_after, s)) != hipSuccess) return hip_error("fi_run: hipEventRecord", e);

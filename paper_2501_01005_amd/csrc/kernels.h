@@ -90,6 +90,9 @@ hipError_t launch_decode(const RunParams& p, bool is_bf16, bool kv8, bool varian
 // causal or not; 16-bit pools, page size 16, no variants; grid = ctas_per_head * num_kv_heads with the kv head as
 // the fast index.
 hipError_t launch_tiles(const RunParams& p, bool is_bf16, hipStream_t stream);
+// tile64.hip: query tiles of up to 64 fused rows, CTAs of four wavefronts: tiles of more than 16 rows share every
+// K/V row through LDS, tiles of at most 16 rows are walked by the four wavefronts side by side; same limits and grid.
+hipError_t launch_tiles64(const RunParams& p, bool is_bf16, hipStream_t stream);
 // append.hip: query tile = append_tile_rows()/g positions x g fused heads, 8 wavefronts per CTA.
 // variant: the logits hooks of RunParams are applied (causal batches only; with ALiBi or a window every item takes
 // the generic path, the soft cap alone has a variant of the scheduled loop).

@@ -231,7 +231,9 @@ __global__ void __launch_bounds__(64 * kMergeWaves) merge_planned_kernel(const M
   const int wave = threadIdx.x >> 6;
   const int n_merge = p.header[H_N_MERGE];
   const int H = p.num_qo_heads;
-  const int rows_per_tile = p.t_pos * H;
+  // rows (position, head) of every split tile, up to the largest number of positions a split tile has (a query
+  // tile of a short request holds fewer positions than t_pos: one, for a decode step in a tile mode)
+  const int rows_per_tile = p.header[H_MERGE_POS] * H;
   const int64_t total = static_cast<int64_t>(n_merge) * rows_per_tile;
   for (int64_t r = blockIdx.x; r < total; r += gridDim.x) {
     const int mt = static_cast<int>(r / rows_per_tile);

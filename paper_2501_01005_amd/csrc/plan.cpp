@@ -15,14 +15,16 @@ namespace fi355 {
 static size_t round_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 void WorkspaceLayout::init(int32_t ctas, int32_t max_qo_tiles, int32_t t_pos, int32_t num_qo_heads,
-                           int32_t num_kv_heads, int32_t head_dim, bool formats) {
+                           int32_t num_kv_heads, int32_t head_dim, bool formats, int32_t chunk_factor) {
   ctas_per_head = ctas;
-  // sum_t ceil(kv_eff(t) / L_kv) <= n_tiles + S / L_kv <= n_tiles + #CTA
-  max_work = max_qo_tiles + ctas;
-  max_merge = ctas;
+  // sum_t ceil(kv_eff(t) / L_kv) <= n_tiles + S / L_kv <= n_tiles + #CTA; with PlanParams::weighted_lkv the sum
+  // that sets L_kv counts a light tile's tokens light_pct percent, so S / L_kv <= #CTA * 100 / light_pct
+  // (chunk_factor = that ratio rounded up)
+  max_work = max_qo_tiles + chunk_factor * ctas;
+  max_merge = chunk_factor * ctas;
   // App. D.3: at most 2 * #CTA partial states when unsplit tiles write through; composed formats have no
   // write-through, there every work item owns a slot
-  max_slots = formats ? max_work : 2 * ctas;
+  max_slots = formats ? max_work : 2 * chunk_factor * ctas;
   size_t o = 0;
   off_header = o;
   o += kHeaderInts;
@@ -183,7 +185,10 @@ int32_t make_plan_formats(const PlanParams& pp, const WorkspaceLayout& L, const 
         tl.slot_base = -1;
         tl.merge_index = -1;
         tiles.push_back(tl);
-        S += pp.literal_lkv ? l_kv : tl.kv_eff - tl.kv_begin;
+        int64_t counted = pp.literal_lkv ? l_kv : tl.kv_eff - tl.kv_begin;
+        if (pp.weighted_lkv && pp.refine && pp.light_rows > 0 && static_cast<int64_t>(tl.n_pos) * pp.group <= pp.light_rows)
+          counted = (counted * pp.light_pct + 99) / 100;
+        S += counted;
       }
     }
   }
@@ -390,6 +395,7 @@ int32_t make_plan_formats(const PlanParams& pp, const WorkspaceLayout& L, const 
     plan[L.off_merge[M_N_POS] + mi] = tl.n_pos;
     plan[L.off_merge[M_SLOT_BASE] + mi] = tl.slot_base;
     plan[L.off_merge[M_N_CHUNKS] + mi] = tl.n_chunks;
+    hdr[H_MERGE_POS] = std::max(hdr[H_MERGE_POS], tl.n_pos);
     ++mi;
   }
   return FI_OK;

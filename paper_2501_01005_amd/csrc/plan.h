@@ -16,7 +16,8 @@ constexpr int kMergeArrays = 4;  // q_row0, n_pos, slot_base, n_chunks
 // Indices of the per-work-item arrays inside the plan section.
 enum WorkField { W_REQUEST = 0, W_Q_ROW0, W_N_POS, W_KV_PAGE0, W_KV_START, W_KV_LEN, W_DIAG0, W_OUT_SLOT, W_MERGE };
 enum MergeField { M_Q_ROW0 = 0, M_N_POS, M_SLOT_BASE, M_N_CHUNKS };
-enum HeaderField { H_N_WORK = 0, H_N_MERGE, H_N_SLOTS, H_L_KV, H_T_POS, H_CTAS, H_N_ROWS };
+// (H_MERGE_POS: the largest number of positions of a split tile, which bounds the rows the contraction launch walks)
+enum HeaderField { H_N_WORK = 0, H_N_MERGE, H_N_SLOTS, H_L_KV, H_T_POS, H_CTAS, H_N_ROWS, H_MERGE_POS };
 
 // Section offsets depend only on the creation-time configuration, so the pointers a
 // captured launch holds stay valid across plans (App. D.1).
@@ -44,7 +45,7 @@ struct WorkspaceLayout {
 
   // formats: the handle may plan several formats at once: every work item then owns a partial slot
   void init(int32_t ctas, int32_t max_qo_tiles, int32_t t_pos, int32_t num_qo_heads, int32_t num_kv_heads,
-            int32_t head_dim, bool formats = false);
+            int32_t head_dim, bool formats = false, int32_t chunk_factor = 1);
 };
 
 struct PlanParams {
@@ -75,6 +76,11 @@ struct PlanParams {
   // L up to twice that, in whole pages, are tried and the one with the smallest ceil(#chunks / #CTA) * (item_cost + L)
   // is taken (ties: the shorter): a slightly longer chunk can save every CTA a second work item.
   int32_t item_cost = 0;
+  // With the refinement: a light tile's KV range also counts light_pct percent (rounded up, tile by tile) in the
+  // sum S that sets the chunk length L_kv = S / #CTA, so that the CTAs' loads in cost units, not in tokens, come out
+  // equal when light and full tiles are planned together (the 64-row tile kernel walks a light tile's chunk with
+  // four wavefronts side by side).
+  bool weighted_lkv = false;
 };
 
 // One format (Sec. 3.1.1, Sec. 3.1.2): a block-sparse-row view of the KV pool over the query rows, given by its

@@ -44,7 +44,7 @@ class DeviceBatch:
 def make_wrapper(batch, mode, **kw) -> PagedAttention:
     """A PagedAttention sized for this batch (max_batch, max_qo_tiles from its lengths)."""
     g = batch.num_qo_heads // batch.num_kv_heads
-    t_pos = {"decode": 1, "tile16": 16 // g, "append": 256 // g}[mode]
+    t_pos = {"decode": 1, "tile16": 16 // g, "tile64": 64 // g, "append": 256 // g}[mode]
     tiles = int(sum(-(-int(l) // t_pos) for l in batch.qo_lens()))
     return PagedAttention(dtype=batch.dtype, num_qo_heads=batch.num_qo_heads, num_kv_heads=batch.num_kv_heads,
                           head_dim=batch.head_dim, page_size=batch.page_size, mode=mode,
@@ -80,14 +80,14 @@ def run_gpu(batch, mode="decode", dev: DeviceBatch | None = None, wrapper=None, 
     return res
 
 
-def make_formats_wrapper(batches, **kw) -> PagedAttention:
-    """A 16-row-tile PagedAttention sized for planning these formats (views of one pool over the same query rows)
-    as one work list."""
+def make_formats_wrapper(batches, mode="tile16", **kw) -> PagedAttention:
+    """A 16-row-tile or 64-row-tile PagedAttention sized for planning these formats (views of one pool over the same
+    query rows) as one work list."""
     b0 = batches[0]
-    t_pos = 16 // (b0.num_qo_heads // b0.num_kv_heads)
+    t_pos = {"tile16": 16, "tile64": 64}[mode] // (b0.num_qo_heads // b0.num_kv_heads)
     tiles = int(sum(-(-int(l) // t_pos) for b in batches for l in b.qo_lens()))
     return PagedAttention(dtype=b0.dtype, num_qo_heads=b0.num_qo_heads, num_kv_heads=b0.num_kv_heads,
-                          head_dim=b0.head_dim, page_size=b0.page_size, mode="tile16",
+                          head_dim=b0.head_dim, page_size=b0.page_size, mode=mode,
                           max_batch=max(sum(b.batch for b in batches), 1), max_qo_tiles=max(tiles, 1), **kw)
 
 

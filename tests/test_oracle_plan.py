@@ -46,7 +46,8 @@ def replica_args(fx):
     return dict(page_size=ps, t_pos=fx["t_pos"][0], group=fx["group"][0], num_ctas=fx["num_ctas"][0],
                 causal=bool(fx["causal"][0]), alpha=opt("alpha", 1), beta=opt("beta", 1), min_chunk=opt("min_chunk", ps),
                 refine=bool(opt("refine", 0)), light_rows=opt("light_rows", 0), light_pct=opt("light_pct", 100),
-                kv_quantum=opt("kv_quantum", 1), plan_window=opt("plan_window", 0), item_cost=opt("item_cost", 0))
+                kv_quantum=opt("kv_quantum", 1), plan_window=opt("plan_window", 0), item_cost=opt("item_cost", 0),
+                weighted_lkv=bool(opt("weighted_lkv", 0)))
 
 
 @pytest.mark.parametrize("name", HAND_WORKED)
@@ -315,9 +316,11 @@ def formats_of_fixture(fx):
     return out
 
 
-def test_hand_worked_plan_over_two_formats():
+# (the second: light tiles at 30 percent in the chunk length and in the costs, and one swap of the refinement)
+@pytest.mark.parametrize("name", ["plan_formats_example.txt", "plan_weighted_formats_example.txt"])
+def test_hand_worked_plan_over_two_formats(name):
     from oracle.plan_replica import plan_replica_formats
-    fx = load_fixture("plan_formats_example.txt")
+    fx = load_fixture(name)
     p = plan_replica_formats(formats_of_fixture(fx), **replica_args(fx))
     assert p["L_kv"] == fx["L_kv"][0] and p["n_slots"] == fx["n_slots"][0] and p["n_merge"] == 0
     for key in FIXTURE_KEYS + ("row_indptr", "row_entry"):

@@ -371,6 +371,74 @@ def test_tile16_single_format_plans_equal_the_replica_causal_and_not():
             fi.fi_destroy(h)
 
 
+def make_tile64(g, C, Hkv=2, max_batch=256, max_tiles=1024, **kw):
+    return fi.fi_create(dtype=fi.FI_DTYPE_BF16, num_qo_heads=g * Hkv, num_kv_heads=Hkv, head_dim=128, page_size=16,
+                        mode=fi.FI_MODE_TILE64, num_ctas=C * Hkv, max_batch=max_batch, max_qo_tiles=max_tiles, **kw)
+
+
+# what fi_create sets for the planner in the 64-row tile mode with balance = 0: refined assignment, a tile of at most
+# 16 fused rows counts 30 percent per token, in the costs and in the sum behind the chunk length; costs in steps of 32
+TILE64_PLAN = dict(refine=True, light_rows=16, light_pct=30, kv_quantum=32, weighted_lkv=True)
+
+
+def test_planner_reproduces_the_hand_worked_weighted_plan():
+    from test_oracle_plan import FIXTURE_KEYS, formats_of_fixture, load_fixture
+    fx = load_fixture("plan_weighted_formats_example.txt")
+    h = make_tile64(fx["group"][0], fx["num_ctas"][0], min_chunk=16)
+    fi.fi_plan_formats(h, formats_of_fixture(fx))
+    got = fi.fi_plan_view(h)
+    assert got["l_kv_chunk"] == fx["L_kv"][0] and got["n_slots"] == fx["n_slots"][0] and got["n_merge"] == 0
+    assert got["t_pos"] == fx["t_pos"][0] and got["n_rows"] == 8
+    for key in FIXTURE_KEYS + ("row_indptr", "row_entry"):
+        if key in fx and key != "cta_cost":
+            assert got[key].tolist() == fx[key], key
+    fi.fi_destroy(h)
+
+
+def test_tile64_plans_equal_the_replica():
+    """64-row tile mode: plans over several formats and over one (causal and not), default and as-printed balance;
+    the workspace sections hold every such plan (the weighted chunk length allows more chunks than #CTA extra)."""
+    from oracle.plan_replica import plan_replica_formats
+    rng = np.random.default_rng(47)
+    n_cases = 0
+    for g in (1, 4, 16):
+        for C in (1, 7, 64):
+            for (min_chunk, balance) in ((16, 0), (128, 0), (32, 1)):
+                h = make_tile64(g, C, min_chunk=min_chunk, balance=balance)
+                kw = dict(page_size=16, t_pos=64 // g, group=g, num_ctas=C, min_chunk=min_chunk,
+                          **(TILE64_PLAN if balance == 0 else {}))
+                for trial in range(10):
+                    n_rows = int(rng.integers(1, 90))
+                    n_formats = int(rng.integers(1, 4))
+                    formats, base = [], 0
+                    for f in range(n_formats):
+                        if f == 0 and trial % 2 == 0:
+                            cuts = [0, n_rows]                      # a shared prefix: one row block
+                        else:
+                            cuts = sorted(set(rng.integers(0, n_rows + 1, size=int(rng.integers(0, n_rows + 1))).tolist()) | {0, n_rows})
+                        qo = np.diff(cuts)
+                        kv = rng.integers(0, 3000 if f == 0 else 600, size=len(qo))
+                        qo_indptr, kv_indptr, last = indptrs(qo, kv)
+                        formats.append((qo_indptr, kv_indptr, last, base))
+                        base += int(kv_indptr[-1])
+                    compare_formats(h, formats, plan_replica_formats(formats, causal=False, **kw))
+                    n_cases += 1
+                    B = int(rng.integers(1, 20))
+                    qo = rng.integers(0, 80, size=B)
+                    kv = qo + rng.integers(0, 900, size=B)
+                    for causal in (False, True):
+                        qo_indptr, kv_indptr, last = indptrs(qo, kv)
+                        fi.fi_plan(h, qo_indptr, kv_indptr, last, causal)
+                        got = fi.fi_plan_view(h)
+                        want = plan_replica(qo_indptr, kv_indptr, last, causal=causal, **kw)
+                        assert got["l_kv_chunk"] == want["L_kv"] and got["n_work"] == want["n_work"]
+                        for k in PLAN_KEYS:
+                            assert got[k].tobytes() == np.asarray(want[k], dtype=np.int32).tobytes(), k
+                        n_cases += 1
+                fi.fi_destroy(h)
+    assert n_cases >= 800
+
+
 def test_plan_formats_argument_errors():
     h = make_tile16(4, 4)
     qo, kv, last = indptrs([3], [40])
