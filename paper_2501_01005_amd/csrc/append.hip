@@ -197,7 +197,9 @@ struct WorkItem {
 // VARL: the variant of the loop with the ALiBi bias and the sliding window (Sec. 3.2.3; causal items): `cap` then
 // carries lim - 4 * (lane / 32) uncapped, lim = chunk-local index of the row's own token; `slope` = the row's head's
 // slope times log2(e) (0: none), `win` = window_left (a huge value: none).
-template <bool BF, bool CAP, bool CONTIG, bool VARL>
+// PSL: the variant for page sizes 4, 8 and 32: `g_log2` carries log2 of the page size in bits 8.., `ids_clamp` and
+// `page_ids` count pages of that size, and the per-lane row offsets hold the row's place inside its page.
+template <bool BF, bool CAP, bool CONTIG, bool VARL, bool PSL = false>
 __device__ __forceinline__ void run_scheduled_loop(int n_full, int n_tiles, int kv_len, int cap, int st_tok, int ids_clamp, const int32_t* page_ids, uint32_t k_lo,
                                                    uint32_t k_hi, uint32_t v_lo, uint32_t v_hi, uint32_t page_bytes,
                                                    float scale_log2, uint64_t q_addr, uint32_t st_off_bytes,
@@ -245,6 +247,20 @@ __device__ __forceinline__ void run_scheduled_loop(int n_full, int n_tiles, int 
 #define FI355_ROW_FLAGS [rok] "v"(row_flags),
 #define FI355_HEADS_AND_POSITIONS [hq] "s"(num_qo_heads), [np] "s"(n_pos),
   if constexpr (VARL) {
+  } else if constexpr (PSL && BF) {
+    asm volatile(
+#include "append_loop_bf16_ps.inc"
+        FI355_LOOP_OPERANDS
+        :
+#include "append_loop_clobbers.inc"
+    );
+  } else if constexpr (PSL) {
+    asm volatile(
+#include "append_loop_f16_ps.inc"
+        FI355_LOOP_OPERANDS
+        :
+#include "append_loop_clobbers.inc"
+    );
   } else if constexpr (CONTIG && BF) {
     asm volatile(
 #include "append_loop_bf16_contig.inc"
@@ -790,12 +806,14 @@ __device__ __attribute__((noinline)) void generic_work_item(uint64_t params_addr
 // scheduled loop has a variant for them too.
 // ROPE (with VAR, no loop variant): every item on the general path, queries and keys rotated by their positions.
 struct NoRopeTable {};
-template <bool BF, bool VAR = false, bool CAPLOOP = false, bool CONTIG = false, bool VARLOOP = false, bool ROPE = false>
+template <bool BF, bool VAR = false, bool CAPLOOP = false, bool CONTIG = false, bool VARLOOP = false, bool ROPE = false,
+          bool PSLOOP = false>
 __global__ void __launch_bounds__(kCtaThreads) __attribute__((amdgpu_waves_per_eu(2, 2)))
 append_kernel(const RunParams p, const typename std::conditional<ROPE, RopeTable, NoRopeTable>::type rope) {
   static_assert(!CONTIG || !VAR, "affine addressing is built for the plain kernel");
   static_assert(!(CAPLOOP && VARLOOP) && (!VARLOOP || VAR), "one variant of the loop per instantiation");
   static_assert(!ROPE || (VAR && !CAPLOOP && !VARLOOP), "the rotary transform is built into the general path");
+  static_assert(!PSLOOP || (!VAR && !CONTIG), "the loop for other page sizes is the plain one");
   const int tid = threadIdx.x;
   if constexpr (ROPE) {
     if (tid < 64) {
@@ -833,7 +851,9 @@ append_kernel(const RunParams p, const typename std::conditional<ROPE, RopeTable
       const int64_t page_bytes = p.stride_page * 2;
       // (the loop addresses its outputs with 32-bit byte offsets)
       const int64_t out_rows_bound = (out_slot < 0 ? static_cast<int64_t>(q_row0) + p.t_pos : (static_cast<int64_t>(out_slot) + 1) * p.t_pos) * H;
-      if (p.page_log2 == 4 && n_full >= 1 && kv_len >= kLoopMinTokens && page_bytes > 0 && page_bytes < (int64_t(1) << 32) &&
+      // (PSLOOP: page sizes 4, 8, 32: a wavefront's four consecutive rows per load lie in one page, and the two
+      // 32-token halves of a tile in different pages or in the two halves of one)
+      if ((PSLOOP ? (p.page_log2 == 2 || p.page_log2 == 3 || p.page_log2 == 5) : p.page_log2 == 4) && n_full >= 1 && kv_len >= kLoopMinTokens && page_bytes > 0 && page_bytes < (int64_t(1) << 32) &&
           (!VARLOOP || H < 65536) &&  // (that variant takes num_qo_heads in 16 bits of an operand)
           out_rows_bound * (kHeadDim * 4) < (int64_t(1) << 32)) {
         // The loop clobbers nearly every vector register, so its lane-dependent operands are
@@ -854,18 +874,19 @@ append_kernel(const RunParams p, const typename std::conditional<ROPE, RopeTable
         const uint64_t v_base = reinterpret_cast<uint64_t>(static_cast<const uint16_t*>(p.v_pool) + kvh * p.stride_head);
         const uint64_t all_ids = reinterpret_cast<uint64_t>(p.kv_indices);
         const uint32_t lds0 = lds_offset(lds_raw);
-        const int chunk_pages = (kv_len + kPageSize - 1) / kPageSize;
+        const int chunk_pages = PSLOOP ? (kv_len + (1 << p.page_log2) - 1) >> p.page_log2 : (kv_len + kPageSize - 1) / kPageSize;
+        const int row_in_page = PSLOOP ? st_tok_o & (min(1 << p.page_log2, 32) - 1) : st_tok_o & 15;
         const int last_seen = causal ? min(diag0 + pos_r - kv_start, kv_len - 1) : kv_len - 1;
         // where the rows go: the final output (write-through, App. D.2) or this item's partial slot
         const bool final_out = out_slot < 0;
         const int64_t out_row = (final_out ? static_cast<int64_t>(q_row0 + pos_r)
                                            : static_cast<int64_t>(out_slot) * p.t_pos + pos_r) * H + head;
-        const uint32_t st_off_bytes = static_cast<uint32_t>((st_tok_o & 15) * p.stride_tok + st_chunk_o * 8) * 2;
+        const uint32_t st_off_bytes = static_cast<uint32_t>(row_in_page * p.stride_tok + st_chunk_o * 8) * 2;
         // K goes straight to LDS in packed 256-byte rows whose 16-byte chunks are XOR-swizzled by the
         // row index (conflict-free operand reads without padding): LDS slot st_chunk of row st_tok
         // holds chunk st_chunk ^ (st_tok % 16) of that token
         const uint32_t k_off_bytes =
-            static_cast<uint32_t>((st_tok_o & 15) * p.stride_tok + ((st_chunk_o ^ st_tok_o) & 15) * 8) * 2;
+            static_cast<uint32_t>(row_in_page * p.stride_tok + ((st_chunk_o ^ st_tok_o) & 15) * 8) * 2;
         const uint32_t epi0 = lds0 + kEpilogueBase + wave_o * kEpilogueLdsBytes;
         WorkItem next;
         int prefetched_next;
@@ -876,7 +897,7 @@ append_kernel(const RunParams p, const typename std::conditional<ROPE, RopeTable
         if constexpr (VARLOOP) {
           if (p.alibi_slopes != nullptr) slope_o = p.alibi_slopes[head] * 1.4426950408889634f;
         }
-        run_scheduled_loop<BF, CAPLOOP, CONTIG, VARLOOP>(n_full, (kv_len + kTileKv - 1) / kTileKv, kv_len, seen_bound - 4 * c_o, st_tok_o,
+        run_scheduled_loop<BF, CAPLOOP, CONTIG, VARLOOP, PSLOOP>(n_full, (kv_len + kTileKv - 1) / kTileKv, kv_len, seen_bound - 4 * c_o, st_tok_o,
                                (chunk_pages - 1) * 4, p.kv_indices + kv_page0, static_cast<uint32_t>(k_base),
                                static_cast<uint32_t>(k_base >> 32), static_cast<uint32_t>(v_base),
                                static_cast<uint32_t>(v_base >> 32), static_cast<uint32_t>(page_bytes),
@@ -895,6 +916,7 @@ append_kernel(const RunParams p, const typename std::conditional<ROPE, RopeTable
                                st_chunk_o * 16,
                                CAPLOOP   ? g_log2 | (__builtin_amdgcn_readfirstlane(wave_o) << 8)
                                : VARLOOP ? g_log2 | (n_pos << 5) | (H << 16)
+                               : PSLOOP  ? g_log2 | (p.page_log2 << 8)
                                          : g_log2,
                                H,
                                static_cast<int>((final_out ? static_cast<int64_t>(q_row0)
@@ -954,6 +976,13 @@ hipError_t launch_append(const RunParams& p, bool is_bf16, bool variant, const R
       hipLaunchKernelGGL((append_kernel<true, true>), grid, block, 0, stream, p, NoRopeTable{});
     else
       hipLaunchKernelGGL((append_kernel<false, true>), grid, block, 0, stream, p, NoRopeTable{});
+    return hipGetLastError();
+  }
+  if (p.kv_indices != nullptr && (p.page_log2 == 2 || p.page_log2 == 3 || p.page_log2 == 5)) {  // their variant of the loop
+    if (is_bf16)
+      hipLaunchKernelGGL((append_kernel<true, false, false, false, false, false, true>), grid, block, 0, stream, p, NoRopeTable{});
+    else
+      hipLaunchKernelGGL((append_kernel<false, false, false, false, false, false, true>), grid, block, 0, stream, p, NoRopeTable{});
     return hipGetLastError();
   }
   if (p.kv_indices == nullptr) {  // contiguous KV (the caller has refused variants)

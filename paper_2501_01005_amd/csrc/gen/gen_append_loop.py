@@ -52,6 +52,7 @@ S_EXEC = 96
 S_IDK = 88                     # page ids of the tile whose K goes to LDS next (takes over S_IDA after start-up)
 S_ONES = 98                    # var variant: fp16 ones in both halves (the vector register of the constant is needed otherwise)
 S_NP, S_HQ = 99, 100           # var variant: n_pos and num_qo_heads, unpacked from %[gl]
+S_PSL, S_W4 = 98, 99           # page-size variant: log2 of the page size (from %[gl]); 4 * (wavefront % 4) = first row of its row group
 S_M0 = 97                      # saved m0 (the register doubles as half of S_EXEC, which is used only after m0 is restored)
 S_NX = 92                      # this wavefront's page ids of tiles 0 and 1 of the CTA's next work item (takes over S_IDB after start-up)
 S_STP = 96                     # which page of a 32-token half this thread's staging rows are in (wavefront / 4); the epilogue reuses the register
@@ -103,8 +104,14 @@ def merge_even(*lists):
 
 
 class Gen:
-    def __init__(self, bf16, cap=False, contig=False, var=False):
+    def __init__(self, bf16, cap=False, contig=False, var=False, anyps=False):
         self.bf = bf16
+        # Page sizes 4, 8 and 32 (the plain loop): a wavefront stages four consecutive token rows per load, all in one
+        # page, so what changes is which page id it fetches for them: token (64 t + 16 r + first row of its group)
+        # >> log2(page size) of the chunk, for each 16-token segment r of tile t.  The row's place inside its page
+        # is part of the per-lane offsets the C++ side passes.  %[gl] carries log2 of the page size in bits 8..
+        self.anyps = anyps
+        assert not (anyps and (cap or contig or var))
         # ALiBi bias and sliding window (Sec. 3.2.3) for causal work items: like the soft cap, the logits of a step are
         # transformed in place as soon as they are complete: s <- s * sm_scale * log2(e) + slope * (t - pos), then -inf
         # where t < pos - W.  Per lane: %[cap] carries lim - 4 c uncapped (lim = chunk-local index of the row's own
@@ -304,6 +311,23 @@ class Gen:
         """request the page ids of tile t + ahead; each of the four is clamped to the chunk's last
         page, so a partial last tile still gets its own pages and nothing past the chunk is read"""
         ops = []
+        if self.anyps:
+            # token of this wavefront's first row in segment r of the tile -> its page -> byte offset of the page id
+            if ahead:
+                ops.append('s_add_u32 s%d, s%d, %d' % (S_TMP, S_T, ahead))
+                ops.append('s_lshl_b32 s%d, s%d, 6' % (S_TMP, S_TMP))
+            else:
+                ops.append('s_lshl_b32 s%d, s%d, 6' % (S_TMP, S_T))
+            ops.append('s_add_u32 s%d, s%d, s%d' % (S_TMP, S_TMP, S_W4))
+            for r, off in enumerate(S_OFFS):
+                if r:
+                    ops.append('s_add_u32 s%d, s%d, %d' % (off, S_TMP, 16 * r))
+                    ops.append('s_lshr_b32 s%d, s%d, s%d' % (off, off, S_PSL))
+                else:
+                    ops.append('s_lshr_b32 s%d, s%d, s%d' % (off, S_TMP, S_PSL))
+                ops += ['s_lshl_b32 s%d, s%d, 2' % (off, off), 's_min_u32 s%d, s%d, %%[npg1]' % (off, off),
+                        's_load_dword s%d, %%[idp], s%d' % (dst + r, off)]
+            return ops
         if ahead:
             ops.append('s_add_u32 s%d, s%d, %d' % (S_TMP, S_T, ahead))
             ops.append('s_lshl_b32 s%d, s%d, 4' % (S_TMP, S_TMP))
@@ -347,17 +371,28 @@ class Gen:
                's_max_i32 s%d, s%d, 0' % (S_LO, S_LO), 's_min_i32 s%d, s%d, s%d' % (S_REM, S_REM, S_LO),
                vis + ':',
                's_cmp_lt_u32 s%d, 64' % S_REM, 's_cbranch_scc1 ' + no,
-               's_mov_b32 %[preo], 1',
-               # byte offset of the chunk's last page id (S_REM); address of its first one (S_KA pair)
-               's_add_u32 s%d, %%[nkl], 15' % S_REM, 's_lshr_b32 s%d, s%d, 4' % (S_REM, S_REM),
-               's_sub_u32 s%d, s%d, 1' % (S_REM, S_REM), 's_lshl_b32 s%d, s%d, 2' % (S_REM, S_REM),
+               's_mov_b32 %[preo], 1']
+        # byte offset of the chunk's last page id (S_REM); address of its first one (S_KA pair)
+        if self.anyps:
+            ops += ['s_lshl_b32 s%d, 1, s%d' % (S_REM, S_PSL), 's_sub_u32 s%d, s%d, 1' % (S_REM, S_REM),
+                    's_add_u32 s%d, s%d, %%[nkl]' % (S_REM, S_REM), 's_lshr_b32 s%d, s%d, s%d' % (S_REM, S_REM, S_PSL)]
+        else:
+            ops += ['s_add_u32 s%d, %%[nkl], 15' % S_REM, 's_lshr_b32 s%d, s%d, 4' % (S_REM, S_REM)]
+        ops += ['s_sub_u32 s%d, s%d, 1' % (S_REM, S_REM), 's_lshl_b32 s%d, s%d, 2' % (S_REM, S_REM),
                's_mov_b32 s%d, %%[npg]' % S_LO, 's_mov_b32 s%d, 0' % S_HI,
                's_lshl_b64 s[%d:%d], s[%d:%d], 2' % (S_LO, S_HI, S_LO, S_HI),
                's_add_u32 s%d, %%[idblo], s%d' % (S_KA, S_LO), 's_addc_u32 s%d, %%[idbhi], s%d' % (S_KA + 1, S_HI)]
         # of a tile's four pages this thread's rows are in pages S_STP and 2 + S_STP
-        ops.append('s_lshl_b32 s%d, s%d, 2' % (S_LO, S_STP))
+        if self.anyps:  # (token of this wavefront's first row in half i of the first two tiles: 32 i + 4 * wavefront)
+            ops += ['s_lshl_b32 s%d, s%d, 4' % (S_LO, S_STP), 's_add_u32 s%d, s%d, s%d' % (S_LO, S_LO, S_W4)]
+        else:
+            ops.append('s_lshl_b32 s%d, s%d, 2' % (S_LO, S_STP))
         for i in range(4):
-            ops += ['s_add_u32 s%d, s%d, %d' % (S_TMP, S_LO, 8 * i), 's_min_u32 s%d, s%d, s%d' % (S_TMP, S_TMP, S_REM)]
+            if self.anyps:
+                ops += ['s_add_u32 s%d, s%d, %d' % (S_TMP, S_LO, 32 * i), 's_lshr_b32 s%d, s%d, s%d' % (S_TMP, S_TMP, S_PSL),
+                        's_lshl_b32 s%d, s%d, 2' % (S_TMP, S_TMP), 's_min_u32 s%d, s%d, s%d' % (S_TMP, S_TMP, S_REM)]
+            else:
+                ops += ['s_add_u32 s%d, s%d, %d' % (S_TMP, S_LO, 8 * i), 's_min_u32 s%d, s%d, s%d' % (S_TMP, S_TMP, S_REM)]
             if self.contig:  # the next item's page ids follow from its kv_page0
                 ops += ['s_lshr_b32 s%d, s%d, 2' % (S_NX + i, S_TMP), 's_add_u32 s%d, s%d, %%[npg]' % (S_NX + i, S_NX + i)]
             else:
@@ -555,6 +590,10 @@ class Gen:
         e.raw('s_mov_b32 s%d, 0x%x' % (S_THR, LAZY_THR))
         for o in self.wave_shift(S_STP, 'lshr', 2):
             e.raw(o)
+        if self.anyps:
+            e.raw('s_lshr_b32 s%d, %%[gl], 8' % S_PSL)
+            e.raw('s_and_b32 s%d, %%[stp8], 3' % S_W4)
+            e.raw('s_lshl_b32 s%d, s%d, 2' % (S_W4, S_W4))
         for s in range(8):
             e.emit('global_load_dwordx4 %s, %%[qp], off offset:%d' % (vr(Q + 4 * s, 4), 32 * s))
         for o in self.header_next():
@@ -785,8 +824,9 @@ if __name__ == '__main__':
     for bf, cap, contig, name in ((True, False, False, 'bf16'), (False, False, False, 'f16'), (True, True, False, 'bf16_cap'),
                                   (False, True, False, 'f16_cap'), (True, False, True, 'bf16_contig'),
                                   (False, False, True, 'f16_contig'), (True, False, False, 'bf16_var'),
-                                  (False, False, False, 'f16_var')):
-        lines = Gen(bf, cap, contig, var=name.endswith('_var')).program()
+                                  (False, False, False, 'f16_var'), (True, False, False, 'bf16_ps'),
+                                  (False, False, False, 'f16_ps')):
+        lines = Gen(bf, cap, contig, var=name.endswith('_var'), anyps=name.endswith('_ps')).program()
         write(os.path.join(out_dir, 'append_loop_%s.inc' % name), lines, name)
         n_mfma = sum(1 for l in lines if l.startswith('v_mfma'))
         print('%s: %d lines, %d matrix instructions, %d waits' % (name, len(lines), n_mfma, sum(1 for l in lines if l.startswith('s_waitcnt'))))

@@ -1,6 +1,7 @@
 """GPU parity for page sizes other than the tuned 16 (Sec. 3.1.1: the block size of the BSR cache is a free
-parameter; App. B compares page sizes): decode and append go through their general code paths, where every
-lane or staging thread looks up the page of the token row it loads."""
+parameter; App. B compares page sizes): decode goes through its general code path, where every lane looks up the
+page of the token row it loads; append runs the scheduled loop's variant for page sizes 4, 8 and 32 (a wavefront's
+four consecutive rows per load share a page) and the general path for the others."""
 import numpy as np
 import pytest
 
@@ -32,13 +33,27 @@ def test_decode(ps):
     check(b, "decode", f"decode split ps={ps}", num_ctas=2 * 16, min_chunk=64)
 
 
-@pytest.mark.parametrize("ps", [1, 8, 32, 64])
+@pytest.mark.parametrize("ps", [1, 4, 8, 32, 64])
 def test_append(ps):
     for seed, dtype, causal in ((321, workloads.BF16, True), (322, workloads.F16, False)):
         b = workloads.make_batch("app", seed + ps, dtype, 8, 2, 128, ps, [70, 9, 130, 1], [400, 9, 333, 64], causal)
         check(b, "append", f"append ps={ps} causal={causal}", num_ctas=2 * 4, min_chunk=128)
     b = workloads.make_batch("appsplit", 330 + ps, workloads.BF16, 8, 2, 128, ps, [64, 30], [1000, 777], True)
     check(b, "append", f"append split ps={ps}", num_ctas=2 * 16, min_chunk=128)
+
+
+@pytest.mark.parametrize("ps", [4, 8, 32])
+def test_append_work_items_that_follow_each_other_in_the_scheduled_loop(ps):
+    """Default grid on the small causal-append configuration and long chunks on few CTAs: several work items per CTA
+    run the loop back to back (the next item's first tiles are requested by the item before it), with ragged last
+    pages, chunk ends inside a page-size-32 page pair, and both storage types."""
+    check(workloads.config3(small=True, page_size=ps), "append", f"c3 small ps={ps}")
+    for seed, dtype in ((351, workloads.BF16), (352, workloads.F16)):
+        b = workloads.make_batch("appchain", seed + ps, dtype, 8, 2, 128, ps, [200, 64, 130, 300], [1500, 700, 131, 900], True)
+        check(b, "append", f"append chain ps={ps}", num_ctas=2 * 3, min_chunk=128)
+        check(b, "append", f"append chain ps={ps}, default grid")
+    b = workloads.make_batch("appfull", 360 + ps, workloads.BF16, 8, 2, 128, ps, [64, 64], [2048, 1000], False)
+    check(b, "append", f"append not causal ps={ps}", num_ctas=2 * 8, min_chunk=256)
 
 
 def test_strided_layout_with_small_pages():
