@@ -11,7 +11,7 @@ from gpu_util import DeviceBatch, assert_close, run_gpu
 pytestmark = pytest.mark.gpu
 
 
-def check(batch, mode, what, layout="HND", **kw):
+def check(batch, mode, what, layout="HND", same_path=True, **kw):
     print(f"[case] {what}: {batch.name} page_size={batch.page_size} layout={layout} qo={batch.qo_lens()[:6].tolist()} "
           f"kv={batch.kv_lens()[:6].tolist()} kw={kw}", flush=True)
     o_ref, lse_ref = oracle.run_batch(batch)
@@ -19,8 +19,12 @@ def check(batch, mode, what, layout="HND", **kw):
     o, lse = run_gpu(batch, mode, dev=dev, contiguous=True, **kw)
     e = assert_close(o, lse, o_ref, lse_ref, what)
     o_p, lse_p = run_gpu(batch, mode, dev=dev, **kw)                      # the identity table given explicitly
-    assert np.array_equal(o, o_p) and np.array_equal(lse, lse_p), f"{what}: differs from the paged run"
-    print(f"[ok] {what}: err_o={e[0]:.2e} err_lse={e[1]:.2e}; bit-identical to the paged run", flush=True)
+    if same_path:
+        assert np.array_equal(o, o_p) and np.array_equal(lse, lse_p), f"{what}: differs from the paged run"
+    else:
+        assert_close(o_p, lse_p, o_ref, lse_ref, what + " (paged run)")
+    print(f"[ok] {what}: err_o={e[0]:.2e} err_lse={e[1]:.2e}" + ("; bit-identical to the paged run" if same_path else ""),
+          flush=True)
 
 
 @pytest.mark.parametrize("layout", ["HND", "NHD"])
@@ -34,8 +38,11 @@ def test_decode_over_contiguous_kv(page_size, layout):
 @pytest.mark.parametrize("page_size", [16, 1, 32])
 def test_append_over_contiguous_kv(page_size, layout):
     b = workloads.config3(small=True, permute_pages=False, page_size=page_size)
-    check(b, "append", f"append contiguous ps{page_size}", layout)                              # default grid
-    check(b, "append", f"append contiguous ps{page_size}, split", layout, num_ctas=8 * 16, min_chunk=32)
+    # (at page size 32 the paged run takes the scheduled loop's page-size variant and the run without a page table
+    # the general path: the same result within the tolerance, not the same bits)
+    same = page_size != 32
+    check(b, "append", f"append contiguous ps{page_size}", layout, same_path=same)              # default grid
+    check(b, "append", f"append contiguous ps{page_size}, split", layout, same_path=same, num_ctas=8 * 16, min_chunk=32)
 
 
 def test_ragged_tensor_is_page_size_one_nhd():
