@@ -230,9 +230,16 @@ def main() -> int:
     # first 15 ms and settles near 329 us)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=50)
-    ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4", "c5"] + E2_WORKLOADS,
+    ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4", "c5", "sa"] + E2_WORKLOADS,
                     help="c1..c5: the benchmark configurations; e2-<decode|prefill>-<constant|uniform|zipf>: batch 16 "
-                         "with the three length distributions of the paper's kernel experiment (Sec. 4.2)")
+                         "with the three length distributions of the paper's kernel experiment (Sec. 4.2); sa: short "
+                         "appends (--sa-qo tokens per request, --sa-batch requests, caches up to --sa-kv-max tokens) through "
+                         "the handle mode --handle-mode")
+    ap.add_argument("--sa-qo", type=int, default=16)
+    ap.add_argument("--sa-batch", type=int, default=64)
+    ap.add_argument("--sa-kv-max", type=int, default=4096)
+    ap.add_argument("--handle-mode", default="append", choices=["decode", "tile16", "tile64", "append"],
+                    help="sa: the query tile of the handle (decode needs --sa-qo 1)")
     ap.add_argument("--small", action="store_true", help="small variant of the workload (debug)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-plan", action="store_true", help="time fi_run only (plan once, as for layers 2..L)")
@@ -357,7 +364,13 @@ def run_workload(args):
             print("bench.py: --page-size is for c2 and c3", file=sys.stderr)
             return 2
         cfg_kw["page_size"] = args.page_size
-    if args.workload in E2_WORKLOADS:
+    if args.workload == "sa":
+        if args.handle_mode == "decode" and args.sa_qo != 1:
+            print("bench.py: a decode-mode handle takes one query position per request (--sa-qo 1)", file=sys.stderr)
+            return 2
+        batch = workloads.short_append(args.sa_qo, args.sa_batch, args.sa_kv_max)
+        mode = args.handle_mode
+    elif args.workload in E2_WORKLOADS:
         _, kind, dist = args.workload.split("-")
         batch = workloads.config_e2(kind, dist)
         mode = "append" if kind == "prefill" else "decode"
@@ -454,12 +467,14 @@ def run_workload(args):
                                              ("_rope" if args.rope_theta > 0 else "") +
                                              ("_small" if args.small else ""))
 
-    if mode == "decode":
+    if mode != "append" or args.workload == "sa":   # bound by the K/V bytes: every attended token once per kv head
         ab = decode_algorithmic_bytes(batch, view)
         value = ab["step"] / (ms_per_step * 1e-3) / 1e9
         achieved = ab["attention_kernel"] / (kern_avg_ms * 1e-3) / 1e9
-        metric, unit = "achieved HBM bandwidth, paged GQA decode step (algorithmic bytes / step time)", "GB/s"
-        roof = {"bound": "hbm", "kernel": "decode_kernel", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+        metric, unit = ("achieved HBM bandwidth, short causal appends (algorithmic bytes / step time)" if args.workload == "sa" else
+                        "achieved HBM bandwidth, paged GQA decode step (algorithmic bytes / step time)"), "GB/s"
+        roof = {"bound": "hbm", "kernel": {"decode": "decode_kernel", "tile16": "tile_kernel", "tile64": "tile64_kernel",
+                                           "append": "append_kernel"}[mode], "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
                 "traffic_source": "profiles/traffic.json: rocprofv3 FETCH_SIZE + WRITE_SIZE of an earlier run of this workload, not of this run",
                 "algorithmic_bytes_per_launch": ab["attention_kernel"], "avg_kernel_us": kern_avg_ms * 1e3,
@@ -484,7 +499,7 @@ def run_workload(args):
         "ms_per_step": ms_per_step, "us_per_batch": ms_per_step * 1e3, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": batch.dtype, "data": "synthetic",
         "config": {"workload": batch.name, "batch": batch.batch, "num_qo_heads": batch.num_qo_heads,
-                   "num_kv_heads": batch.num_kv_heads, "head_dim": batch.head_dim, "page_size": batch.page_size, "page_order": args.page_order, "kv_layout": args.kv_layout,
+                   "num_kv_heads": batch.num_kv_heads, "head_dim": batch.head_dim, "page_size": batch.page_size, "handle_mode": mode, "page_order": args.page_order, "kv_layout": args.kv_layout,
                    "page_table": "none (contiguous KV, affine addressing)" if args.kv_contiguous else "kv_indices",
                    "kv_dtype": batch.kv_dtype or batch.dtype, "o_dtype": batch.dtype if args.out16 else "f32",
                    **({"fused_rope_theta": args.rope_theta} if args.rope_theta > 0 else {}),
@@ -495,7 +510,7 @@ def run_workload(args):
                             "fi_run only (plan reused)" if args.no_plan else "fi_plan + fi_run"),
                    "ctas_per_head": int(view["ctas_per_head"]), "l_kv_chunk": int(view["l_kv_chunk"]),
                    "n_work": int(view["n_work"]), "n_split_tiles": int(view["n_merge"])},
-        "frac_of_peak": (value / HBM_PEAK_GBS) if mode == "decode" else (value / MFMA_PEAK_TFLOPS),
+        "frac_of_peak": (value / HBM_PEAK_GBS) if unit == "GB/s" else (value / MFMA_PEAK_TFLOPS),
         "host_plan_us": plan_us, "roofline": roof, **extra,
     }
     if not args.no_cpu_baseline:

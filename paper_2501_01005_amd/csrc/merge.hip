@@ -235,6 +235,34 @@ __global__ void __launch_bounds__(64 * kMergeWaves) merge_planned_kernel(const M
   // tile of a short request holds fewer positions than t_pos: one, for a decode step in a tile mode)
   const int rows_per_tile = p.header[H_MERGE_POS] * H;
   const int64_t total = static_cast<int64_t>(n_merge) * rows_per_tile;
+  // Many rows (query tiles of several positions: tens of thousands of rows of a few states each): a wavefront per
+  // row, the row's loads all in flight at once, no LDS, no barriers; the same sums in the same order as fold_row,
+  // hence the same bits whichever way a plan's rows are walked.
+  if (total > 4 * static_cast<int64_t>(gridDim.x)) {
+    for (int64_t r = static_cast<int64_t>(blockIdx.x) * kMergeWaves + wave; r < total;
+         r += static_cast<int64_t>(gridDim.x) * kMergeWaves) {
+      const int mt = static_cast<int>(r / rows_per_tile);
+      const int rr = static_cast<int>(r % rows_per_tile);
+      const int pos = rr / H;
+      const int head = rr % H;
+      if (pos >= p.m_n_pos[mt]) continue;  // wavefront-uniform
+      const int n = p.m_n_chunks[mt];
+      const int64_t slot_row0 = (static_cast<int64_t>(p.m_slot_base[mt]) * p.t_pos + pos) * H + head;
+      const int64_t slot_stride = static_cast<int64_t>(p.t_pos) * H;
+      f32x2_t o2;
+      float l;
+      if (n <= 8) {  // (a split tile has at least two chunks)
+        RowStates<8> rs;
+        load_states<8>(&rs, p.part_lse + slot_row0, slot_stride, p.part_o + slot_row0 * kHeadDim, slot_stride * kHeadDim, n, lane);
+        reduce_states<8>(rs, n, lane, &o2, &l);
+      } else {
+        fold_row_wave(p.part_lse + slot_row0, slot_stride, p.part_o + slot_row0 * kHeadDim, slot_stride * kHeadDim, n,
+                      lane, &o2, &l);
+      }
+      planned_store(p, (static_cast<int64_t>(p.m_q_row0[mt]) + pos) * H + head, lane, o2, l);
+    }
+    return;
+  }
   for (int64_t r = blockIdx.x; r < total; r += gridDim.x) {
     const int mt = static_cast<int>(r / rows_per_tile);
     const int rr = static_cast<int>(r % rows_per_tile);

@@ -366,6 +366,16 @@ def config5(small: bool = False) -> SharedPrefixCase:
     return SharedPrefixCase(prefix=prefix, suffix=suffix, single=single)
 
 
+def short_append(qo_len: int, batch: int, kv_max: int) -> PagedBatch:
+    """Every request appends `qo_len` tokens (a verification step of speculative decoding, a chunk of a chunked
+    prefill) to a cache of U{kv_max/4 .. kv_max - 1} tokens (the new tokens included); causal; GQA 32/8, D 128, bf16,
+    page 16.  No NaN poisoning (these are timing inputs)."""
+    g = np.random.Generator(np.random.PCG64(1100 + qo_len))
+    kv = np.maximum(g.integers(kv_max // 4, kv_max, size=batch), qo_len)
+    return make_batch(f"short_append_qo{qo_len}_bs{batch}_kv{kv_max}", 1100 + qo_len, BF16, 32, 8, 128, 16,
+                      [qo_len] * batch, kv, causal=True, poison=False)
+
+
 def random_case(seed: int, *, dtype: str = BF16, num_qo_heads: int = 32, num_kv_heads: int = 8,
                 head_dim: int = 128, page_size: int = 16, batch: int = 5, max_qo: int = 1,
                 max_kv: int = 300, causal: bool = False, allow_empty: bool = True,
