@@ -10,11 +10,12 @@
 // step are loaded once per wavefront whatever NB is.  Only NB = 1 is instantiated: measured on the shared-prefix
 // workload (64 queries x 4 096 keys + 64 suffixes), NB = 1 at two wavefronts per SIMD takes 32 us, NB = 2 at one
 // wavefront per SIMD 35 us, NB = 4 (which needs more than the 512 registers of a lone wavefront and spills) 71 us:
-// the re-reads of the prefix hit in the XCD's L2 and are not what bounds the launch.  Neither is the count of vector
-// instructions (about 255 per 32-token step): a build with the K/V address arithmetic moved to scalar registers
-// (buffer loads off per-page descriptors) ran 2.8 us slower, one with the softmax scale folded into the exponent's
-// multiply-add 0.7 us slower.  What remains is the rate of 16-byte-per-lane requests through the CU's vector cache
-// (451 MB per launch, 28 bytes per clock and CU) with two wavefronts per SIMD to hide it.
+// the re-reads of the prefix hit in the XCD's L2 and are not what bounds the launch (the 64-row tile kernel cuts
+// them fourfold and gains 10 %).  Neither is the count of vector instructions (about 255 per 32-token step): a build
+// with the K/V address arithmetic moved to scalar registers (buffer loads off per-page descriptors) ran 2.8 us
+// slower, one with the softmax scale folded into the exponent's multiply-add 0.7 us slower.  A step is a chain of
+// dependent phases (K through LDS, product, softmax, product) of one in-order wavefront, and with 239 registers
+// only two wavefronts share a SIMD to overlap it.
 // bf16: P enters the second product as head + remainder (see decode.hip).
 //
 // Causal items mask per row: row R sees chunk tokens <= diag0 - kv_start + position(R).  A row that has seen no
