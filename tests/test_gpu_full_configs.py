@@ -53,6 +53,20 @@ def test_config3_full_causal_append():
     sampled_check(b, "append", list(range(b.batch)), "c3 full")
 
 
+@pytest.mark.parametrize("mode", ["tile16", "tile64"])
+def test_full_decode_and_append_batches_through_the_tile_modes(mode):
+    """The benchmark's decode and causal-append batches through the 16-row and 64-row tile kernels at the library's
+    default grid: one-position tiles with long split chunks (a 32 768-token request), and tiles of 16 / g and 64 / g
+    positions over 16 requests of 128..1 024 new tokens (hundreds of work items per CTA queue); a sample of requests
+    against the oracle, every row checked for NaN."""
+    b = workloads.config2()
+    sampled_check(b, mode, [0, 1, 5, 17, 64, 127], f"c2 full as {mode}")
+    b = workloads.config3()
+    sampled_check(b, mode, [0, 1, 2, 9, 15], f"c3 full as {mode}")
+    b = workloads.config3(page_size=32)
+    sampled_check(b, "append", [1, 2, 7, 12], "c3 full, page size 32 (the scheduled loop's page-size variant)")
+
+
 def test_config5_full_shared_prefix():
     import torch
     import paper_2501_01005_amd as fi
