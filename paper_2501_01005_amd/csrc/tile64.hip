@@ -4,8 +4,8 @@
 //   wide  (more than 16 live rows: a block of queries over a shared prefix, Sec. 3.1.2; a short append): wavefront w
 //         owns rows 16 w .. 16 w + 15, and the four stage every 32-token step of K and V through LDS, a quarter of
 //         the rows each, so that the CTA reads a K/V row once whatever the number of rows (the 16-row tile kernel
-//         re-reads it per 16 rows: on the shared-prefix workload 451 MB of L2 requests for 92 MB of K/V, and the
-//         rate of those requests, not instruction issue, bounded it);
+//         re-reads it per 16 rows: on the shared-prefix workload 451 MB of L2 requests for 92 MB of K/V; cutting
+//         them fourfold gains 10 % there, the steps being chains of dependent phases rather than waits for data);
 //   light (at most 16 live rows: a decode step): all four wavefronts hold the same rows, wavefront w walks steps
 //         w, w + 4, ... of the chunk on its own (K through a private LDS area, V in registers, streaming loads),
 //         and wavefront 0 merges the four states (Sec. 2.2) through LDS before the epilogue.  Four wavefronts side
