@@ -105,3 +105,72 @@ def test_random_variants_fp8_and_contiguous(seed):
         else:
             o, lse = run_gpu(b, mode, contiguous=(kind == "contig"), **kw)
         assert_close(o, lse, o_ref, lse_ref, what)
+
+
+@pytest.mark.parametrize("mode", ["tile16", "tile64"])
+def test_random_plans_over_two_and_three_formats(mode):
+    """Random row partitions and page lists per format (Sec. 3.1.2), planned as one work list and run in one launch;
+    expected: each format's attention by the oracle, then the oracle's merge of the states (Sec. 2.2: the merged state
+    is the attention over the union of the formats' keys)."""
+    import dataclasses
+    import torch
+    from oracle.attention import merge_pair
+    from gpu_util import DeviceBatch
+    from paper_2501_01005_amd.device import formats_of, make_formats_wrapper
+    rng = np.random.default_rng(31 if mode == "tile16" else 32)
+    for case in range(40):
+        g = int(rng.choice([1, 2, 4, 8]))
+        hkv = int(rng.choice([1, 2]))
+        dtype = workloads.F16 if rng.integers(2) else workloads.BF16
+        n_rows = int(rng.integers(1, 50))
+        n_formats = int(rng.integers(2, 4))
+        cuts_of, kv_of = [], []
+        for f in range(n_formats):
+            if f == 0 and rng.integers(2):
+                cuts = [0, n_rows]                                      # a shared prefix: one row block
+            else:
+                cuts = sorted(set(rng.integers(0, n_rows + 1, size=int(rng.integers(0, n_rows + 1))).tolist()) | {0, n_rows})
+            cuts_of.append(np.array(cuts))
+            kv_of.append(rng.integers(0, int(rng.choice([50, 400, 2000])), size=len(cuts) - 1))
+        # one pool for all formats: the requests of all formats one after the other; the query rows ride on the first
+        # format's requests
+        qo_all = np.concatenate([np.diff(cuts_of[0])] + [np.zeros(len(k), dtype=np.int64) for k in kv_of[1:]])
+        kv_all = np.concatenate(kv_of)
+        data_seed = 7000 + int(rng.integers(100000))
+        base = workloads.make_batch("formats_pool", data_seed, dtype, g * hkv, hkv, 128, 16, qo_all, kv_all, False,
+                                    num_pages=int(((kv_all + 15) // 16).sum()) + 2, value_scale=float(rng.choice([0.5, 1.0, 2.0])))
+        batches, first = [], 0
+        for f in range(n_formats):
+            n_req = len(kv_of[f])
+            p0 = int(base.kv_indptr[first])
+            batches.append(dataclasses.replace(
+                base, name=f"format{f}", qo_indptr=cuts_of[f].astype(np.int32),
+                kv_indptr=(base.kv_indptr[first:first + n_req + 1] - p0).astype(np.int32),
+                kv_indices=base.kv_indices[p0:int(base.kv_indptr[first + n_req])].copy(),
+                last_page_len=base.last_page_len[first:first + n_req].copy()))
+            first += n_req
+        kw = {}
+        if rng.integers(2):
+            kw["num_ctas"] = hkv * int(rng.choice([1, 3, 16, 64]))
+        if rng.integers(2):
+            kw["min_chunk"] = int(rng.choice([16, 32, 128]))
+        what = (f"formats {mode}/{case}: g={g} hkv={hkv} {dtype} rows={n_rows} cuts={[c.tolist() for c in cuts_of]} "
+                f"kv={[k.tolist() for k in kv_of]} kw={kw} data_seed={data_seed}")
+        print("[case] " + what, flush=True)
+        o_ref, lse_ref = oracle.run_batch(batches[0])
+        for b in batches[1:]:
+            o_f, lse_f = oracle.run_batch(b)
+            o_ref, lse_ref = merge_pair(o_ref, lse_ref, o_f, lse_f)
+        formats, ids = formats_of(batches)
+        w = make_formats_wrapper(batches, mode=mode, **kw)
+        dev = DeviceBatch(batches[0])
+        ids_dev = torch.from_numpy(ids).to("cuda:0")
+        w.workspace.view(torch.float32)[w.pin_bytes // 4:].fill_(float("nan"))
+        w.plan_formats(formats)
+        H = g * hkv
+        o = torch.full((n_rows, H, 128), float("nan"), dtype=torch.float32, device="cuda:0")
+        lse = torch.full((n_rows, H), float("nan"), dtype=torch.float32, device="cuda:0")
+        w.run(dev.q, dev.k_pool, dev.v_pool, ids_dev, base.sm_scale, o=o, lse=lse)
+        torch.cuda.synchronize()
+        w.close()
+        assert_close(o.double().cpu().numpy(), lse.double().cpu().numpy(), o_ref, lse_ref, what)
