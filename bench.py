@@ -134,7 +134,8 @@ def bench_shared_prefix(args) -> int:
     side = torch.cuda.Stream() if args.graph and args.c5_path != "formats" else None  # default priority
     # both formats as one plan of one handle (fi_plan_formats): one attention launch + one contraction launch
     formats, ids = formats_of([c.prefix, c.suffix])
-    wf = make_formats_wrapper([c.prefix, c.suffix], mode=args.tile_mode, num_ctas=args.num_ctas, min_chunk=args.min_chunk)
+    wf = make_formats_wrapper([c.prefix, c.suffix], mode=args.tile_mode, num_ctas=args.num_ctas, min_chunk=args.min_chunk,
+                              alpha=args.alpha, beta=args.beta)
     ids_dev = torch.from_numpy(ids).to("cuda:0")
 
     def composed(plan=True):
