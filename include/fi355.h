@@ -325,6 +325,14 @@ int32_t fi_run_composed_static(fi_handle* h_a, fi_handle* h_b, const void* q, co
                                const int32_t* kv_indices_b, float sm_scale, int64_t nnz_qo, float* o,
                                float* lse, void* o_cast, fi_stream stream);
 
+/* HOST helper: which handle mode to create for a batch whose requests bring `mean_qo_len` query positions each on
+ * average (Sec. 3.2.2 picks the query tile size from the average query length; here the tile size is the handle's
+ * mode).  With g = num_qo_heads / num_kv_heads fused rows per position: one position -> FI_MODE_DECODE; at most 16
+ * fused rows per request -> FI_MODE_TILE64 (its four wavefronts walk a chunk side by side); more -> FI_MODE_APPEND
+ * (the 256-row matrix kernel wins from there on although most of its rows are empty).  Measured on this part at
+ * g = 4, page size 16; a rule of thumb, not a guarantee.  Returns the mode, or FI_ERR_INVALID_ARG (< 0). */
+int32_t fi_suggest_mode(int32_t num_qo_heads, int32_t num_kv_heads, double mean_qo_len);
+
 /* HOST helper for tests: FI_OK iff every indices[i] is in [0, num_pages). */
 int32_t fi_check_indices(const int32_t* indices_host, int64_t n, int32_t num_pages);
 

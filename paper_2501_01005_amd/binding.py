@@ -14,7 +14,7 @@ __all__ = [
     "FI_ERR_HIP", "FI_ERR_HOST_MEMORY", "FI_DTYPE_F16", "FI_DTYPE_BF16", "FI_MODE_DECODE", "FI_MODE_APPEND", "FI_MODE_TILE16", "FI_MODE_TILE64",
     "Fi355Error", "fi_config", "fi_plan_arrays", "lib", "library_path",
     "fi_create", "fi_destroy", "fi_workspace_bytes", "fi_plan", "fi_plan_formats", "fi_plan_view", "fi_run", "fi_run_kv8",
-    "fi_run_variant", "fi_run_composed", "fi_run_composed_static", "fi_variant", "fi_merge_states", "fi_merge_state_pair", "fi_check_indices", "fi_set_timing_events", "fi_last_error",
+    "fi_run_variant", "fi_run_composed", "fi_run_composed_static", "fi_variant", "fi_merge_states", "fi_merge_state_pair", "fi_check_indices", "fi_suggest_mode", "fi_set_timing_events", "fi_last_error",
     "PagedAttention",
 ]
 
@@ -99,6 +99,8 @@ def _load() -> ctypes.CDLL:
                                   vp, vp, vp, vp]
     L.fi_run_composed_static.argtypes = [vp, vp, vp, vp, vp, ctypes.POINTER(i64), vp, vp, ctypes.c_float, i64, vp, vp, vp, vp]
     L.fi_check_indices.argtypes = [vp, i64, i32]
+    L.fi_suggest_mode.argtypes = [i32, i32, ctypes.c_double]
+    L.fi_suggest_mode.restype = i32
     L.fi_set_timing_events.argtypes = [vp, vp, vp]
     L.fi_last_error.argtypes = []
     L.fi_last_error.restype = ctypes.c_char_p
@@ -262,6 +264,14 @@ def fi_run_composed_static(handle_a: int, handle_b: int, q, k_pool, v_pool, kv_s
 
 def fi_set_timing_events(handle: int, before, after) -> None:
     _check(lib.fi_set_timing_events(handle, before, after))
+
+
+def fi_suggest_mode(num_qo_heads: int, num_kv_heads: int, mean_qo_len: float) -> str:
+    """the PagedAttention mode name for a batch of that average query length"""
+    rc = lib.fi_suggest_mode(num_qo_heads, num_kv_heads, float(mean_qo_len))
+    if rc < 0:
+        _check(rc)
+    return {FI_MODE_DECODE: "decode", FI_MODE_APPEND: "append", FI_MODE_TILE16: "tile16", FI_MODE_TILE64: "tile64"}[rc]
 
 
 def fi_check_indices(indices, num_pages: int) -> None:

@@ -603,6 +603,15 @@ int32_t fi_merge_state_pair(const float* o_a, const float* lse_a, const float* o
   return FI_OK;
 }
 
+int32_t fi_suggest_mode(int32_t num_qo_heads, int32_t num_kv_heads, double mean_qo_len) {
+  if (num_qo_heads <= 0 || num_kv_heads <= 0 || num_qo_heads % num_kv_heads != 0 || !(mean_qo_len >= 0))
+    return set_error(FI_ERR_INVALID_ARG, "fi_suggest_mode: heads must be positive, num_qo_heads a multiple of num_kv_heads, mean_qo_len >= 0");
+  const double rows = mean_qo_len * (num_qo_heads / num_kv_heads);  // fused rows per request and kv head
+  if (mean_qo_len <= 1.0) return FI_MODE_DECODE;
+  if (rows <= 16.0) return FI_MODE_TILE64;
+  return FI_MODE_APPEND;
+}
+
 int32_t fi_check_indices(const int32_t* indices_host, int64_t n, int32_t num_pages) {
   if (n < 0 || (n > 0 && !indices_host)) return set_error(FI_ERR_INVALID_ARG, "fi_check_indices: bad arguments");
   for (int64_t i = 0; i < n; ++i)
@@ -674,6 +683,10 @@ int32_t fi_merge_states(const float* o_parts, const float* lse_parts, int64_t n_
 
 int32_t fi_merge_state_pair(const float* o_a, const float* lse_a, const float* o_b, const float* lse_b, int64_t n_rows, int32_t head_dim, float* o, float* lse, fi_stream stream) {
   return guarded([&]() -> int32_t { return impl::fi_merge_state_pair(o_a, lse_a, o_b, lse_b, n_rows, head_dim, o, lse, stream); });
+}
+
+int32_t fi_suggest_mode(int32_t num_qo_heads, int32_t num_kv_heads, double mean_qo_len) {
+  return guarded([&]() -> int32_t { return impl::fi_suggest_mode(num_qo_heads, num_kv_heads, mean_qo_len); });
 }
 
 int32_t fi_check_indices(const int32_t* indices_host, int64_t n, int32_t num_pages) {

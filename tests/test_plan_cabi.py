@@ -455,3 +455,12 @@ def test_plan_formats_argument_errors():
         fi.fi_plan_formats(hd, [(qo2, kv2, last2, 0)])
     assert e.value.code == fi.FI_ERR_UNSUPPORTED
     fi.fi_destroy(hd)
+
+
+def test_suggested_mode_follows_the_mean_query_length():
+    assert fi.fi_suggest_mode(32, 8, 1.0) == "decode" and fi.fi_suggest_mode(8, 8, 0.5) == "decode"
+    assert fi.fi_suggest_mode(32, 8, 4.0) == "tile64" and fi.fi_suggest_mode(8, 8, 16.0) == "tile64"
+    assert fi.fi_suggest_mode(32, 8, 5.0) == "append" and fi.fi_suggest_mode(32, 2, 2.0) == "append"
+    with pytest.raises(fi.Fi355Error) as e:
+        fi.fi_suggest_mode(6, 4, 1.0)
+    assert e.value.code == fi.FI_ERR_INVALID_ARG
