@@ -235,6 +235,17 @@ def test_argument_errors():
     expect(fi.FI_ERR_INVALID_ARG, fi.fi_check_indices, [0, -1], 5)
     fi.fi_check_indices([0, 4, 2], 5)
     expect(fi.FI_ERR_UNSUPPORTED, fi.fi_merge_states, dummy, dummy, 1, 1, 64, dummy, dummy)
+    # the tile modes: page size 16 only, no planned window, no in-launch contraction, no variants, no 8-bit cache
+    for mode in (fi.FI_MODE_TILE16, fi.FI_MODE_TILE64):
+        expect(fi.FI_ERR_UNSUPPORTED, fi.fi_create, **{**ok, "mode": mode, "page_size": 8})
+        expect(fi.FI_ERR_UNSUPPORTED, fi.fi_create, **{**ok, "mode": mode, "plan_window": 9})
+        expect(fi.FI_ERR_UNSUPPORTED, fi.fi_create, **{**ok, "mode": mode, "merge": 2})
+        ht = fi.fi_create(**{**ok, "mode": mode})
+        expect(fi.FI_ERR_UNSUPPORTED, fi.fi_run_variant, ht, dummy, dummy, dummy, (8, 8, 8), dummy, dummy, dummy, 1.0, dummy, dummy,
+               window_left=5)
+        expect(fi.FI_ERR_UNSUPPORTED, fi.fi_run_kv8, ht, dummy, dummy, dummy, (8, 8, 8), dummy, 1.0, 1.0, 1.0, dummy, dummy)
+        fi.fi_destroy(ht)
+    expect(fi.FI_ERR_INVALID_ARG, fi.fi_create, **{**ok, "mode": 4})
 
 
 def test_header_is_plain_c():
