@@ -149,7 +149,8 @@ __device__ __forceinline__ void reduce_states(const RowStates<T>& rs, int n, int
   }
 }
 
-// Any number of states, 32 loads in flight at a time.
+// Any number of states, T loads in flight at a time (the sums and their order do not depend on T).
+template <int T = 32>
 __device__ __forceinline__ void fold_row_wave(const float* lse_ptr, int64_t lse_stride, const float* o_ptr,
                                               int64_t o_stride, int n, int lane, f32x2_t* o_out, float* lse_out) {
   const float NEG_INF = -__builtin_inff();
@@ -166,13 +167,13 @@ __device__ __forceinline__ void fold_row_wave(const float* lse_ptr, int64_t lse_
     const float w_mine =
         (s0 + lane < n) ? __builtin_amdgcn_exp2f((lse_ptr[(s0 + lane) * lse_stride] - mx_safe) * kLog2e) : 0.f;
     const int cnt = min(64, n - s0);
-    for (int j0 = 0; j0 < cnt; j0 += 32) {
-      f32x2_t v[32];
+    for (int j0 = 0; j0 < cnt; j0 += T) {
+      f32x2_t v[T];
 #pragma unroll
-      for (int u = 0; u < 32; ++u)
+      for (int u = 0; u < T; ++u)
         v[u] = *reinterpret_cast<const f32x2_t*>(o_ptr + min(s0 + j0 + u, n - 1) * o_stride + 2 * lane);
 #pragma unroll
-      for (int u = 0; u < 32; ++u) {
+      for (int u = 0; u < T; ++u) {
         const int st = s0 + j0 + u;
         if (st < n) {
           if (st == next) {
@@ -256,8 +257,9 @@ __global__ void __launch_bounds__(64 * kMergeWaves) merge_planned_kernel(const M
         load_states<8>(&rs, p.part_lse + slot_row0, slot_stride, p.part_o + slot_row0 * kHeadDim, slot_stride * kHeadDim, n, lane);
         reduce_states<8>(rs, n, lane, &o2, &l);
       } else {
-        fold_row_wave(p.part_lse + slot_row0, slot_stride, p.part_o + slot_row0 * kHeadDim, slot_stride * kHeadDim, n,
-                      lane, &o2, &l);
+        // (eight loads in flight: the kernel stays within 128 registers, two CTAs per CU, for the other way too)
+        fold_row_wave<8>(p.part_lse + slot_row0, slot_stride, p.part_o + slot_row0 * kHeadDim, slot_stride * kHeadDim, n,
+                         lane, &o2, &l);
       }
       planned_store(p, (static_cast<int64_t>(p.m_q_row0[mt]) + pos) * H + head, lane, o2, l);
     }
