@@ -199,7 +199,9 @@ struct WorkItem {
 // slope times log2(e) (0: none), `win` = window_left (a huge value: none).
 // PSL: the variant for page sizes 4, 8 and 32: `g_log2` carries log2 of the page size in bits 8.., `ids_clamp` and
 // `page_ids` count pages of that size, and the per-lane row offsets hold the row's place inside its page.
-template <bool BF, bool CAP, bool CONTIG, bool VARL, bool PSL = false>
+// ROWS: the variant for page sizes 1 and 2 (a page id per token row, 64-bit addresses per lane): operands as for PSL,
+// except that the row flags are not passed (the loop needs the register and finds the lanes that write lse itself).
+template <bool BF, bool CAP, bool CONTIG, bool VARL, bool PSL = false, bool ROWS = false>
 __device__ __forceinline__ void run_scheduled_loop(int n_full, int n_tiles, int kv_len, int cap, int st_tok, int ids_clamp, const int32_t* page_ids, uint32_t k_lo,
                                                    uint32_t k_hi, uint32_t v_lo, uint32_t v_hi, uint32_t page_bytes,
                                                    float scale_log2, uint64_t q_addr, uint32_t st_off_bytes,
@@ -217,7 +219,7 @@ __device__ __forceinline__ void run_scheduled_loop(int n_full, int n_tiles, int 
           [nkl] "=&s"(next.kv_len), [ndg] "=&s"(next.diag0), [nos] "=&s"(next.out_slot), [preo] "=&s"(prefetched_out)        \
         : [nf] "s"(n_full), [nt] "s"(n_tiles), [kvl] "s"(kv_len), [cap] "v"(cap), [stk] "v"(st_tok), [npg1] "s"(ids_clamp), [idp] "s"(page_ids), [kblo] "s"(k_lo), [kbhi] "s"(k_hi), \
           [vblo] "s"(v_lo), [vbhi] "s"(v_hi), [sp] "s"(page_bytes), [sc] "s"(scale_log2),                                 \
-          [qp] "v"(q_addr), [so] "v"(st_off_bytes), [sok] "v"(k_off_bytes), [kb] "v"(k_read), [kxs] "v"(k_swizzle),        \
+          [qp] "v"(q_addr), FI355_STAGING_OFFSETS [kb] "v"(k_read), [kxs] "v"(k_swizzle),        \
           [va] "v"(v_read), [kd] "s"(k_dma), [wv] "v"(v_write), [ooff] "v"(o_off), FI355_ROW_FLAGS [ob] "s"(o_base), [lb] "s"(lse_base), \
           [cb] "s"(cast_base), [oc] "s"(has_cast), [ew] "v"(epi_write), [er] "v"(epi_read), [l16] "v"(epi_chunk),          \
           [gl] "s"(g_log2), FI355_HEADS_AND_POSITIONS [rb] "s"(row_base), [stp8] "s"(wave_index),                          \
@@ -225,6 +227,7 @@ __device__ __forceinline__ void run_scheduled_loop(int n_full, int n_tiles, int 
           [idblo] "s"(all_ids_lo), [idbhi] "s"(all_ids_hi)
   // (the bias / window variant has a per-lane and a scalar operand more than there are registers left: it finds the
   // lanes that write lse itself instead of taking row_flags, and takes n_pos and num_qo_heads packed into g_log2)
+#define FI355_STAGING_OFFSETS [so] "v"(st_off_bytes), [sok] "v"(k_off_bytes),
 #define FI355_ROW_FLAGS
 #define FI355_HEADS_AND_POSITIONS
   if constexpr (VARL && BF) {
@@ -244,9 +247,26 @@ __device__ __forceinline__ void run_scheduled_loop(int n_full, int n_tiles, int 
   }
 #undef FI355_ROW_FLAGS
 #undef FI355_HEADS_AND_POSITIONS
-#define FI355_ROW_FLAGS [rok] "v"(row_flags),
 #define FI355_HEADS_AND_POSITIONS [hq] "s"(num_qo_heads), [np] "s"(n_pos),
-  if constexpr (VARL) {
+#define FI355_ROW_FLAGS
+  if constexpr (ROWS && BF) {
+    asm volatile(
+#include "append_loop_bf16_rows.inc"
+        FI355_LOOP_OPERANDS
+        :
+#include "append_loop_clobbers.inc"
+    );
+  } else if constexpr (ROWS) {
+    asm volatile(
+#include "append_loop_f16_rows.inc"
+        FI355_LOOP_OPERANDS
+        :
+#include "append_loop_clobbers.inc"
+    );
+  }
+#undef FI355_ROW_FLAGS
+#define FI355_ROW_FLAGS [rok] "v"(row_flags),
+  if constexpr (VARL || ROWS) {
   } else if constexpr (PSL && BF) {
     asm volatile(
 #include "append_loop_bf16_ps.inc"
@@ -307,6 +327,7 @@ __device__ __forceinline__ void run_scheduled_loop(int n_full, int n_tiles, int 
 #undef FI355_LOOP_OPERANDS
 #undef FI355_ROW_FLAGS
 #undef FI355_HEADS_AND_POSITIONS
+#undef FI355_STAGING_OFFSETS
 }
 
 // K tiles, then V tiles (three buffers each: the scheduled loop rotates over three, the generic
@@ -807,13 +828,14 @@ __device__ __attribute__((noinline)) void generic_work_item(uint64_t params_addr
 // ROPE (with VAR, no loop variant): every item on the general path, queries and keys rotated by their positions.
 struct NoRopeTable {};
 template <bool BF, bool VAR = false, bool CAPLOOP = false, bool CONTIG = false, bool VARLOOP = false, bool ROPE = false,
-          bool PSLOOP = false>
+          bool PSLOOP = false, bool ROWLOOP = false>
 __global__ void __launch_bounds__(kCtaThreads) __attribute__((amdgpu_waves_per_eu(2, 2)))
 append_kernel(const RunParams p, const typename std::conditional<ROPE, RopeTable, NoRopeTable>::type rope) {
   static_assert(!CONTIG || !VAR, "affine addressing is built for the plain kernel");
   static_assert(!(CAPLOOP && VARLOOP) && (!VARLOOP || VAR), "one variant of the loop per instantiation");
   static_assert(!ROPE || (VAR && !CAPLOOP && !VARLOOP), "the rotary transform is built into the general path");
   static_assert(!PSLOOP || (!VAR && !CONTIG), "the loop for other page sizes is the plain one");
+  static_assert(!ROWLOOP || PSLOOP, "the per-row loop is a kind of the loop for other page sizes");
   const int tid = threadIdx.x;
   if constexpr (ROPE) {
     if (tid < 64) {
@@ -852,8 +874,12 @@ append_kernel(const RunParams p, const typename std::conditional<ROPE, RopeTable
       // (the loop addresses its outputs with 32-bit byte offsets)
       const int64_t out_rows_bound = (out_slot < 0 ? static_cast<int64_t>(q_row0) + p.t_pos : (static_cast<int64_t>(out_slot) + 1) * p.t_pos) * H;
       // (PSLOOP: page sizes 4, 8, 32: a wavefront's four consecutive rows per load lie in one page, and the two
-      // 32-token halves of a tile in different pages or in the two halves of one)
-      if ((PSLOOP ? (p.page_log2 == 2 || p.page_log2 == 3 || p.page_log2 == 5) : p.page_log2 == 4) && n_full >= 1 && kv_len >= kLoopMinTokens && page_bytes > 0 && page_bytes < (int64_t(1) << 32) &&
+      // 32-token halves of a tile in different pages or in the two halves of one;
+      // ROWLOOP: page sizes 1 and 2: a page id per token row, 64-bit addresses per lane)
+      if ((ROWLOOP  ? p.page_log2 <= 1
+           : PSLOOP ? (p.page_log2 == 2 || p.page_log2 == 3 || p.page_log2 == 5)
+                    : p.page_log2 == 4) &&
+          n_full >= 1 && kv_len >= kLoopMinTokens && page_bytes > 0 && page_bytes < (int64_t(1) << 32) &&
           (!VARLOOP || H < 65536) &&  // (that variant takes num_qo_heads in 16 bits of an operand)
           out_rows_bound * (kHeadDim * 4) < (int64_t(1) << 32)) {
         // The loop clobbers nearly every vector register, so its lane-dependent operands are
@@ -897,7 +923,7 @@ append_kernel(const RunParams p, const typename std::conditional<ROPE, RopeTable
         if constexpr (VARLOOP) {
           if (p.alibi_slopes != nullptr) slope_o = p.alibi_slopes[head] * 1.4426950408889634f;
         }
-        run_scheduled_loop<BF, CAPLOOP, CONTIG, VARLOOP, PSLOOP>(n_full, (kv_len + kTileKv - 1) / kTileKv, kv_len, seen_bound - 4 * c_o, st_tok_o,
+        run_scheduled_loop<BF, CAPLOOP, CONTIG, VARLOOP, PSLOOP, ROWLOOP>(n_full, (kv_len + kTileKv - 1) / kTileKv, kv_len, seen_bound - 4 * c_o, st_tok_o,
                                (chunk_pages - 1) * 4, p.kv_indices + kv_page0, static_cast<uint32_t>(k_base),
                                static_cast<uint32_t>(k_base >> 32), static_cast<uint32_t>(v_base),
                                static_cast<uint32_t>(v_base >> 32), static_cast<uint32_t>(page_bytes),
@@ -976,6 +1002,13 @@ hipError_t launch_append(const RunParams& p, bool is_bf16, bool variant, const R
       hipLaunchKernelGGL((append_kernel<true, true>), grid, block, 0, stream, p, NoRopeTable{});
     else
       hipLaunchKernelGGL((append_kernel<false, true>), grid, block, 0, stream, p, NoRopeTable{});
+    return hipGetLastError();
+  }
+  if (p.kv_indices != nullptr && p.page_log2 <= 1) {  // page sizes 1 and 2: the loop with a page id per token row
+    if (is_bf16)
+      hipLaunchKernelGGL((append_kernel<true, false, false, false, false, false, true, true>), grid, block, 0, stream, p, NoRopeTable{});
+    else
+      hipLaunchKernelGGL((append_kernel<false, false, false, false, false, false, true, true>), grid, block, 0, stream, p, NoRopeTable{});
     return hipGetLastError();
   }
   if (p.kv_indices != nullptr && (p.page_log2 == 2 || p.page_log2 == 3 || p.page_log2 == 5)) {  // their variant of the loop

@@ -53,6 +53,8 @@ S_IDK = 88                     # page ids of the tile whose K goes to LDS next (
 S_ONES = 98                    # var variant: fp16 ones in both halves (the vector register of the constant is needed otherwise)
 S_NP, S_HQ = 99, 100           # var variant: n_pos and num_qo_heads, unpacked from %[gl]
 S_PSL, S_W4 = 98, 99           # page-size variant: log2 of the page size (from %[gl]); 4 * (wavefront % 4) = first row of its row group
+S_G0, S_G1 = 68, 88            # per-row variant: two groups of eight page ids (a wavefront's 2 x 4 rows of a tile); there S_W4 = 4 * wavefront
+ROW_MASKS = ((0xffff, 0), (0xffff0000, 0), (0, 0xffff), (0, 0xffff0000))   # exec_lo, exec_hi of the 16 lanes that load row q
 S_M0 = 97                      # saved m0 (the register doubles as half of S_EXEC, which is used only after m0 is restored)
 S_NX = 92                      # this wavefront's page ids of tiles 0 and 1 of the CTA's next work item (takes over S_IDB after start-up)
 S_STP = 96                     # which page of a 32-token half this thread's staging rows are in (wavefront / 4); the epilogue reuses the register
@@ -79,6 +81,13 @@ def vr(base, n=1):
     return 'v%d' % base if n == 1 else 'v[%d:%d]' % (base, base + n - 1)
 
 
+def emit_item(e, o):
+    """one instruction, or a tuple of instructions that must follow each other directly (vector moves under a
+    narrowed exec mask: nothing else may run while the mask is narrow)"""
+    for x in (o if isinstance(o, tuple) else (o,)):
+        e.emit(x)
+
+
 def spread(e, mfmas, others):
     """each matrix instruction is followed by an even share of the other instructions"""
     n = len(mfmas)
@@ -87,7 +96,7 @@ def spread(e, mfmas, others):
         e.emit(m)
         hi = (len(others) * (i + 1)) // n
         for o in others[k:hi]:
-            e.emit(o)
+            emit_item(e, o)
         k = hi
 
 
@@ -104,8 +113,22 @@ def merge_even(*lists):
 
 
 class Gen:
-    def __init__(self, bf16, cap=False, contig=False, var=False, anyps=False):
+    def __init__(self, bf16, cap=False, contig=False, var=False, anyps=False, rowids=False):
         self.bf = bf16
+        # Page sizes 1 and 2 (the plain loop): the four token rows a wavefront stages per load lie in different pages,
+        # so a lane addresses its row with 64 bits: pool base + page id * page bytes + the lane's offset in the row
+        # group.  The ids of a wavefront's rows are scalar as before; a lane picks its row's id by four moves under
+        # exec masks of 16 lanes.  A wavefront needs 2 x 4 ids per tile; two groups of eight scalar registers alternate: K of tile
+        # t + 2 is requested from group 0 at the head of tile t, which then receives the ids of tile t + 4; V of tile
+        # t + 3 is requested from group 1 at the tile's end; after the barrier (which waits for the ids) the groups
+        # swap.  The next work item's first tiles are not requested ahead (sixteen more scalar registers), and the
+        # row flags are found in the epilogue as in the bias / window variant (the operand's register is needed).
+        self.rowids = rowids
+        assert not (rowids and (cap or contig or var or anyps))
+        self.norok = var or rowids
+        # in the tile loop: ids of the tile whose K is requested next / where the ids requested at a tile's head go /
+        # ids of the tile whose V is requested at the tile's end
+        self.gk, self.gn, self.gs = (S_G0, S_G0, S_G1) if rowids else (S_IDK, S_IDN, S_IDS)
         # Page sizes 4, 8 and 32 (the plain loop): a wavefront stages four consecutive token rows per load, all in one
         # page, so what changes is which page id it fetches for them: token (64 t + 16 r + first row of its group)
         # >> log2(page size) of the chunk, for each 16-token segment r of tile t.  The row's place inside its page
@@ -280,6 +303,23 @@ class Gen:
                 ops.append('v_cndmask_b32 v%d, 0, v%d, vcc' % (x, x))
         return ops
 
+    def row_ids(self, ids, dst):
+        """v<dst> <- the page id of this lane's row: s[ids + q] for the 16 lanes of row q (one unit: nothing else may
+        run while the exec mask is narrow)"""
+        ops = []
+        for q, (lo, hi) in enumerate(ROW_MASKS):
+            ops += ['s_mov_b32 exec_lo, 0x%x' % lo, 's_mov_b32 exec_hi, 0x%x' % hi, 'v_mov_b32 v%d, s%d' % (dst, ids + q)]
+        return tuple(ops + ['s_mov_b64 exec, -1'])
+
+    def row_address(self, dst, idreg, tmp, spair, lo, hi, off):
+        """v[dst:dst+1] <- pool base + page id * page bytes + this lane's offset in the row group (vcc is clobbered:
+        callers place this where no comparison result is pending)"""
+        return ['s_mov_b32 s%d, %%[%s]' % (spair, lo), 's_mov_b32 s%d, %%[%s]' % (spair + 1, hi),
+                'v_mov_b32 v%d, %%[sp]' % tmp,
+                'v_mad_u64_u32 %s, s[%d:%d], v%d, v%d, s[%d:%d]' % (vr(dst, 2), S_LO, S_HI, idreg, tmp, spair, spair + 1),
+                'v_add_co_u32 v%d, vcc, v%d, %%[%s]' % (dst, dst, off),
+                'v_addc_co_u32 v%d, vcc, 0, v%d, vcc' % (dst + 1, dst + 1)]
+
     def page_select(self, ids):
         return ['s_cmp_eq_u32 s%d, 0' % S_STP,
                 's_cselect_b32 s%d, s%d, s%d' % (S_PG0, ids, ids + 1),
@@ -288,6 +328,13 @@ class Gen:
     def fetch(self, ids=S_IDS, base=ST):
         """global loads of the V rows of the tile whose four page ids are in s[ids..+3]; this
         thread's two pages are 2 r + st_page, r = 0, 1"""
+        if self.rowids:  # (address and id pass through the registers the load then fills)
+            ops = []
+            for r in range(2):
+                dst = base + 8 + 4 * r
+                ops += [self.row_ids(ids + 4 * r, dst + 2)] + self.row_address(dst, dst + 2, dst + 3, S_VA, 'vblo', 'vbhi', 'so')
+                ops.append('global_load_dwordx4 %s, %s, off' % (vr(dst, 4), vr(dst, 2)))
+            return ops
         ops = self.page_select(ids)
         for r, pg in enumerate((S_PG0, S_PG1)):
             ops += ['s_mul_hi_u32 s%d, s%d, %%[sp]' % (S_HI, pg), 's_mul_i32 s%d, s%d, %%[sp]' % (S_LO, pg),
@@ -299,6 +346,13 @@ class Gen:
         """K rows of that tile straight into LDS buffer `buf` (no registers, no LDS store
         instruction): a wavefront's load lands as 1 KB = its four consecutive 256-byte rows at m0,
         lane l at m0 + 16 l, and each lane fetches the chunk that the swizzle puts there"""
+        if self.rowids:
+            ops = []
+            for r in range(2):
+                ops += [self.row_ids(ids + 4 * r, X0)] + self.row_address(X0, X0, X1, S_KA, 'kblo', 'kbhi', 'sok')
+                ops += ['s_add_u32 m0, %%[kd], %d' % (buf * KTILE + r * 32 * KROW), 's_nop 0',
+                        'global_load_lds_dwordx4 %s, off' % vr(X0, 2)]
+            return ops
         ops = self.page_select(ids)
         for r, pg in enumerate((S_PG0, S_PG1)):
             ops += ['s_mul_hi_u32 s%d, s%d, %%[sp]' % (S_HI, pg), 's_mul_i32 s%d, s%d, %%[sp]' % (S_LO, pg),
@@ -311,6 +365,24 @@ class Gen:
         """request the page ids of tile t + ahead; each of the four is clamped to the chunk's last
         page, so a partial last tile still gets its own pages and nothing past the chunk is read"""
         ops = []
+        if self.rowids:
+            # token 64 t + 32 r + 4 * wavefront + q of the chunk -> its page -> byte offset of the page id, clamped
+            if ahead:
+                ops.append('s_add_u32 s%d, s%d, %d' % (S_TMP, S_T, ahead))
+                ops.append('s_lshl_b32 s%d, s%d, 6' % (S_TMP, S_TMP))
+            else:
+                ops.append('s_lshl_b32 s%d, s%d, 6' % (S_TMP, S_T))
+            ops.append('s_add_u32 s%d, s%d, s%d' % (S_TMP, S_TMP, S_W4))
+            for r in range(2):
+                for q, off in enumerate(S_OFFS):
+                    if 32 * r + q:
+                        ops.append('s_add_u32 s%d, s%d, %d' % (off, S_TMP, 32 * r + q))
+                        ops.append('s_lshr_b32 s%d, s%d, s%d' % (off, off, S_PSL))
+                    else:
+                        ops.append('s_lshr_b32 s%d, s%d, s%d' % (off, S_TMP, S_PSL))
+                    ops += ['s_lshl_b32 s%d, s%d, 2' % (off, off), 's_min_u32 s%d, s%d, %%[npg1]' % (off, off),
+                            's_load_dword s%d, %%[idp], s%d' % (dst + 4 * r + q, off)]
+            return ops
         if self.anyps:
             # token of this wavefront's first row in segment r of the tile -> its page -> byte offset of the page id
             if ahead:
@@ -361,6 +433,8 @@ class Gen:
         of its tiles 0 and 1, each clamped to the chunk's last page"""
         no = 'nopre_%s_%s' % (tag, lbl)
         vis = 'vis_%s_%s' % (tag, lbl)
+        if self.rowids:
+            return ['s_mov_b32 %[preo], 0']
         ops = ['s_mov_b32 %[preo], 0',
                's_bitcmp0_b32 %[woff], 0', 's_cbranch_scc1 ' + no,
                's_cmp_lt_u32 %%[nkl], %d' % LOOP_MIN_TOKENS, 's_cbranch_scc1 ' + no,
@@ -426,6 +500,8 @@ class Gen:
         next item runs this loop, request its K tiles 0 and 1 into buffers 0 and 1 and its V tiles 0 and 1 into the
         staging area"""
         skip = 'nopf_%s_%s' % (tag, lbl)
+        if self.rowids:
+            return []
         ops = ['s_waitcnt lgkmcnt(0)', 's_cmp_eq_u32 %[preo], 0', 's_cbranch_scc1 ' + skip]
         for t in range(2):
             ops += self.k_next_to_lds(S_NX + 2 * t, t)
@@ -446,6 +522,13 @@ class Gen:
         return ops
 
     def ids_take(self):
+        if self.rowids:   # the two groups swap
+            ops = []
+            for i in range(0, 8, 2):
+                ops += ['s_mov_b64 s[%d:%d], s[%d:%d]' % (S_LO, S_HI, S_G0 + i, S_G0 + i + 1),
+                        's_mov_b64 s[%d:%d], s[%d:%d]' % (S_G0 + i, S_G0 + i + 1, S_G1 + i, S_G1 + i + 1),
+                        's_mov_b64 s[%d:%d], s[%d:%d]' % (S_G1 + i, S_G1 + i + 1, S_LO, S_HI)]
+            return ops
         return ['s_mov_b64 s[%d:%d], s[%d:%d]' % (S_IDK, S_IDK + 1, S_IDS, S_IDS + 1),
                 's_mov_b64 s[%d:%d], s[%d:%d]' % (S_IDK + 2, S_IDK + 3, S_IDS + 2, S_IDS + 3),
                 's_mov_b64 s[%d:%d], s[%d:%d]' % (S_IDS, S_IDS + 1, S_IDN, S_IDN + 1),
@@ -510,7 +593,7 @@ class Gen:
                 e.raw('s_cbranch_scc1 half_j%d_%s' % (k, lbl))
             # block 1
             # the tile after next: its K goes to the LDS buffer that the barrier before this tile freed
-            head = self.k_to_lds(S_IDK, wr) + self.ids_load(4) if u == 0 else []
+            head = self.k_to_lds(self.gk, wr) + self.ids_load(4, self.gn) if u == 0 else []
             soft = (self.mask(Sc, u) if masked else []) + self.exps(Sc) + self.lazy_check()
             spread(e, [self.qk(Sn, s) for s in range(8)], head + merge_even(self.v_reads(cur, u), soft))
             e.raw('s_cbranch_vccnz raise_%s%d%d_%s' % (kind, k, u, lbl))
@@ -522,7 +605,7 @@ class Gen:
             if u == 0:
                 rest = merge_even(kn, self.rowsum() + self.v_convert()) + self.transform(Sn, 32)
             else:
-                rest = merge_even(kn, self.rowsum() + self.v_zero_tail(2)) + self.stores(wr) + self.fetch() + self.transform(Sn, 64)
+                rest = merge_even(kn, self.rowsum() + self.v_zero_tail(2)) + self.stores(wr) + self.fetch(self.gs) + self.transform(Sn, 64)
             spread(e, [self.pv(db, j) for j in range(2) for db in range(4)], rest)
         e.wait_lds_loads()
         e.emit('s_barrier')
@@ -547,8 +630,8 @@ class Gen:
         wr = (k + 2) % NBUF
         e.label('half_j%d_%s' % (k, lbl))
         e.lgkm, e.vm = [set(d) for d in self.mid_state[k][0]], [set(d) for d in self.mid_state[k][1]]
-        for o in self.v_zero_tail(2) + self.stores(wr) + self.fetch():
-            e.emit(o)
+        for o in self.v_zero_tail(2) + self.stores(wr) + self.fetch(self.gs):
+            emit_item(e, o)
         e.wait_lds_loads()
         e.emit('s_barrier')
         for o in self.ids_take():
@@ -568,9 +651,9 @@ class Gen:
         e.label('tile_%s%d_%s' % (tag, k, lbl))
         e.lgkm = []
         e.vm = [set(('v', ST + 8 + 4 * r + i) for i in range(4)) for r in (0, 1)]
-        for o in (self.k_to_lds(S_IDK, wr) + self.ids_load(4) + self.v_convert() + self.v_zero_tail(2) + self.stores(wr) +
-                  self.fetch()):
-            e.emit(o)
+        for o in (self.k_to_lds(self.gk, wr) + self.ids_load(4, self.gn) + self.v_convert() + self.v_zero_tail(2) + self.stores(wr) +
+                  self.fetch(self.gs)):
+            emit_item(e, o)
         e.wait_lds_loads()
         e.emit('s_barrier')
         for o in self.ids_take():
@@ -594,6 +677,9 @@ class Gen:
             e.raw('s_lshr_b32 s%d, %%[gl], 8' % S_PSL)
             e.raw('s_and_b32 s%d, %%[stp8], 3' % S_W4)
             e.raw('s_lshl_b32 s%d, s%d, 2' % (S_W4, S_W4))
+        if self.rowids:
+            e.raw('s_lshr_b32 s%d, %%[gl], 8' % S_PSL)
+            e.raw('s_lshl_b32 s%d, %%[stp8], 2' % S_W4)
         for s in range(8):
             e.emit('global_load_dwordx4 %s, %%[qp], off offset:%d' % (vr(Q + 4 * s, 4), 32 * s))
         for o in self.header_next():
@@ -620,50 +706,73 @@ class Gen:
             e.raw('v_xor_b32 v%d, %d, %%[kxs]' % (KAD + s_, 32 * s_))
             e.raw('v_add_u32 v%d, v%d, %%[kb]' % (KAD + s_, KAD + s_))
         q_loads = list(e.vm)
-        e.raw('s_bitcmp0_b32 %[woff], 1')
-        e.raw('s_cbranch_scc0 staged_%s' % lbl)
+        if not self.rowids:  # (the per-row variant never has tiles requested ahead)
+            e.raw('s_bitcmp0_b32 %[woff], 1')
+            e.raw('s_cbranch_scc0 staged_%s' % lbl)
         # start-up from memory: the page ids of tiles 0..3 in one go, then K of tiles 0 and 1 straight into LDS and
         # V of tiles 0, 1, 2 in flight together (tiles 0 and 1 borrow operand registers as staging)
-        for t, dst in enumerate((S_IDA, S_IDB, S_IDN, S_IDS)):
-            for o in self.ids_load(t, dst):
-                e.raw(o)
-        e.raw('s_waitcnt lgkmcnt(0)')
-        for t, ids in ((0, S_IDA), (1, S_IDB)):
-            for o in self.k_to_lds(ids, t):
-                e.emit(o)
-        for ids, base in ((S_IDA, VT), (S_IDB, KA), (S_IDN, ST)):
-            for o in self.fetch(ids, base):
-                e.emit(o)
+        if self.rowids:
+            # two groups of ids: tiles 0 and 1 first (K into LDS, V into borrowed registers), then tiles 2 and 3,
+            # which leaves group 0 = tile 2 (K at the head of the first tile) and group 1 = tile 3 (V at its end)
+            for t, dst in ((0, S_G0), (1, S_G1)):
+                for o in self.ids_load(t, dst):
+                    e.raw(o)
+            e.raw('s_waitcnt lgkmcnt(0)')
+            for t, ids in ((0, S_G0), (1, S_G1)):
+                for o in self.k_to_lds(ids, t):
+                    emit_item(e, o)
+            for ids, base in ((S_G0, VT), (S_G1, KA)):
+                for o in self.fetch(ids, base):
+                    emit_item(e, o)
+            for t, dst in ((2, S_G0), (3, S_G1)):
+                for o in self.ids_load(t, dst):
+                    e.raw(o)
+            e.raw('s_waitcnt lgkmcnt(0)')
+            for o in self.fetch(S_G0, ST):
+                emit_item(e, o)
+        else:
+            for t, dst in enumerate((S_IDA, S_IDB, S_IDN, S_IDS)):
+                for o in self.ids_load(t, dst):
+                    e.raw(o)
+            e.raw('s_waitcnt lgkmcnt(0)')
+            for t, ids in ((0, S_IDA), (1, S_IDB)):
+                for o in self.k_to_lds(ids, t):
+                    e.emit(o)
+            for ids, base in ((S_IDA, VT), (S_IDB, KA), (S_IDN, ST)):
+                for o in self.fetch(ids, base):
+                    e.emit(o)
         for o in self.next_decision_and_ids('a', lbl):
             e.raw(o)
         for t, base in ((0, VT), (1, KA)):
             for o in self.v_convert(base) + self.v_zero_tail(t, base) + self.stores(t, base):
                 e.emit(o)
         e.wait_lds_loads()
-        e.raw('s_mov_b64 s[%d:%d], s[%d:%d]' % (S_IDK, S_IDK + 1, S_IDN, S_IDN + 1))
-        e.raw('s_mov_b64 s[%d:%d], s[%d:%d]' % (S_IDK + 2, S_IDK + 3, S_IDN + 2, S_IDN + 3))
+        if not self.rowids:
+            e.raw('s_mov_b64 s[%d:%d], s[%d:%d]' % (S_IDK, S_IDK + 1, S_IDN, S_IDN + 1))
+            e.raw('s_mov_b64 s[%d:%d], s[%d:%d]' % (S_IDK + 2, S_IDK + 3, S_IDN + 2, S_IDN + 3))
         e.emit('s_barrier')
         e.raw('s_branch started_%s' % lbl)
         # start-up from LDS: K of tiles 0 and 1 is in its buffers, V of tiles 0 and 1 in the staging area
         e.label('staged_%s' % lbl)
         e.lgkm = []
         e.vm = list(q_loads)
-        for t, dst in ((2, S_IDN), (3, S_IDS)):
+        for t, dst in (() if self.rowids else ((2, S_IDN), (3, S_IDS))):
             for o in self.ids_load(t, dst):
                 e.raw(o)
-        for o in self.stage_reads(lbl):
-            e.emit(o)
-        e.drain(lgkm=True, vm=False)
-        for o in self.fetch(S_IDN, ST):
-            e.emit(o)
-        for o in self.next_decision_and_ids('b', lbl):
-            e.raw(o)
-        for t, base in ((0, VT), (1, KA)):
-            for o in self.v_convert(base) + self.v_zero_tail(t, base) + self.stores(t, base):
+        if not self.rowids:
+            for o in self.stage_reads(lbl):
                 e.emit(o)
-        e.raw('s_mov_b64 s[%d:%d], s[%d:%d]' % (S_IDK, S_IDK + 1, S_IDN, S_IDN + 1))
-        e.raw('s_mov_b64 s[%d:%d], s[%d:%d]' % (S_IDK + 2, S_IDK + 3, S_IDN + 2, S_IDN + 3))
-        e.emit('s_barrier')
+            e.drain(lgkm=True, vm=False)
+            for o in self.fetch(S_IDN, ST):
+                e.emit(o)
+            for o in self.next_decision_and_ids('b', lbl):
+                e.raw(o)
+            for t, base in ((0, VT), (1, KA)):
+                for o in self.v_convert(base) + self.v_zero_tail(t, base) + self.stores(t, base):
+                    e.emit(o)
+            e.raw('s_mov_b64 s[%d:%d], s[%d:%d]' % (S_IDK, S_IDK + 1, S_IDN, S_IDN + 1))
+            e.raw('s_mov_b64 s[%d:%d], s[%d:%d]' % (S_IDK + 2, S_IDK + 3, S_IDN + 2, S_IDN + 3))
+            e.emit('s_barrier')
         e.label('started_%s' % lbl)
         # either way: nothing of LDS in flight; of the loads, at most Q and the V rows of tile 2, in this order
         e.lgkm = []
@@ -737,7 +846,7 @@ class Gen:
                    'v_and_b32 v%d, 31, v%d' % (T + 14, T + 15)] + self.wave_shift(S_TMP, 'lshl', 5) + [
                    'v_add_u32 v%d, s%d, v%d' % (T + 14, S_TMP, T + 14), 'v_lshrrev_b32 v%d, %%[gl], v%d' % (T + 14, T + 14),
                    'v_cmp_gt_i32 vcc, %s, v%d' % (self.np, T + 14), 's_and_b64 exec, exec, vcc',
-                   'v_cmp_gt_u32 vcc, 32, v%d' % (T + 15), 's_and_b64 exec, exec, vcc'] if self.var else
+                   'v_cmp_gt_u32 vcc, 32, v%d' % (T + 15), 's_and_b64 exec, exec, vcc'] if self.norok else
                   ['v_and_b32 v%d, 2, %%[rok]' % self.maxt, 'v_cmp_ne_u32 vcc, 0, v%d' % self.maxt, 's_and_b64 exec, exec, vcc']) + [
                   'v_lshrrev_b32 v%d, 9, %%[ooff]' % T, 'v_lshlrev_b32 v%d, 2, v%d' % (T, T),
                   'global_store_dword v%d, v%d, %%[lb] nt' % (T, X1), 's_mov_b64 exec, s[%d:%d]' % (S_EXEC, S_EXEC + 1)]:
@@ -825,8 +934,10 @@ if __name__ == '__main__':
                                   (False, True, False, 'f16_cap'), (True, False, True, 'bf16_contig'),
                                   (False, False, True, 'f16_contig'), (True, False, False, 'bf16_var'),
                                   (False, False, False, 'f16_var'), (True, False, False, 'bf16_ps'),
-                                  (False, False, False, 'f16_ps')):
-        lines = Gen(bf, cap, contig, var=name.endswith('_var'), anyps=name.endswith('_ps')).program()
+                                  (False, False, False, 'f16_ps'), (True, False, False, 'bf16_rows'),
+                                  (False, False, False, 'f16_rows')):
+        lines = Gen(bf, cap, contig, var=name.endswith('_var'), anyps=name.endswith('_ps'),
+                    rowids=name.endswith('_rows')).program()
         write(os.path.join(out_dir, 'append_loop_%s.inc' % name), lines, name)
         n_mfma = sum(1 for l in lines if l.startswith('v_mfma'))
         print('%s: %d lines, %d matrix instructions, %d waits' % (name, len(lines), n_mfma, sum(1 for l in lines if l.startswith('s_waitcnt'))))

@@ -1,7 +1,8 @@
 """GPU parity for page sizes other than the tuned 16 (Sec. 3.1.1: the block size of the BSR cache is a free
 parameter; App. B compares page sizes): decode goes through its general code path, where every lane looks up the
 page of the token row it loads; append runs the scheduled loop's variant for page sizes 4, 8 and 32 (a wavefront's
-four consecutive rows per load share a page) and the general path for the others."""
+four consecutive rows per load share a page), its per-row variant for page sizes 1 and 2 (a page id per token row,
+64-bit addresses per lane) and the general path for page size 64."""
 import numpy as np
 import pytest
 
@@ -33,7 +34,7 @@ def test_decode(ps):
     check(b, "decode", f"decode split ps={ps}", num_ctas=2 * 16, min_chunk=64)
 
 
-@pytest.mark.parametrize("ps", [1, 4, 8, 32, 64])
+@pytest.mark.parametrize("ps", [1, 2, 4, 8, 32, 64])
 def test_append(ps):
     for seed, dtype, causal in ((321, workloads.BF16, True), (322, workloads.F16, False)):
         b = workloads.make_batch("app", seed + ps, dtype, 8, 2, 128, ps, [70, 9, 130, 1], [400, 9, 333, 64], causal)
@@ -42,7 +43,7 @@ def test_append(ps):
     check(b, "append", f"append split ps={ps}", num_ctas=2 * 16, min_chunk=128)
 
 
-@pytest.mark.parametrize("ps", [4, 8, 32])
+@pytest.mark.parametrize("ps", [1, 2, 4, 8, 32])
 def test_append_work_items_that_follow_each_other_in_the_scheduled_loop(ps):
     """Default grid on the small causal-append configuration and long chunks on few CTAs: several work items per CTA
     run the loop back to back (the next item's first tiles are requested by the item before it), with ragged last
