@@ -1,5 +1,6 @@
 #!/usr/bin/env python3
-"""Writes append_loop_{bf16,f16}[_cap|_contig].inc: the hand-scheduled steady-state loop of the append kernel.
+"""Writes append_loop_{bf16,f16}[_cap|_contig|_var|_ps|_rows].inc: the hand-scheduled steady-state loop of the append
+kernel and its variants (soft cap; contiguous KV; ALiBi and / or sliding window; page sizes 4, 8, 32; page sizes 1, 2).
 
 The loop covers all KV tiles of a work item whose first tile every row of the CTA sees in full:
 first the tiles that need no masking, then, with a compare-and-select on the logits in front of
