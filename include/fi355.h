@@ -259,12 +259,12 @@ typedef struct fi_variant {
 
 /* fi_run with a variant.  (A window alone only masks: to skip the hidden keys, create the handle with
  * fi_config.plan_window.)  kv_indptr [batch+1] and last_page_len [batch] are DEVICE copies of the arrays
- * the batch was planned with (the decode kernel derives pos from them).  Built for 16-bit pools and
- * page_size 16; decode mode: every field of fi_variant; append mode: every field too, for batches planned
- * with causal = 1 (the soft cap alone, and ALiBi and / or a window without the soft cap, run variants of the
- * scheduled tile loop, 1.2-1.3x the time of fi_run; the soft cap together with one of the others, and the rotary
- * embedding, run every work item on the kernel's general path, several times slower).  FI_ERR_UNSUPPORTED
- * otherwise.  Every key of the request is still read, a window only
+ * the batch was planned with (the decode kernel derives pos from them).  Built for 16-bit pools;
+ * decode mode: every field of fi_variant (the rotary embedding at page_size 16 only); append mode: every field
+ * too, for batches planned with causal = 1 (at page_size 16 the soft cap alone, and ALiBi and / or a window
+ * without the soft cap, run variants of the scheduled tile loop, 1.2-1.3x the time of fi_run; the soft cap together
+ * with one of the others, the rotary embedding, and every variant at other page sizes run every work item on the
+ * kernel's general path, several times slower).  FI_ERR_UNSUPPORTED otherwise.  Every key of the request is still read, a window only
  * masks.  variant HOST, read during the call.  Otherwise as fi_run. */
 int32_t fi_run_variant(fi_handle* h, const void* q, const void* k_pool, const void* v_pool,
                        const int64_t* kv_strides, const int32_t* kv_indices,

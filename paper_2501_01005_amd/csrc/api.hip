@@ -338,8 +338,8 @@ int32_t run_impl(fi_handle* h, const void* q, const void* k_pool, const void* v_
   if (variant) {
     if (h->cfg.mode == FI_MODE_TILE16 || h->cfg.mode == FI_MODE_TILE64)
       return set_error(FI_ERR_UNSUPPORTED, "fi_run_variant: not built for the 16-row and 64-row tile modes");
-    if (h->cfg.page_size != kPageSize)
-      return set_error(FI_ERR_UNSUPPORTED, "fi_run_variant: built for page_size 16");
+    if (h->cfg.page_size != kPageSize && h->cfg.mode == FI_MODE_DECODE && variant->rope_theta > 0.f)
+      return set_error(FI_ERR_UNSUPPORTED, "fi_run_variant: the rotary embedding in decode mode is built for page_size 16");
     if (h->cfg.mode != FI_MODE_DECODE && !h->pp_causal_last)
       return set_error(FI_ERR_UNSUPPORTED, "fi_run_variant: in append mode the batch must be planned with causal = 1");
     if (!kv_indptr_dev || !last_page_len_dev) return set_error(FI_ERR_INVALID_ARG, "fi_run_variant: null pointer");

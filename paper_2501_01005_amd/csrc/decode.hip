@@ -251,7 +251,7 @@ decode_kernel(const RunParams p, const RopeArg<ROPE> rope) {
       const int req = as_const(p.w_request)[w];
       ConstInts indptr = as_const(p.kv_indptr);
       const int n_pg = indptr[req + 1] - indptr[req];
-      const int l_kv = n_pg > 0 ? (n_pg - 1) * kPageSize + as_const(p.last_page_len)[req] : 0;
+      const int l_kv = n_pg > 0 ? ((n_pg - 1) << p.page_log2) + as_const(p.last_page_len)[req] : 0;
       tok_abs0 = as_const(p.w_kv_start)[w];
       pos = l_kv - 1;
       tok_minus_pos = tok_abs0 - pos;
@@ -506,8 +506,8 @@ decode_kernel(const RunParams p, const RopeArg<ROPE> rope) {
       }
       int idA = 0, idB = 0;
       if constexpr (ANYPS) {
-        idA = step_ids(0);
-        idB = step_ids(1);
+        idA = step_ids(t_first);
+        idB = step_ids(t_first + 1);
       }
       if (n_tiles > t_first) load_tile(TA, idA, t_first);
       if (n_tiles > t_first + 1) load_tile(TB, idB, t_first + 1);
@@ -712,6 +712,11 @@ hipError_t launch_decode(const RunParams& p, bool is_bf16, bool kv8, bool varian
         hipLaunchKernelGGL((decode_kernel<true, false, false, true, true>), grid, dim3(64, 1, 1), 0, stream, p, *rope);
       else
         hipLaunchKernelGGL((decode_kernel<false, false, false, true, true>), grid, dim3(64, 1, 1), 0, stream, p, *rope);
+    } else if (p.page_log2 != 4) {  // the logits hooks on the general path (any page size)
+      if (is_bf16)
+        hipLaunchKernelGGL((decode_kernel<true, false, true, true>), grid, dim3(64, 1, 1), 0, stream, p, NoRope{});
+      else
+        hipLaunchKernelGGL((decode_kernel<false, false, true, true>), grid, dim3(64, 1, 1), 0, stream, p, NoRope{});
     } else if (is_bf16) {
       hipLaunchKernelGGL((decode_kernel<true, false, false, true>), grid, dim3(64, 1, 1), 0, stream, p, NoRope{});
     } else {

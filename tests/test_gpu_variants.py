@@ -187,8 +187,8 @@ def test_refused_where_not_built():
     dummy = np.zeros(64, dtype=np.uint8)
     ok = dict(dtype=fi.FI_DTYPE_BF16, num_qo_heads=8, num_kv_heads=2, head_dim=128, page_size=16, mode=fi.FI_MODE_DECODE,
               num_ctas=8, max_batch=4, max_qo_tiles=4)
-    # other page sizes; append mode without a causal plan (also for the rotary embedding)
-    for bad, var in (({"page_size": 8}, dict(window_left=3)), ({"mode": fi.FI_MODE_APPEND}, dict(window_left=3)),
+    # the rotary embedding in decode mode at other page sizes; append mode without a causal plan (also for the rotary embedding)
+    for bad, var in (({"page_size": 8}, dict(rope_theta=1e4)), ({"mode": fi.FI_MODE_APPEND}, dict(window_left=3)),
                      ({"mode": fi.FI_MODE_APPEND}, dict(rope_theta=1e4))):
         causal_plan = bad.pop("causal_plan", False)
         h = fi.fi_create(**{**ok, **bad})
@@ -203,3 +203,19 @@ def test_refused_where_not_built():
         fi.fi_run_variant(h, dummy, dummy, dummy, (8, 8, 8), dummy, dummy, dummy, 1.0, dummy, dummy, window_left=-5)
     assert e.value.code == fi.FI_ERR_INVALID_ARG
     fi.fi_destroy(h)
+
+
+@pytest.mark.parametrize("ps", [1, 8, 32])
+def test_variants_at_other_page_sizes(ps):
+    """The hooks on the general paths (decode: a page id per lane; append: a page id per staged row), with windows that
+    hide whole steps of split chunks."""
+    b = workloads.random_case(470 + ps, dtype=workloads.BF16, num_qo_heads=8, num_kv_heads=2, batch=5, max_kv=900, page_size=ps,
+                              value_scale=2.0)
+    check(b, f"decode ps={ps}: all hooks", logits_soft_cap=5.0, window_left=33, alibi_slopes=slopes(8))
+    check(b, f"decode ps={ps}: window over split chunks", num_ctas=2 * 16, min_chunk=64, window_left=100)
+    check(b, f"decode ps={ps}: alibi", alibi_slopes=slopes(8))
+    a = workloads.make_batch("app", 480 + ps, workloads.F16, 8, 2, 128, ps, [70, 9, 130], [400, 9, 333], True)
+    check(a, f"append ps={ps}: all hooks", mode="append", num_ctas=2 * 4, min_chunk=128, logits_soft_cap=5.0, window_left=50,
+          alibi_slopes=slopes(8))
+    check(a, f"append ps={ps}: window", mode="append", window_left=64)
+    check(a, f"append ps={ps}: rotary embedding", mode="append", rope_theta=1e4)
