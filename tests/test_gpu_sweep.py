@@ -92,6 +92,10 @@ def test_random_variants_fp8_and_contiguous(seed):
                 var["rope_theta"] = float(rng.choice([1e4, 5e5]))
             if not var:
                 var["window_left"] = 64
+            ps = int(rng.choice([16, 16, 1, 8, 32]))
+            if ps != 16 and mode == "decode":
+                var.pop("rope_theta", None)    # (the rotary embedding in decode mode is built for page size 16)
+                var.setdefault("window_left", 64)
         need = int(((kv + ps - 1) // ps).sum())
         b = workloads.make_batch("sweep", data_seed, dtype, g * hkv, hkv, 128, ps, qo, kv, causal,
                                  num_pages=need + (0 if kind == "contig" else 2),
