@@ -236,6 +236,8 @@ def main() -> int:
                          "with the three length distributions of the paper's kernel experiment (Sec. 4.2); sa: short "
                          "appends (--sa-qo tokens per request, --sa-batch requests, caches up to --sa-kv-max tokens) through "
                          "the handle mode --handle-mode")
+    ap.add_argument("--e2-len", type=int, default=1024,
+                    help="e2-*-constant: the sequence length (the paper's experiment has 1024)")
     ap.add_argument("--sa-qo", type=int, default=16)
     ap.add_argument("--sa-batch", type=int, default=64)
     ap.add_argument("--sa-kv-max", type=int, default=4096)
@@ -373,7 +375,7 @@ def run_workload(args):
         mode = args.handle_mode
     elif args.workload in E2_WORKLOADS:
         _, kind, dist = args.workload.split("-")
-        batch = workloads.config_e2(kind, dist)
+        batch = workloads.config_e2(kind, dist, args.e2_len)
         mode = "append" if kind == "prefill" else "decode"
     else:
         batch = getattr(workloads, "config" + args.workload[1])(small=args.small, **cfg_kw)

@@ -295,21 +295,24 @@ def config4(small: bool = False, permute_pages: bool = True, kv_dtype: str = "")
                       kv_dtype=kv_dtype, k_scale=0.5 if kv_dtype == FP8 else 1.0, v_scale=2.0 if kv_dtype == FP8 else 1.0)
 
 
-def config_e2(kind: str, dist: str) -> PagedBatch:
+def config_e2(kind: str, dist: str, constant_len: int = 1024) -> PagedBatch:
     """The paper's kernel experiment on input dynamism (Sec. 4.2): batch 16, sequence lengths constant (1024),
     uniform (512..1024) or skewed (Zipf, average about 1024); `kind` "decode": l_qo = 1, l_kv = the length;
     "prefill": causal, l_qo = l_kv = the length.  GQA 32/8, D 128, bf16, page 16 as in the other configurations.
-    Zipf: P(l) proportional to l**-1.2 on [256, 3048], whose mean is 1024 (the paper gives only the average)."""
+    Zipf: P(l) proportional to l**-1.2 on [256, 3048], whose mean is 1024 (the paper gives only the average).
+    `constant_len`: another length for the constant distribution (to see how a kernel's time splits into a part per
+    work item and a part per KV tile)."""
     seed = 1100 + 10 * ("decode", "prefill").index(kind) + ("constant", "uniform", "zipf").index(dist)
     g = np.random.Generator(np.random.PCG64(seed))
     if dist == "constant":
-        lens = np.full(16, 1024, dtype=np.int64)
+        lens = np.full(16, constant_len, dtype=np.int64)
     elif dist == "uniform":
         lens = g.integers(512, 1025, size=16)
     else:
         lens = zipf_lengths(g, 16, 256, 3048, 1.2)
     qo = np.ones(16, dtype=np.int64) if kind == "decode" else lens
-    return make_batch(f"e2_{kind}_{dist}", seed, BF16, 32, 8, 128, 16, qo, lens, causal=kind == "prefill", poison=False)
+    name = f"e2_{kind}_{dist}" + (f"_len{constant_len}" if dist == "constant" and constant_len != 1024 else "")
+    return make_batch(name, seed, BF16, 32, 8, 128, 16, qo, lens, causal=kind == "prefill", poison=False)
 
 
 @dataclasses.dataclass
