@@ -12,9 +12,9 @@ from gpu_util import DeviceBatch, assert_close, make_wrapper
 pytestmark = pytest.mark.gpu
 
 
-def run_variant(batch, num_ctas=0, min_chunk=0, mode="decode", plan_window=0, merge=0, **var):
+def run_variant(batch, num_ctas=0, min_chunk=0, mode="decode", plan_window=0, merge=0, dev=None, **var):
     import torch
-    dev = DeviceBatch(batch)
+    dev = dev or DeviceBatch(batch)
     w = make_wrapper(batch, mode, num_ctas=num_ctas, min_chunk=min_chunk, plan_window=plan_window, merge=merge)
     w.plan(batch.qo_indptr, batch.kv_indptr, batch.last_page_len, causal=batch.causal)
     nnz = dev.q.shape[0]
