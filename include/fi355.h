@@ -119,6 +119,12 @@ typedef struct fi_config {
                            work items, so that the time follows the window, not the context length.
                            Such a plan must be run with fi_run_variant and 0 <= window_left <= n - 1
                            (the kernel masks token by token; FI_ERR_INVALID_ARG otherwise)        */
+  int32_t max_formats;  /* how many formats a later fi_plan_formats may plan at once.  0: default = as many
+                           as fit for the tile modes (FI_MODE_TILE16, FI_MODE_TILE64), 1 for the others.
+                           1: one format at a time (fi_plan, or fi_plan_formats with one format): the
+                           workspace then holds partial states for 2 * #CTA-bounded split tiles only
+                           (App. D.3) instead of one per work item, which matters when max_qo_tiles is
+                           large.  More than 1 on a decode or append handle: FI_ERR_UNSUPPORTED       */
 } fi_config;
 
 /* Borrowed HOST views of the last plan, for bit-exact checks against a replica of

@@ -50,7 +50,7 @@ class Fi355Error(RuntimeError):
 class fi_config(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int32) for n in (
         "dtype", "num_qo_heads", "num_kv_heads", "head_dim", "page_size", "mode", "num_ctas", "max_batch",
-        "max_qo_tiles", "alpha", "beta", "min_chunk", "literal_lkv", "balance", "merge", "plan_window")]
+        "max_qo_tiles", "alpha", "beta", "min_chunk", "literal_lkv", "balance", "merge", "plan_window", "max_formats")]
 
 
 _I32P = ctypes.POINTER(ctypes.c_int32)
@@ -288,7 +288,7 @@ class PagedAttention:
     def __init__(self, *, dtype: str, num_qo_heads: int, num_kv_heads: int, head_dim: int = 128,
                  page_size: int = 16, mode: str = "decode", max_batch: int, max_qo_tiles: Optional[int] = None,
                  num_ctas: int = 0, min_chunk: int = 0, alpha: int = 0, beta: int = 0, literal_lkv: bool = False,
-                 balance: int = 0, merge: int = 0, plan_window: int = 0,
+                 balance: int = 0, merge: int = 0, plan_window: int = 0, max_formats: int = 0,
                  device: str = "cuda:0"):
         import torch
 
@@ -304,7 +304,7 @@ class PagedAttention:
                 mode={"decode": FI_MODE_DECODE, "append": FI_MODE_APPEND, "tile16": FI_MODE_TILE16, "tile64": FI_MODE_TILE64}[mode], num_ctas=num_ctas,
                 max_batch=max_batch, max_qo_tiles=max_qo_tiles if max_qo_tiles is not None else max_batch,
                 alpha=alpha, beta=beta, min_chunk=min_chunk, literal_lkv=1 if literal_lkv else 0, balance=balance,
-                merge=merge, plan_window=plan_window)
+                merge=merge, plan_window=plan_window, max_formats=max_formats)
         self.num_qo_heads, self.num_kv_heads, self.head_dim = num_qo_heads, num_kv_heads, head_dim
         dev_bytes, pin_bytes = fi_workspace_bytes(self.handle)
         self.workspace = torch.empty(dev_bytes, dtype=torch.uint8, device=self.device)

@@ -129,6 +129,9 @@ int32_t fi_create(const fi_config* cfg, fi_handle** out) {
   if (cfg->mode == FI_MODE_APPEND && !(g == 1 || g == 2 || g == 4 || g == 8 || g == 16))
     return set_error(FI_ERR_UNSUPPORTED, "fi_create: append mode is built for group size 1, 2, 4, 8, 16");
   const bool small_tiles = cfg->mode == FI_MODE_TILE16 || cfg->mode == FI_MODE_TILE64;
+  if (cfg->max_formats < 0) return set_error(FI_ERR_INVALID_ARG, "fi_create: max_formats must be >= 0");
+  if (cfg->max_formats > 1 && !small_tiles)
+    return set_error(FI_ERR_UNSUPPORTED, "fi_create: several formats in one plan are built for the 16-row and 64-row tile modes");
   if (small_tiles && (!(g == 1 || g == 2 || g == 4 || g == 8 || g == 16) || cfg->page_size != kPageSize || cfg->plan_window > 0))
     return set_error(FI_ERR_UNSUPPORTED, "fi_create: the 16-row and 64-row tile modes are built for group size 1, 2, 4, 8, 16, page_size 16, "
                                          "no planned window");
@@ -187,7 +190,7 @@ int32_t fi_create(const fi_config* cfg, fi_handle** out) {
   pp.max_batch = cfg->max_batch;
   pp.max_qo_tiles = cfg->max_qo_tiles;
   h->layout.init(pp.ctas_per_head, cfg->max_qo_tiles, pp.t_pos, cfg->num_qo_heads, cfg->num_kv_heads, cfg->head_dim,
-                 small_tiles, pp.weighted_lkv ? (100 + pp.light_pct - 1) / pp.light_pct : 1);
+                 small_tiles && cfg->max_formats != 1, pp.weighted_lkv ? (100 + pp.light_pct - 1) / pp.light_pct : 1);
   h->host_plan.assign(h->layout.plan_ints, 0);
   *out = h;
   return FI_OK;

@@ -59,6 +59,16 @@ def test_causal_edges(mode):
         check(b, f"{mode} edge{qo}{kv}", mode, num_ctas=2 * 4, min_chunk=16)
 
 
+@pytest.mark.parametrize("mode", MODES)
+def test_one_format_at_a_time_with_the_small_workspace(mode):
+    """fi_config.max_formats = 1: partial-state sections bounded by the CTAs; long requests split over many CTAs use
+    them, with NaN everywhere else in the workspace"""
+    b = workloads.make_batch("split", 23, workloads.BF16, 32, 8, 128, 16, [4, 1, 16, 3], [5000, 3000, 2500, 40], True)
+    check(b, f"{mode} max_formats=1", mode, max_formats=1)
+    check(b, f"{mode} max_formats=1, few CTAs", mode, max_formats=1, num_ctas=8 * 5, min_chunk=32)
+    check(workloads.config2(small=True), f"c2 small as {mode}, max_formats=1", mode, max_formats=1)
+
+
 def run_formats(case_batches, single, what, mode, **kw):
     import torch
     import paper_2501_01005_amd as fi

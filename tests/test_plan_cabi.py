@@ -475,3 +475,38 @@ def test_suggested_mode_follows_the_mean_query_length():
     with pytest.raises(fi.Fi355Error) as e:
         fi.fi_suggest_mode(6, 4, 1.0)
     assert e.value.code == fi.FI_ERR_INVALID_ARG
+
+
+@pytest.mark.parametrize("mode", [fi.FI_MODE_TILE16, fi.FI_MODE_TILE64])
+def test_one_format_at_a_time_takes_the_small_workspace(mode):
+    """fi_config.max_formats = 1 on a tile handle: the partial-state sections are bounded by the CTAs (App. D.3), not by
+    the work items; single-format plans are the same arrays; several formats at once are refused."""
+    any_formats = make(mode, 4, 8, max_batch=64, max_tiles=20000)
+    one_format = make(mode, 4, 8, max_batch=64, max_tiles=20000, max_formats=1)
+    assert fi.fi_workspace_bytes(one_format)[0] < fi.fi_workspace_bytes(any_formats)[0] // 8
+    rng = np.random.default_rng(31)
+    for trial in range(20):
+        B = int(rng.integers(1, 40))
+        qo = rng.integers(1, 20, size=B)
+        qo_indptr, kv_indptr, last = indptrs(qo, qo + rng.integers(0, 3000, size=B))
+        views = []
+        for h in (any_formats, one_format):
+            fi.fi_plan(h, qo_indptr, kv_indptr, last, True)
+            views.append(fi.fi_plan_view(h))
+        assert views[0]["n_work"] == views[1]["n_work"] and views[0]["n_slots"] == views[1]["n_slots"]
+        for k in PLAN_KEYS:
+            assert views[0][k].tobytes() == views[1][k].tobytes(), k
+    qo2, kv2, last2 = indptrs([1, 1], [5, 6])
+    fi.fi_plan_formats(one_format, [(qo2, kv2, last2, 0)])
+    with pytest.raises(fi.Fi355Error) as e:
+        fi.fi_plan_formats(one_format, [(qo2, kv2, last2, 0), (qo2, kv2, last2, 2)])
+    assert e.value.code == fi.FI_ERR_UNSUPPORTED
+    fi.fi_plan_formats(any_formats, [(qo2, kv2, last2, 0), (qo2, kv2, last2, 2)])
+    fi.fi_destroy(any_formats)
+    fi.fi_destroy(one_format)
+    with pytest.raises(fi.Fi355Error) as e:
+        make(fi.FI_MODE_DECODE, 4, 8, max_formats=2)
+    assert e.value.code == fi.FI_ERR_UNSUPPORTED
+    with pytest.raises(fi.Fi355Error) as e:
+        make(mode, 4, 8, max_formats=-1)
+    assert e.value.code == fi.FI_ERR_INVALID_ARG
