@@ -151,7 +151,8 @@ __device__ __forceinline__ uint32_t lds_offset(const void* p) {
 // are one statement, so the compiler never sees a register whose load is still in flight.
 struct WorkItem {
   int q_row0, n_pos, kv_page0, kv_start, kv_len, diag0, out_slot;
-  __device__ __forceinline__ void load(const RunParams& p, int w) {
+  template <class Params>
+  __device__ __forceinline__ void load(const Params& p, int w) {
     const int off = w * 4;
     asm volatile(
         "s_load_dword %0, %7, %14\n\t"
@@ -177,8 +178,11 @@ struct WorkItem {
 // last one) and finishes the work item.  Output row of tile row R (position R >> g_log2, head
 // R % g) is row_base + position * num_qo_heads + head, written if position < n_pos: o (512 B per
 // row) to o_base, and, if has_cast, o in the input type to cast_base; the rows pass through the
-// wavefront's LDS area (epi_write: this lane's accumulator column, epi_read / epi_chunk: the
-// 16-byte piece it stores).  lse goes to lse_base[o_off / 512] from lanes with row_flags & 2.
+// wavefront's LDS area (epi_write: this lane's accumulator column, epi_read: the 16-byte piece
+// it stores).  lse goes to lse_base[o_off / 512] from the first 32 lanes of a wavefront whose row exists.
+// What depends on the thread index alone (its staging row, the swizzle of its operand reads, the piece of an
+// output row it stores) the block derives from `thread`: every per-lane operand occupies one of the sixteen
+// vector registers the block leaves to the compiler for as long as it runs.
 // Every wavefront of the CTA must call it with the same tile counts (it contains CTA barriers).
 //
 // Seam to the next work item: the block reads the plan entry at byte offset `next_off & ~3` of
@@ -199,17 +203,16 @@ struct WorkItem {
 // slope times log2(e) (0: none), `win` = window_left (a huge value: none).
 // PSL: the variant for page sizes 4, 8 and 32: `g_log2` carries log2 of the page size in bits 8.., `ids_clamp` and
 // `page_ids` count pages of that size, and the per-lane row offsets hold the row's place inside its page.
-// ROWS: the variant for page sizes 1 and 2 (a page id per token row, 64-bit addresses per lane): operands as for PSL,
-// except that the row flags are not passed (the loop needs the register and finds the lanes that write lse itself).
+// ROWS: the variant for page sizes 1 and 2 (a page id per token row, 64-bit addresses per lane): operands as for PSL.
 template <bool BF, bool CAP, bool CONTIG, bool VARL, bool PSL = false, bool ROWS = false>
-__device__ __forceinline__ void run_scheduled_loop(int n_full, int n_tiles, int kv_len, int cap, int st_tok, int ids_clamp, const int32_t* page_ids, uint32_t k_lo,
+__device__ __forceinline__ void run_scheduled_loop(int n_full, int n_tiles, int kv_len, int cap, int thread, int ids_clamp, const int32_t* page_ids, uint32_t k_lo,
                                                    uint32_t k_hi, uint32_t v_lo, uint32_t v_hi, uint32_t page_bytes,
                                                    float scale_log2, uint64_t q_addr, uint32_t st_off_bytes,
-                                                   uint32_t k_off_bytes, uint32_t k_read, uint32_t k_swizzle,
+                                                   uint32_t k_off_bytes, uint32_t k_read,
                                                    uint32_t v_read, uint32_t k_dma, uint32_t v_write,
-                                                   uint32_t o_off, int row_flags, float* o_base, float* lse_base,
+                                                   uint32_t o_off, float* o_base, float* lse_base,
                                                    void* cast_base, int has_cast, uint32_t epi_write, uint32_t epi_read,
-                                                   uint32_t epi_chunk, int g_log2, int num_qo_heads, int row_base,
+                                                   int g_log2, int num_qo_heads, int row_base,
                                                    int n_pos, int wave_index, int next_off,
                                                    const int32_t* w_fields, int w_stride, uint32_t all_ids_lo,
                                                    uint32_t all_ids_hi, WorkItem& next, int& prefetched_out,
@@ -217,38 +220,35 @@ __device__ __forceinline__ void run_scheduled_loop(int n_full, int n_tiles, int 
 #define FI355_LOOP_OPERANDS                                                                                              \
         : [nq] "=&s"(next.q_row0), [nn] "=&s"(next.n_pos), [npg] "=&s"(next.kv_page0), [nks] "=&s"(next.kv_start),          \
           [nkl] "=&s"(next.kv_len), [ndg] "=&s"(next.diag0), [nos] "=&s"(next.out_slot), [preo] "=&s"(prefetched_out)        \
-        : [nf] "s"(n_full), [nt] "s"(n_tiles), [kvl] "s"(kv_len), [cap] "v"(cap), [stk] "v"(st_tok), [npg1] "s"(ids_clamp), [idp] "s"(page_ids), [kblo] "s"(k_lo), [kbhi] "s"(k_hi), \
+        : [nf] "s"(n_full), [nt] "s"(n_tiles), [kvl] "s"(kv_len), [cap] "{v1}"(cap), [tid] "{v4}"(thread), [npg1] "s"(ids_clamp), [idp] "s"(page_ids), [kblo] "s"(k_lo), [kbhi] "s"(k_hi), \
           [vblo] "s"(v_lo), [vbhi] "s"(v_hi), [sp] "s"(page_bytes), [sc] "s"(scale_log2),                                 \
-          [qp] "v"(q_addr), FI355_STAGING_OFFSETS [kb] "v"(k_read), [kxs] "v"(k_swizzle),        \
-          [va] "v"(v_read), [kd] "s"(k_dma), [wv] "v"(v_write), [ooff] "v"(o_off), FI355_ROW_FLAGS [ob] "s"(o_base), [lb] "s"(lse_base), \
-          [cb] "s"(cast_base), [oc] "s"(has_cast), [ew] "v"(epi_write), [er] "v"(epi_read), [l16] "v"(epi_chunk),          \
+          [qp] "{v[2:3]}"(q_addr), FI355_STAGING_OFFSETS [kb] "{v7}"(k_read),                               \
+          [va] "{v8}"(v_read), [kd] "s"(k_dma), [wv] "{v9}"(v_write), [ooff] "{v10}"(o_off), [ob] "s"(o_base), [lb] "s"(lse_base), \
+          [cb] "s"(cast_base), [oc] "s"(has_cast), [ew] "{v11}"(epi_write), [er] "{v12}"(epi_read),                                \
           [gl] "s"(g_log2), FI355_HEADS_AND_POSITIONS [rb] "s"(row_base), [stp8] "s"(wave_index),                          \
           [woff] "s"(next_off), [wq0] "s"(w_fields), [wstr] "s"(w_stride),                                                  \
           [idblo] "s"(all_ids_lo), [idbhi] "s"(all_ids_hi)
-  // (the bias / window variant has a per-lane and a scalar operand more than there are registers left: it finds the
-  // lanes that write lse itself instead of taking row_flags, and takes n_pos and num_qo_heads packed into g_log2)
-#define FI355_STAGING_OFFSETS [so] "v"(st_off_bytes), [sok] "v"(k_off_bytes),
-#define FI355_ROW_FLAGS
+  // (the bias / window variant has a scalar operand more than there are registers left: it takes n_pos and
+  // num_qo_heads packed into g_log2)
+#define FI355_STAGING_OFFSETS [so] "{v5}"(st_off_bytes), [sok] "{v6}"(k_off_bytes),
 #define FI355_HEADS_AND_POSITIONS
   if constexpr (VARL && BF) {
     asm volatile(
 #include "append_loop_bf16_var.inc"
-        FI355_LOOP_OPERANDS, [slope] "v"(slope), [win] "s"(win)
+        FI355_LOOP_OPERANDS, [slope] "{v13}"(slope), [win] "s"(win)
         :
 #include "append_loop_clobbers.inc"
     );
   } else if constexpr (VARL) {
     asm volatile(
 #include "append_loop_f16_var.inc"
-        FI355_LOOP_OPERANDS, [slope] "v"(slope), [win] "s"(win)
+        FI355_LOOP_OPERANDS, [slope] "{v13}"(slope), [win] "s"(win)
         :
 #include "append_loop_clobbers.inc"
     );
   }
-#undef FI355_ROW_FLAGS
 #undef FI355_HEADS_AND_POSITIONS
 #define FI355_HEADS_AND_POSITIONS [hq] "s"(num_qo_heads), [np] "s"(n_pos),
-#define FI355_ROW_FLAGS
   if constexpr (ROWS && BF) {
     asm volatile(
 #include "append_loop_bf16_rows.inc"
@@ -264,8 +264,6 @@ __device__ __forceinline__ void run_scheduled_loop(int n_full, int n_tiles, int 
 #include "append_loop_clobbers.inc"
     );
   }
-#undef FI355_ROW_FLAGS
-#define FI355_ROW_FLAGS [rok] "v"(row_flags),
   if constexpr (VARL || ROWS) {
   } else if constexpr (PSL && BF) {
     asm volatile(
@@ -325,7 +323,6 @@ __device__ __forceinline__ void run_scheduled_loop(int n_full, int n_tiles, int 
     );
   }
 #undef FI355_LOOP_OPERANDS
-#undef FI355_ROW_FLAGS
 #undef FI355_HEADS_AND_POSITIONS
 #undef FI355_STAGING_OFFSETS
 }
@@ -830,13 +827,20 @@ struct NoRopeTable {};
 template <bool BF, bool VAR = false, bool CAPLOOP = false, bool CONTIG = false, bool VARLOOP = false, bool ROPE = false,
           bool PSLOOP = false, bool ROWLOOP = false>
 __global__ void __launch_bounds__(kCtaThreads) __attribute__((amdgpu_waves_per_eu(2, 2)))
-append_kernel(const RunParams p, const typename std::conditional<ROPE, RopeTable, NoRopeTable>::type rope) {
+append_kernel(const RunParams p_arg, const typename std::conditional<ROPE, RopeTable, NoRopeTable>::type rope) {
   static_assert(!CONTIG || !VAR, "affine addressing is built for the plain kernel");
   static_assert(!(CAPLOOP && VARLOOP) && (!VARLOOP || VAR), "one variant of the loop per instantiation");
   static_assert(!ROPE || (VAR && !CAPLOOP && !VARLOOP), "the rotary transform is built into the general path");
   static_assert(!PSLOOP || (!VAR && !CONTIG), "the loop for other page sizes is the plain one");
   static_assert(!ROWLOOP || PSLOOP, "the per-row loop is a kind of the loop for other page sizes");
   const int tid = threadIdx.x;
+  // The launch parameters are read from the argument segment again for every work item (scalar loads): the scheduled
+  // loop takes every scalar register above s63, and parameters kept in registers across it would be spilled into
+  // lanes of a vector register that is itself saved to scratch memory, whose reload after the loop would wait for the
+  // output rows the item has just stored.
+  typedef const __attribute__((address_space(4))) RunParams KernargParams;
+  const uint64_t params_addr = reinterpret_cast<uint64_t>(__builtin_amdgcn_kernarg_segment_ptr());  // p_arg is the first argument
+  KernargParams& p = *reinterpret_cast<KernargParams*>(params_addr);
   if constexpr (ROPE) {
     if (tid < 64) {
       rope_tab_lds[tid] = rope.rev[tid];
@@ -847,11 +851,6 @@ append_kernel(const RunParams p, const typename std::conditional<ROPE, RopeTable
   // Workgroups are handed to the eight XCDs round-robin: with the kv head as the fast index all
   // CTAs of a kv head (which re-read the same K/V) share one XCD's L2 when num_kv_heads is 8.
   const int cta = static_cast<int>(blockIdx.x) / p.num_kv_heads;
-  const int kvh = static_cast<int>(blockIdx.x) % p.num_kv_heads;
-  const int g = p.group;
-  const int g_log2 = 31 - __builtin_clz(g);
-  const int H = p.num_qo_heads;
-
   const int w_begin = __builtin_amdgcn_readfirstlane(p.cta_indptr[cta]);
   const int w_end = __builtin_amdgcn_readfirstlane(p.cta_indptr[cta + 1]);
 
@@ -860,13 +859,29 @@ append_kernel(const RunParams p, const typename std::conditional<ROPE, RopeTable
   WorkItem item;
   if (w_begin < w_end) item.load(p, w_begin);
   int prefetched = 0;
-  for (int w = w_begin; w < w_end; ++w) {
-    const int q_row0 = item.q_row0, n_pos = item.n_pos, kv_page0 = item.kv_page0, kv_start = item.kv_start;
-    const int kv_len = item.kv_len, diag0 = item.diag0, out_slot = item.out_slot;
-    const bool causal = diag0 != kNoDiagMarker;
-
-    // ---- work items whose first tile every row of the CTA sees in full: the scheduled loop ----
+  // (opaque copy of the parameters' address: the parameter loads of a work item stay inside the loop)
+#define FI355_ITEM_SCALARS                                                                                      \
+  uint64_t params_again = params_addr;                                                                          \
+  asm volatile("" : "+s"(params_again));                                                                         \
+  KernargParams& p = *reinterpret_cast<KernargParams*>(params_again);                                            \
+  const int kvh = static_cast<int>(blockIdx.x) % p.num_kv_heads;                                                 \
+  const int g = p.group;                                                                                         \
+  const int g_log2 = 31 - __builtin_clz(g);                                                                      \
+  const int H = p.num_qo_heads;                                                                                  \
+  const int q_row0 = item.q_row0, n_pos = item.n_pos, kv_page0 = item.kv_page0, kv_start = item.kv_start;        \
+  const int kv_len = item.kv_len, diag0 = item.diag0, out_slot = item.out_slot;                                  \
+  const bool causal = diag0 != kNoDiagMarker;
+  const int wave_s = __builtin_amdgcn_readfirstlane(tid >> 6);
+  int w = w_begin;
+  while (w < w_end) {
+    // ---- work items whose first tile every row of the CTA sees in full: the scheduled loop, one item after the
+    // other in a loop of their own (the general path below is a function call, after which the compiler must
+    // assume loads in flight into any register: at a common loop head it would wait for all of memory before
+    // every item, which is where the rows that the item before has just stored are still on their way) ----
     if constexpr (kUseScheduledLoop && (!VAR || CAPLOOP || VARLOOP)) {
+     for (;;) {
+      FI355_ITEM_SCALARS
+      (void)g;
       int vis = kv_len;  // tokens visible to the CTA's first position, which sees the fewest
       if (causal) vis = min(vis, max(0, diag0 - kv_start + 1));
       const int n_full = __builtin_amdgcn_readfirstlane(vis / kTileKv);
@@ -883,10 +898,13 @@ append_kernel(const RunParams p, const typename std::conditional<ROPE, RopeTable
           (!VARLOOP || H < 65536) &&  // (that variant takes num_qo_heads in 16 bits of an operand)
           out_rows_bound * (kHeadDim * 4) < (int64_t(1) << 32)) {
         // The loop clobbers nearly every vector register, so its lane-dependent operands are
-        // derived here from an opaque copy of the thread index: the compiler cannot hoist them out
-        // of the work loop and keep them in scratch memory across the loop.
-        int tid_o = tid;
-        asm volatile("" : "+v"(tid_o));
+        // derived here from a thread index that is formed anew for every item (wavefront index,
+        // a scalar, and the lane's number): the compiler can neither hoist them out of the work loop
+        // nor keep the index itself in scratch memory across the loop, whose reload would wait for
+        // the rows that the item before has just stored.
+        int lane_o;
+        asm volatile("v_mbcnt_lo_u32_b32 %0, -1, 0\n\tv_mbcnt_hi_u32_b32 %0, -1, %0" : "=v"(lane_o));
+        const int tid_o = wave_s * 64 + lane_o;
         const int wave_o = tid_o >> 6, n_o = tid_o & 31, c_o = (tid_o >> 5) & 1;
         const int st_tok_o = tid_o >> 4, st_chunk_o = tid_o & 15;
         const int tr_row_o = (tid_o & 15) >> 2, tr_col_o = 16 * ((tid_o >> 4) & 1) + 4 * (tid_o & 3);
@@ -923,23 +941,22 @@ append_kernel(const RunParams p, const typename std::conditional<ROPE, RopeTable
         if constexpr (VARLOOP) {
           if (p.alibi_slopes != nullptr) slope_o = p.alibi_slopes[head] * 1.4426950408889634f;
         }
-        run_scheduled_loop<BF, CAPLOOP, CONTIG, VARLOOP, PSLOOP, ROWLOOP>(n_full, (kv_len + kTileKv - 1) / kTileKv, kv_len, seen_bound - 4 * c_o, st_tok_o,
+        run_scheduled_loop<BF, CAPLOOP, CONTIG, VARLOOP, PSLOOP, ROWLOOP>(n_full, (kv_len + kTileKv - 1) / kTileKv, kv_len, seen_bound - 4 * c_o, tid_o,
                                (chunk_pages - 1) * 4, p.kv_indices + kv_page0, static_cast<uint32_t>(k_base),
                                static_cast<uint32_t>(k_base >> 32), static_cast<uint32_t>(v_base),
                                static_cast<uint32_t>(v_base >> 32), static_cast<uint32_t>(page_bytes),
                                CAPLOOP ? p.cap_k1 : p.scale_log2,
                                q_addr, st_off_bytes, k_off_bytes,
-                               lds0 + n_o * 256 + ((c_o ^ n_o) & 1) * 16, ((n_o >> 1) & 7) * 32,
+                               lds0 + n_o * 256 + ((c_o ^ n_o) & 1) * 16,
                                lds0 + kLdsVOffset + (4 * c_o + tr_row_o) * (kRowElemsV * 2) + tr_col_o * 2,
                                lds0 + __builtin_amdgcn_readfirstlane(wave_o) * 1024,
                                lds0 + kLdsVOffset + st_tok_o * (kRowElemsV * 2) + st_chunk_o * 16,
                                static_cast<uint32_t>(out_row * (kHeadDim * 4) + c_o * 16),
-                               pos_r < n_pos ? (c_o == 0 ? 3 : 1) : 0, final_out ? p.o : p.part_o,
+                               final_out ? p.o : p.part_o,
                                final_out ? p.lse : p.part_lse, p.o_cast,
                                __builtin_amdgcn_readfirstlane(final_out && p.o_cast != nullptr ? (p.o != nullptr ? 1 : 2) : 0),
                                epi0 + n_o * kEpilogueRowBytes + c_o * 16,
                                epi0 + ((tid_o >> 4) & 3) * kEpilogueRowBytes + st_chunk_o * 16,
-                               st_chunk_o * 16,
                                CAPLOOP   ? g_log2 | (__builtin_amdgcn_readfirstlane(wave_o) << 8)
                                : VARLOOP ? g_log2 | (n_pos << 5) | (H << 16)
                                : PSLOOP  ? g_log2 | (p.page_log2 << 8)
@@ -956,17 +973,24 @@ append_kernel(const RunParams p, const typename std::conditional<ROPE, RopeTable
                                p.window_left >= 0 ? p.window_left : 0x3FFFFFFF);
         item = next;
         prefetched = prefetched_next;
-        continue;  // the work item is finished
+        if (++w >= w_end) return;  // (the same for every thread of the CTA)
+        continue;                  // the work item is finished
       }
+      break;
+     }
     }
+    FI355_ITEM_SCALARS
+    (void)kvh; (void)g; (void)g_log2; (void)H; (void)causal;
     if (prefetched) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // tiles requested for this item: not used, but on their way into LDS
     prefetched = 0;
     __syncthreads();  // the previous work item is done with the tile buffers
     // (the kernel's only argument sits at the start of its argument segment)
-    generic_work_item<BF, VAR, ROPE>(reinterpret_cast<uint64_t>(__builtin_amdgcn_kernarg_segment_ptr()), q_row0, n_pos,
+    generic_work_item<BF, VAR, ROPE>(params_addr, q_row0, n_pos,
                                      kv_page0, kv_start, kv_len, diag0, out_slot);
     if (w + 1 < w_end) item.load(p, w + 1);
+    ++w;
   }
+#undef FI355_ITEM_SCALARS
 }
 
 }  // namespace

@@ -122,11 +122,9 @@ class Gen:
         # exec masks of 16 lanes.  A wavefront needs 2 x 4 ids per tile; two groups of eight scalar registers alternate: K of tile
         # t + 2 is requested from group 0 at the head of tile t, which then receives the ids of tile t + 4; V of tile
         # t + 3 is requested from group 1 at the tile's end; after the barrier (which waits for the ids) the groups
-        # swap.  The next work item's first tiles are not requested ahead (sixteen more scalar registers), and the
-        # row flags are found in the epilogue as in the bias / window variant (the operand's register is needed).
+        # swap.  The next work item's first tiles are not requested ahead (sixteen more scalar registers).
         self.rowids = rowids
         assert not (rowids and (cap or contig or var or anyps))
-        self.norok = var or rowids
         # in the tile loop: ids of the tile whose K is requested next / where the ids requested at a tile's head go /
         # ids of the tile whose V is requested at the tile's end
         self.gk, self.gn, self.gs = (S_G0, S_G0, S_G1) if rowids else (S_IDK, S_IDN, S_IDS)
@@ -295,11 +293,12 @@ class Gen:
         """V rows of tile t + ahead at or past the end of the chunk must not reach P.V (their
         logits are masked, but 0 x garbage need not be 0): this thread's rows are 32 r + st_tok"""
         ops = ['s_add_u32 s%d, s%d, %d' % (S_TMP, S_T, ahead), 's_lshl_b32 s%d, s%d, 6' % (S_TMP, S_TMP),
-               's_sub_i32 s%d, %%[kvl], s%d' % (S_REM, S_TMP)]  # rows of that tile inside the chunk (may be <= 0 or > 64)
+               's_sub_i32 s%d, %%[kvl], s%d' % (S_REM, S_TMP),  # rows of that tile inside the chunk (may be <= 0 or > 64)
+               's_lshl_b32 s%d, s%d, 4' % (S_REM, S_REM)]          # (st_tok = thread / 16 < rows  <=>  thread < 16 rows)
         for r in range(2):
             if r:
-                ops.append('s_sub_i32 s%d, s%d, 32' % (S_REM, S_REM))
-            ops.append('v_cmp_gt_i32 vcc, s%d, %%[stk]' % S_REM)
+                ops.append('s_sub_i32 s%d, s%d, 512' % (S_REM, S_REM))
+            ops.append('v_cmp_gt_i32 vcc, s%d, %%[tid]' % S_REM)
             for x in range(base + 8 + 4 * r, base + 12 + 4 * r):
                 ops.append('v_cndmask_b32 v%d, 0, v%d, vcc' % (x, x))
         return ops
@@ -515,7 +514,8 @@ class Gen:
         """this thread's pieces of the staged V tiles 0 and 1 (the ones it requested itself at the end of the
         previous work item) into the registers the start-up converts them from"""
         ops = self.wave_shift(S_TMP, 'lshl', 10) + ['s_sub_u32 s%d, %%[kd], s%d' % (S_TMP, S_TMP),  # LDS offset of the tile area
-               'v_lshlrev_b32 v%d, 8, %%[stk]' % X0, 'v_add_u32 v%d, v%d, %%[l16]' % (X0, X0),
+               'v_lshrrev_b32 v%d, 4, %%[tid]' % X0, 'v_lshlrev_b32 v%d, 8, v%d' % (X0, X0),   # 256 * st_tok
+               'v_and_b32 v%d, 15, %%[tid]' % X1, 'v_lshl_add_u32 v%d, v%d, 4, v%d' % (X0, X1, X0),  # + 16 * st_chunk
                'v_add_u32 v%d, s%d, v%d' % (X0, S_TMP, X0)]
         for t, base in ((0, VT), (1, KA)):
             for r in range(2):
@@ -703,8 +703,10 @@ class Gen:
         for i in range(64):
             e.raw('v_mov_b32 v%d, 0' % (ACC + i))
         # the eight K operand reads of a lane: row n, chunk (2 s + c) ^ (n % 16) -> kb + (32 s ^ kxs)
+        e.raw('v_bfe_u32 v%d, %%[tid], 1, 3' % X0)   # ((n >> 1) & 7) * 32, n = thread % 32
+        e.raw('v_lshlrev_b32 v%d, 5, v%d' % (X0, X0))
         for s_ in range(8):
-            e.raw('v_xor_b32 v%d, %d, %%[kxs]' % (KAD + s_, 32 * s_))
+            e.raw('v_xor_b32 v%d, %d, v%d' % (KAD + s_, 32 * s_, X0))
             e.raw('v_add_u32 v%d, v%d, %%[kb]' % (KAD + s_, KAD + s_))
         q_loads = list(e.vm)
         if not self.rowids:  # (the per-row variant never has tiles requested ahead)
@@ -840,15 +842,13 @@ class Gen:
                   ['v_cmp_neq_f32 vcc, 0, v%d' % LSUM, 'v_cndmask_b32 v%d, 0, v%d, vcc' % (X0, X0)] if self.var else []) + [
                   'v_add_f32 v%d, v%d, v%d' % (X1, MRUN, X1) if self.inplace else 'v_fma_f32 v%d, v%d, %%[sc], v%d' % (X1, MRUN, X1),
                   'v_mul_f32 v%d, 0x3f317218, v%d' % (X1, X1),
-                  's_mov_b64 s[%d:%d], exec' % (S_EXEC, S_EXEC + 1)] + (
-                  # one lane per live row writes lse: bit 1 of %[rok]; the bias / window variant has no register for
-                  # that operand and finds the lanes itself: lane < 32 and position of row 32 wave + lane % 32 < n_pos
-                  ['v_mbcnt_lo_u32_b32 v%d, -1, 0' % (T + 15), 'v_mbcnt_hi_u32_b32 v%d, -1, v%d' % (T + 15, T + 15),
-                   'v_and_b32 v%d, 31, v%d' % (T + 14, T + 15)] + self.wave_shift(S_TMP, 'lshl', 5) + [
-                   'v_add_u32 v%d, s%d, v%d' % (T + 14, S_TMP, T + 14), 'v_lshrrev_b32 v%d, %%[gl], v%d' % (T + 14, T + 14),
-                   'v_cmp_gt_i32 vcc, %s, v%d' % (self.np, T + 14), 's_and_b64 exec, exec, vcc',
-                   'v_cmp_gt_u32 vcc, 32, v%d' % (T + 15), 's_and_b64 exec, exec, vcc'] if self.norok else
-                  ['v_and_b32 v%d, 2, %%[rok]' % self.maxt, 'v_cmp_ne_u32 vcc, 0, v%d' % self.maxt, 's_and_b64 exec, exec, vcc']) + [
+                  's_mov_b64 s[%d:%d], exec' % (S_EXEC, S_EXEC + 1),
+                  # one lane per live row writes lse: lane < 32 and position of row 32 wave + lane % 32 < n_pos
+                  'v_mbcnt_lo_u32_b32 v%d, -1, 0' % (T + 15), 'v_mbcnt_hi_u32_b32 v%d, -1, v%d' % (T + 15, T + 15),
+                  'v_and_b32 v%d, 31, v%d' % (T + 14, T + 15)] + self.wave_shift(S_TMP, 'lshl', 5) + [
+                  'v_add_u32 v%d, s%d, v%d' % (T + 14, S_TMP, T + 14), 'v_lshrrev_b32 v%d, %%[gl], v%d' % (T + 14, T + 14),
+                  'v_cmp_gt_i32 vcc, %s, v%d' % (self.np, T + 14), 's_and_b64 exec, exec, vcc',
+                  'v_cmp_gt_u32 vcc, 32, v%d' % (T + 15), 's_and_b64 exec, exec, vcc',
                   'v_lshrrev_b32 v%d, 9, %%[ooff]' % T, 'v_lshlrev_b32 v%d, 2, v%d' % (T, T),
                   'global_store_dword v%d, v%d, %%[lb] nt' % (T, X1), 's_mov_b64 exec, s[%d:%d]' % (S_EXEC, S_EXEC + 1)]:
             e.raw(o)
@@ -858,15 +858,17 @@ class Gen:
         # halved for the rounded copy (S0 + k), and whether the row exists (scalar masks)
         OFF, COFF, ROW0 = KA, S0, T
         masks = [S_IDA, S_IDA + 2, S_IDB, S_IDB + 2, S_IDS, S_IDS + 2, S_IDN, S_IDN + 2]
-        for o in ['v_lshrrev_b32 v%d, 2, %%[stk]' % ROW0, 'v_lshlrev_b32 v%d, 5, v%d' % (ROW0, ROW0),
-                  'v_and_b32 v%d, 3, %%[stk]' % (T + 1), 'v_or_b32 v%d, v%d, v%d' % (ROW0, ROW0, T + 1)]:
+        L16 = T + 5   # 16 * (thread % 16): the 16-byte piece of a row this lane stores
+        for o in ['v_lshrrev_b32 v%d, 6, %%[tid]' % ROW0, 'v_lshlrev_b32 v%d, 5, v%d' % (ROW0, ROW0),
+                  'v_bfe_u32 v%d, %%[tid], 4, 2' % (T + 1), 'v_or_b32 v%d, v%d, v%d' % (ROW0, ROW0, T + 1),
+                  'v_and_b32 v%d, 15, %%[tid]' % L16, 'v_lshlrev_b32 v%d, 4, v%d' % (L16, L16)]:
             e.raw(o)
         for k in range(8):
             R, P, B = T + 2, T + 3, T + 4
             for o in ['v_add_u32 v%d, %d, v%d' % (R, 4 * k, ROW0), 'v_lshrrev_b32 v%d, %%[gl], v%d' % (P, R),
                       'v_lshlrev_b32 v%d, %%[gl], v%d' % (B, P), 'v_sub_u32 v%d, v%d, v%d' % (B, R, B),
                       'v_mad_u32_u24 v%d, v%d, %s, v%d' % (B, P, self.hq, B), 'v_add_u32 v%d, %%[rb], v%d' % (B, B),
-                      'v_lshlrev_b32 v%d, 9, v%d' % (B, B), 'v_add_u32 v%d, v%d, %%[l16]' % (OFF + k, B),
+                      'v_lshlrev_b32 v%d, 9, v%d' % (B, B), 'v_add_u32 v%d, v%d, v%d' % (OFF + k, B, L16),
                       'v_lshrrev_b32 v%d, 1, v%d' % (COFF + k, OFF + k),
                       'v_cmp_gt_i32 s[%d:%d], %s, v%d' % (masks[k], masks[k] + 1, self.np, P)]:
                 e.raw(o)
