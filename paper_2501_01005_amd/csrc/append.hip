@@ -249,7 +249,21 @@ __device__ __forceinline__ void run_scheduled_loop(int n_full, int n_tiles, int 
   }
 #undef FI355_HEADS_AND_POSITIONS
 #define FI355_HEADS_AND_POSITIONS [hq] "s"(num_qo_heads), [np] "s"(n_pos),
-  if constexpr (ROWS && BF) {
+  if constexpr (ROWS && CONTIG && BF) {
+    asm volatile(
+#include "append_loop_bf16_contig_rows.inc"
+        FI355_LOOP_OPERANDS
+        :
+#include "append_loop_clobbers.inc"
+    );
+  } else if constexpr (ROWS && CONTIG) {
+    asm volatile(
+#include "append_loop_f16_contig_rows.inc"
+        FI355_LOOP_OPERANDS
+        :
+#include "append_loop_clobbers.inc"
+    );
+  } else if constexpr (ROWS && BF) {
     asm volatile(
 #include "append_loop_bf16_rows.inc"
         FI355_LOOP_OPERANDS
@@ -265,6 +279,20 @@ __device__ __forceinline__ void run_scheduled_loop(int n_full, int n_tiles, int 
     );
   }
   if constexpr (VARL || ROWS) {
+  } else if constexpr (PSL && CONTIG && BF) {
+    asm volatile(
+#include "append_loop_bf16_contig_ps.inc"
+        FI355_LOOP_OPERANDS
+        :
+#include "append_loop_clobbers.inc"
+    );
+  } else if constexpr (PSL && CONTIG) {
+    asm volatile(
+#include "append_loop_f16_contig_ps.inc"
+        FI355_LOOP_OPERANDS
+        :
+#include "append_loop_clobbers.inc"
+    );
   } else if constexpr (PSL && BF) {
     asm volatile(
 #include "append_loop_bf16_ps.inc"
@@ -831,7 +859,7 @@ append_kernel(const RunParams p_arg, const typename std::conditional<ROPE, RopeT
   static_assert(!CONTIG || !VAR, "affine addressing is built for the plain kernel");
   static_assert(!(CAPLOOP && VARLOOP) && (!VARLOOP || VAR), "one variant of the loop per instantiation");
   static_assert(!ROPE || (VAR && !CAPLOOP && !VARLOOP), "the rotary transform is built into the general path");
-  static_assert(!PSLOOP || (!VAR && !CONTIG), "the loop for other page sizes is the plain one");
+  static_assert(!PSLOOP || !VAR, "the loop for other page sizes is the plain one, with or without a page table");
   static_assert(!ROWLOOP || PSLOOP, "the per-row loop is a kind of the loop for other page sizes");
   const int tid = threadIdx.x;
   // The launch parameters are read from the argument segment again for every work item (scalar loads): the scheduled
@@ -1026,6 +1054,20 @@ hipError_t launch_append(const RunParams& p, bool is_bf16, bool variant, const R
       hipLaunchKernelGGL((append_kernel<true, true>), grid, block, 0, stream, p, NoRopeTable{});
     else
       hipLaunchKernelGGL((append_kernel<false, true>), grid, block, 0, stream, p, NoRopeTable{});
+    return hipGetLastError();
+  }
+  if (p.kv_indices == nullptr && p.page_log2 <= 1) {  // contiguous KV (the caller has refused variants), page sizes 1 and 2
+    if (is_bf16)
+      hipLaunchKernelGGL((append_kernel<true, false, false, true, false, false, true, true>), grid, block, 0, stream, p, NoRopeTable{});
+    else
+      hipLaunchKernelGGL((append_kernel<false, false, false, true, false, false, true, true>), grid, block, 0, stream, p, NoRopeTable{});
+    return hipGetLastError();
+  }
+  if (p.kv_indices == nullptr && (p.page_log2 == 2 || p.page_log2 == 3 || p.page_log2 == 5)) {  // contiguous, page sizes 4, 8, 32
+    if (is_bf16)
+      hipLaunchKernelGGL((append_kernel<true, false, false, true, false, false, true>), grid, block, 0, stream, p, NoRopeTable{});
+    else
+      hipLaunchKernelGGL((append_kernel<false, false, false, true, false, false, true>), grid, block, 0, stream, p, NoRopeTable{});
     return hipGetLastError();
   }
   if (p.kv_indices != nullptr && p.page_log2 <= 1) {  // page sizes 1 and 2: the loop with a page id per token row

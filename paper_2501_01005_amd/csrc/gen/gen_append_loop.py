@@ -1,6 +1,7 @@
 #!/usr/bin/env python3
-"""Writes append_loop_{bf16,f16}[_cap|_contig|_var|_ps|_rows].inc: the hand-scheduled steady-state loop of the append
-kernel and its variants (soft cap; contiguous KV; ALiBi and / or sliding window; page sizes 4, 8, 32; page sizes 1, 2).
+"""Writes append_loop_{bf16,f16}[_cap|_contig|_var|_ps|_rows|_contig_ps|_contig_rows].inc: the hand-scheduled
+steady-state loop of the append kernel and its variants (soft cap; contiguous KV; ALiBi and / or sliding window; page
+sizes 4, 8, 32; page sizes 1, 2; the last two also for contiguous KV).
 
 The loop covers all KV tiles of a work item whose first tile every row of the CTA sees in full:
 first the tiles that need no masking, then, with a compare-and-select on the logits in front of
@@ -124,7 +125,7 @@ class Gen:
         # t + 3 is requested from group 1 at the tile's end; after the barrier (which waits for the ids) the groups
         # swap.  The next work item's first tiles are not requested ahead (sixteen more scalar registers).
         self.rowids = rowids
-        assert not (rowids and (cap or contig or var or anyps))
+        assert not (rowids and (cap or var or anyps))
         # in the tile loop: ids of the tile whose K is requested next / where the ids requested at a tile's head go /
         # ids of the tile whose V is requested at the tile's end
         self.gk, self.gn, self.gs = (S_G0, S_G0, S_G1) if rowids else (S_IDK, S_IDN, S_IDS)
@@ -133,7 +134,7 @@ class Gen:
         # >> log2(page size) of the chunk, for each 16-token segment r of tile t.  The row's place inside its page
         # is part of the per-lane offsets the C++ side passes.  %[gl] carries log2 of the page size in bits 8..
         self.anyps = anyps
-        assert not (anyps and (cap or contig or var))
+        assert not (anyps and (cap or var))
         # ALiBi bias and sliding window (Sec. 3.2.3) for causal work items: like the soft cap, the logits of a step are
         # transformed in place as soon as they are complete: s <- s * sm_scale * log2(e) + slope * (t - pos), then -inf
         # where t < pos - W.  Per lane: %[cap] carries lim - 4 c uncapped (lim = chunk-local index of the row's own
@@ -380,8 +381,8 @@ class Gen:
                         ops.append('s_lshr_b32 s%d, s%d, s%d' % (off, off, S_PSL))
                     else:
                         ops.append('s_lshr_b32 s%d, s%d, s%d' % (off, S_TMP, S_PSL))
-                    ops += ['s_lshl_b32 s%d, s%d, 2' % (off, off), 's_min_u32 s%d, s%d, %%[npg1]' % (off, off),
-                            's_load_dword s%d, %%[idp], s%d' % (dst + 4 * r + q, off)]
+                    ops += ['s_lshl_b32 s%d, s%d, 2' % (off, off), 's_min_u32 s%d, s%d, %%[npg1]' % (off, off)]
+                    ops += self.id_at(dst + 4 * r + q, off)
             return ops
         if self.anyps:
             # token of this wavefront's first row in segment r of the tile -> its page -> byte offset of the page id
@@ -397,8 +398,8 @@ class Gen:
                     ops.append('s_lshr_b32 s%d, s%d, s%d' % (off, off, S_PSL))
                 else:
                     ops.append('s_lshr_b32 s%d, s%d, s%d' % (off, S_TMP, S_PSL))
-                ops += ['s_lshl_b32 s%d, s%d, 2' % (off, off), 's_min_u32 s%d, s%d, %%[npg1]' % (off, off),
-                        's_load_dword s%d, %%[idp], s%d' % (dst + r, off)]
+                ops += ['s_lshl_b32 s%d, s%d, 2' % (off, off), 's_min_u32 s%d, s%d, %%[npg1]' % (off, off)]
+                ops += self.id_at(dst + r, off)
             return ops
         if ahead:
             ops.append('s_add_u32 s%d, s%d, %d' % (S_TMP, S_T, ahead))
@@ -411,11 +412,14 @@ class Gen:
                 ops.append('s_min_u32 s%d, s%d, %%[npg1]' % (off, off))
             else:
                 ops.append('s_min_u32 s%d, s%d, %%[npg1]' % (off, S_TMP))
-            if self.contig:
-                ops += ['s_lshr_b32 s%d, s%d, 2' % (dst + r, off), 's_add_u32 s%d, s%d, %%[idblo]' % (dst + r, dst + r)]
-            else:
-                ops.append('s_load_dword s%d, %%[idp], s%d' % (dst + r, off))
+            ops += self.id_at(dst + r, off)
         return ops
+
+    def id_at(self, dst, off):
+        """s<dst> <- the page id at byte offset s<off> of the chunk's ids: loaded, or, with contiguous KV, computed"""
+        if self.contig:
+            return ['s_lshr_b32 s%d, s%d, 2' % (dst, off), 's_add_u32 s%d, s%d, %%[idblo]' % (dst, dst)]
+        return ['s_load_dword s%d, %%[idp], s%d' % (dst, off)]
 
     def header_next(self):
         """request the plan entry of the CTA's next work item (of this one again if it is the last): the seven
@@ -938,7 +942,9 @@ if __name__ == '__main__':
                                   (False, False, True, 'f16_contig'), (True, False, False, 'bf16_var'),
                                   (False, False, False, 'f16_var'), (True, False, False, 'bf16_ps'),
                                   (False, False, False, 'f16_ps'), (True, False, False, 'bf16_rows'),
-                                  (False, False, False, 'f16_rows')):
+                                  (False, False, False, 'f16_rows'), (True, False, True, 'bf16_contig_ps'),
+                                  (False, False, True, 'f16_contig_ps'), (True, False, True, 'bf16_contig_rows'),
+                                  (False, False, True, 'f16_contig_rows')):
         lines = Gen(bf, cap, contig, var=name.endswith('_var'), anyps=name.endswith('_ps'),
                     rowids=name.endswith('_rows')).program()
         write(os.path.join(out_dir, 'append_loop_%s.inc' % name), lines, name)

@@ -35,14 +35,18 @@ def test_decode_over_contiguous_kv(page_size, layout):
 
 
 @pytest.mark.parametrize("layout", ["HND", "NHD"])
-@pytest.mark.parametrize("page_size", [16, 1, 32])
+@pytest.mark.parametrize("page_size", [16, 1, 2, 4, 8, 32, 64])
 def test_append_over_contiguous_kv(page_size, layout):
+    """At every page size the run without a page table takes the same variant of the scheduled loop as the paged run,
+    with computed instead of loaded page ids (page size 64: both on the general path): the same bits."""
     b = workloads.config3(small=True, permute_pages=False, page_size=page_size)
-    # (at page sizes 1 and 32 the paged run takes a page-size variant of the scheduled loop and the run without a
-    # page table the general path: the same result within the tolerance, not the same bits)
-    same = page_size == 16
-    check(b, "append", f"append contiguous ps{page_size}", layout, same_path=same)              # default grid
-    check(b, "append", f"append contiguous ps{page_size}, split", layout, same_path=same, num_ctas=8 * 16, min_chunk=32)
+    check(b, "append", f"append contiguous ps{page_size}", layout)              # default grid
+    check(b, "append", f"append contiguous ps{page_size}, split", layout, num_ctas=8 * 16, min_chunk=32)
+    # long chunks on few CTAs: several items per CTA run the loop back to back (the next item's first tiles are
+    # requested with computed ids too)
+    b = workloads.make_batch("contig_chain", 77 + page_size, workloads.F16, 8, 2, 128, page_size, [200, 64, 130, 300],
+                             [1500, 700, 131, 900], True, permute_pages=False)
+    check(b, "append", f"append contiguous chain ps{page_size}", layout, num_ctas=2 * 3, min_chunk=128)
 
 
 def test_ragged_tensor_is_page_size_one_nhd():
