@@ -216,10 +216,11 @@ __device__ __forceinline__ void run_scheduled_loop(int n_full, int n_tiles, int 
                                                    int n_pos, int wave_index, int next_off,
                                                    const int32_t* w_fields, int w_stride, uint32_t all_ids_lo,
                                                    uint32_t all_ids_hi, WorkItem& next, int& prefetched_out,
-                                                   float slope = 0.f, int win = 0) {
+                                                   float& slope, int win = 0) {
 #define FI355_LOOP_OPERANDS                                                                                              \
         : [nq] "=&s"(next.q_row0), [nn] "=&s"(next.n_pos), [npg] "=&s"(next.kv_page0), [nks] "=&s"(next.kv_start),          \
           [nkl] "=&s"(next.kv_len), [ndg] "=&s"(next.diag0), [nos] "=&s"(next.out_slot), [preo] "=&s"(prefetched_out)        \
+          FI355_SLOPE_OPERAND                                                                                                  \
         : [nf] "s"(n_full), [nt] "s"(n_tiles), [kvl] "s"(kv_len), [cap] "{v1}"(cap), [tid] "{v4}"(thread), [npg1] "s"(ids_clamp), [idp] "s"(page_ids), [kblo] "s"(k_lo), [kbhi] "s"(k_hi), \
           [vblo] "s"(v_lo), [vbhi] "s"(v_hi), [sp] "s"(page_bytes), [sc] "s"(scale_log2),                                 \
           [qp] "{v[2:3]}"(q_addr), FI355_STAGING_OFFSETS [kb] "{v7}"(k_read),                               \
@@ -232,22 +233,26 @@ __device__ __forceinline__ void run_scheduled_loop(int n_full, int n_tiles, int 
   // num_qo_heads packed into g_log2)
 #define FI355_STAGING_OFFSETS [so] "{v5}"(st_off_bytes), [sok] "{v6}"(k_off_bytes),
 #define FI355_HEADS_AND_POSITIONS
+  // (the row's slope is loaded once per launch and handed from block to block in its register: read and written)
+#define FI355_SLOPE_OPERAND , [slope] "+{v13}"(slope)
   if constexpr (VARL && BF) {
     asm volatile(
 #include "append_loop_bf16_var.inc"
-        FI355_LOOP_OPERANDS, [slope] "{v13}"(slope), [win] "s"(win)
+        FI355_LOOP_OPERANDS, [win] "s"(win)
         :
 #include "append_loop_clobbers.inc"
     );
   } else if constexpr (VARL) {
     asm volatile(
 #include "append_loop_f16_var.inc"
-        FI355_LOOP_OPERANDS, [slope] "{v13}"(slope), [win] "s"(win)
+        FI355_LOOP_OPERANDS, [win] "s"(win)
         :
 #include "append_loop_clobbers.inc"
     );
   }
 #undef FI355_HEADS_AND_POSITIONS
+#undef FI355_SLOPE_OPERAND
+#define FI355_SLOPE_OPERAND
 #define FI355_HEADS_AND_POSITIONS [hq] "s"(num_qo_heads), [np] "s"(n_pos),
   if constexpr (ROWS && CONTIG && BF) {
     asm volatile(
@@ -351,6 +356,7 @@ __device__ __forceinline__ void run_scheduled_loop(int n_full, int n_tiles, int 
     );
   }
 #undef FI355_LOOP_OPERANDS
+#undef FI355_SLOPE_OPERAND
 #undef FI355_HEADS_AND_POSITIONS
 #undef FI355_STAGING_OFFSETS
 }
@@ -900,6 +906,15 @@ append_kernel(const RunParams p_arg, const typename std::conditional<ROPE, RopeT
   const int kv_len = item.kv_len, diag0 = item.diag0, out_slot = item.out_slot;                                  \
   const bool causal = diag0 != kNoDiagMarker;
   const int wave_s = __builtin_amdgcn_readfirstlane(tid >> 6);
+  // ALiBi slope of this lane's row (its head depends on the thread alone), times log2(e): one load per launch
+  float slope_o = 0.f;
+  if constexpr (VARLOOP) {
+    if (p.alibi_slopes != nullptr) {
+      const int R = 32 * (tid >> 6) + (tid & 31);
+      const int head = (static_cast<int>(blockIdx.x) % p.num_kv_heads) * p.group + (R & (p.group - 1));
+      slope_o = p.alibi_slopes[head] * 1.4426950408889634f;
+    }
+  }
   int w = w_begin;
   while (w < w_end) {
     // ---- work items whose first tile every row of the CTA sees in full: the scheduled loop, one item after the
@@ -965,10 +980,6 @@ append_kernel(const RunParams p_arg, const typename std::conditional<ROPE, RopeT
         __syncthreads();  // the previous work item is done with the tile buffers and the transpose area
         // (with the bias / window variant the loop caps the bound itself and also needs it uncapped)
         const int seen_bound = VARLOOP ? diag0 + pos_r - kv_start : last_seen;
-        float slope_o = 0.f;
-        if constexpr (VARLOOP) {
-          if (p.alibi_slopes != nullptr) slope_o = p.alibi_slopes[head] * 1.4426950408889634f;
-        }
         run_scheduled_loop<BF, CAPLOOP, CONTIG, VARLOOP, PSLOOP, ROWLOOP>(n_full, (kv_len + kTileKv - 1) / kTileKv, kv_len, seen_bound - 4 * c_o, tid_o,
                                (chunk_pages - 1) * 4, p.kv_indices + kv_page0, static_cast<uint32_t>(k_base),
                                static_cast<uint32_t>(k_base >> 32), static_cast<uint32_t>(v_base),
